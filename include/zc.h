@@ -1,0 +1,190 @@
+/*
+ * zc.h -- C ABI of the field-split Huffman tensor codec for MI355X (gfx950).
+ *
+ * Method: Heilper & Singer, "Lossless Compression of Neural Network Components:
+ * Weights, Checkpoints, and K/V Caches in Low-Precision Formats" (2025).
+ * Every value of a BF16 / FP8 E4M3 / FP4 E2M1 tensor is split into its exponent
+ * bits and its sign+mantissa bits (Sec. 3.1, 3.2, 3.4, Fig. 5); each field is
+ * histogrammed over the tensor and Huffman coded on its own (Sec. 3.1, 3.2, 4);
+ * FP4 block scales form a third field (Sec. 3.4, 4.4); a checkpoint delta is the
+ * bitwise XOR against a base tensor (Sec. 3.1, 4.1); a field that does not
+ * compress may be stored as is (Sec. 3.1, 4.3); data is cut into fixed-size
+ * chunks that decode independently (Sec. 3.1), which also serves paged K/V
+ * caches (Sec. 3.3, 4.3, 5.2).  The result is lossless (Sec. 1, 2.2).
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are GPU memory of the current HIP device, 16-byte
+ *     aligned, owned by the caller; "host" pointers are ordinary memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Kernels are enqueued on it.  Calls that must read results back (noted
+ *     below) synchronise that stream before returning.
+ *   - The library keeps no state between calls and never allocates or frees
+ *     device memory: scratch space comes in through `d_ws`.
+ *   - Errors are returned as zc_status; nothing is thrown.  On error the
+ *     destination contents are unspecified but nothing is written outside the
+ *     capacities given.
+ *   - Element layout: BF16 little-endian u16; FP8 one byte; FP4 two elements per
+ *     byte, element 2i in the low nibble, with one E8M0 scale byte per 32
+ *     consecutive elements in a separate array.
+ */
+#ifndef ZC_H
+#define ZC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ZC_OK = 0,
+    ZC_ERR_INVALID_ARG = 1,      /* bad pointer, size, alignment or parameter value */
+    ZC_ERR_UNSUPPORTED = 2,      /* unknown format / struct size */
+    ZC_ERR_BUFFER_TOO_SMALL = 3, /* destination or workspace capacity */
+    ZC_ERR_CORRUPT = 4,          /* container fails validation */
+    ZC_ERR_DEVICE = 5            /* a HIP call failed */
+} zc_status;
+
+typedef enum {
+    ZC_FMT_BF16 = 1,        /* fields: 8-bit exponent, 8-bit sign+mantissa (Sec. 3.1) */
+    ZC_FMT_FP8_E4M3 = 2,    /* fields: 4-bit exponent, 4-bit sign+mantissa (Sec. 3.2) */
+    ZC_FMT_FP4_E2M1_MX = 3  /* fields: 2-bit exponent, 2-bit sign+mantissa, 8-bit E8M0 scale (Sec. 3.4) */
+} zc_format;
+
+typedef enum {
+    ZC_POLICY_HUFF_ALL = 0, /* every field with >= 2 distinct symbols is Huffman coded */
+    ZC_POLICY_AUTO = 1      /* a field is stored raw unless Huffman saves >= 1/16 (Sec. 3.1) */
+} zc_policy;
+
+typedef enum { ZC_MODE_EMPTY = 0, ZC_MODE_HUFF = 1, ZC_MODE_RAW = 2, ZC_MODE_CONST = 3 } zc_mode;
+
+typedef struct {
+    uint32_t struct_size;       /* = sizeof(zc_params) */
+    uint32_t format;            /* zc_format */
+    uint32_t chunk_bytes;       /* element bytes per chunk; multiple of 16 (FP4: of 256) */
+    uint32_t max_code_len[3];   /* per field, 1..16 with 2^L >= alphabet; 0 = 16 for 8-bit symbols, else 8 */
+    uint32_t streams_per_chunk; /* lanes per chunk: 1,2,4,...,64; 0 = 64.  Device paths need >= 4 */
+    uint32_t policy;            /* zc_policy */
+} zc_params;
+
+/* Parsed, validated container header plus the code-length tables: everything the
+ * host needs to launch a decode.  Filled by zc_compress / zc_read_info; may be
+ * cached by the caller for as long as the container bytes do not change. */
+typedef struct {
+    uint32_t format, policy, streams, n_fields, xor_delta, chunk_bytes;
+    uint32_t n_chunks, reserved;
+    uint64_t n_elems;
+    uint64_t total_bytes;       /* size of the container */
+    uint64_t payload_offset;
+    uint64_t table_offset[3];   /* code-length table of each field */
+    uint64_t index_offset[3];   /* chunk index of each field */
+    uint8_t mode[3], sym_bits[3], max_len[3], const_symbol[3];
+    uint8_t code_len[3][256];
+} zc_info;
+
+typedef struct {
+    uint32_t alphabet, distinct, mode, max_len;
+    uint64_t n_symbols;
+    uint64_t hist[256];
+    uint8_t code_len[256];
+    double entropy_bits;        /* -sum p log2 p, bits per symbol */
+    double mean_code_len;       /* payload_bits / n_symbols */
+    uint64_t payload_bits;      /* sum f*len (HUFF), n*sym_bits (RAW), 0 (CONST) */
+    uint64_t stream_bytes;      /* bytes of this field's chunk streams in the container */
+    double ratio_payload;       /* payload_bits / (n_symbols*sym_bits); "ratio" as in Sec. 4: coded/original */
+} zc_field_stats;
+
+typedef struct {
+    uint32_t n_fields, reserved;
+    uint64_t raw_bytes;         /* element bytes + scale bytes */
+    uint64_t container_bytes;
+    double ratio_payload_total;
+    double ratio_container_total;
+    zc_field_stats field[3];
+} zc_stats_out;
+
+/* One tensor of a batched call (host array).  Inputs are set by the caller;
+ * `out_bytes` and `info` are filled by zc_compress_batch and read by zc_decompress_batch. */
+typedef struct {
+    const void *d_src;          /* compress: elements (device) */
+    const void *d_xor_base;     /* device, same shape as the tensor, or NULL (Sec. 3.1 delta) */
+    const void *d_scales;       /* compress, FP4 only: n_elems/32 scale bytes (device) */
+    uint64_t n_elems;
+    void *d_comp;               /* container (device): written by compress, read by decompress */
+    uint64_t comp_capacity;     /* compress: bytes available at d_comp */
+    void *d_dst;                /* decompress: elements out (device) */
+    void *d_scales_out;         /* decompress, FP4 only */
+    uint64_t out_bytes;         /* container size */
+    zc_info info;
+} zc_tensor;
+
+/* Worst-case container size for n_elems (0 if the parameters are invalid).  Host only. */
+uint64_t zc_compress_bound(uint64_t n_elems, const zc_params *params);
+
+/* Scratch bytes a call on these tensors needs in d_ws (compress, stats and the
+ * batched decompress).  n_elems: host array of n_tensors element counts. */
+uint64_t zc_workspace_bytes(const uint64_t *n_elems, uint32_t n_tensors, const zc_params *params);
+
+/* Compress one tensor: field split (+ XOR delta) and per-field histogram over the tensor,
+ * length-limited canonical Huffman code per field, per-chunk stream sizes, exclusive scan
+ * into the chunk index, chunked encode (Sec. 3.1, 3.2, 3.4, 4).
+ * d_src/d_xor_base/d_scales/d_dst/d_ws: device.  out_bytes, out_info (may be NULL): host.
+ * dst_capacity must hold the result (zc_compress_bound always suffices), else
+ * ZC_ERR_BUFFER_TOO_SMALL.  Synchronises the stream (the code is built on the host from
+ * the device histogram).  n_elems == 0 gives a header-only container. */
+zc_status zc_compress(const void *d_src, uint64_t n_elems, const zc_params *params,
+                      const void *d_xor_base, const void *d_scales,
+                      void *d_dst, uint64_t dst_capacity, uint64_t *out_bytes, zc_info *out_info,
+                      void *d_ws, uint64_t ws_bytes, void *stream);
+
+/* Same over a host array of tensors sharing one zc_params: one launch sequence for the set. */
+zc_status zc_compress_batch(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params,
+                            void *d_ws, uint64_t ws_bytes, void *stream);
+
+/* Read and validate a container's header and tables (blocking copy of at most 1 KiB from
+ * the device; with check_index != 0 also the chunk index).  d_comp: device; out: host. */
+zc_status zc_read_info(const void *d_comp, uint64_t comp_bytes, int check_index, zc_info *out, void *stream);
+
+/* Decompress a whole tensor: per chunk, table-driven decode of every field and
+ * re-interleave into the original bit patterns (XORed with the base for a delta
+ * container).  info: host, from zc_compress / zc_read_info, or NULL (then the header is
+ * read with a blocking copy first).  Does not synchronise when info is given.
+ * d_scales_out: FP4 only.  d_xor_base: required iff the container is a delta. */
+zc_status zc_decompress(const void *d_comp, uint64_t comp_bytes, const zc_info *info,
+                        void *d_dst, uint64_t dst_capacity, void *d_scales_out,
+                        const void *d_xor_base, void *stream);
+
+/* Random-access decode (Sec. 3.1: chunks decode independently; Sec. 4.3 / 5.2: K/V pages):
+ * chunk d_chunk_ids[i] is written to d_dst + i*chunk_bytes (and its scales to
+ * d_scales_out + i*chunk_bytes/16).  A short last chunk leaves the rest of its slot
+ * untouched.  d_chunk_ids: device array of n_ids u32, each < n_chunks (ids out of range
+ * are skipped).  Delta containers: d_xor_base is the whole base tensor. */
+zc_status zc_decompress_chunks(const void *d_comp, uint64_t comp_bytes, const zc_info *info,
+                               const uint32_t *d_chunk_ids, uint32_t n_ids,
+                               void *d_dst, uint64_t dst_capacity, void *d_scales_out,
+                               const void *d_xor_base, void *stream);
+
+/* Whole-set decode in one launch: every tensor's d_comp/info/d_dst (and d_xor_base,
+ * d_scales_out) must be set.  All tensors must share format and streams.  Does not synchronise. */
+zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors,
+                              void *d_ws, uint64_t ws_bytes, void *stream);
+
+/* Per-field histogram, entropy, code lengths, payload bits, stream and container bytes
+ * and the ratios of Sec. 4, without producing the container.  out: host.  Synchronises. */
+zc_status zc_stats(const void *d_src, uint64_t n_elems, const zc_params *params,
+                   const void *d_xor_base, const void *d_scales, zc_stats_out *out,
+                   void *d_ws, uint64_t ws_bytes, void *stream);
+
+/* Length-limited canonical Huffman code for one histogram (host only; exposed so that the
+ * code construction can be checked without a GPU).  hist: `alphabet` counts;
+ * len_out/code_out: `alphabet` entries.  Returns ZC_ERR_INVALID_ARG if 2^limit < number of
+ * used symbols.  A single used symbol gets length 1. */
+zc_status zc_build_code(const uint64_t *hist, uint32_t alphabet, uint32_t limit,
+                        uint8_t *len_out, uint16_t *code_out);
+
+const char *zc_status_string(zc_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZC_H */

@@ -1,0 +1,595 @@
+// C ABI of the codec: argument checks, container layout, host-side code construction
+// between the histogram and the encode kernels, and kernel launches.  See include/zc.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "zc_internal.h"
+
+using namespace zc;
+
+namespace {
+
+struct Geometry {
+    uint32_t fmt, S, nf;
+    uint32_t chunk_bytes;
+    uint64_t elems_per_chunk;
+    int limit[kMaxFields];
+};
+
+zc_status check_params(const zc_params *p, Geometry *g)
+{
+    if (!p) return ZC_ERR_INVALID_ARG;
+    if (p->struct_size != sizeof(zc_params)) return ZC_ERR_UNSUPPORTED;
+    if (!elem_bits(p->format)) return ZC_ERR_UNSUPPORTED;
+    g->fmt = p->format;
+    g->S = p->streams_per_chunk ? p->streams_per_chunk : 64;
+    if (g->S > 64 || (g->S & (g->S - 1))) return ZC_ERR_INVALID_ARG;
+    if (p->chunk_bytes == 0 || p->chunk_bytes % 16) return ZC_ERR_INVALID_ARG;
+    if (p->format == ZC_FMT_FP4_E2M1_MX && p->chunk_bytes % 256) return ZC_ERR_INVALID_ARG;
+    if (p->policy > ZC_POLICY_AUTO) return ZC_ERR_INVALID_ARG;
+    g->nf = (uint32_t)num_fields(p->format);
+    g->chunk_bytes = p->chunk_bytes;
+    g->elems_per_chunk = (uint64_t)p->chunk_bytes * 8 / (uint64_t)elem_bits(p->format);
+    for (uint32_t f = 0; f < g->nf; f++) {
+        const int sb = sym_bits(p->format, (int)f);
+        int L = (int)p->max_code_len[f];
+        if (L == 0) L = sb == 8 ? 16 : 8;
+        if (L < sb || L > 16) return ZC_ERR_INVALID_ARG;      // 2^L must cover the alphabet
+        g->limit[f] = L;
+    }
+    return ZC_OK;
+}
+
+zc_status check_count(const Geometry &g, uint64_t n_elems, uint64_t *n_chunks)
+{
+    if (g.fmt == ZC_FMT_FP4_E2M1_MX && n_elems % 32) return ZC_ERR_INVALID_ARG;
+    const uint64_t nc = (n_elems + g.elems_per_chunk - 1) / g.elems_per_chunk;
+    if (nc >= 0xFFFFFFFFull) return ZC_ERR_INVALID_ARG;
+    *n_chunks = nc;
+    return ZC_OK;
+}
+
+uint64_t field_symbols(uint32_t fmt, int f, uint64_t n_elems) { return (fmt == ZC_FMT_FP4_E2M1_MX && f == 2) ? n_elems / 32 : n_elems; }
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+// offsets of tables / indices / payload for a tensor of nc chunks
+void layout(uint32_t fmt, uint64_t nc, uint64_t table_off[3], uint64_t index_off[3], uint64_t *payload_off)
+{
+    uint64_t off = kHeaderBytes;
+    const int nf = num_fields(fmt);
+    for (int f = 0; f < nf; f++) { table_off[f] = off; off += pad16(1ull << sym_bits(fmt, f)); }
+    for (int f = 0; f < nf; f++) { index_off[f] = off; off += pad16(4 * (nc + 1)); }
+    *payload_off = off;
+}
+
+void put32(uint8_t *p, uint32_t v) { std::memcpy(p, &v, 4); }
+void put64(uint8_t *p, uint64_t v) { std::memcpy(p, &v, 8); }
+uint32_t get32(const uint8_t *p) { uint32_t v; std::memcpy(&v, p, 4); return v; }
+uint64_t get64(const uint8_t *p) { uint64_t v; std::memcpy(&v, p, 8); return v; }
+
+// ---- workspace carving ------------------------------------------------------
+struct Workspace {
+    uint64_t descs, hist_work, scale_work, chunk_work, hist, enc, units, scan, blobs, total;
+    uint32_t n_hist_work, n_scale_work, n_chunk_work;
+    uint64_t n_units;
+};
+
+uint64_t align256(uint64_t x) { return (x + 255) / 256 * 256; }
+constexpr uint64_t kBlobBytes = 1024;     // header + code-length tables of one tensor (<= 64 + 3*256)
+
+zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T, Workspace *w)
+{
+    uint64_t hw = 0, sw = 0, cw = 0, units = 0;
+    const uint32_t cpi = chunks_per_work_item(g.S);
+    for (uint32_t t = 0; t < T; t++) {
+        uint64_t nc;
+        zc_status st = check_count(g, n_elems[t], &nc);
+        if (st) return st;
+        const uint64_t bytes = (n_elems[t] * (uint64_t)elem_bits(g.fmt) + 7) / 8;
+        hw += (bytes + kHistBlockBytes - 1) / kHistBlockBytes;
+        if (g.nf == 3) sw += (n_elems[t] / 32 + kHistBlockBytes - 1) / kHistBlockBytes;
+        cw += (nc + cpi - 1) / cpi;
+        units += nc * g.nf;
+    }
+    if (hw > 0x7FFFFFFFull || cw > 0x7FFFFFFFull || units > 0xFFFFFFFFull) return ZC_ERR_INVALID_ARG;
+    uint64_t off = 0;
+    w->descs = off; off = align256(off + (uint64_t)T * sizeof(TensorDev));
+    w->hist_work = off; off = align256(off + hw * sizeof(WorkItem));
+    w->scale_work = off; off = align256(off + sw * sizeof(WorkItem));
+    w->chunk_work = off; off = align256(off + cw * sizeof(WorkItem));
+    w->hist = off; off = align256(off + (uint64_t)T * 3 * 256 * 8);
+    w->enc = off; off = align256(off + (uint64_t)T * 768 * 4);
+    w->units = off; off = align256(off + units * 4);
+    w->scan = off; off = align256(off + (uint64_t)T * sizeof(ScanOut));
+    w->blobs = off; off = align256(off + (uint64_t)T * kBlobBytes);
+    w->total = off;
+    w->n_hist_work = (uint32_t)hw; w->n_scale_work = (uint32_t)sw; w->n_chunk_work = (uint32_t)cw; w->n_units = units;
+    return ZC_OK;
+}
+
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) return ZC_ERR_DEVICE; } while (0)
+#define LAUNCH_TRY(expr) do { if ((expr) != 0) return ZC_ERR_DEVICE; } while (0)
+
+// ---- code construction from the device histograms ---------------------------
+struct FieldCode {
+    uint64_t hist[256];
+    uint8_t len[256];
+    uint16_t code[256];
+    uint32_t mode, lmax, konst, distinct;
+    uint64_t n_symbols, payload_bits;
+};
+
+// hist3: the three 256-bin device histograms of one tensor (meaning depends on the format)
+zc_status build_codes(const Geometry &g, uint32_t policy, uint64_t n_elems, const uint64_t *hist3, FieldCode fc[3])
+{
+    for (uint32_t f = 0; f < g.nf; f++) {
+        FieldCode &c = fc[f];
+        std::memset(&c, 0, sizeof(c));
+        const int sb = sym_bits(g.fmt, (int)f), A = 1 << sb;
+        // marginals of the joint byte histogram (FP8: one element per byte, FP4: two)
+        if (g.fmt == ZC_FMT_BF16) std::memcpy(c.hist, hist3 + 256 * f, 256 * 8);
+        else if (g.fmt == ZC_FMT_FP8_E4M3) {
+            for (int b = 0; b < 256; b++) {
+                const int sym = f == 0 ? (b >> 3) & 0xF : ((b >> 4) & 8) | (b & 7);
+                c.hist[sym] += hist3[b];
+            }
+        } else if (f == 2) std::memcpy(c.hist, hist3 + 512, 256 * 8);
+        else {
+            for (int b = 0; b < 256; b++)
+                for (int h = 0; h < 2; h++) {
+                    const int nib = (b >> (4 * h)) & 0xF;
+                    const int sym = f == 0 ? (nib >> 1) & 3 : ((nib >> 2) & 2) | (nib & 1);
+                    c.hist[sym] += hist3[b];
+                }
+        }
+        c.n_symbols = field_symbols(g.fmt, (int)f, n_elems);
+        uint64_t sum = 0;
+        for (int v = 0; v < A; v++) { sum += c.hist[v]; if (c.hist[v]) { c.distinct++; c.konst = (uint32_t)v; } }
+        if (sum != c.n_symbols) return ZC_ERR_DEVICE;          // the histogram kernel must count every symbol once
+        c.mode = ZC_MODE_EMPTY;
+        if (c.distinct == 1) c.mode = ZC_MODE_CONST;
+        else if (c.distinct > 1) {
+            c.konst = 0;
+            if (!build_code_lengths(c.hist, A, g.limit[f], c.len)) return ZC_ERR_INVALID_ARG;
+            for (int v = 0; v < A; v++) { c.payload_bits += c.hist[v] * c.len[v]; if (c.len[v] > c.lmax) c.lmax = c.len[v]; }
+            c.mode = ZC_MODE_HUFF;
+            // Sec. 3.1: a field that does not compress is stored as is
+            if (policy == ZC_POLICY_AUTO && 16 * c.payload_bits > 15 * c.n_symbols * (uint64_t)sb) {
+                c.mode = ZC_MODE_RAW; c.lmax = 0; std::memset(c.len, 0, sizeof(c.len));
+                c.payload_bits = c.n_symbols * (uint64_t)sb;
+            } else assign_canonical(c.len, A, c.code);
+        }
+    }
+    return ZC_OK;
+}
+
+uint32_t reverse_bits(uint32_t v, int n)
+{
+    uint32_t r = 0;
+    for (int i = 0; i < n; i++) r |= ((v >> i) & 1u) << (n - 1 - i);
+    return r;
+}
+
+void fill_info(const Geometry &g, uint32_t policy, bool xor_delta, uint64_t n_elems, uint64_t nc, const FieldCode fc[3], uint64_t total, zc_info *info)
+{
+    std::memset(info, 0, sizeof(*info));
+    info->format = g.fmt; info->policy = policy; info->streams = g.S; info->n_fields = g.nf;
+    info->xor_delta = xor_delta; info->chunk_bytes = g.chunk_bytes; info->n_chunks = (uint32_t)nc;
+    info->n_elems = n_elems; info->total_bytes = total;
+    layout(g.fmt, nc, info->table_offset, info->index_offset, &info->payload_offset);
+    for (uint32_t f = 0; f < g.nf; f++) {
+        info->mode[f] = (uint8_t)fc[f].mode; info->sym_bits[f] = (uint8_t)sym_bits(g.fmt, (int)f);
+        info->max_len[f] = (uint8_t)fc[f].lmax; info->const_symbol[f] = (uint8_t)fc[f].konst;
+        std::memcpy(info->code_len[f], fc[f].len, 256);
+    }
+}
+
+// header + tables exactly as they sit at the start of the container (total_bytes is
+// patched in by the scan kernel)
+void serialize_blob(const zc_info &info, uint8_t *blob)
+{
+    std::memset(blob, 0, kBlobBytes);
+    put32(blob, kMagic);
+    blob[4] = 1; blob[6] = (uint8_t)info.format; blob[7] = (uint8_t)info.policy;
+    blob[8] = (uint8_t)info.streams; blob[9] = (uint8_t)info.n_fields; blob[10] = (uint8_t)(info.xor_delta ? 1 : 0);
+    put32(blob + 12, info.chunk_bytes);
+    put64(blob + 16, info.n_elems);
+    put32(blob + 24, info.n_chunks);
+    for (uint32_t f = 0; f < info.n_fields; f++) {
+        blob[32 + 4 * f] = info.mode[f]; blob[33 + 4 * f] = info.sym_bits[f];
+        blob[34 + 4 * f] = info.max_len[f]; blob[35 + 4 * f] = info.const_symbol[f];
+        std::memcpy(blob + info.table_offset[f], info.code_len[f], (size_t)1 << info.sym_bits[f]);
+    }
+    put64(blob + 48, info.total_bytes);
+    put64(blob + 56, info.payload_offset);
+}
+
+TensorDev make_desc(const zc_info &info)
+{
+    TensorDev d;
+    std::memset(&d, 0, sizeof(d));
+    d.n_elems = info.n_elems; d.total_bytes = info.total_bytes; d.payload_off = info.payload_offset;
+    d.n_chunks = info.n_chunks; d.chunk_bytes = info.chunk_bytes; d.streams = info.streams;
+    for (uint32_t f = 0; f < info.n_fields; f++) {
+        d.table_off[f] = (uint32_t)info.table_offset[f]; d.index_off[f] = (uint32_t)info.index_offset[f];
+        d.mode[f] = info.mode[f]; d.lmax[f] = info.max_len[f]; d.konst[f] = info.const_symbol[f];
+        d.period[f] = (uint8_t)refill_period(run_len(info.format, (int)f), info.max_len[f]);
+    }
+    return d;
+}
+
+// shared by zc_compress_batch and zc_stats: histogram -> codes (-> sizes -> scan [-> encode])
+zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, void *d_ws, uint64_t ws_bytes, void *stream,
+                       bool stats_only, std::vector<FieldCode> *codes_out, std::vector<ScanOut> *scan_out)
+{
+    Geometry g;
+    zc_status st = check_params(params, &g);
+    if (st) return st;
+    if (T == 0) return ZC_OK;
+    if (!tensors || !d_ws || !aligned16(d_ws)) return ZC_ERR_INVALID_ARG;
+    std::vector<uint64_t> counts(T);
+    for (uint32_t t = 0; t < T; t++) {
+        zc_tensor &x = tensors[t];
+        counts[t] = x.n_elems;
+        if (x.n_elems && (!x.d_src || !aligned16(x.d_src))) return ZC_ERR_INVALID_ARG;
+        if (x.d_xor_base && !aligned16(x.d_xor_base)) return ZC_ERR_INVALID_ARG;
+        if (g.nf == 3 && x.n_elems && (!x.d_scales || !aligned16(x.d_scales))) return ZC_ERR_INVALID_ARG;
+        if (!stats_only && (!x.d_comp || !aligned16(x.d_comp))) return ZC_ERR_INVALID_ARG;
+    }
+    Workspace w;
+    st = plan_workspace(g, counts.data(), T, &w);
+    if (st) return st;
+    if (ws_bytes < w.total) return ZC_ERR_BUFFER_TOO_SMALL;
+    uint8_t *ws = (uint8_t *)d_ws;
+    hipStream_t hs = (hipStream_t)stream;
+    const uint32_t cpi = chunks_per_work_item(g.S);
+
+    // descriptors and work lists
+    std::vector<TensorDev> descs(T);
+    std::vector<WorkItem> hist_work, scale_work, chunk_work;
+    std::vector<uint64_t> ncs(T);
+    uint64_t units_off = 0;
+    for (uint32_t t = 0; t < T; t++) {
+        zc_tensor &x = tensors[t];
+        uint64_t nc;
+        check_count(g, x.n_elems, &nc);
+        ncs[t] = nc;
+        uint64_t table_off[3] = {0, 0, 0}, index_off[3] = {0, 0, 0}, payload_off;
+        layout(g.fmt, nc, table_off, index_off, &payload_off);
+        if (!stats_only && x.comp_capacity < payload_off) return ZC_ERR_BUFFER_TOO_SMALL;
+        TensorDev &d = descs[t];
+        std::memset(&d, 0, sizeof(d));
+        d.src = (const uint8_t *)x.d_src; d.base = (const uint8_t *)x.d_xor_base; d.scales = (const uint8_t *)x.d_scales;
+        d.comp = stats_only ? nullptr : (uint8_t *)x.d_comp;
+        d.n_elems = x.n_elems; d.n_chunks = (uint32_t)nc; d.chunk_bytes = g.chunk_bytes; d.streams = g.S;
+        d.payload_off = payload_off;
+        for (uint32_t f = 0; f < g.nf; f++) { d.table_off[f] = (uint32_t)table_off[f]; d.index_off[f] = (uint32_t)index_off[f]; }
+        d.units_off = (uint32_t)units_off;
+        units_off += nc * g.nf;
+        const uint64_t bytes = (x.n_elems * (uint64_t)elem_bits(g.fmt) + 7) / 8;
+        for (uint64_t b = 0; b * kHistBlockBytes < bytes; b++) hist_work.push_back({t, (uint32_t)b});
+        if (g.nf == 3) for (uint64_t b = 0; b * kHistBlockBytes < x.n_elems / 32; b++) scale_work.push_back({t, (uint32_t)b});
+        for (uint64_t c = 0; c < nc; c += cpi) chunk_work.push_back({t, (uint32_t)c});
+    }
+    TensorDev *d_descs = (TensorDev *)(ws + w.descs);
+    uint64_t *d_hist = (uint64_t *)(ws + w.hist);
+    HIP_TRY(hipMemcpyAsync(d_descs, descs.data(), T * sizeof(TensorDev), hipMemcpyHostToDevice, hs));
+    if (!hist_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
+    if (!scale_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
+    if (!chunk_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.chunk_work, chunk_work.data(), chunk_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
+    HIP_TRY(hipMemsetAsync(d_hist, 0, (uint64_t)T * 3 * 256 * 8, hs));
+
+    // field split + histogram (a1-a3)
+    LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
+    if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), 1, d_hist, stream));
+    std::vector<uint64_t> hist((size_t)T * 768);
+    HIP_TRY(hipMemcpyAsync(hist.data(), d_hist, hist.size() * 8, hipMemcpyDeviceToHost, hs));
+    HIP_TRY(hipStreamSynchronize(hs));
+
+    // code construction on the host (a4)
+    std::vector<FieldCode> codes((size_t)T * 3);
+    std::vector<uint32_t> enc((size_t)T * 768, 0);
+    std::vector<uint8_t> blobs((size_t)T * kBlobBytes, 0);
+    for (uint32_t t = 0; t < T; t++) {
+        FieldCode *fc = &codes[(size_t)t * 3];
+        st = build_codes(g, params->policy, tensors[t].n_elems, &hist[(size_t)t * 768], fc);
+        if (st) return st;
+        fill_info(g, params->policy, tensors[t].d_xor_base != nullptr, tensors[t].n_elems, ncs[t], fc, 0, &tensors[t].info);
+        serialize_blob(tensors[t].info, &blobs[(size_t)t * kBlobBytes]);
+        for (uint32_t f = 0; f < g.nf; f++) {
+            descs[t].mode[f] = (uint8_t)fc[f].mode; descs[t].lmax[f] = (uint8_t)fc[f].lmax; descs[t].konst[f] = (uint8_t)fc[f].konst;
+            descs[t].period[f] = (uint8_t)refill_period(run_len(g.fmt, (int)f), (int)fc[f].lmax);
+            for (int v = 0; v < 256; v++)
+                enc[(size_t)t * 768 + f * 256 + v] = ((uint32_t)fc[f].len[v] << 16) | reverse_bits(fc[f].code[v], fc[f].len[v]);
+        }
+    }
+    if (codes_out) *codes_out = codes;
+    HIP_TRY(hipMemcpyAsync(d_descs, descs.data(), T * sizeof(TensorDev), hipMemcpyHostToDevice, hs));
+    HIP_TRY(hipMemcpyAsync(ws + w.enc, enc.data(), enc.size() * 4, hipMemcpyHostToDevice, hs));
+    if (!stats_only) {
+        HIP_TRY(hipMemcpyAsync(ws + w.blobs, blobs.data(), blobs.size(), hipMemcpyHostToDevice, hs));
+        LAUNCH_TRY(launch_write_headers(d_descs, T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
+    }
+
+    // stream sizes (a5) and their exclusive scan into the chunk index (a6)
+    const uint32_t *d_enc = (const uint32_t *)(ws + w.enc);
+    uint32_t *d_units = (uint32_t *)(ws + w.units);
+    LAUNCH_TRY(launch_sizes(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)chunk_work.size(), cpi, d_enc, d_units, stream));
+    LAUNCH_TRY(launch_scan(d_descs, T, (int)g.nf, d_units, (ScanOut *)(ws + w.scan), stream));
+    std::vector<ScanOut> scan(T);
+    HIP_TRY(hipMemcpyAsync(scan.data(), ws + w.scan, T * sizeof(ScanOut), hipMemcpyDeviceToHost, hs));
+    HIP_TRY(hipStreamSynchronize(hs));
+    for (uint32_t t = 0; t < T; t++) {
+        const uint64_t total = descs[t].payload_off + 16ull * scan[t].total_units;
+        tensors[t].out_bytes = total;
+        tensors[t].info.total_bytes = total;
+        if (!stats_only && total > tensors[t].comp_capacity) return ZC_ERR_BUFFER_TOO_SMALL;
+    }
+    if (scan_out) *scan_out = scan;
+    if (stats_only) return ZC_OK;
+
+    // chunked encode (a7)
+    LAUNCH_TRY(launch_encode(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)chunk_work.size(), cpi, d_enc, stream));
+    return ZC_OK;
+}
+
+zc_status parse_info(const uint8_t *c, uint64_t have, uint64_t comp_bytes, zc_info *out)
+{
+    if (have < kHeaderBytes || comp_bytes < kHeaderBytes) return ZC_ERR_CORRUPT;
+    if (get32(c) != kMagic || c[4] != 1 || c[5] != 0) return ZC_ERR_CORRUPT;
+    std::memset(out, 0, sizeof(*out));
+    out->format = c[6]; out->policy = c[7]; out->streams = c[8]; out->n_fields = c[9]; out->xor_delta = c[10] & 1;
+    out->chunk_bytes = get32(c + 12); out->n_elems = get64(c + 16); out->n_chunks = get32(c + 24);
+    out->total_bytes = get64(c + 48); out->payload_offset = get64(c + 56);
+    zc_params p;
+    std::memset(&p, 0, sizeof(p));
+    p.struct_size = sizeof(p); p.format = out->format; p.chunk_bytes = out->chunk_bytes; p.streams_per_chunk = out->streams; p.policy = out->policy;
+    Geometry g;
+    if (out->streams == 0 || check_params(&p, &g) != ZC_OK || out->n_fields != g.nf) return ZC_ERR_CORRUPT;
+    uint64_t nc;
+    if (check_count(g, out->n_elems, &nc) != ZC_OK || nc != out->n_chunks) return ZC_ERR_CORRUPT;
+    uint64_t payload;
+    layout(out->format, nc, out->table_offset, out->index_offset, &payload);
+    if (payload != out->payload_offset || out->total_bytes < payload || out->total_bytes > comp_bytes || (out->total_bytes - payload) % 16) return ZC_ERR_CORRUPT;
+    for (uint32_t f = 0; f < g.nf; f++) {
+        out->mode[f] = c[32 + 4 * f]; out->sym_bits[f] = c[33 + 4 * f]; out->max_len[f] = c[34 + 4 * f]; out->const_symbol[f] = c[35 + 4 * f];
+        if (out->mode[f] > ZC_MODE_CONST || out->sym_bits[f] != sym_bits(out->format, (int)f)) return ZC_ERR_CORRUPT;
+        const uint32_t A = 1u << out->sym_bits[f];
+        if (out->table_offset[f] + A > have) return ZC_ERR_CORRUPT;
+        std::memcpy(out->code_len[f], c + out->table_offset[f], A);
+        if (out->mode[f] == ZC_MODE_HUFF) {
+            uint64_t kraft = 0;
+            uint32_t lmax = 0;
+            for (uint32_t v = 0; v < A; v++) {
+                const uint32_t l = out->code_len[f][v];
+                if (l > 16) return ZC_ERR_CORRUPT;
+                if (l) { kraft += 1ull << (16 - l); if (l > lmax) lmax = l; }
+            }
+            if (kraft != 65536 || lmax != out->max_len[f]) return ZC_ERR_CORRUPT;   // complete prefix code
+        } else if (out->const_symbol[f] >= A) return ZC_ERR_CORRUPT;
+        if (out->mode[f] == ZC_MODE_EMPTY && out->n_elems) return ZC_ERR_CORRUPT;
+    }
+    return ZC_OK;
+}
+
+zc_status check_index(const zc_info &info, const uint8_t *d_comp, hipStream_t hs)
+{
+    uint32_t prev = 0;
+    std::vector<uint32_t> idx((size_t)info.n_chunks + 1);
+    for (uint32_t f = 0; f < info.n_fields; f++) {
+        HIP_TRY(hipMemcpyAsync(idx.data(), d_comp + info.index_offset[f], idx.size() * 4, hipMemcpyDeviceToHost, hs));
+        HIP_TRY(hipStreamSynchronize(hs));
+        if (idx[0] != prev) return ZC_ERR_CORRUPT;
+        for (size_t i = 0; i < idx.size(); i++) { if (idx[i] < prev) return ZC_ERR_CORRUPT; prev = idx[i]; }
+    }
+    if (info.payload_offset + 16ull * prev != info.total_bytes) return ZC_ERR_CORRUPT;
+    return ZC_OK;
+}
+
+zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *info_in, const uint32_t *d_ids, uint32_t n_ids, bool by_ids,
+                        void *d_dst, uint64_t dst_capacity, void *d_scales_out, const void *d_xor_base, void *stream)
+{
+    if (!d_comp || !aligned16(d_comp)) return ZC_ERR_INVALID_ARG;
+    zc_info local;
+    if (!info_in) {
+        zc_status st = zc_read_info(d_comp, comp_bytes, 0, &local, stream);
+        if (st) return st;
+        info_in = &local;
+    }
+    const zc_info &info = *info_in;
+    if (!elem_bits(info.format) || info.total_bytes > comp_bytes || info.streams == 0) return ZC_ERR_INVALID_ARG;
+    const uint64_t raw = (info.n_elems * (uint64_t)elem_bits(info.format) + 7) / 8;
+    const uint64_t need = by_ids ? (uint64_t)n_ids * info.chunk_bytes : raw;
+    const uint32_t slots = by_ids ? n_ids : info.n_chunks;
+    if (slots == 0) return ZC_OK;
+    if (by_ids && !d_ids) return ZC_ERR_INVALID_ARG;
+    if (!d_dst || !aligned16(d_dst)) return ZC_ERR_INVALID_ARG;
+    if (dst_capacity < need) return ZC_ERR_BUFFER_TOO_SMALL;
+    if (info.n_fields == 3 && (!d_scales_out || !aligned16(d_scales_out))) return ZC_ERR_INVALID_ARG;
+    if (info.xor_delta && (!d_xor_base || !aligned16(d_xor_base))) return ZC_ERR_INVALID_ARG;
+    TensorDev d = make_desc(info);
+    d.comp = (uint8_t *)d_comp; d.dst = (uint8_t *)d_dst; d.scales_out = (uint8_t *)d_scales_out;
+    d.base = info.xor_delta ? (const uint8_t *)d_xor_base : nullptr;
+    const uint32_t cpi = chunks_per_work_item(info.streams);
+    const uint32_t n_work = (slots + cpi - 1) / cpi;
+    LAUNCH_TRY(launch_decode(info.format, nullptr, nullptr, n_work, cpi, &d, by_ids ? d_ids : nullptr, n_ids, stream));
+    return ZC_OK;
+}
+
+}  // namespace
+
+// ----------------------------------------------------------------------- C ABI
+
+extern "C" {
+
+const char *zc_status_string(zc_status s)
+{
+    switch (s) {
+    case ZC_OK: return "ok";
+    case ZC_ERR_INVALID_ARG: return "invalid argument";
+    case ZC_ERR_UNSUPPORTED: return "unsupported format or struct size";
+    case ZC_ERR_BUFFER_TOO_SMALL: return "buffer too small";
+    case ZC_ERR_CORRUPT: return "corrupt container";
+    case ZC_ERR_DEVICE: return "device error";
+    }
+    return "unknown status";
+}
+
+uint64_t zc_compress_bound(uint64_t n_elems, const zc_params *params)
+{
+    Geometry g;
+    uint64_t nc;
+    if (check_params(params, &g) || check_count(g, n_elems, &nc)) return 0;
+    uint64_t table_off[3], index_off[3], total;
+    layout(g.fmt, nc, table_off, index_off, &total);
+    for (uint32_t f = 0; f < g.nf; f++) {
+        // per lane: its bits rounded up to a word plus two look-ahead words; per stream: padding
+        const uint64_t ns = field_symbols(g.fmt, (int)f, n_elems);
+        total += nc * ((uint64_t)g.S * 12 + 32) + pad16((ns * (uint64_t)g.limit[f] + 7) / 8);
+    }
+    return total;
+}
+
+uint64_t zc_workspace_bytes(const uint64_t *n_elems, uint32_t n_tensors, const zc_params *params)
+{
+    Geometry g;
+    Workspace w;
+    if (!n_elems || check_params(params, &g) || plan_workspace(g, n_elems, n_tensors, &w)) return 0;
+    return w.total;
+}
+
+zc_status zc_build_code(const uint64_t *hist, uint32_t alphabet, uint32_t limit, uint8_t *len_out, uint16_t *code_out)
+{
+    if (!hist || !len_out || !code_out || alphabet == 0 || alphabet > 256) return ZC_ERR_INVALID_ARG;
+    if (!build_code_lengths(hist, (int)alphabet, (int)limit, len_out)) return ZC_ERR_INVALID_ARG;
+    assign_canonical(len_out, (int)alphabet, code_out);
+    return ZC_OK;
+}
+
+zc_status zc_compress_batch(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params, void *d_ws, uint64_t ws_bytes, void *stream)
+{
+    return run_compress(tensors, n_tensors, params, d_ws, ws_bytes, stream, false, nullptr, nullptr);
+}
+
+zc_status zc_compress(const void *d_src, uint64_t n_elems, const zc_params *params, const void *d_xor_base, const void *d_scales,
+                      void *d_dst, uint64_t dst_capacity, uint64_t *out_bytes, zc_info *out_info, void *d_ws, uint64_t ws_bytes, void *stream)
+{
+    if (!out_bytes) return ZC_ERR_INVALID_ARG;
+    zc_tensor t;
+    std::memset(&t, 0, sizeof(t));
+    t.d_src = d_src; t.d_xor_base = d_xor_base; t.d_scales = d_scales; t.n_elems = n_elems;
+    t.d_comp = d_dst; t.comp_capacity = dst_capacity;
+    zc_status st = run_compress(&t, 1, params, d_ws, ws_bytes, stream, false, nullptr, nullptr);
+    if (st) return st;
+    *out_bytes = t.out_bytes;
+    if (out_info) *out_info = t.info;
+    return ZC_OK;
+}
+
+zc_status zc_stats(const void *d_src, uint64_t n_elems, const zc_params *params, const void *d_xor_base, const void *d_scales,
+                   zc_stats_out *out, void *d_ws, uint64_t ws_bytes, void *stream)
+{
+    if (!out) return ZC_ERR_INVALID_ARG;
+    zc_tensor t;
+    std::memset(&t, 0, sizeof(t));
+    t.d_src = d_src; t.d_xor_base = d_xor_base; t.d_scales = d_scales; t.n_elems = n_elems;
+    std::vector<FieldCode> codes;
+    std::vector<ScanOut> scan;
+    zc_status st = run_compress(&t, 1, params, d_ws, ws_bytes, stream, true, &codes, &scan);
+    if (st) return st;
+    std::memset(out, 0, sizeof(*out));
+    const uint32_t fmt = params->format;
+    out->n_fields = (uint32_t)num_fields(fmt);
+    out->raw_bytes = (n_elems * (uint64_t)elem_bits(fmt) + 7) / 8 + (out->n_fields == 3 ? n_elems / 32 : 0);
+    out->container_bytes = t.out_bytes;
+    uint64_t all_bits = 0;
+    for (uint32_t f = 0; f < out->n_fields; f++) {
+        const FieldCode &c = codes[f];
+        zc_field_stats &fs = out->field[f];
+        const int sb = sym_bits(fmt, (int)f);
+        fs.alphabet = 1u << sb; fs.distinct = c.distinct; fs.mode = c.mode; fs.max_len = c.lmax; fs.n_symbols = c.n_symbols;
+        std::memcpy(fs.hist, c.hist, sizeof(fs.hist));
+        std::memcpy(fs.code_len, c.len, sizeof(fs.code_len));
+        for (uint32_t v = 0; v < fs.alphabet; v++)
+            if (c.hist[v]) { const double p = (double)c.hist[v] / (double)c.n_symbols; fs.entropy_bits -= p * std::log2(p); }
+        fs.payload_bits = c.mode == ZC_MODE_CONST ? 0 : c.payload_bits;
+        if (c.n_symbols) {
+            fs.mean_code_len = (double)fs.payload_bits / (double)c.n_symbols;
+            fs.ratio_payload = (double)fs.payload_bits / ((double)c.n_symbols * sb);
+        }
+        fs.stream_bytes = 16ull * scan[0].field_units[f];
+        all_bits += fs.payload_bits;
+    }
+    if (out->raw_bytes) {
+        out->ratio_payload_total = (double)all_bits / (8.0 * (double)out->raw_bytes);
+        out->ratio_container_total = (double)out->container_bytes / (double)out->raw_bytes;
+    }
+    return ZC_OK;
+}
+
+zc_status zc_read_info(const void *d_comp, uint64_t comp_bytes, int check_index_too, zc_info *out, void *stream)
+{
+    if (!d_comp || !out) return ZC_ERR_INVALID_ARG;
+    if (comp_bytes < kHeaderBytes) return ZC_ERR_CORRUPT;
+    uint8_t head[kBlobBytes];
+    const uint64_t have = comp_bytes < kBlobBytes ? comp_bytes : kBlobBytes;
+    hipStream_t hs = (hipStream_t)stream;
+    HIP_TRY(hipMemcpyAsync(head, d_comp, have, hipMemcpyDeviceToHost, hs));
+    HIP_TRY(hipStreamSynchronize(hs));
+    zc_status st = parse_info(head, have, comp_bytes, out);
+    if (st) return st;
+    if (check_index_too) return check_index(*out, (const uint8_t *)d_comp, hs);
+    return ZC_OK;
+}
+
+zc_status zc_decompress(const void *d_comp, uint64_t comp_bytes, const zc_info *info, void *d_dst, uint64_t dst_capacity,
+                        void *d_scales_out, const void *d_xor_base, void *stream)
+{
+    return decode_common(d_comp, comp_bytes, info, nullptr, 0, false, d_dst, dst_capacity, d_scales_out, d_xor_base, stream);
+}
+
+zc_status zc_decompress_chunks(const void *d_comp, uint64_t comp_bytes, const zc_info *info, const uint32_t *d_chunk_ids, uint32_t n_ids,
+                               void *d_dst, uint64_t dst_capacity, void *d_scales_out, const void *d_xor_base, void *stream)
+{
+    return decode_common(d_comp, comp_bytes, info, d_chunk_ids, n_ids, true, d_dst, dst_capacity, d_scales_out, d_xor_base, stream);
+}
+
+zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors, void *d_ws, uint64_t ws_bytes, void *stream)
+{
+    if (n_tensors == 0) return ZC_OK;
+    if (!tensors || !d_ws || !aligned16(d_ws)) return ZC_ERR_INVALID_ARG;
+    const uint32_t fmt = tensors[0].info.format, S = tensors[0].info.streams;
+    if (!elem_bits(fmt) || S == 0 || S > 64 || (S & (S - 1))) return ZC_ERR_INVALID_ARG;
+    const uint32_t cpi = chunks_per_work_item(S);
+    std::vector<TensorDev> descs(n_tensors);
+    std::vector<WorkItem> work;
+    for (uint32_t t = 0; t < n_tensors; t++) {
+        const zc_tensor &x = tensors[t];
+        const zc_info &info = x.info;
+        if (info.format != fmt || info.streams != S) return ZC_ERR_INVALID_ARG;
+        if (!x.d_comp || !aligned16(x.d_comp) || (info.n_elems && (!x.d_dst || !aligned16(x.d_dst)))) return ZC_ERR_INVALID_ARG;
+        if (info.n_fields == 3 && info.n_elems && (!x.d_scales_out || !aligned16(x.d_scales_out))) return ZC_ERR_INVALID_ARG;
+        if (info.xor_delta && (!x.d_xor_base || !aligned16(x.d_xor_base))) return ZC_ERR_INVALID_ARG;
+        if (info.total_bytes > x.out_bytes && info.total_bytes > x.comp_capacity) return ZC_ERR_INVALID_ARG;
+        descs[t] = make_desc(info);
+        descs[t].comp = (uint8_t *)x.d_comp; descs[t].dst = (uint8_t *)x.d_dst; descs[t].scales_out = (uint8_t *)x.d_scales_out;
+        descs[t].base = info.xor_delta ? (const uint8_t *)x.d_xor_base : nullptr;
+        for (uint32_t c = 0; c < info.n_chunks; c += cpi) work.push_back({t, c});
+    }
+    const uint64_t descs_bytes = align256((uint64_t)n_tensors * sizeof(TensorDev));
+    if (ws_bytes < descs_bytes + work.size() * sizeof(WorkItem)) return ZC_ERR_BUFFER_TOO_SMALL;
+    hipStream_t hs = (hipStream_t)stream;
+    uint8_t *ws = (uint8_t *)d_ws;
+    HIP_TRY(hipMemcpyAsync(ws, descs.data(), descs.size() * sizeof(TensorDev), hipMemcpyHostToDevice, hs));
+    if (work.empty()) return ZC_OK;
+    HIP_TRY(hipMemcpyAsync(ws + descs_bytes, work.data(), work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
+    HIP_TRY(hipStreamSynchronize(hs));      // the host arrays above go away when this call returns
+    LAUNCH_TRY(launch_decode(fmt, (const TensorDev *)ws, (const WorkItem *)(ws + descs_bytes), (uint32_t)work.size(), cpi, nullptr, nullptr, 0, stream));
+    return ZC_OK;
+}
+
+}  // extern "C"

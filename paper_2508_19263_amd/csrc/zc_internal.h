@@ -1,0 +1,78 @@
+// Internal declarations shared by the host side (zc_api.cpp, zc_codebook.cpp) and the
+// kernels (zc_kernels.hip) of the HIP library.  Not part of the C ABI.
+#pragma once
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/zc.h"
+
+namespace zc {
+
+constexpr uint32_t kMagic = 0x0031435Au;   // "ZC1\0"
+constexpr uint32_t kHeaderBytes = 64;
+constexpr int kMaxFields = 3;
+
+// ---- format geometry -------------------------------------------------------
+inline int elem_bits(uint32_t fmt) { return fmt == ZC_FMT_BF16 ? 16 : fmt == ZC_FMT_FP8_E4M3 ? 8 : fmt == ZC_FMT_FP4_E2M1_MX ? 4 : 0; }
+inline int num_fields(uint32_t fmt) { return fmt == ZC_FMT_FP4_E2M1_MX ? 3 : 2; }
+inline int sym_bits(uint32_t fmt, int f) { return fmt == ZC_FMT_BF16 ? 8 : fmt == ZC_FMT_FP8_E4M3 ? 4 : (f == 2 ? 8 : 2); }
+// symbols per 16-byte run of the field's plain array
+inline int run_len(uint32_t fmt, int f) { return (fmt == ZC_FMT_FP4_E2M1_MX && f == 2) ? 16 : 128 / elem_bits(fmt); }
+inline uint64_t pad16(uint64_t x) { return (x + 15) / 16 * 16; }
+// refill period of a field's stream: symbols between two refill steps
+inline int refill_period(int G, int lmax)
+{
+    int r = 1;
+    if (lmax < 1) lmax = 1;
+    while (2 * r * lmax <= 32) r *= 2;
+    return r < G ? r : G;
+}
+
+// ---- per-tensor descriptor handed to every kernel --------------------------
+struct alignas(16) TensorDev {
+    const uint8_t *src;       // compress: elements
+    const uint8_t *base;      // XOR base or null
+    const uint8_t *scales;    // compress, FP4: scale bytes
+    uint8_t *comp;            // container
+    uint8_t *dst;             // decompress: elements out
+    uint8_t *scales_out;      // decompress, FP4
+    uint64_t n_elems;
+    uint64_t total_bytes;     // decompress: container size (bounds for reads)
+    uint64_t payload_off;
+    uint32_t n_chunks;
+    uint32_t chunk_bytes;
+    uint32_t table_off[kMaxFields];
+    uint32_t index_off[kMaxFields];
+    uint32_t units_off;       // compress: first entry of this tensor in the units array (field-major, n_chunks each)
+    uint32_t streams;         // S
+    uint8_t mode[4], lmax[4], konst[4], period[4];
+};
+
+struct WorkItem { uint32_t tensor, first; };   // `first`: first chunk / block of the item
+
+// histogram block: bytes of input handled by one workgroup pass
+constexpr uint32_t kHistBlockBytes = 256 * 1024;
+// chunks (or chunk slots) handled by one workgroup of the chunk kernels
+constexpr uint32_t kWavesPerGroup = 4;
+
+// per-tensor scratch written by the scan kernel and read back by the host
+struct ScanOut { uint32_t field_units[kMaxFields]; uint32_t total_units; };
+
+// ---- host-side code construction (zc_codebook.cpp) --------------------------
+// Length-limited canonical Huffman code; returns false if 2^limit < used symbols.
+bool build_code_lengths(const uint64_t *hist, int alphabet, int limit, uint8_t *len_out);
+void assign_canonical(const uint8_t *len, int alphabet, uint16_t *code_out);
+
+// ---- kernel launchers (zc_kernels.hip); all return a hipError_t as int ------
+int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+                int scales_view, uint64_t *d_hist, void *stream);
+int launch_write_headers(const TensorDev *d_descs, uint32_t n_tensors, const uint8_t *d_blobs, uint32_t blob_bytes, int n_fields, void *stream);
+int launch_sizes(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
+                 const uint32_t *d_enc_tables, uint32_t *d_units, void *stream);
+int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, const uint32_t *d_units, ScanOut *d_out, void *stream);
+int launch_encode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
+                  const uint32_t *d_enc_tables, void *stream);
+int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
+                  const TensorDev *single, const uint32_t *d_ids, uint32_t n_ids, void *stream);
+uint32_t chunks_per_work_item(uint32_t streams);
+
+}  // namespace zc

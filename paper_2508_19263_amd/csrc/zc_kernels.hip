@@ -1,0 +1,771 @@
+// HIP kernels (gfx950, wave64) of the field-split Huffman codec.
+//
+//   k_hist     field split + histogram over a tensor            (paper Sec. 3.1 / 3.2 / 3.4)
+//   k_encode   per-chunk stream sizes (dry run) and the chunked encoder
+//   k_scan     exclusive scan of the stream sizes into the chunk index
+//   k_decode   chunked table-driven decode fused with the re-interleave of the fields
+//
+// Stream layout of one (chunk, field): the chunk's symbols are dealt to S lanes in runs of
+// G symbols (16 bytes of the plain array), lane = (j / G) mod S.  A lane's codes, most
+// significant bit first, form a bit string stored LSB-first in 32-bit words.  The words of
+// all lanes are interleaved in the order a lock-step decoder asks for them: at every r-th
+// symbol step each lane holding <= 32 unread bits takes the next word of the stream, lanes
+// in ascending order.  One wavefront (or an S-lane part of it) owns one chunk, so the
+// "next word" is a ballot + prefix count and both stream reads and 16-byte result writes
+// are contiguous across the lanes.
+#include <hip/hip_runtime.h>
+
+#include "zc_internal.h"
+
+namespace zc {
+
+// ------------------------------------------------------------------ lane helpers
+
+struct Lanes {
+    uint32_t lane, s, grp;     // lane in wave, lane in its S-lane group, group in wave
+    uint64_t gmask;            // wave mask of the lanes of this group
+};
+
+__device__ __forceinline__ Lanes make_lanes(uint32_t S)
+{
+    Lanes L;
+    L.lane = threadIdx.x & 63;
+    L.s = L.lane & (S - 1);
+    L.grp = L.lane / S;
+    L.gmask = (S == 64) ? ~0ull : (((1ull << S) - 1) << (L.lane - L.s));
+    return L;
+}
+
+// number of set bits of m in lanes below this one
+__device__ __forceinline__ uint32_t prefix_count(uint64_t m)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
+}
+
+template <int FMT> struct Fmt;
+template <> struct Fmt<ZC_FMT_BF16> { static constexpr int EB = 16, G = 8, SB = 8, NF = 2; };
+template <> struct Fmt<ZC_FMT_FP8_E4M3> { static constexpr int EB = 8, G = 16, SB = 4, NF = 2; };
+template <> struct Fmt<ZC_FMT_FP4_E2M1_MX> { static constexpr int EB = 4, G = 32, SB = 2, NF = 3; };
+
+// ------------------------------------------------- field split / join of one 16-byte run
+// P0 = the run's exponent symbols, P1 = its sign+mantissa symbols, SB bits each, symbol j at
+// bits j*SB (always 64 bits per field per run).
+
+__device__ __forceinline__ uint32_t pack_nibbles_of_bytes(uint32_t x)   // 4 bytes with a value < 16 each -> 16 bits
+{
+    x = (x | (x >> 4)) & 0x00FF00FFu;
+    return (x | (x >> 8)) & 0xFFFFu;
+}
+__device__ __forceinline__ uint32_t pack_pairs_of_nibbles(uint32_t x)   // 8 nibbles with a value < 4 each -> 16 bits
+{
+    x = (x | (x >> 2)) & 0x0F0F0F0Fu;
+    return pack_nibbles_of_bytes(x);
+}
+__device__ __forceinline__ uint32_t spread_nibbles_to_bytes(uint32_t x)  // inverse of pack_nibbles_of_bytes
+{
+    x = (x | (x << 8)) & 0x00FF00FFu;
+    return (x | (x << 4)) & 0x0F0F0F0Fu;
+}
+__device__ __forceinline__ uint32_t spread_pairs_to_nibbles(uint32_t x)  // inverse of pack_pairs_of_nibbles
+{
+    x = spread_nibbles_to_bytes(x);
+    return (x | (x << 2)) & 0x33333333u;
+}
+
+template <int FMT>
+__device__ __forceinline__ void split_run(const uint4 &v, uint64_t &P0, uint64_t &P1)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    P0 = 0; P1 = 0;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        uint32_t e, m;
+        if (FMT == ZC_FMT_BF16) {                       // s eeeeeeee mmmmmmm, two per word
+            uint32_t lo = w[i] & 0xFFFFu, hi = w[i] >> 16;
+            e = ((lo >> 7) & 0xFFu) | (((hi >> 7) & 0xFFu) << 8);
+            m = (((lo >> 8) & 0x80u) | (lo & 0x7Fu)) | ((((hi >> 8) & 0x80u) | (hi & 0x7Fu)) << 8);
+        } else if (FMT == ZC_FMT_FP8_E4M3) {            // s eeee mmm, four per word
+            e = pack_nibbles_of_bytes((w[i] >> 3) & 0x0F0F0F0Fu);
+            m = pack_nibbles_of_bytes(((w[i] >> 4) & 0x08080808u) | (w[i] & 0x07070707u));
+        } else {                                        // s ee m, eight per word
+            e = pack_pairs_of_nibbles((w[i] >> 1) & 0x33333333u);
+            m = pack_pairs_of_nibbles(((w[i] >> 2) & 0x22222222u) | (w[i] & 0x11111111u));
+        }
+        P0 |= (uint64_t)e << (16 * i);
+        P1 |= (uint64_t)m << (16 * i);
+    }
+}
+
+template <int FMT>
+__device__ __forceinline__ uint4 join_run(uint64_t P0, uint64_t P1)
+{
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        uint32_t e = (uint32_t)(P0 >> (16 * i)) & 0xFFFFu, m = (uint32_t)(P1 >> (16 * i)) & 0xFFFFu;
+        if (FMT == ZC_FMT_BF16) {
+            uint32_t e0 = e & 0xFFu, e1 = e >> 8, m0 = m & 0xFFu, m1 = m >> 8;
+            uint32_t lo = ((m0 & 0x80u) << 8) | (e0 << 7) | (m0 & 0x7Fu);
+            uint32_t hi = ((m1 & 0x80u) << 8) | (e1 << 7) | (m1 & 0x7Fu);
+            w[i] = lo | (hi << 16);
+        } else if (FMT == ZC_FMT_FP8_E4M3) {
+            uint32_t eb = spread_nibbles_to_bytes(e), mb = spread_nibbles_to_bytes(m);
+            w[i] = ((mb & 0x08080808u) << 4) | (eb << 3) | (mb & 0x07070707u);
+        } else {
+            uint32_t en = spread_pairs_to_nibbles(e), mn = spread_pairs_to_nibbles(m);
+            w[i] = ((mn & 0x22222222u) << 2) | (en << 1) | (mn & 0x11111111u);
+        }
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// 16 bytes from p, of which only the first `valid` may be read
+__device__ __forceinline__ uint4 load_run(const uint8_t *p, uint32_t valid)
+{
+    if (valid >= 16) return *reinterpret_cast<const uint4 *>(p);
+    uint32_t w[4] = {0, 0, 0, 0};
+    for (uint32_t i = 0; i < valid; i++) w[i >> 2] |= (uint32_t)p[i] << (8 * (i & 3));
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+__device__ __forceinline__ void store_run(uint8_t *p, const uint4 &v, uint32_t valid)
+{
+    if (valid >= 16) { *reinterpret_cast<uint4 *>(p) = v; return; }
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    for (uint32_t i = 0; i < valid; i++) p[i] = (uint8_t)(w[i >> 2] >> (8 * (i & 3)));
+}
+
+__device__ __forceinline__ uint4 xor4(const uint4 &a, const uint4 &b) { return make_uint4(a.x ^ b.x, a.y ^ b.y, a.z ^ b.z, a.w ^ b.w); }
+
+// ------------------------------------------------------------------------ histogram
+// One workgroup counts kHistBlockBytes of one tensor into LDS (8 replicas per bin to spread
+// same-address atomics of skewed data) and merges into the tensor's 64-bit global bins.
+// BYTES: one 256-bin histogram of the bytes (FP8: the joint (exponent, sign+mantissa)
+// histogram; FP4: joint over two elements; E8M0 scales: the field itself); the host takes
+// the marginals.  BF16: two histograms, exponent and sign+mantissa symbol.
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void k_hist(const TensorDev *descs, const WorkItem *work, int elem_bits_, int scales_view, uint64_t *hist)
+{
+    __shared__ uint32_t h[2][256 * 8];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev &d = descs[it.tensor];
+    const uint8_t *p = scales_view ? d.scales : d.src;
+    const uint8_t *base = scales_view ? nullptr : d.base;
+    const uint64_t nbytes = scales_view ? d.n_elems / 32 : (d.n_elems * (uint64_t)elem_bits_ + 7) / 8;
+    for (uint32_t i = threadIdx.x; i < 2 * 256 * 8; i += 256) (&h[0][0])[i] = 0;
+    __syncthreads();
+    const uint64_t start = (uint64_t)it.first * kHistBlockBytes;
+    const uint64_t end = start + kHistBlockBytes < nbytes ? start + kHistBlockBytes : nbytes;
+    const uint32_t rep = threadIdx.x & 7;
+    for (uint64_t off = start + (uint64_t)threadIdx.x * 16; off < end; off += 256 * 16) {
+        const uint32_t valid = end - off >= 16 ? 16u : (uint32_t)(end - off);
+        uint4 v = load_run(p + off, valid);
+        if (base) v = xor4(v, load_run(base + off, valid));
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        if (BF16) {
+#pragma unroll
+            for (int i = 0; i < 8; i++)
+                if (2u * i < valid) {
+                    const uint32_t x = (w[i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
+                    atomicAdd(&h[0][((x >> 7) & 0xFFu) * 8 + rep], 1u);
+                    atomicAdd(&h[1][(((x >> 8) & 0x80u) | (x & 0x7Fu)) * 8 + rep], 1u);
+                }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; i++)
+                if ((uint32_t)i < valid) atomicAdd(&h[0][((w[i >> 2] >> (8 * (i & 3))) & 0xFFu) * 8 + rep], 1u);
+        }
+    }
+    __syncthreads();
+    const uint32_t bin = threadIdx.x;
+    for (int f = 0; f < (BF16 ? 2 : 1); f++) {
+        uint32_t sum = 0;
+#pragma unroll
+        for (int r = 0; r < 8; r++) sum += h[f][bin * 8 + r];
+        const int slot = BF16 ? f : (scales_view ? 2 : 0);
+        if (sum) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + slot) * 256 + bin]), (unsigned long long)sum);
+    }
+}
+
+int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, int scales_view, uint64_t *d_hist, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    if (fmt == ZC_FMT_BF16 && !scales_view)
+        hipLaunchKernelGGL(k_hist<true>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, 16, 0, d_hist);
+    else
+        hipLaunchKernelGGL(k_hist<false>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, elem_bits(fmt), scales_view, d_hist);
+    return (int)hipGetLastError();
+}
+
+// ------------------------------------------------------------- chunk geometry shared by
+// the encoder and the decoder: which chunk a lane group works on and how many symbols it has
+
+uint32_t chunks_per_work_item(uint32_t streams) { return kWavesPerGroup * (64 / streams); }
+
+struct ChunkJob {
+    bool valid;
+    uint32_t chunk;        // chunk id inside the tensor
+    uint64_t slot;         // output slot (== chunk unless decoding an id list)
+    uint64_t n_elems;      // elements in this chunk
+};
+
+// ------------------------------------------------------------------------- encoder
+// One S-lane group per chunk, all fields of a run handled from one 16-byte load.
+// WRITE = false is the dry run that only counts the words of every (chunk, field) stream.
+
+struct EncField {
+    uint64_t acc;          // bits not yet written, next free bit = nacc
+    uint32_t nacc;
+    int32_t k;             // unread bits the decoder would hold at this point
+    uint32_t pend, p0, p1; // requested but unwritten words and their positions in the stream
+    uint32_t wpos;         // words of the stream handed out so far (same in all lanes of the group)
+};
+
+template <bool WRITE>
+__device__ __forceinline__ void enc_request(EncField &F, bool active, const Lanes &L, uint32_t S)
+{
+    const bool req = active && F.k <= 32;
+    const uint64_t bm = __ballot(req) & L.gmask;
+    if (req) {
+        const uint32_t pos = F.wpos + prefix_count(bm);
+        if (F.pend == 0) F.p0 = pos; else F.p1 = pos;
+        F.pend++;
+        F.k += 32;
+    }
+    F.wpos += (uint32_t)__popcll(bm);
+    (void)S;
+}
+
+template <bool WRITE>
+__device__ __forceinline__ void enc_flush_word(EncField &F, uint8_t *stream)
+{
+    if (WRITE) reinterpret_cast<uint32_t *>(stream)[F.p0] = (uint32_t)F.acc;
+    F.acc >>= 32;
+    F.p0 = F.p1;
+    F.pend--;
+}
+
+// encode symbols [J0, J0+R) of a run; sym(j) = (P >> (j*SB)) & mask
+template <bool WRITE, int SB, int R, bool FULL>
+__device__ __forceinline__ void enc_group(EncField &F, uint64_t P, int j0, uint32_t nsym, const uint32_t *enc, uint8_t *stream, const Lanes &L, uint32_t S)
+{
+    enc_request<WRITE>(F, FULL || (uint32_t)j0 < nsym, L, S);
+#pragma unroll
+    for (int j = 0; j < R; j++) {
+        if (FULL || (uint32_t)(j0 + j) < nsym) {
+            const uint32_t v = (uint32_t)(P >> ((j0 + j) * SB)) & ((1u << SB) - 1);
+            const uint32_t e = enc[v];
+            F.acc |= (uint64_t)(e & 0xFFFFu) << F.nacc;
+            F.nacc += e >> 16;
+            F.k -= (int32_t)(e >> 16);
+        }
+    }
+    if (F.nacc >= 32) { enc_flush_word<WRITE>(F, stream); F.nacc -= 32; }
+}
+
+template <bool WRITE, int SB, int G, int R, bool FULL>
+__device__ __forceinline__ void enc_run_r(EncField &F, uint64_t P0, uint64_t P1, uint32_t nsym, const uint32_t *enc, uint8_t *stream, const Lanes &L, uint32_t S)
+{
+    // G*SB may be 64 (element fields) or 128 (scale field: P0 low half, P1 high half)
+    constexpr int PER64 = 64 / SB;
+#pragma unroll
+    for (int j0 = 0; j0 < G; j0 += R) {
+        if (j0 < PER64) enc_group<WRITE, SB, R, FULL>(F, P0, j0, nsym, enc, stream, L, S);
+        else {
+            // symbols of the upper half: shift indices down, keep the activity test on the real index
+            EncField &Fr = F;
+            enc_request<WRITE>(Fr, FULL || (uint32_t)j0 < nsym, L, S);
+#pragma unroll
+            for (int j = 0; j < R; j++) {
+                if (FULL || (uint32_t)(j0 + j) < nsym) {
+                    const uint32_t v = (uint32_t)(P1 >> ((j0 + j - PER64) * SB)) & ((1u << SB) - 1);
+                    const uint32_t e = enc[v];
+                    Fr.acc |= (uint64_t)(e & 0xFFFFu) << Fr.nacc;
+                    Fr.nacc += e >> 16;
+                    Fr.k -= (int32_t)(e >> 16);
+                }
+            }
+            if (Fr.nacc >= 32) { enc_flush_word<WRITE>(Fr, stream); Fr.nacc -= 32; }
+        }
+    }
+}
+
+template <bool WRITE, int SB, int G, bool FULL>
+__device__ __forceinline__ void enc_run(EncField &F, uint32_t period, uint64_t P0, uint64_t P1, uint32_t nsym, const uint32_t *enc, uint8_t *stream, const Lanes &L, uint32_t S)
+{
+    switch (period) {
+    case 2: enc_run_r<WRITE, SB, G, 2, FULL>(F, P0, P1, nsym, enc, stream, L, S); break;
+    case 4: enc_run_r<WRITE, SB, G, 4, FULL>(F, P0, P1, nsym, enc, stream, L, S); break;
+    case 8: enc_run_r<WRITE, SB, G, 8, FULL>(F, P0, P1, nsym, enc, stream, L, S); break;
+    case 16: if (G >= 16) enc_run_r<WRITE, SB, G, (G >= 16 ? 16 : G), FULL>(F, P0, P1, nsym, enc, stream, L, S); break;
+    default: if (G >= 32) enc_run_r<WRITE, SB, G, (G >= 32 ? 32 : G), FULL>(F, P0, P1, nsym, enc, stream, L, S); break;
+    }
+}
+
+// write the words still owed to the decoder, then zero the tail of the last 16-byte unit
+template <bool WRITE>
+__device__ __forceinline__ uint32_t enc_finish(EncField &F, uint8_t *stream, const Lanes &L)
+{
+    if (F.pend > 0) enc_flush_word<WRITE>(F, stream);
+    if (F.pend > 0) enc_flush_word<WRITE>(F, stream);
+    const uint32_t words = F.wpos;
+    if (WRITE && L.s == 0)
+        for (uint32_t w = words; w & 3; w++) reinterpret_cast<uint32_t *>(stream)[w] = 0;
+    return (words + 3) / 4;
+}
+
+// Encoder body for the symbols of one field kind.  ELEM = true: fields 0 and 1 of the
+// element array; false: the FP4 scale field.
+template <int FMT, bool WRITE>
+__global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units)
+{
+    using F_ = Fmt<FMT>;
+    __shared__ uint32_t enc[3][256];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev &d = descs[it.tensor];
+    for (uint32_t i = threadIdx.x; i < 3 * 256; i += 256) (&enc[0][0])[i] = enc_tables[(uint64_t)it.tensor * 768 + i];
+    __syncthreads();
+    const uint32_t S = d.streams;
+    const Lanes L = make_lanes(S);
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t chunk = it.first + wave * (64 / S) + L.grp;
+    const bool valid = chunk < d.n_chunks;
+    const uint64_t E = (uint64_t)d.chunk_bytes * 8 / F_::EB;
+    const uint64_t first = (uint64_t)chunk * E;
+    const uint32_t n = valid ? (uint32_t)(d.n_elems - first < E ? d.n_elems - first : E) : 0;
+    const uint32_t *index[3];
+    uint8_t *stream[3] = {nullptr, nullptr, nullptr};
+    for (int f = 0; f < F_::NF; f++) {
+        index[f] = reinterpret_cast<const uint32_t *>(d.comp + d.index_off[f]);
+        if (WRITE && valid) stream[f] = d.comp + d.payload_off + 16ull * index[f][chunk];
+    }
+    uint32_t *my_units = units + d.units_off;
+
+    // ---- element fields ----
+    EncField F0 = {0, 0, 0, 0, 0, 0, 0}, F1 = F0;
+    const uint32_t chunk_runs = (uint32_t)((E + F_::G - 1) / F_::G);
+    const uint32_t rows = (chunk_runs + S - 1) / S;
+    const uint8_t *src = d.src + (uint64_t)chunk * d.chunk_bytes;
+    const uint8_t *base = d.base ? d.base + (uint64_t)chunk * d.chunk_bytes : nullptr;
+    const uint32_t nbytes = (uint32_t)(((uint64_t)n * F_::EB + 7) / 8);
+    const uint32_t m0 = d.mode[0], m1 = d.mode[1];
+    for (uint32_t i = 0; i < rows; i++) {
+        const uint32_t run = i * S + L.s;
+        const uint32_t done = run * F_::G;
+        const uint32_t nsym = n > done ? (n - done < (uint32_t)F_::G ? n - done : (uint32_t)F_::G) : 0;
+        uint64_t P0 = 0, P1 = 0;
+        if (nsym) {
+            const uint32_t vb = nbytes - run * 16;
+            uint4 v = load_run(src + (uint64_t)run * 16, vb);
+            if (base) v = xor4(v, load_run(base + (uint64_t)run * 16, vb));
+            split_run<FMT>(v, P0, P1);
+        }
+        const bool full = __all(nsym == (uint32_t)F_::G);
+        if (m0 == ZC_MODE_HUFF) {
+            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F0, d.period[0], P0, 0, nsym, enc[0], stream[0], L, S);
+            else enc_run<WRITE, F_::SB, F_::G, false>(F0, d.period[0], P0, 0, nsym, enc[0], stream[0], L, S);
+        } else if (m0 == ZC_MODE_RAW && WRITE && nsym) {
+            reinterpret_cast<uint64_t *>(stream[0])[run] = P0;
+            if ((run & 1) == 0 && done + F_::G >= n) reinterpret_cast<uint64_t *>(stream[0])[run + 1] = 0;
+        }
+        if (m1 == ZC_MODE_HUFF) {
+            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F1, d.period[1], P1, 0, nsym, enc[1], stream[1], L, S);
+            else enc_run<WRITE, F_::SB, F_::G, false>(F1, d.period[1], P1, 0, nsym, enc[1], stream[1], L, S);
+        } else if (m1 == ZC_MODE_RAW && WRITE && nsym) {
+            reinterpret_cast<uint64_t *>(stream[1])[run] = P1;
+            if ((run & 1) == 0 && done + F_::G >= n) reinterpret_cast<uint64_t *>(stream[1])[run + 1] = 0;
+        }
+    }
+    {
+        uint32_t u0 = 0, u1 = 0;
+        if (m0 == ZC_MODE_HUFF) u0 = enc_finish<WRITE>(F0, stream[0], L);
+        else if (m0 == ZC_MODE_RAW) u0 = (uint32_t)((((uint64_t)n * F_::SB + 7) / 8 + 15) / 16);
+        if (m1 == ZC_MODE_HUFF) u1 = enc_finish<WRITE>(F1, stream[1], L);
+        else if (m1 == ZC_MODE_RAW) u1 = (uint32_t)((((uint64_t)n * F_::SB + 7) / 8 + 15) / 16);
+        if (!WRITE && valid && L.s == 0) { my_units[chunk] = u0; my_units[d.n_chunks + chunk] = u1; }
+    }
+
+    // ---- FP4 block scales: one byte per 32 elements, runs of 16 bytes ----
+    if (FMT == ZC_FMT_FP4_E2M1_MX) {
+        EncField F2 = {0, 0, 0, 0, 0, 0, 0};
+        const uint32_t ns = n / 32;
+        const uint32_t srows = (uint32_t)((E / 32 + 15) / 16 + S - 1) / S;
+        const uint8_t *sc = d.scales + (uint64_t)chunk * (E / 32);
+        const uint32_t m2 = d.mode[2];
+        for (uint32_t i = 0; i < srows; i++) {
+            const uint32_t run = i * S + L.s;
+            const uint32_t done = run * 16;
+            const uint32_t nsym = ns > done ? (ns - done < 16u ? ns - done : 16u) : 0;
+            uint64_t P0 = 0, P1 = 0;
+            if (nsym) {
+                const uint4 v = load_run(sc + (uint64_t)run * 16, nsym);
+                P0 = (uint64_t)v.x | ((uint64_t)v.y << 32);
+                P1 = (uint64_t)v.z | ((uint64_t)v.w << 32);
+            }
+            const bool full = __all(nsym == 16u);
+            if (m2 == ZC_MODE_HUFF) {
+                if (full) enc_run<WRITE, 8, 16, true>(F2, d.period[2], P0, P1, nsym, enc[2], stream[2], L, S);
+                else enc_run<WRITE, 8, 16, false>(F2, d.period[2], P0, P1, nsym, enc[2], stream[2], L, S);
+            } else if (m2 == ZC_MODE_RAW && WRITE && nsym) {
+                reinterpret_cast<uint64_t *>(stream[2])[2 * run] = P0;
+                reinterpret_cast<uint64_t *>(stream[2])[2 * run + 1] = P1;
+            }
+        }
+        uint32_t u2 = 0;
+        if (m2 == ZC_MODE_HUFF) u2 = enc_finish<WRITE>(F2, stream[2], L);
+        else if (m2 == ZC_MODE_RAW) u2 = (ns + 15) / 16;
+        if (!WRITE && valid && L.s == 0) my_units[2 * d.n_chunks + chunk] = u2;
+    }
+}
+
+template <bool WRITE>
+static int launch_encode_t(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
+{
+    if (n_work == 0) return 0;
+    if (fmt == ZC_FMT_BF16) hipLaunchKernelGGL((k_encode<ZC_FMT_BF16, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units);
+    else if (fmt == ZC_FMT_FP8_E4M3) hipLaunchKernelGGL((k_encode<ZC_FMT_FP8_E4M3, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units);
+    else hipLaunchKernelGGL((k_encode<ZC_FMT_FP4_E2M1_MX, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units);
+    return (int)hipGetLastError();
+}
+
+int launch_sizes(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t, const uint32_t *d_enc, uint32_t *d_units, void *stream)
+{
+    return launch_encode_t<false>(fmt, d_descs, d_work, n_work, d_enc, d_units, (hipStream_t)stream);
+}
+
+int launch_encode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t, const uint32_t *d_enc, void *stream)
+{
+    return launch_encode_t<true>(fmt, d_descs, d_work, n_work, d_enc, nullptr, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------- scan
+// One workgroup per tensor: exclusive scan of the stream sizes (16-byte units) in
+// field-major order.  Writes the chunk index and the total size into the container
+// (when there is one) and the per-field totals for the host.
+
+__global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fields, const uint32_t *units, ScanOut *out)
+{
+    __shared__ uint32_t wave_sum[16];
+    __shared__ uint32_t carry_s;
+    const TensorDev &d = descs[blockIdx.x];
+    const uint32_t *u = units + d.units_off;
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    uint32_t field_start[kMaxFields + 1];
+    for (int f = 0; f < n_fields; f++) {
+        uint32_t *index = d.comp ? reinterpret_cast<uint32_t *>(d.comp + d.index_off[f]) : nullptr;
+        field_start[f] = carry_s;
+        for (uint32_t c0 = 0; c0 < d.n_chunks; c0 += 1024) {
+            const uint32_t c = c0 + threadIdx.x;
+            const uint32_t v = c < d.n_chunks ? u[(uint64_t)f * d.n_chunks + c] : 0;
+            uint32_t x = v;                                   // inclusive scan inside the wave
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t y = __shfl_up(x, o, 64);
+                if (lane >= (uint32_t)o) x += y;
+            }
+            if (lane == 63) wave_sum[wave] = x;
+            __syncthreads();
+            uint32_t before = carry_s;
+            for (uint32_t w = 0; w < wave; w++) before += wave_sum[w];
+            if (index && c < d.n_chunks) index[c] = before + x - v;
+            __syncthreads();
+            if (threadIdx.x == 1023) carry_s = before + x;
+            __syncthreads();
+        }
+        if (index && threadIdx.x == 0) index[d.n_chunks] = carry_s;
+        __syncthreads();
+    }
+    field_start[n_fields] = carry_s;
+    if (threadIdx.x == 0) {
+        ScanOut o = {{0, 0, 0}, 0};
+        for (int f = 0; f < n_fields; f++) o.field_units[f] = field_start[f + 1] - field_start[f];
+        o.total_units = carry_s;
+        out[blockIdx.x] = o;
+        if (d.comp) *reinterpret_cast<uint64_t *>(d.comp + 48) = d.payload_off + 16ull * carry_s;
+    }
+}
+
+int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, const uint32_t *d_units, ScanOut *d_out, void *stream)
+{
+    if (n_tensors == 0) return 0;
+    hipLaunchKernelGGL(k_scan, dim3(n_tensors), dim3(1024), 0, (hipStream_t)stream, d_descs, n_fields, d_units, d_out);
+    return (int)hipGetLastError();
+}
+
+// container prologue: header and code-length tables (prepared on the host) and the zero
+// padding behind each chunk index
+__global__ __launch_bounds__(256) void k_write_headers(const TensorDev *descs, const uint8_t *blobs, uint32_t blob_bytes, int n_fields)
+{
+    const TensorDev &d = descs[blockIdx.x];
+    if (!d.comp) return;
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(blobs + (uint64_t)blockIdx.x * blob_bytes);
+    uint32_t *dst = reinterpret_cast<uint32_t *>(d.comp);
+    for (uint32_t i = threadIdx.x; i < d.index_off[0] / 4; i += 256) dst[i] = src[i];
+    if (threadIdx.x < 4 * (uint32_t)n_fields) {
+        const uint32_t f = threadIdx.x / 4, w = d.n_chunks + 1 + (threadIdx.x & 3);
+        if (w < ((d.n_chunks + 1 + 3) & ~3u)) dst[d.index_off[f] / 4 + w] = 0;
+    }
+}
+
+int launch_write_headers(const TensorDev *d_descs, uint32_t n_tensors, const uint8_t *d_blobs, uint32_t blob_bytes, int n_fields, void *stream)
+{
+    if (n_tensors == 0) return 0;
+    hipLaunchKernelGGL(k_write_headers, dim3(n_tensors), dim3(256), 0, (hipStream_t)stream, d_descs, d_blobs, blob_bytes, n_fields);
+    return (int)hipGetLastError();
+}
+
+// ------------------------------------------------------------------------- decoder
+// Tables of one field in LDS: a direct lookup on the next kLutBits stream bits and the
+// canonical first-code arrays for the rare codes longer than that.
+
+constexpr int kLutBits = 11;
+
+struct FieldTab {
+    uint16_t lut[1 << kLutBits];   // (symbol << 8) | length, 0 = code longer than the index
+    uint32_t first[17], cnt[17], start[17];
+    uint8_t sorted[256];
+    uint8_t len[256];
+    uint32_t mask;                 // (1 << min(Lmax, kLutBits)) - 1
+    uint32_t lmax;
+};
+
+// all threads of the workgroup; lengths come from the container's table
+__device__ void build_field_tab(FieldTab &T, const uint8_t *len_table, int alphabet, uint32_t lmax)
+{
+    const uint32_t tid = threadIdx.x, nt = blockDim.x;
+    if (tid < 17) T.cnt[tid] = 0;
+    for (uint32_t v = tid; v < 256; v += nt) T.len[v] = v < (uint32_t)alphabet ? len_table[v] : 0;
+    if (lmax > 16) lmax = 16;
+    __syncthreads();
+    for (uint32_t v = tid; v < (uint32_t)alphabet; v += nt)
+        if (T.len[v] && T.len[v] <= 16) atomicAdd(&T.cnt[T.len[v]], 1u);
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t code = 0, idx = 0;
+        for (int l = 1; l <= 16; l++) {
+            code <<= 1;
+            T.first[l] = code; T.start[l] = idx;
+            code += T.cnt[l]; idx += T.cnt[l];
+        }
+        const uint32_t bits = lmax < (uint32_t)kLutBits ? lmax : (uint32_t)kLutBits;
+        T.mask = (1u << bits) - 1;
+        T.lmax = lmax;
+    }
+    __syncthreads();
+    for (uint32_t v = tid; v < (uint32_t)alphabet; v += nt) {
+        const uint32_t l = T.len[v];
+        if (l && l <= 16) {
+            uint32_t rank = 0;
+            for (uint32_t u = 0; u < v; u++) rank += T.len[u] == l;
+            T.sorted[T.start[l] + rank] = (uint8_t)v;
+        }
+    }
+    __syncthreads();
+    const uint32_t bits = lmax < (uint32_t)kLutBits ? lmax : (uint32_t)kLutBits;
+    for (uint32_t idx = tid; idx < (1u << bits); idx += nt) {
+        const uint32_t msb = __brev(idx);                  // stream bits in code order, left aligned
+        uint32_t entry = 0;
+        for (uint32_t l = 1; l <= bits; l++) {
+            const uint32_t code = msb >> (32 - l);
+            if (code - T.first[l] < T.cnt[l] && code >= T.first[l]) { entry = l | ((uint32_t)T.sorted[T.start[l] + code - T.first[l]] << 8); break; }
+        }
+        T.lut[idx] = (uint16_t)entry;
+    }
+    __syncthreads();
+}
+
+struct DecField {
+    uint32_t lo, hi;       // 64 stream bits, next unread bit = bit c of {hi, lo}
+    uint32_t c;
+    uint32_t wpos;         // words of the stream taken so far by the group
+    const uint8_t *ptr;    // stream start
+    uint32_t words;        // stream length in words (reads beyond it return 0)
+};
+
+__device__ __forceinline__ void dec_refill(DecField &D, bool active, const Lanes &L)
+{
+    const bool need = active && D.c >= 32;
+    const uint64_t bm = __ballot(need) & L.gmask;
+    if (need) {
+        const uint32_t pos = D.wpos + prefix_count(bm);
+        const uint32_t w = pos < D.words ? reinterpret_cast<const uint32_t *>(D.ptr)[pos] : 0u;
+        D.lo = D.hi; D.hi = w; D.c -= 32;
+    }
+    D.wpos += (uint32_t)__popcll(bm);
+}
+
+// code longer than the lookup index: canonical search on the bit-reversed window
+__device__ __noinline__ uint32_t dec_long(const FieldTab &T, uint32_t x)
+{
+    const uint32_t msb = __brev(x);
+    for (uint32_t l = kLutBits + 1; l <= T.lmax; l++) {
+        const uint32_t code = msb >> (32 - l);
+        if (code >= T.first[l] && code - T.first[l] < T.cnt[l]) return l | ((uint32_t)T.sorted[T.start[l] + code - T.first[l]] << 8);
+    }
+    return T.lmax ? T.lmax : 1;      // malformed table: consume something, symbol 0
+}
+
+// decode symbols [j0, j0+R) of a run into P (SB bits each, symbol j at bit j*SB of a 64-bit half)
+template <int SB, int R, bool FULL>
+__device__ __forceinline__ void dec_group(DecField &D, const FieldTab &T, uint64_t &P, int j0, int shift0, uint32_t nsym, const Lanes &L)
+{
+    dec_refill(D, FULL || (uint32_t)j0 < nsym, L);
+    uint32_t x = (uint32_t)((((uint64_t)D.hi << 32) | D.lo) >> D.c);
+    const uint32_t mask = T.mask;
+#pragma unroll
+    for (int j = 0; j < R; j++) {
+        if (FULL || (uint32_t)(j0 + j) < nsym) {
+            uint32_t e = T.lut[x & mask];
+            if (e == 0) e = dec_long(T, x);
+            x >>= (e & 31u);
+            D.c += (e & 31u);
+            P |= (uint64_t)(e >> 8) << ((j0 + j - shift0) * SB);
+        }
+    }
+}
+
+template <int SB, int G, int R, bool FULL>
+__device__ __forceinline__ void dec_run_r(DecField &D, const FieldTab &T, uint64_t &P0, uint64_t &P1, uint32_t nsym, const Lanes &L)
+{
+    constexpr int PER64 = 64 / SB;
+#pragma unroll
+    for (int j0 = 0; j0 < G; j0 += R) {
+        if (j0 < PER64) dec_group<SB, R, FULL>(D, T, P0, j0, 0, nsym, L);
+        else dec_group<SB, R, FULL>(D, T, P1, j0, PER64, nsym, L);
+    }
+}
+
+template <int SB, int G, bool FULL>
+__device__ __forceinline__ void dec_run(DecField &D, const FieldTab &T, uint32_t period, uint64_t &P0, uint64_t &P1, uint32_t nsym, const Lanes &L)
+{
+    switch (period) {
+    case 2: dec_run_r<SB, G, 2, FULL>(D, T, P0, P1, nsym, L); break;
+    case 4: dec_run_r<SB, G, 4, FULL>(D, T, P0, P1, nsym, L); break;
+    case 8: dec_run_r<SB, G, 8, FULL>(D, T, P0, P1, nsym, L); break;
+    case 16: if (G >= 16) dec_run_r<SB, G, (G >= 16 ? 16 : G), FULL>(D, T, P0, P1, nsym, L); break;
+    default: if (G >= 32) dec_run_r<SB, G, (G >= 32 ? 32 : G), FULL>(D, T, P0, P1, nsym, L); break;
+    }
+}
+
+// every symbol of a 64-bit packed run equal to v
+__device__ __forceinline__ uint64_t splat(uint32_t v, int sb)
+{
+    uint64_t x = v;
+    for (int w = sb; w < 64; w *= 2) x |= x << w;
+    return x;
+}
+
+__device__ __forceinline__ DecField open_stream(const TensorDev &d, int f, uint32_t chunk, bool valid)
+{
+    DecField D = {0, 0, 64, 0, d.comp, 0};
+    if (valid && (d.mode[f] == ZC_MODE_HUFF || d.mode[f] == ZC_MODE_RAW)) {
+        const uint32_t *index = reinterpret_cast<const uint32_t *>(d.comp + d.index_off[f]);
+        const uint64_t a = index[chunk], b = index[chunk + 1];
+        const uint64_t lo = d.payload_off + 16 * a, hi = d.payload_off + 16 * b;
+        if (a <= b && hi <= d.total_bytes) { D.ptr = d.comp + lo; D.words = (uint32_t)((hi - lo) / 4); }
+    }
+    return D;
+}
+
+template <int FMT>
+__global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single,
+                                                const uint32_t *ids, uint32_t n_ids)
+{
+    using F_ = Fmt<FMT>;
+    __shared__ FieldTab tab[F_::NF];
+    __shared__ TensorDev dsh;
+    WorkItem it;
+    if (use_single) { it.tensor = 0; it.first = blockIdx.x * kWavesPerGroup * (64 / single.streams); }
+    else it = work[blockIdx.x];
+    if (threadIdx.x == 0) dsh = use_single ? single : descs[it.tensor];
+    __syncthreads();
+    const TensorDev &d = dsh;
+    for (int f = 0; f < F_::NF; f++)
+        if (d.mode[f] == ZC_MODE_HUFF) build_field_tab(tab[f], d.comp + d.table_off[f], 1 << (f == 2 ? 8 : F_::SB), d.lmax[f]);
+    const uint32_t S = d.streams;
+    const Lanes L = make_lanes(S);
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t slot = it.first + wave * (64 / S) + L.grp;
+    uint32_t chunk = slot;
+    bool valid = slot < d.n_chunks;
+    if (ids) { valid = slot < n_ids; chunk = valid ? ids[slot] : 0; valid = valid && chunk < d.n_chunks; }
+    const uint64_t E = (uint64_t)d.chunk_bytes * 8 / F_::EB;
+    const uint64_t first = (uint64_t)chunk * E;
+    const uint32_t n = valid ? (uint32_t)(d.n_elems - first < E ? d.n_elems - first : E) : 0;
+    const uint32_t nbytes = (uint32_t)(((uint64_t)n * F_::EB + 7) / 8);
+    uint8_t *dst = d.dst + (uint64_t)slot * d.chunk_bytes;
+    const uint8_t *base = d.base ? d.base + (uint64_t)chunk * d.chunk_bytes : nullptr;
+
+    DecField D0 = open_stream(d, 0, chunk, valid), D1 = open_stream(d, 1, chunk, valid);
+    const uint32_t m0 = d.mode[0], m1 = d.mode[1];
+    const uint64_t K0 = splat(d.konst[0], F_::SB), K1 = splat(d.konst[1], F_::SB);
+    const uint32_t chunk_runs = (uint32_t)((E + F_::G - 1) / F_::G);
+    const uint32_t rows = (chunk_runs + S - 1) / S;
+    for (uint32_t i = 0; i < rows; i++) {
+        const uint32_t run = i * S + L.s;
+        const uint32_t done = run * F_::G;
+        const uint32_t nsym = n > done ? (n - done < (uint32_t)F_::G ? n - done : (uint32_t)F_::G) : 0;
+        const bool full = __all(nsym == (uint32_t)F_::G);
+        uint64_t P0 = 0, P1 = 0, unused = 0;
+        if (m0 == ZC_MODE_HUFF) {
+            if (full) dec_run<F_::SB, F_::G, true>(D0, tab[0], d.period[0], P0, unused, nsym, L);
+            else dec_run<F_::SB, F_::G, false>(D0, tab[0], d.period[0], P0, unused, nsym, L);
+        } else if (m0 == ZC_MODE_RAW) {
+            if (nsym && 2 * run + 1 < D0.words) P0 = reinterpret_cast<const uint64_t *>(D0.ptr)[run];
+        } else P0 = K0;
+        if (m1 == ZC_MODE_HUFF) {
+            if (full) dec_run<F_::SB, F_::G, true>(D1, tab[1], d.period[1], P1, unused, nsym, L);
+            else dec_run<F_::SB, F_::G, false>(D1, tab[1], d.period[1], P1, unused, nsym, L);
+        } else if (m1 == ZC_MODE_RAW) {
+            if (nsym && 2 * run + 1 < D1.words) P1 = reinterpret_cast<const uint64_t *>(D1.ptr)[run];
+        } else P1 = K1;
+        if (nsym) {
+            const uint32_t vb = nbytes - run * 16;
+            uint4 v = join_run<FMT>(P0, P1);
+            if (base) v = xor4(v, load_run(base + (uint64_t)run * 16, vb));
+            store_run(dst + (uint64_t)run * 16, v, vb);
+        }
+    }
+
+    if (FMT == ZC_FMT_FP4_E2M1_MX) {
+        DecField D2 = open_stream(d, F_::NF - 1, chunk, valid);
+        const uint32_t m2 = d.mode[F_::NF - 1];
+        const uint32_t ns = n / 32;
+        const uint32_t srows = (uint32_t)((E / 32 + 15) / 16 + S - 1) / S;
+        uint8_t *sc = d.scales_out + (uint64_t)slot * (E / 32);
+        const uint64_t K2 = splat(d.konst[F_::NF - 1], 8);
+        for (uint32_t i = 0; i < srows; i++) {
+            const uint32_t run = i * S + L.s;
+            const uint32_t done = run * 16;
+            const uint32_t nsym = ns > done ? (ns - done < 16u ? ns - done : 16u) : 0;
+            const bool full = __all(nsym == 16u);
+            uint64_t P0 = 0, P1 = 0;
+            if (m2 == ZC_MODE_HUFF) {
+                if (full) dec_run<8, 16, true>(D2, tab[F_::NF - 1], d.period[F_::NF - 1], P0, P1, nsym, L);
+                else dec_run<8, 16, false>(D2, tab[F_::NF - 1], d.period[F_::NF - 1], P0, P1, nsym, L);
+            } else if (m2 == ZC_MODE_RAW) {
+                if (nsym && 4 * run + 3 < D2.words) { P0 = reinterpret_cast<const uint64_t *>(D2.ptr)[2 * run]; P1 = reinterpret_cast<const uint64_t *>(D2.ptr)[2 * run + 1]; }
+            } else { P0 = K2; P1 = K2; }
+            if (nsym) store_run(sc + (uint64_t)run * 16, make_uint4((uint32_t)P0, (uint32_t)(P0 >> 32), (uint32_t)P1, (uint32_t)(P1 >> 32)), nsym);
+        }
+    }
+}
+
+int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t,
+                  const TensorDev *single, const uint32_t *d_ids, uint32_t n_ids, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    TensorDev s = single ? *single : TensorDev{};
+    const int use_single = single ? 1 : 0;
+    if (fmt == ZC_FMT_BF16) hipLaunchKernelGGL(k_decode<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, d_ids, n_ids);
+    else if (fmt == ZC_FMT_FP8_E4M3) hipLaunchKernelGGL(k_decode<ZC_FMT_FP8_E4M3>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, d_ids, n_ids);
+    else hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_MX>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, d_ids, n_ids);
+    return (int)hipGetLastError();
+}
+
+}  // namespace zc

@@ -1,0 +1,272 @@
+"""GPU parity: the HIP library against the CPU oracle, byte for byte, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import zc_oracle as o
+from paper_2508_19263_amd import workloads as wl
+from paper_2508_19263_amd import zc
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def make_input(fmt, n, seed):
+    if fmt == zc.FMT_BF16:
+        return wl.bf16_weight(n, seed=seed).view(torch.uint8), None
+    if fmt == zc.FMT_FP8_E4M3:
+        return wl.fp8_weight(n, seed=seed) if n else torch.zeros(0, dtype=torch.uint8), None
+    if n == 0:
+        return torch.zeros(0, dtype=torch.uint8), torch.zeros(0, dtype=torch.uint8)
+    return wl.mxfp4_weight(1, n, seed=seed)
+
+
+def dev(t):
+    if t is None:
+        return None
+    if t.numel() == 0:
+        return torch.zeros(16, dtype=torch.uint8, device=DEV)[:0]
+    return t.to(DEV)
+
+
+def check_case(fmt, n, cb, S, policy=zc.POLICY_HUFF_ALL, L=(0, 0, 0), data=None, base=None, tag=""):
+    """compress on both sides -> identical containers; decode the oracle's container on the
+    GPU -> original bytes; decode on the GPU from the header alone -> original bytes."""
+    src, sc = data if data is not None else make_input(fmt, n, seed=n % 1000 + S)
+    print("case", tag, "fmt", fmt, "n", n, "chunk", cb, "S", S, "policy", policy, "L", L, flush=True)
+    p, po = zc.params(fmt, cb, L, S, policy), o.params(fmt, cb, L, S, policy)
+    want = o.compress(src.numpy(), n, po, xor_base=None if base is None else base.numpy(),
+                      scales=None if sc is None else sc.numpy())
+    comp, info = zc.compress(dev(src), n, p, xor_base=dev(base), scales=dev(sc))
+    got = comp.cpu().numpy()
+    assert got.shape == want.shape, (got.shape, want.shape)
+    assert np.array_equal(got, want), "first difference at byte %d" % int(np.argmax(got != want))
+    assert info.total_bytes == len(want)
+    # decoder fed by the oracle's bytes, header parsed by the library
+    oc = torch.from_numpy(want).to(DEV)
+    info2 = zc.read_info(oc, check_index=True)
+    out, sco = zc.decompress(oc, info2, xor_base=dev(base))
+    torch.cuda.synchronize()
+    assert torch.equal(out.cpu()[:src.numel()], src.view(torch.uint8).reshape(-1))
+    if sc is not None and sc.numel():
+        assert torch.equal(sco.cpu()[:sc.numel()], sc)
+    return want, src, sc
+
+
+@pytest.mark.parametrize("fmt,G", [(zc.FMT_BF16, 8), (zc.FMT_FP8_E4M3, 16)])
+@pytest.mark.parametrize("S", [64, 8, 1])
+def test_sizes_and_tails(fmt, G, S):
+    cb = 4096
+    E = cb * 8 // zc.elem_bits(fmt)
+    for n in (1, G * S - 1, G * S, G * S + 1, E - 1, E, E + 1, 3 * E + 17 * G + 5, 40 * E + 3):
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            check_case(fmt, n, cb, S, policy)
+
+
+@pytest.mark.parametrize("S", [64, 16, 2])
+def test_fp4_sizes(S):
+    for n in (32, 32 * 15, 32 * 17, 2048 - 32, 2048, 2048 + 32, 3 * 2048 + 32 * 37, 70 * 2048):
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            check_case(zc.FMT_FP4_E2M1_MX, n, 1024, S, policy)
+
+
+def test_empty_tensor():
+    for fmt in (zc.FMT_BF16, zc.FMT_FP8_E4M3, zc.FMT_FP4_E2M1_MX):
+        p = zc.params(fmt, 4096)
+        src = torch.zeros(16, dtype=torch.uint8, device=DEV)
+        comp, info = zc.compress(src, 0, p, scales=src if fmt == zc.FMT_FP4_E2M1_MX else None)
+        want = o.compress(np.zeros(0, np.uint8), 0, o.params(fmt, 4096), scales=np.zeros(0, np.uint8))
+        assert np.array_equal(comp.cpu().numpy(), want)
+        out, _ = zc.decompress(comp, info, out=torch.zeros(16, dtype=torch.uint8, device=DEV),
+                               scales_out=torch.zeros(16, dtype=torch.uint8, device=DEV))
+
+
+def test_config1_bf16_full():
+    # BASELINE config 1: 1,048,576 BF16 values N(0, 0.02), seed 0, max length 16, 64 KiB chunks
+    n = 1 << 20
+    x = wl.bf16_weight(n, seed=0).view(torch.uint8)
+    want, _, _ = check_case(zc.FMT_BF16, n, 65536, 64, L=(16, 16, 0), data=(x, None), tag="config1")
+    assert want[34] > 11          # the code has words longer than the lookup table: slow path exercised
+    st = zc.stats(x.to(DEV), n, zc.params(zc.FMT_BF16, 65536, (16, 16, 0)))
+    so = o.stats(x.numpy(), n, o.params(o.BF16, 65536, (16, 16, 0)))
+    compare_stats(st, so)
+
+
+def compare_stats(st, so):
+    assert st.n_fields == so.n_fields and st.raw_bytes == so.raw_bytes and st.container_bytes == so.container_bytes
+    assert st.ratio_payload_total == so.ratio_payload_total and st.ratio_container_total == so.ratio_container_total
+    for f in range(st.n_fields):
+        a, b = st.field[f], so.field[f]
+        assert list(a.hist) == list(b.hist) and list(a.code_len) == list(b.code_len)
+        for k in ("alphabet", "distinct", "mode", "max_len", "n_symbols", "payload_bits", "stream_bytes"):
+            assert getattr(a, k) == getattr(b, k), (f, k)
+        assert abs(a.entropy_bits - b.entropy_bits) < 1e-12 and a.mean_code_len == b.mean_code_len
+        assert a.ratio_payload == b.ratio_payload
+
+
+def test_stats_all_formats():
+    for fmt, n, cb in ((zc.FMT_FP8_E4M3, 300000, 65536), (zc.FMT_BF16, 200001, 16384), (zc.FMT_FP4_E2M1_MX, 32 * 9001, 8192)):
+        src, sc = make_input(fmt, n, 77)
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            st = zc.stats(dev(src), n, zc.params(fmt, cb, policy=policy), scales=dev(sc))
+            so = o.stats(src.numpy(), n, o.params(fmt, cb, policy=policy), scales=None if sc is None else sc.numpy())
+            compare_stats(st, so)
+
+
+def test_config2_fp8_layer_shapes_reduced():
+    # one decoder layer of config 2 with both matrix dimensions / 8, 256 KiB chunks, S = 64
+    for i, (name, r, c) in enumerate(wl.LAYER_8B):
+        n = (r // 8) * (c // 8)
+        x = wl.fp8_weight(n, seed=1000 + i)
+        check_case(zc.FMT_FP8_E4M3, n, 262144, 64, data=(x, None), tag=name)
+
+
+def test_config3_mxfp4_reduced():
+    p, s = wl.mxfp4_weight(512, 3584, seed=3)
+    want, _, _ = check_case(zc.FMT_FP4_E2M1_MX, 512 * 3584, 262144, 64, data=(p, s), tag="config3")
+    check_case(zc.FMT_FP4_E2M1_MX, 512 * 3584, 262144, 64, policy=zc.POLICY_AUTO, data=(p, s), tag="config3-auto")
+
+
+def test_config4_checkpoint_delta_reduced():
+    n = 1 << 21
+    w0, w1 = wl.bf16_checkpoint_pair(n, seed=4)
+    w0, w1 = w0.view(torch.uint8), w1.view(torch.uint8)
+    plain, _, _ = check_case(zc.FMT_BF16, n, 262144, 64, data=(w1, None), tag="config4-plain")
+    delta, _, _ = check_case(zc.FMT_BF16, n, 262144, 64, data=(w1, None), base=w0, tag="config4-delta")
+    assert len(delta) < 0.6 * len(plain)
+    check_case(zc.FMT_BF16, n, 65536, 64, policy=zc.POLICY_AUTO, data=(w1, None), base=w0, tag="config4-delta-auto")
+
+
+def test_config5_kv_pages_random_access():
+    # pages of 16 tokens x 128 = 2 KiB are the chunks; decode a random 25% of the pages densely
+    k, v = wl.fp8_kv_pair(batch=2, heads=4, tokens=1024, seed=5)
+    for name, t in (("K", k), ("V", v)):
+        flat = t.reshape(-1)
+        n = flat.numel()
+        for S in (8, 16, 4):
+            want, _, _ = check_case(zc.FMT_FP8_E4M3, n, 2048, S, data=(flat, None), tag="config5-" + name)
+            n_pages = n // 2048
+            ids = wl.page_sample(n_pages, 0.25, seed=S)
+            comp = torch.from_numpy(want).to(DEV)
+            info = zc.read_info(comp)
+            out, _ = zc.decompress_chunks(comp, info, ids.to(DEV))
+            torch.cuda.synchronize()
+            pages = flat.reshape(n_pages, 2048)[ids.long()]
+            assert torch.equal(out.cpu().reshape(-1, 2048), pages)
+            # the oracle decodes the same pages one by one
+            for i in ids[:5].tolist():
+                rc, pg, _ = o.decompress_chunk(want, i, 2048)
+                assert rc == o.OK and np.array_equal(pg, pages[ids.tolist().index(i)].numpy())
+
+
+def test_random_access_with_short_last_chunk_and_bad_ids():
+    n, cb = 10 * 4096 + 100, 4096
+    x = wl.fp8_weight(n, seed=9)
+    comp, info = zc.compress(x.to(DEV), n, zc.params(zc.FMT_FP8_E4M3, cb, streams=16))
+    ids = torch.tensor([10, 0, 99, 3, 10], dtype=torch.int32)
+    out = torch.full((5 * cb,), 0xA5, dtype=torch.uint8, device=DEV)
+    zc.decompress_chunks(comp, info, ids.to(DEV), out=out)
+    torch.cuda.synchronize()
+    out = out.cpu().reshape(5, cb)
+    assert torch.equal(out[0, :100], x[10 * cb:]) and bool((out[0, 100:] == 0xA5).all())
+    assert torch.equal(out[1], x[:cb]) and torch.equal(out[3], x[3 * cb:4 * cb]) and torch.equal(out[4], out[0])
+    assert bool((out[2] == 0xA5).all())          # id out of range: slot untouched
+
+
+def test_modes_const_two_valued_uniform_and_binding_limit():
+    n = 50000
+    rng = np.random.default_rng(12)
+    x = torch.full((n,), 0x38, dtype=torch.uint8)
+    check_case(zc.FMT_FP8_E4M3, n, 4096, 64, data=(x, None), tag="const")
+    x = torch.where(torch.arange(n) % 3 == 0, 0x38, 0x40).to(torch.uint8)
+    check_case(zc.FMT_FP8_E4M3, n, 4096, 64, data=(x, None), tag="two-valued")
+    x = torch.from_numpy(rng.integers(0, 256, n).astype(np.uint8))
+    check_case(zc.FMT_FP8_E4M3, n, 4096, 64, data=(x, None), tag="uniform")
+    check_case(zc.FMT_FP8_E4M3, n, 4096, 64, policy=zc.POLICY_AUTO, data=(x, None), tag="uniform-auto")
+    check_case(zc.FMT_BF16, n // 2, 4096, 64, data=(x, None), tag="uniform-bf16")
+    pr = np.exp2(-np.arange(1, 17, dtype=float)); pr /= pr.sum()
+    e = rng.choice(16, size=n, p=pr).astype(np.uint8)
+    x = torch.from_numpy(((e << 3) | rng.integers(0, 8, n).astype(np.uint8)).astype(np.uint8))
+    for L in (4, 5, 6, 8, 15):
+        check_case(zc.FMT_FP8_E4M3, n, 8192, 64, L=(L, L, 0), data=(x, None), tag="limit%d" % L)
+    # 256-symbol alphabet with geometric weights: code lengths up to 16 on both BF16 fields
+    pr = np.exp2(-np.minimum(np.arange(1, 257, dtype=float), 30) * 0.7); pr /= pr.sum()
+    a = rng.choice(256, size=n, p=pr).astype(np.uint16)
+    b = rng.choice(256, size=n, p=pr[::-1]).astype(np.uint16)
+    w = (((b & 0x80) << 8) | (a << 7) | (b & 0x7F)).astype(np.uint16)
+    x = torch.from_numpy(w.view(np.uint8).copy())
+    for L in (16, 12, 9):
+        check_case(zc.FMT_BF16, n, 16384, 64, L=(L, L, 0), data=(x, None), tag="bf16-limit%d" % L)
+
+
+def test_batch_round_trip_and_parity():
+    shapes = [70000, 1, 262144 * 2, 262144 + 5, 16, 300001]
+    srcs = [wl.fp8_weight(n, seed=50 + i) for i, n in enumerate(shapes)]
+    p = zc.params(zc.FMT_FP8_E4M3, 262144)
+    b = zc.Batch([s.to(DEV) for s in srcs], shapes, p)
+    sizes = b.compress()
+    for i, n in enumerate(shapes):
+        want = o.compress(srcs[i].numpy(), n, o.params(o.FP8_E4M3, 262144))
+        assert sizes[i] == len(want)
+        assert np.array_equal(b.container(i).cpu().numpy(), want), i
+    outs = b.decompress()
+    torch.cuda.synchronize()
+    for i, n in enumerate(shapes):
+        assert torch.equal(outs[i].cpu()[:n], srcs[i])
+    # second pass reuses every buffer and gives the same bytes (no stale state in the workspace)
+    for o_ in outs:
+        o_.fill_(0xA5)
+    sizes2 = b.compress()
+    outs = b.decompress()
+    torch.cuda.synchronize()
+    assert sizes2 == sizes
+    for i, n in enumerate(shapes):
+        assert torch.equal(outs[i].cpu()[:n], srcs[i])
+
+
+def test_errors():
+    x = wl.fp8_weight(9000, seed=22).to(DEV)
+    p = zc.params(zc.FMT_FP8_E4M3, 4096)
+    comp, info = zc.compress(x, 9000, p)
+    bad = comp.clone(); bad[0] = 0x5B
+    with pytest.raises(zc.ZcError) as e:
+        zc.read_info(bad)
+    assert e.value.status == zc.ERR_CORRUPT
+    bad = comp.clone(); bad[64] = 0            # incomplete code
+    with pytest.raises(zc.ZcError):
+        zc.read_info(bad)
+    bad = comp.clone(); bad[100:104] = 0xFF    # chunk offsets out of order
+    with pytest.raises(zc.ZcError):
+        zc.read_info(bad, check_index=True)
+    with pytest.raises(zc.ZcError) as e:
+        zc.decompress(comp, info, out=torch.empty(8992, dtype=torch.uint8, device=DEV))
+    assert e.value.status == zc.ERR_BUFFER_TOO_SMALL
+    with pytest.raises(zc.ZcError) as e:
+        zc.compress(x, 9000, p, dst=torch.empty(4096, dtype=torch.uint8, device=DEV))
+    assert e.value.status == zc.ERR_BUFFER_TOO_SMALL
+    with pytest.raises(zc.ZcError) as e:
+        zc.compress(x[1:], 8000, p)              # misaligned source
+    assert e.value.status == zc.ERR_INVALID_ARG
+    # a delta container cannot be decoded without its base
+    w0, w1 = wl.bf16_checkpoint_pair(5000, seed=1)
+    comp, info = zc.compress(w1.to(DEV), 5000, zc.params(zc.FMT_BF16, 4096), xor_base=w0.to(DEV))
+    with pytest.raises(zc.ZcError):
+        zc.decompress(comp, info)
+
+
+def test_determinism_and_poisoned_buffers():
+    n = 500000
+    x = wl.fp8_weight(n, seed=31).to(DEV)
+    p = zc.params(zc.FMT_FP8_E4M3, 65536)
+    ref = None
+    for fill in (0x00, 0xA5, 0xFF):
+        dst = torch.full((zc.compress_bound(n, p),), fill, dtype=torch.uint8, device=DEV)
+        ws = torch.full((zc.workspace_bytes([n], p),), fill, dtype=torch.uint8, device=DEV)
+        comp, info = zc.compress(x, n, p, dst=dst, ws=ws)
+        out = torch.full((n,), fill, dtype=torch.uint8, device=DEV)
+        zc.decompress(comp, info, out=out)
+        torch.cuda.synchronize()
+        assert torch.equal(out, x)
+        if ref is None:
+            ref = comp.clone()
+        assert torch.equal(comp, ref)

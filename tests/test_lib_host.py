@@ -1,0 +1,72 @@
+"""Host-side checks of the HIP library that need no GPU: it loads, exports every symbol
+of include/zc.h, and its code construction agrees with the oracle's."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import zc_oracle as o
+from paper_2508_19263_amd import zc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "zc.h")).read()
+    declared = set(re.findall(r"\b(zc_[a-z_]+)\s*\(", header))
+    assert declared == set(zc.EXPORTS)
+    L = zc.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_struct_sizes_match_the_header():
+    # sizes computed from the header's field lists by hand: see include/zc.h
+    assert C.sizeof(zc.Params) == 4 * 8
+    assert C.sizeof(zc.Info) == 8 * 4 + 3 * 8 + 6 * 8 + 12 + 768 + 4      # +4: tail padding to 8
+    assert C.sizeof(zc.FieldStats) == 16 + 8 + 2048 + 256 + 8 + 8 + 8 + 8 + 8
+    assert C.sizeof(zc.Tensor) == 9 * 8 + C.sizeof(zc.Info)
+
+
+def test_code_construction_matches_oracle_on_random_histograms():
+    rng = np.random.default_rng(40)
+    for trial in range(3000):
+        A = [4, 16, 256][trial % 3]
+        kind = (trial // 3) % 4
+        if kind == 0:
+            f = np.floor(np.exp2(rng.uniform(0, 30, A))).astype(np.uint64)
+        elif kind == 1:
+            f = rng.integers(0, 4, A).astype(np.uint64)                       # many ties and zeros
+        elif kind == 2:
+            f = (rng.integers(1, 100, A) * (rng.random(A) < 0.3)).astype(np.uint64)
+        else:
+            f = np.sort(np.floor(np.exp2(np.arange(A) * 40.0 / A)).astype(np.uint64))[::-1].copy()
+        if (f > 0).sum() < 2:
+            continue
+        L = int(rng.integers(max(1, int(np.ceil(np.log2((f > 0).sum())))), 17))
+        want = o.code_lengths(f.tolist(), L)
+        ln, cd = zc.build_code(f.tolist(), L)
+        assert ln == want.tolist(), (trial, L)
+        assert cd == o.canonical_codes(want).tolist()
+
+
+def test_code_construction_rejects_too_small_limit():
+    with pytest.raises(zc.ZcError):
+        zc.build_code([1] * 9, 3)
+
+
+def test_bounds_and_workspace():
+    for fmt, cb in ((zc.FMT_BF16, 65536), (zc.FMT_FP8_E4M3, 262144), (zc.FMT_FP4_E2M1_MX, 262144)):
+        p = zc.params(fmt, cb)
+        po = o.params(fmt, cb)
+        for n in (0, 32, 1 << 20, (1 << 22) + 32 * 5):
+            assert zc.compress_bound(n, p) >= 64
+            assert zc.workspace_bytes([n], p) > 0
+            assert zc.compress_bound(n, p) > 0 and o.compress_bound(n, po) > 0
+    assert zc.compress_bound(100, zc.params(zc.FMT_FP8_E4M3, 100)) == 0       # chunk not a multiple of 16
+    assert zc.compress_bound(100, zc.params(9, 4096)) == 0
+    assert zc.compress_bound(33, zc.params(zc.FMT_FP4_E2M1_MX, 256)) == 0     # FP4 needs whole 32-blocks
+    assert zc.compress_bound(64, zc.params(zc.FMT_FP8_E4M3, 4096, (3, 0, 0))) == 0   # 2^3 < 16 symbols
+    assert zc.status_string(zc.ERR_CORRUPT) == "corrupt container"
