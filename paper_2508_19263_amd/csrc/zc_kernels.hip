@@ -224,7 +224,7 @@ struct EncField {
 };
 
 template <bool WRITE>
-__device__ __forceinline__ void enc_request(EncField &F, bool active, const Lanes &L, uint32_t S)
+__device__ __forceinline__ void enc_request(EncField &F, bool active, const Lanes &L)
 {
     const bool req = active && F.k <= 32;
     const uint64_t bm = __ballot(req) & L.gmask;
@@ -235,7 +235,6 @@ __device__ __forceinline__ void enc_request(EncField &F, bool active, const Lane
         F.k += 32;
     }
     F.wpos += (uint32_t)__popcll(bm);
-    (void)S;
 }
 
 template <bool WRITE>
@@ -247,15 +246,18 @@ __device__ __forceinline__ void enc_flush_word(EncField &F, uint8_t *stream)
     F.pend--;
 }
 
-// encode symbols [J0, J0+R) of a run; sym(j) = (P >> (j*SB)) & mask
+// encode symbols [j0, j0+R) of a run; symbol j sits at bit (j % PER64)*SB of P0 (j < PER64) or P1
 template <bool WRITE, int SB, int R, bool FULL>
-__device__ __forceinline__ void enc_group(EncField &F, uint64_t P, int j0, uint32_t nsym, const uint32_t *enc, uint8_t *stream, const Lanes &L, uint32_t S)
+__device__ __forceinline__ void enc_group(EncField &F, uint64_t P0, uint64_t P1, int j0, uint32_t nsym, const uint32_t *enc, uint8_t *stream, const Lanes &L)
 {
-    enc_request<WRITE>(F, FULL || (uint32_t)j0 < nsym, L, S);
+    constexpr int PER64 = 64 / SB;
+    enc_request<WRITE>(F, FULL || (uint32_t)j0 < nsym, L);
 #pragma unroll
     for (int j = 0; j < R; j++) {
         if (FULL || (uint32_t)(j0 + j) < nsym) {
-            const uint32_t v = (uint32_t)(P >> ((j0 + j) * SB)) & ((1u << SB) - 1);
+            const int jj = j0 + j;
+            const uint64_t P = jj < PER64 ? P0 : P1;
+            const uint32_t v = (uint32_t)(P >> ((jj % PER64) * SB)) & ((1u << SB) - 1);
             const uint32_t e = enc[v];
             F.acc |= (uint64_t)(e & 0xFFFFu) << F.nacc;
             F.nacc += e >> 16;
@@ -266,41 +268,21 @@ __device__ __forceinline__ void enc_group(EncField &F, uint64_t P, int j0, uint3
 }
 
 template <bool WRITE, int SB, int G, int R, bool FULL>
-__device__ __forceinline__ void enc_run_r(EncField &F, uint64_t P0, uint64_t P1, uint32_t nsym, const uint32_t *enc, uint8_t *stream, const Lanes &L, uint32_t S)
+__device__ __forceinline__ void enc_run_r(EncField &F, uint64_t P0, uint64_t P1, uint32_t nsym, const uint32_t *enc, uint8_t *stream, const Lanes &L)
 {
-    // G*SB may be 64 (element fields) or 128 (scale field: P0 low half, P1 high half)
-    constexpr int PER64 = 64 / SB;
 #pragma unroll
-    for (int j0 = 0; j0 < G; j0 += R) {
-        if (j0 < PER64) enc_group<WRITE, SB, R, FULL>(F, P0, j0, nsym, enc, stream, L, S);
-        else {
-            // symbols of the upper half: shift indices down, keep the activity test on the real index
-            EncField &Fr = F;
-            enc_request<WRITE>(Fr, FULL || (uint32_t)j0 < nsym, L, S);
-#pragma unroll
-            for (int j = 0; j < R; j++) {
-                if (FULL || (uint32_t)(j0 + j) < nsym) {
-                    const uint32_t v = (uint32_t)(P1 >> ((j0 + j - PER64) * SB)) & ((1u << SB) - 1);
-                    const uint32_t e = enc[v];
-                    Fr.acc |= (uint64_t)(e & 0xFFFFu) << Fr.nacc;
-                    Fr.nacc += e >> 16;
-                    Fr.k -= (int32_t)(e >> 16);
-                }
-            }
-            if (Fr.nacc >= 32) { enc_flush_word<WRITE>(Fr, stream); Fr.nacc -= 32; }
-        }
-    }
+    for (int j0 = 0; j0 < G; j0 += R) enc_group<WRITE, SB, R, FULL>(F, P0, P1, j0, nsym, enc, stream, L);
 }
 
 template <bool WRITE, int SB, int G, bool FULL>
-__device__ __forceinline__ void enc_run(EncField &F, uint32_t period, uint64_t P0, uint64_t P1, uint32_t nsym, const uint32_t *enc, uint8_t *stream, const Lanes &L, uint32_t S)
+__device__ __forceinline__ void enc_run(EncField &F, uint32_t period, uint64_t P0, uint64_t P1, uint32_t nsym, const uint32_t *enc, uint8_t *stream, const Lanes &L)
 {
     switch (period) {
-    case 2: enc_run_r<WRITE, SB, G, 2, FULL>(F, P0, P1, nsym, enc, stream, L, S); break;
-    case 4: enc_run_r<WRITE, SB, G, 4, FULL>(F, P0, P1, nsym, enc, stream, L, S); break;
-    case 8: enc_run_r<WRITE, SB, G, 8, FULL>(F, P0, P1, nsym, enc, stream, L, S); break;
-    case 16: if (G >= 16) enc_run_r<WRITE, SB, G, (G >= 16 ? 16 : G), FULL>(F, P0, P1, nsym, enc, stream, L, S); break;
-    default: if (G >= 32) enc_run_r<WRITE, SB, G, (G >= 32 ? 32 : G), FULL>(F, P0, P1, nsym, enc, stream, L, S); break;
+    case 2: enc_run_r<WRITE, SB, G, 2, FULL>(F, P0, P1, nsym, enc, stream, L); break;
+    case 4: enc_run_r<WRITE, SB, G, 4, FULL>(F, P0, P1, nsym, enc, stream, L); break;
+    case 8: enc_run_r<WRITE, SB, G, 8, FULL>(F, P0, P1, nsym, enc, stream, L); break;
+    case 16: if (G >= 16) enc_run_r<WRITE, SB, G, (G >= 16 ? 16 : G), FULL>(F, P0, P1, nsym, enc, stream, L); break;
+    default: if (G >= 32) enc_run_r<WRITE, SB, G, (G >= 32 ? 32 : G), FULL>(F, P0, P1, nsym, enc, stream, L); break;
     }
 }
 
@@ -364,15 +346,15 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
         }
         const bool full = __all(nsym == (uint32_t)F_::G);
         if (m0 == ZC_MODE_HUFF) {
-            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F0, d.period[0], P0, 0, nsym, enc[0], stream[0], L, S);
-            else enc_run<WRITE, F_::SB, F_::G, false>(F0, d.period[0], P0, 0, nsym, enc[0], stream[0], L, S);
+            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F0, d.period[0], P0, 0, nsym, enc[0], stream[0], L);
+            else enc_run<WRITE, F_::SB, F_::G, false>(F0, d.period[0], P0, 0, nsym, enc[0], stream[0], L);
         } else if (m0 == ZC_MODE_RAW && WRITE && nsym) {
             reinterpret_cast<uint64_t *>(stream[0])[run] = P0;
             if ((run & 1) == 0 && done + F_::G >= n) reinterpret_cast<uint64_t *>(stream[0])[run + 1] = 0;
         }
         if (m1 == ZC_MODE_HUFF) {
-            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F1, d.period[1], P1, 0, nsym, enc[1], stream[1], L, S);
-            else enc_run<WRITE, F_::SB, F_::G, false>(F1, d.period[1], P1, 0, nsym, enc[1], stream[1], L, S);
+            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F1, d.period[1], P1, 0, nsym, enc[1], stream[1], L);
+            else enc_run<WRITE, F_::SB, F_::G, false>(F1, d.period[1], P1, 0, nsym, enc[1], stream[1], L);
         } else if (m1 == ZC_MODE_RAW && WRITE && nsym) {
             reinterpret_cast<uint64_t *>(stream[1])[run] = P1;
             if ((run & 1) == 0 && done + F_::G >= n) reinterpret_cast<uint64_t *>(stream[1])[run + 1] = 0;
@@ -406,8 +388,8 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
             }
             const bool full = __all(nsym == 16u);
             if (m2 == ZC_MODE_HUFF) {
-                if (full) enc_run<WRITE, 8, 16, true>(F2, d.period[2], P0, P1, nsym, enc[2], stream[2], L, S);
-                else enc_run<WRITE, 8, 16, false>(F2, d.period[2], P0, P1, nsym, enc[2], stream[2], L, S);
+                if (full) enc_run<WRITE, 8, 16, true>(F2, d.period[2], P0, P1, nsym, enc[2], stream[2], L);
+                else enc_run<WRITE, 8, 16, false>(F2, d.period[2], P0, P1, nsym, enc[2], stream[2], L);
             } else if (m2 == ZC_MODE_RAW && WRITE && nsym) {
                 reinterpret_cast<uint64_t *>(stream[2])[2 * run] = P0;
                 reinterpret_cast<uint64_t *>(stream[2])[2 * run + 1] = P1;
@@ -609,21 +591,24 @@ __device__ __noinline__ uint32_t dec_long(const FieldTab &T, uint32_t x)
     return T.lmax ? T.lmax : 1;      // malformed table: consume something, symbol 0
 }
 
-// decode symbols [j0, j0+R) of a run into P (SB bits each, symbol j at bit j*SB of a 64-bit half)
+// decode symbols [j0, j0+R) of a run; symbol j goes to bit (j % PER64)*SB of P0 (j < PER64) or P1
 template <int SB, int R, bool FULL>
-__device__ __forceinline__ void dec_group(DecField &D, const FieldTab &T, uint64_t &P, int j0, int shift0, uint32_t nsym, const Lanes &L)
+__device__ __forceinline__ void dec_group(DecField &D, const FieldTab &T, uint64_t &P0, uint64_t &P1, int j0, uint32_t nsym, const Lanes &L)
 {
+    constexpr int PER64 = 64 / SB;
     dec_refill(D, FULL || (uint32_t)j0 < nsym, L);
     uint32_t x = (uint32_t)((((uint64_t)D.hi << 32) | D.lo) >> D.c);
     const uint32_t mask = T.mask;
 #pragma unroll
     for (int j = 0; j < R; j++) {
         if (FULL || (uint32_t)(j0 + j) < nsym) {
+            const int jj = j0 + j;
             uint32_t e = T.lut[x & mask];
             if (e == 0) e = dec_long(T, x);
             x >>= (e & 31u);
             D.c += (e & 31u);
-            P |= (uint64_t)(e >> 8) << ((j0 + j - shift0) * SB);
+            if (jj < PER64) P0 |= (uint64_t)(e >> 8) << ((jj % PER64) * SB);
+            else P1 |= (uint64_t)(e >> 8) << ((jj % PER64) * SB);
         }
     }
 }
@@ -631,12 +616,8 @@ __device__ __forceinline__ void dec_group(DecField &D, const FieldTab &T, uint64
 template <int SB, int G, int R, bool FULL>
 __device__ __forceinline__ void dec_run_r(DecField &D, const FieldTab &T, uint64_t &P0, uint64_t &P1, uint32_t nsym, const Lanes &L)
 {
-    constexpr int PER64 = 64 / SB;
 #pragma unroll
-    for (int j0 = 0; j0 < G; j0 += R) {
-        if (j0 < PER64) dec_group<SB, R, FULL>(D, T, P0, j0, 0, nsym, L);
-        else dec_group<SB, R, FULL>(D, T, P1, j0, PER64, nsym, L);
-    }
+    for (int j0 = 0; j0 < G; j0 += R) dec_group<SB, R, FULL>(D, T, P0, P1, j0, nsym, L);
 }
 
 template <int SB, int G, bool FULL>
