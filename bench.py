@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the field-split Huffman codec on one MI355X.
+
+Workload (the configuration the headline metric is quoted on): the FP8 E4M3 weight set
+shaped like 32 decoder layers of an 8B-class model (224 tensors, 6.98 GB), synthetic
+N(0, 0.02) values with 0.1% outliers, per-tensor scaled to amax = 448, one Huffman code
+per field per tensor, 256 KiB chunks, 64 lanes per chunk.
+
+One step = one pass of the whole path over the set with inputs resident in HBM:
+  compress   (field split + histogram, code construction, stream sizes, scan, encode)
+  decompress (descriptor upload, then the chunked decode + re-interleave kernel)
+`value` is the decompress throughput in GB/s of uncompressed bytes; the compress
+throughput and the ratios ride along in the same JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per decode launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each
+# scaled by what the same counter reads for a plain copy of known size); None = not measured
+MEASURED_TRAFFIC_BYTES = {"fp8_e4m3_weight_set_8b_x32": None}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--layers", type=int, default=32, help="decoder layers in the weight set (32 = the full configuration)")
+    ap.add_argument("--chunk-kib", type=int, default=256)
+    ap.add_argument("--max-len", type=int, default=0, help="code length limit of the exponent field (0 = library default)")
+    ap.add_argument("--policy", choices=["huff_all", "auto"], default="huff_all")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--decode-only", action="store_true", help="timed steps run only the decode kernel (for profiling)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (every chunk and tensor is "
+              "independent, so N GPUs would each take whole tensors); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2508_19263_amd import workloads as wl
+    from paper_2508_19263_amd import zc
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    policy = zc.POLICY_AUTO if args.policy == "auto" else zc.POLICY_HUFF_ALL
+    p = zc.params(zc.FMT_FP8_E4M3, args.chunk_kib * 1024, (args.max_len, 0, 0), 64, policy)
+
+    names, srcs = [], []
+    for name, t in wl.fp8_weight_set(args.layers, device=dev):
+        names.append(name)
+        srcs.append(t)
+    counts = [t.numel() for t in srcs]
+    raw_bytes = sum(counts)
+    batch = zc.Batch(srcs, counts, p)
+    batch.prepare_outputs()
+
+    def step(ev):
+        if ev:
+            ev[0].record()
+        if not args.decode_only:
+            batch.compress()
+        if ev:
+            ev[1].record()
+        if not args.decode_only:
+            batch.plan_decompress()
+        if ev:
+            ev[2].record()
+        batch.run_decompress()
+        if ev:
+            ev[3].record()
+
+    sizes = batch.compress()
+    batch.plan_decompress()
+    comp_bytes = sum(sizes)
+    for _ in range(args.warmup):
+        step(None)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_comp = [e[0].elapsed_time(e[1]) for e in events]
+    ms_plan = [e[1].elapsed_time(e[2]) for e in events]
+    ms_kern = [e[2].elapsed_time(e[3]) for e in events]
+    mean = lambda v: sum(v) / len(v)
+    ms_decomp = mean(ms_plan) + mean(ms_kern)
+    ms_step = wall * 1000.0 / args.steps
+
+    # bit-exact round trip of the whole set
+    ok = all(torch.equal(o[:n], s) for o, s, n in zip(batch.out, srcs, counts))
+    if not ok:
+        print("ROUND TRIP MISMATCH", file=sys.stderr)
+        sys.exit(1)
+
+    # per-field ratios on layer 0 (payload bits / raw bits), container ratio on the whole set
+    f0_bits = f1_bits = f_syms = 0
+    for i in range(min(7, len(srcs))):
+        st = zc.stats(srcs[i], counts[i], p)
+        f0_bits += st.field[0].payload_bits
+        f1_bits += st.field[1].payload_bits
+        f_syms += st.field[0].n_symbols
+    ratio_exp = f0_bits / (4.0 * f_syms)
+    ratio_sm = f1_bits / (4.0 * f_syms)
+
+    workload = "fp8_e4m3_weight_set_8b_x%d" % args.layers
+    algo_bytes = comp_bytes + raw_bytes               # decode reads the containers, writes the tensors
+    kern_s = mean(ms_kern) / 1000.0
+    result = {
+        "metric": "decompress GB/s (uncompressed bytes) + compression ratio, FP8 E4M3 weights",
+        "value": raw_bytes / (ms_decomp / 1000.0) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": workload, "tensors": len(srcs), "uncompressed_bytes": raw_bytes,
+                   "chunk_bytes": args.chunk_kib * 1024, "streams_per_chunk": 64, "policy": args.policy,
+                   "max_code_len_exponent": args.max_len or 8, "decode_only": args.decode_only},
+        "compression_ratio": {"total_container": comp_bytes / raw_bytes, "exponent_payload": ratio_exp,
+                              "sign_mantissa_payload": ratio_sm, "compressed_bytes": comp_bytes},
+        "decompress_ms": ms_decomp, "decode_kernel_ms": mean(ms_kern), "decode_kernel_ms_min": min(ms_kern),
+        "compress_ms": mean(ms_comp), "compress_GBps": (raw_bytes / (mean(ms_comp) / 1000.0) / 1e9) if mean(ms_comp) > 0 else None,
+        "decompress_frac_of_hbm_peak_uncompressed": raw_bytes / (ms_decomp / 1000.0) / 1e9 / HBM_PEAK_GBPS,
+        "round_trip_bit_exact": ok,
+        "roofline": {"bound": "hbm", "kernel": "k_decode<FP8_E4M3>", "achieved": algo_bytes / kern_s / 1e9, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": algo_bytes / kern_s / 1e9 / HBM_PEAK_GBPS,
+                     "algorithmic_bytes_per_launch": algo_bytes, "traffic": MEASURED_TRAFFIC_BYTES.get(workload)},
+    }
+
+    if not args.no_cpu_baseline:
+        # the oracle as it stands, single thread, on a bounded sample of the same workload
+        import numpy as np
+        from oracle import zc_oracle as o
+        sample = [i for i in range(min(5, len(srcs)))]            # layer 0: q, k, v, o, gate
+        po = o.params(o.FP8_E4M3, args.chunk_kib * 1024, (args.max_len, 0, 0), 64, 1 if args.policy == "auto" else 0)
+        host = [srcs[i].cpu().numpy() for i in sample]
+        t_c = t_d = 0.0
+        nbytes = 0
+        for x in host:
+            t = time.perf_counter(); c = o.compress(x, len(x), po); t_c += time.perf_counter() - t
+            t = time.perf_counter(); rc, out, _ = o.decompress(c, len(x)); t_d += time.perf_counter() - t
+            assert rc == 0 and np.array_equal(out, x)
+            nbytes += len(x)
+        result["cpu_baseline"] = {"value": nbytes / t_d / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                  "sample": "oracle decompress of layer 0's q,k,v,o,gate tensors (%d bytes, %.1f s); "
+                                            "its compress ran at %.4f GB/s" % (nbytes, t_d, nbytes / t_c / 1e9),
+                                  "host_cores_visible": os.cpu_count()}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

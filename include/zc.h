@@ -63,7 +63,7 @@ typedef struct {
     uint32_t format;            /* zc_format */
     uint32_t chunk_bytes;       /* element bytes per chunk; multiple of 16 (FP4: of 256) */
     uint32_t max_code_len[3];   /* per field, 1..16 with 2^L >= alphabet; 0 = 16 for 8-bit symbols, else 8 */
-    uint32_t streams_per_chunk; /* lanes per chunk: 1,2,4,...,64; 0 = 64.  Device paths need >= 4 */
+    uint32_t streams_per_chunk; /* lanes per chunk: 1,2,4,...,64; 0 = 64 */
     uint32_t policy;            /* zc_policy */
 } zc_params;
 
@@ -165,9 +165,20 @@ zc_status zc_decompress_chunks(const void *d_comp, uint64_t comp_bytes, const zc
                                const void *d_xor_base, void *stream);
 
 /* Whole-set decode in one launch: every tensor's d_comp/info/d_dst (and d_xor_base,
- * d_scales_out) must be set.  All tensors must share format and streams.  Does not synchronise. */
+ * d_scales_out) must be set.  All tensors must share format and streams.  The per-tensor
+ * descriptors and the work list are uploaded to d_ws with a blocking copy (the stream is
+ * synchronised before the launch, not after it). */
 zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors,
                               void *d_ws, uint64_t ws_bytes, void *stream);
+
+/* The two halves of zc_decompress_batch, for callers that decode the same set more than
+ * once: _plan validates and uploads the descriptors and the work list to d_ws (blocking)
+ * and returns the number of work items (host); _run only enqueues the decode kernel on
+ * d_ws as left by _plan (never synchronises). */
+zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors, void *d_ws, uint64_t ws_bytes,
+                                   uint32_t *out_n_work, void *stream);
+zc_status zc_decompress_batch_run(uint32_t format, uint32_t streams, uint32_t n_tensors, uint32_t n_work,
+                                  const void *d_ws, void *stream);
 
 /* Per-field histogram, entropy, code lengths, payload bits, stream and container bytes
  * and the ratios of Sec. 4, without producing the container.  out: host.  Synchronises. */

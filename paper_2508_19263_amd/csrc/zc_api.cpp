@@ -558,8 +558,11 @@ zc_status zc_decompress_chunks(const void *d_comp, uint64_t comp_bytes, const zc
     return decode_common(d_comp, comp_bytes, info, d_chunk_ids, n_ids, true, d_dst, dst_capacity, d_scales_out, d_xor_base, stream);
 }
 
-zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors, void *d_ws, uint64_t ws_bytes, void *stream)
+zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors, void *d_ws, uint64_t ws_bytes,
+                                   uint32_t *out_n_work, void *stream)
 {
+    if (!out_n_work) return ZC_ERR_INVALID_ARG;
+    *out_n_work = 0;
     if (n_tensors == 0) return ZC_OK;
     if (!tensors || !d_ws || !aligned16(d_ws)) return ZC_ERR_INVALID_ARG;
     const uint32_t fmt = tensors[0].info.format, S = tensors[0].info.streams;
@@ -585,11 +588,29 @@ zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors, void
     hipStream_t hs = (hipStream_t)stream;
     uint8_t *ws = (uint8_t *)d_ws;
     HIP_TRY(hipMemcpyAsync(ws, descs.data(), descs.size() * sizeof(TensorDev), hipMemcpyHostToDevice, hs));
-    if (work.empty()) return ZC_OK;
-    HIP_TRY(hipMemcpyAsync(ws + descs_bytes, work.data(), work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
+    if (!work.empty()) HIP_TRY(hipMemcpyAsync(ws + descs_bytes, work.data(), work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
     HIP_TRY(hipStreamSynchronize(hs));      // the host arrays above go away when this call returns
-    LAUNCH_TRY(launch_decode(fmt, (const TensorDev *)ws, (const WorkItem *)(ws + descs_bytes), (uint32_t)work.size(), cpi, nullptr, nullptr, 0, stream));
+    *out_n_work = (uint32_t)work.size();
     return ZC_OK;
+}
+
+zc_status zc_decompress_batch_run(uint32_t format, uint32_t streams, uint32_t n_tensors, uint32_t n_work,
+                                  const void *d_ws, void *stream)
+{
+    if (n_work == 0) return ZC_OK;
+    if (!d_ws || !elem_bits(format) || streams == 0 || streams > 64 || (streams & (streams - 1)) || n_tensors == 0) return ZC_ERR_INVALID_ARG;
+    const uint8_t *ws = (const uint8_t *)d_ws;
+    const uint64_t descs_bytes = align256((uint64_t)n_tensors * sizeof(TensorDev));
+    LAUNCH_TRY(launch_decode(format, (const TensorDev *)ws, (const WorkItem *)(ws + descs_bytes), n_work, chunks_per_work_item(streams), nullptr, nullptr, 0, stream));
+    return ZC_OK;
+}
+
+zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors, void *d_ws, uint64_t ws_bytes, void *stream)
+{
+    uint32_t n_work = 0;
+    zc_status st = zc_decompress_batch_plan(tensors, n_tensors, d_ws, ws_bytes, &n_work, stream);
+    if (st || n_work == 0) return st;
+    return zc_decompress_batch_run(tensors[0].info.format, tensors[0].info.streams, n_tensors, n_work, d_ws, stream);
 }
 
 }  // extern "C"

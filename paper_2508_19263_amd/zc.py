@@ -19,7 +19,8 @@ MODE_EMPTY, MODE_HUFF, MODE_RAW, MODE_CONST = 0, 1, 2, 3
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_BUFFER_TOO_SMALL, ERR_CORRUPT, ERR_DEVICE = range(6)
 
 EXPORTS = ["zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_compress_batch", "zc_read_info",
-           "zc_decompress", "zc_decompress_chunks", "zc_decompress_batch", "zc_stats", "zc_build_code",
+           "zc_decompress", "zc_decompress_chunks", "zc_decompress_batch", "zc_decompress_batch_plan",
+           "zc_decompress_batch_run", "zc_stats", "zc_build_code",
            "zc_status_string"]
 
 
@@ -91,6 +92,10 @@ def lib():
         L.zc_decompress_chunks.argtypes = [vp, u64, C.POINTER(Info), vp, u32, vp, u64, vp, vp, vp]
         L.zc_decompress_batch.restype = C.c_int
         L.zc_decompress_batch.argtypes = [C.POINTER(Tensor), u32, vp, u64, vp]
+        L.zc_decompress_batch_plan.restype = C.c_int
+        L.zc_decompress_batch_plan.argtypes = [C.POINTER(Tensor), u32, vp, u64, C.POINTER(u32), vp]
+        L.zc_decompress_batch_run.restype = C.c_int
+        L.zc_decompress_batch_run.argtypes = [u32, u32, u32, u32, vp, vp]
         L.zc_stats.restype = C.c_int
         L.zc_stats.argtypes = [vp, u64, C.POINTER(Params), vp, vp, C.POINTER(StatsOut), vp, u64, vp]
         L.zc_build_code.restype = C.c_int
@@ -266,4 +271,20 @@ class Batch:
         if self.out is None:
             self.prepare_outputs()
         _check(lib().zc_decompress_batch(self.arr, self.n, _ptr(self.ws), self.ws.numel(), _stream()), "zc_decompress_batch")
+        return self.out
+
+    def plan_decompress(self):
+        """Upload descriptors and work list (blocking); returns the number of work items."""
+        if self.out is None:
+            self.prepare_outputs()
+        n_work = C.c_uint32(0)
+        _check(lib().zc_decompress_batch_plan(self.arr, self.n, _ptr(self.ws), self.ws.numel(), C.byref(n_work), _stream()),
+               "zc_decompress_batch_plan")
+        self.n_work = n_work.value
+        return self.n_work
+
+    def run_decompress(self):
+        """Enqueue the decode kernel on the plan left in the workspace by plan_decompress()."""
+        _check(lib().zc_decompress_batch_run(self.p.format, int(self.arr[0].info.streams), self.n, self.n_work, _ptr(self.ws), _stream()),
+               "zc_decompress_batch_run")
         return self.out
