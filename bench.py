@@ -133,7 +133,7 @@ def main():
         "compress_ms": mean(ms_comp), "compress_GBps": (raw_bytes / (mean(ms_comp) / 1000.0) / 1e9) if mean(ms_comp) > 0 else None,
         "decompress_frac_of_hbm_peak_uncompressed": raw_bytes / (ms_decomp / 1000.0) / 1e9 / HBM_PEAK_GBPS,
         "round_trip_bit_exact": ok,
-        "roofline": {"bound": "hbm", "kernel": "k_decode<FP8_E4M3>", "achieved": algo_bytes / kern_s / 1e9, "peak": HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": "k_decode_fp8", "achieved": algo_bytes / kern_s / 1e9, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": algo_bytes / kern_s / 1e9 / HBM_PEAK_GBPS,
                      "algorithmic_bytes_per_launch": algo_bytes, "traffic": MEASURED_TRAFFIC_BYTES.get(workload)},
     }

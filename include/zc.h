@@ -172,13 +172,19 @@ zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors,
                               void *d_ws, uint64_t ws_bytes, void *stream);
 
 /* The two halves of zc_decompress_batch, for callers that decode the same set more than
- * once: _plan validates and uploads the descriptors and the work list to d_ws (blocking)
- * and returns the number of work items (host); _run only enqueues the decode kernel on
- * d_ws as left by _plan (never synchronises). */
+ * once: _plan validates and uploads the descriptors and the work lists to d_ws (blocking)
+ * and fills *plan (host); _run only enqueues the decode kernels on d_ws as left by _plan
+ * (never synchronises).  The plan is plain data; it stays valid while d_ws, the containers
+ * and the destination pointers are unchanged. */
+typedef struct {
+    uint32_t format, streams, n_tensors;
+    uint32_t n_fast_work, n_work;               /* work items of the specialised / generic kernel */
+    uint32_t fast_exp_kind, fast_sm_kind, xor_delta;
+    uint64_t fast_work_offset, work_offset;     /* byte offsets of the two work lists in d_ws */
+} zc_batch_plan;
 zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors, void *d_ws, uint64_t ws_bytes,
-                                   uint32_t *out_n_work, void *stream);
-zc_status zc_decompress_batch_run(uint32_t format, uint32_t streams, uint32_t n_tensors, uint32_t n_work,
-                                  const void *d_ws, void *stream);
+                                   zc_batch_plan *plan, void *stream);
+zc_status zc_decompress_batch_run(const zc_batch_plan *plan, const void *d_ws, void *stream);
 
 /* Per-field histogram, entropy, code lengths, payload bits, stream and container bytes
  * and the ratios of Sec. 4, without producing the container.  out: host.  Synchronises. */

@@ -337,6 +337,24 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     return ZC_OK;
 }
 
+// Can the specialised FP8 kernel decode this container's full chunks?
+struct FastKind { bool ok; int exp_kind, sm_kind; };
+
+FastKind fast_kind(const zc_info &info)
+{
+    FastKind k = {false, 0, 0};
+    if (info.format != ZC_FMT_FP8_E4M3 || info.streams != 64 || info.chunk_bytes % 1024) return k;
+    if (info.mode[0] != ZC_MODE_HUFF || info.max_len[0] > 8 || info.max_len[0] == 0) return k;
+    if (info.mode[1] == ZC_MODE_RAW) k.sm_kind = 1;
+    else if (info.mode[1] == ZC_MODE_HUFF) {
+        for (int v = 0; v < 16; v++) if (info.code_len[1][v] != 4) return k;   // flat: canonical code == symbol
+        k.sm_kind = 0;
+    } else return k;
+    k.exp_kind = info.max_len[0] <= 6 ? 1 : 0;
+    k.ok = true;
+    return k;
+}
+
 zc_status parse_info(const uint8_t *c, uint64_t have, uint64_t comp_bytes, zc_info *out)
 {
     if (have < kHeaderBytes || comp_bytes < kHeaderBytes) return ZC_ERR_CORRUPT;
@@ -415,8 +433,18 @@ zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *
     d.comp = (uint8_t *)d_comp; d.dst = (uint8_t *)d_dst; d.scales_out = (uint8_t *)d_scales_out;
     d.base = info.xor_delta ? (const uint8_t *)d_xor_base : nullptr;
     const uint32_t cpi = chunks_per_work_item(info.streams);
-    const uint32_t n_work = (slots + cpi - 1) / cpi;
-    LAUNCH_TRY(launch_decode(info.format, nullptr, nullptr, n_work, cpi, &d, by_ids ? d_ids : nullptr, n_ids, stream));
+    const FastKind fk = fast_kind(info);
+    uint32_t first_slot = 0;
+    if (fk.ok && !by_ids) {
+        // full chunks through the specialised kernel, a short last chunk through the generic one
+        const uint32_t n_full = (uint32_t)(info.n_elems / ((uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(info.format)));
+        LAUNCH_TRY(launch_decode_fp8_fast(fk.exp_kind, fk.sm_kind, info.xor_delta != 0, nullptr, nullptr, (n_full + kWavesPerGroup - 1) / kWavesPerGroup, &d, stream));
+        first_slot = n_full;
+    }
+    if (first_slot < slots) {
+        const uint32_t n_work = (slots - first_slot + cpi - 1) / cpi;
+        LAUNCH_TRY(launch_decode(info.format, nullptr, nullptr, n_work, cpi, &d, first_slot, by_ids ? d_ids : nullptr, n_ids, stream));
+    }
     return ZC_OK;
 }
 
@@ -559,17 +587,23 @@ zc_status zc_decompress_chunks(const void *d_comp, uint64_t comp_bytes, const zc
 }
 
 zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors, void *d_ws, uint64_t ws_bytes,
-                                   uint32_t *out_n_work, void *stream)
+                                   zc_batch_plan *plan, void *stream)
 {
-    if (!out_n_work) return ZC_ERR_INVALID_ARG;
-    *out_n_work = 0;
+    if (!plan) return ZC_ERR_INVALID_ARG;
+    std::memset(plan, 0, sizeof(*plan));
     if (n_tensors == 0) return ZC_OK;
     if (!tensors || !d_ws || !aligned16(d_ws)) return ZC_ERR_INVALID_ARG;
     const uint32_t fmt = tensors[0].info.format, S = tensors[0].info.streams;
     if (!elem_bits(fmt) || S == 0 || S > 64 || (S & (S - 1))) return ZC_ERR_INVALID_ARG;
     const uint32_t cpi = chunks_per_work_item(S);
+    // the specialised kernel is used when every tensor of the set qualifies in the same way
+    FastKind fk = fast_kind(tensors[0].info);
+    for (uint32_t t = 1; t < n_tensors && fk.ok; t++) {
+        const FastKind k = fast_kind(tensors[t].info);
+        if (!k.ok || k.exp_kind != fk.exp_kind || k.sm_kind != fk.sm_kind || tensors[t].info.xor_delta != tensors[0].info.xor_delta) fk.ok = false;
+    }
     std::vector<TensorDev> descs(n_tensors);
-    std::vector<WorkItem> work;
+    std::vector<WorkItem> fast_work, work;
     for (uint32_t t = 0; t < n_tensors; t++) {
         const zc_tensor &x = tensors[t];
         const zc_info &info = x.info;
@@ -581,36 +615,51 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
         descs[t] = make_desc(info);
         descs[t].comp = (uint8_t *)x.d_comp; descs[t].dst = (uint8_t *)x.d_dst; descs[t].scales_out = (uint8_t *)x.d_scales_out;
         descs[t].base = info.xor_delta ? (const uint8_t *)x.d_xor_base : nullptr;
-        for (uint32_t c = 0; c < info.n_chunks; c += cpi) work.push_back({t, c});
+        uint32_t first_generic = 0;
+        if (fk.ok) {
+            const uint32_t n_full = (uint32_t)(info.n_elems / ((uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(fmt)));
+            for (uint32_t c = 0; c < n_full; c += kWavesPerGroup) fast_work.push_back({t, c});
+            first_generic = n_full;
+        }
+        for (uint32_t c = first_generic; c < info.n_chunks; c += cpi) work.push_back({t, c});
     }
     const uint64_t descs_bytes = align256((uint64_t)n_tensors * sizeof(TensorDev));
-    if (ws_bytes < descs_bytes + work.size() * sizeof(WorkItem)) return ZC_ERR_BUFFER_TOO_SMALL;
+    const uint64_t fast_bytes = align256(fast_work.size() * sizeof(WorkItem));
+    if (ws_bytes < descs_bytes + fast_bytes + work.size() * sizeof(WorkItem)) return ZC_ERR_BUFFER_TOO_SMALL;
     hipStream_t hs = (hipStream_t)stream;
     uint8_t *ws = (uint8_t *)d_ws;
     HIP_TRY(hipMemcpyAsync(ws, descs.data(), descs.size() * sizeof(TensorDev), hipMemcpyHostToDevice, hs));
-    if (!work.empty()) HIP_TRY(hipMemcpyAsync(ws + descs_bytes, work.data(), work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
+    if (!fast_work.empty()) HIP_TRY(hipMemcpyAsync(ws + descs_bytes, fast_work.data(), fast_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
+    if (!work.empty()) HIP_TRY(hipMemcpyAsync(ws + descs_bytes + fast_bytes, work.data(), work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
     HIP_TRY(hipStreamSynchronize(hs));      // the host arrays above go away when this call returns
-    *out_n_work = (uint32_t)work.size();
+    plan->format = fmt; plan->streams = S; plan->n_tensors = n_tensors;
+    plan->n_fast_work = (uint32_t)fast_work.size(); plan->n_work = (uint32_t)work.size();
+    plan->fast_exp_kind = (uint32_t)fk.exp_kind; plan->fast_sm_kind = (uint32_t)fk.sm_kind; plan->xor_delta = tensors[0].info.xor_delta;
+    plan->fast_work_offset = descs_bytes; plan->work_offset = descs_bytes + fast_bytes;
     return ZC_OK;
 }
 
-zc_status zc_decompress_batch_run(uint32_t format, uint32_t streams, uint32_t n_tensors, uint32_t n_work,
-                                  const void *d_ws, void *stream)
+zc_status zc_decompress_batch_run(const zc_batch_plan *plan, const void *d_ws, void *stream)
 {
-    if (n_work == 0) return ZC_OK;
-    if (!d_ws || !elem_bits(format) || streams == 0 || streams > 64 || (streams & (streams - 1)) || n_tensors == 0) return ZC_ERR_INVALID_ARG;
+    if (!plan) return ZC_ERR_INVALID_ARG;
+    if (plan->n_tensors == 0 || (plan->n_work == 0 && plan->n_fast_work == 0)) return ZC_OK;
+    if (!d_ws || !elem_bits(plan->format) || plan->streams == 0 || plan->streams > 64 || (plan->streams & (plan->streams - 1))) return ZC_ERR_INVALID_ARG;
     const uint8_t *ws = (const uint8_t *)d_ws;
-    const uint64_t descs_bytes = align256((uint64_t)n_tensors * sizeof(TensorDev));
-    LAUNCH_TRY(launch_decode(format, (const TensorDev *)ws, (const WorkItem *)(ws + descs_bytes), n_work, chunks_per_work_item(streams), nullptr, nullptr, 0, stream));
+    if (plan->n_fast_work)
+        LAUNCH_TRY(launch_decode_fp8_fast((int)plan->fast_exp_kind, (int)plan->fast_sm_kind, plan->xor_delta != 0, (const TensorDev *)ws,
+                                          (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, stream));
+    if (plan->n_work)
+        LAUNCH_TRY(launch_decode(plan->format, (const TensorDev *)ws, (const WorkItem *)(ws + plan->work_offset), plan->n_work,
+                                 chunks_per_work_item(plan->streams), nullptr, 0, nullptr, 0, stream));
     return ZC_OK;
 }
 
 zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors, void *d_ws, uint64_t ws_bytes, void *stream)
 {
-    uint32_t n_work = 0;
-    zc_status st = zc_decompress_batch_plan(tensors, n_tensors, d_ws, ws_bytes, &n_work, stream);
-    if (st || n_work == 0) return st;
-    return zc_decompress_batch_run(tensors[0].info.format, tensors[0].info.streams, n_tensors, n_work, d_ws, stream);
+    zc_batch_plan plan;
+    zc_status st = zc_decompress_batch_plan(tensors, n_tensors, d_ws, ws_bytes, &plan, stream);
+    if (st) return st;
+    return zc_decompress_batch_run(&plan, d_ws, stream);
 }
 
 }  // extern "C"

@@ -72,7 +72,10 @@ int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, cons
 int launch_encode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
                   const uint32_t *d_enc_tables, void *stream);
 int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
-                  const TensorDev *single, const uint32_t *d_ids, uint32_t n_ids, void *stream);
+                  const TensorDev *single, uint32_t first_slot, const uint32_t *d_ids, uint32_t n_ids, void *stream);
+// specialised FP8 decode of full chunks (zc_decode_fast.hip); exp_kind 0 = single, 1 = pair lookups; sm_kind 0 = flat, 1 = raw
+int launch_decode_fp8_fast(int exp_kind, int sm_kind, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+                           const TensorDev *single, void *stream);
 uint32_t chunks_per_work_item(uint32_t streams);
 
 }  // namespace zc

@@ -654,13 +654,13 @@ __device__ __forceinline__ DecField open_stream(const TensorDev &d, int f, uint3
 
 template <int FMT>
 __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single,
-                                                const uint32_t *ids, uint32_t n_ids)
+                                                uint32_t first_slot, const uint32_t *ids, uint32_t n_ids)
 {
     using F_ = Fmt<FMT>;
     __shared__ FieldTab tab[F_::NF];
     __shared__ TensorDev dsh;
     WorkItem it;
-    if (use_single) { it.tensor = 0; it.first = blockIdx.x * kWavesPerGroup * (64 / single.streams); }
+    if (use_single) { it.tensor = 0; it.first = first_slot + blockIdx.x * kWavesPerGroup * (64 / single.streams); }
     else it = work[blockIdx.x];
     if (threadIdx.x == 0) dsh = use_single ? single : descs[it.tensor];
     __syncthreads();
@@ -737,15 +737,15 @@ __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const Wo
 }
 
 int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t,
-                  const TensorDev *single, const uint32_t *d_ids, uint32_t n_ids, void *stream)
+                  const TensorDev *single, uint32_t first_slot, const uint32_t *d_ids, uint32_t n_ids, void *stream)
 {
     if (n_work == 0) return 0;
     hipStream_t st = (hipStream_t)stream;
     TensorDev s = single ? *single : TensorDev{};
     const int use_single = single ? 1 : 0;
-    if (fmt == ZC_FMT_BF16) hipLaunchKernelGGL(k_decode<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, d_ids, n_ids);
-    else if (fmt == ZC_FMT_FP8_E4M3) hipLaunchKernelGGL(k_decode<ZC_FMT_FP8_E4M3>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, d_ids, n_ids);
-    else hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_MX>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, d_ids, n_ids);
+    if (fmt == ZC_FMT_BF16) hipLaunchKernelGGL(k_decode<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot, d_ids, n_ids);
+    else if (fmt == ZC_FMT_FP8_E4M3) hipLaunchKernelGGL(k_decode<ZC_FMT_FP8_E4M3>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot, d_ids, n_ids);
+    else hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_MX>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot, d_ids, n_ids);
     return (int)hipGetLastError();
 }
 

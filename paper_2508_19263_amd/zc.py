@@ -57,6 +57,12 @@ class Tensor(C.Structure):
                 ("out_bytes", C.c_uint64), ("info", Info)]
 
 
+class BatchPlan(C.Structure):
+    _fields_ = [("format", C.c_uint32), ("streams", C.c_uint32), ("n_tensors", C.c_uint32), ("n_fast_work", C.c_uint32),
+                ("n_work", C.c_uint32), ("fast_exp_kind", C.c_uint32), ("fast_sm_kind", C.c_uint32), ("xor_delta", C.c_uint32),
+                ("fast_work_offset", C.c_uint64), ("work_offset", C.c_uint64)]
+
+
 class ZcError(RuntimeError):
     def __init__(self, status, what):
         self.status = status
@@ -93,9 +99,9 @@ def lib():
         L.zc_decompress_batch.restype = C.c_int
         L.zc_decompress_batch.argtypes = [C.POINTER(Tensor), u32, vp, u64, vp]
         L.zc_decompress_batch_plan.restype = C.c_int
-        L.zc_decompress_batch_plan.argtypes = [C.POINTER(Tensor), u32, vp, u64, C.POINTER(u32), vp]
+        L.zc_decompress_batch_plan.argtypes = [C.POINTER(Tensor), u32, vp, u64, C.POINTER(BatchPlan), vp]
         L.zc_decompress_batch_run.restype = C.c_int
-        L.zc_decompress_batch_run.argtypes = [u32, u32, u32, u32, vp, vp]
+        L.zc_decompress_batch_run.argtypes = [C.POINTER(BatchPlan), vp, vp]
         L.zc_stats.restype = C.c_int
         L.zc_stats.argtypes = [vp, u64, C.POINTER(Params), vp, vp, C.POINTER(StatsOut), vp, u64, vp]
         L.zc_build_code.restype = C.c_int
@@ -274,17 +280,15 @@ class Batch:
         return self.out
 
     def plan_decompress(self):
-        """Upload descriptors and work list (blocking); returns the number of work items."""
+        """Upload descriptors and work lists (blocking); returns the plan."""
         if self.out is None:
             self.prepare_outputs()
-        n_work = C.c_uint32(0)
-        _check(lib().zc_decompress_batch_plan(self.arr, self.n, _ptr(self.ws), self.ws.numel(), C.byref(n_work), _stream()),
+        self.plan = BatchPlan()
+        _check(lib().zc_decompress_batch_plan(self.arr, self.n, _ptr(self.ws), self.ws.numel(), C.byref(self.plan), _stream()),
                "zc_decompress_batch_plan")
-        self.n_work = n_work.value
-        return self.n_work
+        return self.plan
 
     def run_decompress(self):
-        """Enqueue the decode kernel on the plan left in the workspace by plan_decompress()."""
-        _check(lib().zc_decompress_batch_run(self.p.format, int(self.arr[0].info.streams), self.n, self.n_work, _ptr(self.ws), _stream()),
-               "zc_decompress_batch_run")
+        """Enqueue the decode kernels on the plan left in the workspace by plan_decompress()."""
+        _check(lib().zc_decompress_batch_run(C.byref(self.plan), _ptr(self.ws), _stream()), "zc_decompress_batch_run")
         return self.out

@@ -270,3 +270,24 @@ def test_determinism_and_poisoned_buffers():
         if ref is None:
             ref = comp.clone()
         assert torch.equal(comp, ref)
+
+
+def test_fp8_fast_path_variants():
+    # the specialised FP8 kernel: single / pair lookups x flat / raw sign+mantissa x delta,
+    # whole chunks through it and a short last chunk through the generic kernel
+    n = 37 * 65536 + 12345
+    x = wl.fp8_weight(n, seed=61)
+    y = wl.fp8_weight(n, seed=62)
+    for L in (8, 7, 6, 5):
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            check_case(zc.FMT_FP8_E4M3, n, 65536, 64, policy, L=(L, 0, 0), data=(x, None), tag="fast-L%d" % L)
+            check_case(zc.FMT_FP8_E4M3, n, 65536, 64, policy, L=(L, 0, 0), data=(x, None), base=y, tag="fast-xor-L%d" % L)
+    # worst case for the window: every code 8 bits long for long stretches (16 equiprobable
+    # exponents would be flat, so skew the histogram just enough to get lengths up to 8)
+    rng = np.random.default_rng(63)
+    pr = np.array([2.0 ** -min(k + 1, 8) for k in range(16)]); pr /= pr.sum()
+    e = rng.choice(16, size=n, p=pr).astype(np.uint8)
+    e[1000:200000] = 15                       # long runs of the rarest symbols
+    e[300000:400000] = np.where(rng.random(100000) < 0.5, 14, 15)
+    z = torch.from_numpy(((e << 3) | rng.integers(0, 8, n).astype(np.uint8)).astype(np.uint8))
+    want, _, _ = check_case(zc.FMT_FP8_E4M3, n, 65536, 64, L=(8, 0, 0), data=(z, None), tag="fast-worst")
