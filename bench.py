@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--policy", choices=["huff_all", "auto"], default="huff_all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-only", action="store_true", help="timed steps run only the decode kernel (for profiling)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the timed steps run one plain elementwise kernel that reads 1 GiB and writes 1 GiB "
+                         "(scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (every chunk and tensor is "
@@ -96,6 +99,13 @@ def main():
     mean = lambda v: sum(v) / len(v)
     ms_decomp = mean(ms_plan) + mean(ms_kern)
     ms_step = wall * 1000.0 / args.steps
+
+    if args.copy_calibration:
+        cal = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+        cal_out = torch.empty_like(cal)
+        torch.add(cal, 1, out=cal_out)
+        torch.cuda.synchronize()
+        del cal, cal_out
 
     # bit-exact round trip of the whole set
     ok = all(torch.equal(o[:n], s) for o, s, n in zip(batch.out, srcs, counts))

@@ -61,6 +61,33 @@ __device__ __forceinline__ uint32_t canon_decode(const Canon16 &Cn, uint32_t bit
 
 }  // namespace
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+constexpr uint32_t kRingWords = 1024, kRingSegment = 256;
+
+// raw buffer resource over [p, p + bytes): a load whose vector offset is past the end returns 0
+// and such a store is dropped by the hardware (the scalar offset operand is NOT range checked:
+// it is used only for offsets that are in range by construction), so a damaged stream cannot
+// make a lane touch memory outside its chunk's streams
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+// (x & 0xFF) * 4 in one instruction (byte select on the shift operand)
+__device__ __forceinline__ uint32_t byte0_times4(uint32_t x, uint32_t two)
+{
+    uint32_t r;
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(two), "v"(x));
+    return r;
+}
+
+// readfirstlane returns a signed int: go through uint32_t so that nothing is sign-extended
+__device__ __forceinline__ uint32_t uniform32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ uint64_t uniform64(uint64_t v)
+{
+    return ((uint64_t)uniform32((uint32_t)(v >> 32)) << 32) | (uint64_t)uniform32((uint32_t)v);
+}
+
 // EK: 0 = one symbol per lookup (codes <= 8 bits, 256 entries), 1 = two symbols per lookup
 //     (codes <= 6 bits, 4096 entries).  MK: 0 = flat 4-bit code, 1 = raw.  XOR: delta container.
 template <int EK, int MK, bool XOR>
@@ -68,6 +95,9 @@ __global__ __launch_bounds__(256) void k_decode_fp8(const TensorDev *descs, cons
 {
     constexpr uint32_t kEntries = EK ? 4096u : 256u;
     __shared__ uint32_t lut[kEntries];
+    // per wavefront: the next 1024 words of its exponent stream, refilled 256 words at a time
+    // one output row ahead of use, so that a refill step never waits on global memory
+    __shared__ __attribute__((aligned(16))) uint32_t ring[kWavesPerGroup][kRingWords];
     __shared__ Canon16 canon;
     __shared__ TensorDev dsh;
     WorkItem it;
@@ -91,89 +121,110 @@ __global__ __launch_bounds__(256) void k_decode_fp8(const TensorDev *descs, cons
     __syncthreads();
 
     const uint32_t lane = threadIdx.x & 63;
-    const uint32_t chunk = __builtin_amdgcn_readfirstlane(it.first + (threadIdx.x >> 6));
-    const uint32_t E = d.chunk_bytes;                       // one element per byte
-    const uint32_t n_full = (uint32_t)(d.n_elems / E);
+    const uint32_t chunk = uniform32(it.first + (threadIdx.x >> 6));
+    const uint32_t E = uniform32(d.chunk_bytes);     // one element per byte
+    const uint32_t n_full = (uint32_t)(uniform64(d.n_elems) / E);
     if (chunk >= n_full) return;                            // partial or absent chunk: not ours
-    const uint32_t *index0 = reinterpret_cast<const uint32_t *>(d.comp + d.index_off[0]);
-    const uint32_t *index1 = reinterpret_cast<const uint32_t *>(d.comp + d.index_off[1]);
-    const uint64_t a0 = index0[chunk], b0 = index0[chunk + 1], a1 = index1[chunk], b1 = index1[chunk + 1];
+    const uint8_t *comp = reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.comp));
+    const uint64_t payload = uniform64(d.payload_off), total = uniform64(d.total_bytes);
+    const uint32_t *index0 = reinterpret_cast<const uint32_t *>(comp + uniform32(d.index_off[0]));
+    const uint32_t *index1 = reinterpret_cast<const uint32_t *>(comp + uniform32(d.index_off[1]));
+    const uint64_t a0 = uniform32(index0[chunk]), b0 = uniform32(index0[chunk + 1]);
+    const uint64_t a1 = uniform32(index1[chunk]), b1 = uniform32(index1[chunk + 1]);
     const uint32_t rows = E / (16 * 64);
     // a stream that does not lie inside the container, or a sign+mantissa stream shorter than
     // its fixed size, means a damaged index: leave the chunk alone rather than read outside
-    if (a0 > b0 || a1 > b1 || d.payload_off + 16 * b1 > d.total_bytes || d.payload_off + 16 * b0 > d.total_bytes) return;
-    if ((b1 - a1) * 16 < (uint64_t)E / 2) return;
-    const uint32_t *es = reinterpret_cast<const uint32_t *>(d.comp + d.payload_off + 16 * a0);
-    const uint32_t *ms = reinterpret_cast<const uint32_t *>(d.comp + d.payload_off + 16 * a1);
-    const uint32_t e_words = (uint32_t)(b0 - a0) * 4;
-    uint4 *dst = reinterpret_cast<uint4 *>(d.dst + (uint64_t)chunk * E);
-    const uint4 *base = XOR ? reinterpret_cast<const uint4 *>(d.base + (uint64_t)chunk * E) : nullptr;
+    if (a0 > b0 || a1 > b1 || payload + 16 * b1 > total || payload + 16 * b0 > total) return;
+    if ((b1 - a1) * 16 < (uint64_t)E / 2 || (b0 - a0) * 16 > 0x7FFFFFFFull) return;
+    const __amdgpu_buffer_rsrc_t es = make_rsrc(comp + payload + 16 * a0, (uint32_t)((b0 - a0) * 16));
+    const __amdgpu_buffer_rsrc_t ms = make_rsrc(comp + payload + 16 * a1, E / 2);
+    const __amdgpu_buffer_rsrc_t ds = make_rsrc(reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.dst)) + (uint64_t)chunk * E, E);
+    const __amdgpu_buffer_rsrc_t bs = make_rsrc(XOR ? reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.base)) + (uint64_t)chunk * E : comp, XOR ? E : 0);
 
-    uint32_t lo = 0, hi = 0, c = 64, wpos = 0;
-    constexpr uint32_t kMask = kEntries - 1;
+    // Ring invariant at the top of every row: words [wbase, wbase + 1024) of the stream are in the
+    // ring, except the newest 256 while their load is in flight; a row takes at most 4 * 64 words
+    // and wpos - wbase < 512, so every word a row can ask for is already there.
+    const uint32_t wave = threadIdx.x >> 6;
+    char *const ring_bytes = reinterpret_cast<char *>(&ring[wave][0]);
+#pragma unroll
+    for (uint32_t q = 0; q < kRingWords / kRingSegment; q++) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(es, (int)(lane * 16 + q * kRingSegment * 4), 0, 0);
+        *reinterpret_cast<u32x4 *>(ring_bytes + q * kRingSegment * 4 + lane * 16) = v;
+    }
+    // step 0 of the stream: every lane takes its first word
+    uint64_t W = (uint64_t)(*reinterpret_cast<const uint32_t *>(ring_bytes + lane * 4)) << 32;
+    uint32_t c = 32, wpos = 64, wbase = 0;
+    bool pending = false;
+    u32x4 pv = {0, 0, 0, 0};
+    uint32_t pslot = 0;
+    const uint32_t two = 2;
+    const char *lut_bytes = reinterpret_cast<const char *>(lut);
     for (uint32_t row = 0; row < rows; row++) {
-        // ---- sign+mantissa: 16 nibbles -> bytes 0000smmm, four per word
+        if (pending) {                                   // the segment asked for one row ago has arrived
+            *reinterpret_cast<u32x4 *>(ring_bytes + pslot * 4 + lane * 16) = pv;
+            pending = false;
+        }
+        if (wpos - wbase >= kRingSegment) {              // oldest segment used up: fetch the one that replaces it
+            pv = __builtin_amdgcn_raw_buffer_load_b128(es, (int)(lane * 16 + (wbase + kRingWords) * 4), 0, 0);
+            pslot = wbase & (kRingWords - 1);
+            wbase += kRingSegment;
+            pending = true;
+        }
+        // ---- sign+mantissa: 16 nibbles -> bytes s0000mmm, four per word
         uint32_t m[4];
         if (MK == 0) {
             // flat code: one word per 8 symbols, rows of 64 words; code bits are MSB first in an
             // LSB-first string, so a bit reversal gives natural nibbles in reverse symbol order
 #pragma unroll
             for (int h = 0; h < 2; h++) {
-                const uint32_t w = __brev(ms[(row * 2 + h) * 64 + lane]);
-                const uint32_t A = w & 0x0F0F0F0Fu;            // symbols 7,5,3,1 in bytes 0..3
-                const uint32_t B = (w >> 4) & 0x0F0F0F0Fu;     // symbols 6,4,2,0
+                const uint32_t w = __brev(__builtin_amdgcn_raw_buffer_load_b32(ms, (int)(lane * 4), (int)((row * 2 + h) * 256), 0));
+                const uint32_t A = ((w << 4) & 0x80808080u) | (w & 0x07070707u);          // symbols 7,5,3,1 in bytes 0..3
+                const uint32_t B = (w & 0x80808080u) | ((w >> 4) & 0x07070707u);          // symbols 6,4,2,0
                 m[2 * h] = perm(A, B, 0x06020703u);            // bytes: B3 A3 B2 A2 -> symbols 0,1,2,3
                 m[2 * h + 1] = perm(A, B, 0x04000501u);        // bytes: B1 A1 B0 A0 -> symbols 4,5,6,7
             }
         } else {
-            const uint2 w2 = reinterpret_cast<const uint2 *>(ms)[row * 64 + lane];
-            const uint32_t w[2] = {w2.x, w2.y};
 #pragma unroll
             for (int h = 0; h < 2; h++) {
-                const uint32_t A = w[h] & 0x0F0F0F0Fu;         // symbols 0,2,4,6
-                const uint32_t B = (w[h] >> 4) & 0x0F0F0F0Fu;  // symbols 1,3,5,7
+                const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(ms, (int)(lane * 8 + h * 4), (int)(row * 512), 0);
+                const uint32_t A = ((w << 4) & 0x80808080u) | (w & 0x07070707u);          // symbols 0,2,4,6
+                const uint32_t B = (w & 0x80808080u) | ((w >> 4) & 0x07070707u);          // symbols 1,3,5,7
                 m[2 * h] = perm(A, B, 0x01050004u);            // bytes: A0 B0 A1 B1
                 m[2 * h + 1] = perm(A, B, 0x03070206u);        // bytes: A2 B2 A3 B3
             }
         }
-        // ---- exponent: 4 groups of 4 symbols
-        uint32_t ex[4];
-#pragma unroll
-        for (int g = 0; g < 4; g++) {
-            const bool need = c >= 32;
-            const uint64_t bm = __ballot(need);
-            if (need) {
-                const uint32_t pos = wpos + prefix_count64(bm);
-                const uint32_t w = pos < e_words ? es[pos] : 0u;
-                lo = hi; hi = w; c -= 32;
-            }
-            wpos += (uint32_t)__popcll(bm);
-            uint32_t x = (uint32_t)((((uint64_t)hi << 32) | lo) >> c);
-            if (EK == 0) {
-                const uint32_t t0 = lut[x & kMask]; x >>= (t0 & 31u);
-                const uint32_t t1 = lut[x & kMask]; x >>= (t1 & 31u);
-                const uint32_t t2 = lut[x & kMask]; x >>= (t2 & 31u);
-                const uint32_t t3 = lut[x & kMask];
-                c += (t0 + t1 + t2 + t3) & 0xFFu;
-                // byte 1 of each entry -> bytes 0..3 of the output word
-                const uint32_t p01 = perm(t1, t0, 0x0C0C0501u);   // [t0.b1, t1.b1, 0, 0]
-                const uint32_t p23 = perm(t3, t2, 0x05010C0Cu);   // [0, 0, t2.b1, t3.b1]
-                ex[g] = p01 | p23;
-            } else {
-                const uint32_t t0 = lut[x & kMask]; x >>= (t0 & 31u);
-                const uint32_t t1 = lut[x & kMask];
-                c += (t0 + t1) & 0xFFu;
-                ex[g] = perm(t1, t0, 0x06050201u);                // [t0.b1, t0.b2, t1.b1, t1.b2]
-            }
-        }
-        // ---- merge: byte = s eeee mmm
-        uint4 v;
+        // ---- exponent: 4 groups of 4 symbols, each followed by the refill step of the next group
         uint32_t o[4];
 #pragma unroll
-        for (int q = 0; q < 4; q++) o[q] = ex[q] | (m[q] & 0x07070707u) | ((m[q] & 0x08080808u) << 4);
-        v = make_uint4(o[0], o[1], o[2], o[3]);
-        if (XOR) { const uint4 b = base[row * 64 + lane]; v.x ^= b.x; v.y ^= b.y; v.z ^= b.z; v.w ^= b.w; }
-        dst[row * 64 + lane] = v;
+        for (int g = 0; g < 4; g++) {
+            uint32_t x = (uint32_t)(W >> c);
+            if (EK == 0) {
+                const uint32_t t0 = *reinterpret_cast<const uint32_t *>(lut_bytes + byte0_times4(x, two)); x >>= (t0 & 31u);
+                const uint32_t t1 = *reinterpret_cast<const uint32_t *>(lut_bytes + byte0_times4(x, two)); x >>= (t1 & 31u);
+                const uint32_t t2 = *reinterpret_cast<const uint32_t *>(lut_bytes + byte0_times4(x, two)); x >>= (t2 & 31u);
+                const uint32_t t3 = *reinterpret_cast<const uint32_t *>(lut_bytes + byte0_times4(x, two));
+                c += (t0 + t1 + t2 + t3) & 0xFFu;
+                // byte 1 of each entry -> bytes 0..3 of the output word
+                o[g] = perm(t1, t0, 0x0C0C0501u) | perm(t3, t2, 0x05010C0Cu) | m[g];
+            } else {
+                x <<= 2;                                           // 30 bits left: two lookups need 24
+                const uint32_t t0 = *reinterpret_cast<const uint32_t *>(lut_bytes + (x & 0x3FFCu)); x >>= (t0 & 31u);
+                const uint32_t t1 = *reinterpret_cast<const uint32_t *>(lut_bytes + (x & 0x3FFCu));
+                c += (t0 + t1) & 0xFFu;
+                o[g] = perm(t1, t0, 0x06050201u) | m[g];          // [t0.b1, t0.b2, t1.b1, t1.b2]
+            }
+            // refill step: lanes whose low word is used up take the next word of the stream, in lane order
+            const bool need = c >= 32;
+            const uint64_t bm = __ballot(need);
+            const uint32_t w = *reinterpret_cast<const uint32_t *>(ring_bytes + ((prefix_count64(bm) * 4 + wpos * 4) & (kRingWords * 4 - 1)));
+            W = need ? ((W >> 32) | ((uint64_t)w << 32)) : W;
+            c = need ? c - 32 : c;
+            wpos += (uint32_t)__popcll(bm);
+        }
+        // ---- byte = s eeee mmm
+        u32x4 v = {o[0], o[1], o[2], o[3]};
+        if (XOR) v ^= __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)(row * 1024), 0);
+        __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
     }
 }
 
