@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per decode launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each
 # scaled by what the same counter reads for a plain copy of known size); None = not measured
-MEASURED_TRAFFIC_BYTES = {"fp8_e4m3_weight_set_8b_x32": None}
+MEASURED_TRAFFIC_BYTES = {"fp8_e4m3_weight_set_8b_x32": 12965000000}
 
 
 def main():
