@@ -291,3 +291,32 @@ def test_fp8_fast_path_variants():
     e[300000:400000] = np.where(rng.random(100000) < 0.5, 14, 15)
     z = torch.from_numpy(((e << 3) | rng.integers(0, 8, n).astype(np.uint8)).astype(np.uint8))
     want, _, _ = check_case(zc.FMT_FP8_E4M3, n, 65536, 64, L=(8, 0, 0), data=(z, None), tag="fast-worst")
+
+
+def test_config2_full_size_tensors_in_the_benchmark_launch_configuration():
+    # Three tensors of config 2 at their real sizes (k: 4 MiB, q: 16 MiB, gate: 56 MiB), generated
+    # on the GPU exactly as bench.py does, compressed and decoded as one batch (the launch
+    # configuration bench.py times).  The oracle compresses the same bytes: containers must be
+    # identical; then sampled chunks of the oracle's container are decoded one by one on the CPU
+    # and compared with the GPU output.
+    shapes = [("k", 4096 * 1024), ("q", 4096 * 4096), ("gate", 4096 * 14336)]
+    dev_srcs = [wl.fp8_weight(n, device=DEV, seed=2000 + i) for i, (_, n) in enumerate(shapes)]
+    counts = [n for _, n in shapes]
+    p = zc.params(zc.FMT_FP8_E4M3, 262144, streams=64)
+    b = zc.Batch(dev_srcs, counts, p)
+    sizes = b.compress()
+    outs = b.decompress()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(7)
+    for i, (name, n) in enumerate(shapes):
+        print("full-size", name, n, flush=True)
+        host = dev_srcs[i].cpu().numpy()
+        want = o.compress(host, n, o.params(o.FP8_E4M3, 262144, streams=64))
+        got = b.container(i).cpu().numpy()
+        assert sizes[i] == len(want) and np.array_equal(got, want), name
+        gpu_out = outs[i].cpu().numpy()
+        assert np.array_equal(gpu_out[:n], host)
+        n_chunks = n // 262144
+        for c in sorted(set([0, n_chunks - 1] + rng.integers(0, n_chunks, 4).tolist())):
+            rc, chunk, _ = o.decompress_chunk(want, c, 262144)
+            assert rc == o.OK and np.array_equal(chunk, gpu_out[c * 262144:(c + 1) * 262144]), (name, c)
