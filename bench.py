@@ -28,6 +28,74 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 MEASURED_TRAFFIC_BYTES = {"fp8_e4m3_weight_set_8b_x32": 12965000000}
 
 
+def _time_ms(torch, fn, reps=5):
+    fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) for a, b in ev)
+    return t[len(t) // 2]
+
+
+def other_workloads(torch, wl, zc, dev):
+    """Configs 1, 3, 4, 5 at full size: ratios, compress and decompress GB/s (median of 5)."""
+    out = {}
+
+    def run(name, fmt, srcs, counts, chunk, streams, bases=None, scales=None, limit=(0, 0, 0), ids=None):
+        p = zc.params(fmt, chunk, limit, streams)
+        b = zc.Batch(srcs, counts, p, xor_bases=bases, scales=scales)
+        sizes = b.compress()
+        b.plan_decompress()
+        raw = sum(s.numel() * s.element_size() for s in srcs) + (sum(s.numel() for s in scales) if scales else 0)
+        t_c = _time_ms(torch, b.compress)
+        b.plan_decompress()
+        t_d = _time_ms(torch, b.run_decompress)
+        ok = all(torch.equal(o.view(torch.uint8)[:s.numel() * s.element_size()], s.view(torch.uint8).reshape(-1)) for o, s in zip(b.out, srcs))
+        st = zc.stats(srcs[0], counts[0], p, xor_base=bases[0] if bases else None, scales=scales[0] if scales else None)
+        r = {"uncompressed_bytes": raw, "compressed_bytes": sum(sizes), "ratio_total": sum(sizes) / raw,
+             "ratio_fields_payload": [st.field[f].ratio_payload for f in range(st.n_fields)],
+             "compress_ms": t_c, "compress_GBps": raw / t_c / 1e6, "decompress_ms": t_d, "decompress_GBps": raw / t_d / 1e6,
+             "decompress_traffic_frac_of_hbm_peak": (raw + sum(sizes) + (raw if bases else 0)) / t_d / 1e6 / HBM_PEAK_GBPS,
+             "round_trip_bit_exact": bool(ok)}
+        if ids is not None:
+            # random-access decode of a page sample of every tensor into dense buffers
+            infos = [b.arr[i].info for i in range(b.n)]
+            outs = [torch.empty(ids[i].numel() * chunk, dtype=torch.uint8, device=dev) for i in range(b.n)]
+            def pages():
+                for i in range(b.n):
+                    zc.decompress_chunks(b.container(i), infos[i], ids[i], out=outs[i])
+            t_p = _time_ms(torch, pages)
+            nb = sum(o.numel() for o in outs)
+            okp = all(torch.equal(outs[i].view(-1, chunk), srcs[i].view(-1, chunk)[ids[i].long()]) for i in range(b.n))
+            r.update({"page_decode_ms": t_p, "page_decode_GBps": nb / t_p / 1e6, "pages": nb // chunk, "page_decode_bit_exact": bool(okp)})
+        out[name] = r
+        del b
+        torch.cuda.empty_cache()
+
+    x = wl.bf16_weight(1 << 20, device=dev, seed=0)
+    run("c1_bf16_1M", zc.FMT_BF16, [x], [1 << 20], 65536, 64, limit=(16, 16, 0))
+    mats = [wl.mxfp4_weight(8192, 28672, device=dev, seed=300 + i) for i in range(3)]
+    run("c3_mxfp4_70b_mlp", zc.FMT_FP4_E2M1_MX, [m[0] for m in mats], [8192 * 28672] * 3, 262144, 64, scales=[m[1] for m in mats])
+    del mats
+    pairs = [wl.bf16_checkpoint_pair(4096 * 16384, device=dev, seed=400 + i) for i in range(16)]
+    w0, w1 = [q[0] for q in pairs], [q[1] for q in pairs]
+    run("c4_bf16_checkpoint_w1", zc.FMT_BF16, w1, [4096 * 16384] * 16, 262144, 64, limit=(16, 16, 0))
+    run("c4_bf16_checkpoint_xor_delta", zc.FMT_BF16, w1, [4096 * 16384] * 16, 262144, 64, bases=w0, limit=(16, 16, 0))
+    del pairs, w0, w1
+    kv = []
+    for layer in range(32):
+        k, v = wl.fp8_kv_pair(device=dev, seed=500 + layer)
+        kv += [k.reshape(-1), v.reshape(-1)]
+    n_pages = kv[0].numel() // 2048
+    ids = [wl.page_sample(n_pages, 0.25, device=dev, seed=600 + i) for i in range(len(kv))]
+    run("c5_fp8_kv_pages", zc.FMT_FP8_E4M3, kv, [t.numel() for t in kv], 2048, 8, ids=ids)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -39,6 +107,8 @@ def main():
     ap.add_argument("--policy", choices=["huff_all", "auto"], default="huff_all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-only", action="store_true", help="timed steps run only the decode kernel (for profiling)")
+    ap.add_argument("--other-workloads", action="store_true",
+                    help="also time configs 1, 3, 4 and 5 (reported under 'other_workloads' in the same JSON line)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed steps run one plain elementwise kernel that reads 1 GiB and writes 1 GiB "
                          "(scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -147,6 +217,9 @@ def main():
                      "unit": "GB/s", "frac": algo_bytes / kern_s / 1e9 / HBM_PEAK_GBPS,
                      "algorithmic_bytes_per_launch": algo_bytes, "traffic": MEASURED_TRAFFIC_BYTES.get(workload)},
     }
+
+    if args.other_workloads:
+        result["other_workloads"] = other_workloads(torch, wl, zc, dev)
 
     if not args.no_cpu_baseline:
         # the oracle as it stands, single thread, on a bounded sample of the same workload

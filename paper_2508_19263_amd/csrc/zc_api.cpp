@@ -218,6 +218,14 @@ TensorDev make_desc(const zc_info &info)
         d.table_off[f] = (uint32_t)info.table_offset[f]; d.index_off[f] = (uint32_t)info.index_offset[f];
         d.mode[f] = info.mode[f]; d.lmax[f] = info.max_len[f]; d.konst[f] = info.const_symbol[f];
         d.period[f] = (uint8_t)refill_period(run_len(info.format, (int)f), info.max_len[f]);
+        // how the specialised decoders read the field: 0 table, 1 flat code, 2 raw, 3 constant
+        uint8_t kind = 3;
+        if (info.mode[f] == ZC_MODE_RAW) kind = 2;
+        else if (info.mode[f] == ZC_MODE_HUFF) {
+            kind = 1;       // flat: every symbol present with length sym_bits, so the canonical code is the symbol itself
+            for (uint32_t v = 0; v < (1u << info.sym_bits[f]); v++) if (info.code_len[f][v] != info.sym_bits[f]) kind = 0;
+        }
+        d.kind[f] = kind;
     }
     return d;
 }
@@ -355,6 +363,20 @@ FastKind fast_kind(const zc_info &info)
     return k;
 }
 
+// Can the 64-lane full-chunk kernel decode this container?  Returns the number of LDS rings
+// it needs per wavefront (1 or 2), or 0 if the container has to go through the generic kernel.
+uint32_t s64_rings(const zc_info &info)
+{
+    if (info.streams != 64 || info.chunk_bytes % (info.format == ZC_FMT_FP4_E2M1_MX ? 16384u : 1024u)) return 0;
+    uint32_t huff = 0;
+    const TensorDev d = make_desc(info);
+    for (uint32_t f = 0; f < info.n_fields; f++) {
+        if (info.mode[f] == ZC_MODE_EMPTY) return 0;
+        if (f < 2 && d.kind[f] == 0) huff++;
+    }
+    return huff < 1 ? 1 : huff;
+}
+
 zc_status parse_info(const uint8_t *c, uint64_t have, uint64_t comp_bytes, zc_info *out)
 {
     if (have < kHeaderBytes || comp_bytes < kHeaderBytes) return ZC_ERR_CORRUPT;
@@ -435,10 +457,13 @@ zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *
     const uint32_t cpi = chunks_per_work_item(info.streams);
     const FastKind fk = fast_kind(info);
     uint32_t first_slot = 0;
-    if (fk.ok && !by_ids) {
-        // full chunks through the specialised kernel, a short last chunk through the generic one
+    const uint32_t rings = s64_rings(info);
+    if ((fk.ok || rings) && !by_ids) {
+        // full chunks through a specialised kernel, a short last chunk through the generic one
         const uint32_t n_full = (uint32_t)(info.n_elems / ((uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(info.format)));
-        LAUNCH_TRY(launch_decode_fp8_fast(fk.exp_kind, fk.sm_kind, info.xor_delta != 0, nullptr, nullptr, (n_full + kWavesPerGroup - 1) / kWavesPerGroup, &d, stream));
+        const uint32_t n_fast = (n_full + kWavesPerGroup - 1) / kWavesPerGroup;
+        if (fk.ok) LAUNCH_TRY(launch_decode_fp8_fast(fk.exp_kind, fk.sm_kind, info.xor_delta != 0, nullptr, nullptr, n_fast, &d, stream));
+        else LAUNCH_TRY(launch_decode_s64(info.format, rings, info.xor_delta != 0, nullptr, nullptr, n_fast, &d, stream));
         first_slot = n_full;
     }
     if (first_slot < slots) {
@@ -602,6 +627,19 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
         const FastKind k = fast_kind(tensors[t].info);
         if (!k.ok || k.exp_kind != fk.exp_kind || k.sm_kind != fk.sm_kind || tensors[t].info.xor_delta != tensors[0].info.xor_delta) fk.ok = false;
     }
+    // otherwise the 64-lane full-chunk kernel, when every tensor qualifies
+    uint32_t rings = 0;
+    if (!fk.ok) {
+        rings = 2;
+        uint32_t most = 1;
+        for (uint32_t t = 0; t < n_tensors && rings; t++) {
+            const uint32_t r = s64_rings(tensors[t].info);
+            if (r == 0 || tensors[t].info.xor_delta != tensors[0].info.xor_delta) rings = 0;
+            else if (r > most) most = r;
+        }
+        if (rings) rings = most;
+    }
+    const bool fast = fk.ok || rings != 0;
     std::vector<TensorDev> descs(n_tensors);
     std::vector<WorkItem> fast_work, work;
     for (uint32_t t = 0; t < n_tensors; t++) {
@@ -616,7 +654,7 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
         descs[t].comp = (uint8_t *)x.d_comp; descs[t].dst = (uint8_t *)x.d_dst; descs[t].scales_out = (uint8_t *)x.d_scales_out;
         descs[t].base = info.xor_delta ? (const uint8_t *)x.d_xor_base : nullptr;
         uint32_t first_generic = 0;
-        if (fk.ok) {
+        if (fast) {
             const uint32_t n_full = (uint32_t)(info.n_elems / ((uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(fmt)));
             for (uint32_t c = 0; c < n_full; c += kWavesPerGroup) fast_work.push_back({t, c});
             first_generic = n_full;
@@ -635,6 +673,7 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
     plan->format = fmt; plan->streams = S; plan->n_tensors = n_tensors;
     plan->n_fast_work = (uint32_t)fast_work.size(); plan->n_work = (uint32_t)work.size();
     plan->fast_exp_kind = (uint32_t)fk.exp_kind; plan->fast_sm_kind = (uint32_t)fk.sm_kind; plan->xor_delta = tensors[0].info.xor_delta;
+    plan->fast_kernel = fk.ok ? 1u : (rings ? 2u : 0u); plan->n_rings = rings;
     plan->fast_work_offset = descs_bytes; plan->work_offset = descs_bytes + fast_bytes;
     return ZC_OK;
 }
@@ -645,9 +684,13 @@ zc_status zc_decompress_batch_run(const zc_batch_plan *plan, const void *d_ws, v
     if (plan->n_tensors == 0 || (plan->n_work == 0 && plan->n_fast_work == 0)) return ZC_OK;
     if (!d_ws || !elem_bits(plan->format) || plan->streams == 0 || plan->streams > 64 || (plan->streams & (plan->streams - 1))) return ZC_ERR_INVALID_ARG;
     const uint8_t *ws = (const uint8_t *)d_ws;
-    if (plan->n_fast_work)
+    if (plan->n_fast_work && plan->fast_kernel == 1)
         LAUNCH_TRY(launch_decode_fp8_fast((int)plan->fast_exp_kind, (int)plan->fast_sm_kind, plan->xor_delta != 0, (const TensorDev *)ws,
                                           (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, stream));
+    else if (plan->n_fast_work && plan->fast_kernel == 2)
+        LAUNCH_TRY(launch_decode_s64(plan->format, plan->n_rings, plan->xor_delta != 0, (const TensorDev *)ws,
+                                     (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, stream));
+    else if (plan->n_fast_work) return ZC_ERR_INVALID_ARG;
     if (plan->n_work)
         LAUNCH_TRY(launch_decode(plan->format, (const TensorDev *)ws, (const WorkItem *)(ws + plan->work_offset), plan->n_work,
                                  chunks_per_work_item(plan->streams), nullptr, 0, nullptr, 0, stream));

@@ -14,7 +14,10 @@
 //   - merges both into the original bytes and stores 128 bits, contiguous across lanes.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "zc_internal.h"
+#include "zc_device.cuh"
 
 namespace zc {
 
@@ -73,11 +76,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint3
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
 }
 
-// (x & 0xFF) * 4 in one instruction (byte select on the shift operand)
-__device__ __forceinline__ uint32_t byte0_times4(uint32_t x, uint32_t two)
+// (x & 0xFF) << sh in one instruction (byte select on the shifted operand); sh lives in a VGPR
+__device__ __forceinline__ uint32_t byte0_shl(uint32_t x, uint32_t sh)
 {
     uint32_t r;
-    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(two), "v"(x));
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(sh), "v"(x));
     return r;
 }
 
@@ -94,7 +97,10 @@ template <int EK, int MK, bool XOR>
 __global__ __launch_bounds__(256) void k_decode_fp8(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single)
 {
     constexpr uint32_t kEntries = EK ? 4096u : 256u;
-    __shared__ uint32_t lut[kEntries];
+    // single lookups use 16-bit entries (length, exponent << 3): half as many distinct words
+    // per LDS bank as 32-bit entries, so fewer bank conflicts at data-dependent addresses
+    typedef typename std::conditional<EK == 0, uint16_t, uint32_t>::type entry_t;
+    __shared__ entry_t lut[kEntries];
     // per wavefront: the next 1024 words of its exponent stream, refilled 256 words at a time
     // one output row ahead of use, so that a refill step never waits on global memory
     __shared__ __attribute__((aligned(16))) uint32_t ring[kWavesPerGroup][kRingWords];
@@ -116,7 +122,7 @@ __global__ __launch_bounds__(256) void k_decode_fp8(const TensorDev *descs, cons
             const uint32_t e2 = canon_decode(canon, idx >> (e & 31u), lmax);
             entry = ((e & 31u) + (e2 & 31u)) | (((e >> 8) << 3) << 8) | (((e2 >> 8) << 3) << 16);
         }
-        lut[idx] = entry;
+        lut[idx] = (entry_t)entry;
     }
     __syncthreads();
 
@@ -157,7 +163,7 @@ __global__ __launch_bounds__(256) void k_decode_fp8(const TensorDev *descs, cons
     bool pending = false;
     u32x4 pv = {0, 0, 0, 0};
     uint32_t pslot = 0;
-    const uint32_t two = 2;
+    const uint32_t one = 1;
     const char *lut_bytes = reinterpret_cast<const char *>(lut);
     for (uint32_t row = 0; row < rows; row++) {
         if (pending) {                                   // the segment asked for one row ago has arrived
@@ -199,10 +205,10 @@ __global__ __launch_bounds__(256) void k_decode_fp8(const TensorDev *descs, cons
         for (int g = 0; g < 4; g++) {
             uint32_t x = (uint32_t)(W >> c);
             if (EK == 0) {
-                const uint32_t t0 = *reinterpret_cast<const uint32_t *>(lut_bytes + byte0_times4(x, two)); x >>= (t0 & 31u);
-                const uint32_t t1 = *reinterpret_cast<const uint32_t *>(lut_bytes + byte0_times4(x, two)); x >>= (t1 & 31u);
-                const uint32_t t2 = *reinterpret_cast<const uint32_t *>(lut_bytes + byte0_times4(x, two)); x >>= (t2 & 31u);
-                const uint32_t t3 = *reinterpret_cast<const uint32_t *>(lut_bytes + byte0_times4(x, two));
+                const uint32_t t0 = *reinterpret_cast<const uint16_t *>(lut_bytes + byte0_shl(x, one)); x >>= (t0 & 31u);
+                const uint32_t t1 = *reinterpret_cast<const uint16_t *>(lut_bytes + byte0_shl(x, one)); x >>= (t1 & 31u);
+                const uint32_t t2 = *reinterpret_cast<const uint16_t *>(lut_bytes + byte0_shl(x, one)); x >>= (t2 & 31u);
+                const uint32_t t3 = *reinterpret_cast<const uint16_t *>(lut_bytes + byte0_shl(x, one));
                 c += (t0 + t1 + t2 + t3) & 0xFFu;
                 // byte 1 of each entry -> bytes 0..3 of the output word
                 o[g] = perm(t1, t0, 0x0C0C0501u) | perm(t3, t2, 0x05010C0Cu) | m[g];
@@ -226,6 +232,244 @@ __global__ __launch_bounds__(256) void k_decode_fp8(const TensorDev *descs, cons
         if (XOR) v ^= __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)(row * 1024), 0);
         __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// Full chunks of any format with 64 lanes per chunk: the same machinery (buffer accesses,
+// LDS ring per Huffman-coded field, 16-byte stores) with table-driven decoding of any code
+// (11-bit lookup + canonical search for longer codes) and a per-field switch between
+// Huffman, flat code, raw and constant.
+
+enum FieldKind : uint32_t { KIND_HUFF = 0, KIND_FLAT = 1, KIND_RAW = 2, KIND_CONST = 3 };
+
+struct HuffStream {
+    uint64_t W;            // 64 stream bits, next unread bit = bit c
+    uint32_t c;
+    uint32_t wpos, wbase;  // words handed out so far; first word still in the ring
+    uint32_t pslot;
+    bool pending;
+    u32x4 pv;
+    char *ring;            // this wavefront's 1024-word ring in LDS
+    __amdgpu_buffer_rsrc_t rs;
+};
+
+__device__ __forceinline__ void huff_open(HuffStream &H, __amdgpu_buffer_rsrc_t rs, char *ring, uint32_t lane)
+{
+    H.rs = rs; H.ring = ring;
+#pragma unroll
+    for (uint32_t q = 0; q < kRingWords / kRingSegment; q++) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(lane * 16 + q * kRingSegment * 4), 0, 0);
+        *reinterpret_cast<u32x4 *>(ring + q * kRingSegment * 4 + lane * 16) = v;
+    }
+    H.W = (uint64_t)(*reinterpret_cast<const uint32_t *>(ring + lane * 4)) << 32;   // step 0: word `lane`
+    H.c = 32; H.wpos = 64; H.wbase = 0; H.pslot = 0; H.pending = false;
+    H.pv = u32x4{0, 0, 0, 0};
+}
+
+// call at least once per 4 refill steps (4 * 64 words <= one segment)
+__device__ __forceinline__ void huff_ring_service(HuffStream &H, uint32_t lane)
+{
+    if (H.pending) {
+        *reinterpret_cast<u32x4 *>(H.ring + H.pslot * 4 + lane * 16) = H.pv;
+        H.pending = false;
+    }
+    if (H.wpos - H.wbase >= kRingSegment) {
+        H.pv = __builtin_amdgcn_raw_buffer_load_b128(H.rs, (int)(lane * 16 + (H.wbase + kRingWords) * 4), 0, 0);
+        H.pslot = H.wbase & (kRingWords - 1);
+        H.wbase += kRingSegment;
+        H.pending = true;
+    }
+}
+
+__device__ __forceinline__ void huff_refill(HuffStream &H)
+{
+    const bool need = H.c >= 32;
+    const uint64_t bm = __ballot(need);
+    const uint32_t w = *reinterpret_cast<const uint32_t *>(H.ring + ((prefix_count64(bm) * 4 + H.wpos * 4) & (kRingWords * 4 - 1)));
+    H.W = need ? ((H.W >> 32) | ((uint64_t)w << 32)) : H.W;
+    H.c = need ? H.c - 32 : H.c;
+    H.wpos += (uint32_t)__popcll(bm);
+}
+
+// decode one run of G symbols (SB bits each) into P0 (symbols 0..64/SB-1) and P1 (the rest)
+template <int SB, int G, int R>
+__device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uint64_t &P0, uint64_t &P1, uint32_t lane)
+{
+    constexpr int PER64 = 64 / SB;
+    const uint32_t mask = T.mask;
+    const char *lut = reinterpret_cast<const char *>(T.lut);
+#pragma unroll
+    for (int g = 0; g < G / R; g++) {
+        if ((g & 3) == 0) huff_ring_service(H, lane);
+        uint32_t x = (uint32_t)(H.W >> H.c);
+        uint32_t used = 0;
+#pragma unroll
+        for (int j = 0; j < R; j++) {
+            const int jj = g * R + j;
+            uint32_t e = *reinterpret_cast<const uint16_t *>(lut + ((x & mask) << 1));
+            if (e == 0) e = dec_long(T, x);
+            x >>= (e & 31u);
+            used += e;
+            const uint64_t sym = (uint64_t)(e >> 8) << ((jj % PER64) * SB);
+            if (jj < PER64) P0 |= sym; else P1 |= sym;
+        }
+        H.c += used & 0xFFu;           // the low bytes hold the lengths; their sum is at most 32
+        huff_refill(H);
+    }
+}
+
+template <int SB, int G>
+__device__ __forceinline__ void huff_run(HuffStream &H, const FieldTab &T, uint32_t period, uint64_t &P0, uint64_t &P1, uint32_t lane)
+{
+    switch (period) {
+    case 2: huff_run_r<SB, G, 2>(H, T, P0, P1, lane); break;
+    case 4: huff_run_r<SB, G, 4>(H, T, P0, P1, lane); break;
+    case 8: huff_run_r<SB, G, 8>(H, T, P0, P1, lane); break;
+    case 16: if (G >= 16) huff_run_r<SB, G, (G >= 16 ? 16 : G)>(H, T, P0, P1, lane); break;
+    default: if (G >= 32) huff_run_r<SB, G, (G >= 32 ? 32 : G)>(H, T, P0, P1, lane); break;
+    }
+}
+
+// reverse the bit order inside every SB-bit group of a word (a flat code is the symbol value
+// written most significant bit first into an LSB-first string)
+template <int SB>
+__device__ __forceinline__ uint32_t reverse_in_groups(uint32_t w)
+{
+    if (SB == 8) return __builtin_amdgcn_perm(0, __brev(w), 0x00010203u);          // all bits reversed, then bytes back in order
+    if (SB == 4) { w = ((w >> 1) & 0x55555555u) | ((w & 0x55555555u) << 1); return ((w >> 2) & 0x33333333u) | ((w & 0x33333333u) << 2); }
+    return ((w >> 1) & 0x55555555u) | ((w & 0x55555555u) << 1);
+}
+
+// one field of one run when it is not table decoded.  words_per_run = G*SB/32.
+template <int SB, int G>
+__device__ __forceinline__ void plain_run(uint32_t kind, __amdgpu_buffer_rsrc_t rs, uint32_t row, uint32_t lane, uint64_t konst, uint64_t &P0, uint64_t &P1)
+{
+    constexpr int WPR = G * SB / 32;           // 2 for element fields, 4 for the scale field
+    uint32_t w[WPR];
+    if (kind == KIND_FLAT) {
+        // regular schedule: every lane takes one word per 32/SB symbols, rows of 64 words
+#pragma unroll
+        for (int h = 0; h < WPR; h++) w[h] = reverse_in_groups<SB>(__builtin_amdgcn_raw_buffer_load_b32(rs, (int)(((row * WPR + h) * 64 + lane) * 4), 0, 0));
+    } else if (kind == KIND_RAW) {
+#pragma unroll
+        for (int h = 0; h < WPR; h++) w[h] = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(((row * 64 + lane) * WPR + h) * 4), 0, 0);
+    } else {
+        P0 = konst; P1 = konst;
+        return;
+    }
+    P0 = (uint64_t)w[0] | ((uint64_t)w[1] << 32);
+    if (WPR == 4) P1 = (uint64_t)w[2] | ((uint64_t)w[3] << 32);
+}
+
+__device__ __forceinline__ bool stream_range(const TensorDev &d, const uint8_t *comp, int f, uint32_t chunk, uint64_t payload, uint64_t total,
+                                             const uint8_t *&ptr, uint32_t &bytes)
+{
+    ptr = comp; bytes = 0;
+    if (d.mode[f] != ZC_MODE_HUFF && d.mode[f] != ZC_MODE_RAW) return true;
+    const uint32_t *index = reinterpret_cast<const uint32_t *>(comp + uniform32(d.index_off[f]));
+    const uint64_t a = uniform32(index[chunk]), b = uniform32(index[chunk + 1]);
+    if (a > b || payload + 16 * b > total || (b - a) * 16 > 0x7FFFFFFFull) return false;
+    ptr = comp + payload + 16 * a;
+    bytes = (uint32_t)((b - a) * 16);
+    return true;
+}
+
+template <int FMT, bool XOR>
+__global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single)
+{
+    using F_ = Fmt<FMT>;
+    extern __shared__ __attribute__((aligned(16))) uint32_t rings[];     // [ring][wave][kRingWords], sized by the host
+    __shared__ FieldTab tab[F_::NF];
+    __shared__ TensorDev dsh;
+    WorkItem it;
+    if (use_single) { it.tensor = 0; it.first = blockIdx.x * kWavesPerGroup; }
+    else it = work[blockIdx.x];
+    if (threadIdx.x == 0) dsh = use_single ? single : descs[it.tensor];
+    __syncthreads();
+    const TensorDev &d = dsh;
+    uint32_t kind[F_::NF];
+    for (int f = 0; f < F_::NF; f++) {
+        kind[f] = uniform32(d.kind[f]);
+        if (kind[f] == KIND_HUFF) build_field_tab(tab[f], d.comp + d.table_off[f], 1 << (f == 2 ? 8 : F_::SB), d.lmax[f]);
+    }
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t chunk = uniform32(it.first + wave);
+    const uint32_t cb = uniform32(d.chunk_bytes);
+    const uint32_t E = cb * 8 / F_::EB;
+    const uint32_t n_full = (uint32_t)(uniform64(d.n_elems) / E);
+    if (chunk >= n_full) return;
+    const uint8_t *comp = reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.comp));
+    const uint64_t payload = uniform64(d.payload_off), total = uniform64(d.total_bytes);
+    const uint8_t *sp[F_::NF];
+    uint32_t sb[F_::NF];
+    for (int f = 0; f < F_::NF; f++)
+        if (!stream_range(d, comp, f, chunk, payload, total, sp[f], sb[f])) return;      // damaged index: leave the chunk alone
+    const __amdgpu_buffer_rsrc_t r0 = make_rsrc(sp[0], sb[0]), r1 = make_rsrc(sp[1], sb[1]);
+    const __amdgpu_buffer_rsrc_t ds = make_rsrc(reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.dst)) + (uint64_t)chunk * cb, cb);
+    const __amdgpu_buffer_rsrc_t bs = make_rsrc(XOR ? reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.base)) + (uint64_t)chunk * cb : comp, XOR ? cb : 0);
+    const uint32_t p0 = uniform32(d.period[0]), p1 = uniform32(d.period[1]);
+    const uint64_t K0 = splat(uniform32(d.konst[0]), F_::SB), K1 = splat(uniform32(d.konst[1]), F_::SB);
+
+    // rings: field 0 uses ring 0; field 1 uses ring 1 if field 0 is table decoded too, else ring 0
+    char *ring_base = reinterpret_cast<char *>(rings) + wave * (kRingWords * 4);
+    char *ring0 = ring_base, *ring1 = ring_base + (kind[0] == KIND_HUFF ? kWavesPerGroup * kRingWords * 4 : 0);
+    HuffStream H0, H1;
+    if (kind[0] == KIND_HUFF) huff_open(H0, r0, ring0, lane);
+    if (kind[1] == KIND_HUFF) huff_open(H1, r1, ring1, lane);
+
+    const uint32_t rows = cb / 1024;                          // 64 lanes x 16 bytes per row
+    for (uint32_t row = 0; row < rows; row++) {
+        uint64_t P0 = 0, P1 = 0, unused = 0;
+        if (kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, unused, lane);
+        else plain_run<F_::SB, F_::G>(kind[0], r0, row, lane, K0, P0, unused);
+        if (kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, unused, lane);
+        else plain_run<F_::SB, F_::G>(kind[1], r1, row, lane, K1, P1, unused);
+        const uint4 j = join_run<FMT>(P0, P1);
+        u32x4 v = {j.x, j.y, j.z, j.w};
+        if (XOR) v ^= __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)(row * 1024), 0);
+        __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
+    }
+
+    if (FMT == ZC_FMT_FP4_E2M1_MX) {
+        // block scales: one byte per 32 elements, 16 per run, the chunk's E/32 scales in rows of 1024
+        constexpr int F2 = F_::NF - 1;
+        const uint32_t n_sc = E / 32;
+        const __amdgpu_buffer_rsrc_t r2 = make_rsrc(sp[F2], sb[F2]);
+        const __amdgpu_buffer_rsrc_t ss = make_rsrc(reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.scales_out)) + (uint64_t)chunk * n_sc, n_sc);
+        const uint32_t p2 = uniform32(d.period[F2]);
+        const uint64_t K2 = splat(uniform32(d.konst[F2]), 8);
+        HuffStream H2;
+        if (kind[F2] == KIND_HUFF) huff_open(H2, r2, ring_base, lane);      // the element rings are free again
+        for (uint32_t row = 0; row < n_sc / 1024; row++) {
+            uint64_t P0 = 0, P1 = 0;
+            if (kind[F2] == KIND_HUFF) huff_run<8, 16>(H2, tab[F2], p2, P0, P1, lane);
+            else plain_run<8, 16>(kind[F2], r2, row, lane, K2, P0, P1);
+            const u32x4 v = {(uint32_t)P0, (uint32_t)(P0 >> 32), (uint32_t)P1, (uint32_t)(P1 >> 32)};
+            __builtin_amdgcn_raw_buffer_store_b128(v, ss, (int)(lane * 16), (int)(row * 1024), 0);
+        }
+    }
+}
+
+template <int FMT>
+static int launch_s64_x(bool xor_delta, uint32_t lds_bytes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single, hipStream_t st)
+{
+    if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single);
+    else hipLaunchKernelGGL((k_decode_s64<FMT, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single);
+    return (int)hipGetLastError();
+}
+
+// n_rings: 1 or 2 rings per wavefront (2 only when both element fields are table decoded)
+int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+                      const TensorDev *single, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    const TensorDev s = single ? *single : TensorDev{};
+    const int use_single = single ? 1 : 0;
+    const uint32_t lds = (n_rings >= 2 ? 2u : 1u) * kWavesPerGroup * kRingWords * 4;
+    if (fmt == ZC_FMT_BF16) return launch_s64_x<ZC_FMT_BF16>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
+    if (fmt == ZC_FMT_FP8_E4M3) return launch_s64_x<ZC_FMT_FP8_E4M3>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
+    return launch_s64_x<ZC_FMT_FP4_E2M1_MX>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
 }
 
 template <int EK, int MK>

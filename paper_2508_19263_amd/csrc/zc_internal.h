@@ -45,6 +45,8 @@ struct alignas(16) TensorDev {
     uint32_t units_off;       // compress: first entry of this tensor in the units array (field-major, n_chunks each)
     uint32_t streams;         // S
     uint8_t mode[4], lmax[4], konst[4], period[4];
+    uint8_t kind[4];          // decode: how the specialised kernels read the field (0 table, 1 flat code, 2 raw, 3 constant)
+    uint8_t pad_[12];
 };
 
 struct WorkItem { uint32_t tensor, first; };   // `first`: first chunk / block of the item
@@ -76,6 +78,9 @@ int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work
 // specialised FP8 decode of full chunks (zc_decode_fast.hip); exp_kind 0 = single, 1 = pair lookups; sm_kind 0 = flat, 1 = raw
 int launch_decode_fp8_fast(int exp_kind, int sm_kind, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                            const TensorDev *single, void *stream);
+// any format, 64 lanes per chunk, full chunks (zc_decode_fast.hip); n_rings = element fields that are table decoded (1..2)
+int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+                      const TensorDev *single, void *stream);
 uint32_t chunks_per_work_item(uint32_t streams);
 
 }  // namespace zc

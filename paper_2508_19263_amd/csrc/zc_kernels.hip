@@ -16,126 +16,9 @@
 #include <hip/hip_runtime.h>
 
 #include "zc_internal.h"
+#include "zc_device.cuh"
 
 namespace zc {
-
-// ------------------------------------------------------------------ lane helpers
-
-struct Lanes {
-    uint32_t lane, s, grp;     // lane in wave, lane in its S-lane group, group in wave
-    uint64_t gmask;            // wave mask of the lanes of this group
-};
-
-__device__ __forceinline__ Lanes make_lanes(uint32_t S)
-{
-    Lanes L;
-    L.lane = threadIdx.x & 63;
-    L.s = L.lane & (S - 1);
-    L.grp = L.lane / S;
-    L.gmask = (S == 64) ? ~0ull : (((1ull << S) - 1) << (L.lane - L.s));
-    return L;
-}
-
-// number of set bits of m in lanes below this one
-__device__ __forceinline__ uint32_t prefix_count(uint64_t m)
-{
-    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
-}
-
-template <int FMT> struct Fmt;
-template <> struct Fmt<ZC_FMT_BF16> { static constexpr int EB = 16, G = 8, SB = 8, NF = 2; };
-template <> struct Fmt<ZC_FMT_FP8_E4M3> { static constexpr int EB = 8, G = 16, SB = 4, NF = 2; };
-template <> struct Fmt<ZC_FMT_FP4_E2M1_MX> { static constexpr int EB = 4, G = 32, SB = 2, NF = 3; };
-
-// ------------------------------------------------- field split / join of one 16-byte run
-// P0 = the run's exponent symbols, P1 = its sign+mantissa symbols, SB bits each, symbol j at
-// bits j*SB (always 64 bits per field per run).
-
-__device__ __forceinline__ uint32_t pack_nibbles_of_bytes(uint32_t x)   // 4 bytes with a value < 16 each -> 16 bits
-{
-    x = (x | (x >> 4)) & 0x00FF00FFu;
-    return (x | (x >> 8)) & 0xFFFFu;
-}
-__device__ __forceinline__ uint32_t pack_pairs_of_nibbles(uint32_t x)   // 8 nibbles with a value < 4 each -> 16 bits
-{
-    x = (x | (x >> 2)) & 0x0F0F0F0Fu;
-    return pack_nibbles_of_bytes(x);
-}
-__device__ __forceinline__ uint32_t spread_nibbles_to_bytes(uint32_t x)  // inverse of pack_nibbles_of_bytes
-{
-    x = (x | (x << 8)) & 0x00FF00FFu;
-    return (x | (x << 4)) & 0x0F0F0F0Fu;
-}
-__device__ __forceinline__ uint32_t spread_pairs_to_nibbles(uint32_t x)  // inverse of pack_pairs_of_nibbles
-{
-    x = spread_nibbles_to_bytes(x);
-    return (x | (x << 2)) & 0x33333333u;
-}
-
-template <int FMT>
-__device__ __forceinline__ void split_run(const uint4 &v, uint64_t &P0, uint64_t &P1)
-{
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    P0 = 0; P1 = 0;
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        uint32_t e, m;
-        if (FMT == ZC_FMT_BF16) {                       // s eeeeeeee mmmmmmm, two per word
-            uint32_t lo = w[i] & 0xFFFFu, hi = w[i] >> 16;
-            e = ((lo >> 7) & 0xFFu) | (((hi >> 7) & 0xFFu) << 8);
-            m = (((lo >> 8) & 0x80u) | (lo & 0x7Fu)) | ((((hi >> 8) & 0x80u) | (hi & 0x7Fu)) << 8);
-        } else if (FMT == ZC_FMT_FP8_E4M3) {            // s eeee mmm, four per word
-            e = pack_nibbles_of_bytes((w[i] >> 3) & 0x0F0F0F0Fu);
-            m = pack_nibbles_of_bytes(((w[i] >> 4) & 0x08080808u) | (w[i] & 0x07070707u));
-        } else {                                        // s ee m, eight per word
-            e = pack_pairs_of_nibbles((w[i] >> 1) & 0x33333333u);
-            m = pack_pairs_of_nibbles(((w[i] >> 2) & 0x22222222u) | (w[i] & 0x11111111u));
-        }
-        P0 |= (uint64_t)e << (16 * i);
-        P1 |= (uint64_t)m << (16 * i);
-    }
-}
-
-template <int FMT>
-__device__ __forceinline__ uint4 join_run(uint64_t P0, uint64_t P1)
-{
-    uint32_t w[4];
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        uint32_t e = (uint32_t)(P0 >> (16 * i)) & 0xFFFFu, m = (uint32_t)(P1 >> (16 * i)) & 0xFFFFu;
-        if (FMT == ZC_FMT_BF16) {
-            uint32_t e0 = e & 0xFFu, e1 = e >> 8, m0 = m & 0xFFu, m1 = m >> 8;
-            uint32_t lo = ((m0 & 0x80u) << 8) | (e0 << 7) | (m0 & 0x7Fu);
-            uint32_t hi = ((m1 & 0x80u) << 8) | (e1 << 7) | (m1 & 0x7Fu);
-            w[i] = lo | (hi << 16);
-        } else if (FMT == ZC_FMT_FP8_E4M3) {
-            uint32_t eb = spread_nibbles_to_bytes(e), mb = spread_nibbles_to_bytes(m);
-            w[i] = ((mb & 0x08080808u) << 4) | (eb << 3) | (mb & 0x07070707u);
-        } else {
-            uint32_t en = spread_pairs_to_nibbles(e), mn = spread_pairs_to_nibbles(m);
-            w[i] = ((mn & 0x22222222u) << 2) | (en << 1) | (mn & 0x11111111u);
-        }
-    }
-    return make_uint4(w[0], w[1], w[2], w[3]);
-}
-
-// 16 bytes from p, of which only the first `valid` may be read
-__device__ __forceinline__ uint4 load_run(const uint8_t *p, uint32_t valid)
-{
-    if (valid >= 16) return *reinterpret_cast<const uint4 *>(p);
-    uint32_t w[4] = {0, 0, 0, 0};
-    for (uint32_t i = 0; i < valid; i++) w[i >> 2] |= (uint32_t)p[i] << (8 * (i & 3));
-    return make_uint4(w[0], w[1], w[2], w[3]);
-}
-
-__device__ __forceinline__ void store_run(uint8_t *p, const uint4 &v, uint32_t valid)
-{
-    if (valid >= 16) { *reinterpret_cast<uint4 *>(p) = v; return; }
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    for (uint32_t i = 0; i < valid; i++) p[i] = (uint8_t)(w[i >> 2] >> (8 * (i & 3)));
-}
-
-__device__ __forceinline__ uint4 xor4(const uint4 &a, const uint4 &b) { return make_uint4(a.x ^ b.x, a.y ^ b.y, a.z ^ b.z, a.w ^ b.w); }
 
 // ------------------------------------------------------------------------ histogram
 // One workgroup counts kHistBlockBytes of one tensor into LDS (8 replicas per bin to spread
@@ -501,65 +384,6 @@ int launch_write_headers(const TensorDev *d_descs, uint32_t n_tensors, const uin
 }
 
 // ------------------------------------------------------------------------- decoder
-// Tables of one field in LDS: a direct lookup on the next kLutBits stream bits and the
-// canonical first-code arrays for the rare codes longer than that.
-
-constexpr int kLutBits = 11;
-
-struct FieldTab {
-    uint16_t lut[1 << kLutBits];   // (symbol << 8) | length, 0 = code longer than the index
-    uint32_t first[17], cnt[17], start[17];
-    uint8_t sorted[256];
-    uint8_t len[256];
-    uint32_t mask;                 // (1 << min(Lmax, kLutBits)) - 1
-    uint32_t lmax;
-};
-
-// all threads of the workgroup; lengths come from the container's table
-__device__ void build_field_tab(FieldTab &T, const uint8_t *len_table, int alphabet, uint32_t lmax)
-{
-    const uint32_t tid = threadIdx.x, nt = blockDim.x;
-    if (tid < 17) T.cnt[tid] = 0;
-    for (uint32_t v = tid; v < 256; v += nt) T.len[v] = v < (uint32_t)alphabet ? len_table[v] : 0;
-    if (lmax > 16) lmax = 16;
-    __syncthreads();
-    for (uint32_t v = tid; v < (uint32_t)alphabet; v += nt)
-        if (T.len[v] && T.len[v] <= 16) atomicAdd(&T.cnt[T.len[v]], 1u);
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t code = 0, idx = 0;
-        for (int l = 1; l <= 16; l++) {
-            code <<= 1;
-            T.first[l] = code; T.start[l] = idx;
-            code += T.cnt[l]; idx += T.cnt[l];
-        }
-        const uint32_t bits = lmax < (uint32_t)kLutBits ? lmax : (uint32_t)kLutBits;
-        T.mask = (1u << bits) - 1;
-        T.lmax = lmax;
-    }
-    __syncthreads();
-    for (uint32_t v = tid; v < (uint32_t)alphabet; v += nt) {
-        const uint32_t l = T.len[v];
-        if (l && l <= 16) {
-            uint32_t rank = 0;
-            for (uint32_t u = 0; u < v; u++) rank += T.len[u] == l;
-            T.sorted[T.start[l] + rank] = (uint8_t)v;
-        }
-    }
-    __syncthreads();
-    const uint32_t bits = lmax < (uint32_t)kLutBits ? lmax : (uint32_t)kLutBits;
-    for (uint32_t idx = tid; idx < (1u << bits); idx += nt) {
-        const uint32_t msb = __brev(idx);                  // stream bits in code order, left aligned
-        uint32_t entry = 0;
-        for (uint32_t l = 1; l <= bits; l++) {
-            const uint32_t code = msb >> (32 - l);
-            if (code - T.first[l] < T.cnt[l] && code >= T.first[l]) { entry = l | ((uint32_t)T.sorted[T.start[l] + code - T.first[l]] << 8); break; }
-        }
-        T.lut[idx] = (uint16_t)entry;
-    }
-    __syncthreads();
-}
-
 struct DecField {
     uint32_t lo, hi;       // 64 stream bits, next unread bit = bit c of {hi, lo}
     uint32_t c;
@@ -578,17 +402,6 @@ __device__ __forceinline__ void dec_refill(DecField &D, bool active, const Lanes
         D.lo = D.hi; D.hi = w; D.c -= 32;
     }
     D.wpos += (uint32_t)__popcll(bm);
-}
-
-// code longer than the lookup index: canonical search on the bit-reversed window
-__device__ __noinline__ uint32_t dec_long(const FieldTab &T, uint32_t x)
-{
-    const uint32_t msb = __brev(x);
-    for (uint32_t l = kLutBits + 1; l <= T.lmax; l++) {
-        const uint32_t code = msb >> (32 - l);
-        if (code >= T.first[l] && code - T.first[l] < T.cnt[l]) return l | ((uint32_t)T.sorted[T.start[l] + code - T.first[l]] << 8);
-    }
-    return T.lmax ? T.lmax : 1;      // malformed table: consume something, symbol 0
 }
 
 // decode symbols [j0, j0+R) of a run; symbol j goes to bit (j % PER64)*SB of P0 (j < PER64) or P1
@@ -630,14 +443,6 @@ __device__ __forceinline__ void dec_run(DecField &D, const FieldTab &T, uint32_t
     case 16: if (G >= 16) dec_run_r<SB, G, (G >= 16 ? 16 : G), FULL>(D, T, P0, P1, nsym, L); break;
     default: if (G >= 32) dec_run_r<SB, G, (G >= 32 ? 32 : G), FULL>(D, T, P0, P1, nsym, L); break;
     }
-}
-
-// every symbol of a 64-bit packed run equal to v
-__device__ __forceinline__ uint64_t splat(uint32_t v, int sb)
-{
-    uint64_t x = v;
-    for (int w = sb; w < 64; w *= 2) x |= x << w;
-    return x;
 }
 
 __device__ __forceinline__ DecField open_stream(const TensorDev &d, int f, uint32_t chunk, bool valid)

@@ -59,7 +59,8 @@ class Tensor(C.Structure):
 
 class BatchPlan(C.Structure):
     _fields_ = [("format", C.c_uint32), ("streams", C.c_uint32), ("n_tensors", C.c_uint32), ("n_fast_work", C.c_uint32),
-                ("n_work", C.c_uint32), ("fast_exp_kind", C.c_uint32), ("fast_sm_kind", C.c_uint32), ("xor_delta", C.c_uint32),
+                ("n_work", C.c_uint32), ("fast_kernel", C.c_uint32), ("fast_exp_kind", C.c_uint32), ("fast_sm_kind", C.c_uint32),
+                ("n_rings", C.c_uint32), ("xor_delta", C.c_uint32), ("reserved", C.c_uint32),
                 ("fast_work_offset", C.c_uint64), ("work_offset", C.c_uint64)]
 
 
@@ -245,6 +246,8 @@ class Batch:
         self.arena = torch.empty(total, dtype=torch.uint8, device=dev)
         self.comp = [self.arena[o:o + c] for o, c in zip(offs, self.caps)]
         self.ws = _workspace(list(n_elems), p, dev)
+        # the decode plan lives in a workspace of its own: compress() rewrites self.ws
+        self.ws_plan = torch.empty(self.ws.numel(), dtype=torch.uint8, device=dev)
         for i in range(self.n):
             a = self.arr[i]
             a.d_src = srcs[i].data_ptr()
@@ -284,11 +287,11 @@ class Batch:
         if self.out is None:
             self.prepare_outputs()
         self.plan = BatchPlan()
-        _check(lib().zc_decompress_batch_plan(self.arr, self.n, _ptr(self.ws), self.ws.numel(), C.byref(self.plan), _stream()),
+        _check(lib().zc_decompress_batch_plan(self.arr, self.n, _ptr(self.ws_plan), self.ws_plan.numel(), C.byref(self.plan), _stream()),
                "zc_decompress_batch_plan")
         return self.plan
 
     def run_decompress(self):
         """Enqueue the decode kernels on the plan left in the workspace by plan_decompress()."""
-        _check(lib().zc_decompress_batch_run(C.byref(self.plan), _ptr(self.ws), _stream()), "zc_decompress_batch_run")
+        _check(lib().zc_decompress_batch_run(C.byref(self.plan), _ptr(self.ws_plan), _stream()), "zc_decompress_batch_run")
         return self.out
