@@ -73,7 +73,7 @@ uint64_t get64(const uint8_t *p) { uint64_t v; std::memcpy(&v, p, 8); return v; 
 
 // ---- workspace carving ------------------------------------------------------
 struct Workspace {
-    uint64_t descs, hist_work, scale_work, chunk_work, hist, enc, units, scan, blobs, total;
+    uint64_t descs, hist_work, scale_work, chunk_work, fast_work, hist, enc, units, scan, blobs, total;
     uint32_t n_hist_work, n_scale_work, n_chunk_work;
     uint64_t n_units;
 };
@@ -101,6 +101,7 @@ zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T,
     w->hist_work = off; off = align256(off + hw * sizeof(WorkItem));
     w->scale_work = off; off = align256(off + sw * sizeof(WorkItem));
     w->chunk_work = off; off = align256(off + cw * sizeof(WorkItem));
+    w->fast_work = off; off = align256(off + cw * sizeof(WorkItem));
     w->hist = off; off = align256(off + (uint64_t)T * 3 * 256 * 8);
     w->enc = off; off = align256(off + (uint64_t)T * 768 * 4);
     w->units = off; off = align256(off + units * 4);
@@ -208,6 +209,16 @@ void serialize_blob(const zc_info &info, uint8_t *blob)
     put64(blob + 56, info.payload_offset);
 }
 
+// how the specialised kernels treat a field: 0 table, 1 flat code, 2 raw, 3 constant
+uint8_t field_kind(uint32_t mode, uint32_t sym_bits_, const uint8_t *code_len)
+{
+    if (mode == ZC_MODE_RAW) return 2;
+    if (mode != ZC_MODE_HUFF) return 3;
+    // flat: every symbol present with length sym_bits, so the canonical code is the symbol itself
+    for (uint32_t v = 0; v < (1u << sym_bits_); v++) if (code_len[v] != sym_bits_) return 0;
+    return 1;
+}
+
 TensorDev make_desc(const zc_info &info)
 {
     TensorDev d;
@@ -218,14 +229,7 @@ TensorDev make_desc(const zc_info &info)
         d.table_off[f] = (uint32_t)info.table_offset[f]; d.index_off[f] = (uint32_t)info.index_offset[f];
         d.mode[f] = info.mode[f]; d.lmax[f] = info.max_len[f]; d.konst[f] = info.const_symbol[f];
         d.period[f] = (uint8_t)refill_period(run_len(info.format, (int)f), info.max_len[f]);
-        // how the specialised decoders read the field: 0 table, 1 flat code, 2 raw, 3 constant
-        uint8_t kind = 3;
-        if (info.mode[f] == ZC_MODE_RAW) kind = 2;
-        else if (info.mode[f] == ZC_MODE_HUFF) {
-            kind = 1;       // flat: every symbol present with length sym_bits, so the canonical code is the symbol itself
-            for (uint32_t v = 0; v < (1u << info.sym_bits[f]); v++) if (info.code_len[f][v] != info.sym_bits[f]) kind = 0;
-        }
-        d.kind[f] = kind;
+        d.kind[f] = field_kind(info.mode[f], info.sym_bits[f], info.code_len[f]);
     }
     return d;
 }
@@ -258,7 +262,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
 
     // descriptors and work lists
     std::vector<TensorDev> descs(T);
-    std::vector<WorkItem> hist_work, scale_work, chunk_work;
+    std::vector<WorkItem> hist_work, scale_work;
     std::vector<uint64_t> ncs(T);
     uint64_t units_off = 0;
     for (uint32_t t = 0; t < T; t++) {
@@ -281,14 +285,12 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         const uint64_t bytes = (x.n_elems * (uint64_t)elem_bits(g.fmt) + 7) / 8;
         for (uint64_t b = 0; b * kHistBlockBytes < bytes; b++) hist_work.push_back({t, (uint32_t)b});
         if (g.nf == 3) for (uint64_t b = 0; b * kHistBlockBytes < x.n_elems / 32; b++) scale_work.push_back({t, (uint32_t)b});
-        for (uint64_t c = 0; c < nc; c += cpi) chunk_work.push_back({t, (uint32_t)c});
     }
     TensorDev *d_descs = (TensorDev *)(ws + w.descs);
     uint64_t *d_hist = (uint64_t *)(ws + w.hist);
     HIP_TRY(hipMemcpyAsync(d_descs, descs.data(), T * sizeof(TensorDev), hipMemcpyHostToDevice, hs));
     if (!hist_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
     if (!scale_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
-    if (!chunk_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.chunk_work, chunk_work.data(), chunk_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
     HIP_TRY(hipMemsetAsync(d_hist, 0, (uint64_t)T * 3 * 256 * 8, hs));
 
     // field split + histogram (a1-a3)
@@ -300,6 +302,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
 
     // code construction on the host (a4)
     std::vector<FieldCode> codes((size_t)T * 3);
+    std::vector<WorkItem> fast_work, slow_work;
     std::vector<uint32_t> enc((size_t)T * 768, 0);
     std::vector<uint8_t> blobs((size_t)T * kBlobBytes, 0);
     for (uint32_t t = 0; t < T; t++) {
@@ -311,13 +314,29 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         for (uint32_t f = 0; f < g.nf; f++) {
             descs[t].mode[f] = (uint8_t)fc[f].mode; descs[t].lmax[f] = (uint8_t)fc[f].lmax; descs[t].konst[f] = (uint8_t)fc[f].konst;
             descs[t].period[f] = (uint8_t)refill_period(run_len(g.fmt, (int)f), (int)fc[f].lmax);
+            descs[t].kind[f] = field_kind(fc[f].mode, (uint32_t)sym_bits(g.fmt, (int)f), fc[f].len);
             for (int v = 0; v < 256; v++)
                 enc[(size_t)t * 768 + f * 256 + v] = ((uint32_t)fc[f].len[v] << 16) | reverse_bits(fc[f].code[v], fc[f].len[v]);
         }
+        // FP8 shape the specialised size/encode kernels take: 64 lanes, chunks of whole 1 KiB rows,
+        // exponent codes of at most 8 bits, sign+mantissa flat or raw.  Their table (slot of the
+        // unused third field) maps a pair of exponents to the two codes concatenated.
+        const bool fast_ok = g.fmt == ZC_FMT_FP8_E4M3 && g.S == 64 && g.chunk_bytes % 1024 == 0 && fc[0].mode == ZC_MODE_HUFF &&
+                             fc[0].lmax <= 8 && (descs[t].kind[1] == 1 || descs[t].kind[1] == 2);
+        if (fast_ok)
+            for (uint32_t u = 0; u < 256; u++) {
+                const uint32_t e0 = u & 15, e1 = u >> 4, l0 = fc[0].len[e0], l1 = fc[0].len[e1];
+                enc[(size_t)t * 768 + 512 + u] = ((l0 + l1) << 16) | reverse_bits(fc[0].code[e0], (int)l0) | (reverse_bits(fc[0].code[e1], (int)l1) << l0);
+            }
+        const uint64_t n_full = fast_ok ? tensors[t].n_elems / g.elems_per_chunk : 0;
+        for (uint64_t c = 0; c < n_full; c += kWavesPerGroup) fast_work.push_back({t, (uint32_t)c});
+        for (uint64_t c = n_full; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
     }
     if (codes_out) *codes_out = codes;
     HIP_TRY(hipMemcpyAsync(d_descs, descs.data(), T * sizeof(TensorDev), hipMemcpyHostToDevice, hs));
     HIP_TRY(hipMemcpyAsync(ws + w.enc, enc.data(), enc.size() * 4, hipMemcpyHostToDevice, hs));
+    if (!fast_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.fast_work, fast_work.data(), fast_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
+    if (!slow_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.chunk_work, slow_work.data(), slow_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
     if (!stats_only) {
         HIP_TRY(hipMemcpyAsync(ws + w.blobs, blobs.data(), blobs.size(), hipMemcpyHostToDevice, hs));
         LAUNCH_TRY(launch_write_headers(d_descs, T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
@@ -326,7 +345,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     // stream sizes (a5) and their exclusive scan into the chunk index (a6)
     const uint32_t *d_enc = (const uint32_t *)(ws + w.enc);
     uint32_t *d_units = (uint32_t *)(ws + w.units);
-    LAUNCH_TRY(launch_sizes(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)chunk_work.size(), cpi, d_enc, d_units, stream));
+    LAUNCH_TRY(launch_sizes_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, stream));
+    LAUNCH_TRY(launch_sizes(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), cpi, d_enc, d_units, stream));
     LAUNCH_TRY(launch_scan(d_descs, T, (int)g.nf, d_units, (ScanOut *)(ws + w.scan), stream));
     std::vector<ScanOut> scan(T);
     HIP_TRY(hipMemcpyAsync(scan.data(), ws + w.scan, T * sizeof(ScanOut), hipMemcpyDeviceToHost, hs));
@@ -341,7 +361,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     if (stats_only) return ZC_OK;
 
     // chunked encode (a7)
-    LAUNCH_TRY(launch_encode(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)chunk_work.size(), cpi, d_enc, stream));
+    LAUNCH_TRY(launch_encode_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, stream));
+    LAUNCH_TRY(launch_encode(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), cpi, d_enc, stream));
     return ZC_OK;
 }
 

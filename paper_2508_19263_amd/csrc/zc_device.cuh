@@ -140,7 +140,7 @@ struct FieldTab {
 };
 
 // all threads of the workgroup; lengths come from the container's table
-static __device__ void build_field_tab(FieldTab &T, const uint8_t *len_table, int alphabet, uint32_t lmax)
+__attribute__((unused)) static __device__ void build_field_tab(FieldTab &T, const uint8_t *len_table, int alphabet, uint32_t lmax)
 {
     const uint32_t tid = threadIdx.x, nt = blockDim.x;
     if (tid < 17) T.cnt[tid] = 0;
@@ -185,7 +185,7 @@ static __device__ void build_field_tab(FieldTab &T, const uint8_t *len_table, in
 }
 
 // code longer than the lookup index: canonical search on the bit-reversed window
-static __device__ __noinline__ uint32_t dec_long(const FieldTab &T, uint32_t x)
+__attribute__((unused)) static __device__ __noinline__ uint32_t dec_long(const FieldTab &T, uint32_t x)
 {
     const uint32_t msb = __brev(x);
     for (uint32_t l = kLutBits + 1; l <= T.lmax; l++) {

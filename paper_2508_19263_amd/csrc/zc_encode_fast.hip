@@ -1,0 +1,198 @@
+// Specialised stream-size and encode kernels for the common FP8 E4M3 container shape:
+// 64 lanes per chunk, full chunks, exponent codes of at most 8 bits, sign+mantissa field
+// stored raw or with the flat 4-bit code.  Everything else goes through k_encode in
+// zc_kernels.hip; both produce the same bytes.
+//
+// A refill period of 4 symbols is one 32-bit word of source, so a group is handled as two
+// exponent pairs: the two exponents of adjacent bytes index a 256-entry table (built on the
+// host from the tensor's code) that holds the two codes already concatenated and their total
+// length, halving the table lookups and the shift/or work per symbol.
+#include <hip/hip_runtime.h>
+
+#include "zc_internal.h"
+#include "zc_device.cuh"
+
+namespace zc {
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t uni32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ uint64_t uni64(uint64_t v) { return ((uint64_t)uni32((uint32_t)(v >> 32)) << 32) | (uint64_t)uni32((uint32_t)v); }
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc_of(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+// (x.byte[B]) << 2: LDS byte offset of a 32-bit table entry
+template <int B>
+__device__ __forceinline__ uint32_t byte_times4(uint32_t x, uint32_t two)
+{
+    uint32_t r;
+    if (B == 0) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(two), "v"(x));
+    else asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(two), "v"(x));
+    return r;
+}
+
+// code and length of the four exponents of one source word: bits 15..0 of an entry are the
+// two codes of a byte pair (first symbol in the low bits), bits 20..16 their total length
+__device__ __forceinline__ void group_code(uint32_t w, const char *pair_lut, uint32_t two, uint32_t &code, uint32_t &len)
+{
+    const uint32_t t = (w >> 3) & 0x0F0F0F0Fu;          // exponent of every byte
+    const uint32_t u = t | (t >> 4);                    // bytes 0 and 2: e0 | e1 << 4, e2 | e3 << 4
+    const uint32_t a = *reinterpret_cast<const uint32_t *>(pair_lut + byte_times4<0>(u, two));
+    const uint32_t b = *reinterpret_cast<const uint32_t *>(pair_lut + byte_times4<2>(u, two));
+    const uint32_t la = a >> 16;
+    code = (a & 0xFFFFu) | ((b & 0xFFFFu) << la);
+    len = la + (b >> 16);
+}
+
+}  // namespace
+
+// stream sizes of full chunks: per lane only arithmetic on code lengths, no stream positions
+__global__ __launch_bounds__(256) void k_sizes_fp8(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units)
+{
+    __shared__ uint32_t pair[256];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev *dp = descs + it.tensor;
+    pair[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + 512 + threadIdx.x];
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t chunk = uni32(it.first + (threadIdx.x >> 6));
+    const uint32_t E = uni32(dp->chunk_bytes);
+    const uint64_t n_elems = uni64(dp->n_elems);
+    if (chunk >= (uint32_t)(n_elems / E)) return;
+    const bool has_base = uni64((uint64_t)dp->base) != 0;
+    const __amdgpu_buffer_rsrc_t src = rsrc_of(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)) + (uint64_t)chunk * E, E);
+    const __amdgpu_buffer_rsrc_t bas = rsrc_of(has_base ? reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) + (uint64_t)chunk * E : nullptr, has_base ? E : 0);
+    const char *pair_lut = reinterpret_cast<const char *>(pair);
+    const uint32_t two = 2;
+    int32_t k = 0;              // unread bits the decoder would hold
+    uint32_t q = 0;             // words this lane's decoder asks for
+    const uint32_t rows = E / 1024;
+    for (uint32_t row = 0; row < rows; row++) {
+        u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(src, (int)(lane * 16), (int)(row * 1024), 0);
+        if (has_base) v ^= __builtin_amdgcn_raw_buffer_load_b128(bas, (int)(lane * 16), (int)(row * 1024), 0);
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+            const bool req = k <= 32;
+            q += req ? 1u : 0u;
+            k += req ? 32 : 0;
+            uint32_t code, len;
+            group_code(v[g], pair_lut, two, code, len);
+            k -= (int32_t)len;
+        }
+    }
+    // words of the chunk's exponent stream = sum over the lanes
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+    if (lane == 0) {
+        uint32_t *my = units + uni32(dp->units_off);
+        const uint32_t nc = uni32(dp->n_chunks);
+        my[chunk] = (q + 3) / 4;
+        my[nc + chunk] = E / 32;                            // 4 bits per element, 16-byte units (flat code and raw alike)
+    }
+}
+
+__global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables)
+{
+    __shared__ uint32_t pair[256];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev *dp = descs + it.tensor;
+    pair[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + 512 + threadIdx.x];
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t chunk = uni32(it.first + (threadIdx.x >> 6));
+    const uint32_t E = uni32(dp->chunk_bytes);
+    const uint64_t n_elems = uni64(dp->n_elems);
+    if (chunk >= (uint32_t)(n_elems / E)) return;
+    const bool has_base = uni64((uint64_t)dp->base) != 0;
+    const bool sm_raw = uni32(dp->kind[1]) == 2;
+    uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
+    const uint64_t payload = uni64(dp->payload_off);
+    const uint32_t *index0 = reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[0]));
+    const uint32_t *index1 = reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[1]));
+    const uint64_t a0 = uni32(index0[chunk]), b0 = uni32(index0[chunk + 1]), a1 = uni32(index1[chunk]), b1 = uni32(index1[chunk + 1]);
+    if (a0 > b0 || a1 > b1 || (b0 - a0) * 16 > 0x7FFFFFFFull || (b1 - a1) * 16 != (uint64_t)E / 2) return;   // index not as the size pass left it
+    const __amdgpu_buffer_rsrc_t src = rsrc_of(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)) + (uint64_t)chunk * E, E);
+    const __amdgpu_buffer_rsrc_t bas = rsrc_of(has_base ? reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) + (uint64_t)chunk * E : nullptr, has_base ? E : 0);
+    const __amdgpu_buffer_rsrc_t es = rsrc_of(comp + payload + 16 * a0, (uint32_t)((b0 - a0) * 16));
+    const __amdgpu_buffer_rsrc_t ms = rsrc_of(comp + payload + 16 * a1, E / 2);
+    const char *pair_lut = reinterpret_cast<const char *>(pair);
+    const uint32_t two = 2;
+
+    uint64_t acc = 0;           // bits not yet written, next free bit = nacc (< 32 between groups)
+    uint32_t nacc = 0;
+    int32_t k = 0;              // unread bits the decoder would hold at this point
+    uint32_t pend = 0, p0 = 0, p1 = 0;     // words the decoder has asked for and we still owe, and where they go
+    uint32_t wpos = 0;          // words of the stream handed out so far
+    const uint32_t rows = E / 1024;
+    for (uint32_t row = 0; row < rows; row++) {
+        u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(src, (int)(lane * 16), (int)(row * 1024), 0);
+        if (has_base) v ^= __builtin_amdgcn_raw_buffer_load_b128(bas, (int)(lane * 16), (int)(row * 1024), 0);
+        // ---- sign+mantissa nibbles of the run, packed (symbol j at bits 4j)
+        uint32_t m[2];
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const uint32_t lo = pack_nibbles_of_bytes(((v[2 * h] >> 4) & 0x08080808u) | (v[2 * h] & 0x07070707u));
+            const uint32_t hi = pack_nibbles_of_bytes(((v[2 * h + 1] >> 4) & 0x08080808u) | (v[2 * h + 1] & 0x07070707u));
+            m[h] = lo | (hi << 16);
+        }
+        if (sm_raw) {
+            __builtin_amdgcn_raw_buffer_store_b64(u32x2{m[0], m[1]}, ms, (int)(lane * 8), (int)(row * 512), 0);
+        } else {
+            // flat code: each symbol written most significant bit first, one word per 8 symbols, rows of 64 words
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                uint32_t w = ((m[h] >> 1) & 0x55555555u) | ((m[h] & 0x55555555u) << 1);
+                w = ((w >> 2) & 0x33333333u) | ((w & 0x33333333u) << 2);
+                __builtin_amdgcn_raw_buffer_store_b32(w, ms, (int)(lane * 4), (int)((row * 2 + h) * 256), 0);
+            }
+        }
+        // ---- exponent: one refill step of the decoder, then the four codes of a source word
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+            const bool req = k <= 32;
+            const uint64_t bm = __ballot(req);
+            if (req) {
+                const uint32_t pos = wpos + __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, 0));
+                if (pend == 0) p0 = pos; else p1 = pos;
+                pend++;
+                k += 32;
+            }
+            wpos += (uint32_t)__popcll(bm);
+            uint32_t code, len;
+            group_code(v[g], pair_lut, two, code, len);
+            acc |= (uint64_t)code << nacc;
+            nacc += len;
+            k -= (int32_t)len;
+            if (nacc >= 32) {
+                __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, es, (int)(p0 * 4), 0, 0);
+                acc >>= 32; nacc -= 32; p0 = p1; pend--;
+            }
+        }
+    }
+    // the words still owed to the decoder (a partial word and look-ahead words), then zero padding
+    if (pend > 0) { __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, es, (int)(p0 * 4), 0, 0); acc >>= 32; p0 = p1; pend--; }
+    if (pend > 0) { __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, es, (int)(p0 * 4), 0, 0); pend--; }
+    if (lane < ((4 - (wpos & 3)) & 3)) __builtin_amdgcn_raw_buffer_store_b32(0u, es, (int)((wpos + lane) * 4), 0, 0);
+}
+
+int launch_sizes_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipLaunchKernelGGL(k_sizes_fp8, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_units);
+    return (int)hipGetLastError();
+}
+
+int launch_encode_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipLaunchKernelGGL(k_encode_fp8, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc);
+    return (int)hipGetLastError();
+}
+
+}  // namespace zc

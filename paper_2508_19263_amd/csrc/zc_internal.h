@@ -81,6 +81,9 @@ int launch_decode_fp8_fast(int exp_kind, int sm_kind, bool xor_delta, const Tens
 // any format, 64 lanes per chunk, full chunks (zc_decode_fast.hip); n_rings = element fields that are table decoded (1..2)
 int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                       const TensorDev *single, void *stream);
+// FP8, 64 lanes, full chunks, exponent codes <= 8 bits, sign+mantissa flat or raw (zc_encode_fast.hip)
+int launch_sizes_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream);
+int launch_encode_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
 uint32_t chunks_per_work_item(uint32_t streams);
 
 }  // namespace zc

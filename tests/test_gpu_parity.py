@@ -320,3 +320,40 @@ def test_config2_full_size_tensors_in_the_benchmark_launch_configuration():
         for c in sorted(set([0, n_chunks - 1] + rng.integers(0, n_chunks, 4).tolist())):
             rc, chunk, _ = o.decompress_chunk(want, c, 262144)
             assert rc == o.OK and np.array_equal(chunk, gpu_out[c * 262144:(c + 1) * 262144]), (name, c)
+
+
+def test_full_chunk_kernel_all_formats_and_kinds():
+    # the 64-lane full-chunk decoder: every format, table-decoded / flat / raw / constant fields,
+    # one or two LDS rings, delta, chunks that are whole multiples of its row size
+    rng = np.random.default_rng(71)
+    # FP4 with skewed element fields (mostly small magnitudes) so that exponent and sign+mantissa
+    # get real Huffman codes, and few distinct scales
+    n = 5 * 32768 + 32 * 77
+    nib = rng.choice(16, size=n, p=np.array([40, 20, 8, 4, 2, 1, 1, 1, 10, 5, 3, 2, 1, 1, 0.5, 0.5]) / 100.0).astype(np.uint8)
+    packed = torch.from_numpy((nib[0::2] | (nib[1::2] << 4)).astype(np.uint8))
+    scales = torch.from_numpy(rng.choice([118, 119, 120, 121, 127], size=n // 32, p=[0.5, 0.3, 0.1, 0.05, 0.05]).astype(np.uint8))
+    for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+        check_case(zc.FMT_FP4_E2M1_MX, n, 16384, 64, policy, data=(packed, scales), tag="fp4-skewed")
+    flat_nib = rng.integers(0, 16, n).astype(np.uint8)
+    packed2 = torch.from_numpy((flat_nib[0::2] | (flat_nib[1::2] << 4)).astype(np.uint8))
+    const_scales = torch.full((n // 32,), 119, dtype=torch.uint8)
+    check_case(zc.FMT_FP4_E2M1_MX, n, 16384, 64, data=(packed2, const_scales), tag="fp4-flat-constscale")
+    check_case(zc.FMT_FP4_E2M1_MX, n, 32768, 64, zc.POLICY_AUTO, data=(packed2, scales), tag="fp4-raw")
+    # BF16: plain weights (exponent table decoded, sign+mantissa flat) and a delta with both fields table decoded
+    m = 9 * 8192 + 4097
+    w0, w1 = wl.bf16_checkpoint_pair(m, seed=72)
+    w0, w1 = w0.view(torch.uint8), w1.view(torch.uint8)
+    for cb in (1024, 16384):
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            check_case(zc.FMT_BF16, m, cb, 64, policy, data=(w1, None), tag="bf16-plain")
+            check_case(zc.FMT_BF16, m, cb, 64, policy, data=(w1, None), base=w0, tag="bf16-delta")
+    # identical checkpoints: the delta is all zero, both fields constant
+    check_case(zc.FMT_BF16, m, 16384, 64, data=(w1, None), base=w1, tag="bf16-zero-delta")
+    # FP8 with exponent codes longer than 8 bits (not the specialised FP8 kernel) and both fields skewed
+    pr = np.exp2(-np.arange(1, 17, dtype=float)); pr /= pr.sum()
+    k = 20 * 4096 + 100
+    e = rng.choice(16, size=k, p=pr).astype(np.uint8)
+    sm = rng.choice(16, size=k, p=pr[::-1]).astype(np.uint8)
+    x = torch.from_numpy((((sm >> 3) << 7) | (e << 3) | (sm & 7)).astype(np.uint8))
+    for L in (15, 12, 9):
+        check_case(zc.FMT_FP8_E4M3, k, 4096, 64, L=(L, L, 0), data=(x, None), tag="fp8-long-L%d" % L)
