@@ -319,10 +319,10 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
                 enc[(size_t)t * 768 + f * 256 + v] = ((uint32_t)fc[f].len[v] << 16) | reverse_bits(fc[f].code[v], fc[f].len[v]);
         }
         // FP8 shape the specialised size/encode kernels take: 64 lanes, chunks of whole 1 KiB rows,
-        // exponent codes of at most 8 bits, sign+mantissa flat or raw.  Their table (slot of the
+        // exponent refill period 4 (longest code 5..8 bits), sign+mantissa flat or raw.  Their table (slot of the
         // unused third field) maps a pair of exponents to the two codes concatenated.
         const bool fast_ok = g.fmt == ZC_FMT_FP8_E4M3 && g.S == 64 && g.chunk_bytes % 1024 == 0 && fc[0].mode == ZC_MODE_HUFF &&
-                             fc[0].lmax <= 8 && (descs[t].kind[1] == 1 || descs[t].kind[1] == 2);
+                             descs[t].period[0] == 4 && (descs[t].kind[1] == 1 || descs[t].kind[1] == 2);
         if (fast_ok)
             for (uint32_t u = 0; u < 256; u++) {
                 const uint32_t e0 = u & 15, e1 = u >> 4, l0 = fc[0].len[e0], l1 = fc[0].len[e1];
@@ -373,7 +373,8 @@ FastKind fast_kind(const zc_info &info)
 {
     FastKind k = {false, 0, 0};
     if (info.format != ZC_FMT_FP8_E4M3 || info.streams != 64 || info.chunk_bytes % 1024) return k;
-    if (info.mode[0] != ZC_MODE_HUFF || info.max_len[0] > 8 || info.max_len[0] == 0) return k;
+    // the kernel is written for a refill period of 4 symbols, i.e. a longest code of 5..8 bits
+    if (info.mode[0] != ZC_MODE_HUFF || refill_period(16, info.max_len[0]) != 4) return k;
     if (info.mode[1] == ZC_MODE_RAW) k.sm_kind = 1;
     else if (info.mode[1] == ZC_MODE_HUFF) {
         for (int v = 0; v < 16; v++) if (info.code_len[1][v] != 4) return k;   // flat: canonical code == symbol

@@ -1,5 +1,6 @@
 // Specialised decode kernels for the common shapes of a container: FP8 E4M3, 64 lanes per
-// chunk, full chunks, exponent field Huffman coded with codes of at most 8 bits, and a
+// chunk, full chunks, exponent field Huffman coded with a longest code of 5..8 bits (refill
+// period 4), and a
 // sign+mantissa field that is either stored raw or coded with the flat 4-bit code (which
 // is what the Huffman construction returns for its near-uniform histogram).
 // Everything else goes through the generic kernel in zc_kernels.hip.

@@ -1,5 +1,5 @@
 // Specialised stream-size and encode kernels for the common FP8 E4M3 container shape:
-// 64 lanes per chunk, full chunks, exponent codes of at most 8 bits, sign+mantissa field
+// 64 lanes per chunk, full chunks, longest exponent code 5..8 bits (refill period 4), sign+mantissa field
 // stored raw or with the flat 4-bit code.  Everything else goes through k_encode in
 // zc_kernels.hip; both produce the same bytes.
 //

@@ -357,3 +357,14 @@ def test_full_chunk_kernel_all_formats_and_kinds():
     x = torch.from_numpy((((sm >> 3) << 7) | (e << 3) | (sm & 7)).astype(np.uint8))
     for L in (15, 12, 9):
         check_case(zc.FMT_FP8_E4M3, k, 4096, 64, L=(L, L, 0), data=(x, None), tag="fp8-long-L%d" % L)
+
+
+def test_fp8_short_exponent_codes_take_the_general_path():
+    # longest exponent code below 5 bits -> refill period 8 or 16: not the period-4 FP8 kernels
+    rng = np.random.default_rng(81)
+    n = 11 * 4096 + 300
+    for probs in ([0.6, 0.25, 0.1, 0.05], [0.9, 0.1], [0.3, 0.3, 0.2, 0.1, 0.05, 0.05]):
+        e = rng.choice(len(probs), size=n, p=probs).astype(np.uint8) + 5
+        x = torch.from_numpy(((e << 3) | rng.integers(0, 8, n).astype(np.uint8) | (rng.integers(0, 2, n).astype(np.uint8) << 7)).astype(np.uint8))
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            check_case(zc.FMT_FP8_E4M3, n, 4096, 64, policy, data=(x, None), tag="fp8-short-%d" % len(probs))
