@@ -63,15 +63,15 @@ def other_workloads(torch, wl, zc, dev):
              "round_trip_bit_exact": bool(ok)}
         if ids is not None:
             # random-access decode of a page sample of every tensor into dense buffers
-            infos = [b.arr[i].info for i in range(b.n)]
-            outs = [torch.empty(ids[i].numel() * chunk, dtype=torch.uint8, device=dev) for i in range(b.n)]
-            def pages():
-                for i in range(b.n):
-                    zc.decompress_chunks(b.container(i), infos[i], ids[i], out=outs[i])
-            t_p = _time_ms(torch, pages)
+            b.set_chunk_ids(ids)
+            b.plan_decompress()
+            outs = b.out
+            t_p = _time_ms(torch, b.run_decompress)
             nb = sum(o.numel() for o in outs)
             okp = all(torch.equal(outs[i].view(-1, chunk), srcs[i].view(-1, chunk)[ids[i].long()]) for i in range(b.n))
-            r.update({"page_decode_ms": t_p, "page_decode_GBps": nb / t_p / 1e6, "pages": nb // chunk, "page_decode_bit_exact": bool(okp)})
+            comp_read = sum(sizes) * (nb / raw)
+            r.update({"page_decode_ms": t_p, "page_decode_GBps": nb / t_p / 1e6, "pages": nb // chunk, "page_decode_bit_exact": bool(okp),
+                      "page_decode_traffic_frac_of_hbm_peak": (nb + comp_read) / t_p / 1e6 / HBM_PEAK_GBPS})
         out[name] = r
         del b
         torch.cuda.empty_cache()

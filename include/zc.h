@@ -114,6 +114,9 @@ typedef struct {
     uint64_t comp_capacity;     /* compress: bytes available at d_comp */
     void *d_dst;                /* decompress: elements out (device) */
     void *d_scales_out;         /* decompress, FP4 only */
+    const uint32_t *d_chunk_ids;/* decompress: device list of chunk ids to decode densely into d_dst (chunk
+                                   ids[i] -> d_dst + i*chunk_bytes), or NULL for the whole tensor */
+    uint32_t n_chunk_ids, reserved;
     uint64_t out_bytes;         /* container size */
     zc_info info;
 } zc_tensor;
@@ -165,7 +168,9 @@ zc_status zc_decompress_chunks(const void *d_comp, uint64_t comp_bytes, const zc
                                const void *d_xor_base, void *stream);
 
 /* Whole-set decode in one launch: every tensor's d_comp/info/d_dst (and d_xor_base,
- * d_scales_out) must be set.  All tensors must share format and streams.  The per-tensor
+ * d_scales_out) must be set.  All tensors must share format and streams.  A tensor with
+ * d_chunk_ids set decodes only those chunks, densely (random-access page decode of a whole
+ * K/V cache in one launch).  The per-tensor
  * descriptors and the work list are uploaded to d_ws with a blocking copy (the stream is
  * synchronised before the launch, not after it). */
 zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors,
@@ -179,8 +184,8 @@ zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors,
 typedef struct {
     uint32_t format, streams, n_tensors;
     uint32_t n_fast_work, n_work;               /* work items of the specialised / generic kernel */
-    uint32_t fast_kernel;                       /* 0 none, 1 FP8 specialised, 2 64-lane full-chunk kernel */
-    uint32_t fast_exp_kind, fast_sm_kind, n_rings, xor_delta, reserved;
+    uint32_t fast_kernel;                       /* 0 none, 1 FP8 specialised, 2 64-lane full-chunk kernel, 3 FP8 small chunks */
+    uint32_t fast_exp_kind, fast_sm_kind, n_rings /* kernel 3: slots per workgroup */, xor_delta, reserved;
     uint64_t fast_work_offset, work_offset;     /* byte offsets of the two work lists in d_ws */
 } zc_batch_plan;
 zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors, void *d_ws, uint64_t ws_bytes,

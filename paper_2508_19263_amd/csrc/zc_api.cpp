@@ -399,6 +399,32 @@ uint32_t s64_rings(const zc_info &info)
     return huff < 1 ? 1 : huff;
 }
 
+// Can the sub-wavefront FP8 kernel (S < 64, e.g. K/V pages) decode this container's full chunks
+// into a destination of dst_bytes?
+bool fp8_sub_ok(const zc_info &info, uint64_t dst_bytes)
+{
+    if (info.format != ZC_FMT_FP8_E4M3 || info.streams < 4 || info.streams > 32) return false;
+    if (info.chunk_bytes % (16 * info.streams) || info.chunk_bytes > (1u << 24)) return false;
+    if (info.mode[0] != ZC_MODE_HUFF || refill_period(16, info.max_len[0]) != 4) return false;
+    const TensorDev d = make_desc(info);
+    if (d.kind[1] != 1 && d.kind[1] != 2) return false;
+    // one 32-bit offset space per buffer: payload, destination and (for a delta) the base tensor
+    if (info.total_bytes - info.payload_offset > 0xF0000000ull || dst_bytes > 0xF0000000ull) return false;
+    if (info.xor_delta && info.n_elems > 0xF0000000ull) return false;
+    return true;
+}
+
+// slots one workgroup of the sub-wavefront kernel takes: enough passes to amortise its table
+// build, few enough to leave >= ~2048 workgroups
+uint32_t sub_slots_per_group(uint32_t streams, uint64_t slots)
+{
+    const uint32_t per_pass = kWavesPerGroup * (64 / streams);
+    uint64_t passes = slots / (2048ull * per_pass);
+    if (passes < 1) passes = 1;
+    if (passes > 8) passes = 8;
+    return (uint32_t)passes * per_pass;
+}
+
 zc_status parse_info(const uint8_t *c, uint64_t have, uint64_t comp_bytes, zc_info *out)
 {
     if (have < kHeaderBytes || comp_bytes < kHeaderBytes) return ZC_ERR_CORRUPT;
@@ -476,11 +502,20 @@ zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *
     TensorDev d = make_desc(info);
     d.comp = (uint8_t *)d_comp; d.dst = (uint8_t *)d_dst; d.scales_out = (uint8_t *)d_scales_out;
     d.base = info.xor_delta ? (const uint8_t *)d_xor_base : nullptr;
+    d.ids = by_ids ? d_ids : nullptr; d.n_ids = by_ids ? n_ids : 0; d.dst_bytes = need;
     const uint32_t cpi = chunks_per_work_item(info.streams);
     const FastKind fk = fast_kind(info);
     uint32_t first_slot = 0;
     const uint32_t rings = s64_rings(info);
-    if ((fk.ok || rings) && !by_ids) {
+    const uint64_t elems_per_chunk = (uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(info.format);
+    if (fp8_sub_ok(info, need) && (!by_ids || info.n_elems % elems_per_chunk == 0)) {
+        // small chunks (pages): several per wavefront.  An id list may name a short last chunk, which
+        // this kernel does not take, so lists go here only when every chunk is whole.
+        const uint32_t n_fast = by_ids ? n_ids : (uint32_t)(info.n_elems / elems_per_chunk);
+        const uint32_t spg = sub_slots_per_group(info.streams, n_fast);
+        LAUNCH_TRY(launch_decode_fp8_sub(info.streams, info.xor_delta != 0, nullptr, nullptr, (n_fast + spg - 1) / spg, &d, spg, stream));
+        first_slot = n_fast;
+    } else if ((fk.ok || rings) && !by_ids) {
         // full chunks through a specialised kernel, a short last chunk through the generic one
         const uint32_t n_full = (uint32_t)(info.n_elems / ((uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(info.format)));
         const uint32_t n_fast = (n_full + kWavesPerGroup - 1) / kWavesPerGroup;
@@ -490,7 +525,7 @@ zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *
     }
     if (first_slot < slots) {
         const uint32_t n_work = (slots - first_slot + cpi - 1) / cpi;
-        LAUNCH_TRY(launch_decode(info.format, nullptr, nullptr, n_work, cpi, &d, first_slot, by_ids ? d_ids : nullptr, n_ids, stream));
+        LAUNCH_TRY(launch_decode(info.format, nullptr, nullptr, n_work, cpi, &d, first_slot, stream));
     }
     return ZC_OK;
 }
@@ -649,9 +684,17 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
         const FastKind k = fast_kind(tensors[t].info);
         if (!k.ok || k.exp_kind != fk.exp_kind || k.sm_kind != fk.sm_kind || tensors[t].info.xor_delta != tensors[0].info.xor_delta) fk.ok = false;
     }
+    // small chunks (S < 64): the sub-wavefront FP8 kernel when every tensor qualifies
+    bool sub = S < 64;
+    for (uint32_t t = 0; t < n_tensors && sub; t++) {
+        const zc_info &info = tensors[t].info;
+        const uint64_t need = tensors[t].d_chunk_ids ? (uint64_t)tensors[t].n_chunk_ids * info.chunk_bytes : info.n_elems;
+        if (!fp8_sub_ok(info, need) || info.xor_delta != tensors[0].info.xor_delta) sub = false;
+        if (tensors[t].d_chunk_ids && info.n_elems % info.chunk_bytes) sub = false;
+    }
     // otherwise the 64-lane full-chunk kernel, when every tensor qualifies
     uint32_t rings = 0;
-    if (!fk.ok) {
+    if (!fk.ok && !sub) {
         rings = 2;
         uint32_t most = 1;
         for (uint32_t t = 0; t < n_tensors && rings; t++) {
@@ -661,7 +704,10 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
         }
         if (rings) rings = most;
     }
-    const bool fast = fk.ok || rings != 0;
+    const bool fast = fk.ok || rings != 0 || sub;
+    uint64_t all_slots = 0;
+    for (uint32_t t = 0; t < n_tensors; t++) all_slots += tensors[t].d_chunk_ids ? tensors[t].n_chunk_ids : tensors[t].info.n_chunks;
+    const uint32_t spg = sub ? sub_slots_per_group(S, all_slots) : kWavesPerGroup;
     std::vector<TensorDev> descs(n_tensors);
     std::vector<WorkItem> fast_work, work;
     for (uint32_t t = 0; t < n_tensors; t++) {
@@ -675,13 +721,18 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
         descs[t] = make_desc(info);
         descs[t].comp = (uint8_t *)x.d_comp; descs[t].dst = (uint8_t *)x.d_dst; descs[t].scales_out = (uint8_t *)x.d_scales_out;
         descs[t].base = info.xor_delta ? (const uint8_t *)x.d_xor_base : nullptr;
+        const uint64_t raw = (info.n_elems * (uint64_t)elem_bits(fmt) + 7) / 8;
+        descs[t].ids = x.d_chunk_ids; descs[t].n_ids = x.d_chunk_ids ? x.n_chunk_ids : 0;
+        descs[t].dst_bytes = x.d_chunk_ids ? (uint64_t)x.n_chunk_ids * info.chunk_bytes : raw;
+        const uint32_t slots = x.d_chunk_ids ? x.n_chunk_ids : info.n_chunks;
         uint32_t first_generic = 0;
-        if (fast) {
+        if (fast && (sub || !x.d_chunk_ids)) {
             const uint32_t n_full = (uint32_t)(info.n_elems / ((uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(fmt)));
-            for (uint32_t c = 0; c < n_full; c += kWavesPerGroup) fast_work.push_back({t, c});
-            first_generic = n_full;
-        }
-        for (uint32_t c = first_generic; c < info.n_chunks; c += cpi) work.push_back({t, c});
+            const uint32_t n_fast = x.d_chunk_ids ? slots : n_full;        // lists reach here only when every chunk is whole
+            for (uint32_t c = 0; c < n_fast; c += spg) fast_work.push_back({t, c});
+            first_generic = n_fast;
+        }                                                                   // an id list with 64-lane chunks goes through the generic kernel
+        for (uint32_t c = first_generic; c < slots; c += cpi) work.push_back({t, c});
     }
     const uint64_t descs_bytes = align256((uint64_t)n_tensors * sizeof(TensorDev));
     const uint64_t fast_bytes = align256(fast_work.size() * sizeof(WorkItem));
@@ -695,7 +746,7 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
     plan->format = fmt; plan->streams = S; plan->n_tensors = n_tensors;
     plan->n_fast_work = (uint32_t)fast_work.size(); plan->n_work = (uint32_t)work.size();
     plan->fast_exp_kind = (uint32_t)fk.exp_kind; plan->fast_sm_kind = (uint32_t)fk.sm_kind; plan->xor_delta = tensors[0].info.xor_delta;
-    plan->fast_kernel = fk.ok ? 1u : (rings ? 2u : 0u); plan->n_rings = rings;
+    plan->fast_kernel = fk.ok ? 1u : (rings ? 2u : (sub ? 3u : 0u)); plan->n_rings = sub ? spg : rings;
     plan->fast_work_offset = descs_bytes; plan->work_offset = descs_bytes + fast_bytes;
     return ZC_OK;
 }
@@ -712,10 +763,13 @@ zc_status zc_decompress_batch_run(const zc_batch_plan *plan, const void *d_ws, v
     else if (plan->n_fast_work && plan->fast_kernel == 2)
         LAUNCH_TRY(launch_decode_s64(plan->format, plan->n_rings, plan->xor_delta != 0, (const TensorDev *)ws,
                                      (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, stream));
+    else if (plan->n_fast_work && plan->fast_kernel == 3)
+        LAUNCH_TRY(launch_decode_fp8_sub(plan->streams, plan->xor_delta != 0, (const TensorDev *)ws,
+                                         (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, plan->n_rings, stream));
     else if (plan->n_fast_work) return ZC_ERR_INVALID_ARG;
     if (plan->n_work)
         LAUNCH_TRY(launch_decode(plan->format, (const TensorDev *)ws, (const WorkItem *)(ws + plan->work_offset), plan->n_work,
-                                 chunks_per_work_item(plan->streams), nullptr, 0, nullptr, 0, stream));
+                                 chunks_per_work_item(plan->streams), nullptr, 0, stream));
     return ZC_OK;
 }
 

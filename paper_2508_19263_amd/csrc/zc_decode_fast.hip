@@ -473,6 +473,166 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const Tens
     return launch_s64_x<ZC_FMT_FP4_E2M1_MX>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
 }
 
+// ---------------------------------------------------------------------------------------
+// FP8 with fewer than 64 lanes per chunk (small chunks such as K/V-cache pages): a wavefront
+// decodes 64/S chunks at once, one per S-lane group, optionally picked from an id list and
+// written densely.  Same per-lane work as k_decode_fp8; what differs is that every stream
+// position is per group (vector registers, prefix counts masked to the group) and that one
+// buffer resource spans the whole payload, with the group's stream offset in the vector
+// offset.  Each group owns 16*S words of the wavefront's 1024-word ring, refilled 4*S words
+// (one 16-byte load per lane) at a time.
+template <int S, bool XOR>
+__global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single,
+                                                        uint32_t slots_per_group)
+{
+    constexpr uint32_t kGroups = 64 / S;
+    constexpr uint32_t kSeg = 4 * S, kRing = 16 * S;             // words per group
+    __shared__ uint16_t lut[256];
+    __shared__ __attribute__((aligned(16))) uint32_t ring[kWavesPerGroup][kRingWords];
+    __shared__ Canon16 canon;
+    __shared__ TensorDev dsh;
+    WorkItem it;
+    if (use_single) { it.tensor = 0; it.first = blockIdx.x * slots_per_group; }
+    else it = work[blockIdx.x];
+    if (threadIdx.x == 0) dsh = use_single ? single : descs[it.tensor];
+    __syncthreads();
+    const TensorDev &d = dsh;
+    build_canon16(canon, d.comp + d.table_off[0]);
+    {
+        const uint32_t lmax = d.lmax[0] < 8u ? d.lmax[0] : 8u;
+        const uint32_t e = canon_decode(canon, threadIdx.x, lmax);
+        lut[threadIdx.x] = (uint16_t)((e & 31u) | (((e >> 8) << 3) << 8));
+    }
+    __syncthreads();
+
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t s = lane & (S - 1), grp = lane / S;
+    const uint64_t gmask = ((1ull << S) - 1) << (lane - s);
+    const uint32_t cb = uniform32(d.chunk_bytes);                // one element per byte
+    const uint64_t n_elems = uniform64(d.n_elems);
+    const uint32_t n_full = (uint32_t)(n_elems / cb);
+    const uint32_t *ids = reinterpret_cast<const uint32_t *>(uniform64((uint64_t)d.ids));
+    const uint64_t dst_bytes = uniform64(d.dst_bytes);
+    const uint32_t n_slots = ids ? uniform32(d.n_ids) : uniform32(d.n_chunks);
+    const uint8_t *comp = reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.comp));
+    const uint64_t payload = uniform64(d.payload_off), total = uniform64(d.total_bytes);
+    if (total < payload || total - payload > 0xFFFFFFF0ull || dst_bytes > 0xFFFFFFF0ull) return;   // the host never launches this
+    const uint32_t pay_bytes = (uint32_t)(total - payload);
+    const __amdgpu_buffer_rsrc_t ps = make_rsrc(comp + payload, pay_bytes);
+    const __amdgpu_buffer_rsrc_t ds = make_rsrc(reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.dst)), (uint32_t)dst_bytes);
+    const uint64_t base_bytes = XOR ? n_elems : 0;
+    const __amdgpu_buffer_rsrc_t bs = make_rsrc(XOR ? reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.base)) : comp,
+                                                base_bytes > 0xFFFFFFF0ull ? 0u : (uint32_t)base_bytes);
+    const uint32_t *index0 = reinterpret_cast<const uint32_t *>(comp + uniform32(d.index_off[0]));
+    const uint32_t *index1 = reinterpret_cast<const uint32_t *>(comp + uniform32(d.index_off[1]));
+    const bool sm_raw = uniform32(d.kind[1]) == 2;
+    const uint32_t rows = cb / (16 * S);
+    const uint32_t one = 1;
+    const char *lut_bytes = reinterpret_cast<const char *>(lut);
+    char *const ring_bytes = reinterpret_cast<char *>(&ring[wave][0]) + grp * (kRing * 4);
+
+    // the workgroup owns slots [first, first + slots_per_group): each pass takes 4 waves x kGroups of them
+    for (uint32_t pass = 0; pass * kWavesPerGroup * kGroups < slots_per_group; pass++) {
+        const uint32_t slot = it.first + (pass * kWavesPerGroup + wave) * kGroups + grp;
+        uint32_t chunk = slot;
+        bool alive = slot < n_slots && (pass * kWavesPerGroup + wave) * kGroups + grp < slots_per_group;
+        if (ids && alive) chunk = ids[slot];
+        alive = alive && chunk < n_full;                         // short last chunk: the host sends it to the generic kernel
+        uint32_t e_off = pay_bytes, m_off = pay_bytes;           // out of range: loads return 0
+        if (alive) {
+            const uint64_t a0 = index0[chunk], b0 = index0[chunk + 1], a1 = index1[chunk], b1 = index1[chunk + 1];
+            if (a0 <= b0 && a1 <= b1 && 16 * b1 <= pay_bytes && 16 * b0 <= pay_bytes && (b1 - a1) * 16 >= cb / 2) { e_off = (uint32_t)(16 * a0); m_off = (uint32_t)(16 * a1); }
+            else alive = false;
+        }
+        const uint32_t out_off = slot * cb, base_off = chunk * cb;
+
+        // ring prologue: the group's first 16*S words (each lane 4 loads of 16 bytes)
+#pragma unroll
+        for (uint32_t q = 0; q < 4; q++) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(ps, (int)(e_off + (q * kSeg + s * 4) * 4), 0, 0);
+            *reinterpret_cast<u32x4 *>(ring_bytes + (q * kSeg + s * 4) * 4) = v;
+        }
+        uint64_t W = (uint64_t)(*reinterpret_cast<const uint32_t *>(ring_bytes + s * 4)) << 32;    // step 0: lane s takes word s
+        uint32_t c = 32, wpos = S, wbase = 0, pslot = 0;
+        bool pending = false;
+        u32x4 pv = {0, 0, 0, 0};
+        for (uint32_t row = 0; row < rows; row++) {
+            if (pending) { *reinterpret_cast<u32x4 *>(ring_bytes + (pslot + s * 4) * 4) = pv; pending = false; }
+            if (wpos - wbase >= kSeg) {
+                pv = __builtin_amdgcn_raw_buffer_load_b128(ps, (int)(e_off + (wbase + kRing + s * 4) * 4), 0, 0);
+                pslot = wbase & (kRing - 1);
+                wbase += kSeg;
+                pending = true;
+            }
+            uint32_t m[4];
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                uint32_t A, B;
+                if (sm_raw) {
+                    const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(ps, (int)(m_off + ((row * S + s) * 2 + h) * 4), 0, 0);
+                    A = ((w << 4) & 0x80808080u) | (w & 0x07070707u);
+                    B = (w & 0x80808080u) | ((w >> 4) & 0x07070707u);
+                    m[2 * h] = perm(A, B, 0x01050004u);
+                    m[2 * h + 1] = perm(A, B, 0x03070206u);
+                } else {
+                    const uint32_t w = __brev(__builtin_amdgcn_raw_buffer_load_b32(ps, (int)(m_off + ((row * 2 + h) * S + s) * 4), 0, 0));
+                    A = ((w << 4) & 0x80808080u) | (w & 0x07070707u);
+                    B = (w & 0x80808080u) | ((w >> 4) & 0x07070707u);
+                    m[2 * h] = perm(A, B, 0x06020703u);
+                    m[2 * h + 1] = perm(A, B, 0x04000501u);
+                }
+            }
+            uint32_t o[4];
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                uint32_t x = (uint32_t)(W >> c);
+                const uint32_t t0 = *reinterpret_cast<const uint16_t *>(lut_bytes + byte0_shl(x, one)); x >>= (t0 & 31u);
+                const uint32_t t1 = *reinterpret_cast<const uint16_t *>(lut_bytes + byte0_shl(x, one)); x >>= (t1 & 31u);
+                const uint32_t t2 = *reinterpret_cast<const uint16_t *>(lut_bytes + byte0_shl(x, one)); x >>= (t2 & 31u);
+                const uint32_t t3 = *reinterpret_cast<const uint16_t *>(lut_bytes + byte0_shl(x, one));
+                c += (t0 + t1 + t2 + t3) & 0xFFu;
+                o[g] = perm(t1, t0, 0x0C0C0501u) | perm(t3, t2, 0x05010C0Cu) | m[g];
+                const bool need = c >= 32;
+                const uint64_t bm = __ballot(need) & gmask;
+                const uint32_t w = *reinterpret_cast<const uint32_t *>(ring_bytes + ((prefix_count64(bm) + wpos) & (kRing - 1)) * 4);
+                W = need ? ((W >> 32) | ((uint64_t)w << 32)) : W;
+                c = need ? c - 32 : c;
+                wpos += (uint32_t)__popcll(bm);
+            }
+            u32x4 v = {o[0], o[1], o[2], o[3]};
+            if (XOR) v ^= __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(base_off + (row * S + s) * 16), 0, 0);
+            if (alive) __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(out_off + (row * S + s) * 16), 0, 0);
+        }
+    }
+}
+
+template <int S>
+static int launch_fp8_sub_s(bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single,
+                            uint32_t slots_per_group, hipStream_t st)
+{
+    if (xor_delta) hipLaunchKernelGGL((k_decode_fp8_sub<S, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, slots_per_group);
+    else hipLaunchKernelGGL((k_decode_fp8_sub<S, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, slots_per_group);
+    return (int)hipGetLastError();
+}
+
+// FP8, S in {4, 8, 16, 32}, full chunks, exponent refill period 4, sign+mantissa flat or raw.
+// Each workgroup takes slots_per_group consecutive slots (chunk ids, or positions in d_ids).
+int launch_decode_fp8_sub(uint32_t streams, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+                          const TensorDev *single, uint32_t slots_per_group, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    const TensorDev s = single ? *single : TensorDev{};
+    const int use_single = single ? 1 : 0;
+    switch (streams) {
+    case 4: return launch_fp8_sub_s<4>(xor_delta, d_descs, d_work, n_work, s, use_single, slots_per_group, st);
+    case 8: return launch_fp8_sub_s<8>(xor_delta, d_descs, d_work, n_work, s, use_single, slots_per_group, st);
+    case 16: return launch_fp8_sub_s<16>(xor_delta, d_descs, d_work, n_work, s, use_single, slots_per_group, st);
+    case 32: return launch_fp8_sub_s<32>(xor_delta, d_descs, d_work, n_work, s, use_single, slots_per_group, st);
+    }
+    return (int)hipErrorInvalidValue;
+}
+
 template <int EK, int MK>
 static int launch_fp8_x(bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single, hipStream_t st)
 {

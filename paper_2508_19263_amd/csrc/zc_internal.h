@@ -35,6 +35,8 @@ struct alignas(16) TensorDev {
     uint8_t *comp;            // container
     uint8_t *dst;             // decompress: elements out
     uint8_t *scales_out;      // decompress, FP4
+    const uint32_t *ids;      // decompress: chunk id list (slot i decodes chunk ids[i]) or null (slot i = chunk i)
+    uint64_t dst_bytes;       // decompress: bytes that may be written at dst
     uint64_t n_elems;
     uint64_t total_bytes;     // decompress: container size (bounds for reads)
     uint64_t payload_off;
@@ -42,11 +44,12 @@ struct alignas(16) TensorDev {
     uint32_t chunk_bytes;
     uint32_t table_off[kMaxFields];
     uint32_t index_off[kMaxFields];
+    uint32_t n_ids;           // decompress: entries of ids
     uint32_t units_off;       // compress: first entry of this tensor in the units array (field-major, n_chunks each)
     uint32_t streams;         // S
     uint8_t mode[4], lmax[4], konst[4], period[4];
-    uint8_t kind[4];          // decode: how the specialised kernels read the field (0 table, 1 flat code, 2 raw, 3 constant)
-    uint8_t pad_[12];
+    uint8_t kind[4];          // how the specialised kernels treat the field (0 table, 1 flat code, 2 raw, 3 constant)
+    uint8_t pad_[8];
 };
 
 struct WorkItem { uint32_t tensor, first; };   // `first`: first chunk / block of the item
@@ -74,10 +77,13 @@ int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, cons
 int launch_encode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
                   const uint32_t *d_enc_tables, void *stream);
 int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
-                  const TensorDev *single, uint32_t first_slot, const uint32_t *d_ids, uint32_t n_ids, void *stream);
+                  const TensorDev *single, uint32_t first_slot, void *stream);
 // specialised FP8 decode of full chunks (zc_decode_fast.hip); exp_kind 0 = single, 1 = pair lookups; sm_kind 0 = flat, 1 = raw
 int launch_decode_fp8_fast(int exp_kind, int sm_kind, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                            const TensorDev *single, void *stream);
+// FP8, fewer than 64 lanes per chunk (pages), optional id list (zc_decode_fast.hip)
+int launch_decode_fp8_sub(uint32_t streams, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+                          const TensorDev *single, uint32_t slots_per_group, void *stream);
 // any format, 64 lanes per chunk, full chunks (zc_decode_fast.hip); n_rings = element fields that are table decoded (1..2)
 int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                       const TensorDev *single, void *stream);

@@ -459,7 +459,7 @@ __device__ __forceinline__ DecField open_stream(const TensorDev &d, int f, uint3
 
 template <int FMT>
 __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single,
-                                                uint32_t first_slot, const uint32_t *ids, uint32_t n_ids)
+                                                uint32_t first_slot)
 {
     using F_ = Fmt<FMT>;
     __shared__ FieldTab tab[F_::NF];
@@ -478,7 +478,8 @@ __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const Wo
     const uint32_t slot = it.first + wave * (64 / S) + L.grp;
     uint32_t chunk = slot;
     bool valid = slot < d.n_chunks;
-    if (ids) { valid = slot < n_ids; chunk = valid ? ids[slot] : 0; valid = valid && chunk < d.n_chunks; }
+    const uint32_t *ids = d.ids;
+    if (ids) { valid = slot < d.n_ids; chunk = valid ? ids[slot] : 0; valid = valid && chunk < d.n_chunks; }
     const uint64_t E = (uint64_t)d.chunk_bytes * 8 / F_::EB;
     const uint64_t first = (uint64_t)chunk * E;
     const uint32_t n = valid ? (uint32_t)(d.n_elems - first < E ? d.n_elems - first : E) : 0;
@@ -542,15 +543,15 @@ __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const Wo
 }
 
 int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t,
-                  const TensorDev *single, uint32_t first_slot, const uint32_t *d_ids, uint32_t n_ids, void *stream)
+                  const TensorDev *single, uint32_t first_slot, void *stream)
 {
     if (n_work == 0) return 0;
     hipStream_t st = (hipStream_t)stream;
     TensorDev s = single ? *single : TensorDev{};
     const int use_single = single ? 1 : 0;
-    if (fmt == ZC_FMT_BF16) hipLaunchKernelGGL(k_decode<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot, d_ids, n_ids);
-    else if (fmt == ZC_FMT_FP8_E4M3) hipLaunchKernelGGL(k_decode<ZC_FMT_FP8_E4M3>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot, d_ids, n_ids);
-    else hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_MX>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot, d_ids, n_ids);
+    if (fmt == ZC_FMT_BF16) hipLaunchKernelGGL(k_decode<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot);
+    else if (fmt == ZC_FMT_FP8_E4M3) hipLaunchKernelGGL(k_decode<ZC_FMT_FP8_E4M3>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot);
+    else hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_MX>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot);
     return (int)hipGetLastError();
 }
 

@@ -54,6 +54,7 @@ class StatsOut(C.Structure):
 class Tensor(C.Structure):
     _fields_ = [("d_src", C.c_void_p), ("d_xor_base", C.c_void_p), ("d_scales", C.c_void_p), ("n_elems", C.c_uint64),
                 ("d_comp", C.c_void_p), ("comp_capacity", C.c_uint64), ("d_dst", C.c_void_p), ("d_scales_out", C.c_void_p),
+                ("d_chunk_ids", C.c_void_p), ("n_chunk_ids", C.c_uint32), ("reserved", C.c_uint32),
                 ("out_bytes", C.c_uint64), ("info", Info)]
 
 
@@ -275,6 +276,23 @@ class Batch:
         for i in range(self.n):
             self.arr[i].d_dst = self.out[i].data_ptr()
             self.arr[i].d_scales_out = self.scales_out[i].data_ptr() if self.scales_out else None
+
+    def set_chunk_ids(self, ids):
+        """ids: one int32 CUDA tensor of chunk ids per tensor (or None to decode whole tensors again).
+        The next plan/decompress decodes only those chunks, densely, into fresh output buffers."""
+        dev = self.arena.device
+        self.ids = ids
+        if ids is None:
+            self.out = None
+            for i in range(self.n):
+                self.arr[i].d_chunk_ids = None
+                self.arr[i].n_chunk_ids = 0
+            return
+        self.out = [torch.empty(max(ids[i].numel() * self.p.chunk_bytes, 16), dtype=torch.uint8, device=dev) for i in range(self.n)]
+        for i in range(self.n):
+            self.arr[i].d_chunk_ids = ids[i].data_ptr()
+            self.arr[i].n_chunk_ids = ids[i].numel()
+            self.arr[i].d_dst = self.out[i].data_ptr()
 
     def decompress(self):
         if self.out is None:

@@ -368,3 +368,29 @@ def test_fp8_short_exponent_codes_take_the_general_path():
         x = torch.from_numpy(((e << 3) | rng.integers(0, 8, n).astype(np.uint8) | (rng.integers(0, 2, n).astype(np.uint8) << 7)).astype(np.uint8))
         for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
             check_case(zc.FMT_FP8_E4M3, n, 4096, 64, policy, data=(x, None), tag="fp8-short-%d" % len(probs))
+
+
+def test_batched_page_decode():
+    # a whole (small) K/V cache: every tensor's page sample decoded densely in one launch
+    tensors = []
+    for layer in range(3):
+        k, v = wl.fp8_kv_pair(batch=1, heads=2, tokens=512, seed=90 + layer)
+        tensors += [k.reshape(-1), v.reshape(-1)]
+    counts = [t.numel() for t in tensors]
+    n_pages = counts[0] // 2048
+    for S in (8, 16):
+        b = zc.Batch([t.to(DEV) for t in tensors], counts, zc.params(zc.FMT_FP8_E4M3, 2048, streams=S))
+        b.compress()
+        ids = [wl.page_sample(n_pages, 0.25, seed=S * 100 + i) for i in range(len(tensors))]
+        b.set_chunk_ids([i.to(DEV) for i in ids])
+        outs = b.decompress()
+        torch.cuda.synchronize()
+        for i, t in enumerate(tensors):
+            want = t.reshape(n_pages, 2048)[ids[i].long()]
+            assert torch.equal(outs[i].cpu().reshape(-1, 2048), want), (S, i)
+        # and back to whole tensors with the same batch object
+        b.set_chunk_ids(None)
+        outs = b.decompress()
+        torch.cuda.synchronize()
+        for i, t in enumerate(tensors):
+            assert torch.equal(outs[i].cpu()[:counts[i]], t)

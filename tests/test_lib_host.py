@@ -27,7 +27,7 @@ def test_struct_sizes_match_the_header():
     assert C.sizeof(zc.Params) == 4 * 8
     assert C.sizeof(zc.Info) == 8 * 4 + 3 * 8 + 6 * 8 + 12 + 768 + 4      # +4: tail padding to 8
     assert C.sizeof(zc.FieldStats) == 16 + 8 + 2048 + 256 + 8 + 8 + 8 + 8 + 8
-    assert C.sizeof(zc.Tensor) == 9 * 8 + C.sizeof(zc.Info)
+    assert C.sizeof(zc.Tensor) == 11 * 8 + C.sizeof(zc.Info)
 
 
 def test_code_construction_matches_oracle_on_random_histograms():
