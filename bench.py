@@ -141,6 +141,7 @@ def main():
             ev[0].record()
         if not args.decode_only:
             batch.compress()
+            torch.cuda.synchronize()      # decompress is timed from an idle stream: upload of its plan, then the kernel
         if ev:
             ev[1].record()
         if not args.decode_only:
