@@ -331,16 +331,6 @@ __device__ __forceinline__ void huff_run(HuffStream &H, const FieldTab &T, uint3
     }
 }
 
-// reverse the bit order inside every SB-bit group of a word (a flat code is the symbol value
-// written most significant bit first into an LSB-first string)
-template <int SB>
-__device__ __forceinline__ uint32_t reverse_in_groups(uint32_t w)
-{
-    if (SB == 8) return __builtin_amdgcn_perm(0, __brev(w), 0x00010203u);          // all bits reversed, then bytes back in order
-    if (SB == 4) { w = ((w >> 1) & 0x55555555u) | ((w & 0x55555555u) << 1); return ((w >> 2) & 0x33333333u) | ((w & 0x33333333u) << 2); }
-    return ((w >> 1) & 0x55555555u) | ((w & 0x55555555u) << 1);
-}
-
 // one field of one run when it is not table decoded.  words_per_run = G*SB/32.
 template <int SB, int G>
 __device__ __forceinline__ void plain_run(uint32_t kind, __amdgpu_buffer_rsrc_t rs, uint32_t row, uint32_t lane, uint64_t konst, uint64_t &P0, uint64_t &P1)

@@ -204,4 +204,15 @@ __device__ __forceinline__ uint64_t splat(uint32_t v, int sb)
 }
 
 
+// reverse the bit order inside every SB-bit group of a word (a flat code is the symbol value
+// written most significant bit first into an LSB-first string)
+template <int SB>
+__device__ __forceinline__ uint32_t reverse_in_groups(uint32_t w)
+{
+    if (SB == 8) return __builtin_amdgcn_perm(0, __brev(w), 0x00010203u);          // all bits reversed, then bytes back in order
+    if (SB == 4) { w = ((w >> 1) & 0x55555555u) | ((w & 0x55555555u) << 1); return ((w >> 2) & 0x33333333u) | ((w & 0x33333333u) << 2); }
+    return ((w >> 1) & 0x55555555u) | ((w & 0x55555555u) << 1);
+}
+
+
 }  // namespace zc

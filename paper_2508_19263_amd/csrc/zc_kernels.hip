@@ -169,6 +169,22 @@ __device__ __forceinline__ void enc_run(EncField &F, uint32_t period, uint64_t P
     }
 }
 
+// One 64-bit run of a field whose code is flat (the canonical code of a symbol is the symbol),
+// when every lane of the wavefront has a whole run: each refill step hands every lane exactly
+// one word, so the run's two words sit at wpos + h*S + lane and all other encoder state
+// (accumulator, look-ahead, owed words) is back at zero after the run, exactly as enc_run
+// would leave it.
+template <bool WRITE, int SB>
+__device__ __forceinline__ void enc_flat_run(EncField &F, uint64_t P, uint8_t *stream, const Lanes &L, uint32_t S)
+{
+    if (WRITE) {
+        uint32_t *w = reinterpret_cast<uint32_t *>(stream) + F.wpos + L.s;
+        w[0] = reverse_in_groups<SB>((uint32_t)P);
+        w[S] = reverse_in_groups<SB>((uint32_t)(P >> 32));
+    }
+    F.wpos += 2 * S;
+}
+
 // write the words still owed to the decoder, then zero the tail of the last 16-byte unit
 template <bool WRITE>
 __device__ __forceinline__ uint32_t enc_finish(EncField &F, uint8_t *stream, const Lanes &L)
@@ -228,14 +244,16 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
             split_run<FMT>(v, P0, P1);
         }
         const bool full = __all(nsym == (uint32_t)F_::G);
-        if (m0 == ZC_MODE_HUFF) {
+        if (m0 == ZC_MODE_HUFF && d.kind[0] == 1 && full) enc_flat_run<WRITE, F_::SB>(F0, P0, stream[0], L, S);
+        else if (m0 == ZC_MODE_HUFF) {
             if (full) enc_run<WRITE, F_::SB, F_::G, true>(F0, d.period[0], P0, 0, nsym, enc[0], stream[0], L);
             else enc_run<WRITE, F_::SB, F_::G, false>(F0, d.period[0], P0, 0, nsym, enc[0], stream[0], L);
         } else if (m0 == ZC_MODE_RAW && WRITE && nsym) {
             reinterpret_cast<uint64_t *>(stream[0])[run] = P0;
             if ((run & 1) == 0 && done + F_::G >= n) reinterpret_cast<uint64_t *>(stream[0])[run + 1] = 0;
         }
-        if (m1 == ZC_MODE_HUFF) {
+        if (m1 == ZC_MODE_HUFF && d.kind[1] == 1 && full) enc_flat_run<WRITE, F_::SB>(F1, P1, stream[1], L, S);
+        else if (m1 == ZC_MODE_HUFF) {
             if (full) enc_run<WRITE, F_::SB, F_::G, true>(F1, d.period[1], P1, 0, nsym, enc[1], stream[1], L);
             else enc_run<WRITE, F_::SB, F_::G, false>(F1, d.period[1], P1, 0, nsym, enc[1], stream[1], L);
         } else if (m1 == ZC_MODE_RAW && WRITE && nsym) {
