@@ -394,3 +394,13 @@ def test_batched_page_decode():
         torch.cuda.synchronize()
         for i, t in enumerate(tensors):
             assert torch.equal(outs[i].cpu()[:counts[i]], t)
+
+
+def test_odd_geometries():
+    # chunk sizes that are not whole rows of any specialised kernel, every lane count, ragged sizes
+    for fmt, cbs in ((zc.FMT_FP8_E4M3, (16, 1008, 48 * 1024 + 16)), (zc.FMT_BF16, (16, 2064)), (zc.FMT_FP4_E2M1_MX, (256, 768))):
+        for cb in cbs:
+            for S in (2, 4, 16, 32, 64):
+                E = cb * 8 // zc.elem_bits(fmt)
+                n = 5 * E + (E // 3 // 32) * 32 + (0 if fmt == zc.FMT_FP4_E2M1_MX else 7)
+                check_case(fmt, n, cb, S, zc.POLICY_HUFF_ALL if S != 16 else zc.POLICY_AUTO, tag="odd")
