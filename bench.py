@@ -107,6 +107,7 @@ def main():
     ap.add_argument("--policy", choices=["huff_all", "auto"], default="huff_all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-only", action="store_true", help="timed steps run only the decode kernel (for profiling)")
+    ap.add_argument("--no-verify", action="store_true", help="skip the round-trip check (kernel experiments only)")
     ap.add_argument("--other-workloads", action="store_true",
                     help="also time configs 1, 3, 4 and 5 (reported under 'other_workloads' in the same JSON line)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -179,7 +180,7 @@ def main():
         del cal, cal_out
 
     # bit-exact round trip of the whole set
-    ok = all(torch.equal(o[:n], s) for o, s, n in zip(batch.out, srcs, counts))
+    ok = args.no_verify or all(torch.equal(o[:n], s) for o, s, n in zip(batch.out, srcs, counts))
     if not ok:
         print("ROUND TRIP MISMATCH", file=sys.stderr)
         sys.exit(1)
@@ -213,7 +214,7 @@ def main():
         "decompress_ms": ms_decomp, "decode_kernel_ms": mean(ms_kern), "decode_kernel_ms_min": min(ms_kern),
         "compress_ms": mean(ms_comp), "compress_GBps": (raw_bytes / (mean(ms_comp) / 1000.0) / 1e9) if mean(ms_comp) > 0 else None,
         "decompress_frac_of_hbm_peak_uncompressed": raw_bytes / (ms_decomp / 1000.0) / 1e9 / HBM_PEAK_GBPS,
-        "round_trip_bit_exact": ok,
+        "round_trip_bit_exact": bool(ok) and not args.no_verify,
         "roofline": {"bound": "hbm", "kernel": "k_decode_fp8", "achieved": algo_bytes / kern_s / 1e9, "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": algo_bytes / kern_s / 1e9 / HBM_PEAK_GBPS,
                      "algorithmic_bytes_per_launch": algo_bytes, "traffic": MEASURED_TRAFFIC_BYTES.get(workload)},

@@ -292,13 +292,28 @@ __device__ __forceinline__ void huff_refill(HuffStream &H)
     H.wpos += (uint32_t)__popcll(bm);
 }
 
-// decode one run of G symbols (SB bits each) into P0 (symbols 0..64/SB-1) and P1 (the rest)
-template <int SB, int G, int R>
+// code longer than the lookup index: canonical search on the bit-reversed window (inlined: a
+// call here would cost the common path its registers)
+__device__ __forceinline__ uint32_t long_code(const FieldTab &T, uint32_t x)
+{
+    const uint32_t msb = __brev(x);
+    uint32_t e = T.lmax ? T.lmax : 1;       // malformed table: consume something, symbol 0
+    for (uint32_t l = T.lmax; l > (uint32_t)kLutBits; l--) {
+        const uint32_t code = msb >> (32 - l);
+        if (code >= T.first[l] && code - T.first[l] < T.cnt[l]) e = l | ((uint32_t)T.sorted[T.start[l] + code - T.first[l]] << 8);
+    }
+    return e;
+}
+
+// decode one run of G symbols (SB bits each) into P0 (symbols 0..64/SB-1) and P1 (the rest).
+// LONG: the code has words longer than the lookup index.
+template <int SB, int G, int R, bool LONG>
 __device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uint64_t &P0, uint64_t &P1, uint32_t lane)
 {
     constexpr int PER64 = 64 / SB;
     const uint32_t mask = T.mask;
     const char *lut = reinterpret_cast<const char *>(T.lut);
+    uint32_t q[4] = {(uint32_t)P0, (uint32_t)(P0 >> 32), (uint32_t)P1, (uint32_t)(P1 >> 32)};
 #pragma unroll
     for (int g = 0; g < G / R; g++) {
         if ((g & 3) == 0) huff_ring_service(H, lane);
@@ -308,27 +323,42 @@ __device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uin
         for (int j = 0; j < R; j++) {
             const int jj = g * R + j;
             uint32_t e = *reinterpret_cast<const uint16_t *>(lut + ((x & mask) << 1));
-            if (e == 0) e = dec_long(T, x);
+            if (LONG && e == 0) e = long_code(T, x);
             x >>= (e & 31u);
             used += e;
-            const uint64_t sym = (uint64_t)(e >> 8) << ((jj % PER64) * SB);
-            if (jj < PER64) P0 |= sym; else P1 |= sym;
+            constexpr int kPer32 = 32 / SB;
+            const int word = jj / kPer32, pos = jj % kPer32;
+            if (SB == 8) {
+                // byte 1 of the entry (the symbol) into byte `pos` of the word
+                const uint32_t sel = pos == 0 ? 0x03020105u : pos == 1 ? 0x03020500u : pos == 2 ? 0x03050100u : 0x05020100u;
+                q[word] = __builtin_amdgcn_perm(e, q[word], sel);
+            } else q[word] |= (e >> 8) << (pos * SB);
         }
         H.c += used & 0xFFu;           // the low bytes hold the lengths; their sum is at most 32
         huff_refill(H);
+    }
+    P0 = (uint64_t)q[0] | ((uint64_t)q[1] << 32);
+    if (G > PER64) P1 = (uint64_t)q[2] | ((uint64_t)q[3] << 32);
+}
+
+template <int SB, int G, bool LONG>
+__device__ __forceinline__ void huff_run_l(HuffStream &H, const FieldTab &T, uint32_t period, uint64_t &P0, uint64_t &P1, uint32_t lane)
+{
+    switch (period) {
+    case 2: huff_run_r<SB, G, 2, LONG>(H, T, P0, P1, lane); break;
+    case 4: huff_run_r<SB, G, 4, LONG>(H, T, P0, P1, lane); break;
+    case 8: huff_run_r<SB, G, 8, LONG>(H, T, P0, P1, lane); break;
+    case 16: if (G >= 16) huff_run_r<SB, G, (G >= 16 ? 16 : G), LONG>(H, T, P0, P1, lane); break;
+    default: if (G >= 32) huff_run_r<SB, G, (G >= 32 ? 32 : G), LONG>(H, T, P0, P1, lane); break;
     }
 }
 
 template <int SB, int G>
 __device__ __forceinline__ void huff_run(HuffStream &H, const FieldTab &T, uint32_t period, uint64_t &P0, uint64_t &P1, uint32_t lane)
 {
-    switch (period) {
-    case 2: huff_run_r<SB, G, 2>(H, T, P0, P1, lane); break;
-    case 4: huff_run_r<SB, G, 4>(H, T, P0, P1, lane); break;
-    case 8: huff_run_r<SB, G, 8>(H, T, P0, P1, lane); break;
-    case 16: if (G >= 16) huff_run_r<SB, G, (G >= 16 ? 16 : G)>(H, T, P0, P1, lane); break;
-    default: if (G >= 32) huff_run_r<SB, G, (G >= 32 ? 32 : G)>(H, T, P0, P1, lane); break;
-    }
+    // only refill periods of 2 can come with codes longer than the 11-bit index (longest code > 11 bits)
+    if (period == 2 && T.lmax > (uint32_t)kLutBits) huff_run_r<SB, G, 2, true>(H, T, P0, P1, lane);
+    else huff_run_l<SB, G, false>(H, T, period, P0, P1, lane);
 }
 
 // one field of one run when it is not table decoded.  words_per_run = G*SB/32.
