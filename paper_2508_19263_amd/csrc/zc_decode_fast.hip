@@ -243,14 +243,20 @@ __global__ __launch_bounds__(256) void k_decode_fp8(const TensorDev *descs, cons
 
 enum FieldKind : uint32_t { KIND_HUFF = 0, KIND_FLAT = 1, KIND_RAW = 2, KIND_CONST = 3 };
 
+// ring of this kernel: 512 words per wavefront and field, refilled 128 words (8 bytes per lane) at
+// a time; serviced every 2 refill steps (2 * 64 words <= one segment), which keeps the LDS
+// footprint small enough for 8 workgroups per CU
+constexpr uint32_t kRing2Words = 512, kRing2Segment = 128;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
 struct HuffStream {
     uint64_t W;            // 64 stream bits, next unread bit = bit c
     uint32_t c;
     uint32_t wpos, wbase;  // words handed out so far; first word still in the ring
     uint32_t pslot;
     bool pending;
-    u32x4 pv;
-    char *ring;            // this wavefront's 1024-word ring in LDS
+    u32x2 pv;
+    char *ring;            // this wavefront's ring in LDS
     __amdgpu_buffer_rsrc_t rs;
 };
 
@@ -258,26 +264,28 @@ __device__ __forceinline__ void huff_open(HuffStream &H, __amdgpu_buffer_rsrc_t 
 {
     H.rs = rs; H.ring = ring;
 #pragma unroll
-    for (uint32_t q = 0; q < kRingWords / kRingSegment; q++) {
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(lane * 16 + q * kRingSegment * 4), 0, 0);
-        *reinterpret_cast<u32x4 *>(ring + q * kRingSegment * 4 + lane * 16) = v;
+    for (uint32_t q = 0; q < kRing2Words / kRing2Segment; q++) {
+        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(lane * 8 + q * kRing2Segment * 4), 0, 0);
+        *reinterpret_cast<u32x2 *>(ring + q * kRing2Segment * 4 + lane * 8) = v;
     }
     H.W = (uint64_t)(*reinterpret_cast<const uint32_t *>(ring + lane * 4)) << 32;   // step 0: word `lane`
     H.c = 32; H.wpos = 64; H.wbase = 0; H.pslot = 0; H.pending = false;
-    H.pv = u32x4{0, 0, 0, 0};
+    H.pv = u32x2{0, 0};
 }
 
-// call at least once per 4 refill steps (4 * 64 words <= one segment)
+// Invariant when this is called: words [wbase, wbase + 512) are in the ring except the newest
+// 128 while their load is in flight, and wpos - wbase < 256; at most 2 refill steps (128 words)
+// follow before the next call, so every word they can ask for is present.
 __device__ __forceinline__ void huff_ring_service(HuffStream &H, uint32_t lane)
 {
     if (H.pending) {
-        *reinterpret_cast<u32x4 *>(H.ring + H.pslot * 4 + lane * 16) = H.pv;
+        *reinterpret_cast<u32x2 *>(H.ring + H.pslot * 4 + lane * 8) = H.pv;
         H.pending = false;
     }
-    if (H.wpos - H.wbase >= kRingSegment) {
-        H.pv = __builtin_amdgcn_raw_buffer_load_b128(H.rs, (int)(lane * 16 + (H.wbase + kRingWords) * 4), 0, 0);
-        H.pslot = H.wbase & (kRingWords - 1);
-        H.wbase += kRingSegment;
+    if (H.wpos - H.wbase >= kRing2Segment) {
+        H.pv = __builtin_amdgcn_raw_buffer_load_b64(H.rs, (int)(lane * 8 + (H.wbase + kRing2Words) * 4), 0, 0);
+        H.pslot = H.wbase & (kRing2Words - 1);
+        H.wbase += kRing2Segment;
         H.pending = true;
     }
 }
@@ -286,7 +294,7 @@ __device__ __forceinline__ void huff_refill(HuffStream &H)
 {
     const bool need = H.c >= 32;
     const uint64_t bm = __ballot(need);
-    const uint32_t w = *reinterpret_cast<const uint32_t *>(H.ring + ((prefix_count64(bm) * 4 + H.wpos * 4) & (kRingWords * 4 - 1)));
+    const uint32_t w = *reinterpret_cast<const uint32_t *>(H.ring + ((prefix_count64(bm) * 4 + H.wpos * 4) & (kRing2Words * 4 - 1)));
     H.W = need ? ((H.W >> 32) | ((uint64_t)w << 32)) : H.W;
     H.c = need ? H.c - 32 : H.c;
     H.wpos += (uint32_t)__popcll(bm);
@@ -316,7 +324,7 @@ __device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uin
     uint32_t q[4] = {(uint32_t)P0, (uint32_t)(P0 >> 32), (uint32_t)P1, (uint32_t)(P1 >> 32)};
 #pragma unroll
     for (int g = 0; g < G / R; g++) {
-        if ((g & 3) == 0) huff_ring_service(H, lane);
+        if ((g & 1) == 0) huff_ring_service(H, lane);
         uint32_t x = (uint32_t)(H.W >> H.c);
         uint32_t used = 0;
 #pragma unroll
@@ -399,7 +407,7 @@ template <int FMT, bool XOR>
 __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single)
 {
     using F_ = Fmt<FMT>;
-    extern __shared__ __attribute__((aligned(16))) uint32_t rings[];     // [ring][wave][kRingWords], sized by the host
+    extern __shared__ __attribute__((aligned(16))) uint32_t rings[];     // [ring][wave][kRing2Words], sized by the host
     __shared__ FieldTab tab[F_::NF];
     __shared__ TensorDev dsh;
     WorkItem it;
@@ -432,8 +440,8 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     const uint64_t K0 = splat(uniform32(d.konst[0]), F_::SB), K1 = splat(uniform32(d.konst[1]), F_::SB);
 
     // rings: field 0 uses ring 0; field 1 uses ring 1 if field 0 is table decoded too, else ring 0
-    char *ring_base = reinterpret_cast<char *>(rings) + wave * (kRingWords * 4);
-    char *ring0 = ring_base, *ring1 = ring_base + (kind[0] == KIND_HUFF ? kWavesPerGroup * kRingWords * 4 : 0);
+    char *ring_base = reinterpret_cast<char *>(rings) + wave * (kRing2Words * 4);
+    char *ring0 = ring_base, *ring1 = ring_base + (kind[0] == KIND_HUFF ? kWavesPerGroup * kRing2Words * 4 : 0);
     HuffStream H0, H1;
     if (kind[0] == KIND_HUFF) huff_open(H0, r0, ring0, lane);
     if (kind[1] == KIND_HUFF) huff_open(H1, r1, ring1, lane);
@@ -487,7 +495,7 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const Tens
     hipStream_t st = (hipStream_t)stream;
     const TensorDev s = single ? *single : TensorDev{};
     const int use_single = single ? 1 : 0;
-    const uint32_t lds = (n_rings >= 2 ? 2u : 1u) * kWavesPerGroup * kRingWords * 4;
+    const uint32_t lds = (n_rings >= 2 ? 2u : 1u) * kWavesPerGroup * kRing2Words * 4;
     if (fmt == ZC_FMT_BF16) return launch_s64_x<ZC_FMT_BF16>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
     if (fmt == ZC_FMT_FP8_E4M3) return launch_s64_x<ZC_FMT_FP8_E4M3>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
     return launch_s64_x<ZC_FMT_FP4_E2M1_MX>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
