@@ -404,3 +404,33 @@ def test_odd_geometries():
                 E = cb * 8 // zc.elem_bits(fmt)
                 n = 5 * E + (E // 3 // 32) * 32 + (0 if fmt == zc.FMT_FP4_E2M1_MX else 7)
                 check_case(fmt, n, cb, S, zc.POLICY_HUFF_ALL if S != 16 else zc.POLICY_AUTO, tag="odd")
+
+
+def test_damaged_payload_and_index_do_not_escape_the_buffers():
+    # The decoders' own range checks must turn a damaged stream into wrong output, never into an
+    # access outside the container or the destination: canaries around both stay intact.
+    rng = np.random.default_rng(91)
+    cases = [(zc.FMT_FP8_E4M3, 8 * 65536, 65536, 64, None), (zc.FMT_FP8_E4M3, 64 * 2048, 2048, 8, None),
+             (zc.FMT_BF16, 6 * 8192, 16384, 64, None), (zc.FMT_FP8_E4M3, 9 * 4096 + 11, 4096, 16, None)]
+    for fmt, n, cb, S, _ in cases:
+        src, _sc = make_input(fmt, n, 17)
+        comp, info = zc.compress(dev(src), n, zc.params(fmt, cb, streams=S))
+        raw = src.numel() * src.element_size()
+        pay = int(info.payload_offset)
+        for what in ("payload", "index"):
+            guard = 4096
+            buf = torch.full((guard + comp.numel() + guard,), 0x5A, dtype=torch.uint8, device=DEV)
+            body = buf[guard:guard + comp.numel()]
+            body.copy_(comp)
+            if what == "payload":
+                noise = torch.from_numpy(rng.integers(0, 256, comp.numel() - pay).astype(np.uint8)).to(DEV)
+                body[pay:] = noise
+            else:
+                lo = int(info.index_offset[0])
+                body[lo:pay] = torch.from_numpy(rng.integers(0, 256, pay - lo).astype(np.uint8)).to(DEV)
+            out = torch.full((guard + raw + guard,), 0xC3, dtype=torch.uint8, device=DEV)
+            print("damaged", what, "fmt", fmt, "n", n, "chunk", cb, "S", S, flush=True)
+            zc.decompress(body, info, out=out[guard:guard + raw])
+            torch.cuda.synchronize()
+            assert bool((out[:guard] == 0xC3).all()) and bool((out[guard + raw:] == 0xC3).all())
+            assert bool((buf[:guard] == 0x5A).all()) and bool((buf[guard + comp.numel():] == 0x5A).all())
