@@ -144,6 +144,27 @@ zc_status zc_compress(const void *d_src, uint64_t n_elems, const zc_params *para
 zc_status zc_compress_batch(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params,
                             void *d_ws, uint64_t ws_bytes, void *stream);
 
+/* Static dictionaries (Sec. 3.3: "precomputed Huffman dictionaries when exponent distributions are
+ * stable"; Sec. 5.2: "static Huffman dictionaries trained on representative data").
+ * zc_train_code builds a dictionary from a representative tensor: its per-field histogram with
+ * every count raised by one (so that any symbol can be coded later), then the usual code
+ * construction and raw/Huffman decision.  Only format, policy, mode[], sym_bits[], max_len[] and
+ * code_len[][] of *out_code are meaningful.  Synchronises.
+ * zc_compress_with_code / zc_compress_batch_with_code code every tensor with that dictionary:
+ * no histogram pass and no code construction, one synchronisation (to size the output) instead
+ * of two.  The container is an ordinary one (it carries the dictionary's length tables), so
+ * every decompress entry point reads it.  A dictionary whose Huffman fields do not cover the
+ * whole alphabet is rejected with ZC_ERR_INVALID_ARG. */
+zc_status zc_train_code(const void *d_src, uint64_t n_elems, const zc_params *params,
+                        const void *d_xor_base, const void *d_scales, zc_info *out_code,
+                        void *d_ws, uint64_t ws_bytes, void *stream);
+zc_status zc_compress_with_code(const void *d_src, uint64_t n_elems, const zc_params *params, const zc_info *code,
+                                const void *d_xor_base, const void *d_scales,
+                                void *d_dst, uint64_t dst_capacity, uint64_t *out_bytes, zc_info *out_info,
+                                void *d_ws, uint64_t ws_bytes, void *stream);
+zc_status zc_compress_batch_with_code(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params, const zc_info *code,
+                                      void *d_ws, uint64_t ws_bytes, void *stream);
+
 /* Read and validate a container's header and tables (blocking copy of at most 1 KiB from
  * the device; with check_index != 0 also the chunk index).  d_comp: device; out: host. */
 zc_status zc_read_info(const void *d_comp, uint64_t comp_bytes, int check_index, zc_info *out, void *stream);

@@ -507,8 +507,9 @@ uint64_t zco_compress_bound(uint64_t n_elems, const zco_params *p)
 /* Compress.  src: the tensor (FP4: two elements per byte, element 2i in the low
  * nibble).  xor_base: NULL or a tensor of the same shape.  scales: FP4 only,
  * n_elems/32 E8M0 bytes.  Returns a status; *out_bytes = container size. */
-int zco_compress(const uint8_t *src, uint64_t n_elems, const zco_params *p, const uint8_t *xor_base,
-                 const uint8_t *scales, uint8_t *dst, uint64_t cap, uint64_t *out_bytes)
+static int compress_impl(const uint8_t *src, uint64_t n_elems, const zco_params *p, const uint8_t *xor_base,
+                         const uint8_t *scales, const uint8_t *static_len, const uint8_t *static_mode,
+                         uint8_t *dst, uint64_t cap, uint64_t *out_bytes)
 {
     int S, rc = check_params(p, n_elems, &S);
     if (rc) return rc;
@@ -533,7 +534,23 @@ int zco_compress(const uint8_t *src, uint64_t n_elems, const zco_params *p, cons
         memset(len[f], 0, 256); memset(code[f], 0, sizeof(code[f]));
         mode[f] = ZCO_MODE_EMPTY; lmax[f] = 0; konst[f] = 0;
         for (int v = 0; v < A; v++) if (hist[v]) { distinct++; konst[f] = (uint8_t)v; }
-        if (distinct == 1) mode[f] = ZCO_MODE_CONST;
+        if (static_len && ns) {
+            /* Sec. 3.3 / 5.2: a precomputed (static) dictionary is used as given, no histogram of this tensor
+             * enters the code.  It must be able to code every symbol: all 2^sym_bits lengths present. */
+            mode[f] = static_mode[f];
+            if (mode[f] == ZCO_MODE_HUFF) {
+                uint64_t kraft = 0;
+                for (int v = 0; v < A; v++) {
+                    len[f][v] = static_len[256 * f + v];
+                    if (len[f][v] == 0 || len[f][v] > 16) { rc = ZCO_ERR_ARG; goto done; }
+                    kraft += (uint64_t)1 << (16 - len[f][v]);
+                    if (len[f][v] > lmax[f]) lmax[f] = len[f][v];
+                }
+                if (kraft != 65536) { rc = ZCO_ERR_ARG; goto done; }
+                zco_canonical_codes(len[f], A, code[f]);
+            } else if (mode[f] != ZCO_MODE_RAW) { rc = ZCO_ERR_ARG; goto done; }
+            konst[f] = 0;
+        } else if (distinct == 1) mode[f] = ZCO_MODE_CONST;
         else if (distinct > 1) {
             konst[f] = 0;
             if (zco_code_lengths(hist, A, limit_for(p, f), len[f])) { rc = ZCO_ERR_ARG; goto done; }
@@ -593,6 +610,50 @@ int zco_compress(const uint8_t *src, uint64_t n_elems, const zco_params *p, cons
     *out_bytes = total;
 done:
     free(sym[0]); free(sym[1]); free(sym[2]);
+    return rc;
+}
+
+int zco_compress(const uint8_t *src, uint64_t n_elems, const zco_params *p, const uint8_t *xor_base,
+                 const uint8_t *scales, uint8_t *dst, uint64_t cap, uint64_t *out_bytes)
+{
+    return compress_impl(src, n_elems, p, xor_base, scales, NULL, NULL, dst, cap, out_bytes);
+}
+
+/* Compress with a precomputed code (Sec. 3.3: "precomputed Huffman dictionaries when exponent
+ * distributions are stable"; Sec. 5.2: "static Huffman dictionaries trained on representative
+ * data").  static_len: 3 x 256 code lengths, static_mode: 3 modes (HUFF or RAW). */
+int zco_compress_with_code(const uint8_t *src, uint64_t n_elems, const zco_params *p, const uint8_t *xor_base,
+                           const uint8_t *scales, const uint8_t *static_len, const uint8_t *static_mode,
+                           uint8_t *dst, uint64_t cap, uint64_t *out_bytes)
+{
+    if (!static_len || !static_mode) return ZCO_ERR_ARG;
+    return compress_impl(src, n_elems, p, xor_base, scales, static_len, static_mode, dst, cap, out_bytes);
+}
+
+/* Train a static dictionary on representative data: the tensor's histogram with every count
+ * raised by one (so that every symbol of the alphabet can be coded later), then the same code
+ * construction and the same raw/Huffman decision as zco_compress. */
+int zco_train_code(const uint8_t *src, uint64_t n_elems, const zco_params *p, const uint8_t *xor_base,
+                   const uint8_t *scales, uint8_t *len_out /* 3 x 256 */, uint8_t *mode_out /* 3 */)
+{
+    int S, rc = check_params(p, n_elems, &S);
+    if (rc) return rc;
+    int fmt = (int)p->format, nf = zco_num_fields(fmt);
+    uint8_t *e = malloc((size_t)n_elems + 1), *m = malloc((size_t)n_elems + 1);
+    zco_split(fmt, src, xor_base, n_elems, e, m);
+    memset(len_out, 0, 768); memset(mode_out, 0, 3);
+    for (int f = 0; f < nf && !rc; f++) {
+        const uint8_t *syms = f == 0 ? e : f == 1 ? m : scales;
+        uint64_t hist[256], ns = num_symbols(fmt, f, n_elems), bits = 0, total = 0;
+        int sb = zco_sym_bits(fmt, f), A = 1 << sb;
+        zco_histogram(syms, ns, hist);
+        for (int v = 0; v < A; v++) { hist[v] += 1; total += hist[v]; }
+        if (zco_code_lengths(hist, A, limit_for(p, f), len_out + 256 * f)) { rc = ZCO_ERR_ARG; break; }
+        for (int v = 0; v < A; v++) bits += hist[v] * len_out[256 * f + v];
+        mode_out[f] = ZCO_MODE_HUFF;
+        if (p->policy == ZCO_POLICY_AUTO && 16 * bits > 15 * total * (uint64_t)sb) { mode_out[f] = ZCO_MODE_RAW; memset(len_out + 256 * f, 0, 256); }
+    }
+    free(e); free(m);
     return rc;
 }
 

@@ -77,6 +77,10 @@ def lib():
         _lib.zco_compress_bound.argtypes = [u64, C.POINTER(Params)]
         _lib.zco_compress.restype = C.c_int
         _lib.zco_compress.argtypes = [u8p, u64, C.POINTER(Params), u8p, u8p, u8p, u64, C.POINTER(u64)]
+        _lib.zco_compress_with_code.restype = C.c_int
+        _lib.zco_compress_with_code.argtypes = [u8p, u64, C.POINTER(Params), u8p, u8p, u8p, u8p, u8p, u64, C.POINTER(u64)]
+        _lib.zco_train_code.restype = C.c_int
+        _lib.zco_train_code.argtypes = [u8p, u64, C.POINTER(Params), u8p, u8p, u8p, u8p]
         _lib.zco_decompress.restype = C.c_int
         _lib.zco_decompress.argtypes = [u8p, u64, u8p, u8p, u64, u8p]
         _lib.zco_decompress_chunk.restype = C.c_int
@@ -187,6 +191,29 @@ def compress(src, n_elems, p, xor_base=None, scales=None):
     rc = lib().zco_compress(_p(src), n_elems, C.byref(p), _p(xor_base), _p(scales), _p(dst), cap, C.byref(size))
     if rc:
         raise ValueError("zco_compress status %d" % rc)
+    return dst[:size.value].copy()
+
+
+def train_code(src, n_elems, p, xor_base=None, scales=None):
+    """Static dictionary from representative data: (lengths uint8[3,256], modes uint8[3])."""
+    ln = np.zeros((3, 256), np.uint8)
+    md = np.zeros(3, np.uint8)
+    rc = lib().zco_train_code(_p(_bytes(src)), n_elems, C.byref(p), _p(_bytes(xor_base)), _p(_bytes(scales)), _p(ln), _p(md))
+    if rc:
+        raise ValueError("zco_train_code status %d" % rc)
+    return ln, md
+
+
+def compress_with_code(src, n_elems, p, lengths, modes, xor_base=None, scales=None):
+    src, xor_base, scales = _bytes(src), _bytes(xor_base), _bytes(scales)
+    cap = compress_bound(n_elems, p)
+    dst = np.zeros(cap, np.uint8)
+    size = C.c_uint64(0)
+    ln = np.ascontiguousarray(lengths, np.uint8)
+    md = np.ascontiguousarray(modes, np.uint8)
+    rc = lib().zco_compress_with_code(_p(src), n_elems, C.byref(p), _p(xor_base), _p(scales), _p(ln), _p(md), _p(dst), cap, C.byref(size))
+    if rc:
+        raise ValueError("zco_compress_with_code status %d" % rc)
     return dst[:size.value].copy()
 
 

@@ -125,7 +125,7 @@ struct FieldCode {
 };
 
 // hist3: the three 256-bin device histograms of one tensor (meaning depends on the format)
-zc_status build_codes(const Geometry &g, uint32_t policy, uint64_t n_elems, const uint64_t *hist3, FieldCode fc[3])
+zc_status build_codes(const Geometry &g, uint32_t policy, uint64_t n_elems, const uint64_t *hist3, FieldCode fc[3], bool train = false)
 {
     for (uint32_t f = 0; f < g.nf; f++) {
         FieldCode &c = fc[f];
@@ -151,6 +151,17 @@ zc_status build_codes(const Geometry &g, uint32_t policy, uint64_t n_elems, cons
         uint64_t sum = 0;
         for (int v = 0; v < A; v++) { sum += c.hist[v]; if (c.hist[v]) { c.distinct++; c.konst = (uint32_t)v; } }
         if (sum != c.n_symbols) return ZC_ERR_DEVICE;          // the histogram kernel must count every symbol once
+        if (train) {
+            // static dictionary (Sec. 3.3, 5.2): every count raised by one, so that every symbol of the
+            // alphabet can be coded when the dictionary is applied to other tensors
+            uint64_t total = 0;
+            for (int v = 0; v < A; v++) { c.hist[v] += 1; total += c.hist[v]; }
+            if (!build_code_lengths(c.hist, A, g.limit[f], c.len)) return ZC_ERR_INVALID_ARG;
+            for (int v = 0; v < A; v++) { c.payload_bits += c.hist[v] * c.len[v]; if (c.len[v] > c.lmax) c.lmax = c.len[v]; }
+            c.mode = ZC_MODE_HUFF; c.konst = 0;
+            if (policy == ZC_POLICY_AUTO && 16 * c.payload_bits > 15 * total * (uint64_t)sb) { c.mode = ZC_MODE_RAW; c.lmax = 0; std::memset(c.len, 0, sizeof(c.len)); }
+            continue;
+        }
         c.mode = ZC_MODE_EMPTY;
         if (c.distinct == 1) c.mode = ZC_MODE_CONST;
         else if (c.distinct > 1) {
@@ -164,6 +175,34 @@ zc_status build_codes(const Geometry &g, uint32_t policy, uint64_t n_elems, cons
                 c.payload_bits = c.n_symbols * (uint64_t)sb;
             } else assign_canonical(c.len, A, c.code);
         }
+    }
+    return ZC_OK;
+}
+
+// field codes taken from a precomputed dictionary instead of this tensor's histogram
+zc_status codes_from_dictionary(const Geometry &g, uint64_t n_elems, const zc_info &dict, FieldCode fc[3])
+{
+    if (dict.format != g.fmt) return ZC_ERR_INVALID_ARG;
+    for (uint32_t f = 0; f < g.nf; f++) {
+        FieldCode &c = fc[f];
+        std::memset(&c, 0, sizeof(c));
+        const int sb = sym_bits(g.fmt, (int)f), A = 1 << sb;
+        c.n_symbols = field_symbols(g.fmt, (int)f, n_elems);
+        c.mode = ZC_MODE_EMPTY;
+        if (c.n_symbols == 0) continue;
+        if (dict.mode[f] == ZC_MODE_RAW) { c.mode = ZC_MODE_RAW; c.payload_bits = c.n_symbols * (uint64_t)sb; continue; }
+        if (dict.mode[f] != ZC_MODE_HUFF) return ZC_ERR_INVALID_ARG;
+        uint64_t kraft = 0;
+        for (int v = 0; v < A; v++) {
+            const uint32_t l = dict.code_len[f][v];
+            if (l == 0 || l > 16) return ZC_ERR_INVALID_ARG;      // it must be able to code every symbol
+            c.len[v] = (uint8_t)l;
+            kraft += 1ull << (16 - l);
+            if (l > c.lmax) c.lmax = l;
+        }
+        if (kraft != 65536) return ZC_ERR_INVALID_ARG;
+        c.mode = ZC_MODE_HUFF;
+        assign_canonical(c.len, A, c.code);
     }
     return ZC_OK;
 }
@@ -235,8 +274,11 @@ TensorDev make_desc(const zc_info &info)
 }
 
 // shared by zc_compress_batch and zc_stats: histogram -> codes (-> sizes -> scan [-> encode])
+// dict: precomputed dictionary to code with (no histogram pass), or null.  train: stop after the
+// code construction with smoothed counts (codes_out receives the dictionary).
 zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, void *d_ws, uint64_t ws_bytes, void *stream,
-                       bool stats_only, std::vector<FieldCode> *codes_out, std::vector<ScanOut> *scan_out)
+                       bool stats_only, std::vector<FieldCode> *codes_out, std::vector<ScanOut> *scan_out,
+                       const zc_info *dict = nullptr, bool train = false)
 {
     Geometry g;
     zc_status st = check_params(params, &g);
@@ -293,12 +335,14 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     if (!scale_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
     HIP_TRY(hipMemsetAsync(d_hist, 0, (uint64_t)T * 3 * 256 * 8, hs));
 
-    // field split + histogram (a1-a3)
-    LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
-    if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), 1, d_hist, stream));
+    // field split + histogram (a1-a3); not needed when the code comes from a dictionary
     std::vector<uint64_t> hist((size_t)T * 768);
-    HIP_TRY(hipMemcpyAsync(hist.data(), d_hist, hist.size() * 8, hipMemcpyDeviceToHost, hs));
-    HIP_TRY(hipStreamSynchronize(hs));
+    if (!dict) {
+        LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
+        if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), 1, d_hist, stream));
+        HIP_TRY(hipMemcpyAsync(hist.data(), d_hist, hist.size() * 8, hipMemcpyDeviceToHost, hs));
+        HIP_TRY(hipStreamSynchronize(hs));
+    }
 
     // code construction on the host (a4)
     std::vector<FieldCode> codes((size_t)T * 3);
@@ -307,7 +351,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     std::vector<uint8_t> blobs((size_t)T * kBlobBytes, 0);
     for (uint32_t t = 0; t < T; t++) {
         FieldCode *fc = &codes[(size_t)t * 3];
-        st = build_codes(g, params->policy, tensors[t].n_elems, &hist[(size_t)t * 768], fc);
+        st = dict ? codes_from_dictionary(g, tensors[t].n_elems, *dict, fc)
+                  : build_codes(g, params->policy, tensors[t].n_elems, &hist[(size_t)t * 768], fc, train);
         if (st) return st;
         fill_info(g, params->policy, tensors[t].d_xor_base != nullptr, tensors[t].n_elems, ncs[t], fc, 0, &tensors[t].info);
         serialize_blob(tensors[t].info, &blobs[(size_t)t * kBlobBytes]);
@@ -333,6 +378,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         for (uint64_t c = n_full; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
     }
     if (codes_out) *codes_out = codes;
+    if (train) return ZC_OK;
     HIP_TRY(hipMemcpyAsync(d_descs, descs.data(), T * sizeof(TensorDev), hipMemcpyHostToDevice, hs));
     HIP_TRY(hipMemcpyAsync(ws + w.enc, enc.data(), enc.size() * 4, hipMemcpyHostToDevice, hs));
     if (!fast_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.fast_work, fast_work.data(), fast_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
@@ -594,6 +640,51 @@ zc_status zc_compress(const void *d_src, uint64_t n_elems, const zc_params *para
     t.d_src = d_src; t.d_xor_base = d_xor_base; t.d_scales = d_scales; t.n_elems = n_elems;
     t.d_comp = d_dst; t.comp_capacity = dst_capacity;
     zc_status st = run_compress(&t, 1, params, d_ws, ws_bytes, stream, false, nullptr, nullptr);
+    if (st) return st;
+    *out_bytes = t.out_bytes;
+    if (out_info) *out_info = t.info;
+    return ZC_OK;
+}
+
+zc_status zc_train_code(const void *d_src, uint64_t n_elems, const zc_params *params, const void *d_xor_base, const void *d_scales,
+                        zc_info *out_code, void *d_ws, uint64_t ws_bytes, void *stream)
+{
+    if (!out_code || n_elems == 0) return ZC_ERR_INVALID_ARG;
+    zc_tensor t;
+    std::memset(&t, 0, sizeof(t));
+    t.d_src = d_src; t.d_xor_base = d_xor_base; t.d_scales = d_scales; t.n_elems = n_elems;
+    std::vector<FieldCode> codes;
+    zc_status st = run_compress(&t, 1, params, d_ws, ws_bytes, stream, true, &codes, nullptr, nullptr, true);
+    if (st) return st;
+    std::memset(out_code, 0, sizeof(*out_code));
+    out_code->format = params->format; out_code->policy = params->policy;
+    out_code->streams = params->streams_per_chunk ? params->streams_per_chunk : 64;
+    out_code->n_fields = (uint32_t)num_fields(params->format); out_code->chunk_bytes = params->chunk_bytes;
+    for (uint32_t f = 0; f < out_code->n_fields; f++) {
+        out_code->mode[f] = (uint8_t)codes[f].mode; out_code->sym_bits[f] = (uint8_t)sym_bits(params->format, (int)f);
+        out_code->max_len[f] = (uint8_t)codes[f].lmax;
+        std::memcpy(out_code->code_len[f], codes[f].len, 256);
+    }
+    return ZC_OK;
+}
+
+zc_status zc_compress_batch_with_code(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params, const zc_info *code,
+                                      void *d_ws, uint64_t ws_bytes, void *stream)
+{
+    if (!code) return ZC_ERR_INVALID_ARG;
+    return run_compress(tensors, n_tensors, params, d_ws, ws_bytes, stream, false, nullptr, nullptr, code, false);
+}
+
+zc_status zc_compress_with_code(const void *d_src, uint64_t n_elems, const zc_params *params, const zc_info *code,
+                                const void *d_xor_base, const void *d_scales, void *d_dst, uint64_t dst_capacity,
+                                uint64_t *out_bytes, zc_info *out_info, void *d_ws, uint64_t ws_bytes, void *stream)
+{
+    if (!out_bytes || !code) return ZC_ERR_INVALID_ARG;
+    zc_tensor t;
+    std::memset(&t, 0, sizeof(t));
+    t.d_src = d_src; t.d_xor_base = d_xor_base; t.d_scales = d_scales; t.n_elems = n_elems;
+    t.d_comp = d_dst; t.comp_capacity = dst_capacity;
+    zc_status st = run_compress(&t, 1, params, d_ws, ws_bytes, stream, false, nullptr, nullptr, code, false);
     if (st) return st;
     *out_bytes = t.out_bytes;
     if (out_info) *out_info = t.info;

@@ -20,7 +20,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_BUFFER_TOO_SMALL, ERR_CORRUPT, ERR_DEV
 
 EXPORTS = ["zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_compress_batch", "zc_read_info",
            "zc_decompress", "zc_decompress_chunks", "zc_decompress_batch", "zc_decompress_batch_plan",
-           "zc_decompress_batch_run", "zc_stats", "zc_build_code",
+           "zc_decompress_batch_run", "zc_stats", "zc_build_code", "zc_train_code", "zc_compress_with_code",
+           "zc_compress_batch_with_code",
            "zc_status_string"]
 
 
@@ -92,6 +93,12 @@ def lib():
         L.zc_compress.argtypes = [vp, u64, C.POINTER(Params), vp, vp, vp, u64, C.POINTER(u64), C.POINTER(Info), vp, u64, vp]
         L.zc_compress_batch.restype = C.c_int
         L.zc_compress_batch.argtypes = [C.POINTER(Tensor), u32, C.POINTER(Params), vp, u64, vp]
+        L.zc_train_code.restype = C.c_int
+        L.zc_train_code.argtypes = [vp, u64, C.POINTER(Params), vp, vp, C.POINTER(Info), vp, u64, vp]
+        L.zc_compress_with_code.restype = C.c_int
+        L.zc_compress_with_code.argtypes = [vp, u64, C.POINTER(Params), C.POINTER(Info), vp, vp, vp, u64, C.POINTER(u64), C.POINTER(Info), vp, u64, vp]
+        L.zc_compress_batch_with_code.restype = C.c_int
+        L.zc_compress_batch_with_code.argtypes = [C.POINTER(Tensor), u32, C.POINTER(Params), C.POINTER(Info), vp, u64, vp]
         L.zc_read_info.restype = C.c_int
         L.zc_read_info.argtypes = [vp, u64, C.c_int, C.POINTER(Info), vp]
         L.zc_decompress.restype = C.c_int
@@ -183,6 +190,30 @@ def compress(src, n_elems, p, xor_base=None, scales=None, dst=None, ws=None):
     return dst.view(torch.uint8).reshape(-1)[:size.value], info
 
 
+def train_code(src, n_elems, p, xor_base=None, scales=None, ws=None):
+    """Static dictionary (an Info whose mode/code_len fields are meaningful) from a representative tensor."""
+    if ws is None:
+        ws = _workspace([n_elems], p, src.device)
+    code = Info()
+    st = lib().zc_train_code(_ptr(src), n_elems, C.byref(p), _ptr(xor_base), _ptr(scales), C.byref(code), _ptr(ws), ws.numel(), _stream())
+    _check(st, "zc_train_code")
+    return code
+
+
+def compress_with_code(src, n_elems, p, code, xor_base=None, scales=None, dst=None, ws=None):
+    dev = src.device
+    if dst is None:
+        dst = torch.empty(max(compress_bound(n_elems, p), 16), dtype=torch.uint8, device=dev)
+    if ws is None:
+        ws = _workspace([n_elems], p, dev)
+    size = C.c_uint64(0)
+    info = Info()
+    st = lib().zc_compress_with_code(_ptr(src), n_elems, C.byref(p), C.byref(code), _ptr(xor_base), _ptr(scales), _ptr(dst),
+                                     dst.numel() * dst.element_size(), C.byref(size), C.byref(info), _ptr(ws), ws.numel(), _stream())
+    _check(st, "zc_compress_with_code")
+    return dst.view(torch.uint8).reshape(-1)[:size.value], info
+
+
 def read_info(comp, check_index=False):
     info = Info()
     _check(lib().zc_read_info(_ptr(comp), comp.numel(), 1 if check_index else 0, C.byref(info), _stream()), "zc_read_info")
@@ -260,8 +291,13 @@ class Batch:
         self.out = None
         self.scales_out = None
 
-    def compress(self):
-        _check(lib().zc_compress_batch(self.arr, self.n, C.byref(self.p), _ptr(self.ws), self.ws.numel(), _stream()), "zc_compress_batch")
+    def compress(self, code=None):
+        """code: a static dictionary from train_code() (then no histogram pass), or None."""
+        if code is None:
+            _check(lib().zc_compress_batch(self.arr, self.n, C.byref(self.p), _ptr(self.ws), self.ws.numel(), _stream()), "zc_compress_batch")
+        else:
+            _check(lib().zc_compress_batch_with_code(self.arr, self.n, C.byref(self.p), C.byref(code), _ptr(self.ws), self.ws.numel(), _stream()),
+                   "zc_compress_batch_with_code")
         return [int(self.arr[i].out_bytes) for i in range(self.n)]
 
     def container(self, i):

@@ -434,3 +434,28 @@ def test_damaged_payload_and_index_do_not_escape_the_buffers():
             torch.cuda.synchronize()
             assert bool((out[:guard] == 0xC3).all()) and bool((out[guard + raw:] == 0xC3).all())
             assert bool((buf[:guard] == 0x5A).all()) and bool((buf[guard + comp.numel():] == 0x5A).all())
+
+
+def test_static_dictionary():
+    # dictionary trained on one tensor, applied to others: same dictionary and same container bytes as the oracle
+    for fmt, n_a, n_b, cb, S in ((zc.FMT_FP8_E4M3, 300000, 5 * 65536 + 777, 65536, 64), (zc.FMT_FP8_E4M3, 64 * 2048, 96 * 2048, 2048, 8),
+                                 (zc.FMT_BF16, 100000, 70001, 16384, 64), (zc.FMT_FP4_E2M1_MX, 32 * 4000, 32 * 5001, 16384, 64)):
+        a, sa = make_input(fmt, n_a, 41)
+        b, sb_ = make_input(fmt, n_b, 42)
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            print("dictionary fmt", fmt, "policy", policy, flush=True)
+            p, po = zc.params(fmt, cb, streams=S, policy=policy), o.params(fmt, cb, streams=S, policy=policy)
+            code = zc.train_code(dev(a), n_a, p, scales=dev(sa))
+            ln, md = o.train_code(a.numpy(), n_a, po, scales=None if sa is None else sa.numpy())
+            for f in range(code.n_fields):
+                assert list(code.code_len[f]) == ln[f].tolist() and code.mode[f] == md[f]
+            want = o.compress_with_code(b.numpy(), n_b, po, ln, md, scales=None if sb_ is None else sb_.numpy())
+            comp, info = zc.compress_with_code(dev(b), n_b, p, code, scales=dev(sb_))
+            assert np.array_equal(comp.cpu().numpy(), want)
+            out, sco = zc.decompress(comp, info)
+            torch.cuda.synchronize()
+            assert torch.equal(out.cpu()[:b.numel() * b.element_size()], b.view(torch.uint8).reshape(-1))
+    # a dictionary that cannot code every symbol is refused
+    code.code_len[0][2] = 0
+    with pytest.raises(zc.ZcError):
+        zc.compress_with_code(dev(b), n_b, p, code, scales=dev(sb_))

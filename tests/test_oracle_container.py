@@ -195,3 +195,46 @@ def test_bad_parameters():
         assert o.compress_bound(64, p) == 0
     with pytest.raises(ValueError):
         o.compress(x, 33, o.params(o.FP4_E2M1_MX, 256), scales=np.zeros(2, np.uint8))
+
+
+def test_static_dictionary_training_and_use():
+    # Sec. 3.3 / 5.2: a dictionary trained on representative data is applied to other tensors
+    a, _ = make_input(o.FP8_E4M3, 150000, 31)
+    b, _ = make_input(o.FP8_E4M3, 90001, 32)
+    p = o.params(o.FP8_E4M3, 16384, streams=16)
+    ln, md = o.train_code(a, len(a), p)
+    e, sm = o.split(o.FP8_E4M3, a, len(a))
+    # the training rule: histogram with every count raised by one, then the usual construction
+    assert ln[0, :16].tolist() == o.code_lengths((np.bincount(e, minlength=16) + 1).tolist(), 8).tolist()
+    assert ln[1, :16].tolist() == o.code_lengths((np.bincount(sm, minlength=16) + 1).tolist(), 8).tolist()
+    assert md.tolist() == [o.MODE_HUFF, o.MODE_HUFF, 0] and ln[0, :16].min() >= 1
+    comp = o.compress_with_code(b, len(b), p, ln, md)
+    rc, out, _ = o.decompress(comp, len(b))
+    assert rc == o.OK and np.array_equal(out, b)
+    # the container carries the dictionary, not b's own code
+    assert comp[64:80].tolist() == ln[0, :16].tolist() and comp[80:96].tolist() == ln[1, :16].tolist()
+    own = o.compress(b, len(b), p)
+    assert len(comp) >= len(own)
+    # size: sum(hist_b * len_dict) payload bits plus at most the look-ahead and padding overhead
+    eb, smb = o.split(o.FP8_E4M3, b, len(b))
+    bits = int((np.bincount(eb, minlength=16) * ln[0, :16].astype(np.int64)).sum() + (np.bincount(smb, minlength=16) * ln[1, :16].astype(np.int64)).sum())
+    pay = int(np.frombuffer(comp[56:64].tobytes(), "<u8")[0])
+    n_chunks = (len(b) + 16383) // 16384
+    assert bits / 8 <= len(comp) - pay <= bits / 8 + 2 * n_chunks * (16 * 12 + 16)
+    # AUTO: the flat sign+mantissa field of the dictionary is raw
+    ln2, md2 = o.train_code(a, len(a), o.params(o.FP8_E4M3, 16384, streams=16, policy=o.POLICY_AUTO))
+    assert md2.tolist() == [o.MODE_HUFF, o.MODE_RAW, 0]
+    comp2 = o.compress_with_code(b, len(b), p, ln2, md2)
+    assert comp2[36] == o.MODE_RAW and np.array_equal(o.decompress(comp2, len(b))[1], b)
+    # a dictionary that cannot code every symbol is rejected
+    bad = ln.copy(); bad[0, 3] = 0
+    with pytest.raises(ValueError):
+        o.compress_with_code(b, len(b), p, bad, md)
+    # BF16 delta with a dictionary trained on another delta
+    w0, w1 = wl.bf16_checkpoint_pair(40000, seed=5)
+    v0, v1 = wl.bf16_checkpoint_pair(30000, seed=6)
+    pb = o.params(o.BF16, 8192)
+    lnb, mdb = o.train_code(w1.numpy(), 40000, pb, xor_base=w0.numpy())
+    cb = o.compress_with_code(v1.numpy(), 30000, pb, lnb, mdb, xor_base=v0.numpy())
+    rc, out, _ = o.decompress(cb, 60000, xor_base=v0.numpy().view(np.uint8))
+    assert rc == o.OK and np.array_equal(out, v1.numpy().view(np.uint8))
