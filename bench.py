@@ -45,7 +45,7 @@ def other_workloads(torch, wl, zc, dev):
     """Configs 1, 3, 4, 5 at full size: ratios, compress and decompress GB/s (median of 5)."""
     out = {}
 
-    def run(name, fmt, srcs, counts, chunk, streams, bases=None, scales=None, limit=(0, 0, 0), ids=None):
+    def run(name, fmt, srcs, counts, chunk, streams, bases=None, scales=None, limit=(0, 0, 0), ids=None, dictionary=False):
         p = zc.params(fmt, chunk, limit, streams)
         b = zc.Batch(srcs, counts, p, xor_bases=bases, scales=scales)
         sizes = b.compress()
@@ -72,6 +72,27 @@ def other_workloads(torch, wl, zc, dev):
             comp_read = sum(sizes) * (nb / raw)
             r.update({"page_decode_ms": t_p, "page_decode_GBps": nb / t_p / 1e6, "pages": nb // chunk, "page_decode_bit_exact": bool(okp),
                       "page_decode_traffic_frac_of_hbm_peak": (nb + comp_read) / t_p / 1e6 / HBM_PEAK_GBPS})
+        if dictionary:
+            # static dictionaries, one per tensor role (K, V: even and odd list positions), each trained on the
+            # first tensor of its role and applied to all of that role: no histogram pass, no code construction
+            del b
+            torch.cuda.empty_cache()
+            halves = []
+            for role in (0, 1):
+                sub = srcs[role::2]
+                hb = zc.Batch(sub, counts[role::2], p)
+                halves.append((hb, zc.train_code(sub[0], counts[role], p), sub))
+            dsizes = sum(sum(hb.compress(code=code)) for hb, code, _ in halves)
+            t_s = _time_ms(torch, lambda: [hb.compress(code=code) for hb, code, _ in halves])
+            oks = True
+            for hb, code, sub in halves:
+                hb.plan_decompress()
+                hb.run_decompress()
+                oks = oks and all(torch.equal(o.view(torch.uint8)[:s.numel()], s.view(torch.uint8).reshape(-1)) for o, s in zip(hb.out, sub))
+            r.update({"static_dictionary_compress_ms": t_s, "static_dictionary_compress_GBps": raw / t_s / 1e6,
+                      "static_dictionary_ratio_total": dsizes / raw, "static_dictionary_round_trip_bit_exact": bool(oks)})
+            del halves
+            b = None
         out[name] = r
         del b
         torch.cuda.empty_cache()
@@ -92,7 +113,7 @@ def other_workloads(torch, wl, zc, dev):
         kv += [k.reshape(-1), v.reshape(-1)]
     n_pages = kv[0].numel() // 2048
     ids = [wl.page_sample(n_pages, 0.25, device=dev, seed=600 + i) for i in range(len(kv))]
-    run("c5_fp8_kv_pages", zc.FMT_FP8_E4M3, kv, [t.numel() for t in kv], 2048, 8, ids=ids)
+    run("c5_fp8_kv_pages", zc.FMT_FP8_E4M3, kv, [t.numel() for t in kv], 2048, 8, ids=ids, dictionary=True)
     return out
 
 
@@ -227,7 +248,7 @@ def main():
         # the oracle as it stands, single thread, on a bounded sample of the same workload
         import numpy as np
         from oracle import zc_oracle as o
-        sample = [i for i in range(min(5, len(srcs)))]            # layer 0: q, k, v, o, gate
+        sample = [i for i in range(min(7, len(srcs)))]            # layer 0: q, k, v, o, gate, up, down
         po = o.params(o.FP8_E4M3, args.chunk_kib * 1024, (args.max_len, 0, 0), 64, 1 if args.policy == "auto" else 0)
         host = [srcs[i].cpu().numpy() for i in sample]
         t_c = t_d = 0.0
@@ -238,7 +259,7 @@ def main():
             assert rc == 0 and np.array_equal(out, x)
             nbytes += len(x)
         result["cpu_baseline"] = {"value": nbytes / t_d / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-                                  "sample": "oracle decompress of layer 0's q,k,v,o,gate tensors (%d bytes, %.1f s); "
+                                  "sample": "oracle decompress of layer 0's seven tensors (%d bytes, %.1f s); "
                                             "its compress ran at %.4f GB/s" % (nbytes, t_d, nbytes / t_c / 1e9),
                                   "host_cores_visible": os.cpu_count()}
     print(json.dumps(result))

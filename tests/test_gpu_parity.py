@@ -456,6 +456,9 @@ def test_static_dictionary():
             torch.cuda.synchronize()
             assert torch.equal(out.cpu()[:b.numel() * b.element_size()], b.view(torch.uint8).reshape(-1))
     # a dictionary that cannot code every symbol is refused
+    p = zc.params(fmt, cb, streams=S, policy=zc.POLICY_HUFF_ALL)
+    code = zc.train_code(dev(a), n_a, p, scales=dev(sa))
+    assert code.mode[0] == zc.MODE_HUFF
     code.code_len[0][2] = 0
     with pytest.raises(zc.ZcError):
         zc.compress_with_code(dev(b), n_b, p, code, scales=dev(sb_))
