@@ -144,17 +144,23 @@ zc_status zc_compress(const void *d_src, uint64_t n_elems, const zc_params *para
 zc_status zc_compress_batch(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params,
                             void *d_ws, uint64_t ws_bytes, void *stream);
 
-/* Static dictionaries (Sec. 3.3: "precomputed Huffman dictionaries when exponent distributions are
- * stable"; Sec. 5.2: "static Huffman dictionaries trained on representative data").
+/* Static dictionaries (Sec. 3.3, 5.2: a code computed ahead of time on representative data and
+ * reused while the exponent distribution stays stable, e.g. across K/V-cache time steps).
  * zc_train_code builds a dictionary from a representative tensor: its per-field histogram with
  * every count raised by one (so that any symbol can be coded later), then the usual code
- * construction and raw/Huffman decision.  Only format, policy, mode[], sym_bits[], max_len[] and
- * code_len[][] of *out_code are meaningful.  Synchronises.
+ * construction and raw/Huffman decision.  In *out_code, format, policy, mode[], sym_bits[],
+ * max_len[] and code_len[][] describe the dictionary; n_elems, n_chunks, payload_offset and
+ * total_bytes are those of the training tensor's container under it (nothing is written).
+ * Synchronises.
  * zc_compress_with_code / zc_compress_batch_with_code code every tensor with that dictionary:
  * no histogram pass and no code construction, one synchronisation (to size the output) instead
  * of two.  The container is an ordinary one (it carries the dictionary's length tables), so
- * every decompress entry point reads it.  A dictionary whose Huffman fields do not cover the
- * whole alphabet is rejected with ZC_ERR_INVALID_ARG. */
+ * every decompress entry point reads it.  A dictionary whose Huffman fields do not form a
+ * complete prefix code over the whole alphabet is rejected with ZC_ERR_INVALID_ARG.
+ * zc_code_stale (host arithmetic only) is the refresh test of Sec. 3.3: 1 when the container
+ * described by *written (from a *_with_code call) is larger, as a fraction of its raw size, than
+ * the training tensor's was by more than `slack` (absolute, e.g. 0.02), 0 when not, -1 on
+ * arguments that do not fit together. */
 zc_status zc_train_code(const void *d_src, uint64_t n_elems, const zc_params *params,
                         const void *d_xor_base, const void *d_scales, zc_info *out_code,
                         void *d_ws, uint64_t ws_bytes, void *stream);
@@ -164,6 +170,7 @@ zc_status zc_compress_with_code(const void *d_src, uint64_t n_elems, const zc_pa
                                 void *d_ws, uint64_t ws_bytes, void *stream);
 zc_status zc_compress_batch_with_code(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params, const zc_info *code,
                                       void *d_ws, uint64_t ws_bytes, void *stream);
+int zc_code_stale(const zc_info *code, const zc_info *written, double slack);
 
 /* Read and validate a container's header and tables (blocking copy of at most 1 KiB from
  * the device; with check_index != 0 also the chunk index).  d_comp: device; out: host. */

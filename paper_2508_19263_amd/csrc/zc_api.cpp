@@ -378,7 +378,6 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         for (uint64_t c = n_full; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
     }
     if (codes_out) *codes_out = codes;
-    if (train) return ZC_OK;
     HIP_TRY(hipMemcpyAsync(d_descs, descs.data(), T * sizeof(TensorDev), hipMemcpyHostToDevice, hs));
     HIP_TRY(hipMemcpyAsync(ws + w.enc, enc.data(), enc.size() * 4, hipMemcpyHostToDevice, hs));
     if (!fast_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.fast_work, fast_work.data(), fast_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
@@ -665,7 +664,20 @@ zc_status zc_train_code(const void *d_src, uint64_t n_elems, const zc_params *pa
         out_code->max_len[f] = (uint8_t)codes[f].lmax;
         std::memcpy(out_code->code_len[f], codes[f].len, 256);
     }
+    // what the training tensor itself costs under its dictionary: the reference point of zc_code_stale
+    out_code->n_elems = n_elems; out_code->n_chunks = t.info.n_chunks;
+    out_code->total_bytes = t.info.total_bytes; out_code->payload_offset = t.info.payload_offset;
     return ZC_OK;
+}
+
+int zc_code_stale(const zc_info *code, const zc_info *written, double slack)
+{
+    if (!code || !written || code->format != written->format || code->n_elems == 0 || written->n_elems == 0) return -1;
+    if (code->format < ZC_FMT_BF16 || code->format > ZC_FMT_FP4_E2M1_MX || !(slack >= 0.0)) return -1;
+    auto raw = [](const zc_info *i) {
+        return (double)((i->n_elems * (uint64_t)elem_bits(i->format) + 7) / 8 + (i->format == ZC_FMT_FP4_E2M1_MX ? i->n_elems / 32 : 0));
+    };
+    return (double)written->total_bytes / raw(written) > (double)code->total_bytes / raw(code) + slack ? 1 : 0;
 }
 
 zc_status zc_compress_batch_with_code(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params, const zc_info *code,

@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_BUFFER_TOO_SMALL, ERR_CORRUPT, ERR_DEV
 EXPORTS = ["zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_compress_batch", "zc_read_info",
            "zc_decompress", "zc_decompress_chunks", "zc_decompress_batch", "zc_decompress_batch_plan",
            "zc_decompress_batch_run", "zc_stats", "zc_build_code", "zc_train_code", "zc_compress_with_code",
-           "zc_compress_batch_with_code",
+           "zc_compress_batch_with_code", "zc_code_stale",
            "zc_status_string"]
 
 
@@ -93,6 +93,8 @@ def lib():
         L.zc_compress.argtypes = [vp, u64, C.POINTER(Params), vp, vp, vp, u64, C.POINTER(u64), C.POINTER(Info), vp, u64, vp]
         L.zc_compress_batch.restype = C.c_int
         L.zc_compress_batch.argtypes = [C.POINTER(Tensor), u32, C.POINTER(Params), vp, u64, vp]
+        L.zc_code_stale.restype = C.c_int
+        L.zc_code_stale.argtypes = [C.POINTER(Info), C.POINTER(Info), C.c_double]
         L.zc_train_code.restype = C.c_int
         L.zc_train_code.argtypes = [vp, u64, C.POINTER(Params), vp, vp, C.POINTER(Info), vp, u64, vp]
         L.zc_compress_with_code.restype = C.c_int
@@ -198,6 +200,15 @@ def train_code(src, n_elems, p, xor_base=None, scales=None, ws=None):
     st = lib().zc_train_code(_ptr(src), n_elems, C.byref(p), _ptr(xor_base), _ptr(scales), C.byref(code), _ptr(ws), ws.numel(), _stream())
     _check(st, "zc_train_code")
     return code
+
+
+def code_stale(code, written, slack=0.02):
+    """Refresh test for a static dictionary: True when `written` (the Info of a compress_with_code call) is
+    larger relative to its raw size than the training tensor was, by more than `slack`."""
+    r = lib().zc_code_stale(C.byref(code), C.byref(written), slack)
+    if r < 0:
+        raise ZcError(ERR_INVALID_ARG, "zc_code_stale")
+    return bool(r)
 
 
 def compress_with_code(src, n_elems, p, code, xor_base=None, scales=None, dst=None, ws=None):

@@ -449,13 +449,28 @@ def test_static_dictionary():
             ln, md = o.train_code(a.numpy(), n_a, po, scales=None if sa is None else sa.numpy())
             for f in range(code.n_fields):
                 assert list(code.code_len[f]) == ln[f].tolist() and code.mode[f] == md[f]
+            # the dictionary records what its own training tensor costs under it
+            assert code.n_elems == n_a and code.total_bytes == len(o.compress_with_code(a.numpy(), n_a, po, ln, md, scales=None if sa is None else sa.numpy()))
             want = o.compress_with_code(b.numpy(), n_b, po, ln, md, scales=None if sb_ is None else sb_.numpy())
             comp, info = zc.compress_with_code(dev(b), n_b, p, code, scales=dev(sb_))
             assert np.array_equal(comp.cpu().numpy(), want)
             out, sco = zc.decompress(comp, info)
             torch.cuda.synchronize()
             assert torch.equal(out.cpu()[:b.numel() * b.element_size()], b.view(torch.uint8).reshape(-1))
+            assert not zc.code_stale(code, info, 0.02)      # same distribution: no refresh
+    # refresh test: data of another distribution compresses worse under the dictionary than the training data did
+    p = zc.params(zc.FMT_FP8_E4M3, 65536)
+    a = wl.fp8_weight(1 << 20, seed=50)
+    k, v = wl.fp8_kv_pair(batch=1, heads=2, tokens=4096, seed=51)
+    code = zc.train_code(dev(a), a.numel(), p)
+    _, info_k = zc.compress_with_code(dev(k.reshape(-1)), k.numel(), p, code)
+    want_k = o.compress_with_code(k.reshape(-1).numpy(), k.numel(), o.params(o.FP8_E4M3, 65536), *o.train_code(a.numpy(), a.numel(), o.params(o.FP8_E4M3, 65536)))
+    assert info_k.total_bytes == len(want_k)
+    assert zc.code_stale(code, info_k, 0.02) == (len(want_k) / k.numel() > code.total_bytes / a.numel() + 0.02)
+    assert zc.code_stale(code, info_k, 0.02)
     # a dictionary that cannot code every symbol is refused
+    fmt, n_a, cb, S = zc.FMT_FP4_E2M1_MX, 32 * 4000, 16384, 64
+    a, sa = make_input(fmt, n_a, 41)
     p = zc.params(fmt, cb, streams=S, policy=zc.POLICY_HUFF_ALL)
     code = zc.train_code(dev(a), n_a, p, scales=dev(sa))
     assert code.mode[0] == zc.MODE_HUFF

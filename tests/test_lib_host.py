@@ -70,3 +70,22 @@ def test_bounds_and_workspace():
     assert zc.compress_bound(33, zc.params(zc.FMT_FP4_E2M1_MX, 256)) == 0     # FP4 needs whole 32-blocks
     assert zc.compress_bound(64, zc.params(zc.FMT_FP8_E4M3, 4096, (3, 0, 0))) == 0   # 2^3 < 16 symbols
     assert zc.status_string(zc.ERR_CORRUPT) == "corrupt container"
+
+
+def test_code_stale_arithmetic():
+    # the refresh test of a static dictionary is host arithmetic on two container descriptions
+    code, w = zc.Info(), zc.Info()
+    code.format = w.format = zc.FMT_FP8_E4M3
+    code.n_elems, code.total_bytes = 1000000, 800000          # training tensor: ratio 0.80
+    w.n_elems, w.total_bytes = 500000, 410000                 # 0.82
+    assert zc.code_stale(code, w, 0.03) is False
+    assert zc.code_stale(code, w, 0.01) is True
+    w.format = zc.FMT_BF16                                    # another format: refused
+    with pytest.raises(zc.ZcError):
+        zc.code_stale(code, w, 0.01)
+    code.format = w.format = zc.FMT_FP4_E2M1_MX               # raw size counts the scale bytes: n/2 + n/32
+    code.n_elems, code.total_bytes = 3200, 1700
+    w.n_elems, w.total_bytes = 6400, 3400 + 33
+    assert zc.code_stale(code, w, 0.01) is False              # 3433/3400 = 1.0097 against 1700/1700 = 1
+    w.total_bytes = 3400 + 69
+    assert zc.code_stale(code, w, 0.01) is True
