@@ -3,7 +3,9 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <algorithm>
 #include <cstring>
+#include <thread>
 #include <vector>
 
 #include "zc_internal.h"
@@ -344,23 +346,25 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         HIP_TRY(hipStreamSynchronize(hs));
     }
 
-    // code construction on the host (a4)
+    // code construction on the host (a4): tensors are independent, so a large set is split over a few threads
     std::vector<FieldCode> codes((size_t)T * 3);
     std::vector<WorkItem> fast_work, slow_work;
     std::vector<uint32_t> enc((size_t)T * 768, 0);
     std::vector<uint8_t> blobs((size_t)T * kBlobBytes, 0);
-    for (uint32_t t = 0; t < T; t++) {
+    std::vector<uint8_t> fast_flag(T, 0);
+    auto build_one = [&](uint32_t t) -> zc_status {
         FieldCode *fc = &codes[(size_t)t * 3];
-        st = dict ? codes_from_dictionary(g, tensors[t].n_elems, *dict, fc)
-                  : build_codes(g, params->policy, tensors[t].n_elems, &hist[(size_t)t * 768], fc, train);
-        if (st) return st;
+        const zc_status s1 = dict ? codes_from_dictionary(g, tensors[t].n_elems, *dict, fc)
+                                  : build_codes(g, params->policy, tensors[t].n_elems, &hist[(size_t)t * 768], fc, train);
+        if (s1) return s1;
         fill_info(g, params->policy, tensors[t].d_xor_base != nullptr, tensors[t].n_elems, ncs[t], fc, 0, &tensors[t].info);
         serialize_blob(tensors[t].info, &blobs[(size_t)t * kBlobBytes]);
         for (uint32_t f = 0; f < g.nf; f++) {
             descs[t].mode[f] = (uint8_t)fc[f].mode; descs[t].lmax[f] = (uint8_t)fc[f].lmax; descs[t].konst[f] = (uint8_t)fc[f].konst;
             descs[t].period[f] = (uint8_t)refill_period(run_len(g.fmt, (int)f), (int)fc[f].lmax);
             descs[t].kind[f] = field_kind(fc[f].mode, (uint32_t)sym_bits(g.fmt, (int)f), fc[f].len);
-            for (int v = 0; v < 256; v++)
+            const int A = 1 << sym_bits(g.fmt, (int)f);
+            for (int v = 0; v < A; v++)
                 enc[(size_t)t * 768 + f * 256 + v] = ((uint32_t)fc[f].len[v] << 16) | reverse_bits(fc[f].code[v], fc[f].len[v]);
         }
         // FP8 shape the specialised size/encode kernels take: 64 lanes, chunks of whole 1 KiB rows,
@@ -371,9 +375,30 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         if (fast_ok)
             for (uint32_t u = 0; u < 256; u++) {
                 const uint32_t e0 = u & 15, e1 = u >> 4, l0 = fc[0].len[e0], l1 = fc[0].len[e1];
-                enc[(size_t)t * 768 + 512 + u] = ((l0 + l1) << 16) | reverse_bits(fc[0].code[e0], (int)l0) | (reverse_bits(fc[0].code[e1], (int)l1) << l0);
+                enc[(size_t)t * 768 + 512 + u] = ((l0 + l1) << 16) | (enc[(size_t)t * 768 + e0] & 0xFFFFu) | ((enc[(size_t)t * 768 + e1] & 0xFFFFu) << l0);
             }
-        const uint64_t n_full = fast_ok ? tensors[t].n_elems / g.elems_per_chunk : 0;
+        fast_flag[t] = fast_ok;
+        return ZC_OK;
+    };
+    const uint32_t n_threads = T >= 64 ? std::min<uint32_t>(8, std::max(1u, std::thread::hardware_concurrency())) : 1;
+    if (n_threads <= 1) {
+        for (uint32_t t = 0; t < T; t++) { st = build_one(t); if (st) return st; }
+    } else {
+        std::vector<zc_status> status(n_threads, ZC_OK);
+        std::vector<std::thread> pool;
+        auto range = [&](uint32_t k) {
+            for (uint32_t t = (uint32_t)((uint64_t)T * k / n_threads); t < (uint32_t)((uint64_t)T * (k + 1) / n_threads); t++) {
+                const zc_status s1 = build_one(t);
+                if (s1) { status[k] = s1; return; }
+            }
+        };
+        for (uint32_t k = 1; k < n_threads; k++) pool.emplace_back(range, k);
+        range(0);
+        for (auto &th : pool) th.join();
+        for (uint32_t k = 0; k < n_threads; k++) if (status[k]) return status[k];
+    }
+    for (uint32_t t = 0; t < T; t++) {
+        const uint64_t n_full = fast_flag[t] ? tensors[t].n_elems / g.elems_per_chunk : 0;
         for (uint64_t c = 0; c < n_full; c += kWavesPerGroup) fast_work.push_back({t, (uint32_t)c});
         for (uint64_t c = n_full; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
     }

@@ -27,48 +27,75 @@ namespace zc {
 // histogram; FP4: joint over two elements; E8M0 scales: the field itself); the host takes
 // the marginals.  BF16: two histograms, exponent and sign+mantissa symbol.
 
+// One copy of the 256 bins per LDS bank: lane l counts in copy l % 32, at word bin * 32 + l % 32, so the
+// 32 lanes of an LDS pass always hit 32 different banks whatever the data is.  BF16 keeps both fields in
+// one word (exponent count in the low half, sign+mantissa count in the high half): a copy is fed by 8
+// threads with at most 512 elements each per block, so neither half can overflow.
 template <bool BF16>
 __global__ __launch_bounds__(256) void k_hist(const TensorDev *descs, const WorkItem *work, int elem_bits_, int scales_view, uint64_t *hist)
 {
-    __shared__ uint32_t h[2][256 * 8];
+    static_assert(kHistBlockBytes / 2 / 32 < 65536, "a copy counts at most block elements / 32 per half-word");
+    __shared__ uint32_t h[256 * 32];
     const WorkItem it = work[blockIdx.x];
     const TensorDev &d = descs[it.tensor];
     const uint8_t *p = scales_view ? d.scales : d.src;
     const uint8_t *base = scales_view ? nullptr : d.base;
     const uint64_t nbytes = scales_view ? d.n_elems / 32 : (d.n_elems * (uint64_t)elem_bits_ + 7) / 8;
-    for (uint32_t i = threadIdx.x; i < 2 * 256 * 8; i += 256) (&h[0][0])[i] = 0;
+    for (uint32_t i = threadIdx.x; i < 256 * 32; i += 256) h[i] = 0;
     __syncthreads();
     const uint64_t start = (uint64_t)it.first * kHistBlockBytes;
     const uint64_t end = start + kHistBlockBytes < nbytes ? start + kHistBlockBytes : nbytes;
-    const uint32_t rep = threadIdx.x & 7;
-    for (uint64_t off = start + (uint64_t)threadIdx.x * 16; off < end; off += 256 * 16) {
-        const uint32_t valid = end - off >= 16 ? 16u : (uint32_t)(end - off);
-        uint4 v = load_run(p + off, valid);
-        if (base) v = xor4(v, load_run(base + off, valid));
+    uint32_t *const mine = h + (threadIdx.x & 31);
+    auto count = [&](const uint4 &v, uint32_t valid) {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
         if (BF16) {
 #pragma unroll
             for (int i = 0; i < 8; i++)
                 if (2u * i < valid) {
                     const uint32_t x = (w[i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
-                    atomicAdd(&h[0][((x >> 7) & 0xFFu) * 8 + rep], 1u);
-                    atomicAdd(&h[1][(((x >> 8) & 0x80u) | (x & 0x7Fu)) * 8 + rep], 1u);
+                    atomicAdd(mine + ((x >> 7) & 0xFFu) * 32, 1u);
+                    atomicAdd(mine + (((x >> 8) & 0x80u) | (x & 0x7Fu)) * 32, 0x10000u);
                 }
         } else {
 #pragma unroll
             for (int i = 0; i < 16; i++)
-                if ((uint32_t)i < valid) atomicAdd(&h[0][((w[i >> 2] >> (8 * (i & 3))) & 0xFFu) * 8 + rep], 1u);
+                if ((uint32_t)i < valid) atomicAdd(mine + ((w[i >> 2] >> (8 * (i & 3))) & 0xFFu) * 32, 1u);
+        }
+    };
+    if (end - start == kHistBlockBytes) {
+        // whole block: four 16-byte loads per thread in flight at a time
+        constexpr uint32_t kStep = 256 * 16;
+        for (uint64_t off = start + (uint64_t)threadIdx.x * 16; off < end; off += 4 * kStep) {
+            uint4 v[4];
+#pragma unroll
+            for (int k = 0; k < 4; k++) v[k] = *reinterpret_cast<const uint4 *>(p + off + k * kStep);
+            if (base) {
+#pragma unroll
+                for (int k = 0; k < 4; k++) v[k] = xor4(v[k], *reinterpret_cast<const uint4 *>(base + off + k * kStep));
+            }
+#pragma unroll
+            for (int k = 0; k < 4; k++) count(v[k], 16);
+        }
+    } else {
+        for (uint64_t off = start + (uint64_t)threadIdx.x * 16; off < end; off += 256 * 16) {
+            const uint32_t valid = end - off >= 16 ? 16u : (uint32_t)(end - off);
+            uint4 v = load_run(p + off, valid);
+            if (base) v = xor4(v, load_run(base + off, valid));
+            count(v, valid);
         }
     }
     __syncthreads();
+    // thread b sums the 32 copies of bin b, starting at a different copy per thread (different banks)
     const uint32_t bin = threadIdx.x;
-    for (int f = 0; f < (BF16 ? 2 : 1); f++) {
-        uint32_t sum = 0;
-#pragma unroll
-        for (int r = 0; r < 8; r++) sum += h[f][bin * 8 + r];
-        const int slot = BF16 ? f : (scales_view ? 2 : 0);
-        if (sum) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + slot) * 256 + bin]), (unsigned long long)sum);
+    uint32_t lo = 0, hi = 0;
+#pragma unroll 8
+    for (uint32_t r = 0; r < 32; r++) {
+        const uint32_t c = h[bin * 32 + ((r + bin) & 31)];
+        if (BF16) { lo += c & 0xFFFFu; hi += c >> 16; } else lo += c;
     }
+    const int slot = BF16 ? 0 : (scales_view ? 2 : 0);
+    if (lo) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + slot) * 256 + bin]), (unsigned long long)lo);
+    if (BF16 && hi) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + 1) * 256 + bin]), (unsigned long long)hi);
 }
 
 int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, int scales_view, uint64_t *d_hist, void *stream)
