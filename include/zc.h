@@ -48,7 +48,14 @@ typedef enum {
 typedef enum {
     ZC_FMT_BF16 = 1,        /* fields: 8-bit exponent, 8-bit sign+mantissa (Sec. 3.1) */
     ZC_FMT_FP8_E4M3 = 2,    /* fields: 4-bit exponent, 4-bit sign+mantissa (Sec. 3.2) */
-    ZC_FMT_FP4_E2M1_MX = 3  /* fields: 2-bit exponent, 2-bit sign+mantissa, 8-bit E8M0 scale (Sec. 3.4) */
+    ZC_FMT_FP4_E2M1_MX = 3, /* fields: 2-bit exponent, 2-bit sign+mantissa, 8-bit E8M0 scale (Sec. 3.4) */
+    /* The same elements and fields as formats 2 and 3, coded in byte-sized groups (Sec. 3.2 with Fig. 7:
+     * FP8 exponents, and sign+mantissa values, paired into bytes; Sec. 3.4: four 2-bit FP4 values per
+     * byte): one Huffman symbol is one byte of the packed field array, i.e. 2 (FP8) or 4 (FP4)
+     * consecutive field values with the first in the low bits, so every field has a 256-symbol alphabet.
+     * A last group that runs past the tensor is filled with zero values. */
+    ZC_FMT_FP8_E4M3_BYTES = 4,
+    ZC_FMT_FP4_E2M1_MX_BYTES = 5
 } zc_format;
 
 typedef enum {

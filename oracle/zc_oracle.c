@@ -43,7 +43,11 @@
 
 /* ------------------------------------------------------------------ formats */
 
-enum { ZCO_BF16 = 1, ZCO_FP8_E4M3 = 2, ZCO_FP4_E2M1_MX = 3 };
+/* Formats 4 and 5 hold the same elements and the same two (three) fields as 2 and 3, but code the
+ * field values in byte-sized groups (Sec. 3.2, Fig. 7: FP8 exponents and sign+mantissa values
+ * paired into bytes; Sec. 3.4: four 2-bit FP4 values per byte): one Huffman symbol = one byte of
+ * the packed field array = 2 (FP8) or 4 (FP4) consecutive field values, first value in the low bits. */
+enum { ZCO_BF16 = 1, ZCO_FP8_E4M3 = 2, ZCO_FP4_E2M1_MX = 3, ZCO_FP8_E4M3_BYTES = 4, ZCO_FP4_E2M1_MX_BYTES = 5 };
 enum { ZCO_MODE_EMPTY = 0, ZCO_MODE_HUFF = 1, ZCO_MODE_RAW = 2, ZCO_MODE_CONST = 3 };
 enum { ZCO_POLICY_HUFF_ALL = 0, ZCO_POLICY_AUTO = 1 };
 enum { ZCO_OK = 0, ZCO_ERR_ARG = 1, ZCO_ERR_UNSUPPORTED = 2, ZCO_ERR_SMALL = 3, ZCO_ERR_CORRUPT = 4 };
@@ -56,36 +60,57 @@ typedef struct {
     uint32_t policy;
 } zco_params;
 
+/* element format of a (possibly byte-grouped) format, and field values per coded symbol */
+static int base_format(int format)
+{
+    return format == ZCO_FP8_E4M3_BYTES ? ZCO_FP8_E4M3 : format == ZCO_FP4_E2M1_MX_BYTES ? ZCO_FP4_E2M1_MX : format;
+}
+
+static int group_of(int format)
+{
+    return format == ZCO_FP8_E4M3_BYTES ? 2 : format == ZCO_FP4_E2M1_MX_BYTES ? 4 : 1;
+}
+
 static int elem_bits(int format)
 {
+    format = base_format(format);
     return format == ZCO_BF16 ? 16 : format == ZCO_FP8_E4M3 ? 8 : format == ZCO_FP4_E2M1_MX ? 4 : 0;
 }
 
 int zco_num_fields(int format)
 {
+    format = base_format(format);
     return format == ZCO_FP4_E2M1_MX ? 3 : (format == ZCO_BF16 || format == ZCO_FP8_E4M3) ? 2 : 0;
 }
 
-/* width of one symbol of field f: field 0 = exponent, 1 = sign+mantissa, 2 = block scale */
-int zco_sym_bits(int format, int f)
+/* width of one field value of field f: field 0 = exponent, 1 = sign+mantissa, 2 = block scale */
+static int value_bits(int format, int f)
 {
+    format = base_format(format);
     if (format == ZCO_BF16) return 8;
     if (format == ZCO_FP8_E4M3) return 4;
     if (format == ZCO_FP4_E2M1_MX) return f == 2 ? 8 : 2;
     return 0;
 }
 
+/* width of one coded symbol of field f */
+int zco_sym_bits(int format, int f)
+{
+    if (!elem_bits(format)) return 0;
+    return f == 2 ? 8 : value_bits(format, f) * group_of(format);
+}
+
 /* symbols that make up one 16-byte run of the field's plain array */
 static int run_len(int format, int f)
 {
-    if (format == ZCO_FP4_E2M1_MX && f == 2) return 16;   /* 16 scale bytes */
-    return 128 / elem_bits(format);                       /* 16 bytes of elements */
+    if (f == 2) return 16;                                     /* 16 scale bytes */
+    return 128 / elem_bits(format) / group_of(format);         /* 16 bytes of elements */
 }
 
 static uint64_t num_symbols(int format, int f, uint64_t n_elems)
 {
-    if (format == ZCO_FP4_E2M1_MX && f == 2) return n_elems / 32;  /* one E8M0 byte per 32 elements */
-    return n_elems;
+    if (f == 2) return n_elems / 32;                           /* one E8M0 byte per 32 elements */
+    return (n_elems + (uint64_t)group_of(format) - 1) / (uint64_t)group_of(format);
 }
 
 /* ---------------------------------------------------- field split / rebuild */
@@ -95,6 +120,7 @@ static uint64_t num_symbols(int format, int f, uint64_t n_elems)
 /* element i of the tensor as an unsigned integer (FP4: element 2i is the low nibble) */
 static unsigned load_elem(int format, const uint8_t *p, uint64_t i)
 {
+    format = base_format(format);
     if (format == ZCO_BF16) return (unsigned)p[2 * i] | ((unsigned)p[2 * i + 1] << 8);
     if (format == ZCO_FP8_E4M3) return p[i];
     return (i & 1) ? (p[i / 2] >> 4) : (p[i / 2] & 0xF);
@@ -102,6 +128,7 @@ static unsigned load_elem(int format, const uint8_t *p, uint64_t i)
 
 static void store_elem(int format, uint8_t *p, uint64_t i, unsigned x)
 {
+    format = base_format(format);
     if (format == ZCO_BF16) { p[2 * i] = (uint8_t)(x & 0xFF); p[2 * i + 1] = (uint8_t)(x >> 8); }
     else if (format == ZCO_FP8_E4M3) p[i] = (uint8_t)x;
     else if (i & 1) p[i / 2] = (uint8_t)((p[i / 2] & 0x0F) | (x << 4));
@@ -110,6 +137,7 @@ static void store_elem(int format, uint8_t *p, uint64_t i, unsigned x)
 
 unsigned zco_exponent_of(int format, unsigned x)
 {
+    format = base_format(format);
     if (format == ZCO_BF16) return (x >> 7) & 0xFF;        /* s eeeeeeee mmmmmmm */
     if (format == ZCO_FP8_E4M3) return (x >> 3) & 0xF;     /* s eeee mmm */
     return (x >> 1) & 0x3;                                 /* s ee m */
@@ -117,6 +145,7 @@ unsigned zco_exponent_of(int format, unsigned x)
 
 unsigned zco_signmant_of(int format, unsigned x)
 {
+    format = base_format(format);
     if (format == ZCO_BF16) return ((x >> 15) << 7) | (x & 0x7F);
     if (format == ZCO_FP8_E4M3) return ((x >> 7) << 3) | (x & 0x7);
     return ((x >> 3) << 1) | (x & 0x1);
@@ -124,6 +153,7 @@ unsigned zco_signmant_of(int format, unsigned x)
 
 unsigned zco_rebuild(int format, unsigned e, unsigned sm)
 {
+    format = base_format(format);
     if (format == ZCO_BF16) return ((sm >> 7) << 15) | (e << 7) | (sm & 0x7F);
     if (format == ZCO_FP8_E4M3) return ((sm >> 3) << 7) | (e << 3) | (sm & 0x7);
     return ((sm >> 1) << 3) | (e << 1) | (sm & 0x1);
@@ -150,6 +180,27 @@ void zco_join(int format, const uint8_t *exp_in, const uint8_t *sm_in, const uin
         if (base) x ^= load_elem(format, base, i);
         store_elem(format, dst, i, x);
     }
+}
+
+/* Coded symbols of field f (0 or 1) from its field values (one per byte, as zco_split leaves them):
+ * symbol j = values g*j .. g*j+g-1, the first in the low bits; values past the end count as 0. */
+void zco_group_values(int format, int f, const uint8_t *values, uint64_t n_elems, uint8_t *syms)
+{
+    int g = group_of(format), vb = value_bits(format, f);
+    uint64_t ns = num_symbols(format, f, n_elems);
+    for (uint64_t j = 0; j < ns; j++) {
+        unsigned s = 0;
+        for (int k = 0; k < g; k++)
+            if (g * j + (uint64_t)k < n_elems) s |= (unsigned)values[g * j + (uint64_t)k] << (k * vb);
+        syms[j] = (uint8_t)s;
+    }
+}
+
+void zco_ungroup_symbols(int format, int f, const uint8_t *syms, uint64_t n_elems, uint8_t *values)
+{
+    int g = group_of(format), vb = value_bits(format, f);
+    for (uint64_t i = 0; i < n_elems; i++)
+        values[i] = (uint8_t)((syms[i / (uint64_t)g] >> ((int)(i % (uint64_t)g) * vb)) & ((1u << vb) - 1));
 }
 
 void zco_histogram(const uint8_t *syms, uint64_t n, uint64_t *hist256)
@@ -465,7 +516,7 @@ static int check_params(const zco_params *p, uint64_t n_elems, int *S)
     *S = p->streams_per_chunk ? (int)p->streams_per_chunk : 64;
     if (*S != 1 && *S != 2 && *S != 4 && *S != 8 && *S != 16 && *S != 32 && *S != 64) return ZCO_ERR_ARG;
     if (p->chunk_bytes == 0 || p->chunk_bytes % 16) return ZCO_ERR_ARG;
-    if (p->format == ZCO_FP4_E2M1_MX && (p->chunk_bytes % 256 || n_elems % 32)) return ZCO_ERR_ARG;
+    if (base_format((int)p->format) == ZCO_FP4_E2M1_MX && (p->chunk_bytes % 256 || n_elems % 32)) return ZCO_ERR_ARG;
     if (p->policy > 1) return ZCO_ERR_ARG;
     return ZCO_OK;
 }
@@ -486,7 +537,8 @@ static uint64_t chunk_symbols(const zco_params *p, int f, uint64_t n_elems, uint
     uint64_t E = elems_per_chunk(p);
     uint64_t lo = c * E, hi = lo + E;
     if (hi > n_elems) hi = n_elems;
-    if (p->format == ZCO_FP4_E2M1_MX && f == 2) { lo /= 32; hi /= 32; }
+    if (f == 2) { lo /= 32; hi /= 32; }
+    else { uint64_t g = (uint64_t)group_of((int)p->format); lo /= g; hi = (hi + g - 1) / g; }   /* E is a multiple of g */
     *first = lo;
     return hi - lo;
 }
@@ -504,6 +556,24 @@ uint64_t zco_compress_bound(uint64_t n_elems, const zco_params *p)
     return total;
 }
 
+/* The coded symbols of every field of a tensor, one per byte, in freshly allocated arrays:
+ * field split (+ XOR delta), then byte grouping for the formats that have it. */
+static void tensor_symbols(int fmt, const uint8_t *src, const uint8_t *xor_base, const uint8_t *scales,
+                           uint64_t n_elems, uint8_t *sym[3])
+{
+    int nf = zco_num_fields(fmt);
+    uint8_t *e = malloc((size_t)n_elems + 1), *m = malloc((size_t)n_elems + 1);
+    zco_split(fmt, src, xor_base, n_elems, e, m);
+    sym[0] = e; sym[1] = m; sym[2] = NULL;
+    if (group_of(fmt) > 1) {
+        sym[0] = malloc((size_t)num_symbols(fmt, 0, n_elems) + 1); sym[1] = malloc((size_t)num_symbols(fmt, 1, n_elems) + 1);
+        zco_group_values(fmt, 0, e, n_elems, sym[0]);
+        zco_group_values(fmt, 1, m, n_elems, sym[1]);
+        free(e); free(m);
+    }
+    if (nf == 3) { sym[2] = malloc((size_t)(n_elems / 32) + 1); if (n_elems) memcpy(sym[2], scales, (size_t)(n_elems / 32)); }
+}
+
 /* Compress.  src: the tensor (FP4: two elements per byte, element 2i in the low
  * nibble).  xor_base: NULL or a tensor of the same shape.  scales: FP4 only,
  * n_elems/32 E8M0 bytes.  Returns a status; *out_bytes = container size. */
@@ -514,15 +584,13 @@ static int compress_impl(const uint8_t *src, uint64_t n_elems, const zco_params 
     int S, rc = check_params(p, n_elems, &S);
     if (rc) return rc;
     int fmt = (int)p->format, nf = zco_num_fields(fmt);
-    if (fmt == ZCO_FP4_E2M1_MX && n_elems && !scales) return ZCO_ERR_ARG;
+    if (nf == 3 && n_elems && !scales) return ZCO_ERR_ARG;
     uint64_t E = elems_per_chunk(p), nc = (n_elems + E - 1) / E;
     if (nc > 0xFFFFFFFFu) return ZCO_ERR_ARG;
 
     /* 1. split into per-field symbol arrays (one symbol per byte) */
     uint8_t *sym[3] = { 0, 0, 0 };
-    sym[0] = malloc((size_t)n_elems + 1); sym[1] = malloc((size_t)n_elems + 1);
-    zco_split(fmt, src, xor_base, n_elems, sym[0], sym[1]);
-    if (nf == 3) { sym[2] = malloc((size_t)(n_elems / 32) + 1); memcpy(sym[2], scales, (size_t)(n_elems / 32)); }
+    tensor_symbols(fmt, src, xor_base, scales, n_elems, sym);
 
     /* 2. histogram, mode, code per field (one code per field per tensor) */
     uint8_t len[3][256], mode[3], lmax[3], konst[3];
@@ -619,9 +687,9 @@ int zco_compress(const uint8_t *src, uint64_t n_elems, const zco_params *p, cons
     return compress_impl(src, n_elems, p, xor_base, scales, NULL, NULL, dst, cap, out_bytes);
 }
 
-/* Compress with a precomputed code (Sec. 3.3: "precomputed Huffman dictionaries when exponent
- * distributions are stable"; Sec. 5.2: "static Huffman dictionaries trained on representative
- * data").  static_len: 3 x 256 code lengths, static_mode: 3 modes (HUFF or RAW). */
+/* Compress with a code computed ahead of time on other, representative data (Sec. 3.3 and 5.2:
+ * static dictionaries for K/V caches whose exponent distribution stays stable).
+ * static_len: 3 x 256 code lengths, static_mode: 3 modes (HUFF or RAW). */
 int zco_compress_with_code(const uint8_t *src, uint64_t n_elems, const zco_params *p, const uint8_t *xor_base,
                            const uint8_t *scales, const uint8_t *static_len, const uint8_t *static_mode,
                            uint8_t *dst, uint64_t cap, uint64_t *out_bytes)
@@ -639,11 +707,12 @@ int zco_train_code(const uint8_t *src, uint64_t n_elems, const zco_params *p, co
     int S, rc = check_params(p, n_elems, &S);
     if (rc) return rc;
     int fmt = (int)p->format, nf = zco_num_fields(fmt);
-    uint8_t *e = malloc((size_t)n_elems + 1), *m = malloc((size_t)n_elems + 1);
-    zco_split(fmt, src, xor_base, n_elems, e, m);
+    uint8_t *sym[3];
+    if (nf == 3 && n_elems && !scales) return ZCO_ERR_ARG;
+    tensor_symbols(fmt, src, xor_base, scales, n_elems, sym);
     memset(len_out, 0, 768); memset(mode_out, 0, 3);
     for (int f = 0; f < nf && !rc; f++) {
-        const uint8_t *syms = f == 0 ? e : f == 1 ? m : scales;
+        const uint8_t *syms = sym[f];
         uint64_t hist[256], ns = num_symbols(fmt, f, n_elems), bits = 0, total = 0;
         int sb = zco_sym_bits(fmt, f), A = 1 << sb;
         zco_histogram(syms, ns, hist);
@@ -653,7 +722,7 @@ int zco_train_code(const uint8_t *src, uint64_t n_elems, const zco_params *p, co
         mode_out[f] = ZCO_MODE_HUFF;
         if (p->policy == ZCO_POLICY_AUTO && 16 * bits > 15 * total * (uint64_t)sb) { mode_out[f] = ZCO_MODE_RAW; memset(len_out + 256 * f, 0, 256); }
     }
-    free(e); free(m);
+    free(sym[0]); free(sym[1]); free(sym[2]);
     return rc;
 }
 
@@ -728,12 +797,21 @@ int zco_decompress_chunk(const uint8_t *comp, uint64_t comp_bytes, uint64_t c, c
     if (v.xor_flag && !xor_base_chunk) return ZCO_ERR_ARG;
     zco_params p; memset(&p, 0, sizeof(p));
     p.format = (uint32_t)v.fmt; p.chunk_bytes = v.chunk_bytes;
-    uint64_t first, n = chunk_symbols(&p, 0, v.n_elems, c, &first);
+    uint64_t first, ns01 = chunk_symbols(&p, 0, v.n_elems, c, &first);
+    uint64_t E = elems_per_chunk(&p), n = v.n_elems - c * E < E ? v.n_elems - c * E : E;    /* elements in the chunk */
     uint64_t out_bytes = (n * (uint64_t)elem_bits(v.fmt) + 7) / 8;
     if (out_bytes > dst_cap) return ZCO_ERR_SMALL;
     uint8_t *e = malloc((size_t)n + 1), *m = malloc((size_t)n + 1);
-    rc = decode_field_chunk(comp, &v, 0, c, n, e);
-    if (!rc) rc = decode_field_chunk(comp, &v, 1, c, n, m);
+    if (group_of(v.fmt) == 1) {
+        rc = decode_field_chunk(comp, &v, 0, c, n, e);
+        if (!rc) rc = decode_field_chunk(comp, &v, 1, c, n, m);
+    } else {
+        uint8_t *s0 = malloc((size_t)ns01 + 1), *s1 = malloc((size_t)ns01 + 1);
+        rc = decode_field_chunk(comp, &v, 0, c, ns01, s0);
+        if (!rc) rc = decode_field_chunk(comp, &v, 1, c, ns01, s1);
+        if (!rc) { zco_ungroup_symbols(v.fmt, 0, s0, n, e); zco_ungroup_symbols(v.fmt, 1, s1, n, m); }
+        free(s0); free(s1);
+    }
     if (!rc) zco_join(v.fmt, e, m, v.xor_flag ? xor_base_chunk : NULL, n, dst);
     if (!rc && v.nf == 3) {
         uint64_t ns = chunk_symbols(&p, 2, v.n_elems, c, &first);
@@ -799,12 +877,12 @@ int zco_stats(const uint8_t *src, uint64_t n_elems, const zco_params *p, const u
     zco_view v;
     parse(tmp, total, &v);
     out->container_bytes = total;
-    uint8_t *e = malloc((size_t)n_elems + 1), *m = malloc((size_t)n_elems + 1);
-    zco_split(fmt, src, xor_base, n_elems, e, m);
+    uint8_t *sym[3];
+    tensor_symbols(fmt, src, xor_base, scales, n_elems, sym);
     uint64_t all_bits = 0;
     for (int f = 0; f < nf; f++) {
         zco_field_stats *fs = &out->field[f];
-        const uint8_t *syms = f == 0 ? e : f == 1 ? m : scales;
+        const uint8_t *syms = sym[f];
         int sb = zco_sym_bits(fmt, f);
         fs->alphabet = 1u << sb; fs->n_symbols = num_symbols(fmt, f, n_elems); fs->mode = v.mode[f]; fs->max_len = v.lmax[f];
         zco_histogram(syms, fs->n_symbols, fs->hist);
@@ -827,6 +905,6 @@ int zco_stats(const uint8_t *src, uint64_t n_elems, const zco_params *p, const u
         out->ratio_payload_total = (double)all_bits / (8.0 * (double)out->raw_bytes);
         out->ratio_container_total = (double)total / (double)out->raw_bytes;
     }
-    free(e); free(m); free(tmp);
+    free(sym[0]); free(sym[1]); free(sym[2]); free(tmp);
     return ZCO_OK;
 }

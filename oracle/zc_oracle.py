@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "zc_oracle.c")
 _LIB = os.path.join(_HERE, "libzc_oracle.so")
 
-BF16, FP8_E4M3, FP4_E2M1_MX = 1, 2, 3
+BF16, FP8_E4M3, FP4_E2M1_MX, FP8_E4M3_BYTES, FP4_E2M1_MX_BYTES = 1, 2, 3, 4, 5
 MODE_EMPTY, MODE_HUFF, MODE_RAW, MODE_CONST = 0, 1, 2, 3
 POLICY_HUFF_ALL, POLICY_AUTO = 0, 1
 OK, ERR_ARG, ERR_UNSUPPORTED, ERR_SMALL, ERR_CORRUPT = 0, 1, 2, 3, 4
@@ -64,6 +64,8 @@ def lib():
         _lib.zco_split.argtypes = [C.c_int, u8p, u8p, u64, u8p, u8p]
         _lib.zco_join.argtypes = [C.c_int, u8p, u8p, u8p, u64, u8p]
         _lib.zco_histogram.argtypes = [u8p, u64, u8p]
+        _lib.zco_group_values.argtypes = [C.c_int, C.c_int, u8p, u64, u8p]
+        _lib.zco_ungroup_symbols.argtypes = [C.c_int, C.c_int, u8p, u64, u8p]
         _lib.zco_code_lengths.restype = C.c_int
         _lib.zco_code_lengths.argtypes = [u8p, C.c_int, C.c_int, u8p]
         _lib.zco_canonical_codes.argtypes = [u8p, C.c_int, u8p]
@@ -110,7 +112,25 @@ def params(fmt, chunk_bytes, max_code_len=(0, 0, 0), streams=0, policy=POLICY_HU
 
 
 def elem_bits(fmt):
-    return {BF16: 16, FP8_E4M3: 8, FP4_E2M1_MX: 4}[fmt]
+    return {BF16: 16, FP8_E4M3: 8, FP4_E2M1_MX: 4, FP8_E4M3_BYTES: 8, FP4_E2M1_MX_BYTES: 4}[fmt]
+
+
+def group_of(fmt):
+    """Field values per coded symbol."""
+    return {FP8_E4M3_BYTES: 2, FP4_E2M1_MX_BYTES: 4}.get(fmt, 1)
+
+
+def group_values(fmt, f, values, n_elems):
+    """Coded symbols of field f from its per-element field values (byte-grouped formats)."""
+    out = np.zeros((n_elems + group_of(fmt) - 1) // group_of(fmt), np.uint8)
+    lib().zco_group_values(fmt, f, _p(np.ascontiguousarray(values, np.uint8)), n_elems, _p(out))
+    return out
+
+
+def ungroup_symbols(fmt, f, syms, n_elems):
+    out = np.zeros(n_elems, np.uint8)
+    lib().zco_ungroup_symbols(fmt, f, _p(np.ascontiguousarray(syms, np.uint8)), n_elems, _p(out))
+    return out
 
 
 def split(fmt, src, n_elems, base=None):

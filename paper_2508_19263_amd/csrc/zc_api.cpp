@@ -30,7 +30,7 @@ zc_status check_params(const zc_params *p, Geometry *g)
     g->S = p->streams_per_chunk ? p->streams_per_chunk : 64;
     if (g->S > 64 || (g->S & (g->S - 1))) return ZC_ERR_INVALID_ARG;
     if (p->chunk_bytes == 0 || p->chunk_bytes % 16) return ZC_ERR_INVALID_ARG;
-    if (p->format == ZC_FMT_FP4_E2M1_MX && p->chunk_bytes % 256) return ZC_ERR_INVALID_ARG;
+    if (is_fp4(p->format) && p->chunk_bytes % 256) return ZC_ERR_INVALID_ARG;
     if (p->policy > ZC_POLICY_AUTO) return ZC_ERR_INVALID_ARG;
     g->nf = (uint32_t)num_fields(p->format);
     g->chunk_bytes = p->chunk_bytes;
@@ -47,14 +47,19 @@ zc_status check_params(const zc_params *p, Geometry *g)
 
 zc_status check_count(const Geometry &g, uint64_t n_elems, uint64_t *n_chunks)
 {
-    if (g.fmt == ZC_FMT_FP4_E2M1_MX && n_elems % 32) return ZC_ERR_INVALID_ARG;
+    if (is_fp4(g.fmt) && n_elems % 32) return ZC_ERR_INVALID_ARG;
     const uint64_t nc = (n_elems + g.elems_per_chunk - 1) / g.elems_per_chunk;
     if (nc >= 0xFFFFFFFFull) return ZC_ERR_INVALID_ARG;
     *n_chunks = nc;
     return ZC_OK;
 }
 
-uint64_t field_symbols(uint32_t fmt, int f, uint64_t n_elems) { return (fmt == ZC_FMT_FP4_E2M1_MX && f == 2) ? n_elems / 32 : n_elems; }
+uint64_t field_symbols(uint32_t fmt, int f, uint64_t n_elems)
+{
+    if (f == 2) return n_elems / 32;
+    const uint64_t grp = (uint64_t)group_of(fmt);
+    return (n_elems + grp - 1) / grp;                       // a last partial group counts as one symbol
+}
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 
@@ -134,7 +139,8 @@ zc_status build_codes(const Geometry &g, uint32_t policy, uint64_t n_elems, cons
         std::memset(&c, 0, sizeof(c));
         const int sb = sym_bits(g.fmt, (int)f), A = 1 << sb;
         // marginals of the joint byte histogram (FP8: one element per byte, FP4: two)
-        if (g.fmt == ZC_FMT_BF16) std::memcpy(c.hist, hist3 + 256 * f, 256 * 8);
+        // formats with 8-bit symbols in both fields are counted per field by the kernel
+        if (g.fmt == ZC_FMT_BF16 || (group_of(g.fmt) > 1 && f < 2)) std::memcpy(c.hist, hist3 + 256 * f, 256 * 8);
         else if (g.fmt == ZC_FMT_FP8_E4M3) {
             for (int b = 0; b < 256; b++) {
                 const int sym = f == 0 ? (b >> 3) & 0xF : ((b >> 4) & 8) | (b & 7);
@@ -459,7 +465,7 @@ FastKind fast_kind(const zc_info &info)
 // it needs per wavefront (1 or 2), or 0 if the container has to go through the generic kernel.
 uint32_t s64_rings(const zc_info &info)
 {
-    if (info.streams != 64 || info.chunk_bytes % (info.format == ZC_FMT_FP4_E2M1_MX ? 16384u : 1024u)) return 0;
+    if (info.streams != 64 || info.chunk_bytes % (is_fp4(info.format) ? 16384u : 1024u)) return 0;
     uint32_t huff = 0;
     const TensorDev d = make_desc(info);
     for (uint32_t f = 0; f < info.n_fields; f++) {
@@ -698,9 +704,9 @@ zc_status zc_train_code(const void *d_src, uint64_t n_elems, const zc_params *pa
 int zc_code_stale(const zc_info *code, const zc_info *written, double slack)
 {
     if (!code || !written || code->format != written->format || code->n_elems == 0 || written->n_elems == 0) return -1;
-    if (code->format < ZC_FMT_BF16 || code->format > ZC_FMT_FP4_E2M1_MX || !(slack >= 0.0)) return -1;
+    if (!elem_bits(code->format) || !(slack >= 0.0)) return -1;
     auto raw = [](const zc_info *i) {
-        return (double)((i->n_elems * (uint64_t)elem_bits(i->format) + 7) / 8 + (i->format == ZC_FMT_FP4_E2M1_MX ? i->n_elems / 32 : 0));
+        return (double)((i->n_elems * (uint64_t)elem_bits(i->format) + 7) / 8 + (is_fp4(i->format) ? i->n_elems / 32 : 0));
     };
     return (double)written->total_bytes / raw(written) > (double)code->total_bytes / raw(code) + slack ? 1 : 0;
 }

@@ -459,7 +459,7 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
         __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
     }
 
-    if (FMT == ZC_FMT_FP4_E2M1_MX) {
+    if (F_::NF == 3) {
         // block scales: one byte per 32 elements, 16 per run, the chunk's E/32 scales in rows of 1024
         constexpr int F2 = F_::NF - 1;
         const uint32_t n_sc = E / 32;
@@ -496,9 +496,14 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const Tens
     const TensorDev s = single ? *single : TensorDev{};
     const int use_single = single ? 1 : 0;
     const uint32_t lds = (n_rings >= 2 ? 2u : 1u) * kWavesPerGroup * kRing2Words * 4;
-    if (fmt == ZC_FMT_BF16) return launch_s64_x<ZC_FMT_BF16>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
-    if (fmt == ZC_FMT_FP8_E4M3) return launch_s64_x<ZC_FMT_FP8_E4M3>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
-    return launch_s64_x<ZC_FMT_FP4_E2M1_MX>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
+    switch (fmt) {
+    case ZC_FMT_BF16: return launch_s64_x<ZC_FMT_BF16>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_FP8_E4M3: return launch_s64_x<ZC_FMT_FP8_E4M3>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_FP4_E2M1_MX: return launch_s64_x<ZC_FMT_FP4_E2M1_MX>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_FP8_E4M3_BYTES: return launch_s64_x<ZC_FMT_FP8_E4M3_BYTES>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_FP4_E2M1_MX_BYTES: return launch_s64_x<ZC_FMT_FP4_E2M1_MX_BYTES>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
+    default: return 1;
+    }
 }
 
 // ---------------------------------------------------------------------------------------

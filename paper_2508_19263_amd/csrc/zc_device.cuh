@@ -30,10 +30,15 @@ __device__ __forceinline__ uint32_t prefix_count(uint64_t m)
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
 }
 
+// EB element bits, EPR elements per 16-byte run, GRP field values per coded symbol, G symbols per run,
+// SB symbol bits, NF fields, BASE the element format (whose split and join the format uses)
 template <int FMT> struct Fmt;
-template <> struct Fmt<ZC_FMT_BF16> { static constexpr int EB = 16, G = 8, SB = 8, NF = 2; };
-template <> struct Fmt<ZC_FMT_FP8_E4M3> { static constexpr int EB = 8, G = 16, SB = 4, NF = 2; };
-template <> struct Fmt<ZC_FMT_FP4_E2M1_MX> { static constexpr int EB = 4, G = 32, SB = 2, NF = 3; };
+template <> struct Fmt<ZC_FMT_BF16> { static constexpr int EB = 16, EPR = 8, GRP = 1, G = 8, SB = 8, NF = 2, BASE = ZC_FMT_BF16; };
+template <> struct Fmt<ZC_FMT_FP8_E4M3> { static constexpr int EB = 8, EPR = 16, GRP = 1, G = 16, SB = 4, NF = 2, BASE = ZC_FMT_FP8_E4M3; };
+template <> struct Fmt<ZC_FMT_FP4_E2M1_MX> { static constexpr int EB = 4, EPR = 32, GRP = 1, G = 32, SB = 2, NF = 3, BASE = ZC_FMT_FP4_E2M1_MX; };
+// byte-grouped symbols: the packed field words are those of the element format, read 8 bits at a time
+template <> struct Fmt<ZC_FMT_FP8_E4M3_BYTES> { static constexpr int EB = 8, EPR = 16, GRP = 2, G = 8, SB = 8, NF = 2, BASE = ZC_FMT_FP8_E4M3; };
+template <> struct Fmt<ZC_FMT_FP4_E2M1_MX_BYTES> { static constexpr int EB = 4, EPR = 32, GRP = 4, G = 8, SB = 8, NF = 3, BASE = ZC_FMT_FP4_E2M1_MX; };
 
 // ------------------------------------------------- field split / join of one 16-byte run
 // P0 = the run's exponent symbols, P1 = its sign+mantissa symbols, SB bits each, symbol j at
@@ -60,9 +65,10 @@ __device__ __forceinline__ uint32_t spread_pairs_to_nibbles(uint32_t x)  // inve
     return (x | (x << 2)) & 0x33333333u;
 }
 
-template <int FMT>
+template <int FMT_>
 __device__ __forceinline__ void split_run(const uint4 &v, uint64_t &P0, uint64_t &P1)
 {
+    constexpr int FMT = Fmt<FMT_>::BASE;
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
     P0 = 0; P1 = 0;
 #pragma unroll
@@ -84,9 +90,10 @@ __device__ __forceinline__ void split_run(const uint4 &v, uint64_t &P0, uint64_t
     }
 }
 
-template <int FMT>
+template <int FMT_>
 __device__ __forceinline__ uint4 join_run(uint64_t P0, uint64_t P1)
 {
+    constexpr int FMT = Fmt<FMT_>::BASE;
     uint32_t w[4];
 #pragma unroll
     for (int i = 0; i < 4; i++) {

@@ -12,11 +12,19 @@ constexpr uint32_t kHeaderBytes = 64;
 constexpr int kMaxFields = 3;
 
 // ---- format geometry -------------------------------------------------------
-inline int elem_bits(uint32_t fmt) { return fmt == ZC_FMT_BF16 ? 16 : fmt == ZC_FMT_FP8_E4M3 ? 8 : fmt == ZC_FMT_FP4_E2M1_MX ? 4 : 0; }
-inline int num_fields(uint32_t fmt) { return fmt == ZC_FMT_FP4_E2M1_MX ? 3 : 2; }
-inline int sym_bits(uint32_t fmt, int f) { return fmt == ZC_FMT_BF16 ? 8 : fmt == ZC_FMT_FP8_E4M3 ? 4 : (f == 2 ? 8 : 2); }
+// element format of a (possibly byte-grouped) format, and field values per coded symbol
+inline uint32_t base_format(uint32_t fmt) { return fmt == ZC_FMT_FP8_E4M3_BYTES ? ZC_FMT_FP8_E4M3 : fmt == ZC_FMT_FP4_E2M1_MX_BYTES ? ZC_FMT_FP4_E2M1_MX : fmt; }
+inline int group_of(uint32_t fmt) { return fmt == ZC_FMT_FP8_E4M3_BYTES ? 2 : fmt == ZC_FMT_FP4_E2M1_MX_BYTES ? 4 : 1; }
+inline bool is_fp4(uint32_t fmt) { return base_format(fmt) == ZC_FMT_FP4_E2M1_MX; }
+inline int elem_bits(uint32_t fmt) { fmt = base_format(fmt); return fmt == ZC_FMT_BF16 ? 16 : fmt == ZC_FMT_FP8_E4M3 ? 8 : fmt == ZC_FMT_FP4_E2M1_MX ? 4 : 0; }
+inline int num_fields(uint32_t fmt) { return is_fp4(fmt) ? 3 : 2; }
+inline int sym_bits(uint32_t fmt, int f)
+{
+    if (f == 2 || group_of(fmt) > 1) return 8;
+    return fmt == ZC_FMT_BF16 ? 8 : fmt == ZC_FMT_FP8_E4M3 ? 4 : 2;
+}
 // symbols per 16-byte run of the field's plain array
-inline int run_len(uint32_t fmt, int f) { return (fmt == ZC_FMT_FP4_E2M1_MX && f == 2) ? 16 : 128 / elem_bits(fmt); }
+inline int run_len(uint32_t fmt, int f) { return f == 2 ? 16 : 128 / elem_bits(fmt) / group_of(fmt); }
 inline uint64_t pad16(uint64_t x) { return (x + 15) / 16 * 16; }
 // refill period of a field's stream: symbols between two refill steps
 inline int refill_period(int G, int lmax)

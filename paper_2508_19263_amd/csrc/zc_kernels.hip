@@ -28,13 +28,17 @@ namespace zc {
 // the marginals.  BF16: two histograms, exponent and sign+mantissa symbol.
 
 // One copy of the 256 bins per LDS bank: lane l counts in copy l % 32, at word bin * 32 + l % 32, so the
-// 32 lanes of an LDS pass always hit 32 different banks whatever the data is.  BF16 keeps both fields in
-// one word (exponent count in the low half, sign+mantissa count in the high half): a copy is fed by 8
-// threads with at most 512 elements each per block, so neither half can overflow.
-template <bool BF16>
+// 32 lanes of an LDS pass always hit 32 different banks whatever the data is.
+// FMT == 0: histogram of the bytes themselves (FP8 and FP4 elements, whose field histograms are marginals
+// of the byte histogram, and the FP4 scale bytes).  Otherwise a format whose two fields have 8-bit symbols
+// (BF16, the byte-grouped formats): the run is split and both fields are counted in one word, field 0 in
+// the low half and field 1 in the high half: a copy is fed by 8 threads with at most 512 symbols each per
+// block, so neither half can overflow.
+template <int FMT>
 __global__ __launch_bounds__(256) void k_hist(const TensorDev *descs, const WorkItem *work, int elem_bits_, int scales_view, uint64_t *hist)
 {
-    static_assert(kHistBlockBytes / 2 / 32 < 65536, "a copy counts at most block elements / 32 per half-word");
+    constexpr bool TWO = FMT != 0;
+    static_assert(kHistBlockBytes / 16 * 8 / 32 < 65536, "a copy counts at most 8 symbols per 16-byte run of the block, over 32 copies");
     __shared__ uint32_t h[256 * 32];
     const WorkItem it = work[blockIdx.x];
     const TensorDev &d = descs[it.tensor];
@@ -47,16 +51,19 @@ __global__ __launch_bounds__(256) void k_hist(const TensorDev *descs, const Work
     const uint64_t end = start + kHistBlockBytes < nbytes ? start + kHistBlockBytes : nbytes;
     uint32_t *const mine = h + (threadIdx.x & 31);
     auto count = [&](const uint4 &v, uint32_t valid) {
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-        if (BF16) {
+        if (TWO) {
+            constexpr int F = TWO ? FMT : ZC_FMT_BF16;
+            uint64_t P0, P1;
+            split_run<F>(v, P0, P1);                      // bytes past `valid` are zero: a last partial group is zero filled
+            const uint32_t nsym = (valid * 8 / Fmt<F>::EB + Fmt<F>::GRP - 1) / Fmt<F>::GRP;
 #pragma unroll
             for (int i = 0; i < 8; i++)
-                if (2u * i < valid) {
-                    const uint32_t x = (w[i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
-                    atomicAdd(mine + ((x >> 7) & 0xFFu) * 32, 1u);
-                    atomicAdd(mine + (((x >> 8) & 0x80u) | (x & 0x7Fu)) * 32, 0x10000u);
+                if ((uint32_t)i < nsym) {
+                    atomicAdd(mine + ((uint32_t)(P0 >> (8 * i)) & 0xFFu) * 32, 1u);
+                    atomicAdd(mine + ((uint32_t)(P1 >> (8 * i)) & 0xFFu) * 32, 0x10000u);
                 }
         } else {
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int i = 0; i < 16; i++)
                 if ((uint32_t)i < valid) atomicAdd(mine + ((w[i >> 2] >> (8 * (i & 3))) & 0xFFu) * 32, 1u);
@@ -91,11 +98,11 @@ __global__ __launch_bounds__(256) void k_hist(const TensorDev *descs, const Work
 #pragma unroll 8
     for (uint32_t r = 0; r < 32; r++) {
         const uint32_t c = h[bin * 32 + ((r + bin) & 31)];
-        if (BF16) { lo += c & 0xFFFFu; hi += c >> 16; } else lo += c;
+        if (TWO) { lo += c & 0xFFFFu; hi += c >> 16; } else lo += c;
     }
-    const int slot = BF16 ? 0 : (scales_view ? 2 : 0);
+    const int slot = TWO ? 0 : (scales_view ? 2 : 0);
     if (lo) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + slot) * 256 + bin]), (unsigned long long)lo);
-    if (BF16 && hi) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + 1) * 256 + bin]), (unsigned long long)hi);
+    if (TWO && hi) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + 1) * 256 + bin]), (unsigned long long)hi);
 }
 
 int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, int scales_view, uint64_t *d_hist, void *stream)
@@ -103,9 +110,13 @@ int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, 
     if (n_work == 0) return 0;
     hipStream_t st = (hipStream_t)stream;
     if (fmt == ZC_FMT_BF16 && !scales_view)
-        hipLaunchKernelGGL(k_hist<true>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, 16, 0, d_hist);
+        hipLaunchKernelGGL(k_hist<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, 16, 0, d_hist);
+    else if (fmt == ZC_FMT_FP8_E4M3_BYTES && !scales_view)
+        hipLaunchKernelGGL(k_hist<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, 8, 0, d_hist);
+    else if (fmt == ZC_FMT_FP4_E2M1_MX_BYTES && !scales_view)
+        hipLaunchKernelGGL(k_hist<ZC_FMT_FP4_E2M1_MX_BYTES>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, 4, 0, d_hist);
     else
-        hipLaunchKernelGGL(k_hist<false>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, elem_bits(fmt), scales_view, d_hist);
+        hipLaunchKernelGGL(k_hist<0>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, elem_bits(fmt), scales_view, d_hist);
     return (int)hipGetLastError();
 }
 
@@ -253,7 +264,7 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
 
     // ---- element fields ----
     EncField F0 = {0, 0, 0, 0, 0, 0, 0}, F1 = F0;
-    const uint32_t chunk_runs = (uint32_t)((E + F_::G - 1) / F_::G);
+    const uint32_t chunk_runs = (uint32_t)((E + F_::EPR - 1) / F_::EPR);
     const uint32_t rows = (chunk_runs + S - 1) / S;
     const uint8_t *src = d.src + (uint64_t)chunk * d.chunk_bytes;
     const uint8_t *base = d.base ? d.base + (uint64_t)chunk * d.chunk_bytes : nullptr;
@@ -261,8 +272,9 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
     const uint32_t m0 = d.mode[0], m1 = d.mode[1];
     for (uint32_t i = 0; i < rows; i++) {
         const uint32_t run = i * S + L.s;
-        const uint32_t done = run * F_::G;
-        const uint32_t nsym = n > done ? (n - done < (uint32_t)F_::G ? n - done : (uint32_t)F_::G) : 0;
+        const uint32_t done = run * F_::EPR;                                                       // elements before this run
+        const uint32_t nel = n > done ? (n - done < (uint32_t)F_::EPR ? n - done : (uint32_t)F_::EPR) : 0;
+        const uint32_t nsym = (nel + F_::GRP - 1) / F_::GRP;                                       // a last partial group is filled with zeros
         uint64_t P0 = 0, P1 = 0;
         if (nsym) {
             const uint32_t vb = nbytes - run * 16;
@@ -277,7 +289,7 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
             else enc_run<WRITE, F_::SB, F_::G, false>(F0, d.period[0], P0, 0, nsym, enc[0], stream[0], L);
         } else if (m0 == ZC_MODE_RAW && WRITE && nsym) {
             reinterpret_cast<uint64_t *>(stream[0])[run] = P0;
-            if ((run & 1) == 0 && done + F_::G >= n) reinterpret_cast<uint64_t *>(stream[0])[run + 1] = 0;
+            if ((run & 1) == 0 && done + F_::EPR >= n) reinterpret_cast<uint64_t *>(stream[0])[run + 1] = 0;
         }
         if (m1 == ZC_MODE_HUFF && d.kind[1] == 1 && full) enc_flat_run<WRITE, F_::SB>(F1, P1, stream[1], L, S);
         else if (m1 == ZC_MODE_HUFF) {
@@ -285,20 +297,21 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
             else enc_run<WRITE, F_::SB, F_::G, false>(F1, d.period[1], P1, 0, nsym, enc[1], stream[1], L);
         } else if (m1 == ZC_MODE_RAW && WRITE && nsym) {
             reinterpret_cast<uint64_t *>(stream[1])[run] = P1;
-            if ((run & 1) == 0 && done + F_::G >= n) reinterpret_cast<uint64_t *>(stream[1])[run + 1] = 0;
+            if ((run & 1) == 0 && done + F_::EPR >= n) reinterpret_cast<uint64_t *>(stream[1])[run + 1] = 0;
         }
     }
     {
         uint32_t u0 = 0, u1 = 0;
+        const uint32_t nsyms = (n + F_::GRP - 1) / F_::GRP;
         if (m0 == ZC_MODE_HUFF) u0 = enc_finish<WRITE>(F0, stream[0], L);
-        else if (m0 == ZC_MODE_RAW) u0 = (uint32_t)((((uint64_t)n * F_::SB + 7) / 8 + 15) / 16);
+        else if (m0 == ZC_MODE_RAW) u0 = (uint32_t)((((uint64_t)nsyms * F_::SB + 7) / 8 + 15) / 16);
         if (m1 == ZC_MODE_HUFF) u1 = enc_finish<WRITE>(F1, stream[1], L);
-        else if (m1 == ZC_MODE_RAW) u1 = (uint32_t)((((uint64_t)n * F_::SB + 7) / 8 + 15) / 16);
+        else if (m1 == ZC_MODE_RAW) u1 = (uint32_t)((((uint64_t)nsyms * F_::SB + 7) / 8 + 15) / 16);
         if (!WRITE && valid && L.s == 0) { my_units[chunk] = u0; my_units[d.n_chunks + chunk] = u1; }
     }
 
     // ---- FP4 block scales: one byte per 32 elements, runs of 16 bytes ----
-    if (FMT == ZC_FMT_FP4_E2M1_MX) {
+    if (F_::NF == 3) {
         EncField F2 = {0, 0, 0, 0, 0, 0, 0};
         const uint32_t ns = n / 32;
         const uint32_t srows = (uint32_t)((E / 32 + 15) / 16 + S - 1) / S;
@@ -334,9 +347,14 @@ template <bool WRITE>
 static int launch_encode_t(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
 {
     if (n_work == 0) return 0;
-    if (fmt == ZC_FMT_BF16) hipLaunchKernelGGL((k_encode<ZC_FMT_BF16, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units);
-    else if (fmt == ZC_FMT_FP8_E4M3) hipLaunchKernelGGL((k_encode<ZC_FMT_FP8_E4M3, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units);
-    else hipLaunchKernelGGL((k_encode<ZC_FMT_FP4_E2M1_MX, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units);
+    switch (fmt) {
+    case ZC_FMT_BF16: hipLaunchKernelGGL((k_encode<ZC_FMT_BF16, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
+    case ZC_FMT_FP8_E4M3: hipLaunchKernelGGL((k_encode<ZC_FMT_FP8_E4M3, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
+    case ZC_FMT_FP4_E2M1_MX: hipLaunchKernelGGL((k_encode<ZC_FMT_FP4_E2M1_MX, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
+    case ZC_FMT_FP8_E4M3_BYTES: hipLaunchKernelGGL((k_encode<ZC_FMT_FP8_E4M3_BYTES, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
+    case ZC_FMT_FP4_E2M1_MX_BYTES: hipLaunchKernelGGL((k_encode<ZC_FMT_FP4_E2M1_MX_BYTES, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
+    default: return 1;
+    }
     return (int)hipGetLastError();
 }
 
@@ -535,12 +553,13 @@ __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const Wo
     DecField D0 = open_stream(d, 0, chunk, valid), D1 = open_stream(d, 1, chunk, valid);
     const uint32_t m0 = d.mode[0], m1 = d.mode[1];
     const uint64_t K0 = splat(d.konst[0], F_::SB), K1 = splat(d.konst[1], F_::SB);
-    const uint32_t chunk_runs = (uint32_t)((E + F_::G - 1) / F_::G);
+    const uint32_t chunk_runs = (uint32_t)((E + F_::EPR - 1) / F_::EPR);
     const uint32_t rows = (chunk_runs + S - 1) / S;
     for (uint32_t i = 0; i < rows; i++) {
         const uint32_t run = i * S + L.s;
-        const uint32_t done = run * F_::G;
-        const uint32_t nsym = n > done ? (n - done < (uint32_t)F_::G ? n - done : (uint32_t)F_::G) : 0;
+        const uint32_t done = run * F_::EPR;                                                       // elements before this run
+        const uint32_t nel = n > done ? (n - done < (uint32_t)F_::EPR ? n - done : (uint32_t)F_::EPR) : 0;
+        const uint32_t nsym = (nel + F_::GRP - 1) / F_::GRP;                                       // a last partial group is filled with zeros
         const bool full = __all(nsym == (uint32_t)F_::G);
         uint64_t P0 = 0, P1 = 0, unused = 0;
         if (m0 == ZC_MODE_HUFF) {
@@ -563,7 +582,7 @@ __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const Wo
         }
     }
 
-    if (FMT == ZC_FMT_FP4_E2M1_MX) {
+    if (F_::NF == 3) {
         DecField D2 = open_stream(d, F_::NF - 1, chunk, valid);
         const uint32_t m2 = d.mode[F_::NF - 1];
         const uint32_t ns = n / 32;
@@ -594,9 +613,14 @@ int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work
     hipStream_t st = (hipStream_t)stream;
     TensorDev s = single ? *single : TensorDev{};
     const int use_single = single ? 1 : 0;
-    if (fmt == ZC_FMT_BF16) hipLaunchKernelGGL(k_decode<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot);
-    else if (fmt == ZC_FMT_FP8_E4M3) hipLaunchKernelGGL(k_decode<ZC_FMT_FP8_E4M3>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot);
-    else hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_MX>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot);
+    switch (fmt) {
+    case ZC_FMT_BF16: hipLaunchKernelGGL(k_decode<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
+    case ZC_FMT_FP8_E4M3: hipLaunchKernelGGL(k_decode<ZC_FMT_FP8_E4M3>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
+    case ZC_FMT_FP4_E2M1_MX: hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_MX>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
+    case ZC_FMT_FP8_E4M3_BYTES: hipLaunchKernelGGL(k_decode<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
+    case ZC_FMT_FP4_E2M1_MX_BYTES: hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_MX_BYTES>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
+    default: return 1;
+    }
     return (int)hipGetLastError();
 }
 

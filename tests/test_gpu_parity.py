@@ -14,7 +14,7 @@ DEV = "cuda:0"
 def make_input(fmt, n, seed):
     if fmt == zc.FMT_BF16:
         return wl.bf16_weight(n, seed=seed).view(torch.uint8), None
-    if fmt == zc.FMT_FP8_E4M3:
+    if fmt in (zc.FMT_FP8_E4M3, zc.FMT_FP8_E4M3_BYTES):
         return wl.fp8_weight(n, seed=seed) if n else torch.zeros(0, dtype=torch.uint8), None
     if n == 0:
         return torch.zeros(0, dtype=torch.uint8), torch.zeros(0, dtype=torch.uint8)
@@ -477,3 +477,48 @@ def test_static_dictionary():
     code.code_len[0][2] = 0
     with pytest.raises(zc.ZcError):
         zc.compress_with_code(dev(b), n_b, p, code, scales=dev(sb_))
+
+
+def test_byte_grouped_symbols():
+    # Sec. 3.2 (Fig. 7) / 3.4: field values coded in byte-sized groups; same bar as the plain formats
+    F8, F4 = zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP4_E2M1_MX_BYTES
+    for S in (64, 8, 1):
+        cb = 4096
+        for n in (1, 2, 16 * S - 1, 16 * S + 1, cb - 1, cb, cb + 1, 3 * cb + 17 * 16 + 5, 40 * cb + 3):
+            for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+                check_case(F8, n, cb, S, policy, tag="fp8-bytes")
+    for S in (64, 16, 2):
+        for n in (32, 32 * S * 3, 8192 - 32, 8192, 8192 + 32, 5 * 8192 + 96):
+            check_case(F4, n, 4096, S, tag="fp4-bytes")
+    # full chunks through the 64-lane kernel: both fields table decoded, long codes, raw, delta, limits
+    check_case(F8, 6 * 65536 + 1234, 65536, 64, tag="fp8-bytes-full")
+    check_case(F8, 6 * 65536 + 1234, 65536, 64, zc.POLICY_AUTO, tag="fp8-bytes-full-auto")
+    check_case(F8, 6 * 65536, 65536, 64, L=(11, 9, 0), tag="fp8-bytes-limits")
+    k, v = wl.fp8_kv_pair(batch=1, heads=2, tokens=2048, seed=9)
+    check_case(F8, k.numel(), 2048, 8, data=(k.reshape(-1), None), tag="fp8-bytes-kv-pages")
+    a, b = wl.fp8_weight(5 * 32768 + 77, seed=1), wl.fp8_weight(5 * 32768 + 77, seed=2)
+    check_case(F8, a.numel(), 32768, 64, data=(a, None), base=b, tag="fp8-bytes-delta")
+    m, sc = wl.mxfp4_weight(256, 3584, seed=3)
+    check_case(F4, 256 * 3584, 262144, 64, data=(m.reshape(-1), sc.reshape(-1)), tag="fp4-bytes-full")
+    check_case(F4, 256 * 3584, 16384, 64, zc.POLICY_AUTO, data=(m.reshape(-1), sc.reshape(-1)), tag="fp4-bytes-auto")
+    # batch with chunk id lists and a static dictionary
+    srcs = [wl.fp8_weight(n, seed=60 + i) for i, n in enumerate((4 * 16384, 7 * 16384 + 5, 16384))]
+    p, po = zc.params(F8, 16384), o.params(F8, 16384)
+    bt = zc.Batch([dev(s) for s in srcs], [s.numel() for s in srcs], p)
+    sizes = bt.compress()
+    for i, s in enumerate(srcs):
+        assert np.array_equal(bt.container(i).cpu().numpy(), o.compress(s.numpy(), s.numel(), po))
+    outs = bt.decompress()
+    torch.cuda.synchronize()
+    for out, s in zip(outs, srcs):
+        assert torch.equal(out.cpu()[:s.numel()], s)
+    code = zc.train_code(dev(srcs[1]), srcs[1].numel(), p)
+    ln, md = o.train_code(srcs[1].numpy(), srcs[1].numel(), po)
+    comp, info = zc.compress_with_code(dev(srcs[0]), srcs[0].numel(), p, code)
+    assert np.array_equal(comp.cpu().numpy(), o.compress_with_code(srcs[0].numpy(), srcs[0].numel(), po, ln, md))
+    # stats agree with the oracle's
+    st, so = zc.stats(dev(srcs[1]), srcs[1].numel(), p), o.stats(srcs[1].numpy(), srcs[1].numel(), po)
+    for f in range(2):
+        assert list(st.field[f].hist) == list(so.field[f].hist) and st.field[f].payload_bits == so.field[f].payload_bits
+        assert abs(st.field[f].entropy_bits - so.field[f].entropy_bits) < 1e-12
+    assert st.container_bytes == so.container_bytes

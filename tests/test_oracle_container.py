@@ -238,3 +238,51 @@ def test_static_dictionary_training_and_use():
     cb = o.compress_with_code(v1.numpy(), 30000, pb, lnb, mdb, xor_base=v0.numpy())
     rc, out, _ = o.decompress(cb, 60000, xor_base=v0.numpy().view(np.uint8))
     assert rc == o.OK and np.array_equal(out, v1.numpy().view(np.uint8))
+
+
+def test_byte_grouped_formats():
+    # Sec. 3.2 (Fig. 7), 3.4: symbols are bytes of the packed field arrays
+    x, _ = make_input(o.FP8_E4M3, 70001, 77)
+    e, sm = o.split(o.FP8_E4M3, x, len(x))
+    # grouping == bytes of the nibble-packed array (numpy), zero filled at the odd end
+    ge = o.group_values(o.FP8_E4M3_BYTES, 0, e, len(e))
+    pad = np.concatenate([e, np.zeros(1, np.uint8)])
+    assert np.array_equal(ge, pad[0::2] | (pad[1::2] << 4)) and len(ge) == 35001
+    assert np.array_equal(o.ungroup_symbols(o.FP8_E4M3_BYTES, 0, ge, len(e)), e)
+    m, sc = make_input(o.FP4_E2M1_MX, 32 * 2000, 78)
+    e4, sm4 = o.split(o.FP4_E2M1_MX, m, 32 * 2000)
+    g4 = o.group_values(o.FP4_E2M1_MX_BYTES, 1, sm4, len(sm4))
+    assert np.array_equal(g4, sm4[0::4] | (sm4[1::4] << 2) | (sm4[2::4] << 4) | (sm4[3::4] << 6))
+    for fmt, plain, src, n, scales in ((o.FP8_E4M3_BYTES, o.FP8_E4M3, x, len(x), None), (o.FP4_E2M1_MX_BYTES, o.FP4_E2M1_MX, m, 32 * 2000, sc)):
+        for S in (64, 4):
+            p, pp = o.params(fmt, 4096, streams=S), o.params(plain, 4096, streams=S)
+            comp = o.compress(src, n, p, scales=scales)
+            rc, out, sco = o.decompress(comp, len(src.reshape(-1)), n_scales=0 if scales is None else n // 32)
+            assert rc == o.OK and np.array_equal(out, src.reshape(-1))
+            assert comp[6] == fmt and comp[33] == 8 and comp[37] == 8
+            st, sp = o.stats(src, n, p, scales=scales), o.stats(src, n, pp, scales=scales)
+            for f in range(2):
+                # the product of the per-value code is one of the codes a group may get (and fits the limit
+                # 16 = 2 x 8 = 4 x 4... of the per-value limits), so the optimal group code cannot cost more,
+                # apart from the zero fill of one last group
+                assert st.field[f].payload_bits <= sp.field[f].payload_bits + 16
+                assert st.field[f].n_symbols == (n + o.group_of(fmt) - 1) // o.group_of(fmt)
+                # the group histogram is the histogram of the packed bytes
+                vals = o.split(plain, src, n)[f]
+                assert list(st.field[f].hist) == np.bincount(o.group_values(fmt, f, vals, n), minlength=256).tolist()
+            # every chunk alone
+            E = 4096 * 8 // o.elem_bits(fmt)
+            c = (n - 1) // E
+            rc, oc, _ = o.decompress_chunk(comp, c, 4096, n_scales=0 if scales is None else E // 32)
+            nb = (n - c * E) * o.elem_bits(fmt) // 8
+            assert rc == o.OK and np.array_equal(oc[:nb], src.reshape(-1)[c * 4096:c * 4096 + nb])
+        # raw storage packs the same bits in both readings of the field: identical payloads
+        u = np.random.default_rng(5).integers(0, 256, len(src.reshape(-1)), dtype=np.uint8)
+        ca = o.compress(u, n, o.params(fmt, 4096, policy=o.POLICY_AUTO), scales=scales)
+        cp = o.compress(u, n, o.params(plain, 4096, policy=o.POLICY_AUTO), scales=scales)
+        assert ca[32] == o.MODE_RAW and cp[32] == o.MODE_RAW and ca[36] == o.MODE_RAW and cp[36] == o.MODE_RAW
+        pa, pb = int(np.frombuffer(ca[56:64].tobytes(), "<u8")[0]), int(np.frombuffer(cp[56:64].tobytes(), "<u8")[0])
+        ia, ib = int(np.frombuffer(ca[24:28].tobytes(), "<u4")[0]), int(np.frombuffer(cp[24:28].tobytes(), "<u4")[0])
+        assert ia == ib
+        if scales is None:
+            assert np.array_equal(ca[pa:], cp[pb:])
