@@ -45,8 +45,9 @@ def other_workloads(torch, wl, zc, dev):
     """Configs 1, 3, 4, 5 at full size: ratios, compress and decompress GB/s (median of 5)."""
     out = {}
 
-    def run(name, fmt, srcs, counts, chunk, streams, bases=None, scales=None, limit=(0, 0, 0), ids=None, dictionary=False):
-        p = zc.params(fmt, chunk, limit, streams)
+    def run(name, fmt, srcs, counts, chunk, streams, bases=None, scales=None, limit=(0, 0, 0), ids=None, dictionary=False,
+            policy=zc.POLICY_HUFF_ALL):
+        p = zc.params(fmt, chunk, limit, streams, policy)
         b = zc.Batch(srcs, counts, p, xor_bases=bases, scales=scales)
         sizes = b.compress()
         b.plan_decompress()
@@ -97,10 +98,17 @@ def other_workloads(torch, wl, zc, dev):
         del b
         torch.cuda.empty_cache()
 
+    # config 2 again with byte-grouped symbols (two exponents per symbol; the flat sign+mantissa field raw)
+    names8 = [t for _, t in wl.fp8_weight_set(8, device=dev)]
+    run("c2_fp8_8_layers_byte_symbols", zc.FMT_FP8_E4M3_BYTES, names8, [t.numel() for t in names8], 262144, 64, policy=zc.POLICY_AUTO)
+    run("c2_fp8_8_layers_plain_symbols", zc.FMT_FP8_E4M3, names8, [t.numel() for t in names8], 262144, 64, policy=zc.POLICY_AUTO)
+    del names8
     x = wl.bf16_weight(1 << 20, device=dev, seed=0)
     run("c1_bf16_1M", zc.FMT_BF16, [x], [1 << 20], 65536, 64, limit=(16, 16, 0))
     mats = [wl.mxfp4_weight(8192, 28672, device=dev, seed=300 + i) for i in range(3)]
     run("c3_mxfp4_70b_mlp", zc.FMT_FP4_E2M1_MX, [m[0] for m in mats], [8192 * 28672] * 3, 262144, 64, scales=[m[1] for m in mats])
+    run("c3_mxfp4_70b_mlp_byte_symbols", zc.FMT_FP4_E2M1_MX_BYTES, [m[0] for m in mats], [8192 * 28672] * 3, 262144, 64,
+        scales=[m[1] for m in mats], policy=zc.POLICY_AUTO)
     del mats
     pairs = [wl.bf16_checkpoint_pair(4096 * 16384, device=dev, seed=400 + i) for i in range(16)]
     w0, w1 = [q[0] for q in pairs], [q[1] for q in pairs]

@@ -1,6 +1,6 @@
 // Host-side Huffman code construction for alphabets of at most 256 symbols:
 // optimal code lengths under a length limit (package-merge, Larmore & Hirschberg 1990),
-// then canonical code values.  The paper asks only for "standard Huffman" per stream
+// then canonical code values.  The paper asks only for plain Huffman coding per stream
 // (Sec. 3.1, 4.1); the limit keeps decode tables small and the tie rules below make the
 // result unique so that an independent implementation arrives at the same bits:
 //   * leaves are ordered by (frequency, symbol value), ascending;
