@@ -69,7 +69,7 @@ def other_workloads(torch, wl, zc, dev):
             outs = b.out
             t_p = _time_ms(torch, b.run_decompress)
             nb = sum(o.numel() for o in outs)
-            okp = all(torch.equal(outs[i].view(-1, chunk), srcs[i].view(-1, chunk)[ids[i].long()]) for i in range(b.n))
+            okp = all(torch.equal(outs[i].view(-1, chunk), srcs[i].view(torch.uint8).view(-1, chunk)[ids[i].long()]) for i in range(b.n))
             comp_read = sum(sizes) * (nb / raw)
             r.update({"page_decode_ms": t_p, "page_decode_GBps": nb / t_p / 1e6, "pages": nb // chunk, "page_decode_bit_exact": bool(okp),
                       "page_decode_traffic_frac_of_hbm_peak": (nb + comp_read) / t_p / 1e6 / HBM_PEAK_GBPS})
@@ -110,6 +110,9 @@ def other_workloads(torch, wl, zc, dev):
     run("c3_mxfp4_70b_mlp_byte_symbols", zc.FMT_FP4_E2M1_MX_BYTES, [m[0] for m in mats], [8192 * 28672] * 3, 262144, 64,
         scales=[m[1] for m in mats], policy=zc.POLICY_AUTO)
     del mats
+    mats = [wl.nvfp4_weight(8192, 28672, device=dev, seed=310 + i) for i in range(3)]
+    run("nvfp4_70b_mlp", zc.FMT_FP4_E2M1_NV, [m[0] for m in mats], [8192 * 28672] * 3, 262144, 64, scales=[m[1] for m in mats])
+    del mats
     pairs = [wl.bf16_checkpoint_pair(4096 * 16384, device=dev, seed=400 + i) for i in range(16)]
     w0, w1 = [q[0] for q in pairs], [q[1] for q in pairs]
     run("c4_bf16_checkpoint_w1", zc.FMT_BF16, w1, [4096 * 16384] * 16, 262144, 64, limit=(16, 16, 0))
@@ -122,6 +125,15 @@ def other_workloads(torch, wl, zc, dev):
     n_pages = kv[0].numel() // 2048
     ids = [wl.page_sample(n_pages, 0.25, device=dev, seed=600 + i) for i in range(len(kv))]
     run("c5_fp8_kv_pages", zc.FMT_FP8_E4M3, kv, [t.numel() for t in kv], 2048, 8, ids=ids, dictionary=True)
+    del kv
+    # the same cache shape in BF16: 16-token pages of 4 KiB, 16 layers
+    kv = []
+    for layer in range(16):
+        k, v = wl.bf16_kv_pair(device=dev, seed=700 + layer)
+        kv += [k.reshape(-1), v.reshape(-1)]
+    n_pages = kv[0].numel() * 2 // 4096
+    ids = [wl.page_sample(n_pages, 0.25, device=dev, seed=800 + i) for i in range(len(kv))]
+    run("bf16_kv_pages", zc.FMT_BF16, kv, [t.numel() for t in kv], 4096, 8, ids=ids)
     return out
 
 

@@ -55,7 +55,10 @@ typedef enum {
      * consecutive field values with the first in the low bits, so every field has a 256-symbol alphabet.
      * A last group that runs past the tensor is filled with zero values. */
     ZC_FMT_FP8_E4M3_BYTES = 4,
-    ZC_FMT_FP4_E2M1_MX_BYTES = 5
+    ZC_FMT_FP4_E2M1_MX_BYTES = 5,
+    /* NVFP4 (Sec. 3.4): the E2M1 elements of format 3 with one FP8 (E4M3) scale byte per 16 elements
+     * (d_scales holds n_elems / 16 bytes); fields as format 3, the scale bytes coded as 8-bit symbols. */
+    ZC_FMT_FP4_E2M1_NV = 6
 } zc_format;
 
 typedef enum {
@@ -115,7 +118,7 @@ typedef struct {
 typedef struct {
     const void *d_src;          /* compress: elements (device) */
     const void *d_xor_base;     /* device, same shape as the tensor, or NULL (Sec. 3.1 delta) */
-    const void *d_scales;       /* compress, FP4 only: n_elems/32 scale bytes (device) */
+    const void *d_scales;       /* compress, FP4 only: one scale byte per 32 (MX) or 16 (NV) elements (device) */
     uint64_t n_elems;
     void *d_comp;               /* container (device): written by compress, read by decompress */
     uint64_t comp_capacity;     /* compress: bytes available at d_comp */

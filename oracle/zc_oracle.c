@@ -47,7 +47,9 @@
  * field values in byte-sized groups (Sec. 3.2, Fig. 7: FP8 exponents and sign+mantissa values
  * paired into bytes; Sec. 3.4: four 2-bit FP4 values per byte): one Huffman symbol = one byte of
  * the packed field array = 2 (FP8) or 4 (FP4) consecutive field values, first value in the low bits. */
-enum { ZCO_BF16 = 1, ZCO_FP8_E4M3 = 2, ZCO_FP4_E2M1_MX = 3, ZCO_FP8_E4M3_BYTES = 4, ZCO_FP4_E2M1_MX_BYTES = 5 };
+/* Format 6 is NVFP4 (Sec. 3.4): the E2M1 elements of format 3 with one FP8 (E4M3) scale byte per 16
+ * elements instead of one E8M0 byte per 32; the scale bytes are coded as 8-bit symbols like the E8M0 ones. */
+enum { ZCO_BF16 = 1, ZCO_FP8_E4M3 = 2, ZCO_FP4_E2M1_MX = 3, ZCO_FP8_E4M3_BYTES = 4, ZCO_FP4_E2M1_MX_BYTES = 5, ZCO_FP4_E2M1_NV = 6 };
 enum { ZCO_MODE_EMPTY = 0, ZCO_MODE_HUFF = 1, ZCO_MODE_RAW = 2, ZCO_MODE_CONST = 3 };
 enum { ZCO_POLICY_HUFF_ALL = 0, ZCO_POLICY_AUTO = 1 };
 enum { ZCO_OK = 0, ZCO_ERR_ARG = 1, ZCO_ERR_UNSUPPORTED = 2, ZCO_ERR_SMALL = 3, ZCO_ERR_CORRUPT = 4 };
@@ -63,7 +65,14 @@ typedef struct {
 /* element format of a (possibly byte-grouped) format, and field values per coded symbol */
 static int base_format(int format)
 {
+    if (format == ZCO_FP4_E2M1_NV) return ZCO_FP4_E2M1_MX;        /* same elements, other scales */
     return format == ZCO_FP8_E4M3_BYTES ? ZCO_FP8_E4M3 : format == ZCO_FP4_E2M1_MX_BYTES ? ZCO_FP4_E2M1_MX : format;
+}
+
+/* elements that share one scale byte (0: the format has no scales) */
+static int scale_block(int format)
+{
+    return format == ZCO_FP4_E2M1_NV ? 16 : (format == ZCO_FP4_E2M1_MX || format == ZCO_FP4_E2M1_MX_BYTES) ? 32 : 0;
 }
 
 static int group_of(int format)
@@ -109,7 +118,7 @@ static int run_len(int format, int f)
 
 static uint64_t num_symbols(int format, int f, uint64_t n_elems)
 {
-    if (f == 2) return n_elems / 32;                           /* one E8M0 byte per 32 elements */
+    if (f == 2) return n_elems / (uint64_t)scale_block(format);   /* one scale byte per block of elements */
     return (n_elems + (uint64_t)group_of(format) - 1) / (uint64_t)group_of(format);
 }
 
@@ -516,7 +525,7 @@ static int check_params(const zco_params *p, uint64_t n_elems, int *S)
     *S = p->streams_per_chunk ? (int)p->streams_per_chunk : 64;
     if (*S != 1 && *S != 2 && *S != 4 && *S != 8 && *S != 16 && *S != 32 && *S != 64) return ZCO_ERR_ARG;
     if (p->chunk_bytes == 0 || p->chunk_bytes % 16) return ZCO_ERR_ARG;
-    if (base_format((int)p->format) == ZCO_FP4_E2M1_MX && (p->chunk_bytes % 256 || n_elems % 32)) return ZCO_ERR_ARG;
+    if (scale_block((int)p->format) && (p->chunk_bytes % 256 || n_elems % (uint64_t)scale_block((int)p->format))) return ZCO_ERR_ARG;
     if (p->policy > 1) return ZCO_ERR_ARG;
     return ZCO_OK;
 }
@@ -537,7 +546,7 @@ static uint64_t chunk_symbols(const zco_params *p, int f, uint64_t n_elems, uint
     uint64_t E = elems_per_chunk(p);
     uint64_t lo = c * E, hi = lo + E;
     if (hi > n_elems) hi = n_elems;
-    if (f == 2) { lo /= 32; hi /= 32; }
+    if (f == 2) { lo /= (uint64_t)scale_block((int)p->format); hi /= (uint64_t)scale_block((int)p->format); }
     else { uint64_t g = (uint64_t)group_of((int)p->format); lo /= g; hi = (hi + g - 1) / g; }   /* E is a multiple of g */
     *first = lo;
     return hi - lo;
@@ -571,7 +580,7 @@ static void tensor_symbols(int fmt, const uint8_t *src, const uint8_t *xor_base,
         zco_group_values(fmt, 1, m, n_elems, sym[1]);
         free(e); free(m);
     }
-    if (nf == 3) { sym[2] = malloc((size_t)(n_elems / 32) + 1); if (n_elems) memcpy(sym[2], scales, (size_t)(n_elems / 32)); }
+    if (nf == 3) { size_t ns = (size_t)num_symbols(fmt, 2, n_elems); sym[2] = malloc(ns + 1); if (ns) memcpy(sym[2], scales, ns); }
 }
 
 /* Compress.  src: the tensor (FP4: two elements per byte, element 2i in the low
@@ -832,7 +841,7 @@ int zco_decompress(const uint8_t *comp, uint64_t comp_bytes, const uint8_t *xor_
     for (uint64_t c = 0; c < v.nc && !rc; c++) {
         uint64_t eoff = c * (uint64_t)v.chunk_bytes;
         rc = zco_decompress_chunk(comp, comp_bytes, c, xor_base ? xor_base + eoff : NULL, dst + eoff,
-                                  dst_cap - eoff, scales_out ? scales_out + c * ((uint64_t)v.chunk_bytes / 16) : NULL);
+                                  dst_cap - eoff, scales_out ? scales_out + c * ((uint64_t)v.chunk_bytes * 2 / (uint64_t)scale_block(v.fmt)) : NULL);
     }
     return rc;
 }
@@ -869,7 +878,7 @@ int zco_stats(const uint8_t *src, uint64_t n_elems, const zco_params *p, const u
     int fmt = (int)p->format, nf = zco_num_fields(fmt);
     memset(out, 0, sizeof(*out));
     out->n_fields = (uint32_t)nf;
-    out->raw_bytes = (n_elems * (uint64_t)elem_bits(fmt) + 7) / 8 + (nf == 3 ? n_elems / 32 : 0);
+    out->raw_bytes = (n_elems * (uint64_t)elem_bits(fmt) + 7) / 8 + (nf == 3 ? num_symbols(fmt, 2, n_elems) : 0);
     uint64_t cap = zco_compress_bound(n_elems, p), total = 0;
     uint8_t *tmp = malloc((size_t)cap);
     rc = zco_compress(src, n_elems, p, xor_base, scales, tmp, cap, &total);

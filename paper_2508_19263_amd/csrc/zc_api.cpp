@@ -47,7 +47,7 @@ zc_status check_params(const zc_params *p, Geometry *g)
 
 zc_status check_count(const Geometry &g, uint64_t n_elems, uint64_t *n_chunks)
 {
-    if (is_fp4(g.fmt) && n_elems % 32) return ZC_ERR_INVALID_ARG;
+    if (is_fp4(g.fmt) && n_elems % scale_block(g.fmt)) return ZC_ERR_INVALID_ARG;
     const uint64_t nc = (n_elems + g.elems_per_chunk - 1) / g.elems_per_chunk;
     if (nc >= 0xFFFFFFFFull) return ZC_ERR_INVALID_ARG;
     *n_chunks = nc;
@@ -56,7 +56,7 @@ zc_status check_count(const Geometry &g, uint64_t n_elems, uint64_t *n_chunks)
 
 uint64_t field_symbols(uint32_t fmt, int f, uint64_t n_elems)
 {
-    if (f == 2) return n_elems / 32;
+    if (f == 2) return n_elems / scale_block(fmt);
     const uint64_t grp = (uint64_t)group_of(fmt);
     return (n_elems + grp - 1) / grp;                       // a last partial group counts as one symbol
 }
@@ -98,7 +98,7 @@ zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T,
         if (st) return st;
         const uint64_t bytes = (n_elems[t] * (uint64_t)elem_bits(g.fmt) + 7) / 8;
         hw += (bytes + kHistBlockBytes - 1) / kHistBlockBytes;
-        if (g.nf == 3) sw += (n_elems[t] / 32 + kHistBlockBytes - 1) / kHistBlockBytes;
+        if (g.nf == 3) sw += (n_elems[t] / scale_block(g.fmt) + kHistBlockBytes - 1) / kHistBlockBytes;
         cw += (nc + cpi - 1) / cpi;
         units += nc * g.nf;
     }
@@ -334,7 +334,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         units_off += nc * g.nf;
         const uint64_t bytes = (x.n_elems * (uint64_t)elem_bits(g.fmt) + 7) / 8;
         for (uint64_t b = 0; b * kHistBlockBytes < bytes; b++) hist_work.push_back({t, (uint32_t)b});
-        if (g.nf == 3) for (uint64_t b = 0; b * kHistBlockBytes < x.n_elems / 32; b++) scale_work.push_back({t, (uint32_t)b});
+        if (g.nf == 3) for (uint64_t b = 0; b * kHistBlockBytes < x.n_elems / scale_block(g.fmt); b++) scale_work.push_back({t, (uint32_t)b});
     }
     TensorDev *d_descs = (TensorDev *)(ws + w.descs);
     uint64_t *d_hist = (uint64_t *)(ws + w.hist);
@@ -347,7 +347,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     std::vector<uint64_t> hist((size_t)T * 768);
     if (!dict) {
         LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
-        if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), 1, d_hist, stream));
+        if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), (int)scale_block(g.fmt), d_hist, stream));
         HIP_TRY(hipMemcpyAsync(hist.data(), d_hist, hist.size() * 8, hipMemcpyDeviceToHost, hs));
         HIP_TRY(hipStreamSynchronize(hs));
     }
@@ -706,7 +706,7 @@ int zc_code_stale(const zc_info *code, const zc_info *written, double slack)
     if (!code || !written || code->format != written->format || code->n_elems == 0 || written->n_elems == 0) return -1;
     if (!elem_bits(code->format) || !(slack >= 0.0)) return -1;
     auto raw = [](const zc_info *i) {
-        return (double)((i->n_elems * (uint64_t)elem_bits(i->format) + 7) / 8 + (is_fp4(i->format) ? i->n_elems / 32 : 0));
+        return (double)((i->n_elems * (uint64_t)elem_bits(i->format) + 7) / 8 + (is_fp4(i->format) ? i->n_elems / scale_block(i->format) : 0));
     };
     return (double)written->total_bytes / raw(written) > (double)code->total_bytes / raw(code) + slack ? 1 : 0;
 }
@@ -748,7 +748,7 @@ zc_status zc_stats(const void *d_src, uint64_t n_elems, const zc_params *params,
     std::memset(out, 0, sizeof(*out));
     const uint32_t fmt = params->format;
     out->n_fields = (uint32_t)num_fields(fmt);
-    out->raw_bytes = (n_elems * (uint64_t)elem_bits(fmt) + 7) / 8 + (out->n_fields == 3 ? n_elems / 32 : 0);
+    out->raw_bytes = (n_elems * (uint64_t)elem_bits(fmt) + 7) / 8 + (out->n_fields == 3 ? n_elems / scale_block(fmt) : 0);
     out->container_bytes = t.out_bytes;
     uint64_t all_bits = 0;
     for (uint32_t f = 0; f < out->n_fields; f++) {

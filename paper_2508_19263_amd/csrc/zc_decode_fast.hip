@@ -462,7 +462,7 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     if (F_::NF == 3) {
         // block scales: one byte per 32 elements, 16 per run, the chunk's E/32 scales in rows of 1024
         constexpr int F2 = F_::NF - 1;
-        const uint32_t n_sc = E / 32;
+        const uint32_t n_sc = E / F_::SCALE;
         const __amdgpu_buffer_rsrc_t r2 = make_rsrc(sp[F2], sb[F2]);
         const __amdgpu_buffer_rsrc_t ss = make_rsrc(reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.scales_out)) + (uint64_t)chunk * n_sc, n_sc);
         const uint32_t p2 = uniform32(d.period[F2]);
@@ -502,6 +502,7 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const Tens
     case ZC_FMT_FP4_E2M1_MX: return launch_s64_x<ZC_FMT_FP4_E2M1_MX>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
     case ZC_FMT_FP8_E4M3_BYTES: return launch_s64_x<ZC_FMT_FP8_E4M3_BYTES>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
     case ZC_FMT_FP4_E2M1_MX_BYTES: return launch_s64_x<ZC_FMT_FP4_E2M1_MX_BYTES>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_FP4_E2M1_NV: return launch_s64_x<ZC_FMT_FP4_E2M1_NV>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
     default: return 1;
     }
 }

@@ -33,12 +33,14 @@ __device__ __forceinline__ uint32_t prefix_count(uint64_t m)
 // EB element bits, EPR elements per 16-byte run, GRP field values per coded symbol, G symbols per run,
 // SB symbol bits, NF fields, BASE the element format (whose split and join the format uses)
 template <int FMT> struct Fmt;
-template <> struct Fmt<ZC_FMT_BF16> { static constexpr int EB = 16, EPR = 8, GRP = 1, G = 8, SB = 8, NF = 2, BASE = ZC_FMT_BF16; };
-template <> struct Fmt<ZC_FMT_FP8_E4M3> { static constexpr int EB = 8, EPR = 16, GRP = 1, G = 16, SB = 4, NF = 2, BASE = ZC_FMT_FP8_E4M3; };
-template <> struct Fmt<ZC_FMT_FP4_E2M1_MX> { static constexpr int EB = 4, EPR = 32, GRP = 1, G = 32, SB = 2, NF = 3, BASE = ZC_FMT_FP4_E2M1_MX; };
+// SCALE elements share one scale byte (1 where the format has none: never used there)
+template <> struct Fmt<ZC_FMT_BF16> { static constexpr int EB = 16, EPR = 8, GRP = 1, G = 8, SB = 8, NF = 2, BASE = ZC_FMT_BF16, SCALE = 1; };
+template <> struct Fmt<ZC_FMT_FP8_E4M3> { static constexpr int EB = 8, EPR = 16, GRP = 1, G = 16, SB = 4, NF = 2, BASE = ZC_FMT_FP8_E4M3, SCALE = 1; };
+template <> struct Fmt<ZC_FMT_FP4_E2M1_MX> { static constexpr int EB = 4, EPR = 32, GRP = 1, G = 32, SB = 2, NF = 3, BASE = ZC_FMT_FP4_E2M1_MX, SCALE = 32; };
+template <> struct Fmt<ZC_FMT_FP4_E2M1_NV> { static constexpr int EB = 4, EPR = 32, GRP = 1, G = 32, SB = 2, NF = 3, BASE = ZC_FMT_FP4_E2M1_MX, SCALE = 16; };
 // byte-grouped symbols: the packed field words are those of the element format, read 8 bits at a time
-template <> struct Fmt<ZC_FMT_FP8_E4M3_BYTES> { static constexpr int EB = 8, EPR = 16, GRP = 2, G = 8, SB = 8, NF = 2, BASE = ZC_FMT_FP8_E4M3; };
-template <> struct Fmt<ZC_FMT_FP4_E2M1_MX_BYTES> { static constexpr int EB = 4, EPR = 32, GRP = 4, G = 8, SB = 8, NF = 3, BASE = ZC_FMT_FP4_E2M1_MX; };
+template <> struct Fmt<ZC_FMT_FP8_E4M3_BYTES> { static constexpr int EB = 8, EPR = 16, GRP = 2, G = 8, SB = 8, NF = 2, BASE = ZC_FMT_FP8_E4M3, SCALE = 1; };
+template <> struct Fmt<ZC_FMT_FP4_E2M1_MX_BYTES> { static constexpr int EB = 4, EPR = 32, GRP = 4, G = 8, SB = 8, NF = 3, BASE = ZC_FMT_FP4_E2M1_MX, SCALE = 32; };
 
 // ------------------------------------------------- field split / join of one 16-byte run
 // P0 = the run's exponent symbols, P1 = its sign+mantissa symbols, SB bits each, symbol j at

@@ -13,7 +13,13 @@ constexpr int kMaxFields = 3;
 
 // ---- format geometry -------------------------------------------------------
 // element format of a (possibly byte-grouped) format, and field values per coded symbol
-inline uint32_t base_format(uint32_t fmt) { return fmt == ZC_FMT_FP8_E4M3_BYTES ? ZC_FMT_FP8_E4M3 : fmt == ZC_FMT_FP4_E2M1_MX_BYTES ? ZC_FMT_FP4_E2M1_MX : fmt; }
+inline uint32_t base_format(uint32_t fmt)
+{
+    if (fmt == ZC_FMT_FP4_E2M1_NV) return ZC_FMT_FP4_E2M1_MX;      // same elements, other scales
+    return fmt == ZC_FMT_FP8_E4M3_BYTES ? ZC_FMT_FP8_E4M3 : fmt == ZC_FMT_FP4_E2M1_MX_BYTES ? ZC_FMT_FP4_E2M1_MX : fmt;
+}
+// elements that share one scale byte (0: the format has no scales)
+inline uint32_t scale_block(uint32_t fmt) { return fmt == ZC_FMT_FP4_E2M1_NV ? 16 : (fmt == ZC_FMT_FP4_E2M1_MX || fmt == ZC_FMT_FP4_E2M1_MX_BYTES) ? 32 : 0; }
 inline int group_of(uint32_t fmt) { return fmt == ZC_FMT_FP8_E4M3_BYTES ? 2 : fmt == ZC_FMT_FP4_E2M1_MX_BYTES ? 4 : 1; }
 inline bool is_fp4(uint32_t fmt) { return base_format(fmt) == ZC_FMT_FP4_E2M1_MX; }
 inline int elem_bits(uint32_t fmt) { fmt = base_format(fmt); return fmt == ZC_FMT_BF16 ? 16 : fmt == ZC_FMT_FP8_E4M3 ? 8 : fmt == ZC_FMT_FP4_E2M1_MX ? 4 : 0; }

@@ -44,7 +44,8 @@ __global__ __launch_bounds__(256) void k_hist(const TensorDev *descs, const Work
     const TensorDev &d = descs[it.tensor];
     const uint8_t *p = scales_view ? d.scales : d.src;
     const uint8_t *base = scales_view ? nullptr : d.base;
-    const uint64_t nbytes = scales_view ? d.n_elems / 32 : (d.n_elems * (uint64_t)elem_bits_ + 7) / 8;
+    // scales_view: 0, or the number of elements per scale byte when the scale bytes are the input
+    const uint64_t nbytes = scales_view ? d.n_elems / (uint32_t)scales_view : (d.n_elems * (uint64_t)elem_bits_ + 7) / 8;
     for (uint32_t i = threadIdx.x; i < 256 * 32; i += 256) h[i] = 0;
     __syncthreads();
     const uint64_t start = (uint64_t)it.first * kHistBlockBytes;
@@ -313,9 +314,9 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
     // ---- FP4 block scales: one byte per 32 elements, runs of 16 bytes ----
     if (F_::NF == 3) {
         EncField F2 = {0, 0, 0, 0, 0, 0, 0};
-        const uint32_t ns = n / 32;
-        const uint32_t srows = (uint32_t)((E / 32 + 15) / 16 + S - 1) / S;
-        const uint8_t *sc = d.scales + (uint64_t)chunk * (E / 32);
+        const uint32_t ns = n / F_::SCALE;
+        const uint32_t srows = (uint32_t)((E / F_::SCALE + 15) / 16 + S - 1) / S;
+        const uint8_t *sc = d.scales + (uint64_t)chunk * (E / F_::SCALE);
         const uint32_t m2 = d.mode[2];
         for (uint32_t i = 0; i < srows; i++) {
             const uint32_t run = i * S + L.s;
@@ -353,6 +354,7 @@ static int launch_encode_t(uint32_t fmt, const TensorDev *d_descs, const WorkIte
     case ZC_FMT_FP4_E2M1_MX: hipLaunchKernelGGL((k_encode<ZC_FMT_FP4_E2M1_MX, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
     case ZC_FMT_FP8_E4M3_BYTES: hipLaunchKernelGGL((k_encode<ZC_FMT_FP8_E4M3_BYTES, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
     case ZC_FMT_FP4_E2M1_MX_BYTES: hipLaunchKernelGGL((k_encode<ZC_FMT_FP4_E2M1_MX_BYTES, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
+    case ZC_FMT_FP4_E2M1_NV: hipLaunchKernelGGL((k_encode<ZC_FMT_FP4_E2M1_NV, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
     default: return 1;
     }
     return (int)hipGetLastError();
@@ -585,9 +587,9 @@ __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const Wo
     if (F_::NF == 3) {
         DecField D2 = open_stream(d, F_::NF - 1, chunk, valid);
         const uint32_t m2 = d.mode[F_::NF - 1];
-        const uint32_t ns = n / 32;
-        const uint32_t srows = (uint32_t)((E / 32 + 15) / 16 + S - 1) / S;
-        uint8_t *sc = d.scales_out + (uint64_t)slot * (E / 32);
+        const uint32_t ns = n / F_::SCALE;
+        const uint32_t srows = (uint32_t)((E / F_::SCALE + 15) / 16 + S - 1) / S;
+        uint8_t *sc = d.scales_out + (uint64_t)slot * (E / F_::SCALE);
         const uint64_t K2 = splat(d.konst[F_::NF - 1], 8);
         for (uint32_t i = 0; i < srows; i++) {
             const uint32_t run = i * S + L.s;
@@ -619,6 +621,7 @@ int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work
     case ZC_FMT_FP4_E2M1_MX: hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_MX>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
     case ZC_FMT_FP8_E4M3_BYTES: hipLaunchKernelGGL(k_decode<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
     case ZC_FMT_FP4_E2M1_MX_BYTES: hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_MX_BYTES>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
+    case ZC_FMT_FP4_E2M1_NV: hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_NV>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
     default: return 1;
     }
     return (int)hipGetLastError();

@@ -58,14 +58,42 @@ def mxfp4_bits(x):
     e = torch.where(amax > 0, e, torch.full_like(e, -127)).clamp(-127, 127)
     scale = (e + 127).to(torch.uint8)
     v = flat * torch.exp2(-e.to(torch.float32)).unsqueeze(1)
+    code = e2m1_codes(v)
+    code = code.reshape(-1, 2)
+    packed = (code[:, 0] | (code[:, 1] << 4)).to(torch.uint8)
+    return packed, scale
+
+
+def e4m3_to_f32(bits):
+    """OCP FP8 E4M3 bytes -> float32 (exact)."""
+    b = bits.to(torch.int32)
+    e, m = (b >> 3) & 0xF, b & 7
+    mag = torch.where(e > 0, (1.0 + m.to(torch.float32) / 8.0) * torch.exp2((e - 7).to(torch.float32)), m.to(torch.float32) * 2.0 ** -9)
+    return torch.where((b & 0x80) != 0, -mag, mag)
+
+
+def e2m1_codes(v):
+    """float32 -> E2M1 codes (sign in bit 3), RNE onto {0, .5, 1, 1.5, 2, 3, 4, 6}, saturating."""
     a = v.abs()
     code = torch.where(a < 1.0, torch.round(a * 2.0),
            torch.where(a < 2.0, 2.0 + torch.round((a - 1.0) * 2.0),
            torch.where(a < 4.0, 4.0 + torch.round(a - 2.0), 6.0 + torch.round((a - 4.0) * 0.5))))
-    code = code.clamp(0, 7).to(torch.int32) | ((v.view(torch.int32) >> 28) & 0x8)
-    code = code.reshape(-1, 2)
-    packed = (code[:, 0] | (code[:, 1] << 4)).to(torch.uint8)
-    return packed, scale
+    return code.clamp(0, 7).to(torch.int32) | ((v.contiguous().view(torch.int32) >> 28) & 0x8)
+
+
+def nvfp4_bits(x):
+    """float32 [.., 16*k] -> (packed E2M1 bytes, E4M3 scale bytes): one FP8 scale per 16 contiguous
+    elements (Sec. 3.4).  The block scale is amax/6 divided by a per-tensor factor that maps the largest
+    block scale to 448, cast to E4M3; the elements are RNE onto the E2M1 grid after division by the scale
+    as stored.  Element 2i is the low nibble of byte i."""
+    flat = x.contiguous().reshape(-1, 16)
+    block = flat.abs().amax(dim=1) / 6.0
+    tensor_scale = block.max().clamp_min(1e-30) / 448.0
+    scale = e4m3_bits(block / tensor_scale)
+    dec = e4m3_to_f32(scale) * tensor_scale
+    v = torch.where(dec.unsqueeze(1) > 0, flat / dec.clamp_min(1e-30).unsqueeze(1), torch.zeros_like(flat))
+    code = e2m1_codes(v).reshape(-1, 2)
+    return (code[:, 0] | (code[:, 1] << 4)).to(torch.uint8), scale
 
 
 # ------------------------------------------------------------- generators
@@ -120,12 +148,41 @@ def mxfp4_weight(rows, cols, device="cpu", seed=0, std=0.015):
     return mxfp4_bits(x)
 
 
+def nvfp4_weight(rows, cols, device="cpu", seed=0, std=0.015):
+    """One NVFP4 matrix -> (packed element bytes, E4M3 scale bytes, one per 16 elements)."""
+    g = _gen(device, seed)
+    x = torch.randn(rows * cols, generator=g, device=device) * std
+    return nvfp4_bits(x)
+
+
 def bf16_checkpoint_pair(n, device="cpu", seed=0, std=0.02, step_std=1e-4):
     """Config 4: W0 ~ N(0, std) in BF16 and W1 = bf16(W0 + N(0, step_std))."""
     g = _gen(device, seed)
     w0 = bf16_bits(torch.randn(n, generator=g, device=device) * std)
     w1 = bf16_bits(bf16_to_f32(w0) + torch.randn(n, generator=g, device=device) * step_std)
     return w0, w1
+
+
+def _kv_values(batch, heads, tokens, head_dim, device, seed):
+    """(K, V) as float32, shape [batch, heads, tokens, head_dim]: V ~ N(0,1); K ~ N(0,1) with 4 fixed
+    outlier channels per head at std 10 plus a slow drift 0.1*sin(t/512)."""
+    g = _gen(device, seed)
+    shape = (batch, heads, tokens, head_dim)
+    v = torch.randn(shape, generator=g, device=device)
+    k = torch.randn(shape, generator=g, device=device)
+    sigma = torch.ones(heads, head_dim, device=device)
+    for h in range(heads):
+        ch = torch.randperm(head_dim, generator=g, device=device)[:4]
+        sigma[h, ch] = 10.0
+    t = torch.arange(tokens, device=device, dtype=torch.float32)
+    k = k * sigma.view(1, heads, 1, head_dim) + 0.1 * torch.sin(t / 512.0).view(1, 1, tokens, 1)
+    return k, v
+
+
+def bf16_kv_pair(batch=4, heads=8, tokens=8192, head_dim=128, device="cpu", seed=0):
+    """One layer's (K, V) cache in BF16 (int16 bit patterns), same distributions as fp8_kv_pair, unscaled."""
+    k, v = _kv_values(batch, heads, tokens, head_dim, device, seed)
+    return bf16_bits(k), bf16_bits(v)
 
 
 def fp8_kv_pair(batch=4, heads=8, tokens=8192, head_dim=128, device="cpu", seed=0):

@@ -13,7 +13,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libzc.so")
 
-FMT_BF16, FMT_FP8_E4M3, FMT_FP4_E2M1_MX, FMT_FP8_E4M3_BYTES, FMT_FP4_E2M1_MX_BYTES = 1, 2, 3, 4, 5
+FMT_BF16, FMT_FP8_E4M3, FMT_FP4_E2M1_MX, FMT_FP8_E4M3_BYTES, FMT_FP4_E2M1_MX_BYTES, FMT_FP4_E2M1_NV = 1, 2, 3, 4, 5, 6
 POLICY_HUFF_ALL, POLICY_AUTO = 0, 1
 MODE_EMPTY, MODE_HUFF, MODE_RAW, MODE_CONST = 0, 1, 2, 3
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_BUFFER_TOO_SMALL, ERR_CORRUPT, ERR_DEVICE = range(6)
@@ -135,7 +135,12 @@ def params(fmt, chunk_bytes, max_code_len=(0, 0, 0), streams=0, policy=POLICY_HU
 
 
 def elem_bits(fmt):
-    return {FMT_BF16: 16, FMT_FP8_E4M3: 8, FMT_FP4_E2M1_MX: 4, FMT_FP8_E4M3_BYTES: 8, FMT_FP4_E2M1_MX_BYTES: 4}[fmt]
+    return {FMT_BF16: 16, FMT_FP8_E4M3: 8, FMT_FP4_E2M1_MX: 4, FMT_FP8_E4M3_BYTES: 8, FMT_FP4_E2M1_MX_BYTES: 4, FMT_FP4_E2M1_NV: 4}[fmt]
+
+
+def scale_block(fmt):
+    """Elements that share one scale byte (0: the format has none)."""
+    return {FMT_FP4_E2M1_MX: 32, FMT_FP4_E2M1_MX_BYTES: 32, FMT_FP4_E2M1_NV: 16}.get(fmt, 0)
 
 
 def _ptr(t):
@@ -239,7 +244,7 @@ def decompress(comp, info=None, out=None, scales_out=None, xor_base=None):
     if out is None:
         out = torch.empty(raw, dtype=torch.uint8, device=comp.device)
     if info.n_fields == 3 and scales_out is None:
-        scales_out = torch.empty(max(info.n_elems // 32, 1), dtype=torch.uint8, device=comp.device)
+        scales_out = torch.empty(max(info.n_elems // scale_block(info.format), 1), dtype=torch.uint8, device=comp.device)
     st = lib().zc_decompress(_ptr(comp), comp.numel(), C.byref(info), _ptr(out), out.numel() * out.element_size(),
                              _ptr(scales_out), _ptr(xor_base), _stream())
     _check(st, "zc_decompress")
@@ -252,7 +257,7 @@ def decompress_chunks(comp, info, ids, out=None, scales_out=None, xor_base=None)
     if out is None:
         out = torch.empty(n * info.chunk_bytes, dtype=torch.uint8, device=comp.device)
     if info.n_fields == 3 and scales_out is None:
-        scales_out = torch.empty(max(n * info.chunk_bytes // 16, 1), dtype=torch.uint8, device=comp.device)
+        scales_out = torch.empty(max(n * info.chunk_bytes * 2 // scale_block(info.format), 1), dtype=torch.uint8, device=comp.device)
     st = lib().zc_decompress_chunks(_ptr(comp), comp.numel(), C.byref(info), _ptr(ids), n, _ptr(out),
                                     out.numel() * out.element_size(), _ptr(scales_out), _ptr(xor_base), _stream())
     _check(st, "zc_decompress_chunks")
@@ -318,8 +323,8 @@ class Batch:
         dev = self.arena.device
         eb = elem_bits(self.p.format)
         self.out = [torch.empty(max((int(self.arr[i].n_elems) * eb + 7) // 8, 16), dtype=torch.uint8, device=dev) for i in range(self.n)]
-        if self.p.format in (FMT_FP4_E2M1_MX, FMT_FP4_E2M1_MX_BYTES):
-            self.scales_out = [torch.empty(max(int(self.arr[i].n_elems) // 32, 16), dtype=torch.uint8, device=dev) for i in range(self.n)]
+        if scale_block(self.p.format):
+            self.scales_out = [torch.empty(max(int(self.arr[i].n_elems) // scale_block(self.p.format), 16), dtype=torch.uint8, device=dev) for i in range(self.n)]
         for i in range(self.n):
             self.arr[i].d_dst = self.out[i].data_ptr()
             self.arr[i].d_scales_out = self.scales_out[i].data_ptr() if self.scales_out else None

@@ -18,6 +18,8 @@ def make_input(fmt, n, seed):
         return wl.fp8_weight(n, seed=seed) if n else torch.zeros(0, dtype=torch.uint8), None
     if n == 0:
         return torch.zeros(0, dtype=torch.uint8), torch.zeros(0, dtype=torch.uint8)
+    if fmt == zc.FMT_FP4_E2M1_NV:
+        return wl.nvfp4_weight(1, n, seed=seed)
     return wl.mxfp4_weight(1, n, seed=seed)
 
 
@@ -522,3 +524,37 @@ def test_byte_grouped_symbols():
         assert list(st.field[f].hist) == list(so.field[f].hist) and st.field[f].payload_bits == so.field[f].payload_bits
         assert abs(st.field[f].entropy_bits - so.field[f].entropy_bits) < 1e-12
     assert st.container_bytes == so.container_bytes
+
+
+def test_nvfp4():
+    # Sec. 3.4: NVFP4 = E2M1 elements + one E4M3 scale byte per 16 elements
+    F = zc.FMT_FP4_E2M1_NV
+    for S in (64, 16, 2):
+        for n in (16, 16 * S * 3, 8192 - 16, 8192, 8192 + 16, 5 * 8192 + 48):
+            for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+                check_case(F, n, 4096, S, policy, tag="nvfp4")
+    m, sc = wl.nvfp4_weight(256, 3584, seed=3)
+    check_case(F, 256 * 3584, 262144, 64, data=(m, sc), tag="nvfp4-full")          # 64-lane full-chunk kernel
+    check_case(F, 256 * 3584, 16384, 64, zc.POLICY_AUTO, data=(m, sc), tag="nvfp4-auto")
+    # random access: chunks by id with their scale bytes
+    p, po = zc.params(F, 16384), o.params(F, 16384)
+    comp, info = zc.compress(dev(m), 256 * 3584, p, scales=dev(sc))
+    ids = torch.tensor([27, 0, 13], dtype=torch.int32, device=DEV)
+    out, sco = zc.decompress_chunks(comp, info, ids)
+    torch.cuda.synchronize()
+    for k, c in enumerate(ids.tolist()):
+        assert torch.equal(out.cpu()[k * 16384:(k + 1) * 16384], m[c * 16384:(c + 1) * 16384])
+        assert torch.equal(sco.cpu()[k * 2048:(k + 1) * 2048], sc[c * 2048:(c + 1) * 2048])
+    # batch + stats
+    mats = [wl.nvfp4_weight(64, 1024 + 512 * i, seed=20 + i) for i in range(3)]
+    bt = zc.Batch([dev(a) for a, _ in mats], [a.numel() * 2 for a, _ in mats], p, scales=[dev(b) for _, b in mats])
+    bt.compress()
+    for i, (a, b) in enumerate(mats):
+        assert np.array_equal(bt.container(i).cpu().numpy(), o.compress(a.numpy(), a.numel() * 2, po, scales=b.numpy()))
+    outs = bt.decompress()
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(mats):
+        assert torch.equal(outs[i].cpu()[:a.numel()], a) and torch.equal(bt.scales_out[i].cpu()[:b.numel()], b)
+    st, so = zc.stats(dev(m), 256 * 3584, p, scales=dev(sc)), o.stats(m.numpy(), 256 * 3584, po, scales=sc.numpy())
+    assert st.raw_bytes == so.raw_bytes and st.container_bytes == so.container_bytes
+    assert list(st.field[2].hist) == list(so.field[2].hist)

