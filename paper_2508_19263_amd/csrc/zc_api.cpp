@@ -284,6 +284,8 @@ TensorDev make_desc(const zc_info &info)
 // shared by zc_compress_batch and zc_stats: histogram -> codes (-> sizes -> scan [-> encode])
 // dict: precomputed dictionary to code with (no histogram pass), or null.  train: stop after the
 // code construction with smoothed counts (codes_out receives the dictionary).
+uint32_t sub_slots_per_group(uint32_t streams, uint64_t slots);
+
 zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, void *d_ws, uint64_t ws_bytes, void *stream,
                        bool stats_only, std::vector<FieldCode> *codes_out, std::vector<ScanOut> *scan_out,
                        const zc_info *dict = nullptr, bool train = false)
@@ -330,6 +332,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         d.n_elems = x.n_elems; d.n_chunks = (uint32_t)nc; d.chunk_bytes = g.chunk_bytes; d.streams = g.S;
         d.payload_off = payload_off;
         for (uint32_t f = 0; f < g.nf; f++) { d.table_off[f] = (uint32_t)table_off[f]; d.index_off[f] = (uint32_t)index_off[f]; }
+        d.dst_bytes = stats_only ? 0 : x.comp_capacity;         // compress: bytes that may be written at comp
         d.units_off = (uint32_t)units_off;
         units_off += nc * g.nf;
         const uint64_t bytes = (x.n_elems * (uint64_t)elem_bits(g.fmt) + 7) / 8;
@@ -376,7 +379,11 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         // FP8 shape the specialised size/encode kernels take: 64 lanes, chunks of whole 1 KiB rows,
         // exponent refill period 4 (longest code 5..8 bits), sign+mantissa flat or raw.  Their table (slot of the
         // unused third field) maps a pair of exponents to the two codes concatenated.
-        const bool fast_ok = g.fmt == ZC_FMT_FP8_E4M3 && g.S == 64 && g.chunk_bytes % 1024 == 0 && fc[0].mode == ZC_MODE_HUFF &&
+        // With 4..32 lanes per chunk (pages) the sub-wavefront kernels take the same shape, as long as the tensor
+        // fits their 32-bit offsets.
+        const bool lanes_ok = g.S == 64 ? g.chunk_bytes % 1024 == 0
+                                        : (g.S >= 4 && g.chunk_bytes % (16 * g.S) == 0 && tensors[t].n_elems <= 0xF0000000ull);
+        const bool fast_ok = g.fmt == ZC_FMT_FP8_E4M3 && lanes_ok && fc[0].mode == ZC_MODE_HUFF &&
                              descs[t].period[0] == 4 && (descs[t].kind[1] == 1 || descs[t].kind[1] == 2);
         if (fast_ok)
             for (uint32_t u = 0; u < 256; u++) {
@@ -403,9 +410,12 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         for (auto &th : pool) th.join();
         for (uint32_t k = 0; k < n_threads; k++) if (status[k]) return status[k];
     }
+    uint64_t all_chunks = 0;
+    for (uint32_t t = 0; t < T; t++) all_chunks += ncs[t];
+    const uint32_t fast_step = g.S == 64 ? kWavesPerGroup : sub_slots_per_group(g.S, all_chunks);    // chunks per fast work item
     for (uint32_t t = 0; t < T; t++) {
         const uint64_t n_full = fast_flag[t] ? tensors[t].n_elems / g.elems_per_chunk : 0;
-        for (uint64_t c = 0; c < n_full; c += kWavesPerGroup) fast_work.push_back({t, (uint32_t)c});
+        for (uint64_t c = 0; c < n_full; c += fast_step) fast_work.push_back({t, (uint32_t)c});
         for (uint64_t c = n_full; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
     }
     if (codes_out) *codes_out = codes;
@@ -421,7 +431,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     // stream sizes (a5) and their exclusive scan into the chunk index (a6)
     const uint32_t *d_enc = (const uint32_t *)(ws + w.enc);
     uint32_t *d_units = (uint32_t *)(ws + w.units);
-    LAUNCH_TRY(launch_sizes_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, stream));
+    if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, stream));
+    else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 0, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
     LAUNCH_TRY(launch_sizes(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), cpi, d_enc, d_units, stream));
     LAUNCH_TRY(launch_scan(d_descs, T, (int)g.nf, d_units, (ScanOut *)(ws + w.scan), stream));
     std::vector<ScanOut> scan(T);
@@ -437,7 +448,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     if (stats_only) return ZC_OK;
 
     // chunked encode (a7)
-    LAUNCH_TRY(launch_encode_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, stream));
+    if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, stream));
+    else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
     LAUNCH_TRY(launch_encode(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), cpi, d_enc, stream));
     return ZC_OK;
 }

@@ -181,6 +181,170 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
     if (lane < ((4 - (wpos & 3)) & 3)) __builtin_amdgcn_raw_buffer_store_b32(0u, es, (int)((wpos + lane) * 4), 0, 0);
 }
 
+// ---------------------------------------------------------------------------------------
+// The same shape with fewer than 64 lanes per chunk (small chunks such as K/V-cache pages, whose
+// compression sits on the critical path of a decoding step: Sec. 5.2): a wavefront handles 64/S chunks
+// at once, one per S-lane group.  Ballots are masked to the group, stream positions are per group, and
+// the buffer resources span the tensor and the container's payload with the group's offsets in the
+// vector offset; a lane with nothing to write aims past the end of the resource, where the hardware
+// drops the store.  WRITE = false is the size pass.  A workgroup takes slots_per_group chunks in passes
+// of 4 wavefronts x 64/S.
+template <int S, bool WRITE>
+__global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units,
+                                                        uint32_t slots_per_group)
+{
+    static_assert(S >= 4 && S <= 32, "the zero padding of a stream's last unit takes up to 3 lanes of the group");
+    constexpr uint32_t kGroups = 64 / S;
+    constexpr uint32_t kNowhere = 0xFFFFFFF0u;
+    __shared__ uint32_t pair[256];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev *dp = descs + it.tensor;
+    pair[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + 512 + threadIdx.x];
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t s = lane & (S - 1), grp = lane / S;
+    const uint64_t gmask = ((1ull << S) - 1) << (lane - s);
+    const uint32_t cb = uni32(dp->chunk_bytes);                  // one element per byte
+    const uint64_t n_elems = uni64(dp->n_elems);
+    const uint32_t n_full = (uint32_t)(n_elems / cb), nc = uni32(dp->n_chunks);
+    const bool has_base = uni64((uint64_t)dp->base) != 0;
+    const bool sm_raw = uni32(dp->kind[1]) == 2;
+    uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
+    const uint64_t payload = uni64(dp->payload_off), cap = uni64(dp->dst_bytes);
+    if (n_elems > 0xFFFFFFF0ull) return;                         // the host never launches this
+    const __amdgpu_buffer_rsrc_t src = rsrc_of(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)), (uint32_t)n_elems);
+    const __amdgpu_buffer_rsrc_t bas = rsrc_of(has_base ? reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) : nullptr, has_base ? (uint32_t)n_elems : 0u);
+    const uint64_t pay_cap = (WRITE && cap > payload) ? (cap - payload > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : cap - payload) : 0;
+    const __amdgpu_buffer_rsrc_t ps = rsrc_of(WRITE ? comp + payload : nullptr, (uint32_t)pay_cap);
+    const uint32_t *index0 = WRITE ? reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[0])) : nullptr;
+    const uint32_t *index1 = WRITE ? reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[1])) : nullptr;
+    uint32_t *my = units + uni32(dp->units_off);
+    const char *pair_lut = reinterpret_cast<const char *>(pair);
+    const uint32_t two = 2;
+    const uint32_t rows = cb / (16 * S);
+
+    for (uint32_t pass = 0; pass * kWavesPerGroup * kGroups < slots_per_group; pass++) {
+        const uint32_t local = (pass * kWavesPerGroup + wave) * kGroups + grp;
+        const uint32_t chunk = it.first + local;
+        bool alive = local < slots_per_group && chunk < n_full;  // a short last chunk goes to the generic kernel
+        uint32_t e_off = kNowhere, e_len = 0, m_off = kNowhere;
+        if (WRITE && alive) {
+            const uint64_t a0 = index0[chunk], b0 = index0[chunk + 1], a1 = index1[chunk], b1 = index1[chunk + 1];
+            // the index must be as the size pass left it, and inside the 32-bit offset space of the payload
+            if (a0 <= b0 && a1 <= b1 && 16 * b1 <= pay_cap && 16 * b0 <= pay_cap && (b1 - a1) * 16 == cb / 2) {
+                e_off = (uint32_t)(16 * a0); e_len = (uint32_t)(16 * (b0 - a0)); m_off = (uint32_t)(16 * a1);
+            } else alive = false;
+        }
+        const uint32_t in_off = alive ? chunk * cb : kNowhere;
+
+        uint64_t acc = 0;           // bits not yet written, next free bit = nacc (< 32 between groups)
+        uint32_t nacc = 0;
+        int32_t k = 0;              // unread bits the decoder would hold at this point
+        uint32_t pend = 0, p0 = 0, p1 = 0;
+        uint32_t wpos = 0, q = 0;
+        for (uint32_t row = 0; row < rows; row++) {
+            const uint32_t at = alive ? in_off + (row * S + s) * 16 : kNowhere;
+            u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(src, (int)at, 0, 0);
+            v ^= __builtin_amdgcn_raw_buffer_load_b128(bas, (int)at, 0, 0);      // empty resource without a base: reads as zero
+            if (WRITE) {
+                uint32_t m[2];
+#pragma unroll
+                for (int h = 0; h < 2; h++) {
+                    const uint32_t lo = pack_nibbles_of_bytes(((v[2 * h] >> 4) & 0x08080808u) | (v[2 * h] & 0x07070707u));
+                    const uint32_t hi = pack_nibbles_of_bytes(((v[2 * h + 1] >> 4) & 0x08080808u) | (v[2 * h + 1] & 0x07070707u));
+                    m[h] = lo | (hi << 16);
+                }
+                // raw: the packed nibbles as they are; flat code: every symbol most significant bit first, one
+                // word per 8 symbols, rows of S words
+                const uint32_t raw_at = (alive && sm_raw) ? m_off + (row * S + s) * 8 : kNowhere;
+                __builtin_amdgcn_raw_buffer_store_b64(u32x2{m[0], m[1]}, ps, (int)raw_at, 0, 0);
+#pragma unroll
+                for (int h = 0; h < 2; h++) {
+                    uint32_t w = ((m[h] >> 1) & 0x55555555u) | ((m[h] & 0x55555555u) << 1);
+                    w = ((w >> 2) & 0x33333333u) | ((w & 0x33333333u) << 2);
+                    const uint32_t flat_at = (alive && !sm_raw) ? m_off + ((row * 2 + h) * S + s) * 4 : kNowhere;
+                    __builtin_amdgcn_raw_buffer_store_b32(w, ps, (int)flat_at, 0, 0);
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                const bool req = k <= 32;
+                if (WRITE) {
+                    const uint64_t bm = __ballot(req) & gmask;
+                    const uint32_t pos = wpos + __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, 0));
+                    p0 = (req && pend == 0) ? pos : p0;
+                    p1 = (req && pend != 0) ? pos : p1;
+                    pend += req ? 1u : 0u;
+                    wpos += (uint32_t)__popcll(bm);
+                } else q += req ? 1u : 0u;
+                k += req ? 32 : 0;
+                uint32_t code, len;
+                group_code(v[g], pair_lut, two, code, len);
+                k -= (int32_t)len;
+                if (WRITE) {
+                    acc |= (uint64_t)code << nacc;
+                    nacc += len;
+                    const bool full = nacc >= 32;
+                    const uint32_t to = (alive && full && p0 * 4 < e_len) ? e_off + p0 * 4 : kNowhere;
+                    __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, ps, (int)to, 0, 0);
+                    acc = full ? acc >> 32 : acc;
+                    nacc = full ? nacc - 32 : nacc;
+                    p0 = full ? p1 : p0;
+                    pend -= full ? 1u : 0u;
+                }
+            }
+        }
+        if (WRITE) {
+            // the words still owed to the decoder (a partial word and look-ahead words), then zero padding
+#pragma unroll
+            for (int t = 0; t < 2; t++) {
+                const uint32_t to = (alive && pend > 0 && p0 * 4 < e_len) ? e_off + p0 * 4 : kNowhere;
+                __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, ps, (int)to, 0, 0);
+                acc = pend > 0 ? acc >> 32 : acc;
+                p0 = pend > 0 ? p1 : p0;
+                pend -= pend > 0 ? 1u : 0u;
+            }
+            const uint32_t padw = wpos + s;
+            const uint32_t to = (alive && s < ((4 - (wpos & 3)) & 3) && padw * 4 < e_len) ? e_off + padw * 4 : kNowhere;
+            __builtin_amdgcn_raw_buffer_store_b32(0u, ps, (int)to, 0, 0);
+        } else {
+            // words of the chunk's exponent stream = sum over the lanes of the group
+#pragma unroll
+            for (int o = S / 2; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+            if (alive && s == 0) {
+                my[chunk] = (q + 3) / 4;
+                my[nc + chunk] = cb / 32;                            // 4 bits per element, 16-byte units (flat code and raw alike)
+            }
+        }
+    }
+}
+
+template <int S, bool WRITE>
+static void launch_sub_t(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, uint32_t slots_per_group, hipStream_t st)
+{
+    hipLaunchKernelGGL((k_encode_fp8_sub<S, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, slots_per_group);
+}
+
+// streams: 4, 8, 16 or 32.  write == 0: size pass (d_units), else encode.
+int launch_encode_fp8_sub(uint32_t streams, int write, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
+                          uint32_t *d_units, uint32_t slots_per_group, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    switch (streams * 2 + (write ? 1 : 0)) {
+    case 8: launch_sub_t<4, false>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 9: launch_sub_t<4, true>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 16: launch_sub_t<8, false>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 17: launch_sub_t<8, true>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 32: launch_sub_t<16, false>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 33: launch_sub_t<16, true>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 64: launch_sub_t<32, false>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 65: launch_sub_t<32, true>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    default: return 1;
+    }
+    return (int)hipGetLastError();
+}
+
 int launch_sizes_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream)
 {
     if (n_work == 0) return 0;

@@ -50,7 +50,7 @@ struct alignas(16) TensorDev {
     uint8_t *dst;             // decompress: elements out
     uint8_t *scales_out;      // decompress, FP4
     const uint32_t *ids;      // decompress: chunk id list (slot i decodes chunk ids[i]) or null (slot i = chunk i)
-    uint64_t dst_bytes;       // decompress: bytes that may be written at dst
+    uint64_t dst_bytes;       // decompress: bytes that may be written at dst; compress: at comp
     uint64_t n_elems;
     uint64_t total_bytes;     // decompress: container size (bounds for reads)
     uint64_t payload_off;
@@ -104,6 +104,8 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const Tens
 // FP8, 64 lanes, full chunks, exponent codes <= 8 bits, sign+mantissa flat or raw (zc_encode_fast.hip)
 int launch_sizes_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream);
 int launch_encode_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
+int launch_encode_fp8_sub(uint32_t streams, int write, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
+                          uint32_t *d_units, uint32_t slots_per_group, void *stream);
 uint32_t chunks_per_work_item(uint32_t streams);
 
 }  // namespace zc

@@ -558,3 +558,26 @@ def test_nvfp4():
     st, so = zc.stats(dev(m), 256 * 3584, p, scales=dev(sc)), o.stats(m.numpy(), 256 * 3584, po, scales=sc.numpy())
     assert st.raw_bytes == so.raw_bytes and st.container_bytes == so.container_bytes
     assert list(st.field[2].hist) == list(so.field[2].hist)
+
+
+def test_fp8_page_encoder():
+    # FP8 with 4..32 lanes per chunk: the sub-wavefront size/encode kernels, byte for byte against the oracle
+    for S in (4, 8, 16, 32):
+        for cb in (16 * S, 2048, 3 * 16 * S):
+            n = 37 * cb + 5
+            for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+                check_case(zc.FMT_FP8_E4M3, n, cb, S, policy, tag="fp8-pages")
+    a, b = wl.fp8_weight(50 * 2048 + 100, seed=71), wl.fp8_weight(50 * 2048 + 100, seed=72)
+    check_case(zc.FMT_FP8_E4M3, a.numel(), 2048, 16, data=(a, None), base=b, tag="fp8-pages-delta")
+    # enough chunks for several passes per workgroup (2 x 2048 x 4 x 64/S chunks)
+    x = wl.fp8_weight(140000 * 128 + 77, seed=73)
+    check_case(zc.FMT_FP8_E4M3, x.numel(), 128, 8, data=(x, None), tag="fp8-pages-passes")
+    # a batch of K/V tensors with a dictionary: no histogram, the same kernels
+    k, v = wl.fp8_kv_pair(batch=1, heads=2, tokens=2048, seed=74)
+    p, po = zc.params(zc.FMT_FP8_E4M3, 2048, streams=8), o.params(o.FP8_E4M3, 2048, streams=8)
+    code = zc.train_code(dev(k.reshape(-1)), k.numel(), p)
+    ln, md = o.train_code(k.reshape(-1).numpy(), k.numel(), po)
+    bt = zc.Batch([dev(k.reshape(-1)), dev(v.reshape(-1))], [k.numel(), v.numel()], p)
+    bt.compress(code=code)
+    for i, t in enumerate((k, v)):
+        assert np.array_equal(bt.container(i).cpu().numpy(), o.compress_with_code(t.reshape(-1).numpy(), t.numel(), po, ln, md))
