@@ -189,6 +189,15 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
 // vector offset; a lane with nothing to write aims past the end of the resource, where the hardware
 // drops the store.  WRITE = false is the size pass.  A workgroup takes slots_per_group chunks in passes
 // of 4 wavefronts x 64/S.
+//
+// The words of the exponent stream are not stored one by one (a lane's word goes to a position that was
+// handed out earlier, so such stores are scattered 4-byte writes): they are collected in a ring of 32*S
+// words per group in LDS and leave it in whole segments of 4*S words, 16 bytes per lane.  A segment is
+// complete when every position in it has been handed out and no lane still owes a word inside it.  A lane
+// that asks for a word has at most 64 more bits to produce before it writes that word (the decoder it
+// mirrors held at most 32 unread bits and the word adds 32), i.e. at most 16 steps of four symbols of at
+// least one bit each, during which the group hands out at most 16*S positions; with the segment rounding
+// and the 4*S positions of the row in progress the ring never holds more than 24*S words.
 template <int S, bool WRITE>
 __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units,
                                                         uint32_t slots_per_group)
@@ -196,7 +205,10 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
     static_assert(S >= 4 && S <= 32, "the zero padding of a stream's last unit takes up to 3 lanes of the group");
     constexpr uint32_t kGroups = 64 / S;
     constexpr uint32_t kNowhere = 0xFFFFFFF0u;
+    constexpr uint32_t kSeg = 4 * S, kRing = 32 * S;             // words per group
     __shared__ uint32_t pair[256];
+    __shared__ __attribute__((aligned(16))) uint32_t stage[WRITE ? kWavesPerGroup * kGroups * kRing : 4];
+    __shared__ __attribute__((aligned(16))) uint32_t pairs_of_rows[WRITE ? kWavesPerGroup * 256 : 4];   // 4*S words per group
     const WorkItem it = work[blockIdx.x];
     const TensorDev *dp = descs + it.tensor;
     pair[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + 512 + threadIdx.x];
@@ -222,6 +234,8 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
     const char *pair_lut = reinterpret_cast<const char *>(pair);
     const uint32_t two = 2;
     const uint32_t rows = cb / (16 * S);
+    uint32_t *const ring = stage + (WRITE ? (wave * kGroups + grp) * kRing : 0);
+    uint32_t *const two_rows = pairs_of_rows + (WRITE ? wave * 256 + grp * 4 * S : 0);
 
     for (uint32_t pass = 0; pass * kWavesPerGroup * kGroups < slots_per_group; pass++) {
         const uint32_t local = (pass * kWavesPerGroup + wave) * kGroups + grp;
@@ -242,10 +256,30 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
         int32_t k = 0;              // unread bits the decoder would hold at this point
         uint32_t pend = 0, p0 = 0, p1 = 0;
         uint32_t wpos = 0, q = 0;
-        for (uint32_t row = 0; row < rows; row++) {
+        uint32_t flushed = 0;       // words of the stream that have left the ring
+        // whole segments that are complete leave the ring, 16 bytes per lane
+        auto flush_segments = [&]() {
+#pragma unroll 1
+            for (int guard = 0; guard < 8; guard++) {
+                const bool owes = pend > 0 && p0 < flushed + kSeg;
+                const bool ready = wpos >= flushed + kSeg && (__ballot(owes) & gmask) == 0;
+                if (!__any(ready)) break;
+                if (ready) {
+                    const u32x4 w = *reinterpret_cast<const u32x4 *>(ring + ((flushed + 4 * s) & (kRing - 1)));
+                    const uint32_t to = (alive && (flushed + 4 * s) * 4 + 16 <= e_len) ? e_off + (flushed + 4 * s) * 4 : kNowhere;
+                    __builtin_amdgcn_raw_buffer_store_b128(w, ps, (int)to, 0, 0);
+                    flushed += kSeg;
+                }
+            }
+        };
+        // the source (and the base of a delta) is fetched two rows ahead, into two register sets used in turn
+        auto fetch = [&](uint32_t row, u32x4 &x, u32x4 &y) {
+            row = row < rows ? row : rows - 1;
             const uint32_t at = alive ? in_off + (row * S + s) * 16 : kNowhere;
-            u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(src, (int)at, 0, 0);
-            v ^= __builtin_amdgcn_raw_buffer_load_b128(bas, (int)at, 0, 0);      // empty resource without a base: reads as zero
+            x = __builtin_amdgcn_raw_buffer_load_b128(src, (int)at, 0, 0);
+            if (has_base) y = __builtin_amdgcn_raw_buffer_load_b128(bas, (int)at, 0, 0);
+        };
+        auto encode_row = [&](const u32x4 &v, uint32_t row) {
             if (WRITE) {
                 uint32_t m[2];
 #pragma unroll
@@ -254,16 +288,31 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
                     const uint32_t hi = pack_nibbles_of_bytes(((v[2 * h + 1] >> 4) & 0x08080808u) | (v[2 * h + 1] & 0x07070707u));
                     m[h] = lo | (hi << 16);
                 }
-                // raw: the packed nibbles as they are; flat code: every symbol most significant bit first, one
-                // word per 8 symbols, rows of S words
-                const uint32_t raw_at = (alive && sm_raw) ? m_off + (row * S + s) * 8 : kNowhere;
-                __builtin_amdgcn_raw_buffer_store_b64(u32x2{m[0], m[1]}, ps, (int)raw_at, 0, 0);
+                if (sm_raw) {
+                    // the packed nibbles as they are: 8 bytes per lane
+                    __builtin_amdgcn_raw_buffer_store_b64(u32x2{m[0], m[1]}, ps, (int)(alive ? m_off + (row * S + s) * 8 : kNowhere), 0, 0);
+                } else {
+                    // flat code: every symbol most significant bit first, one word per 8 symbols, rows of S words.
+                    // Two source rows make 4*S words of the stream: they are exchanged through LDS so that every
+                    // lane stores 16 contiguous bytes; an odd last row is stored word by word.
+                    uint32_t w[2];
 #pragma unroll
-                for (int h = 0; h < 2; h++) {
-                    uint32_t w = ((m[h] >> 1) & 0x55555555u) | ((m[h] & 0x55555555u) << 1);
-                    w = ((w >> 2) & 0x33333333u) | ((w & 0x33333333u) << 2);
-                    const uint32_t flat_at = (alive && !sm_raw) ? m_off + ((row * 2 + h) * S + s) * 4 : kNowhere;
-                    __builtin_amdgcn_raw_buffer_store_b32(w, ps, (int)flat_at, 0, 0);
+                    for (int h = 0; h < 2; h++) {
+                        w[h] = ((m[h] >> 1) & 0x55555555u) | ((m[h] & 0x55555555u) << 1);
+                        w[h] = ((w[h] >> 2) & 0x33333333u) | ((w[h] & 0x33333333u) << 2);
+                    }
+                    if ((row & 1) == 0 && row + 1 == rows) {
+#pragma unroll
+                        for (int h = 0; h < 2; h++)
+                            __builtin_amdgcn_raw_buffer_store_b32(w[h], ps, (int)(alive ? m_off + ((row * 2 + h) * S + s) * 4 : kNowhere), 0, 0);
+                    } else {
+                        two_rows[((row & 1) * 2 + 0) * S + s] = w[0];
+                        two_rows[((row & 1) * 2 + 1) * S + s] = w[1];
+                        if (row & 1) {
+                            const u32x4 t = *reinterpret_cast<const u32x4 *>(two_rows + 4 * s);
+                            __builtin_amdgcn_raw_buffer_store_b128(t, ps, (int)(alive ? m_off + ((row - 1) * 2 * S + 4 * s) * 4 : kNowhere), 0, 0);
+                        }
+                    }
                 }
             }
 #pragma unroll
@@ -285,28 +334,46 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
                     acc |= (uint64_t)code << nacc;
                     nacc += len;
                     const bool full = nacc >= 32;
-                    const uint32_t to = (alive && full && p0 * 4 < e_len) ? e_off + p0 * 4 : kNowhere;
-                    __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, ps, (int)to, 0, 0);
+                    if (full) ring[p0 & (kRing - 1)] = (uint32_t)acc;
                     acc = full ? acc >> 32 : acc;
                     nacc = full ? nacc - 32 : nacc;
                     p0 = full ? p1 : p0;
                     pend -= full ? 1u : 0u;
                 }
             }
+            if (WRITE) flush_segments();
+        };
+        u32x4 xa, ya = {0, 0, 0, 0}, xb, yb = {0, 0, 0, 0};
+        fetch(0, xa, ya);
+        fetch(1, xb, yb);
+        uint32_t row = 0;
+        for (; row + 1 < rows; row += 2) {
+            const u32x4 va = xa ^ ya;
+            fetch(row + 2, xa, ya);
+            encode_row(va, row);
+            const u32x4 vb = xb ^ yb;
+            fetch(row + 3, xb, yb);
+            encode_row(vb, row + 1);
         }
+        if (row < rows) encode_row(xa ^ ya, row);
         if (WRITE) {
-            // the words still owed to the decoder (a partial word and look-ahead words), then zero padding
+            // the words still owed to the decoder (a partial word and look-ahead words) and the zero padding of
+            // the last 16-byte unit go into the ring too; then everything left in it leaves in 16-byte pieces
 #pragma unroll
             for (int t = 0; t < 2; t++) {
-                const uint32_t to = (alive && pend > 0 && p0 * 4 < e_len) ? e_off + p0 * 4 : kNowhere;
-                __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, ps, (int)to, 0, 0);
+                if (pend > 0) ring[p0 & (kRing - 1)] = (uint32_t)acc;
                 acc = pend > 0 ? acc >> 32 : acc;
                 p0 = pend > 0 ? p1 : p0;
                 pend -= pend > 0 ? 1u : 0u;
             }
-            const uint32_t padw = wpos + s;
-            const uint32_t to = (alive && s < ((4 - (wpos & 3)) & 3) && padw * 4 < e_len) ? e_off + padw * 4 : kNowhere;
-            __builtin_amdgcn_raw_buffer_store_b32(0u, ps, (int)to, 0, 0);
+            if (s < ((4 - (wpos & 3)) & 3)) ring[(wpos + s) & (kRing - 1)] = 0;
+            const uint32_t end = alive ? (wpos + 3) & ~3u : 0u;  // words of the stream with its padding
+#pragma unroll 1
+            for (uint32_t at = flushed + 4 * s; __any(at < end); at += kSeg) {
+                const u32x4 w = *reinterpret_cast<const u32x4 *>(ring + (at & (kRing - 1)));
+                const uint32_t to = (alive && at < end && at * 4 + 16 <= e_len) ? e_off + at * 4 : kNowhere;
+                __builtin_amdgcn_raw_buffer_store_b128(w, ps, (int)to, 0, 0);
+            }
         } else {
             // words of the chunk's exponent stream = sum over the lanes of the group
 #pragma unroll
