@@ -142,20 +142,25 @@ struct EncField {
     uint32_t nacc;
     int32_t k;             // unread bits the decoder would hold at this point
     uint32_t pend, p0, p1; // requested but unwritten words and their positions in the stream
-    uint32_t wpos;         // words of the stream handed out so far (same in all lanes of the group)
+    uint32_t wpos;         // writing: words of the stream handed out so far (same in all lanes of the group);
+                           // size pass: words this lane alone has asked for (summed over the group at the end)
 };
 
 template <bool WRITE>
 __device__ __forceinline__ void enc_request(EncField &F, bool active, const Lanes &L)
 {
     const bool req = active && F.k <= 32;
-    const uint64_t bm = __ballot(req) & L.gmask;
-    if (req) {
-        const uint32_t pos = F.wpos + prefix_count(bm);
-        if (F.pend == 0) F.p0 = pos; else F.p1 = pos;
-        F.pend++;
-        F.k += 32;
+    if (!WRITE) {                                   // positions are not needed to count words
+        F.wpos += req ? 1u : 0u;
+        F.k += req ? 32 : 0;
+        return;
     }
+    const uint64_t bm = __ballot(req) & L.gmask;
+    const uint32_t pos = F.wpos + prefix_count(bm);
+    F.p0 = (req && F.pend == 0) ? pos : F.p0;
+    F.p1 = (req && F.pend != 0) ? pos : F.p1;
+    F.pend += req ? 1u : 0u;
+    F.k += req ? 32 : 0;
     F.wpos += (uint32_t)__popcll(bm);
 }
 
@@ -174,19 +179,25 @@ __device__ __forceinline__ void enc_group(EncField &F, uint64_t P0, uint64_t P1,
 {
     constexpr int PER64 = 64 / SB;
     enc_request<WRITE>(F, FULL || (uint32_t)j0 < nsym, L);
+    // the R codes of a refill period take at most 32 bits together (that is what defines the period)
+    uint32_t code = 0, len = 0;
 #pragma unroll
     for (int j = 0; j < R; j++) {
         if (FULL || (uint32_t)(j0 + j) < nsym) {
             const int jj = j0 + j;
-            const uint64_t P = jj < PER64 ? P0 : P1;
-            const uint32_t v = (uint32_t)(P >> ((jj % PER64) * SB)) & ((1u << SB) - 1);
+            const uint32_t half = (uint32_t)((jj < PER64 ? P0 : P1) >> (((jj % PER64) * SB) & 32));
+            const uint32_t v = (half >> (((jj % PER64) * SB) & 31)) & ((1u << SB) - 1);
             const uint32_t e = enc[v];
-            F.acc |= (uint64_t)(e & 0xFFFFu) << F.nacc;
-            F.nacc += e >> 16;
-            F.k -= (int32_t)(e >> 16);
+            if (WRITE) code |= (e & 0xFFFFu) << len;
+            len += e >> 16;
         }
     }
-    if (F.nacc >= 32) { enc_flush_word<WRITE>(F, stream); F.nacc -= 32; }
+    F.k -= (int32_t)len;
+    if (WRITE) {
+        F.acc |= (uint64_t)code << F.nacc;
+        F.nacc += len;
+        if (F.nacc >= 32) { enc_flush_word<WRITE>(F, stream); F.nacc -= 32; }
+    }
 }
 
 template <bool WRITE, int SB, int G, int R, bool FULL>
@@ -220,17 +231,19 @@ __device__ __forceinline__ void enc_flat_run(EncField &F, uint64_t P, uint8_t *s
         uint32_t *w = reinterpret_cast<uint32_t *>(stream) + F.wpos + L.s;
         w[0] = reverse_in_groups<SB>((uint32_t)P);
         w[S] = reverse_in_groups<SB>((uint32_t)(P >> 32));
-    }
-    F.wpos += 2 * S;
+        F.wpos += 2 * S;
+    } else F.wpos += 2;
 }
 
 // write the words still owed to the decoder, then zero the tail of the last 16-byte unit
 template <bool WRITE>
 __device__ __forceinline__ uint32_t enc_finish(EncField &F, uint8_t *stream, const Lanes &L)
 {
-    if (F.pend > 0) enc_flush_word<WRITE>(F, stream);
-    if (F.pend > 0) enc_flush_word<WRITE>(F, stream);
-    const uint32_t words = F.wpos;
+    if (WRITE && F.pend > 0) enc_flush_word<WRITE>(F, stream);
+    if (WRITE && F.pend > 0) enc_flush_word<WRITE>(F, stream);
+    uint32_t words = F.wpos;
+    if (!WRITE)                                     // per-lane counts: sum over the lanes of the group
+        for (uint32_t o = 1; o < 64; o <<= 1) { const uint32_t y = __shfl_xor(words, o, 64); words += o < (uint32_t)__popcll(L.gmask) ? y : 0u; }
     if (WRITE && L.s == 0)
         for (uint32_t w = words; w & 3; w++) reinterpret_cast<uint32_t *>(stream)[w] = 0;
     return (words + 3) / 4;
@@ -300,7 +313,7 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
             reinterpret_cast<uint64_t *>(stream[1])[run] = P1;
             if ((run & 1) == 0 && done + F_::EPR >= n) reinterpret_cast<uint64_t *>(stream[1])[run + 1] = 0;
         }
-    }
+        }
     {
         uint32_t u0 = 0, u1 = 0;
         const uint32_t nsyms = (n + F_::GRP - 1) / F_::GRP;
