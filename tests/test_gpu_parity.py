@@ -581,3 +581,58 @@ def test_fp8_page_encoder():
     bt.compress(code=code)
     for i, t in enumerate((k, v)):
         assert np.array_equal(bt.container(i).cpu().numpy(), o.compress_with_code(t.reshape(-1).numpy(), t.numel(), po, ln, md))
+
+
+def _random_source(rng, fmt, n):
+    """Element bytes (and scale bytes) with a randomly chosen amount of structure."""
+    nbytes = (n * zc.elem_bits(fmt) + 7) // 8
+    kind = int(rng.integers(0, 5))
+    if kind == 0:      # uniform bytes: nothing compresses
+        b = rng.integers(0, 256, nbytes, dtype=np.uint8)
+    elif kind == 1:    # few distinct bytes with skewed frequencies: short and long codes
+        vals = rng.integers(0, 256, int(rng.integers(2, 9)), dtype=np.uint8)
+        pr = rng.dirichlet(np.full(len(vals), 0.3))
+        b = rng.choice(vals, nbytes, p=pr).astype(np.uint8)
+    elif kind == 2:    # one value: constant fields
+        b = np.full(nbytes, int(rng.integers(0, 256)), np.uint8)
+    elif kind == 3:    # geometric byte values: deep code trees (the length limit binds)
+        b = np.minimum(rng.geometric(0.5, nbytes) - 1, 255).astype(np.uint8) * np.uint8(rng.integers(1, 9))
+    else:              # the workload generators
+        blk = zc.scale_block(fmt) or 1
+        t, _ = make_input(fmt, (max(n, 1) + blk - 1) // blk * blk, int(rng.integers(0, 1000)))
+        b = t.numpy().reshape(-1).view(np.uint8)[:nbytes].copy()
+        assert b.size == nbytes
+    sc = None
+    if zc.scale_block(fmt):
+        ns = n // zc.scale_block(fmt)
+        sc = (rng.integers(0, 256, ns, dtype=np.uint8) if rng.integers(0, 2) else np.full(ns, 120, np.uint8) + rng.integers(0, 3, ns, dtype=np.uint8))
+    return torch.from_numpy(b), None if sc is None else torch.from_numpy(sc)
+
+
+def test_random_parameter_sweep():
+    # seeded sweep over formats, lanes, chunk sizes, lengths, policies, length limits and data shapes
+    rng = np.random.default_rng(20250827)
+    fmts = (zc.FMT_BF16, zc.FMT_FP8_E4M3, zc.FMT_FP4_E2M1_MX, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP4_E2M1_MX_BYTES, zc.FMT_FP4_E2M1_NV)
+    for case in range(160):
+        fmt = fmts[case % len(fmts)]
+        S = int(2 ** rng.integers(0, 7))
+        unit = 256 if zc.scale_block(fmt) else 16
+        cb = unit * int(rng.integers(1, 40)) if rng.integers(0, 3) else int(2 ** rng.integers(10, 16))
+        cb = max(cb // unit * unit, unit)
+        E = cb * 8 // zc.elem_bits(fmt)
+        n = int(rng.integers(0, 6 * E + 2)) if rng.integers(0, 4) else int(rng.integers(1, 4)) * E
+        blk = zc.scale_block(fmt)
+        if blk:
+            n = n // blk * blk
+        policy = int(rng.integers(0, 2))
+        sb8 = fmt in (zc.FMT_BF16, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP4_E2M1_MX_BYTES)
+        lo = 8 if sb8 else (4 if fmt == zc.FMT_FP8_E4M3 else 2)
+        L = (int(rng.integers(lo, 17)) if rng.integers(0, 2) else 0, int(rng.integers(lo, 17)) if rng.integers(0, 2) else 0,
+             int(rng.integers(8, 17)) if rng.integers(0, 2) else 0)
+        src, sc = _random_source(rng, fmt, n)
+        base = None
+        if rng.integers(0, 4) == 0 and n:
+            base = torch.from_numpy(rng.integers(0, 256, src.numel(), dtype=np.uint8) & np.uint8(rng.choice([0x01, 0x81, 0xFF])))
+        if src.numel() == 0:
+            src = torch.zeros(0, dtype=torch.uint8)
+        check_case(fmt, n, cb, S, policy, L, data=(src, sc), base=base, tag="sweep-%d" % case)
