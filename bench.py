@@ -99,14 +99,19 @@ def other_workloads(torch, wl, zc, dev):
         torch.cuda.empty_cache()
 
     # config 2 again with byte-grouped symbols (two exponents per symbol; the flat sign+mantissa field raw)
-    names8 = [t for _, t in wl.fp8_weight_set(8, device=dev)]
-    run("c2_fp8_8_layers_byte_symbols", zc.FMT_FP8_E4M3_BYTES, names8, [t.numel() for t in names8], 262144, 64, policy=zc.POLICY_AUTO)
-    run("c2_fp8_8_layers_plain_symbols", zc.FMT_FP8_E4M3, names8, [t.numel() for t in names8], 262144, 64, policy=zc.POLICY_AUTO)
-    del names8
+    set2 = [t for _, t in wl.fp8_weight_set(32, device=dev)]
+    run("c2_fp8_byte_symbols", zc.FMT_FP8_E4M3_BYTES, set2, [t.numel() for t in set2], 262144, 64, policy=zc.POLICY_AUTO)
+    run("c2_fp8_byte_symbols_limit_11", zc.FMT_FP8_E4M3_BYTES, set2, [t.numel() for t in set2], 262144, 64, limit=(11, 11, 0), policy=zc.POLICY_AUTO)
+    run("c2_fp8_plain_symbols_auto", zc.FMT_FP8_E4M3, set2, [t.numel() for t in set2], 262144, 64, policy=zc.POLICY_AUTO)
+    del set2
     x = wl.bf16_weight(1 << 20, device=dev, seed=0)
     run("c1_bf16_1M", zc.FMT_BF16, [x], [1 << 20], 65536, 64, limit=(16, 16, 0))
     mats = [wl.mxfp4_weight(8192, 28672, device=dev, seed=300 + i) for i in range(3)]
     run("c3_mxfp4_70b_mlp", zc.FMT_FP4_E2M1_MX, [m[0] for m in mats], [8192 * 28672] * 3, 262144, 64, scales=[m[1] for m in mats])
+    # the same matrices 12 times over (36 matrices, 4.5 GB): enough chunks to fill the GPU, which 3 matrices do not
+    big = [m for _ in range(12) for m in mats]
+    run("c3_mxfp4_36_matrices", zc.FMT_FP4_E2M1_MX, [m[0] for m in big], [8192 * 28672] * 36, 262144, 64, scales=[m[1] for m in big])
+    del big
     run("c3_mxfp4_70b_mlp_byte_symbols", zc.FMT_FP4_E2M1_MX_BYTES, [m[0] for m in mats], [8192 * 28672] * 3, 262144, 64,
         scales=[m[1] for m in mats], policy=zc.POLICY_AUTO)
     del mats
