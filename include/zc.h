@@ -180,6 +180,14 @@ zc_status zc_compress_with_code(const void *d_src, uint64_t n_elems, const zc_pa
                                 void *d_ws, uint64_t ws_bytes, void *stream);
 zc_status zc_compress_batch_with_code(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params, const zc_info *code,
                                       void *d_ws, uint64_t ws_bytes, void *stream);
+/* zc_compress_batch_with_code without any wait on the stream, for compression on the critical path of a
+ * decoding step (Sec. 5.2): every kernel is queued and the call returns.  Every comp_capacity must be at
+ * least zc_compress_bound(n_elems) (else ZC_ERR_BUFFER_TOO_SMALL, nothing queued).  out_bytes and
+ * info.total_bytes are left 0: once the stream has reached this point the container's header holds its
+ * size, and zc_read_info or the decompress entry points read it from there.  d_ws must stay untouched
+ * until then. */
+zc_status zc_compress_batch_with_code_async(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params, const zc_info *code,
+                                            void *d_ws, uint64_t ws_bytes, void *stream);
 int zc_code_stale(const zc_info *code, const zc_info *written, double slack);
 
 /* Read and validate a container's header and tables (blocking copy of at most 1 KiB from

@@ -288,7 +288,7 @@ uint32_t sub_slots_per_group(uint32_t streams, uint64_t slots);
 
 zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, void *d_ws, uint64_t ws_bytes, void *stream,
                        bool stats_only, std::vector<FieldCode> *codes_out, std::vector<ScanOut> *scan_out,
-                       const zc_info *dict = nullptr, bool train = false)
+                       const zc_info *dict = nullptr, bool train = false, bool no_sync = false)
 {
     Geometry g;
     zc_status st = check_params(params, &g);
@@ -435,9 +435,35 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 0, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
     LAUNCH_TRY(launch_sizes(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), cpi, d_enc, d_units, stream));
     LAUNCH_TRY(launch_scan(d_descs, T, (int)g.nf, d_units, (ScanOut *)(ws + w.scan), stream));
+    // chunked encode (a7).  When every destination can hold the worst case, the sizes need not be known on
+    // the host first: the encoder is queued right behind the scan and the sizes are read back meanwhile (or,
+    // for the call that does not synchronise, not at all: they are in the containers' headers).
+    auto launch_encoders = [&]() -> zc_status {
+        if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, stream));
+        else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), cpi, d_enc, stream));
+        return ZC_OK;
+    };
+    bool roomy = !stats_only;
+    for (uint32_t t = 0; t < T && roomy; t++) roomy = tensors[t].comp_capacity >= zc_compress_bound(tensors[t].n_elems, params);
+    if (no_sync) {
+        if (!roomy) return ZC_ERR_BUFFER_TOO_SMALL;
+        for (uint32_t t = 0; t < T; t++) tensors[t].out_bytes = 0;
+        return launch_encoders();
+    }
     std::vector<ScanOut> scan(T);
     HIP_TRY(hipMemcpyAsync(scan.data(), ws + w.scan, T * sizeof(ScanOut), hipMemcpyDeviceToHost, hs));
-    HIP_TRY(hipStreamSynchronize(hs));
+    if (roomy) {
+        // wait for the copy only, not for the encoder queued behind it
+        hipEvent_t copied;
+        HIP_TRY(hipEventCreateWithFlags(&copied, hipEventDisableTiming));
+        const hipError_t e1 = hipEventRecord(copied, hs);
+        st = e1 == hipSuccess ? launch_encoders() : ZC_ERR_DEVICE;
+        const hipError_t e2 = e1 == hipSuccess ? hipEventSynchronize(copied) : e1;
+        (void)hipEventDestroy(copied);
+        if (st) return st;
+        if (e2 != hipSuccess) return ZC_ERR_DEVICE;
+    } else HIP_TRY(hipStreamSynchronize(hs));
     for (uint32_t t = 0; t < T; t++) {
         const uint64_t total = descs[t].payload_off + 16ull * scan[t].total_units;
         tensors[t].out_bytes = total;
@@ -445,13 +471,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         if (!stats_only && total > tensors[t].comp_capacity) return ZC_ERR_BUFFER_TOO_SMALL;
     }
     if (scan_out) *scan_out = scan;
-    if (stats_only) return ZC_OK;
-
-    // chunked encode (a7)
-    if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, stream));
-    else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
-    LAUNCH_TRY(launch_encode(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), cpi, d_enc, stream));
-    return ZC_OK;
+    if (stats_only || roomy) return ZC_OK;
+    return launch_encoders();
 }
 
 // Can the specialised FP8 kernel decode this container's full chunks?
@@ -728,6 +749,13 @@ zc_status zc_compress_batch_with_code(zc_tensor *tensors, uint32_t n_tensors, co
 {
     if (!code) return ZC_ERR_INVALID_ARG;
     return run_compress(tensors, n_tensors, params, d_ws, ws_bytes, stream, false, nullptr, nullptr, code, false);
+}
+
+zc_status zc_compress_batch_with_code_async(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params, const zc_info *code,
+                                            void *d_ws, uint64_t ws_bytes, void *stream)
+{
+    if (!code) return ZC_ERR_INVALID_ARG;
+    return run_compress(tensors, n_tensors, params, d_ws, ws_bytes, stream, false, nullptr, nullptr, code, false, true);
 }
 
 zc_status zc_compress_with_code(const void *d_src, uint64_t n_elems, const zc_params *params, const zc_info *code,

@@ -636,3 +636,32 @@ def test_random_parameter_sweep():
         if src.numel() == 0:
             src = torch.zeros(0, dtype=torch.uint8)
         check_case(fmt, n, cb, S, policy, L, data=(src, sc), base=base, tag="sweep-%d" % case)
+
+
+def test_dictionary_compress_without_sync():
+    # the queue-only call leaves the same containers as the synchronising one; sizes come from the headers
+    k, v = wl.fp8_kv_pair(batch=1, heads=2, tokens=4096, seed=81)
+    srcs = [k.reshape(-1), v.reshape(-1), wl.fp8_weight(5 * 2048 + 77, seed=82)]
+    p, po = zc.params(zc.FMT_FP8_E4M3, 2048, streams=8), o.params(o.FP8_E4M3, 2048, streams=8)
+    code = zc.train_code(dev(srcs[0]), srcs[0].numel(), p)
+    ln, md = o.train_code(srcs[0].numpy(), srcs[0].numel(), po)
+    bt = zc.Batch([dev(s) for s in srcs], [s.numel() for s in srcs], p)
+    for rep in range(2):                                  # twice: the workspace is reused
+        bt.compress_async(code)
+        sizes = bt.refresh_info()
+        for i, s in enumerate(srcs):
+            want = o.compress_with_code(s.numpy(), s.numel(), po, ln, md)
+            assert sizes[i] == len(want) and np.array_equal(bt.container(i).cpu().numpy(), want)
+    outs = bt.decompress()
+    torch.cuda.synchronize()
+    for out, s in zip(outs, srcs):
+        assert torch.equal(out.cpu()[:s.numel()], s)
+    # a destination below the worst-case bound is refused before anything is queued
+    small = zc.Tensor()
+    small.d_src, small.n_elems = dev(srcs[2]).data_ptr(), srcs[2].numel()
+    buf = torch.empty(zc.compress_bound(srcs[2].numel(), p) - 16, dtype=torch.uint8, device=DEV)
+    small.d_comp, small.comp_capacity = buf.data_ptr(), buf.numel()
+    ws = torch.empty(zc.workspace_bytes([srcs[2].numel()], p), dtype=torch.uint8, device=DEV)
+    arr = (zc.Tensor * 1)(small)
+    st = zc.lib().zc_compress_batch_with_code_async(arr, 1, p, code, zc._ptr(ws), ws.numel(), zc._stream())
+    assert st == zc.ERR_BUFFER_TOO_SMALL
