@@ -130,6 +130,28 @@ def other_workloads(torch, wl, zc, dev):
     n_pages = kv[0].numel() // 2048
     ids = [wl.page_sample(n_pages, 0.25, device=dev, seed=600 + i) for i in range(len(kv))]
     run("c5_fp8_kv_pages", zc.FMT_FP8_E4M3, kv, [t.numel() for t in kv], 2048, 8, ids=ids, dictionary=True)
+    # one decoding step's worth of new pages: 64 tensors x 32 pages of 2 KiB, dictionary known: latency, not throughput
+    step_pages = [t[:32 * 2048].contiguous() for t in kv]
+    p5 = zc.params(zc.FMT_FP8_E4M3, 2048, (0, 0, 0), 8)
+    code_k = zc.train_code(kv[0], kv[0].numel(), p5)
+    sb = zc.Batch(step_pages, [32 * 2048] * len(step_pages), p5)
+    sb.compress(code=code_k)
+    t_sync = _time_ms(torch, lambda: sb.compress(code=code_k))
+    t_async = _time_ms(torch, lambda: sb.compress_async(code_k))
+    torch.cuda.synchronize()
+    h0 = time.perf_counter()
+    for _ in range(20):
+        sb.compress_async(code_k)
+    host_us = (time.perf_counter() - h0) / 20 * 1e6
+    torch.cuda.synchronize()
+    sb.refresh_info()
+    sb.decompress()
+    torch.cuda.synchronize()
+    ok_step = all(torch.equal(o[:s.numel()], s) for o, s in zip(sb.out, step_pages))
+    out["c5_one_step_of_new_pages"] = {"tensors": len(step_pages), "pages": 32 * len(step_pages), "bytes": 32 * 2048 * len(step_pages),
+                                       "compress_with_dictionary_ms": t_sync, "queued_without_wait_gpu_ms": t_async,
+                                       "queued_without_wait_host_us_per_call": host_us, "round_trip_bit_exact": bool(ok_step)}
+    del sb, step_pages
     del kv
     # the same cache shape in BF16: 16-token pages of 4 KiB, 16 layers
     kv = []

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <thread>
 #include <vector>
 
@@ -80,7 +81,7 @@ uint64_t get64(const uint8_t *p) { uint64_t v; std::memcpy(&v, p, 8); return v; 
 
 // ---- workspace carving ------------------------------------------------------
 struct Workspace {
-    uint64_t descs, hist_work, scale_work, chunk_work, fast_work, hist, enc, units, scan, blobs, total;
+    uint64_t descs, hist_work, scale_work, chunk_work, fast_work, hist, enc, units, scan, blobs, total, host_end;
     uint32_t n_hist_work, n_scale_work, n_chunk_work;
     uint64_t n_units;
 };
@@ -104,16 +105,18 @@ zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T,
     }
     if (hw > 0x7FFFFFFFull || cw > 0x7FFFFFFFull || units > 0xFFFFFFFFull) return ZC_ERR_INVALID_ARG;
     uint64_t off = 0;
+    // what the host writes comes first and is contiguous, so that it goes up in one copy
     w->descs = off; off = align256(off + (uint64_t)T * sizeof(TensorDev));
     w->hist_work = off; off = align256(off + hw * sizeof(WorkItem));
     w->scale_work = off; off = align256(off + sw * sizeof(WorkItem));
     w->chunk_work = off; off = align256(off + cw * sizeof(WorkItem));
     w->fast_work = off; off = align256(off + cw * sizeof(WorkItem));
-    w->hist = off; off = align256(off + (uint64_t)T * 3 * 256 * 8);
     w->enc = off; off = align256(off + (uint64_t)T * 768 * 4);
+    w->blobs = off; off = align256(off + (uint64_t)T * kBlobBytes);
+    w->host_end = off;
+    w->hist = off; off = align256(off + (uint64_t)T * 3 * 256 * 8);
     w->units = off; off = align256(off + units * 4);
     w->scan = off; off = align256(off + (uint64_t)T * sizeof(ScanOut));
-    w->blobs = off; off = align256(off + (uint64_t)T * kBlobBytes);
     w->total = off;
     w->n_hist_work = (uint32_t)hw; w->n_scale_work = (uint32_t)sw; w->n_chunk_work = (uint32_t)cw; w->n_units = units;
     return ZC_OK;
@@ -121,6 +124,47 @@ zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T,
 
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) return ZC_ERR_DEVICE; } while (0)
 #define LAUNCH_TRY(expr) do { if ((expr) != 0) return ZC_ERR_DEVICE; } while (0)
+
+// ---- pinned staging for what the host sends to the workspace ------------------
+// One page-locked buffer per process: the pieces of an upload are packed into it at their workspace
+// offsets and leave in a single asynchronous copy that needs no wait (the buffer outlives the call).
+// The next user waits for the previous copy's event before it overwrites the buffer.
+struct Piece { uint64_t off; const void *src; uint64_t bytes; };
+
+class HostStage {
+public:
+    // copies pieces (all inside [lo, hi) of the workspace) to d_ws + lo .. d_ws + hi on `hs`
+    zc_status upload(uint8_t *d_ws, uint64_t lo, uint64_t hi, const Piece *pieces, int n, hipStream_t hs)
+    {
+        if (hi <= lo) return ZC_OK;
+        std::lock_guard<std::mutex> lock(m_);
+        if (pending_ && hipEventSynchronize(ev_) != hipSuccess) return ZC_ERR_DEVICE;
+        pending_ = false;
+        const uint64_t need = hi - lo;
+        if (need > cap_) {
+            if (buf_) (void)hipHostFree(buf_);
+            buf_ = nullptr; cap_ = 0;
+            const uint64_t want = need + need / 2 + 4096;
+            if (hipHostMalloc((void **)&buf_, want, hipHostMallocDefault) != hipSuccess) return ZC_ERR_DEVICE;
+            cap_ = want;
+        }
+        if (!ev_ && hipEventCreateWithFlags(&ev_, hipEventDisableTiming) != hipSuccess) return ZC_ERR_DEVICE;
+        for (int i = 0; i < n; i++)
+            if (pieces[i].bytes) std::memcpy(buf_ + (pieces[i].off - lo), pieces[i].src, pieces[i].bytes);
+        HIP_TRY(hipMemcpyAsync(d_ws + lo, buf_, need, hipMemcpyHostToDevice, hs));
+        HIP_TRY(hipEventRecord(ev_, hs));
+        pending_ = true;
+        return ZC_OK;
+    }
+private:
+    std::mutex m_;
+    uint8_t *buf_ = nullptr;
+    uint64_t cap_ = 0;
+    hipEvent_t ev_ = nullptr;
+    bool pending_ = false;
+};
+
+HostStage &host_stage() { static HostStage s; return s; }
 
 // ---- code construction from the device histograms ---------------------------
 struct FieldCode {
@@ -341,14 +385,15 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     }
     TensorDev *d_descs = (TensorDev *)(ws + w.descs);
     uint64_t *d_hist = (uint64_t *)(ws + w.hist);
-    HIP_TRY(hipMemcpyAsync(d_descs, descs.data(), T * sizeof(TensorDev), hipMemcpyHostToDevice, hs));
-    if (!hist_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
-    if (!scale_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
-    HIP_TRY(hipMemsetAsync(d_hist, 0, (uint64_t)T * 3 * 256 * 8, hs));
-
     // field split + histogram (a1-a3); not needed when the code comes from a dictionary
-    std::vector<uint64_t> hist((size_t)T * 768);
+    std::vector<uint64_t> hist(dict ? 0 : (size_t)T * 768);
     if (!dict) {
+        const Piece first[3] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
+                                {w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem)},
+                                {w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem)}};
+        st = host_stage().upload(ws, w.descs, w.chunk_work, first, 3, hs);
+        if (st) return st;
+        HIP_TRY(hipMemsetAsync(d_hist, 0, (uint64_t)T * 3 * 256 * 8, hs));
         LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
         if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), (int)scale_block(g.fmt), d_hist, stream));
         HIP_TRY(hipMemcpyAsync(hist.data(), d_hist, hist.size() * 8, hipMemcpyDeviceToHost, hs));
@@ -419,14 +464,20 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         for (uint64_t c = n_full; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
     }
     if (codes_out) *codes_out = codes;
-    HIP_TRY(hipMemcpyAsync(d_descs, descs.data(), T * sizeof(TensorDev), hipMemcpyHostToDevice, hs));
-    HIP_TRY(hipMemcpyAsync(ws + w.enc, enc.data(), enc.size() * 4, hipMemcpyHostToDevice, hs));
-    if (!fast_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.fast_work, fast_work.data(), fast_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
-    if (!slow_work.empty()) HIP_TRY(hipMemcpyAsync(ws + w.chunk_work, slow_work.data(), slow_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
-    if (!stats_only) {
-        HIP_TRY(hipMemcpyAsync(ws + w.blobs, blobs.data(), blobs.size(), hipMemcpyHostToDevice, hs));
-        LAUNCH_TRY(launch_write_headers(d_descs, T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
+    {
+        // everything the kernels from here on read from the host, in one copy (the histogram work lists ride
+        // along so that the copied range has no holes)
+        const Piece all[7] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
+                              {w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem)},
+                              {w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem)},
+                              {w.chunk_work, slow_work.data(), slow_work.size() * sizeof(WorkItem)},
+                              {w.fast_work, fast_work.data(), fast_work.size() * sizeof(WorkItem)},
+                              {w.enc, enc.data(), enc.size() * 4},
+                              {w.blobs, blobs.data(), stats_only ? 0 : blobs.size()}};
+        st = host_stage().upload(ws, w.descs, w.host_end, all, 7, hs);
+        if (st) return st;
     }
+    if (!stats_only) LAUNCH_TRY(launch_write_headers(d_descs, T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
 
     // stream sizes (a5) and their exclusive scan into the chunk index (a6)
     const uint32_t *d_enc = (const uint32_t *)(ws + w.enc);
