@@ -665,3 +665,38 @@ def test_dictionary_compress_without_sync():
     arr = (zc.Tensor * 1)(small)
     st = zc.lib().zc_compress_batch_with_code_async(arr, 1, p, code, zc._ptr(ws), ws.numel(), zc._stream())
     assert st == zc.ERR_BUFFER_TOO_SMALL
+
+
+def test_tensor_beyond_4_gib():
+    # One FP8 tensor of 4.5 GiB + a ragged tail: every byte offset past 2^32 must be computed in 64 bits.
+    # The round trip is checked whole on the GPU; sampled chunks (first, the ones on both sides of the
+    # 4 GiB line, the last whole one and the short tail) are encoded by the oracle from the tensor's own
+    # code lengths and compared with the streams the library wrote.
+    cb = 262144
+    n = 18432 * cb + 1000
+    parts = [wl.fp8_weight(2304 * cb, device=DEV, seed=3000 + i) for i in range(8)]
+    src = torch.cat(parts + [wl.fp8_weight(1000, device=DEV, seed=3010)])
+    del parts
+    assert src.numel() == n and n > (1 << 32)
+    p = zc.params(zc.FMT_FP8_E4M3, cb, streams=64)
+    comp, info = zc.compress(src, n, p)
+    print("beyond-4GiB compressed", info.total_bytes, flush=True)
+    out, _ = zc.decompress(comp, info)
+    torch.cuda.synchronize()
+    assert torch.equal(out[:n], src)
+    del out
+    nc = info.n_chunks
+    assert nc == 18433
+    head = comp[:info.payload_offset].cpu().numpy()
+    lens = [head[info.table_offset[f]:info.table_offset[f] + 16] for f in range(2)]
+    index = [np.frombuffer(head[info.index_offset[f]:info.index_offset[f] + 4 * (nc + 1)].tobytes(), "<u4").astype(np.int64) for f in range(2)]
+    assert info.mode[0] == zc.MODE_HUFF and info.mode[1] == zc.MODE_HUFF
+    for c in (0, 16383, 16384, 18431, 18432):
+        lo, hi = c * cb, min((c + 1) * cb, n)
+        chunk = src[lo:hi].cpu().numpy()
+        e, sm = o.split(o.FP8_E4M3, chunk, hi - lo)
+        for f, syms in ((0, e), (1, sm)):
+            a, b = int(info.payload_offset + 16 * index[f][c]), int(info.payload_offset + 16 * index[f][c + 1])
+            got = comp[a:b].cpu().numpy()
+            want = o.encode_stream(syms, lens[f], 16, 64)
+            assert np.array_equal(got, want), (c, f)
