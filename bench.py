@@ -104,6 +104,9 @@ def other_workloads(torch, wl, zc, dev):
     run("c2_fp8_byte_symbols_limit_11", zc.FMT_FP8_E4M3_BYTES, set2, [t.numel() for t in set2], 262144, 64, limit=(11, 11, 0), policy=zc.POLICY_AUTO)
     run("c2_fp8_plain_symbols_auto", zc.FMT_FP8_E4M3, set2, [t.numel() for t in set2], 262144, 64, policy=zc.POLICY_AUTO)
     del set2
+    set2 = [t for _, t in wl.fp8_weight_set(32, device=dev, e5m2=True)]
+    run("c2_shapes_in_fp8_e5m2", zc.FMT_FP8_E5M2, set2, [t.numel() for t in set2], 262144, 64)
+    del set2
     x = wl.bf16_weight(1 << 20, device=dev, seed=0)
     run("c1_bf16_1M", zc.FMT_BF16, [x], [1 << 20], 65536, 64, limit=(16, 16, 0))
     mats = [wl.mxfp4_weight(8192, 28672, device=dev, seed=300 + i) for i in range(3)]

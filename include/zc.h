@@ -58,7 +58,12 @@ typedef enum {
     ZC_FMT_FP4_E2M1_MX_BYTES = 5,
     /* NVFP4 (Sec. 3.4): the E2M1 elements of format 3 with one FP8 (E4M3) scale byte per 16 elements
      * (d_scales holds n_elems / 16 bytes); fields as format 3, the scale bytes coded as 8-bit symbols. */
-    ZC_FMT_FP4_E2M1_NV = 6
+    ZC_FMT_FP4_E2M1_NV = 6,
+    /* The other FP8 variant of Sec. 3.2, E5M2 (s eeeee mm): a 5-bit exponent and a 3-bit sign+mantissa
+     * value per element, each held in an 8-bit symbol (alphabets of 256 of which 32 and 8 can occur), so
+     * that a lane's run of 16 elements is 16 symbols in both fields.  zc_field_stats.ratio_payload of
+     * this format is relative to those 8 bits. */
+    ZC_FMT_FP8_E5M2 = 7
 } zc_format;
 
 typedef enum {

@@ -49,7 +49,11 @@
  * the packed field array = 2 (FP8) or 4 (FP4) consecutive field values, first value in the low bits. */
 /* Format 6 is NVFP4 (Sec. 3.4): the E2M1 elements of format 3 with one FP8 (E4M3) scale byte per 16
  * elements instead of one E8M0 byte per 32; the scale bytes are coded as 8-bit symbols like the E8M0 ones. */
-enum { ZCO_BF16 = 1, ZCO_FP8_E4M3 = 2, ZCO_FP4_E2M1_MX = 3, ZCO_FP8_E4M3_BYTES = 4, ZCO_FP4_E2M1_MX_BYTES = 5, ZCO_FP4_E2M1_NV = 6 };
+/* Format 7 is the other FP8 variant of Sec. 3.2, E5M2 (s eeeee mm): a 5-bit exponent and a 3-bit
+ * sign+mantissa value per element, each coded as a symbol of its own that is held in 8 bits (alphabets of
+ * 256 of which 32 and 8 can occur), so that a lane's run of 16 elements is 16 symbols in both fields. */
+enum { ZCO_BF16 = 1, ZCO_FP8_E4M3 = 2, ZCO_FP4_E2M1_MX = 3, ZCO_FP8_E4M3_BYTES = 4, ZCO_FP4_E2M1_MX_BYTES = 5, ZCO_FP4_E2M1_NV = 6,
+       ZCO_FP8_E5M2 = 7 };
 enum { ZCO_MODE_EMPTY = 0, ZCO_MODE_HUFF = 1, ZCO_MODE_RAW = 2, ZCO_MODE_CONST = 3 };
 enum { ZCO_POLICY_HUFF_ALL = 0, ZCO_POLICY_AUTO = 1 };
 enum { ZCO_OK = 0, ZCO_ERR_ARG = 1, ZCO_ERR_UNSUPPORTED = 2, ZCO_ERR_SMALL = 3, ZCO_ERR_CORRUPT = 4 };
@@ -83,13 +87,13 @@ static int group_of(int format)
 static int elem_bits(int format)
 {
     format = base_format(format);
-    return format == ZCO_BF16 ? 16 : format == ZCO_FP8_E4M3 ? 8 : format == ZCO_FP4_E2M1_MX ? 4 : 0;
+    return format == ZCO_BF16 ? 16 : (format == ZCO_FP8_E4M3 || format == ZCO_FP8_E5M2) ? 8 : format == ZCO_FP4_E2M1_MX ? 4 : 0;
 }
 
 int zco_num_fields(int format)
 {
     format = base_format(format);
-    return format == ZCO_FP4_E2M1_MX ? 3 : (format == ZCO_BF16 || format == ZCO_FP8_E4M3) ? 2 : 0;
+    return format == ZCO_FP4_E2M1_MX ? 3 : (format == ZCO_BF16 || format == ZCO_FP8_E4M3 || format == ZCO_FP8_E5M2) ? 2 : 0;
 }
 
 /* width of one field value of field f: field 0 = exponent, 1 = sign+mantissa, 2 = block scale */
@@ -98,6 +102,7 @@ static int value_bits(int format, int f)
     format = base_format(format);
     if (format == ZCO_BF16) return 8;
     if (format == ZCO_FP8_E4M3) return 4;
+    if (format == ZCO_FP8_E5M2) return f == 0 ? 5 : 3;
     if (format == ZCO_FP4_E2M1_MX) return f == 2 ? 8 : 2;
     return 0;
 }
@@ -106,6 +111,7 @@ static int value_bits(int format, int f)
 int zco_sym_bits(int format, int f)
 {
     if (!elem_bits(format)) return 0;
+    if (format == ZCO_FP8_E5M2) return 8;                      /* 5- and 3-bit values held in 8-bit symbols */
     return f == 2 ? 8 : value_bits(format, f) * group_of(format);
 }
 
@@ -131,7 +137,7 @@ static unsigned load_elem(int format, const uint8_t *p, uint64_t i)
 {
     format = base_format(format);
     if (format == ZCO_BF16) return (unsigned)p[2 * i] | ((unsigned)p[2 * i + 1] << 8);
-    if (format == ZCO_FP8_E4M3) return p[i];
+    if (format == ZCO_FP8_E4M3 || format == ZCO_FP8_E5M2) return p[i];
     return (i & 1) ? (p[i / 2] >> 4) : (p[i / 2] & 0xF);
 }
 
@@ -139,7 +145,7 @@ static void store_elem(int format, uint8_t *p, uint64_t i, unsigned x)
 {
     format = base_format(format);
     if (format == ZCO_BF16) { p[2 * i] = (uint8_t)(x & 0xFF); p[2 * i + 1] = (uint8_t)(x >> 8); }
-    else if (format == ZCO_FP8_E4M3) p[i] = (uint8_t)x;
+    else if (format == ZCO_FP8_E4M3 || format == ZCO_FP8_E5M2) p[i] = (uint8_t)x;
     else if (i & 1) p[i / 2] = (uint8_t)((p[i / 2] & 0x0F) | (x << 4));
     else p[i / 2] = (uint8_t)((p[i / 2] & 0xF0) | (x & 0xF));
 }
@@ -149,6 +155,7 @@ unsigned zco_exponent_of(int format, unsigned x)
     format = base_format(format);
     if (format == ZCO_BF16) return (x >> 7) & 0xFF;        /* s eeeeeeee mmmmmmm */
     if (format == ZCO_FP8_E4M3) return (x >> 3) & 0xF;     /* s eeee mmm */
+    if (format == ZCO_FP8_E5M2) return (x >> 2) & 0x1F;    /* s eeeee mm */
     return (x >> 1) & 0x3;                                 /* s ee m */
 }
 
@@ -157,6 +164,7 @@ unsigned zco_signmant_of(int format, unsigned x)
     format = base_format(format);
     if (format == ZCO_BF16) return ((x >> 15) << 7) | (x & 0x7F);
     if (format == ZCO_FP8_E4M3) return ((x >> 7) << 3) | (x & 0x7);
+    if (format == ZCO_FP8_E5M2) return ((x >> 7) << 2) | (x & 0x3);
     return ((x >> 3) << 1) | (x & 0x1);
 }
 
@@ -165,6 +173,7 @@ unsigned zco_rebuild(int format, unsigned e, unsigned sm)
     format = base_format(format);
     if (format == ZCO_BF16) return ((sm >> 7) << 15) | (e << 7) | (sm & 0x7F);
     if (format == ZCO_FP8_E4M3) return ((sm >> 3) << 7) | (e << 3) | (sm & 0x7);
+    if (format == ZCO_FP8_E5M2) return ((sm >> 2) << 7) | (e << 2) | (sm & 0x3);
     return ((sm >> 1) << 3) | (e << 1) | (sm & 0x1);
 }
 

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "zc_oracle.c")
 _LIB = os.path.join(_HERE, "libzc_oracle.so")
 
-BF16, FP8_E4M3, FP4_E2M1_MX, FP8_E4M3_BYTES, FP4_E2M1_MX_BYTES, FP4_E2M1_NV = 1, 2, 3, 4, 5, 6
+BF16, FP8_E4M3, FP4_E2M1_MX, FP8_E4M3_BYTES, FP4_E2M1_MX_BYTES, FP4_E2M1_NV, FP8_E5M2 = 1, 2, 3, 4, 5, 6, 7
 MODE_EMPTY, MODE_HUFF, MODE_RAW, MODE_CONST = 0, 1, 2, 3
 POLICY_HUFF_ALL, POLICY_AUTO = 0, 1
 OK, ERR_ARG, ERR_UNSUPPORTED, ERR_SMALL, ERR_CORRUPT = 0, 1, 2, 3, 4
@@ -112,7 +112,7 @@ def params(fmt, chunk_bytes, max_code_len=(0, 0, 0), streams=0, policy=POLICY_HU
 
 
 def elem_bits(fmt):
-    return {BF16: 16, FP8_E4M3: 8, FP4_E2M1_MX: 4, FP8_E4M3_BYTES: 8, FP4_E2M1_MX_BYTES: 4, FP4_E2M1_NV: 4}[fmt]
+    return {BF16: 16, FP8_E4M3: 8, FP4_E2M1_MX: 4, FP8_E4M3_BYTES: 8, FP4_E2M1_MX_BYTES: 4, FP4_E2M1_NV: 4, FP8_E5M2: 8}[fmt]
 
 
 def group_of(fmt):

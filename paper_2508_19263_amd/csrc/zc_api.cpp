@@ -190,6 +190,11 @@ zc_status build_codes(const Geometry &g, uint32_t policy, uint64_t n_elems, cons
                 const int sym = f == 0 ? (b >> 3) & 0xF : ((b >> 4) & 8) | (b & 7);
                 c.hist[sym] += hist3[b];
             }
+        } else if (g.fmt == ZC_FMT_FP8_E5M2) {
+            for (int b = 0; b < 256; b++) {
+                const int sym = f == 0 ? (b >> 2) & 0x1F : ((b >> 5) & 4) | (b & 3);
+                c.hist[sym] += hist3[b];
+            }
         } else if (f == 2) std::memcpy(c.hist, hist3 + 512, 256 * 8);
         else {
             for (int b = 0; b < 256; b++)

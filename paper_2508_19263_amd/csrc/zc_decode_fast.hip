@@ -448,12 +448,12 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
 
     const uint32_t rows = cb / 1024;                          // 64 lanes x 16 bytes per row
     for (uint32_t row = 0; row < rows; row++) {
-        uint64_t P0 = 0, P1 = 0, unused = 0;
-        if (kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, unused, lane);
-        else plain_run<F_::SB, F_::G>(kind[0], r0, row, lane, K0, P0, unused);
-        if (kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, unused, lane);
-        else plain_run<F_::SB, F_::G>(kind[1], r1, row, lane, K1, P1, unused);
-        const uint4 j = join_run<FMT>(P0, P1);
+        uint64_t P0 = 0, P1 = 0, Q0 = 0, Q1 = 0;       // Q: symbols 8..15 of a run of 16 symbols of 8 bits
+        if (kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, Q0, lane);
+        else plain_run<F_::SB, F_::G>(kind[0], r0, row, lane, K0, P0, Q0);
+        if (kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, Q1, lane);
+        else plain_run<F_::SB, F_::G>(kind[1], r1, row, lane, K1, P1, Q1);
+        const uint4 j = join_run4<FMT>(P0, Q0, P1, Q1);
         u32x4 v = {j.x, j.y, j.z, j.w};
         if (XOR) v ^= __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)(row * 1024), 0);
         __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
@@ -503,6 +503,7 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const Tens
     case ZC_FMT_FP8_E4M3_BYTES: return launch_s64_x<ZC_FMT_FP8_E4M3_BYTES>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
     case ZC_FMT_FP4_E2M1_MX_BYTES: return launch_s64_x<ZC_FMT_FP4_E2M1_MX_BYTES>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
     case ZC_FMT_FP4_E2M1_NV: return launch_s64_x<ZC_FMT_FP4_E2M1_NV>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_FP8_E5M2: return launch_s64_x<ZC_FMT_FP8_E5M2>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
     default: return 1;
     }
 }

@@ -39,6 +39,8 @@ template <> struct Fmt<ZC_FMT_FP8_E4M3> { static constexpr int EB = 8, EPR = 16,
 template <> struct Fmt<ZC_FMT_FP4_E2M1_MX> { static constexpr int EB = 4, EPR = 32, GRP = 1, G = 32, SB = 2, NF = 3, BASE = ZC_FMT_FP4_E2M1_MX, SCALE = 32; };
 template <> struct Fmt<ZC_FMT_FP4_E2M1_NV> { static constexpr int EB = 4, EPR = 32, GRP = 1, G = 32, SB = 2, NF = 3, BASE = ZC_FMT_FP4_E2M1_MX, SCALE = 16; };
 // byte-grouped symbols: the packed field words are those of the element format, read 8 bits at a time
+// E5M2: 16 symbols of 8 bits per run and field, i.e. two 64-bit words per field (P, Q)
+template <> struct Fmt<ZC_FMT_FP8_E5M2> { static constexpr int EB = 8, EPR = 16, GRP = 1, G = 16, SB = 8, NF = 2, BASE = ZC_FMT_FP8_E5M2, SCALE = 1; };
 template <> struct Fmt<ZC_FMT_FP8_E4M3_BYTES> { static constexpr int EB = 8, EPR = 16, GRP = 2, G = 8, SB = 8, NF = 2, BASE = ZC_FMT_FP8_E4M3, SCALE = 1; };
 template <> struct Fmt<ZC_FMT_FP4_E2M1_MX_BYTES> { static constexpr int EB = 4, EPR = 32, GRP = 4, G = 8, SB = 8, NF = 3, BASE = ZC_FMT_FP4_E2M1_MX, SCALE = 32; };
 
@@ -114,6 +116,44 @@ __device__ __forceinline__ uint4 join_run(uint64_t P0, uint64_t P1)
         }
     }
     return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// The same for any format: a field's symbols of one run in (P, Q); Q is used only by formats whose run is
+// 16 symbols of 8 bits (E5M2), where P holds symbols 0..7 and Q symbols 8..15.
+template <int FMT>
+__device__ __forceinline__ void split_run4(const uint4 &v, uint64_t &P0, uint64_t &Q0, uint64_t &P1, uint64_t &Q1)
+{
+    if (FMT == ZC_FMT_FP8_E5M2) {                       // s eeeee mm, four per word, one byte per symbol
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        uint32_t e[4], m[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            e[i] = (w[i] >> 2) & 0x1F1F1F1Fu;
+            m[i] = ((w[i] >> 5) & 0x04040404u) | (w[i] & 0x03030303u);
+        }
+        P0 = (uint64_t)e[0] | ((uint64_t)e[1] << 32); Q0 = (uint64_t)e[2] | ((uint64_t)e[3] << 32);
+        P1 = (uint64_t)m[0] | ((uint64_t)m[1] << 32); Q1 = (uint64_t)m[2] | ((uint64_t)m[3] << 32);
+    } else {
+        constexpr int F = FMT == ZC_FMT_FP8_E5M2 ? ZC_FMT_FP8_E4M3 : FMT;
+        split_run<F>(v, P0, P1);
+        Q0 = 0; Q1 = 0;
+    }
+}
+
+template <int FMT>
+__device__ __forceinline__ uint4 join_run4(uint64_t P0, uint64_t Q0, uint64_t P1, uint64_t Q1)
+{
+    if (FMT == ZC_FMT_FP8_E5M2) {
+        const uint32_t e[4] = {(uint32_t)P0, (uint32_t)(P0 >> 32), (uint32_t)Q0, (uint32_t)(Q0 >> 32)};
+        const uint32_t m[4] = {(uint32_t)P1, (uint32_t)(P1 >> 32), (uint32_t)Q1, (uint32_t)(Q1 >> 32)};
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) w[i] = ((m[i] & 0x04040404u) << 5) | ((e[i] & 0x1F1F1F1Fu) << 2) | (m[i] & 0x03030303u);
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    } else {
+        constexpr int F = FMT == ZC_FMT_FP8_E5M2 ? ZC_FMT_FP8_E4M3 : FMT;
+        return join_run<F>(P0, P1);
+    }
 }
 
 // 16 bytes from p, of which only the first `valid` may be read

@@ -22,11 +22,15 @@ inline uint32_t base_format(uint32_t fmt)
 inline uint32_t scale_block(uint32_t fmt) { return fmt == ZC_FMT_FP4_E2M1_NV ? 16 : (fmt == ZC_FMT_FP4_E2M1_MX || fmt == ZC_FMT_FP4_E2M1_MX_BYTES) ? 32 : 0; }
 inline int group_of(uint32_t fmt) { return fmt == ZC_FMT_FP8_E4M3_BYTES ? 2 : fmt == ZC_FMT_FP4_E2M1_MX_BYTES ? 4 : 1; }
 inline bool is_fp4(uint32_t fmt) { return base_format(fmt) == ZC_FMT_FP4_E2M1_MX; }
-inline int elem_bits(uint32_t fmt) { fmt = base_format(fmt); return fmt == ZC_FMT_BF16 ? 16 : fmt == ZC_FMT_FP8_E4M3 ? 8 : fmt == ZC_FMT_FP4_E2M1_MX ? 4 : 0; }
+inline int elem_bits(uint32_t fmt)
+{
+    fmt = base_format(fmt);
+    return fmt == ZC_FMT_BF16 ? 16 : (fmt == ZC_FMT_FP8_E4M3 || fmt == ZC_FMT_FP8_E5M2) ? 8 : fmt == ZC_FMT_FP4_E2M1_MX ? 4 : 0;
+}
 inline int num_fields(uint32_t fmt) { return is_fp4(fmt) ? 3 : 2; }
 inline int sym_bits(uint32_t fmt, int f)
 {
-    if (f == 2 || group_of(fmt) > 1) return 8;
+    if (f == 2 || group_of(fmt) > 1 || fmt == ZC_FMT_FP8_E5M2) return 8;
     return fmt == ZC_FMT_BF16 ? 8 : fmt == ZC_FMT_FP8_E4M3 ? 4 : 2;
 }
 // symbols per 16-byte run of the field's plain array

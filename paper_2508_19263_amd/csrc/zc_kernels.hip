@@ -277,6 +277,7 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
     uint32_t *my_units = units + d.units_off;
 
     // ---- element fields ----
+    constexpr bool kWide = F_::G * F_::SB > 64;
     EncField F0 = {0, 0, 0, 0, 0, 0, 0}, F1 = F0;
     const uint32_t chunk_runs = (uint32_t)((E + F_::EPR - 1) / F_::EPR);
     const uint32_t rows = (chunk_runs + S - 1) / S;
@@ -289,29 +290,38 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
         const uint32_t done = run * F_::EPR;                                                       // elements before this run
         const uint32_t nel = n > done ? (n - done < (uint32_t)F_::EPR ? n - done : (uint32_t)F_::EPR) : 0;
         const uint32_t nsym = (nel + F_::GRP - 1) / F_::GRP;                                       // a last partial group is filled with zeros
-        uint64_t P0 = 0, P1 = 0;
+        // a field's symbols of this run: P (and Q where a run is 16 symbols of 8 bits)
+        uint64_t P0 = 0, P1 = 0, Q0 = 0, Q1 = 0;
         if (nsym) {
             const uint32_t vb = nbytes - run * 16;
             uint4 v = load_run(src + (uint64_t)run * 16, vb);
             if (base) v = xor4(v, load_run(base + (uint64_t)run * 16, vb));
-            split_run<FMT>(v, P0, P1);
+            split_run4<FMT>(v, P0, Q0, P1, Q1);
         }
         const bool full = __all(nsym == (uint32_t)F_::G);
-        if (m0 == ZC_MODE_HUFF && d.kind[0] == 1 && full) enc_flat_run<WRITE, F_::SB>(F0, P0, stream[0], L, S);
+        // the direct path of a flat code is written for one 64-bit word per run; a wide field cannot be flat
+        // anyway (its alphabet of 256 is never used in full)
+        if (!kWide && m0 == ZC_MODE_HUFF && d.kind[0] == 1 && full) enc_flat_run<WRITE, F_::SB>(F0, P0, stream[0], L, S);
         else if (m0 == ZC_MODE_HUFF) {
-            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F0, d.period[0], P0, 0, nsym, enc[0], stream[0], L);
-            else enc_run<WRITE, F_::SB, F_::G, false>(F0, d.period[0], P0, 0, nsym, enc[0], stream[0], L);
+            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F0, d.period[0], P0, Q0, nsym, enc[0], stream[0], L);
+            else enc_run<WRITE, F_::SB, F_::G, false>(F0, d.period[0], P0, Q0, nsym, enc[0], stream[0], L);
         } else if (m0 == ZC_MODE_RAW && WRITE && nsym) {
-            reinterpret_cast<uint64_t *>(stream[0])[run] = P0;
-            if ((run & 1) == 0 && done + F_::EPR >= n) reinterpret_cast<uint64_t *>(stream[0])[run + 1] = 0;
+            if (kWide) { reinterpret_cast<uint64_t *>(stream[0])[2 * run] = P0; reinterpret_cast<uint64_t *>(stream[0])[2 * run + 1] = Q0; }
+            else {
+                reinterpret_cast<uint64_t *>(stream[0])[run] = P0;
+                if ((run & 1) == 0 && done + F_::EPR >= n) reinterpret_cast<uint64_t *>(stream[0])[run + 1] = 0;
+            }
         }
-        if (m1 == ZC_MODE_HUFF && d.kind[1] == 1 && full) enc_flat_run<WRITE, F_::SB>(F1, P1, stream[1], L, S);
+        if (!kWide && m1 == ZC_MODE_HUFF && d.kind[1] == 1 && full) enc_flat_run<WRITE, F_::SB>(F1, P1, stream[1], L, S);
         else if (m1 == ZC_MODE_HUFF) {
-            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F1, d.period[1], P1, 0, nsym, enc[1], stream[1], L);
-            else enc_run<WRITE, F_::SB, F_::G, false>(F1, d.period[1], P1, 0, nsym, enc[1], stream[1], L);
+            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F1, d.period[1], P1, Q1, nsym, enc[1], stream[1], L);
+            else enc_run<WRITE, F_::SB, F_::G, false>(F1, d.period[1], P1, Q1, nsym, enc[1], stream[1], L);
         } else if (m1 == ZC_MODE_RAW && WRITE && nsym) {
-            reinterpret_cast<uint64_t *>(stream[1])[run] = P1;
-            if ((run & 1) == 0 && done + F_::EPR >= n) reinterpret_cast<uint64_t *>(stream[1])[run + 1] = 0;
+            if (kWide) { reinterpret_cast<uint64_t *>(stream[1])[2 * run] = P1; reinterpret_cast<uint64_t *>(stream[1])[2 * run + 1] = Q1; }
+            else {
+                reinterpret_cast<uint64_t *>(stream[1])[run] = P1;
+                if ((run & 1) == 0 && done + F_::EPR >= n) reinterpret_cast<uint64_t *>(stream[1])[run + 1] = 0;
+            }
         }
         }
     {
@@ -368,6 +378,7 @@ static int launch_encode_t(uint32_t fmt, const TensorDev *d_descs, const WorkIte
     case ZC_FMT_FP8_E4M3_BYTES: hipLaunchKernelGGL((k_encode<ZC_FMT_FP8_E4M3_BYTES, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
     case ZC_FMT_FP4_E2M1_MX_BYTES: hipLaunchKernelGGL((k_encode<ZC_FMT_FP4_E2M1_MX_BYTES, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
     case ZC_FMT_FP4_E2M1_NV: hipLaunchKernelGGL((k_encode<ZC_FMT_FP4_E2M1_NV, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
+    case ZC_FMT_FP8_E5M2: hipLaunchKernelGGL((k_encode<ZC_FMT_FP8_E5M2, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
     default: return 1;
     }
     return (int)hipGetLastError();
@@ -576,22 +587,25 @@ __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const Wo
         const uint32_t nel = n > done ? (n - done < (uint32_t)F_::EPR ? n - done : (uint32_t)F_::EPR) : 0;
         const uint32_t nsym = (nel + F_::GRP - 1) / F_::GRP;                                       // a last partial group is filled with zeros
         const bool full = __all(nsym == (uint32_t)F_::G);
-        uint64_t P0 = 0, P1 = 0, unused = 0;
+        constexpr bool kWide = F_::G * F_::SB > 64;
+        uint64_t P0 = 0, P1 = 0, Q0 = 0, Q1 = 0;       // Q: symbols 8..15 of a run of 16 symbols of 8 bits
         if (m0 == ZC_MODE_HUFF) {
-            if (full) dec_run<F_::SB, F_::G, true>(D0, tab[0], d.period[0], P0, unused, nsym, L);
-            else dec_run<F_::SB, F_::G, false>(D0, tab[0], d.period[0], P0, unused, nsym, L);
+            if (full) dec_run<F_::SB, F_::G, true>(D0, tab[0], d.period[0], P0, Q0, nsym, L);
+            else dec_run<F_::SB, F_::G, false>(D0, tab[0], d.period[0], P0, Q0, nsym, L);
         } else if (m0 == ZC_MODE_RAW) {
-            if (nsym && 2 * run + 1 < D0.words) P0 = reinterpret_cast<const uint64_t *>(D0.ptr)[run];
-        } else P0 = K0;
+            if (kWide) { if (nsym && 4 * run + 3 < D0.words) { P0 = reinterpret_cast<const uint64_t *>(D0.ptr)[2 * run]; Q0 = reinterpret_cast<const uint64_t *>(D0.ptr)[2 * run + 1]; } }
+            else if (nsym && 2 * run + 1 < D0.words) P0 = reinterpret_cast<const uint64_t *>(D0.ptr)[run];
+        } else { P0 = K0; Q0 = K0; }
         if (m1 == ZC_MODE_HUFF) {
-            if (full) dec_run<F_::SB, F_::G, true>(D1, tab[1], d.period[1], P1, unused, nsym, L);
-            else dec_run<F_::SB, F_::G, false>(D1, tab[1], d.period[1], P1, unused, nsym, L);
+            if (full) dec_run<F_::SB, F_::G, true>(D1, tab[1], d.period[1], P1, Q1, nsym, L);
+            else dec_run<F_::SB, F_::G, false>(D1, tab[1], d.period[1], P1, Q1, nsym, L);
         } else if (m1 == ZC_MODE_RAW) {
-            if (nsym && 2 * run + 1 < D1.words) P1 = reinterpret_cast<const uint64_t *>(D1.ptr)[run];
-        } else P1 = K1;
+            if (kWide) { if (nsym && 4 * run + 3 < D1.words) { P1 = reinterpret_cast<const uint64_t *>(D1.ptr)[2 * run]; Q1 = reinterpret_cast<const uint64_t *>(D1.ptr)[2 * run + 1]; } }
+            else if (nsym && 2 * run + 1 < D1.words) P1 = reinterpret_cast<const uint64_t *>(D1.ptr)[run];
+        } else { P1 = K1; Q1 = K1; }
         if (nsym) {
             const uint32_t vb = nbytes - run * 16;
-            uint4 v = join_run<FMT>(P0, P1);
+            uint4 v = join_run4<FMT>(P0, Q0, P1, Q1);
             if (base) v = xor4(v, load_run(base + (uint64_t)run * 16, vb));
             store_run(dst + (uint64_t)run * 16, v, vb);
         }
@@ -635,6 +649,7 @@ int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work
     case ZC_FMT_FP8_E4M3_BYTES: hipLaunchKernelGGL(k_decode<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
     case ZC_FMT_FP4_E2M1_MX_BYTES: hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_MX_BYTES>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
     case ZC_FMT_FP4_E2M1_NV: hipLaunchKernelGGL(k_decode<ZC_FMT_FP4_E2M1_NV>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
+    case ZC_FMT_FP8_E5M2: hipLaunchKernelGGL(k_decode<ZC_FMT_FP8_E5M2>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, first_slot); break;
     default: return 1;
     }
     return (int)hipGetLastError();

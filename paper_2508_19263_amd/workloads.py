@@ -46,6 +46,18 @@ def e4m3_bits(x):
     return (sign | code).to(torch.uint8)
 
 
+def e5m2_bits(x):
+    """float32 -> FP8 E5M2 (bias 15, 2 mantissa bits, IEEE-like) bytes, RNE, saturating at 57344."""
+    x = x.contiguous().clamp(-57344.0, 57344.0)
+    b = x.view(torch.int32)
+    sign = (b >> 24) & 0x80
+    mag = b & 0x7FFFFFFF
+    norm = ((mag + 0xFFFFF + ((mag >> 21) & 1)) >> 21) - ((127 - 15) << 2)
+    sub = torch.round(x.abs() * 65536.0).to(torch.int32)          # below 2^-14 the grid is uniform with step 2^-16
+    code = torch.where(x.abs() < 2.0 ** -14, sub, norm).clamp(0, 0x7B)
+    return (sign | code).to(torch.uint8)
+
+
 def mxfp4_bits(x):
     """float32 [.., 32*k] -> (packed E2M1 bytes, E8M0 scale bytes), OCP MX rule.
 
@@ -125,19 +137,29 @@ def fp8_weight(n, device="cpu", seed=0, std=0.02, outlier_frac=1e-3, outlier_gai
     return e4m3_bits(x)
 
 
+def fp8_e5m2_weight(n, device="cpu", seed=0, std=0.02, outlier_frac=1e-3, outlier_gain=20.0):
+    """The FP8 weight recipe of config 2 cast to E5M2 instead (per-tensor scale mapping amax to 57344)."""
+    g = _gen(device, seed)
+    x = torch.randn(n, generator=g, device=device) * std
+    mask = torch.rand(n, generator=g, device=device) < outlier_frac
+    x = torch.where(mask, x * outlier_gain, x)
+    x = x * (57344.0 / x.abs().max())
+    return e5m2_bits(x)
+
+
 # per decoder layer of an 8B-class model: (name, rows, cols)
 LAYER_8B = [("q", 4096, 4096), ("k", 4096, 1024), ("v", 4096, 1024), ("o", 4096, 4096),
             ("gate", 4096, 14336), ("up", 4096, 14336), ("down", 14336, 4096)]
 
 
-def fp8_weight_set(n_layers=32, device="cpu", shrink=1):
+def fp8_weight_set(n_layers=32, device="cpu", shrink=1, e5m2=False):
     """Config 2: yields (name, uint8 tensor) for every tensor of the set.
-    shrink divides both matrix dimensions (tests use a reduced set)."""
+    shrink divides both matrix dimensions (tests use a reduced set); e5m2 casts to E5M2 instead of E4M3."""
     i = 0
     for layer in range(n_layers):
         for name, r, c in LAYER_8B:
             n = (r // shrink) * (c // shrink)
-            yield "L%d.%s" % (layer, name), fp8_weight(n, device, _seed(2, i))
+            yield "L%d.%s" % (layer, name), (fp8_e5m2_weight if e5m2 else fp8_weight)(n, device, _seed(2, i))
             i += 1
 
 

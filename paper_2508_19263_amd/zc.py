@@ -13,7 +13,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libzc.so")
 
-FMT_BF16, FMT_FP8_E4M3, FMT_FP4_E2M1_MX, FMT_FP8_E4M3_BYTES, FMT_FP4_E2M1_MX_BYTES, FMT_FP4_E2M1_NV = 1, 2, 3, 4, 5, 6
+FMT_BF16, FMT_FP8_E4M3, FMT_FP4_E2M1_MX, FMT_FP8_E4M3_BYTES, FMT_FP4_E2M1_MX_BYTES, FMT_FP4_E2M1_NV, FMT_FP8_E5M2 = 1, 2, 3, 4, 5, 6, 7
 POLICY_HUFF_ALL, POLICY_AUTO = 0, 1
 MODE_EMPTY, MODE_HUFF, MODE_RAW, MODE_CONST = 0, 1, 2, 3
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_BUFFER_TOO_SMALL, ERR_CORRUPT, ERR_DEVICE = range(6)
@@ -137,7 +137,7 @@ def params(fmt, chunk_bytes, max_code_len=(0, 0, 0), streams=0, policy=POLICY_HU
 
 
 def elem_bits(fmt):
-    return {FMT_BF16: 16, FMT_FP8_E4M3: 8, FMT_FP4_E2M1_MX: 4, FMT_FP8_E4M3_BYTES: 8, FMT_FP4_E2M1_MX_BYTES: 4, FMT_FP4_E2M1_NV: 4}[fmt]
+    return {FMT_BF16: 16, FMT_FP8_E4M3: 8, FMT_FP4_E2M1_MX: 4, FMT_FP8_E4M3_BYTES: 8, FMT_FP4_E2M1_MX_BYTES: 4, FMT_FP4_E2M1_NV: 4, FMT_FP8_E5M2: 8}[fmt]
 
 
 def scale_block(fmt):

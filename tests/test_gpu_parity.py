@@ -14,6 +14,8 @@ DEV = "cuda:0"
 def make_input(fmt, n, seed):
     if fmt == zc.FMT_BF16:
         return wl.bf16_weight(n, seed=seed).view(torch.uint8), None
+    if fmt == zc.FMT_FP8_E5M2:
+        return wl.fp8_e5m2_weight(n, seed=seed) if n else torch.zeros(0, dtype=torch.uint8), None
     if fmt in (zc.FMT_FP8_E4M3, zc.FMT_FP8_E4M3_BYTES):
         return wl.fp8_weight(n, seed=seed) if n else torch.zeros(0, dtype=torch.uint8), None
     if n == 0:
@@ -612,8 +614,9 @@ def _random_source(rng, fmt, n):
 def test_random_parameter_sweep():
     # seeded sweep over formats, lanes, chunk sizes, lengths, policies, length limits and data shapes
     rng = np.random.default_rng(20250827)
-    fmts = (zc.FMT_BF16, zc.FMT_FP8_E4M3, zc.FMT_FP4_E2M1_MX, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP4_E2M1_MX_BYTES, zc.FMT_FP4_E2M1_NV)
-    for case in range(160):
+    fmts = (zc.FMT_BF16, zc.FMT_FP8_E4M3, zc.FMT_FP4_E2M1_MX, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP4_E2M1_MX_BYTES, zc.FMT_FP4_E2M1_NV,
+            zc.FMT_FP8_E5M2)
+    for case in range(182):
         fmt = fmts[case % len(fmts)]
         S = int(2 ** rng.integers(0, 7))
         unit = 256 if zc.scale_block(fmt) else 16
@@ -625,7 +628,7 @@ def test_random_parameter_sweep():
         if blk:
             n = n // blk * blk
         policy = int(rng.integers(0, 2))
-        sb8 = fmt in (zc.FMT_BF16, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP4_E2M1_MX_BYTES)
+        sb8 = fmt in (zc.FMT_BF16, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP4_E2M1_MX_BYTES, zc.FMT_FP8_E5M2)
         lo = 8 if sb8 else (4 if fmt == zc.FMT_FP8_E4M3 else 2)
         L = (int(rng.integers(lo, 17)) if rng.integers(0, 2) else 0, int(rng.integers(lo, 17)) if rng.integers(0, 2) else 0,
              int(rng.integers(8, 17)) if rng.integers(0, 2) else 0)
@@ -700,3 +703,22 @@ def test_tensor_beyond_4_gib():
             got = comp[a:b].cpu().numpy()
             want = o.encode_stream(syms, lens[f], 16, 64)
             assert np.array_equal(got, want), (c, f)
+
+
+def test_fp8_e5m2():
+    # Sec. 3.2, the other FP8 variant: 5-bit exponent and 3-bit sign+mantissa values held in 8-bit symbols
+    F = zc.FMT_FP8_E5M2
+    for S in (64, 8, 1):
+        cb = 4096
+        for n in (1, 16 * S - 1, 16 * S + 1, cb - 1, cb, cb + 1, 3 * cb + 17 * 16 + 5, 40 * cb + 3):
+            for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+                check_case(F, n, cb, S, policy, tag="e5m2")
+    check_case(F, 6 * 65536 + 1234, 65536, 64, tag="e5m2-full")                       # 64-lane full-chunk kernel
+    check_case(F, 6 * 65536, 65536, 64, L=(9, 8, 0), tag="e5m2-limits")
+    a, b = wl.fp8_e5m2_weight(5 * 32768 + 77, seed=1), wl.fp8_e5m2_weight(5 * 32768 + 77, seed=2)
+    check_case(F, a.numel(), 32768, 64, data=(a, None), base=b, tag="e5m2-delta")
+    rng = np.random.default_rng(3)
+    u = torch.from_numpy(rng.integers(0, 256, 3 * 16384 + 100, dtype=np.uint8))
+    check_case(F, u.numel(), 16384, 64, zc.POLICY_AUTO, data=(u, None), tag="e5m2-uniform")
+    c = torch.full((2 * 16384 + 5,), 0x3C, dtype=torch.uint8)
+    check_case(F, c.numel(), 16384, 64, data=(c, None), tag="e5m2-constant")

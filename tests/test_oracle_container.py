@@ -190,7 +190,7 @@ def test_corrupt_containers_are_rejected():
 
 def test_bad_parameters():
     x = np.zeros(64, np.uint8)
-    for p in (o.params(7, 4096), o.params(o.FP8_E4M3, 100), o.params(o.FP8_E4M3, 4096, streams=3),
+    for p in (o.params(9, 4096), o.params(o.FP8_E4M3, 100), o.params(o.FP8_E4M3, 4096, streams=3),
               o.params(o.FP4_E2M1_MX, 128)):
         assert o.compress_bound(64, p) == 0
     with pytest.raises(ValueError):
@@ -310,3 +310,21 @@ def test_nvfp4_format():
     # element count must be a multiple of the scale block
     with pytest.raises(ValueError):
         o.compress(m, n - 8, p, scales=sc)
+
+
+def test_e5m2_format():
+    x = wl.fp8_e5m2_weight(90001, seed=21).numpy()
+    for S in (64, 4):
+        for policy in (o.POLICY_HUFF_ALL, o.POLICY_AUTO):
+            p = o.params(o.FP8_E5M2, 4096, streams=S, policy=policy)
+            comp = o.compress(x, len(x), p)
+            rc, out, _ = o.decompress(comp, len(x))
+            assert rc == o.OK and np.array_equal(out, x)
+            assert comp[6] == o.FP8_E5M2 and comp[33] == 8 and comp[37] == 8 and comp[32] == o.MODE_HUFF
+    st = o.stats(x, len(x), p)
+    e, sm = o.split(o.FP8_E5M2, x, len(x))
+    assert list(st.field[0].hist) == np.bincount(e, minlength=256).tolist() and st.field[0].distinct <= 32
+    assert list(st.field[1].hist) == np.bincount(sm, minlength=256).tolist() and st.field[1].distinct <= 8
+    # the 3-bit sign+mantissa values of Gaussian data are near uniform: 3 bits each; the exponent beats 5 bits
+    assert 2.99 < st.field[1].mean_code_len <= 3.01 and st.field[0].mean_code_len < 3.2
+    assert abs(st.ratio_payload_total - (st.field[0].mean_code_len + st.field[1].mean_code_len) / 8) < 1e-9

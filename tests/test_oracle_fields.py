@@ -83,3 +83,31 @@ def test_histogram_matches_bincount():
         h = o.histogram(s)
         assert int(h.sum()) == n
         assert np.array_equal(h, np.bincount(s, minlength=256).astype(np.uint64))
+
+
+def test_e5m2_fields():
+    # Sec. 3.2, the other FP8 variant: s eeeee mm.  Exhaustive identity, and the fields against torch's own
+    # decoding of the byte (value = (-1)^s * 2^(e-15) * (1 + m/4) for normal numbers)
+    import torch
+    L = o.lib()
+    seen = set()
+    for x in range(256):
+        e, sm = L.zco_exponent_of(o.FP8_E5M2, x), L.zco_signmant_of(o.FP8_E5M2, x)
+        assert e < 32 and sm < 8 and L.zco_rebuild(o.FP8_E5M2, e, sm) == x
+        seen.add((e, sm))
+    assert len(seen) == 256
+    codes = torch.arange(256, dtype=torch.uint8)
+    vals = codes.view(torch.float8_e5m2).to(torch.float32).numpy()
+    e, sm = o.split(o.FP8_E5M2, codes.numpy(), 256)
+    normal = (e > 0) & (e < 31)
+    _, ex = np.frexp(vals[normal])
+    assert np.array_equal(e[normal].astype(int), ex - 1 + 15)
+    assert np.array_equal(sm[normal] >> 2, (np.signbit(vals[normal])).astype(np.uint8))
+    frac = np.abs(vals[normal]) / np.exp2((ex - 1).astype(np.float32)) - 1.0
+    assert np.array_equal(sm[normal] & 3, np.round(frac * 4).astype(np.uint8))
+    # hand-worked: 0x3C = 0 01111 00 = 1.0; 0xC5 = 1 10001 01 = -(1.25 * 4) = -5.0
+    assert (L.zco_exponent_of(o.FP8_E5M2, 0x3C), L.zco_signmant_of(o.FP8_E5M2, 0x3C)) == (15, 0)
+    assert (L.zco_exponent_of(o.FP8_E5M2, 0xC5), L.zco_signmant_of(o.FP8_E5M2, 0xC5)) == (17, 5)
+    assert float(torch.tensor([0xC5], dtype=torch.uint8).view(torch.float8_e5m2).to(torch.float32)) == -5.0
+    # symbols are held in 8 bits: 16 per 16-byte run in both fields
+    assert o.lib().zco_sym_bits(o.FP8_E5M2, 0) == 8 and o.lib().zco_sym_bits(o.FP8_E5M2, 1) == 8 and o.lib().zco_num_fields(o.FP8_E5M2) == 2

@@ -138,3 +138,12 @@ def test_nvfp4_generator():
     # the MX generator still gives the same bytes after sharing the E2M1 cast
     p2, s2 = wl.mxfp4_weight(8, 64, seed=2)
     assert p2.numel() == 256 and s2.numel() == 16
+
+
+def test_e5m2_cast_matches_torch():
+    g = torch.Generator().manual_seed(5)
+    x = torch.randn(200000, generator=g) * torch.exp2(torch.randint(-18, 15, (200000,), generator=g).float())
+    x = x.clamp(-57344.0, 57344.0)
+    assert torch.equal(wl.e5m2_bits(x), x.to(torch.float8_e5m2).view(torch.uint8))
+    w = wl.fp8_e5m2_weight(4096, seed=3)
+    assert w.dtype == torch.uint8 and int((w & 0x7F).max()) == 0x7B
