@@ -221,15 +221,15 @@ zc_status zc_decompress_chunks(const void *d_comp, uint64_t comp_bytes, const zc
 /* Whole-set decode in one launch: every tensor's d_comp/info/d_dst (and d_xor_base,
  * d_scales_out) must be set.  All tensors must share format and streams.  A tensor with
  * d_chunk_ids set decodes only those chunks, densely (random-access page decode of a whole
- * K/V cache in one launch).  The per-tensor
- * descriptors and the work list are uploaded to d_ws with a blocking copy (the stream is
- * synchronised before the launch, not after it). */
+ * K/V cache in one launch).  The per-tensor descriptors and the work list go to d_ws in a copy
+ * queued on the stream ahead of the kernels; the call never waits. */
 zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors,
                               void *d_ws, uint64_t ws_bytes, void *stream);
 
 /* The two halves of zc_decompress_batch, for callers that decode the same set more than
- * once: _plan validates and uploads the descriptors and the work lists to d_ws (blocking)
- * and fills *plan (host); _run only enqueues the decode kernels on d_ws as left by _plan
+ * once: _plan validates, queues the upload of the descriptors and the work lists to d_ws on the
+ * stream (from a page-locked buffer of the library's: no wait) and fills *plan (host); _run only
+ * enqueues the decode kernels on d_ws as left by _plan, on the same stream or one ordered after it
  * (never synchronises).  The plan is plain data; it stays valid while d_ws, the containers
  * and the destination pointers are unchanged. */
 typedef struct {

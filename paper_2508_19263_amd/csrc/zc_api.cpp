@@ -969,10 +969,12 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
     if (ws_bytes < descs_bytes + fast_bytes + work.size() * sizeof(WorkItem)) return ZC_ERR_BUFFER_TOO_SMALL;
     hipStream_t hs = (hipStream_t)stream;
     uint8_t *ws = (uint8_t *)d_ws;
-    HIP_TRY(hipMemcpyAsync(ws, descs.data(), descs.size() * sizeof(TensorDev), hipMemcpyHostToDevice, hs));
-    if (!fast_work.empty()) HIP_TRY(hipMemcpyAsync(ws + descs_bytes, fast_work.data(), fast_work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
-    if (!work.empty()) HIP_TRY(hipMemcpyAsync(ws + descs_bytes + fast_bytes, work.data(), work.size() * sizeof(WorkItem), hipMemcpyHostToDevice, hs));
-    HIP_TRY(hipStreamSynchronize(hs));      // the host arrays above go away when this call returns
+    // one copy from the page-locked staging buffer: no wait, the host arrays above may go away at once
+    const Piece all[3] = {{0, descs.data(), descs.size() * sizeof(TensorDev)},
+                          {descs_bytes, fast_work.data(), fast_work.size() * sizeof(WorkItem)},
+                          {descs_bytes + fast_bytes, work.data(), work.size() * sizeof(WorkItem)}};
+    const zc_status up = host_stage().upload(ws, 0, descs_bytes + fast_bytes + work.size() * sizeof(WorkItem), all, 3, hs);
+    if (up) return up;
     plan->format = fmt; plan->streams = S; plan->n_tensors = n_tensors;
     plan->n_fast_work = (uint32_t)fast_work.size(); plan->n_work = (uint32_t)work.size();
     plan->fast_exp_kind = (uint32_t)fk.exp_kind; plan->fast_sm_kind = (uint32_t)fk.sm_kind; plan->xor_delta = tensors[0].info.xor_delta;

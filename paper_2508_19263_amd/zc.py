@@ -369,7 +369,7 @@ class Batch:
         return self.out
 
     def plan_decompress(self):
-        """Upload descriptors and work lists (blocking); returns the plan."""
+        """Queue the upload of descriptors and work lists on the current stream; returns the plan."""
         if self.out is None:
             self.prepare_outputs()
         self.plan = BatchPlan()
