@@ -258,11 +258,14 @@ struct HuffStream {
     u32x2 pv;
     char *ring;            // this wavefront's ring in LDS
     __amdgpu_buffer_rsrc_t rs;
+    uint32_t lim[4];       // FieldTab::limit of lengths 12..15 (uniform): the code lengths beyond the lookup index
 };
 
-__device__ __forceinline__ void huff_open(HuffStream &H, __amdgpu_buffer_rsrc_t rs, char *ring, uint32_t lane)
+__device__ __forceinline__ void huff_open(HuffStream &H, const FieldTab &T, __amdgpu_buffer_rsrc_t rs, char *ring, uint32_t lane)
 {
     H.rs = rs; H.ring = ring;
+#pragma unroll
+    for (int i = 0; i < 4; i++) H.lim[i] = uniform32(T.limit[kLutBits + 1 + i]);
 #pragma unroll
     for (uint32_t q = 0; q < kRing2Words / kRing2Segment; q++) {
         const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(lane * 8 + q * kRing2Segment * 4), 0, 0);
@@ -300,17 +303,17 @@ __device__ __forceinline__ void huff_refill(HuffStream &H)
     H.wpos += (uint32_t)__popcll(bm);
 }
 
-// code longer than the lookup index: canonical search on the bit-reversed window (inlined: a
-// call here would cost the common path its registers)
-__device__ __forceinline__ uint32_t long_code(const FieldTab &T, uint32_t x)
+// Code longer than the lookup index (12..16 bits), without a search: in a canonical code the left-aligned
+// codes of length <= l all lie below limit[l], so the length is 12 plus the number of those limits that the
+// next 16 stream bits reach, and the symbol's rank follows from the code value.  Inlined: a call here would
+// cost the common path its registers.  A malformed table can only give a wrong symbol: the index is masked.
+__device__ __forceinline__ uint32_t long_code(const FieldTab &T, const HuffStream &H, uint32_t x)
 {
-    const uint32_t msb = __brev(x);
-    uint32_t e = T.lmax ? T.lmax : 1;       // malformed table: consume something, symbol 0
-    for (uint32_t l = T.lmax; l > (uint32_t)kLutBits; l--) {
-        const uint32_t code = msb >> (32 - l);
-        if (code >= T.first[l] && code - T.first[l] < T.cnt[l]) e = l | ((uint32_t)T.sorted[T.start[l] + code - T.first[l]] << 8);
-    }
-    return e;
+    static_assert(kLutBits == 11, "four limits cover the lengths 12..15; 16 is what is left");
+    const uint32_t w = __brev(x) >> 16;                    // the next 16 stream bits in code order
+    const uint32_t len = 12u + (w >= H.lim[0]) + (w >= H.lim[1]) + (w >= H.lim[2]) + (w >= H.lim[3]);
+    const uint32_t idx = (T.rebase[len] + (w >> (16u - len))) & 255u;
+    return len | ((uint32_t)T.sorted[idx] << 8);
 }
 
 // decode one run of G symbols (SB bits each) into P0 (symbols 0..64/SB-1) and P1 (the rest).
@@ -331,7 +334,7 @@ __device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uin
         for (int j = 0; j < R; j++) {
             const int jj = g * R + j;
             uint32_t e = *reinterpret_cast<const uint16_t *>(lut + ((x & mask) << 1));
-            if (LONG && e == 0) e = long_code(T, x);
+            if (LONG && e == 0) e = long_code(T, H, x);
             x >>= (e & 31u);
             used += e;
             constexpr int kPer32 = 32 / SB;
@@ -443,8 +446,8 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     char *ring_base = reinterpret_cast<char *>(rings) + wave * (kRing2Words * 4);
     char *ring0 = ring_base, *ring1 = ring_base + (kind[0] == KIND_HUFF ? kWavesPerGroup * kRing2Words * 4 : 0);
     HuffStream H0, H1;
-    if (kind[0] == KIND_HUFF) huff_open(H0, r0, ring0, lane);
-    if (kind[1] == KIND_HUFF) huff_open(H1, r1, ring1, lane);
+    if (kind[0] == KIND_HUFF) huff_open(H0, tab[0], r0, ring0, lane);
+    if (kind[1] == KIND_HUFF) huff_open(H1, tab[1], r1, ring1, lane);
 
     const uint32_t rows = cb / 1024;                          // 64 lanes x 16 bytes per row
     for (uint32_t row = 0; row < rows; row++) {
@@ -468,7 +471,7 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
         const uint32_t p2 = uniform32(d.period[F2]);
         const uint64_t K2 = splat(uniform32(d.konst[F2]), 8);
         HuffStream H2;
-        if (kind[F2] == KIND_HUFF) huff_open(H2, r2, ring_base, lane);      // the element rings are free again
+        if (kind[F2] == KIND_HUFF) huff_open(H2, tab[F2], r2, ring_base, lane);      // the element rings are free again
         for (uint32_t row = 0; row < n_sc / 1024; row++) {
             uint64_t P0 = 0, P1 = 0;
             if (kind[F2] == KIND_HUFF) huff_run<8, 16>(H2, tab[F2], p2, P0, P1, lane);

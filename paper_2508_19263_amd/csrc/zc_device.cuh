@@ -182,6 +182,9 @@ constexpr int kLutBits = 11;
 struct FieldTab {
     uint16_t lut[1 << kLutBits];   // (symbol << 8) | length, 0 = code longer than the index
     uint32_t first[17], cnt[17], start[17];
+    // for the codes longer than the index, by length l: limit = (first + cnt) << (16 - l), the left-aligned
+    // exclusive upper bound of all codes of length <= l (non-decreasing in l); rebase = start - first
+    uint32_t limit[17], rebase[17];
     uint8_t sorted[256];
     uint8_t len[256];
     uint32_t mask;                 // (1 << min(Lmax, kLutBits)) - 1
@@ -204,8 +207,11 @@ __attribute__((unused)) static __device__ void build_field_tab(FieldTab &T, cons
         for (int l = 1; l <= 16; l++) {
             code <<= 1;
             T.first[l] = code; T.start[l] = idx;
+            T.rebase[l] = idx - code;
             code += T.cnt[l]; idx += T.cnt[l];
+            T.limit[l] = code << (16 - l);
         }
+        T.limit[0] = 0; T.rebase[0] = 0;
         const uint32_t bits = lmax < (uint32_t)kLutBits ? lmax : (uint32_t)kLutBits;
         T.mask = (1u << bits) - 1;
         T.lmax = lmax;
@@ -233,15 +239,16 @@ __attribute__((unused)) static __device__ void build_field_tab(FieldTab &T, cons
     __syncthreads();
 }
 
-// code longer than the lookup index: canonical search on the bit-reversed window
+// Code longer than the lookup index (12..16 bits), without a search: in a canonical code the left-aligned
+// codes of length <= l all lie below limit[l], so the length is 12 plus the number of those limits that the
+// next 16 stream bits reach, and the symbol's rank follows from the code value.  A malformed table can only
+// give a wrong symbol: the index is masked.
 __attribute__((unused)) static __device__ __noinline__ uint32_t dec_long(const FieldTab &T, uint32_t x)
 {
-    const uint32_t msb = __brev(x);
-    for (uint32_t l = kLutBits + 1; l <= T.lmax; l++) {
-        const uint32_t code = msb >> (32 - l);
-        if (code >= T.first[l] && code - T.first[l] < T.cnt[l]) return l | ((uint32_t)T.sorted[T.start[l] + code - T.first[l]] << 8);
-    }
-    return T.lmax ? T.lmax : 1;      // malformed table: consume something, symbol 0
+    static_assert(kLutBits == 11, "four limits cover the lengths 12..15; 16 is what is left");
+    const uint32_t w = __brev(x) >> 16;                    // the next 16 stream bits in code order
+    const uint32_t len = 12u + (w >= T.limit[12]) + (w >= T.limit[13]) + (w >= T.limit[14]) + (w >= T.limit[15]);
+    return len | ((uint32_t)T.sorted[(T.rebase[len] + (w >> (16u - len))) & 255u] << 8);
 }
 
 // every symbol of a 64-bit packed run equal to v
