@@ -3,7 +3,7 @@
  *
  * Method: Heilper & Singer, "Lossless Compression of Neural Network Components:
  * Weights, Checkpoints, and K/V Caches in Low-Precision Formats" (2025).
- * Every value of a BF16 / FP8 E4M3 / FP4 E2M1 tensor is split into its exponent
+ * Every value of a BF16 / FP8 (E4M3, E5M2) / FP4 E2M1 tensor is split into its exponent
  * bits and its sign+mantissa bits (Sec. 3.1, 3.2, 3.4, Fig. 5); each field is
  * histogrammed over the tensor and Huffman coded on its own (Sec. 3.1, 3.2, 4);
  * FP4 block scales form a third field (Sec. 3.4, 4.4); a checkpoint delta is the
@@ -18,14 +18,16 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Kernels are enqueued on it.  Calls that must read results back (noted
  *     below) synchronise that stream before returning.
- *   - The library keeps no state between calls and never allocates or frees
- *     device memory: scratch space comes in through `d_ws`.
+ *   - The library never allocates or frees device memory: scratch space comes in
+ *     through `d_ws`.  The only state it keeps between calls is one page-locked
+ *     host buffer through which descriptors, work lists and tables are uploaded
+ *     (allocated on first use, grown when needed, held until the process ends).
  *   - Errors are returned as zc_status; nothing is thrown.  On error the
  *     destination contents are unspecified but nothing is written outside the
  *     capacities given.
  *   - Element layout: BF16 little-endian u16; FP8 one byte; FP4 two elements per
- *     byte, element 2i in the low nibble, with one E8M0 scale byte per 32
- *     consecutive elements in a separate array.
+ *     byte, element 2i in the low nibble, with one scale byte per 32 (MX: E8M0) or
+ *     16 (NV: E4M3) consecutive elements in a separate array.
  */
 #ifndef ZC_H
 #define ZC_H
@@ -210,7 +212,7 @@ zc_status zc_decompress(const void *d_comp, uint64_t comp_bytes, const zc_info *
 
 /* Random-access decode (Sec. 3.1: chunks decode independently; Sec. 4.3 / 5.2: K/V pages):
  * chunk d_chunk_ids[i] is written to d_dst + i*chunk_bytes (and its scales to
- * d_scales_out + i*chunk_bytes/16).  A short last chunk leaves the rest of its slot
+ * d_scales_out + i * the scale bytes of a whole chunk: chunk_bytes/16 for MX, chunk_bytes/8 for NV).  A short last chunk leaves the rest of its slot
  * untouched.  d_chunk_ids: device array of n_ids u32, each < n_chunks (ids out of range
  * are skipped).  Delta containers: d_xor_base is the whole base tensor. */
 zc_status zc_decompress_chunks(const void *d_comp, uint64_t comp_bytes, const zc_info *info,
