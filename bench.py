@@ -41,8 +41,9 @@ def _time_ms(torch, fn, reps=5):
     return t[len(t) // 2]
 
 
-def other_workloads(torch, wl, zc, dev):
-    """Configs 1, 3, 4, 5 at full size: ratios, compress and decompress GB/s (median of 5)."""
+def other_workloads(torch, wl, zc, dev, extras):
+    """Configs 1, 3, 4, 5 at full size: ratios, compress and decompress GB/s (median of 5).
+    extras: also the formats and variants beyond the five configurations."""
     out = {}
 
     def run(name, fmt, srcs, counts, chunk, streams, bases=None, scales=None, limit=(0, 0, 0), ids=None, dictionary=False,
@@ -60,6 +61,8 @@ def other_workloads(torch, wl, zc, dev):
         r = {"uncompressed_bytes": raw, "compressed_bytes": sum(sizes), "ratio_total": sum(sizes) / raw,
              "ratio_fields_payload": [st.field[f].ratio_payload for f in range(st.n_fields)],
              "compress_ms": t_c, "compress_GBps": raw / t_c / 1e6, "decompress_ms": t_d, "decompress_GBps": raw / t_d / 1e6,
+             "compress_frac_of_hbm_peak_uncompressed": raw / t_c / 1e6 / HBM_PEAK_GBPS,
+             "decompress_frac_of_hbm_peak_uncompressed": raw / t_d / 1e6 / HBM_PEAK_GBPS,
              "decompress_traffic_frac_of_hbm_peak": (raw + sum(sizes) + (raw if bases else 0)) / t_d / 1e6 / HBM_PEAK_GBPS,
              "round_trip_bit_exact": bool(ok)}
         if ids is not None:
@@ -98,28 +101,29 @@ def other_workloads(torch, wl, zc, dev):
         del b
         torch.cuda.empty_cache()
 
-    # config 2 again with byte-grouped symbols (two exponents per symbol; the flat sign+mantissa field raw)
-    set2 = [t for _, t in wl.fp8_weight_set(32, device=dev)]
-    run("c2_fp8_byte_symbols", zc.FMT_FP8_E4M3_BYTES, set2, [t.numel() for t in set2], 262144, 64, policy=zc.POLICY_AUTO)
-    run("c2_fp8_byte_symbols_limit_11", zc.FMT_FP8_E4M3_BYTES, set2, [t.numel() for t in set2], 262144, 64, limit=(11, 11, 0), policy=zc.POLICY_AUTO)
-    run("c2_fp8_plain_symbols_auto", zc.FMT_FP8_E4M3, set2, [t.numel() for t in set2], 262144, 64, policy=zc.POLICY_AUTO)
-    del set2
-    set2 = [t for _, t in wl.fp8_weight_set(32, device=dev, e5m2=True)]
-    run("c2_shapes_in_fp8_e5m2", zc.FMT_FP8_E5M2, set2, [t.numel() for t in set2], 262144, 64)
-    del set2
+    if extras:
+        # config 2 again with byte-grouped symbols (two exponents per symbol; the flat sign+mantissa field raw)
+        set2 = [t for _, t in wl.fp8_weight_set(32, device=dev)]
+        run("c2_fp8_byte_symbols", zc.FMT_FP8_E4M3_BYTES, set2, [t.numel() for t in set2], 262144, 64, policy=zc.POLICY_AUTO)
+        run("c2_fp8_byte_symbols_limit_11", zc.FMT_FP8_E4M3_BYTES, set2, [t.numel() for t in set2], 262144, 64, limit=(11, 11, 0), policy=zc.POLICY_AUTO)
+        run("c2_fp8_plain_symbols_auto", zc.FMT_FP8_E4M3, set2, [t.numel() for t in set2], 262144, 64, policy=zc.POLICY_AUTO)
+        del set2
+        set2 = [t for _, t in wl.fp8_weight_set(32, device=dev, e5m2=True)]
+        run("c2_shapes_in_fp8_e5m2", zc.FMT_FP8_E5M2, set2, [t.numel() for t in set2], 262144, 64)
+        del set2
     x = wl.bf16_weight(1 << 20, device=dev, seed=0)
     run("c1_bf16_1M", zc.FMT_BF16, [x], [1 << 20], 65536, 64, limit=(16, 16, 0))
     mats = [wl.mxfp4_weight(8192, 28672, device=dev, seed=300 + i) for i in range(3)]
     run("c3_mxfp4_70b_mlp", zc.FMT_FP4_E2M1_MX, [m[0] for m in mats], [8192 * 28672] * 3, 262144, 64, scales=[m[1] for m in mats])
-    # the same matrices 12 times over (36 matrices, 4.5 GB): enough chunks to fill the GPU, which 3 matrices do not
-    big = [m for _ in range(12) for m in mats]
-    run("c3_mxfp4_36_matrices", zc.FMT_FP4_E2M1_MX, [m[0] for m in big], [8192 * 28672] * 36, 262144, 64, scales=[m[1] for m in big])
-    del big
-    run("c3_mxfp4_70b_mlp_byte_symbols", zc.FMT_FP4_E2M1_MX_BYTES, [m[0] for m in mats], [8192 * 28672] * 3, 262144, 64,
-        scales=[m[1] for m in mats], policy=zc.POLICY_AUTO)
-    del mats
-    mats = [wl.nvfp4_weight(8192, 28672, device=dev, seed=310 + i) for i in range(3)]
-    run("nvfp4_70b_mlp", zc.FMT_FP4_E2M1_NV, [m[0] for m in mats], [8192 * 28672] * 3, 262144, 64, scales=[m[1] for m in mats])
+    if extras:
+        # the same matrices 12 times over (36 matrices, 4.5 GB): enough chunks to fill the GPU, which 3 matrices do not
+        big = [m for _ in range(12) for m in mats]
+        run("c3_mxfp4_36_matrices", zc.FMT_FP4_E2M1_MX, [m[0] for m in big], [8192 * 28672] * 36, 262144, 64, scales=[m[1] for m in big])
+        del big
+        run("c3_mxfp4_70b_mlp_byte_symbols", zc.FMT_FP4_E2M1_MX_BYTES, [m[0] for m in mats], [8192 * 28672] * 3, 262144, 64,
+            scales=[m[1] for m in mats], policy=zc.POLICY_AUTO)
+        mats = [wl.nvfp4_weight(8192, 28672, device=dev, seed=310 + i) for i in range(3)]
+        run("nvfp4_70b_mlp", zc.FMT_FP4_E2M1_NV, [m[0] for m in mats], [8192 * 28672] * 3, 262144, 64, scales=[m[1] for m in mats])
     del mats
     pairs = [wl.bf16_checkpoint_pair(4096 * 16384, device=dev, seed=400 + i) for i in range(16)]
     w0, w1 = [q[0] for q in pairs], [q[1] for q in pairs]
@@ -156,14 +160,15 @@ def other_workloads(torch, wl, zc, dev):
                                        "queued_without_wait_host_us_per_call": host_us, "round_trip_bit_exact": bool(ok_step)}
     del sb, step_pages
     del kv
-    # the same cache shape in BF16: 16-token pages of 4 KiB, 16 layers
-    kv = []
-    for layer in range(16):
-        k, v = wl.bf16_kv_pair(device=dev, seed=700 + layer)
-        kv += [k.reshape(-1), v.reshape(-1)]
-    n_pages = kv[0].numel() * 2 // 4096
-    ids = [wl.page_sample(n_pages, 0.25, device=dev, seed=800 + i) for i in range(len(kv))]
-    run("bf16_kv_pages", zc.FMT_BF16, kv, [t.numel() for t in kv], 4096, 8, ids=ids)
+    if extras:
+        # the same cache shape in BF16: 16-token pages of 4 KiB, 16 layers
+        kv = []
+        for layer in range(16):
+            k, v = wl.bf16_kv_pair(device=dev, seed=700 + layer)
+            kv += [k.reshape(-1), v.reshape(-1)]
+        n_pages = kv[0].numel() * 2 // 4096
+        ids = [wl.page_sample(n_pages, 0.25, device=dev, seed=800 + i) for i in range(len(kv))]
+        run("bf16_kv_pages", zc.FMT_BF16, kv, [t.numel() for t in kv], 4096, 8, ids=ids)
     return out
 
 
@@ -179,8 +184,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-only", action="store_true", help="timed steps run only the decode kernel (for profiling)")
     ap.add_argument("--no-verify", action="store_true", help="skip the round-trip check (kernel experiments only)")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="time only the FP8 weight set (the metric); by default configurations 1, 3, 4 and 5 are timed too "
+                         "and reported under 'other_workloads' in the same JSON line")
     ap.add_argument("--other-workloads", action="store_true",
-                    help="also time configs 1, 3, 4 and 5 (reported under 'other_workloads' in the same JSON line)")
+                    help="also the formats and variants beyond the five configurations (byte-grouped symbols, E5M2, NVFP4, "
+                         "BF16 K/V pages, MXFP4 at a size that fills the GPU)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed steps run one plain elementwise kernel that reads 1 GiB and writes 1 GiB "
                          "(scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -291,16 +300,23 @@ def main():
                      "algorithmic_bytes_per_launch": algo_bytes, "traffic": MEASURED_TRAFFIC_BYTES.get(workload)},
     }
 
-    if args.other_workloads:
-        result["other_workloads"] = other_workloads(torch, wl, zc, dev)
+    host = None
+    if not args.no_cpu_baseline:
+        host = [srcs[i].cpu().numpy() for i in range(min(7, len(srcs)))]      # layer 0: q, k, v, o, gate, up, down
+    if not args.headline_only:
+        # the other four configurations (and, on request, the extra formats); a failure here must not cost the line above
+        del batch, srcs
+        torch.cuda.empty_cache()
+        try:
+            result["other_workloads"] = other_workloads(torch, wl, zc, dev, args.other_workloads)
+        except Exception as e:                                  # noqa: BLE001 - reported, not raised
+            result["other_workloads"] = {"error": "%s: %s" % (type(e).__name__, e)}
 
     if not args.no_cpu_baseline:
         # the oracle as it stands, single thread, on a bounded sample of the same workload
         import numpy as np
         from oracle import zc_oracle as o
-        sample = [i for i in range(min(7, len(srcs)))]            # layer 0: q, k, v, o, gate, up, down
         po = o.params(o.FP8_E4M3, args.chunk_kib * 1024, (args.max_len, 0, 0), 64, 1 if args.policy == "auto" else 0)
-        host = [srcs[i].cpu().numpy() for i in sample]
         t_c = t_d = 0.0
         nbytes = 0
         for x in host:
