@@ -527,6 +527,7 @@ __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, 
     constexpr uint32_t kSeg = 4 * S, kRing = 16 * S;             // words per group
     __shared__ uint16_t lut[256];
     __shared__ __attribute__((aligned(16))) uint32_t ring[kWavesPerGroup][kRingWords];
+    __shared__ __attribute__((aligned(16))) uint32_t two_rows[kWavesPerGroup][256];      // 4*S words per group
     __shared__ Canon16 canon;
     __shared__ TensorDev dsh;
     WorkItem it;
@@ -568,6 +569,7 @@ __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, 
     const uint32_t one = 1;
     const char *lut_bytes = reinterpret_cast<const char *>(lut);
     char *const ring_bytes = reinterpret_cast<char *>(&ring[wave][0]) + grp * (kRing * 4);
+    uint32_t *const sm_words = &two_rows[wave][grp * 4 * S];
 
     // the workgroup owns slots [first, first + slots_per_group): each pass takes 4 waves x kGroups of them
     for (uint32_t pass = 0; pass * kWavesPerGroup * kGroups < slots_per_group; pass++) {
@@ -577,27 +579,43 @@ __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, 
         if (ids && alive) chunk = ids[slot];
         alive = alive && chunk < n_full;                         // short last chunk: the host sends it to the generic kernel
         uint32_t e_off = pay_bytes, m_off = pay_bytes;           // out of range: loads return 0
+        uint32_t e_len = 0;                                      // bytes of the exponent stream
         if (alive) {
             const uint64_t a0 = index0[chunk], b0 = index0[chunk + 1], a1 = index1[chunk], b1 = index1[chunk + 1];
-            if (a0 <= b0 && a1 <= b1 && 16 * b1 <= pay_bytes && 16 * b0 <= pay_bytes && (b1 - a1) * 16 >= cb / 2) { e_off = (uint32_t)(16 * a0); m_off = (uint32_t)(16 * a1); }
-            else alive = false;
+            if (a0 <= b0 && a1 <= b1 && 16 * b1 <= pay_bytes && 16 * b0 <= pay_bytes && (b1 - a1) * 16 >= cb / 2) {
+                e_off = (uint32_t)(16 * a0); m_off = (uint32_t)(16 * a1); e_len = (uint32_t)(16 * (b0 - a0));
+            } else alive = false;
         }
+        // the ring reads ahead of what is consumed: a piece past the end of this chunk's stream is not fetched
+        // (it would be the next chunk's data, read a second time by whoever decodes that chunk)
+        auto ring_piece = [&](uint32_t word) -> u32x4 {
+            return __builtin_amdgcn_raw_buffer_load_b128(ps, (int)(word * 4 < e_len ? e_off + word * 4 : pay_bytes), 0, 0);
+        };
         const uint32_t out_off = slot * cb, base_off = chunk * cb;
 
         // ring prologue: the group's first 16*S words (each lane 4 loads of 16 bytes)
 #pragma unroll
         for (uint32_t q = 0; q < 4; q++) {
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(ps, (int)(e_off + (q * kSeg + s * 4) * 4), 0, 0);
+            const u32x4 v = ring_piece(q * kSeg + s * 4);
             *reinterpret_cast<u32x4 *>(ring_bytes + (q * kSeg + s * 4) * 4) = v;
         }
         uint64_t W = (uint64_t)(*reinterpret_cast<const uint32_t *>(ring_bytes + s * 4)) << 32;    // step 0: lane s takes word s
         uint32_t c = 32, wpos = S, wbase = 0, pslot = 0;
         bool pending = false;
         u32x4 pv = {0, 0, 0, 0};
+        // The sign+mantissa stream of two rows is 4*S contiguous words in both layouts: the group fetches them
+        // with one 16-byte load per lane (whole cache lines instead of 4-byte pieces that are evicted between
+        // rows), one pair of rows ahead, and hands every lane its own words through LDS.
+        u32x4 sm_next = __builtin_amdgcn_raw_buffer_load_b128(ps, (int)(m_off + s * 16), 0, 0);
         for (uint32_t row = 0; row < rows; row++) {
+            if ((row & 1) == 0) {
+                *reinterpret_cast<u32x4 *>(sm_words + 4 * s) = sm_next;
+                const uint32_t next = ((row + 2) * 2 * S + 4 * s) * 4;                  // nothing past the chunk's cb/2 bytes
+                sm_next = __builtin_amdgcn_raw_buffer_load_b128(ps, (int)(next < cb / 2 ? m_off + next : pay_bytes), 0, 0);
+            }
             if (pending) { *reinterpret_cast<u32x4 *>(ring_bytes + (pslot + s * 4) * 4) = pv; pending = false; }
             if (wpos - wbase >= kSeg) {
-                pv = __builtin_amdgcn_raw_buffer_load_b128(ps, (int)(e_off + (wbase + kRing + s * 4) * 4), 0, 0);
+                pv = ring_piece(wbase + kRing + s * 4);
                 pslot = wbase & (kRing - 1);
                 wbase += kSeg;
                 pending = true;
@@ -607,13 +625,13 @@ __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, 
             for (int h = 0; h < 2; h++) {
                 uint32_t A, B;
                 if (sm_raw) {
-                    const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(ps, (int)(m_off + ((row * S + s) * 2 + h) * 4), 0, 0);
+                    const uint32_t w = sm_words[((row & 1) * S + s) * 2 + h];
                     A = ((w << 4) & 0x80808080u) | (w & 0x07070707u);
                     B = (w & 0x80808080u) | ((w >> 4) & 0x07070707u);
                     m[2 * h] = perm(A, B, 0x01050004u);
                     m[2 * h + 1] = perm(A, B, 0x03070206u);
                 } else {
-                    const uint32_t w = __brev(__builtin_amdgcn_raw_buffer_load_b32(ps, (int)(m_off + ((row * 2 + h) * S + s) * 4), 0, 0));
+                    const uint32_t w = __brev(sm_words[((row & 1) * 2 + h) * S + s]);
                     A = ((w << 4) & 0x80808080u) | (w & 0x07070707u);
                     B = (w & 0x80808080u) | ((w >> 4) & 0x07070707u);
                     m[2 * h] = perm(A, B, 0x06020703u);
