@@ -678,7 +678,7 @@ zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *
         // this kernel does not take, so lists go here only when every chunk is whole.
         const uint32_t n_fast = by_ids ? n_ids : (uint32_t)(info.n_elems / elems_per_chunk);
         const uint32_t spg = sub_slots_per_group(info.streams, n_fast);
-        LAUNCH_TRY(launch_decode_fp8_sub(info.streams, info.xor_delta != 0, nullptr, nullptr, (n_fast + spg - 1) / spg, &d, spg, stream));
+        LAUNCH_TRY(launch_decode_fp8_sub(info.streams, info.xor_delta != 0, by_ids, nullptr, nullptr, (n_fast + spg - 1) / spg, &d, spg, stream));
         first_slot = n_fast;
     } else if ((fk.ok || rings) && !by_ids) {
         // full chunks through a specialised kernel, a short last chunk through the generic one
@@ -979,6 +979,8 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
     plan->n_fast_work = (uint32_t)fast_work.size(); plan->n_work = (uint32_t)work.size();
     plan->fast_exp_kind = (uint32_t)fk.exp_kind; plan->fast_sm_kind = (uint32_t)fk.sm_kind; plan->xor_delta = tensors[0].info.xor_delta;
     plan->fast_kernel = fk.ok ? 1u : (rings ? 2u : (sub ? 3u : 0u)); plan->n_rings = sub ? spg : rings;
+    plan->scattered = 0;
+    for (uint32_t t = 0; t < n_tensors; t++) if (tensors[t].d_chunk_ids) plan->scattered = 1;
     plan->fast_work_offset = descs_bytes; plan->work_offset = descs_bytes + fast_bytes;
     return ZC_OK;
 }
@@ -996,7 +998,7 @@ zc_status zc_decompress_batch_run(const zc_batch_plan *plan, const void *d_ws, v
         LAUNCH_TRY(launch_decode_s64(plan->format, plan->n_rings, plan->xor_delta != 0, (const TensorDev *)ws,
                                      (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, stream));
     else if (plan->n_fast_work && plan->fast_kernel == 3)
-        LAUNCH_TRY(launch_decode_fp8_sub(plan->streams, plan->xor_delta != 0, (const TensorDev *)ws,
+        LAUNCH_TRY(launch_decode_fp8_sub(plan->streams, plan->xor_delta != 0, plan->scattered != 0, (const TensorDev *)ws,
                                          (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, plan->n_rings, stream));
     else if (plan->n_fast_work) return ZC_ERR_INVALID_ARG;
     if (plan->n_work)

@@ -519,7 +519,10 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const Tens
 // buffer resource spans the whole payload, with the group's stream offset in the vector
 // offset.  Each group owns 16*S words of the wavefront's 1024-word ring, refilled 4*S words
 // (one 16-byte load per lane) at a time.
-template <int S, bool XOR>
+// LINES: the sign+mantissa words are fetched a cache line at a time and handed out through LDS.  That pays
+// when neighbouring chunks are decoded together (whole tensors: 0.98 against 1.02 ms on the K/V set) and
+// costs when pages are picked at random (0.31 against 0.28 ms), so id lists run without it.
+template <int S, bool XOR, bool LINES>
 __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single,
                                                         uint32_t slots_per_group)
 {
@@ -527,7 +530,7 @@ __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, 
     constexpr uint32_t kSeg = 4 * S, kRing = 16 * S;             // words per group
     __shared__ uint16_t lut[256];
     __shared__ __attribute__((aligned(16))) uint32_t ring[kWavesPerGroup][kRingWords];
-    __shared__ __attribute__((aligned(16))) uint32_t two_rows[kWavesPerGroup][256];      // 4*S words per group
+    __shared__ __attribute__((aligned(16))) uint32_t two_rows[kWavesPerGroup][LINES ? 256 : 4];      // 4*S words per group
     __shared__ Canon16 canon;
     __shared__ TensorDev dsh;
     WorkItem it;
@@ -569,7 +572,7 @@ __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, 
     const uint32_t one = 1;
     const char *lut_bytes = reinterpret_cast<const char *>(lut);
     char *const ring_bytes = reinterpret_cast<char *>(&ring[wave][0]) + grp * (kRing * 4);
-    uint32_t *const sm_words = &two_rows[wave][grp * 4 * S];
+    uint32_t *const sm_words = &two_rows[wave][LINES ? grp * 4 * S : 0];
 
     // the workgroup owns slots [first, first + slots_per_group): each pass takes 4 waves x kGroups of them
     for (uint32_t pass = 0; pass * kWavesPerGroup * kGroups < slots_per_group; pass++) {
@@ -593,6 +596,12 @@ __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, 
         };
         const uint32_t out_off = slot * cb, base_off = chunk * cb;
 
+        // The sign+mantissa stream of two rows is 4*S contiguous words in both layouts: the group fetches them
+        // with one 16-byte load per lane (whole cache lines instead of 4-byte pieces that are evicted between
+        // rows), one pair of rows ahead, and hands every lane its own words through LDS.  The first pair is
+        // asked for before the ring's prologue so that both waits overlap.
+        u32x4 sm_next = {0, 0, 0, 0};
+        if (LINES) sm_next = __builtin_amdgcn_raw_buffer_load_b128(ps, (int)(m_off + s * 16), 0, 0);
         // ring prologue: the group's first 16*S words (each lane 4 loads of 16 bytes)
 #pragma unroll
         for (uint32_t q = 0; q < 4; q++) {
@@ -603,12 +612,8 @@ __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, 
         uint32_t c = 32, wpos = S, wbase = 0, pslot = 0;
         bool pending = false;
         u32x4 pv = {0, 0, 0, 0};
-        // The sign+mantissa stream of two rows is 4*S contiguous words in both layouts: the group fetches them
-        // with one 16-byte load per lane (whole cache lines instead of 4-byte pieces that are evicted between
-        // rows), one pair of rows ahead, and hands every lane its own words through LDS.
-        u32x4 sm_next = __builtin_amdgcn_raw_buffer_load_b128(ps, (int)(m_off + s * 16), 0, 0);
         for (uint32_t row = 0; row < rows; row++) {
-            if ((row & 1) == 0) {
+            if (LINES && (row & 1) == 0) {
                 *reinterpret_cast<u32x4 *>(sm_words + 4 * s) = sm_next;
                 const uint32_t next = ((row + 2) * 2 * S + 4 * s) * 4;                  // nothing past the chunk's cb/2 bytes
                 sm_next = __builtin_amdgcn_raw_buffer_load_b128(ps, (int)(next < cb / 2 ? m_off + next : pay_bytes), 0, 0);
@@ -625,13 +630,15 @@ __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, 
             for (int h = 0; h < 2; h++) {
                 uint32_t A, B;
                 if (sm_raw) {
-                    const uint32_t w = sm_words[((row & 1) * S + s) * 2 + h];
+                    const uint32_t w = LINES ? sm_words[((row & 1) * S + s) * 2 + h]
+                                             : __builtin_amdgcn_raw_buffer_load_b32(ps, (int)(m_off + ((row * S + s) * 2 + h) * 4), 0, 0);
                     A = ((w << 4) & 0x80808080u) | (w & 0x07070707u);
                     B = (w & 0x80808080u) | ((w >> 4) & 0x07070707u);
                     m[2 * h] = perm(A, B, 0x01050004u);
                     m[2 * h + 1] = perm(A, B, 0x03070206u);
                 } else {
-                    const uint32_t w = __brev(sm_words[((row & 1) * 2 + h) * S + s]);
+                    const uint32_t w = __brev(LINES ? sm_words[((row & 1) * 2 + h) * S + s]
+                                                    : __builtin_amdgcn_raw_buffer_load_b32(ps, (int)(m_off + ((row * 2 + h) * S + s) * 4), 0, 0));
                     A = ((w << 4) & 0x80808080u) | (w & 0x07070707u);
                     B = (w & 0x80808080u) | ((w >> 4) & 0x07070707u);
                     m[2 * h] = perm(A, B, 0x06020703u);
@@ -663,17 +670,20 @@ __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, 
 }
 
 template <int S>
-static int launch_fp8_sub_s(bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single,
+static int launch_fp8_sub_s(bool xor_delta, bool lines, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single,
                             uint32_t slots_per_group, hipStream_t st)
 {
-    if (xor_delta) hipLaunchKernelGGL((k_decode_fp8_sub<S, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, slots_per_group);
-    else hipLaunchKernelGGL((k_decode_fp8_sub<S, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, slots_per_group);
+    if (xor_delta && lines) hipLaunchKernelGGL((k_decode_fp8_sub<S, true, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, slots_per_group);
+    else if (xor_delta) hipLaunchKernelGGL((k_decode_fp8_sub<S, true, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, slots_per_group);
+    else if (lines) hipLaunchKernelGGL((k_decode_fp8_sub<S, false, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, slots_per_group);
+    else hipLaunchKernelGGL((k_decode_fp8_sub<S, false, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single, slots_per_group);
     return (int)hipGetLastError();
 }
 
 // FP8, S in {4, 8, 16, 32}, full chunks, exponent refill period 4, sign+mantissa flat or raw.
 // Each workgroup takes slots_per_group consecutive slots (chunk ids, or positions in d_ids).
-int launch_decode_fp8_sub(uint32_t streams, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+// scattered: some tensor decodes an id list (pages picked at random rather than neighbours).
+int launch_decode_fp8_sub(uint32_t streams, bool xor_delta, bool scattered, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                           const TensorDev *single, uint32_t slots_per_group, void *stream)
 {
     if (n_work == 0) return 0;
@@ -681,10 +691,10 @@ int launch_decode_fp8_sub(uint32_t streams, bool xor_delta, const TensorDev *d_d
     const TensorDev s = single ? *single : TensorDev{};
     const int use_single = single ? 1 : 0;
     switch (streams) {
-    case 4: return launch_fp8_sub_s<4>(xor_delta, d_descs, d_work, n_work, s, use_single, slots_per_group, st);
-    case 8: return launch_fp8_sub_s<8>(xor_delta, d_descs, d_work, n_work, s, use_single, slots_per_group, st);
-    case 16: return launch_fp8_sub_s<16>(xor_delta, d_descs, d_work, n_work, s, use_single, slots_per_group, st);
-    case 32: return launch_fp8_sub_s<32>(xor_delta, d_descs, d_work, n_work, s, use_single, slots_per_group, st);
+    case 4: return launch_fp8_sub_s<4>(xor_delta, !scattered, d_descs, d_work, n_work, s, use_single, slots_per_group, st);
+    case 8: return launch_fp8_sub_s<8>(xor_delta, !scattered, d_descs, d_work, n_work, s, use_single, slots_per_group, st);
+    case 16: return launch_fp8_sub_s<16>(xor_delta, !scattered, d_descs, d_work, n_work, s, use_single, slots_per_group, st);
+    case 32: return launch_fp8_sub_s<32>(xor_delta, !scattered, d_descs, d_work, n_work, s, use_single, slots_per_group, st);
     }
     return (int)hipErrorInvalidValue;
 }
