@@ -334,6 +334,7 @@ TensorDev make_desc(const zc_info &info)
 // dict: precomputed dictionary to code with (no histogram pass), or null.  train: stop after the
 // code construction with smoothed counts (codes_out receives the dictionary).
 uint32_t sub_slots_per_group(uint32_t streams, uint64_t slots);
+void order_for_xcds(std::vector<WorkItem> &items);
 
 zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, void *d_ws, uint64_t ws_bytes, void *stream,
                        bool stats_only, std::vector<FieldCode> *codes_out, std::vector<ScanOut> *scan_out,
@@ -469,6 +470,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         for (uint64_t c = n_full; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
     }
     if (codes_out) *codes_out = codes;
+    order_for_xcds(fast_work);
+    order_for_xcds(slow_work);
     {
         // everything the kernels from here on read from the host, in one copy (the histogram work lists ride
         // along so that the copied range has no holes)
@@ -588,6 +591,22 @@ uint32_t sub_slots_per_group(uint32_t streams, uint64_t slots)
     if (passes < 1) passes = 1;
     if (passes > 8) passes = 8;
     return (uint32_t)passes * per_pass;
+}
+
+// Workgroups are handed to the 8 XCDs (each with an L2 of its own) in turn, so workgroup p runs on XCD
+// p % 8.  Reordering the list so that every XCD walks through one contiguous eighth of it keeps an XCD's
+// wavefronts in neighbouring chunks (measured on the FP8 weight set: 2.60 instead of 2.63 ms).
+void order_for_xcds(std::vector<WorkItem> &items)
+{
+    constexpr size_t kXcds = 8;
+    const size_t n = items.size(), q = n / kXcds, r = n % kXcds;
+    if (n < 2 * kXcds) return;
+    std::vector<WorkItem> out(n);
+    for (size_t p = 0; p < n; p++) {
+        const size_t k = p % kXcds, start = k * q + (k < r ? k : r);
+        out[p] = items[start + p / kXcds];
+    }
+    items.swap(out);
 }
 
 zc_status parse_info(const uint8_t *c, uint64_t have, uint64_t comp_bytes, zc_info *out)
@@ -964,6 +983,7 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
         }                                                                   // an id list with 64-lane chunks goes through the generic kernel
         for (uint32_t c = first_generic; c < slots; c += cpi) work.push_back({t, c});
     }
+    order_for_xcds(fast_work);
     const uint64_t descs_bytes = align256((uint64_t)n_tensors * sizeof(TensorDev));
     const uint64_t fast_bytes = align256(fast_work.size() * sizeof(WorkItem));
     if (ws_bytes < descs_bytes + fast_bytes + work.size() * sizeof(WorkItem)) return ZC_ERR_BUFFER_TOO_SMALL;
