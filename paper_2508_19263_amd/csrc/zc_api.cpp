@@ -81,7 +81,7 @@ uint64_t get64(const uint8_t *p) { uint64_t v; std::memcpy(&v, p, 8); return v; 
 
 // ---- workspace carving ------------------------------------------------------
 struct Workspace {
-    uint64_t descs, hist_work, scale_work, chunk_work, fast_work, hist, enc, units, scan, blobs, total, host_end;
+    uint64_t descs, hist_work, scale_work, chunk_work, fast_work, whole_work, hist, enc, units, scan, blobs, total, host_end;
     uint32_t n_hist_work, n_scale_work, n_chunk_work;
     uint64_t n_units;
 };
@@ -111,6 +111,7 @@ zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T,
     w->scale_work = off; off = align256(off + sw * sizeof(WorkItem));
     w->chunk_work = off; off = align256(off + cw * sizeof(WorkItem));
     w->fast_work = off; off = align256(off + cw * sizeof(WorkItem));
+    w->whole_work = off; off = align256(off + cw * sizeof(WorkItem));
     w->enc = off; off = align256(off + (uint64_t)T * 768 * 4);
     w->blobs = off; off = align256(off + (uint64_t)T * kBlobBytes);
     w->host_end = off;
@@ -408,7 +409,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
 
     // code construction on the host (a4): tensors are independent, so a large set is split over a few threads
     std::vector<FieldCode> codes((size_t)T * 3);
-    std::vector<WorkItem> fast_work, slow_work;
+    std::vector<WorkItem> fast_work, whole_work, slow_work;
     std::vector<uint32_t> enc((size_t)T * 768, 0);
     std::vector<uint8_t> blobs((size_t)T * kBlobBytes, 0);
     std::vector<uint8_t> fast_flag(T, 0);
@@ -465,24 +466,31 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     for (uint32_t t = 0; t < T; t++) all_chunks += ncs[t];
     const uint32_t fast_step = g.S == 64 ? kWavesPerGroup : sub_slots_per_group(g.S, all_chunks);    // chunks per fast work item
     for (uint32_t t = 0; t < T; t++) {
-        const uint64_t n_full = fast_flag[t] ? tensors[t].n_elems / g.elems_per_chunk : 0;
-        for (uint64_t c = 0; c < n_full; c += fast_step) fast_work.push_back({t, (uint32_t)c});
-        for (uint64_t c = n_full; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
+        // whole chunks: the FP8 kernels where they apply, else (64 lanes, chunks of whole 1 KiB rows) the generic
+        // encoder's whole-chunk build; a short last chunk and every other geometry: the generic encoder
+        const uint64_t whole_chunks = tensors[t].n_elems / g.elems_per_chunk;
+        const uint64_t n_fast = fast_flag[t] ? whole_chunks : 0;
+        const uint64_t n_whole = (!fast_flag[t] && g.S == 64 && g.chunk_bytes % 1024 == 0) ? whole_chunks : 0;
+        for (uint64_t c = 0; c < n_fast; c += fast_step) fast_work.push_back({t, (uint32_t)c});
+        for (uint64_t c = 0; c < n_whole; c += kWavesPerGroup) whole_work.push_back({t, (uint32_t)c});
+        for (uint64_t c = n_fast + n_whole; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
     }
     if (codes_out) *codes_out = codes;
     order_for_xcds(fast_work);
+    order_for_xcds(whole_work);
     order_for_xcds(slow_work);
     {
         // everything the kernels from here on read from the host, in one copy (the histogram work lists ride
         // along so that the copied range has no holes)
-        const Piece all[7] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
+        const Piece all[8] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
+                              {w.whole_work, whole_work.data(), whole_work.size() * sizeof(WorkItem)},
                               {w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem)},
                               {w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem)},
                               {w.chunk_work, slow_work.data(), slow_work.size() * sizeof(WorkItem)},
                               {w.fast_work, fast_work.data(), fast_work.size() * sizeof(WorkItem)},
                               {w.enc, enc.data(), enc.size() * 4},
                               {w.blobs, blobs.data(), stats_only ? 0 : blobs.size()}};
-        st = host_stage().upload(ws, w.descs, w.host_end, all, 7, hs);
+        st = host_stage().upload(ws, w.descs, w.host_end, all, 8, hs);
         if (st) return st;
     }
     if (!stats_only) LAUNCH_TRY(launch_write_headers(d_descs, T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
@@ -492,7 +500,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     uint32_t *d_units = (uint32_t *)(ws + w.units);
     if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, stream));
     else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 0, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
-    LAUNCH_TRY(launch_sizes(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), cpi, d_enc, d_units, stream));
+    LAUNCH_TRY(launch_sizes(g.fmt, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, d_units, stream));
+    LAUNCH_TRY(launch_sizes(g.fmt, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, d_units, stream));
     LAUNCH_TRY(launch_scan(d_descs, T, (int)g.nf, d_units, (ScanOut *)(ws + w.scan), stream));
     // chunked encode (a7).  When every destination can hold the worst case, the sizes need not be known on
     // the host first: the encoder is queued right behind the scan and the sizes are read back meanwhile (or,
@@ -500,7 +509,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     auto launch_encoders = [&]() -> zc_status {
         if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, stream));
         else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
-        LAUNCH_TRY(launch_encode(g.fmt, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), cpi, d_enc, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, stream));
         return ZC_OK;
     };
     bool roomy = !stats_only;

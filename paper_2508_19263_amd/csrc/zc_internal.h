@@ -89,10 +89,10 @@ void assign_canonical(const uint8_t *len, int alphabet, uint16_t *code_out);
 int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                 int scales_view, uint64_t *d_hist, void *stream);
 int launch_write_headers(const TensorDev *d_descs, uint32_t n_tensors, const uint8_t *d_blobs, uint32_t blob_bytes, int n_fields, void *stream);
-int launch_sizes(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
+int launch_sizes(uint32_t fmt, bool whole, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                  const uint32_t *d_enc_tables, uint32_t *d_units, void *stream);
 int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, const uint32_t *d_units, ScanOut *d_out, void *stream);
-int launch_encode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
+int launch_encode(uint32_t fmt, bool whole, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                   const uint32_t *d_enc_tables, void *stream);
 int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
                   const TensorDev *single, uint32_t first_slot, void *stream);

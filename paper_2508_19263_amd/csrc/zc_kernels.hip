@@ -251,22 +251,27 @@ __device__ __forceinline__ uint32_t enc_finish(EncField &F, uint8_t *stream, con
 
 // Encoder body for the symbols of one field kind.  ELEM = true: fields 0 and 1 of the
 // element array; false: the FP4 scale field.
-template <int FMT, bool WRITE>
+// WHOLE: the launch covers only whole chunks of tensors with 64 lanes per chunk (one wavefront per chunk, every
+// run complete), which lets the compiler drop the lane-group masks and every partial-run path.
+template <int FMT, bool WRITE, bool WHOLE>
 __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units)
 {
     using F_ = Fmt<FMT>;
     __shared__ uint32_t enc[3][256];
+    __shared__ TensorDev dsh;                       // a copy the compiler knows no store of this kernel can change
     const WorkItem it = work[blockIdx.x];
-    const TensorDev &d = descs[it.tensor];
+    if (threadIdx.x == 0) dsh = descs[it.tensor];
     for (uint32_t i = threadIdx.x; i < 3 * 256; i += 256) (&enc[0][0])[i] = enc_tables[(uint64_t)it.tensor * 768 + i];
     __syncthreads();
-    const uint32_t S = d.streams;
+    const TensorDev &d = dsh;
+    const uint32_t S = WHOLE ? 64u : d.streams;
     const Lanes L = make_lanes(S);
     const uint32_t wave = threadIdx.x >> 6;
     const uint32_t chunk = it.first + wave * (64 / S) + L.grp;
-    const bool valid = chunk < d.n_chunks;
     const uint64_t E = (uint64_t)d.chunk_bytes * 8 / F_::EB;
     const uint64_t first = (uint64_t)chunk * E;
+    // WHOLE: the host lists only whole chunks, up to four per work item; a wavefront beyond the last one idles
+    const bool valid = WHOLE ? first + E <= d.n_elems : chunk < d.n_chunks;
     const uint32_t n = valid ? (uint32_t)(d.n_elems - first < E ? d.n_elems - first : E) : 0;
     const uint32_t *index[3];
     uint8_t *stream[3] = {nullptr, nullptr, nullptr};
@@ -284,11 +289,12 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
     const uint8_t *src = d.src + (uint64_t)chunk * d.chunk_bytes;
     const uint8_t *base = d.base ? d.base + (uint64_t)chunk * d.chunk_bytes : nullptr;
     const uint32_t nbytes = (uint32_t)(((uint64_t)n * F_::EB + 7) / 8);
-    const uint32_t m0 = d.mode[0], m1 = d.mode[1];
+    const uint32_t m0 = d.mode[0], m1 = d.mode[1], kind0 = d.kind[0], kind1 = d.kind[1], per0 = d.period[0], per1 = d.period[1];
+    if (WHOLE && !valid) return;                    // nothing below synchronises the workgroup
     for (uint32_t i = 0; i < rows; i++) {
         const uint32_t run = i * S + L.s;
         const uint32_t done = run * F_::EPR;                                                       // elements before this run
-        const uint32_t nel = n > done ? (n - done < (uint32_t)F_::EPR ? n - done : (uint32_t)F_::EPR) : 0;
+        const uint32_t nel = WHOLE ? (uint32_t)F_::EPR : (n > done ? (n - done < (uint32_t)F_::EPR ? n - done : (uint32_t)F_::EPR) : 0);
         const uint32_t nsym = (nel + F_::GRP - 1) / F_::GRP;                                       // a last partial group is filled with zeros
         // a field's symbols of this run: P (and Q where a run is 16 symbols of 8 bits)
         uint64_t P0 = 0, P1 = 0, Q0 = 0, Q1 = 0;
@@ -298,13 +304,13 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
             if (base) v = xor4(v, load_run(base + (uint64_t)run * 16, vb));
             split_run4<FMT>(v, P0, Q0, P1, Q1);
         }
-        const bool full = __all(nsym == (uint32_t)F_::G);
+        const bool full = WHOLE || __all(nsym == (uint32_t)F_::G);
         // the direct path of a flat code is written for one 64-bit word per run; a wide field cannot be flat
         // anyway (its alphabet of 256 is never used in full)
-        if (!kWide && m0 == ZC_MODE_HUFF && d.kind[0] == 1 && full) enc_flat_run<WRITE, F_::SB>(F0, P0, stream[0], L, S);
+        if (!kWide && m0 == ZC_MODE_HUFF && kind0 == 1 && full) enc_flat_run<WRITE, F_::SB>(F0, P0, stream[0], L, S);
         else if (m0 == ZC_MODE_HUFF) {
-            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F0, d.period[0], P0, Q0, nsym, enc[0], stream[0], L);
-            else enc_run<WRITE, F_::SB, F_::G, false>(F0, d.period[0], P0, Q0, nsym, enc[0], stream[0], L);
+            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F0, per0, P0, Q0, nsym, enc[0], stream[0], L);
+            else if (!WHOLE) enc_run<WRITE, F_::SB, F_::G, false>(F0, per0, P0, Q0, nsym, enc[0], stream[0], L);
         } else if (m0 == ZC_MODE_RAW && WRITE && nsym) {
             if (kWide) { reinterpret_cast<uint64_t *>(stream[0])[2 * run] = P0; reinterpret_cast<uint64_t *>(stream[0])[2 * run + 1] = Q0; }
             else {
@@ -312,10 +318,10 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
                 if ((run & 1) == 0 && done + F_::EPR >= n) reinterpret_cast<uint64_t *>(stream[0])[run + 1] = 0;
             }
         }
-        if (!kWide && m1 == ZC_MODE_HUFF && d.kind[1] == 1 && full) enc_flat_run<WRITE, F_::SB>(F1, P1, stream[1], L, S);
+        if (!kWide && m1 == ZC_MODE_HUFF && kind1 == 1 && full) enc_flat_run<WRITE, F_::SB>(F1, P1, stream[1], L, S);
         else if (m1 == ZC_MODE_HUFF) {
-            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F1, d.period[1], P1, Q1, nsym, enc[1], stream[1], L);
-            else enc_run<WRITE, F_::SB, F_::G, false>(F1, d.period[1], P1, Q1, nsym, enc[1], stream[1], L);
+            if (full) enc_run<WRITE, F_::SB, F_::G, true>(F1, per1, P1, Q1, nsym, enc[1], stream[1], L);
+            else if (!WHOLE) enc_run<WRITE, F_::SB, F_::G, false>(F1, per1, P1, Q1, nsym, enc[1], stream[1], L);
         } else if (m1 == ZC_MODE_RAW && WRITE && nsym) {
             if (kWide) { reinterpret_cast<uint64_t *>(stream[1])[2 * run] = P1; reinterpret_cast<uint64_t *>(stream[1])[2 * run + 1] = Q1; }
             else {
@@ -367,31 +373,39 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
     }
 }
 
+template <int FMT, bool WRITE>
+static void launch_encode_f(bool whole, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
+{
+    if (whole) hipLaunchKernelGGL((k_encode<FMT, WRITE, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units);
+    else hipLaunchKernelGGL((k_encode<FMT, WRITE, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units);
+}
+
 template <bool WRITE>
-static int launch_encode_t(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
+static int launch_encode_t(uint32_t fmt, bool whole, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
 {
     if (n_work == 0) return 0;
     switch (fmt) {
-    case ZC_FMT_BF16: hipLaunchKernelGGL((k_encode<ZC_FMT_BF16, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
-    case ZC_FMT_FP8_E4M3: hipLaunchKernelGGL((k_encode<ZC_FMT_FP8_E4M3, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
-    case ZC_FMT_FP4_E2M1_MX: hipLaunchKernelGGL((k_encode<ZC_FMT_FP4_E2M1_MX, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
-    case ZC_FMT_FP8_E4M3_BYTES: hipLaunchKernelGGL((k_encode<ZC_FMT_FP8_E4M3_BYTES, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
-    case ZC_FMT_FP4_E2M1_MX_BYTES: hipLaunchKernelGGL((k_encode<ZC_FMT_FP4_E2M1_MX_BYTES, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
-    case ZC_FMT_FP4_E2M1_NV: hipLaunchKernelGGL((k_encode<ZC_FMT_FP4_E2M1_NV, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
-    case ZC_FMT_FP8_E5M2: hipLaunchKernelGGL((k_encode<ZC_FMT_FP8_E5M2, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units); break;
+    case ZC_FMT_BF16: launch_encode_f<ZC_FMT_BF16, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP8_E4M3: launch_encode_f<ZC_FMT_FP8_E4M3, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP4_E2M1_MX: launch_encode_f<ZC_FMT_FP4_E2M1_MX, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP8_E4M3_BYTES: launch_encode_f<ZC_FMT_FP8_E4M3_BYTES, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP4_E2M1_MX_BYTES: launch_encode_f<ZC_FMT_FP4_E2M1_MX_BYTES, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP4_E2M1_NV: launch_encode_f<ZC_FMT_FP4_E2M1_NV, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP8_E5M2: launch_encode_f<ZC_FMT_FP8_E5M2, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
     default: return 1;
     }
     return (int)hipGetLastError();
 }
 
-int launch_sizes(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t, const uint32_t *d_enc, uint32_t *d_units, void *stream)
+// whole: every work item is up to four whole chunks of a tensor with 64 lanes per chunk and chunks of whole 1 KiB rows
+int launch_sizes(uint32_t fmt, bool whole, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream)
 {
-    return launch_encode_t<false>(fmt, d_descs, d_work, n_work, d_enc, d_units, (hipStream_t)stream);
+    return launch_encode_t<false>(fmt, whole, d_descs, d_work, n_work, d_enc, d_units, (hipStream_t)stream);
 }
 
-int launch_encode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t, const uint32_t *d_enc, void *stream)
+int launch_encode(uint32_t fmt, bool whole, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)
 {
-    return launch_encode_t<true>(fmt, d_descs, d_work, n_work, d_enc, nullptr, (hipStream_t)stream);
+    return launch_encode_t<true>(fmt, whole, d_descs, d_work, n_work, d_enc, nullptr, (hipStream_t)stream);
 }
 
 // ---------------------------------------------------------------------------- scan
