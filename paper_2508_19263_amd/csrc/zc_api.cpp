@@ -445,7 +445,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         fast_flag[t] = fast_ok;
         return ZC_OK;
     };
-    const uint32_t n_threads = T >= 64 ? std::min<uint32_t>(8, std::max(1u, std::thread::hardware_concurrency())) : 1;
+    const uint32_t n_threads = T >= 8 ? std::min<uint32_t>(std::min<uint32_t>(8, T / 2), std::max(1u, std::thread::hardware_concurrency())) : 1;
     if (n_threads <= 1) {
         for (uint32_t t = 0; t < T; t++) { st = build_one(t); if (st) return st; }
     } else {
