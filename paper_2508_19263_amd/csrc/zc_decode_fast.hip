@@ -372,6 +372,49 @@ __device__ __forceinline__ void huff_run(HuffStream &H, const FieldTab &T, uint3
     else huff_run_l<SB, G, false>(H, T, period, P0, P1, lane);
 }
 
+// Both element fields table decoded with the same refill period: one run of each, symbol by symbol side by
+// side, so that the two lookups of a step are in flight together (each stream alone is one dependent chain of
+// lookup -> shift -> lookup, and the wavefront spends most of that chain waiting for LDS).
+template <int SB, int G, int R, bool LONG>
+__device__ __forceinline__ void huff_run_pair(HuffStream &A, const FieldTab &TA, HuffStream &B, const FieldTab &TB,
+                                              uint64_t &PA0, uint64_t &PA1, uint64_t &PB0, uint64_t &PB1, uint32_t lane)
+{
+    constexpr int PER64 = 64 / SB;
+    constexpr int kPer32 = 32 / SB;
+    const uint32_t ma = TA.mask, mb = TB.mask;
+    const char *la = reinterpret_cast<const char *>(TA.lut), *lb = reinterpret_cast<const char *>(TB.lut);
+    uint32_t qa[4] = {0, 0, 0, 0}, qb[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int g = 0; g < G / R; g++) {
+        if ((g & 1) == 0) { huff_ring_service(A, lane); huff_ring_service(B, lane); }
+        uint32_t xa = (uint32_t)(A.W >> A.c), xb = (uint32_t)(B.W >> B.c);
+        uint32_t ua = 0, ub = 0;
+#pragma unroll
+        for (int j = 0; j < R; j++) {
+            const int jj = g * R + j;
+            uint32_t ea = *reinterpret_cast<const uint16_t *>(la + ((xa & ma) << 1));
+            uint32_t eb = *reinterpret_cast<const uint16_t *>(lb + ((xb & mb) << 1));
+            if (LONG && ea == 0) ea = long_code(TA, A, xa);
+            if (LONG && eb == 0) eb = long_code(TB, B, xb);
+            xa >>= (ea & 31u); xb >>= (eb & 31u);
+            ua += ea; ub += eb;
+            const int word = jj / kPer32, pos = jj % kPer32;
+            if (SB == 8) {
+                const uint32_t sel = pos == 0 ? 0x03020105u : pos == 1 ? 0x03020500u : pos == 2 ? 0x03050100u : 0x05020100u;
+                qa[word] = __builtin_amdgcn_perm(ea, qa[word], sel);
+                qb[word] = __builtin_amdgcn_perm(eb, qb[word], sel);
+            } else {
+                qa[word] |= (ea >> 8) << (pos * SB);
+                qb[word] |= (eb >> 8) << (pos * SB);
+            }
+        }
+        A.c += ua & 0xFFu; B.c += ub & 0xFFu;
+        huff_refill(A); huff_refill(B);
+    }
+    PA0 = (uint64_t)qa[0] | ((uint64_t)qa[1] << 32); PB0 = (uint64_t)qb[0] | ((uint64_t)qb[1] << 32);
+    if (G > PER64) { PA1 = (uint64_t)qa[2] | ((uint64_t)qa[3] << 32); PB1 = (uint64_t)qb[2] | ((uint64_t)qb[3] << 32); }
+}
+
 // one field of one run when it is not table decoded.  words_per_run = G*SB/32.
 template <int SB, int G>
 __device__ __forceinline__ void plain_run(uint32_t kind, __amdgpu_buffer_rsrc_t rs, uint32_t row, uint32_t lane, uint64_t konst, uint64_t &P0, uint64_t &P1)
@@ -449,13 +492,29 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     if (kind[0] == KIND_HUFF) huff_open(H0, tab[0], r0, ring0, lane);
     if (kind[1] == KIND_HUFF) huff_open(H1, tab[1], r1, ring1, lane);
 
+    // both fields table decoded on the same refill period: 1 = period 2 with codes beyond the lookup index in
+    // either table (a table without them has no empty entry, so the check never fires for it), 2 = period 2,
+    // 3 = period 4 (codes of at most 8 bits)
+    uint32_t pair = 0;
+    // built for BF16 only, where two coded fields occur (checkpoint deltas); in the other kernels the extra code
+    // costs the paths they do use 3 - 10 %
+    constexpr bool kPairs = FMT == ZC_FMT_BF16;
+    if (kPairs && kind[0] == KIND_HUFF && kind[1] == KIND_HUFF && p0 == p1) {
+        const bool any_long = uniform32(tab[0].lmax) > (uint32_t)kLutBits || uniform32(tab[1].lmax) > (uint32_t)kLutBits;
+        pair = p0 == 2 ? (any_long ? 1u : 2u) : p0 == 4 ? 3u : 0u;
+    }
     const uint32_t rows = cb / 1024;                          // 64 lanes x 16 bytes per row
     for (uint32_t row = 0; row < rows; row++) {
         uint64_t P0 = 0, P1 = 0, Q0 = 0, Q1 = 0;       // Q: symbols 8..15 of a run of 16 symbols of 8 bits
-        if (kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, Q0, lane);
-        else plain_run<F_::SB, F_::G>(kind[0], r0, row, lane, K0, P0, Q0);
-        if (kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, Q1, lane);
-        else plain_run<F_::SB, F_::G>(kind[1], r1, row, lane, K1, P1, Q1);
+        if (kPairs && pair == 1) huff_run_pair<F_::SB, F_::G, 2, true>(H0, tab[0], H1, tab[1], P0, Q0, P1, Q1, lane);
+        else if (kPairs && pair == 2) huff_run_pair<F_::SB, F_::G, 2, false>(H0, tab[0], H1, tab[1], P0, Q0, P1, Q1, lane);
+        else if (kPairs && pair == 3) huff_run_pair<F_::SB, F_::G, 4, false>(H0, tab[0], H1, tab[1], P0, Q0, P1, Q1, lane);
+        else {
+            if (kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, Q0, lane);
+            else plain_run<F_::SB, F_::G>(kind[0], r0, row, lane, K0, P0, Q0);
+            if (kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, Q1, lane);
+            else plain_run<F_::SB, F_::G>(kind[1], r1, row, lane, K1, P1, Q1);
+        }
         const uint4 j = join_run4<FMT>(P0, Q0, P1, Q1);
         u32x4 v = {j.x, j.y, j.z, j.w};
         if (XOR) v ^= __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)(row * 1024), 0);

@@ -641,6 +641,25 @@ def test_random_parameter_sweep():
         check_case(fmt, n, cb, S, policy, L, data=(src, sc), base=base, tag="sweep-%d" % case)
 
 
+def test_bf16_two_coded_fields_whole_chunks():
+    # BF16 with both fields table decoded on 64-lane whole chunks (the shape of a checkpoint delta), at every
+    # refill period the two fields can share: limits 16 (period 2, codes beyond the lookup index), 11
+    # (period 2), 8 (period 4), and unequal limits (different periods: the fields are decoded one by one)
+    rng = np.random.default_rng(77)
+    cb, S = 4096, 64
+    E = cb // 2
+    n = 5 * E + 1234
+    # few distinct exponents and sign+mantissa bytes with a long tail of rare ones: deep trees in both fields
+    ex = np.minimum(rng.geometric(0.45, n) - 1, 60).astype(np.uint16) + 100
+    sm = (np.minimum(rng.geometric(0.3, n) - 1, 90).astype(np.uint16) * 37) & 0xFF
+    bits = ((sm >> 7) << 15) | (ex << 7) | (sm & 0x7F)
+    src = torch.from_numpy(bits.astype(np.uint16).view(np.uint8).copy())
+    base = torch.from_numpy((rng.integers(0, 65536, n, dtype=np.uint16) & np.uint16(0x0181)).view(np.uint8).copy())
+    for L in ((16, 16, 0), (11, 11, 0), (8, 8, 0), (8, 16, 0), (16, 9, 0)):
+        for b in (None, base):
+            check_case(zc.FMT_BF16, n, cb, S, zc.POLICY_HUFF_ALL, L, data=(src, None), base=b, tag="two-coded-L%d-%d" % L[:2])
+
+
 def test_dictionary_compress_without_sync():
     # the queue-only call leaves the same containers as the synchronising one; sizes come from the headers
     k, v = wl.fp8_kv_pair(batch=1, heads=2, tokens=4096, seed=81)
