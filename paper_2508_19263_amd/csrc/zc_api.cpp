@@ -167,6 +167,48 @@ private:
 
 HostStage &host_stage() { static HostStage s; return s; }
 
+// ---- pinned landing buffers for what the host reads back -------------------------
+// A copy into pageable memory is staged by the runtime in pieces; into page-locked memory it is one
+// transfer.  Buffers are handed out one per call in flight and kept for the life of the process.
+class HostLanding {
+public:
+    uint8_t *acquire(uint64_t bytes, uint64_t *cap)
+    {
+        std::lock_guard<std::mutex> lock(m_);
+        for (size_t i = 0; i < free_.size(); i++)
+            if (free_[i].second >= bytes) {
+                uint8_t *b = free_[i].first; *cap = free_[i].second;
+                free_.erase(free_.begin() + (long)i);
+                return b;
+            }
+        if (!free_.empty()) { (void)hipHostFree(free_.back().first); free_.pop_back(); }     // too small: replace it
+        uint8_t *b = nullptr;
+        const uint64_t want = bytes + bytes / 2 + 4096;
+        if (hipHostMalloc((void **)&b, want, hipHostMallocDefault) != hipSuccess) return nullptr;
+        *cap = want;
+        return b;
+    }
+    void release(uint8_t *b, uint64_t cap)
+    {
+        std::lock_guard<std::mutex> lock(m_);
+        free_.push_back({b, cap});
+    }
+private:
+    std::mutex m_;
+    std::vector<std::pair<uint8_t *, uint64_t>> free_;
+};
+
+HostLanding &host_landing() { static HostLanding s; return s; }
+
+struct LandingLease {
+    uint8_t *ptr = nullptr;
+    uint64_t cap = 0;
+    explicit LandingLease(uint64_t bytes) { if (bytes) ptr = host_landing().acquire(bytes, &cap); }
+    ~LandingLease() { if (ptr) host_landing().release(ptr, cap); }
+    LandingLease(const LandingLease &) = delete;
+    LandingLease &operator=(const LandingLease &) = delete;
+};
+
 // ---- code construction from the device histograms ---------------------------
 struct FieldCode {
     uint64_t hist[256];
@@ -393,7 +435,21 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     TensorDev *d_descs = (TensorDev *)(ws + w.descs);
     uint64_t *d_hist = (uint64_t *)(ws + w.hist);
     // field split + histogram (a1-a3); not needed when the code comes from a dictionary
-    std::vector<uint64_t> hist(dict ? 0 : (size_t)T * 768);
+    // the histograms land in page-locked memory; what the code construction fills is allocated (and its pages
+    // touched) while the histogram kernel runs
+    const uint64_t hist_bytes = dict ? 0 : (uint64_t)T * 768 * 8;
+    LandingLease landing(hist_bytes);
+    if (hist_bytes && !landing.ptr) return ZC_ERR_DEVICE;
+    const uint64_t *hist = reinterpret_cast<const uint64_t *>(landing.ptr);
+    std::vector<FieldCode> codes;
+    std::vector<uint32_t> enc;
+    std::vector<uint8_t> blobs, fast_flag;
+    auto allocate_tables = [&]() {
+        codes.resize((size_t)T * 3);
+        enc.assign((size_t)T * 768, 0);
+        blobs.assign((size_t)T * kBlobBytes, 0);
+        fast_flag.assign(T, 0);
+    };
     if (!dict) {
         const Piece first[3] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
                                 {w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem)},
@@ -403,16 +459,13 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         HIP_TRY(hipMemsetAsync(d_hist, 0, (uint64_t)T * 3 * 256 * 8, hs));
         LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
         if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), (int)scale_block(g.fmt), d_hist, stream));
-        HIP_TRY(hipMemcpyAsync(hist.data(), d_hist, hist.size() * 8, hipMemcpyDeviceToHost, hs));
+        HIP_TRY(hipMemcpyAsync(landing.ptr, d_hist, hist_bytes, hipMemcpyDeviceToHost, hs));
+        allocate_tables();
         HIP_TRY(hipStreamSynchronize(hs));
-    }
+    } else allocate_tables();
 
     // code construction on the host (a4): tensors are independent, so a large set is split over a few threads
-    std::vector<FieldCode> codes((size_t)T * 3);
     std::vector<WorkItem> fast_work, whole_work, slow_work;
-    std::vector<uint32_t> enc((size_t)T * 768, 0);
-    std::vector<uint8_t> blobs((size_t)T * kBlobBytes, 0);
-    std::vector<uint8_t> fast_flag(T, 0);
     auto build_one = [&](uint32_t t) -> zc_status {
         FieldCode *fc = &codes[(size_t)t * 3];
         const zc_status s1 = dict ? codes_from_dictionary(g, tensors[t].n_elems, *dict, fc)
@@ -520,8 +573,11 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         for (uint32_t t = 0; t < T; t++) tensors[t].out_bytes = 0;
         return launch_encoders();
     }
-    std::vector<ScanOut> scan(T);
-    HIP_TRY(hipMemcpyAsync(scan.data(), ws + w.scan, T * sizeof(ScanOut), hipMemcpyDeviceToHost, hs));
+    // page-locked, so that the copy is queued and the encoder behind it without the host waiting in between
+    LandingLease scan_landing((uint64_t)T * sizeof(ScanOut));
+    if (!scan_landing.ptr) return ZC_ERR_DEVICE;
+    const ScanOut *scan = reinterpret_cast<const ScanOut *>(scan_landing.ptr);
+    HIP_TRY(hipMemcpyAsync(scan_landing.ptr, ws + w.scan, T * sizeof(ScanOut), hipMemcpyDeviceToHost, hs));
     if (roomy) {
         // wait for the copy only, not for the encoder queued behind it
         hipEvent_t copied;
@@ -539,7 +595,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         tensors[t].info.total_bytes = total;
         if (!stats_only && total > tensors[t].comp_capacity) return ZC_ERR_BUFFER_TOO_SMALL;
     }
-    if (scan_out) *scan_out = scan;
+    if (scan_out) scan_out->assign(scan, scan + T);
     if (stats_only || roomy) return ZC_OK;
     return launch_encoders();
 }
