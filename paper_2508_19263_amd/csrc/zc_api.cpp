@@ -4,8 +4,11 @@
 
 #include <cmath>
 #include <algorithm>
+#include <condition_variable>
 #include <cstring>
+#include <functional>
 #include <mutex>
+#include <optional>
 #include <thread>
 #include <vector>
 
@@ -207,6 +210,59 @@ struct LandingLease {
     ~LandingLease() { if (ptr) host_landing().release(ptr, cap); }
     LandingLease(const LandingLease &) = delete;
     LandingLease &operator=(const LandingLease &) = delete;
+};
+
+// ---- a few threads for the per-tensor code construction ------------------------
+// Tensors are independent, so a large set is split into contiguous ranges, one per thread; the calling
+// thread takes the first range.  The destructor joins whatever was started, so an early return between
+// construction and run() is safe (the workers then leave without doing anything).
+class CodeCrew {
+public:
+    CodeCrew(uint32_t n_items, uint32_t n_threads, const std::function<zc_status(uint32_t)> &fn)
+        : n_(n_items), k_(n_threads < 1 ? 1 : n_threads), fn_(fn), status_(k_, ZC_OK)
+    {
+        for (uint32_t k = 1; k < k_; k++)
+            pool_.emplace_back([this, k] {
+                {
+                    std::unique_lock<std::mutex> lock(m_);
+                    cv_.wait(lock, [this] { return state_ != 0; });
+                    if (state_ == 2) return;
+                }
+                range(k);
+            });
+    }
+    ~CodeCrew() { open(2); for (auto &t : pool_) t.join(); }
+    CodeCrew(const CodeCrew &) = delete;
+    CodeCrew &operator=(const CodeCrew &) = delete;
+    zc_status run()
+    {
+        open(1);
+        range(0);
+        for (auto &t : pool_) t.join();
+        pool_.clear();
+        for (uint32_t k = 0; k < k_; k++) if (status_[k]) return status_[k];
+        return ZC_OK;
+    }
+private:
+    void open(int state)
+    {
+        { std::lock_guard<std::mutex> lock(m_); if (state_ == 0) state_ = state; }
+        cv_.notify_all();
+    }
+    void range(uint32_t k)
+    {
+        for (uint32_t t = (uint32_t)((uint64_t)n_ * k / k_); t < (uint32_t)((uint64_t)n_ * (k + 1) / k_); t++) {
+            const zc_status s1 = fn_(t);
+            if (s1) { status_[k] = s1; return; }
+        }
+    }
+    uint32_t n_, k_;
+    std::function<zc_status(uint32_t)> fn_;
+    std::vector<zc_status> status_;
+    std::vector<std::thread> pool_;
+    std::mutex m_;
+    std::condition_variable cv_;
+    int state_ = 0;          // 0 = wait, 1 = go, 2 = leave
 };
 
 // ---- code construction from the device histograms ---------------------------
@@ -434,9 +490,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     }
     TensorDev *d_descs = (TensorDev *)(ws + w.descs);
     uint64_t *d_hist = (uint64_t *)(ws + w.hist);
-    // field split + histogram (a1-a3); not needed when the code comes from a dictionary
-    // the histograms land in page-locked memory; what the code construction fills is allocated (and its pages
-    // touched) while the histogram kernel runs
+    // The histograms land in page-locked memory; what the code construction fills is allocated (and its pages
+    // touched) while the histogram kernel runs.
     const uint64_t hist_bytes = dict ? 0 : (uint64_t)T * 768 * 8;
     LandingLease landing(hist_bytes);
     if (hist_bytes && !landing.ptr) return ZC_ERR_DEVICE;
@@ -450,22 +505,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         blobs.assign((size_t)T * kBlobBytes, 0);
         fast_flag.assign(T, 0);
     };
-    if (!dict) {
-        const Piece first[3] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
-                                {w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem)},
-                                {w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem)}};
-        st = host_stage().upload(ws, w.descs, w.chunk_work, first, 3, hs);
-        if (st) return st;
-        HIP_TRY(hipMemsetAsync(d_hist, 0, (uint64_t)T * 3 * 256 * 8, hs));
-        LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
-        if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), (int)scale_block(g.fmt), d_hist, stream));
-        HIP_TRY(hipMemcpyAsync(landing.ptr, d_hist, hist_bytes, hipMemcpyDeviceToHost, hs));
-        allocate_tables();
-        HIP_TRY(hipStreamSynchronize(hs));
-    } else allocate_tables();
-
-    // code construction on the host (a4): tensors are independent, so a large set is split over a few threads
-    std::vector<WorkItem> fast_work, whole_work, slow_work;
+    // code construction on the host (a4), one tensor
     auto build_one = [&](uint32_t t) -> zc_status {
         FieldCode *fc = &codes[(size_t)t * 3];
         const zc_status s1 = dict ? codes_from_dictionary(g, tensors[t].n_elems, *dict, fc)
@@ -498,23 +538,33 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         fast_flag[t] = fast_ok;
         return ZC_OK;
     };
-    const uint32_t n_threads = T >= 8 ? std::min<uint32_t>(std::min<uint32_t>(8, T / 2), std::max(1u, std::thread::hardware_concurrency())) : 1;
-    if (n_threads <= 1) {
-        for (uint32_t t = 0; t < T; t++) { st = build_one(t); if (st) return st; }
+    // The worker threads are started once the histogram kernel is queued and before the wait for it, so that
+    // their start-up (tens of microseconds each) is hidden behind it; they sleep until run() opens the gate.
+    // With a dictionary there is nothing to wait for and little to do per tensor: one thread.
+    const uint32_t n_threads = (!dict && T >= 8) ? std::min<uint32_t>(std::min<uint32_t>(8, T / 2), std::max(1u, std::thread::hardware_concurrency())) : 1;
+    std::optional<CodeCrew> crew;
+    // field split + histogram (a1-a3); not needed when the code comes from a dictionary
+    if (!dict) {
+        const Piece first[3] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
+                                {w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem)},
+                                {w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem)}};
+        st = host_stage().upload(ws, w.descs, w.chunk_work, first, 3, hs);
+        if (st) return st;
+        HIP_TRY(hipMemsetAsync(d_hist, 0, (uint64_t)T * 3 * 256 * 8, hs));
+        LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
+        if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), (int)scale_block(g.fmt), d_hist, stream));
+        HIP_TRY(hipMemcpyAsync(landing.ptr, d_hist, hist_bytes, hipMemcpyDeviceToHost, hs));
+        crew.emplace(T, n_threads, build_one);
+        allocate_tables();
+        HIP_TRY(hipStreamSynchronize(hs));
     } else {
-        std::vector<zc_status> status(n_threads, ZC_OK);
-        std::vector<std::thread> pool;
-        auto range = [&](uint32_t k) {
-            for (uint32_t t = (uint32_t)((uint64_t)T * k / n_threads); t < (uint32_t)((uint64_t)T * (k + 1) / n_threads); t++) {
-                const zc_status s1 = build_one(t);
-                if (s1) { status[k] = s1; return; }
-            }
-        };
-        for (uint32_t k = 1; k < n_threads; k++) pool.emplace_back(range, k);
-        range(0);
-        for (auto &th : pool) th.join();
-        for (uint32_t k = 0; k < n_threads; k++) if (status[k]) return status[k];
+        crew.emplace(T, n_threads, build_one);
+        allocate_tables();
     }
+
+    st = crew->run();
+    if (st) return st;
+    std::vector<WorkItem> fast_work, whole_work, slow_work;
     uint64_t all_chunks = 0;
     for (uint32_t t = 0; t < T; t++) all_chunks += ncs[t];
     const uint32_t fast_step = g.S == 64 ? kWavesPerGroup : sub_slots_per_group(g.S, all_chunks);    // chunks per fast work item
