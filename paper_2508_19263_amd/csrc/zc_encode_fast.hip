@@ -99,7 +99,9 @@ __global__ __launch_bounds__(256) void k_sizes_fp8(const TensorDev *descs, const
 
 __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables)
 {
+    constexpr uint32_t kSeg = 256, kRing = 2048;                // words: 16 bytes per lane; 32 words per lane
     __shared__ uint32_t pair[256];
+    __shared__ __attribute__((aligned(16))) uint32_t stage[kWavesPerGroup * kRing];
     const WorkItem it = work[blockIdx.x];
     const TensorDev *dp = descs + it.tensor;
     pair[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + 512 + threadIdx.x];
@@ -122,6 +124,7 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
     const __amdgpu_buffer_rsrc_t es = rsrc_of(comp + payload + 16 * a0, (uint32_t)((b0 - a0) * 16));
     const __amdgpu_buffer_rsrc_t ms = rsrc_of(comp + payload + 16 * a1, E / 2);
     const char *pair_lut = reinterpret_cast<const char *>(pair);
+    uint32_t *const ring = stage + (threadIdx.x >> 6) * kRing;
     const uint32_t two = 2;
 
     uint64_t acc = 0;           // bits not yet written, next free bit = nacc (< 32 between groups)
@@ -129,10 +132,15 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
     int32_t k = 0;              // unread bits the decoder would hold at this point
     uint32_t pend = 0, p0 = 0, p1 = 0;     // words the decoder has asked for and we still owe, and where they go
     uint32_t wpos = 0;          // words of the stream handed out so far
+    uint32_t flushed = 0;       // words of the stream that have left the ring
     const uint32_t rows = E / 1024;
-    for (uint32_t row = 0; row < rows; row++) {
-        u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(src, (int)(lane * 16), (int)(row * 1024), 0);
-        if (has_base) v ^= __builtin_amdgcn_raw_buffer_load_b128(bas, (int)(lane * 16), (int)(row * 1024), 0);
+    // the source (and the base of a delta) is fetched two rows ahead, into two register sets used in turn
+    auto fetch = [&](uint32_t row, u32x4 &x, u32x4 &y) {
+        row = row < rows ? row : rows - 1;
+        x = __builtin_amdgcn_raw_buffer_load_b128(src, (int)(lane * 16), (int)(row * 1024), 0);
+        if (has_base) y = __builtin_amdgcn_raw_buffer_load_b128(bas, (int)(lane * 16), (int)(row * 1024), 0);
+    };
+    auto encode_row = [&](const u32x4 &v, uint32_t row) {
         // ---- sign+mantissa nibbles of the run, packed (symbol j at bits 4j)
         uint32_t m[2];
 #pragma unroll
@@ -170,15 +178,46 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
             nacc += len;
             k -= (int32_t)len;
             if (nacc >= 32) {
-                __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, es, (int)(p0 * 4), 0, 0);
+                ring[p0 & (kRing - 1)] = (uint32_t)acc;
                 acc >>= 32; nacc -= 32; p0 = p1; pend--;
             }
         }
+        // Whole segments that are complete leave the ring, 16 bytes per lane: all of them, so that after every
+        // row the ring starts at the segment of the oldest word still owed.  A word is owed for at most 16 steps
+        // (64 bits at one bit per symbol), in which at most 1024 positions are handed out; with the segment
+        // rounding and the 256 positions of the next row the ring never holds more than 1536 words.
+#pragma unroll 1
+        for (int guard = 0; guard < (int)(kRing / kSeg); guard++) {
+            if (wpos < flushed + kSeg || __ballot(pend > 0 && p0 < flushed + kSeg) != 0) break;
+            const u32x4 w = *reinterpret_cast<const u32x4 *>(ring + ((flushed + 4 * lane) & (kRing - 1)));
+            __builtin_amdgcn_raw_buffer_store_b128(w, es, (int)((flushed + 4 * lane) * 4), 0, 0);
+            flushed += kSeg;
+        }
+    };
+    u32x4 xa, ya = {0, 0, 0, 0}, xb, yb = {0, 0, 0, 0};
+    fetch(0, xa, ya);
+    fetch(1, xb, yb);
+    uint32_t row = 0;
+    for (; row + 1 < rows; row += 2) {
+        const u32x4 va = xa ^ ya;
+        fetch(row + 2, xa, ya);
+        encode_row(va, row);
+        const u32x4 vb = xb ^ yb;
+        fetch(row + 3, xb, yb);
+        encode_row(vb, row + 1);
     }
-    // the words still owed to the decoder (a partial word and look-ahead words), then zero padding
-    if (pend > 0) { __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, es, (int)(p0 * 4), 0, 0); acc >>= 32; p0 = p1; pend--; }
-    if (pend > 0) { __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, es, (int)(p0 * 4), 0, 0); pend--; }
-    if (lane < ((4 - (wpos & 3)) & 3)) __builtin_amdgcn_raw_buffer_store_b32(0u, es, (int)((wpos + lane) * 4), 0, 0);
+    if (row < rows) encode_row(xa ^ ya, row);
+    // the words still owed to the decoder (a partial word and look-ahead words) and the zero padding of the
+    // last 16-byte unit go into the ring too; then everything left in it leaves in 16-byte pieces
+    if (pend > 0) { ring[p0 & (kRing - 1)] = (uint32_t)acc; acc >>= 32; p0 = p1; pend--; }
+    if (pend > 0) { ring[p0 & (kRing - 1)] = (uint32_t)acc; pend--; }
+    if (lane < ((4 - (wpos & 3)) & 3)) ring[(wpos + lane) & (kRing - 1)] = 0;
+    const uint32_t end = (wpos + 3) & ~3u;                      // words of the stream with its padding
+#pragma unroll 1
+    for (uint32_t at = flushed + 4 * lane; __any(at < end); at += kSeg) {
+        const u32x4 w = *reinterpret_cast<const u32x4 *>(ring + (at & (kRing - 1)));
+        __builtin_amdgcn_raw_buffer_store_b128(w, es, (int)(at < end ? at * 4 : 0xFFFFFFF0u), 0, 0);
+    }
 }
 
 // ---------------------------------------------------------------------------------------

@@ -660,6 +660,32 @@ def test_bf16_two_coded_fields_whole_chunks():
             check_case(zc.FMT_BF16, n, cb, S, zc.POLICY_HUFF_ALL, L, data=(src, None), base=b, tag="two-coded-L%d-%d" % L[:2])
 
 
+def test_fp8_encoder_uneven_lanes():
+    # 64-lane FP8 chunks whose lanes produce bits at very different rates: half of the lanes see one exponent
+    # only (1-bit codes: a word stays owed for 8 to 16 steps) while the others use the long codes and ask for a
+    # word almost every step, so the encoder's staging ring holds many complete words behind an owed one and
+    # several segments leave it at once.  Also with lanes swapped every few rows.
+    rng = np.random.default_rng(4242)
+    cb, S = 65536, 64
+    n = 3 * cb + 5000
+    j = np.arange(n)
+    lane = (j // 16) % 64
+    row = (j % cb) // 1024
+    for variant in range(3):
+        if variant == 0:
+            cheap = lane < 32
+        elif variant == 1:
+            cheap = ((lane + row // 5) % 64) < 32
+        else:
+            cheap = lane != 63                       # one busy lane among idle ones
+        ex = np.where(cheap, 7, rng.integers(0, 16, n))
+        sm = rng.integers(0, 16, n)
+        b = ((sm & 8) << 4) | (ex << 3) | (sm & 7)
+        src = torch.from_numpy(b.astype(np.uint8))
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            check_case(zc.FMT_FP8_E4M3, n, cb, S, policy, data=(src, None), tag="uneven-%d" % variant)
+
+
 def test_dictionary_compress_without_sync():
     # the queue-only call leaves the same containers as the synchronising one; sizes come from the headers
     k, v = wl.fp8_kv_pair(batch=1, heads=2, tokens=4096, seed=81)
