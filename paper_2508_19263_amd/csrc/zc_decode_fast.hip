@@ -328,22 +328,37 @@ __device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uin
 #pragma unroll
     for (int g = 0; g < G / R; g++) {
         if ((g & 1) == 0) huff_ring_service(H, lane);
-        uint32_t x = (uint32_t)(H.W >> H.c);
-        uint32_t used = 0;
+        const uint32_t x0 = (uint32_t)(H.W >> H.c);
+        uint32_t x = x0, used = 0, e[R];
+#pragma unroll
+        for (int j = 0; j < R; j++) {
+            e[j] = *reinterpret_cast<const uint16_t *>(lut + ((x & mask) << 1));
+            x >>= (e[j] & 31u);
+        }
+        if (LONG) {
+            // An empty entry stands for a code longer than the index; it shifts by nothing, so the entries after
+            // it are empty too and the last one tells.  Rare: the whole step is then done again with the search.
+            if (__any(e[R - 1] == 0)) {
+                x = x0;
+#pragma unroll
+                for (int j = 0; j < R; j++) {
+                    e[j] = *reinterpret_cast<const uint16_t *>(lut + ((x & mask) << 1));
+                    if (e[j] == 0) e[j] = long_code(T, H, x);
+                    x >>= (e[j] & 31u);
+                }
+            }
+        }
 #pragma unroll
         for (int j = 0; j < R; j++) {
             const int jj = g * R + j;
-            uint32_t e = *reinterpret_cast<const uint16_t *>(lut + ((x & mask) << 1));
-            if (LONG && e == 0) e = long_code(T, H, x);
-            x >>= (e & 31u);
-            used += e;
+            used += e[j];
             constexpr int kPer32 = 32 / SB;
             const int word = jj / kPer32, pos = jj % kPer32;
             if (SB == 8) {
                 // byte 1 of the entry (the symbol) into byte `pos` of the word
                 const uint32_t sel = pos == 0 ? 0x03020105u : pos == 1 ? 0x03020500u : pos == 2 ? 0x03050100u : 0x05020100u;
-                q[word] = __builtin_amdgcn_perm(e, q[word], sel);
-            } else q[word] |= (e >> 8) << (pos * SB);
+                q[word] = __builtin_amdgcn_perm(e[j], q[word], sel);
+            } else q[word] |= (e[j] >> 8) << (pos * SB);
         }
         H.c += used & 0xFFu;           // the low bytes hold the lengths; their sum is at most 32
         huff_refill(H);
@@ -387,25 +402,40 @@ __device__ __forceinline__ void huff_run_pair(HuffStream &A, const FieldTab &TA,
 #pragma unroll
     for (int g = 0; g < G / R; g++) {
         if ((g & 1) == 0) { huff_ring_service(A, lane); huff_ring_service(B, lane); }
-        uint32_t xa = (uint32_t)(A.W >> A.c), xb = (uint32_t)(B.W >> B.c);
-        uint32_t ua = 0, ub = 0;
+        const uint32_t xa0 = (uint32_t)(A.W >> A.c), xb0 = (uint32_t)(B.W >> B.c);
+        uint32_t xa = xa0, xb = xb0, ua = 0, ub = 0, ea[R], eb[R];
+#pragma unroll
+        for (int j = 0; j < R; j++) {
+            ea[j] = *reinterpret_cast<const uint16_t *>(la + ((xa & ma) << 1));
+            eb[j] = *reinterpret_cast<const uint16_t *>(lb + ((xb & mb) << 1));
+            xa >>= (ea[j] & 31u); xb >>= (eb[j] & 31u);
+        }
+        if (LONG) {
+            // as in huff_run_r: one test per step for both fields, the step done again with the search when it hits
+            if (__any(ea[R - 1] == 0 || eb[R - 1] == 0)) {
+                xa = xa0; xb = xb0;
+#pragma unroll
+                for (int j = 0; j < R; j++) {
+                    ea[j] = *reinterpret_cast<const uint16_t *>(la + ((xa & ma) << 1));
+                    eb[j] = *reinterpret_cast<const uint16_t *>(lb + ((xb & mb) << 1));
+                    if (ea[j] == 0) ea[j] = long_code(TA, A, xa);
+                    if (eb[j] == 0) eb[j] = long_code(TB, B, xb);
+                    xa >>= (ea[j] & 31u); xb >>= (eb[j] & 31u);
+                }
+            }
+        }
 #pragma unroll
         for (int j = 0; j < R; j++) {
             const int jj = g * R + j;
-            uint32_t ea = *reinterpret_cast<const uint16_t *>(la + ((xa & ma) << 1));
-            uint32_t eb = *reinterpret_cast<const uint16_t *>(lb + ((xb & mb) << 1));
-            if (LONG && ea == 0) ea = long_code(TA, A, xa);
-            if (LONG && eb == 0) eb = long_code(TB, B, xb);
-            xa >>= (ea & 31u); xb >>= (eb & 31u);
-            ua += ea; ub += eb;
+            ua += ea[j]; ub += eb[j];
             const int word = jj / kPer32, pos = jj % kPer32;
             if (SB == 8) {
                 const uint32_t sel = pos == 0 ? 0x03020105u : pos == 1 ? 0x03020500u : pos == 2 ? 0x03050100u : 0x05020100u;
-                qa[word] = __builtin_amdgcn_perm(ea, qa[word], sel);
-                qb[word] = __builtin_amdgcn_perm(eb, qb[word], sel);
+                qa[word] = __builtin_amdgcn_perm(ea[j], qa[word], sel);
+                qb[word] = __builtin_amdgcn_perm(eb[j], qb[word], sel);
             } else {
-                qa[word] |= (ea >> 8) << (pos * SB);
-                qb[word] |= (eb >> 8) << (pos * SB);
+                qa[word] |= (ea[j] >> 8) << (pos * SB);
+                qb[word] |= (eb[j] >> 8) << (pos * SB);
             }
         }
         A.c += ua & 0xFFu; B.c += ub & 0xFFu;
