@@ -155,9 +155,19 @@ def other_workloads(torch, wl, zc, dev, extras):
     sb.decompress()
     torch.cuda.synchronize()
     ok_step = all(torch.equal(o[:s.numel()], s) for o, s in zip(sb.out, step_pages))
+    # the same pages with codes of their own, built on the device: histogram, codes, sizes, scan, encoder queued
+    t_own_sync = _time_ms(torch, lambda: sb.compress())
+    t_own_async = _time_ms(torch, lambda: sb.compress_async())
+    torch.cuda.synchronize()
+    sb.refresh_info()
+    sb.decompress()
+    torch.cuda.synchronize()
+    ok_step = ok_step and all(torch.equal(o[:s.numel()], s) for o, s in zip(sb.out, step_pages))
     out["c5_one_step_of_new_pages"] = {"tensors": len(step_pages), "pages": 32 * len(step_pages), "bytes": 32 * 2048 * len(step_pages),
                                        "compress_with_dictionary_ms": t_sync, "queued_without_wait_gpu_ms": t_async,
-                                       "queued_without_wait_host_us_per_call": host_us, "round_trip_bit_exact": bool(ok_step)}
+                                       "queued_without_wait_host_us_per_call": host_us,
+                                       "own_codes_compress_ms": t_own_sync, "own_codes_queued_without_wait_gpu_ms": t_own_async,
+                                       "round_trip_bit_exact": bool(ok_step)}
     del sb, step_pages
     del kv
     if extras:

@@ -150,8 +150,10 @@ uint64_t zc_workspace_bytes(const uint64_t *n_elems, uint32_t n_tensors, const z
  * into the chunk index, chunked encode (Sec. 3.1, 3.2, 3.4, 4).
  * d_src/d_xor_base/d_scales/d_dst/d_ws: device.  out_bytes, out_info (may be NULL): host.
  * dst_capacity must hold the result (zc_compress_bound always suffices), else
- * ZC_ERR_BUFFER_TOO_SMALL.  Synchronises the stream (the code is built on the host from
- * the device histogram).  n_elems == 0 gives a header-only container. */
+ * ZC_ERR_BUFFER_TOO_SMALL.  The code is built on the device from the device histogram, so the
+ * whole sequence is queued without a wait in between; the call then waits once, for the sizes
+ * (and for nothing but them when dst_capacity >= zc_compress_bound: the encoder is queued
+ * first).  n_elems == 0 gives a header-only container. */
 zc_status zc_compress(const void *d_src, uint64_t n_elems, const zc_params *params,
                       const void *d_xor_base, const void *d_scales,
                       void *d_dst, uint64_t dst_capacity, uint64_t *out_bytes, zc_info *out_info,
@@ -160,6 +162,14 @@ zc_status zc_compress(const void *d_src, uint64_t n_elems, const zc_params *para
 /* Same over a host array of tensors sharing one zc_params: one launch sequence for the set. */
 zc_status zc_compress_batch(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params,
                             void *d_ws, uint64_t ws_bytes, void *stream);
+/* zc_compress_batch without any wait on the stream: histogram, code construction, size pass, scan and
+ * encoder are queued and the call returns.  Every comp_capacity must be at least
+ * zc_compress_bound(n_elems) (else ZC_ERR_BUFFER_TOO_SMALL, nothing queued).  out_bytes and info are not
+ * filled in: once the stream has reached this point each container's header holds its size and its
+ * code, and zc_read_info or the decompress entry points read them from there.  d_ws must stay
+ * untouched until then. */
+zc_status zc_compress_batch_async(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params,
+                                  void *d_ws, uint64_t ws_bytes, void *stream);
 
 /* Static dictionaries (Sec. 3.3, 5.2: a code computed ahead of time on representative data and
  * reused while the exponent distribution stays stable, e.g. across K/V-cache time steps).

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <algorithm>
 #include <condition_variable>
+#include <cstdlib>
 #include <cstring>
 #include <functional>
 #include <mutex>
@@ -84,7 +85,7 @@ uint64_t get64(const uint8_t *p) { uint64_t v; std::memcpy(&v, p, 8); return v; 
 
 // ---- workspace carving ------------------------------------------------------
 struct Workspace {
-    uint64_t descs, hist_work, scale_work, chunk_work, fast_work, whole_work, hist, enc, units, scan, blobs, total, host_end;
+    uint64_t descs, hist_work, scale_work, chunk_work, fast_work, whole_work, other_work, hist, enc, units, scan, blobs, total, host_end;
     uint32_t n_hist_work, n_scale_work, n_chunk_work;
     uint64_t n_units;
 };
@@ -115,8 +116,9 @@ zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T,
     w->chunk_work = off; off = align256(off + cw * sizeof(WorkItem));
     w->fast_work = off; off = align256(off + cw * sizeof(WorkItem));
     w->whole_work = off; off = align256(off + cw * sizeof(WorkItem));
-    w->enc = off; off = align256(off + (uint64_t)T * 768 * 4);
+    w->other_work = off; off = align256(off + cw * sizeof(WorkItem));
     w->blobs = off; off = align256(off + (uint64_t)T * kBlobBytes);
+    w->enc = off; off = align256(off + (uint64_t)T * 768 * 4);      // last: written on the device when the code is built there
     w->host_end = off;
     w->hist = off; off = align256(off + (uint64_t)T * 3 * 256 * 8);
     w->units = off; off = align256(off + units * 4);
@@ -435,6 +437,14 @@ TensorDev make_desc(const zc_info &info)
 uint32_t sub_slots_per_group(uint32_t streams, uint64_t slots);
 void order_for_xcds(std::vector<WorkItem> &items);
 
+// The code of a compress call is built on the device unless the environment says ZC_HOST_CODES=1 (read once):
+// the host construction gives the same bits and is what dictionaries, statistics and training use anyway.
+bool device_codes_enabled()
+{
+    static const bool on = [] { const char *e = std::getenv("ZC_HOST_CODES"); return !(e && e[0] == '1'); }();
+    return on;
+}
+
 zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, void *d_ws, uint64_t ws_bytes, void *stream,
                        bool stats_only, std::vector<FieldCode> *codes_out, std::vector<ScanOut> *scan_out,
                        const zc_info *dict = nullptr, bool train = false, bool no_sync = false)
@@ -490,6 +500,143 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     }
     TensorDev *d_descs = (TensorDev *)(ws + w.descs);
     uint64_t *d_hist = (uint64_t *)(ws + w.hist);
+    const uint32_t *d_enc = (const uint32_t *)(ws + w.enc);
+    uint32_t *d_units = (uint32_t *)(ws + w.units);
+    // Geometry the specialised FP8 size/encode kernels take: 64 lanes and chunks of whole 1 KiB rows, or 4..32
+    // lanes per chunk (pages) for the sub-wavefront kernels as long as the tensor fits their 32-bit offsets.
+    // Whether the code suits them too (exponent refill period 4, i.e. a longest code of 5..8 bits, sign+mantissa
+    // flat coded or raw) is known once the code is: descs[t].route.
+    auto fast_shape = [&](uint32_t t) {
+        if (g.fmt != ZC_FMT_FP8_E4M3) return false;
+        return g.S == 64 ? g.chunk_bytes % 1024 == 0
+                         : (g.S >= 4 && g.chunk_bytes % (16 * g.S) == 0 && tensors[t].n_elems <= 0xF0000000ull);
+    };
+    const bool whole_shape = g.S == 64 && g.chunk_bytes % 1024 == 0;       // the generic encoder's whole-chunk build
+    uint64_t all_chunks = 0;
+    for (uint32_t t = 0; t < T; t++) all_chunks += ncs[t];
+    const uint32_t fast_step = g.S == 64 ? kWavesPerGroup : sub_slots_per_group(g.S, all_chunks);    // chunks per fast work item
+    bool roomy = !stats_only;
+    for (uint32_t t = 0; t < T && roomy; t++) roomy = tensors[t].comp_capacity >= zc_compress_bound(tensors[t].n_elems, params);
+    if (no_sync && !roomy) return ZC_ERR_BUFFER_TOO_SMALL;
+
+    // Work lists of the size pass and the encoder.  fast: whole chunks for the FP8 kernels (route 1); whole: whole
+    // chunks for the generic encoder's 64-lane build; other: whole chunks for the generic encoder where neither
+    // of those applies to the geometry but the FP8 kernels might have (route 0 only); slow: everything else (a short
+    // last chunk, odd geometries).
+    std::vector<WorkItem> fast_work, whole_work, other_work, slow_work;
+    // stream sizes (a5) and their exclusive scan into the chunk index (a6)
+    auto launch_sizes_and_scan = [&]() -> zc_status {
+        if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, stream));
+        else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 0, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
+        LAUNCH_TRY(launch_sizes(g.fmt, true, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, d_units, stream));
+        LAUNCH_TRY(launch_sizes(g.fmt, false, true, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, d_units, stream));
+        LAUNCH_TRY(launch_sizes(g.fmt, false, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, d_units, stream));
+        LAUNCH_TRY(launch_scan(d_descs, T, (int)g.nf, d_units, (ScanOut *)(ws + w.scan), stream));
+        return ZC_OK;
+    };
+    // chunked encode (a7)
+    auto launch_encoders = [&]() -> zc_status {
+        if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, stream));
+        else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, true, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, false, true, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, false, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, stream));
+        return ZC_OK;
+    };
+    // When every destination can hold the worst case, the sizes need not be known on the host first: the encoder
+    // is queued right behind the scan and the sizes are read back meanwhile (or, for a call that does not
+    // synchronise, not at all: they are in the containers' headers).  Otherwise the host waits for the sizes and
+    // checks them before anything is written.  `landing`: page-locked, first the ScanOut of every tensor, then
+    // extra_bytes copied from d_extra.
+    auto encode_and_read_sizes = [&](LandingLease &landing, const void *d_extra, uint64_t extra_bytes) -> zc_status {
+        const uint64_t scan_bytes = (uint64_t)T * sizeof(ScanOut);
+        HIP_TRY(hipMemcpyAsync(landing.ptr, ws + w.scan, scan_bytes, hipMemcpyDeviceToHost, hs));
+        if (extra_bytes) HIP_TRY(hipMemcpyAsync(landing.ptr + scan_bytes, d_extra, extra_bytes, hipMemcpyDeviceToHost, hs));
+        if (roomy) {
+            // wait for the copies only, not for the encoder queued behind them
+            hipEvent_t copied;
+            HIP_TRY(hipEventCreateWithFlags(&copied, hipEventDisableTiming));
+            const hipError_t e1 = hipEventRecord(copied, hs);
+            const zc_status s1 = e1 == hipSuccess ? launch_encoders() : ZC_ERR_DEVICE;
+            const hipError_t e2 = e1 == hipSuccess ? hipEventSynchronize(copied) : e1;
+            (void)hipEventDestroy(copied);
+            if (s1) return s1;
+            if (e2 != hipSuccess) return ZC_ERR_DEVICE;
+        } else HIP_TRY(hipStreamSynchronize(hs));
+        const ScanOut *scan = reinterpret_cast<const ScanOut *>(landing.ptr);
+        for (uint32_t t = 0; t < T; t++) {
+            const uint64_t total = descs[t].payload_off + 16ull * scan[t].total_units;
+            tensors[t].out_bytes = total;
+            if (!stats_only && total > tensors[t].comp_capacity) return ZC_ERR_BUFFER_TOO_SMALL;
+        }
+        if (scan_out) scan_out->assign(scan, scan + T);
+        if (stats_only || roomy) return ZC_OK;
+        return launch_encoders();
+    };
+
+    if (!dict && !stats_only && !train && device_codes_enabled()) {
+        // ---- the code is built on the device (a4): nothing between the histogram and the encoder waits for the host
+        std::vector<uint8_t> blobs((size_t)T * kBlobBytes, 0);
+        const FieldCode no_code[3] = {};
+        for (uint32_t t = 0; t < T; t++) {
+            const uint64_t whole_chunks = tensors[t].n_elems / g.elems_per_chunk;
+            const bool fs = fast_shape(t);
+            descs[t].fast_shape = fs ? 1 : 0;
+            if (fs) for (uint64_t c = 0; c < whole_chunks; c += fast_step) fast_work.push_back({t, (uint32_t)c});
+            if (whole_shape) for (uint64_t c = 0; c < whole_chunks; c += kWavesPerGroup) whole_work.push_back({t, (uint32_t)c});
+            else if (fs) for (uint64_t c = 0; c < whole_chunks; c += cpi) other_work.push_back({t, (uint32_t)c});
+            for (uint64_t c = (fs || whole_shape) ? whole_chunks : 0; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
+            // the header without what depends on the code; k_codes fills that in
+            zc_info blank;
+            fill_info(g, params->policy, tensors[t].d_xor_base != nullptr, tensors[t].n_elems, ncs[t], no_code, 0, &blank);
+            serialize_blob(blank, &blobs[(size_t)t * kBlobBytes]);
+        }
+        order_for_xcds(fast_work);
+        order_for_xcds(whole_work);
+        order_for_xcds(other_work);
+        order_for_xcds(slow_work);
+        const Piece all[8] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
+                              {w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem)},
+                              {w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem)},
+                              {w.chunk_work, slow_work.data(), slow_work.size() * sizeof(WorkItem)},
+                              {w.fast_work, fast_work.data(), fast_work.size() * sizeof(WorkItem)},
+                              {w.whole_work, whole_work.data(), whole_work.size() * sizeof(WorkItem)},
+                              {w.other_work, other_work.data(), other_work.size() * sizeof(WorkItem)},
+                              {w.blobs, blobs.data(), blobs.size()}};
+        st = host_stage().upload(ws, w.descs, w.enc, all, 8, hs);
+        if (st) return st;
+        HIP_TRY(hipMemsetAsync(d_hist, 0, (uint64_t)T * 3 * 256 * 8, hs));
+        LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
+        if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), (int)scale_block(g.fmt), d_hist, stream));
+        CodeParams cp;
+        cp.fmt = g.fmt; cp.policy = params->policy; cp.nf = g.nf; cp.blob_bytes = (uint32_t)kBlobBytes; cp.run_len = (uint32_t)run_len(g.fmt, 0);
+        for (int f = 0; f < kMaxFields; f++) cp.limit[f] = f < (int)g.nf ? g.limit[f] : 0;
+        LAUNCH_TRY(launch_codes(d_descs, T, d_hist, cp, ws + w.blobs, (uint32_t *)(ws + w.enc), stream));
+        LAUNCH_TRY(launch_write_headers(d_descs, T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
+        st = launch_sizes_and_scan();
+        if (st) return st;
+        if (no_sync) {
+            for (uint32_t t = 0; t < T; t++) tensors[t].out_bytes = 0;
+            return launch_encoders();
+        }
+        LandingLease landing((uint64_t)T * (sizeof(ScanOut) + kBlobBytes));
+        if (!landing.ptr) return ZC_ERR_DEVICE;
+        st = encode_and_read_sizes(landing, ws + w.blobs, (uint64_t)T * kBlobBytes);
+        // what the device decided, for the caller's zc_info
+        const uint8_t *got = landing.ptr + (uint64_t)T * sizeof(ScanOut);
+        for (uint32_t t = 0; t < T; t++) {
+            const uint8_t *blob = got + (uint64_t)t * kBlobBytes;
+            FieldCode fc[3] = {};
+            for (uint32_t f = 0; f < g.nf; f++) {
+                fc[f].mode = blob[32 + 4 * f]; fc[f].lmax = blob[34 + 4 * f]; fc[f].konst = blob[35 + 4 * f];
+                std::memcpy(fc[f].len, blob + descs[t].table_off[f], (size_t)1 << sym_bits(g.fmt, (int)f));
+            }
+            fill_info(g, params->policy, tensors[t].d_xor_base != nullptr, tensors[t].n_elems, ncs[t], fc, tensors[t].out_bytes, &tensors[t].info);
+        }
+        return st;
+    }
+
+    // ---- the code is built on the host: a dictionary, statistics, training
     // The histograms land in page-locked memory; what the code construction fills is allocated (and its pages
     // touched) while the histogram kernel runs.
     const uint64_t hist_bytes = dict ? 0 : (uint64_t)T * 768 * 8;
@@ -498,12 +645,11 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     const uint64_t *hist = reinterpret_cast<const uint64_t *>(landing.ptr);
     std::vector<FieldCode> codes;
     std::vector<uint32_t> enc;
-    std::vector<uint8_t> blobs, fast_flag;
+    std::vector<uint8_t> blobs;
     auto allocate_tables = [&]() {
         codes.resize((size_t)T * 3);
         enc.assign((size_t)T * 768, 0);
         blobs.assign((size_t)T * kBlobBytes, 0);
-        fast_flag.assign(T, 0);
     };
     // code construction on the host (a4), one tensor
     auto build_one = [&](uint32_t t) -> zc_status {
@@ -521,21 +667,14 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
             for (int v = 0; v < A; v++)
                 enc[(size_t)t * 768 + f * 256 + v] = ((uint32_t)fc[f].len[v] << 16) | reverse_bits(fc[f].code[v], fc[f].len[v]);
         }
-        // FP8 shape the specialised size/encode kernels take: 64 lanes, chunks of whole 1 KiB rows,
-        // exponent refill period 4 (longest code 5..8 bits), sign+mantissa flat or raw.  Their table (slot of the
-        // unused third field) maps a pair of exponents to the two codes concatenated.
-        // With 4..32 lanes per chunk (pages) the sub-wavefront kernels take the same shape, as long as the tensor
-        // fits their 32-bit offsets.
-        const bool lanes_ok = g.S == 64 ? g.chunk_bytes % 1024 == 0
-                                        : (g.S >= 4 && g.chunk_bytes % (16 * g.S) == 0 && tensors[t].n_elems <= 0xF0000000ull);
-        const bool fast_ok = g.fmt == ZC_FMT_FP8_E4M3 && lanes_ok && fc[0].mode == ZC_MODE_HUFF &&
-                             descs[t].period[0] == 4 && (descs[t].kind[1] == 1 || descs[t].kind[1] == 2);
+        // the FP8 kernels' table (slot of the unused third field) maps a pair of exponents to the two codes concatenated
+        const bool fast_ok = fast_shape(t) && fc[0].mode == ZC_MODE_HUFF && descs[t].period[0] == 4 && (descs[t].kind[1] == 1 || descs[t].kind[1] == 2);
         if (fast_ok)
             for (uint32_t u = 0; u < 256; u++) {
                 const uint32_t e0 = u & 15, e1 = u >> 4, l0 = fc[0].len[e0], l1 = fc[0].len[e1];
                 enc[(size_t)t * 768 + 512 + u] = ((l0 + l1) << 16) | (enc[(size_t)t * 768 + e0] & 0xFFFFu) | ((enc[(size_t)t * 768 + e1] & 0xFFFFu) << l0);
             }
-        fast_flag[t] = fast_ok;
+        descs[t].route = fast_ok ? 1 : 0;
         return ZC_OK;
     };
     // The worker threads are started once the histogram kernel is queued and before the wait for it, so that
@@ -564,16 +703,11 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
 
     st = crew->run();
     if (st) return st;
-    std::vector<WorkItem> fast_work, whole_work, slow_work;
-    uint64_t all_chunks = 0;
-    for (uint32_t t = 0; t < T; t++) all_chunks += ncs[t];
-    const uint32_t fast_step = g.S == 64 ? kWavesPerGroup : sub_slots_per_group(g.S, all_chunks);    // chunks per fast work item
     for (uint32_t t = 0; t < T; t++) {
-        // whole chunks: the FP8 kernels where they apply, else (64 lanes, chunks of whole 1 KiB rows) the generic
-        // encoder's whole-chunk build; a short last chunk and every other geometry: the generic encoder
+        // the route is known, so every chunk is listed once
         const uint64_t whole_chunks = tensors[t].n_elems / g.elems_per_chunk;
-        const uint64_t n_fast = fast_flag[t] ? whole_chunks : 0;
-        const uint64_t n_whole = (!fast_flag[t] && g.S == 64 && g.chunk_bytes % 1024 == 0) ? whole_chunks : 0;
+        const uint64_t n_fast = descs[t].route ? whole_chunks : 0;
+        const uint64_t n_whole = (!descs[t].route && whole_shape) ? whole_chunks : 0;
         for (uint64_t c = 0; c < n_fast; c += fast_step) fast_work.push_back({t, (uint32_t)c});
         for (uint64_t c = 0; c < n_whole; c += kWavesPerGroup) whole_work.push_back({t, (uint32_t)c});
         for (uint64_t c = n_fast + n_whole; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
@@ -591,63 +725,23 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
                               {w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem)},
                               {w.chunk_work, slow_work.data(), slow_work.size() * sizeof(WorkItem)},
                               {w.fast_work, fast_work.data(), fast_work.size() * sizeof(WorkItem)},
-                              {w.enc, enc.data(), enc.size() * 4},
-                              {w.blobs, blobs.data(), stats_only ? 0 : blobs.size()}};
+                              {w.blobs, stats_only ? nullptr : blobs.data(), stats_only ? 0 : blobs.size()},
+                              {w.enc, enc.data(), enc.size() * 4}};
         st = host_stage().upload(ws, w.descs, w.host_end, all, 8, hs);
         if (st) return st;
     }
     if (!stats_only) LAUNCH_TRY(launch_write_headers(d_descs, T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
-
-    // stream sizes (a5) and their exclusive scan into the chunk index (a6)
-    const uint32_t *d_enc = (const uint32_t *)(ws + w.enc);
-    uint32_t *d_units = (uint32_t *)(ws + w.units);
-    if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, stream));
-    else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 0, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
-    LAUNCH_TRY(launch_sizes(g.fmt, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, d_units, stream));
-    LAUNCH_TRY(launch_sizes(g.fmt, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, d_units, stream));
-    LAUNCH_TRY(launch_scan(d_descs, T, (int)g.nf, d_units, (ScanOut *)(ws + w.scan), stream));
-    // chunked encode (a7).  When every destination can hold the worst case, the sizes need not be known on
-    // the host first: the encoder is queued right behind the scan and the sizes are read back meanwhile (or,
-    // for the call that does not synchronise, not at all: they are in the containers' headers).
-    auto launch_encoders = [&]() -> zc_status {
-        if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, stream));
-        else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
-        LAUNCH_TRY(launch_encode(g.fmt, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
-        LAUNCH_TRY(launch_encode(g.fmt, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, stream));
-        return ZC_OK;
-    };
-    bool roomy = !stats_only;
-    for (uint32_t t = 0; t < T && roomy; t++) roomy = tensors[t].comp_capacity >= zc_compress_bound(tensors[t].n_elems, params);
+    st = launch_sizes_and_scan();
+    if (st) return st;
     if (no_sync) {
-        if (!roomy) return ZC_ERR_BUFFER_TOO_SMALL;
         for (uint32_t t = 0; t < T; t++) tensors[t].out_bytes = 0;
         return launch_encoders();
     }
-    // page-locked, so that the copy is queued and the encoder behind it without the host waiting in between
     LandingLease scan_landing((uint64_t)T * sizeof(ScanOut));
     if (!scan_landing.ptr) return ZC_ERR_DEVICE;
-    const ScanOut *scan = reinterpret_cast<const ScanOut *>(scan_landing.ptr);
-    HIP_TRY(hipMemcpyAsync(scan_landing.ptr, ws + w.scan, T * sizeof(ScanOut), hipMemcpyDeviceToHost, hs));
-    if (roomy) {
-        // wait for the copy only, not for the encoder queued behind it
-        hipEvent_t copied;
-        HIP_TRY(hipEventCreateWithFlags(&copied, hipEventDisableTiming));
-        const hipError_t e1 = hipEventRecord(copied, hs);
-        st = e1 == hipSuccess ? launch_encoders() : ZC_ERR_DEVICE;
-        const hipError_t e2 = e1 == hipSuccess ? hipEventSynchronize(copied) : e1;
-        (void)hipEventDestroy(copied);
-        if (st) return st;
-        if (e2 != hipSuccess) return ZC_ERR_DEVICE;
-    } else HIP_TRY(hipStreamSynchronize(hs));
-    for (uint32_t t = 0; t < T; t++) {
-        const uint64_t total = descs[t].payload_off + 16ull * scan[t].total_units;
-        tensors[t].out_bytes = total;
-        tensors[t].info.total_bytes = total;
-        if (!stats_only && total > tensors[t].comp_capacity) return ZC_ERR_BUFFER_TOO_SMALL;
-    }
-    if (scan_out) scan_out->assign(scan, scan + T);
-    if (stats_only || roomy) return ZC_OK;
-    return launch_encoders();
+    st = encode_and_read_sizes(scan_landing, nullptr, 0);
+    for (uint32_t t = 0; t < T; t++) tensors[t].info.total_bytes = tensors[t].out_bytes;
+    return st;
 }
 
 // Can the specialised FP8 kernel decode this container's full chunks?
@@ -940,6 +1034,11 @@ zc_status zc_compress_batch_with_code(zc_tensor *tensors, uint32_t n_tensors, co
 {
     if (!code) return ZC_ERR_INVALID_ARG;
     return run_compress(tensors, n_tensors, params, d_ws, ws_bytes, stream, false, nullptr, nullptr, code, false);
+}
+
+zc_status zc_compress_batch_async(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params, void *d_ws, uint64_t ws_bytes, void *stream)
+{
+    return run_compress(tensors, n_tensors, params, d_ws, ws_bytes, stream, false, nullptr, nullptr, nullptr, false, true);
 }
 
 zc_status zc_compress_batch_with_code_async(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params, const zc_info *code,

@@ -58,6 +58,7 @@ __global__ __launch_bounds__(256) void k_sizes_fp8(const TensorDev *descs, const
     __shared__ uint32_t pair[256];
     const WorkItem it = work[blockIdx.x];
     const TensorDev *dp = descs + it.tensor;
+    if (!dp->route) return;                                      // whole workgroup: the code does not suit this kernel
     pair[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + 512 + threadIdx.x];
     __syncthreads();
     const uint32_t lane = threadIdx.x & 63;
@@ -104,6 +105,7 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
     __shared__ __attribute__((aligned(16))) uint32_t stage[kWavesPerGroup * kRing];
     const WorkItem it = work[blockIdx.x];
     const TensorDev *dp = descs + it.tensor;
+    if (!dp->route) return;                                      // whole workgroup: the code does not suit this kernel
     pair[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + 512 + threadIdx.x];
     __syncthreads();
     const uint32_t lane = threadIdx.x & 63;
@@ -250,6 +252,7 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
     __shared__ __attribute__((aligned(16))) uint32_t pairs_of_rows[WRITE ? kWavesPerGroup * 256 : 4];   // 4*S words per group
     const WorkItem it = work[blockIdx.x];
     const TensorDev *dp = descs + it.tensor;
+    if (!dp->route) return;                                      // whole workgroup: the code does not suit this kernel
     pair[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + 512 + threadIdx.x];
     __syncthreads();
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;

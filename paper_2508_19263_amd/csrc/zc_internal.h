@@ -67,7 +67,9 @@ struct alignas(16) TensorDev {
     uint32_t streams;         // S
     uint8_t mode[4], lmax[4], konst[4], period[4];
     uint8_t kind[4];          // how the specialised kernels treat the field (0 table, 1 flat code, 2 raw, 3 constant)
-    uint8_t pad_[8];
+    uint8_t fast_shape;       // compress: the tensor's geometry suits the specialised FP8 size/encode kernels
+    uint8_t route;            // compress: 1 = those kernels take its whole chunks (the code suits them too), 0 = the generic ones
+    uint8_t pad_[6];
 };
 
 struct WorkItem { uint32_t tensor, first; };   // `first`: first chunk / block of the item
@@ -85,14 +87,26 @@ struct ScanOut { uint32_t field_units[kMaxFields]; uint32_t total_units; };
 bool build_code_lengths(const uint64_t *hist, int alphabet, int limit, uint8_t *len_out);
 void assign_canonical(const uint8_t *len, int alphabet, uint16_t *code_out);
 
+// ---- code construction on the device (zc_codes.hip) ---------------------------
+struct CodeParams {
+    uint32_t fmt, policy, nf;
+    int32_t limit[kMaxFields];
+    uint32_t blob_bytes;      // stride of the per-tensor header blobs
+    uint32_t run_len;         // symbols per 16-byte run of an element field
+};
+// histograms (768 counters per tensor, as k_hist leaves them) -> encode tables, the code-dependent bytes of the
+// header blobs and of the descriptors (mode, lmax, konst, period, kind, route)
+int launch_codes(TensorDev *d_descs, uint32_t n_tensors, const uint64_t *d_hist, const CodeParams &cp, uint8_t *d_blobs, uint32_t *d_enc, void *stream);
+
 // ---- kernel launchers (zc_kernels.hip); all return a hipError_t as int ------
 int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                 int scales_view, uint64_t *d_hist, void *stream);
 int launch_write_headers(const TensorDev *d_descs, uint32_t n_tensors, const uint8_t *d_blobs, uint32_t blob_bytes, int n_fields, void *stream);
-int launch_sizes(uint32_t fmt, bool whole, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+// generic_only: skip tensors whose whole chunks the specialised FP8 kernels take (route 1)
+int launch_sizes(uint32_t fmt, bool whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                  const uint32_t *d_enc_tables, uint32_t *d_units, void *stream);
 int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, const uint32_t *d_units, ScanOut *d_out, void *stream);
-int launch_encode(uint32_t fmt, bool whole, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+int launch_encode(uint32_t fmt, bool whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                   const uint32_t *d_enc_tables, void *stream);
 int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
                   const TensorDev *single, uint32_t first_slot, void *stream);

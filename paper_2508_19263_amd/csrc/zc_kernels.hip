@@ -254,12 +254,13 @@ __device__ __forceinline__ uint32_t enc_finish(EncField &F, uint8_t *stream, con
 // WHOLE: the launch covers only whole chunks of tensors with 64 lanes per chunk (one wavefront per chunk, every
 // run complete), which lets the compiler drop the lane-group masks and every partial-run path.
 template <int FMT, bool WRITE, bool WHOLE>
-__global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units)
+__global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units, int generic_only)
 {
     using F_ = Fmt<FMT>;
     __shared__ uint32_t enc[3][256];
     __shared__ TensorDev dsh;                       // a copy the compiler knows no store of this kernel can change
     const WorkItem it = work[blockIdx.x];
+    if (generic_only && descs[it.tensor].route) return;        // whole workgroup: these chunks belong to the FP8 kernels
     if (threadIdx.x == 0) dsh = descs[it.tensor];
     for (uint32_t i = threadIdx.x; i < 3 * 256; i += 256) (&enc[0][0])[i] = enc_tables[(uint64_t)it.tensor * 768 + i];
     __syncthreads();
@@ -374,38 +375,38 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
 }
 
 template <int FMT, bool WRITE>
-static void launch_encode_f(bool whole, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
+static void launch_encode_f(bool whole, int generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
 {
-    if (whole) hipLaunchKernelGGL((k_encode<FMT, WRITE, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units);
-    else hipLaunchKernelGGL((k_encode<FMT, WRITE, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units);
+    if (whole) hipLaunchKernelGGL((k_encode<FMT, WRITE, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, generic_only);
+    else hipLaunchKernelGGL((k_encode<FMT, WRITE, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, generic_only);
 }
 
 template <bool WRITE>
-static int launch_encode_t(uint32_t fmt, bool whole, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
+static int launch_encode_t(uint32_t fmt, bool whole, int generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
 {
     if (n_work == 0) return 0;
     switch (fmt) {
-    case ZC_FMT_BF16: launch_encode_f<ZC_FMT_BF16, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
-    case ZC_FMT_FP8_E4M3: launch_encode_f<ZC_FMT_FP8_E4M3, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
-    case ZC_FMT_FP4_E2M1_MX: launch_encode_f<ZC_FMT_FP4_E2M1_MX, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
-    case ZC_FMT_FP8_E4M3_BYTES: launch_encode_f<ZC_FMT_FP8_E4M3_BYTES, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
-    case ZC_FMT_FP4_E2M1_MX_BYTES: launch_encode_f<ZC_FMT_FP4_E2M1_MX_BYTES, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
-    case ZC_FMT_FP4_E2M1_NV: launch_encode_f<ZC_FMT_FP4_E2M1_NV, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
-    case ZC_FMT_FP8_E5M2: launch_encode_f<ZC_FMT_FP8_E5M2, WRITE>(whole, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_BF16: launch_encode_f<ZC_FMT_BF16, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP8_E4M3: launch_encode_f<ZC_FMT_FP8_E4M3, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP4_E2M1_MX: launch_encode_f<ZC_FMT_FP4_E2M1_MX, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP8_E4M3_BYTES: launch_encode_f<ZC_FMT_FP8_E4M3_BYTES, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP4_E2M1_MX_BYTES: launch_encode_f<ZC_FMT_FP4_E2M1_MX_BYTES, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP4_E2M1_NV: launch_encode_f<ZC_FMT_FP4_E2M1_NV, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP8_E5M2: launch_encode_f<ZC_FMT_FP8_E5M2, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
     default: return 1;
     }
     return (int)hipGetLastError();
 }
 
 // whole: every work item is up to four whole chunks of a tensor with 64 lanes per chunk and chunks of whole 1 KiB rows
-int launch_sizes(uint32_t fmt, bool whole, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream)
+int launch_sizes(uint32_t fmt, bool whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream)
 {
-    return launch_encode_t<false>(fmt, whole, d_descs, d_work, n_work, d_enc, d_units, (hipStream_t)stream);
+    return launch_encode_t<false>(fmt, whole, generic_only ? 1 : 0, d_descs, d_work, n_work, d_enc, d_units, (hipStream_t)stream);
 }
 
-int launch_encode(uint32_t fmt, bool whole, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)
+int launch_encode(uint32_t fmt, bool whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)
 {
-    return launch_encode_t<true>(fmt, whole, d_descs, d_work, n_work, d_enc, nullptr, (hipStream_t)stream);
+    return launch_encode_t<true>(fmt, whole, generic_only ? 1 : 0, d_descs, d_work, n_work, d_enc, nullptr, (hipStream_t)stream);
 }
 
 // ---------------------------------------------------------------------------- scan

@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_BUFFER_TOO_SMALL, ERR_CORRUPT, ERR_DEV
 EXPORTS = ["zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_compress_batch", "zc_read_info",
            "zc_decompress", "zc_decompress_chunks", "zc_decompress_batch", "zc_decompress_batch_plan",
            "zc_decompress_batch_run", "zc_stats", "zc_build_code", "zc_train_code", "zc_compress_with_code",
-           "zc_compress_batch_with_code", "zc_compress_batch_with_code_async", "zc_code_stale",
+           "zc_compress_batch_with_code", "zc_compress_batch_with_code_async", "zc_compress_batch_async", "zc_code_stale",
            "zc_status_string"]
 
 
@@ -103,6 +103,8 @@ def lib():
         L.zc_compress_batch_with_code.argtypes = [C.POINTER(Tensor), u32, C.POINTER(Params), C.POINTER(Info), vp, u64, vp]
         L.zc_compress_batch_with_code_async.restype = C.c_int
         L.zc_compress_batch_with_code_async.argtypes = [C.POINTER(Tensor), u32, C.POINTER(Params), C.POINTER(Info), vp, u64, vp]
+        L.zc_compress_batch_async.restype = C.c_int
+        L.zc_compress_batch_async.argtypes = [C.POINTER(Tensor), u32, C.POINTER(Params), vp, u64, vp]
         L.zc_read_info.restype = C.c_int
         L.zc_read_info.argtypes = [vp, u64, C.c_int, C.POINTER(Info), vp]
         L.zc_decompress.restype = C.c_int
@@ -318,11 +320,16 @@ class Batch:
                    "zc_compress_batch_with_code")
         return [int(self.arr[i].out_bytes) for i in range(self.n)]
 
-    def compress_async(self, code):
-        """Queue the compression with a static dictionary and return without waiting; call refresh_info()
-        (which waits) before container(), decompress() or plan_decompress()."""
-        _check(lib().zc_compress_batch_with_code_async(self.arr, self.n, C.byref(self.p), C.byref(code), _ptr(self.ws), self.ws.numel(), _stream()),
-               "zc_compress_batch_with_code_async")
+    def compress_async(self, code=None):
+        """Queue the compression (with a static dictionary if one is given, else with codes built on the device)
+        and return without waiting; call refresh_info() (which waits) before container(), decompress() or
+        plan_decompress()."""
+        if code is None:
+            _check(lib().zc_compress_batch_async(self.arr, self.n, C.byref(self.p), _ptr(self.ws), self.ws.numel(), _stream()),
+                   "zc_compress_batch_async")
+        else:
+            _check(lib().zc_compress_batch_with_code_async(self.arr, self.n, C.byref(self.p), C.byref(code), _ptr(self.ws), self.ws.numel(), _stream()),
+                   "zc_compress_batch_with_code_async")
 
     def refresh_info(self):
         """Read every container's header back (blocking) after compress_async()."""

@@ -715,6 +715,77 @@ def test_dictionary_compress_without_sync():
     assert st == zc.ERR_BUFFER_TOO_SMALL
 
 
+def test_compress_without_sync_and_host_built_codes():
+    # zc_compress_batch_async queues histogram, code construction (on the device), size pass, scan and encoder
+    # and returns; the containers equal the oracle's, their sizes are in the headers.  Mixed shapes: a tensor the
+    # specialised FP8 kernels take, one whose exponent code is too short for them, a constant one, a ragged one.
+    rng = np.random.default_rng(99)
+    cb = 4096
+    srcs = [wl.fp8_weight(9 * cb + 77, seed=91),
+            torch.from_numpy(((rng.integers(0, 2, 6 * cb) + 7) << 3).astype(np.uint8)),      # two exponents: 1-bit codes
+            torch.full((3 * cb,), 0x38, dtype=torch.uint8),
+            wl.fp8_weight(123, seed=92)]
+    for S in (64, 8):
+        p, po = zc.params(zc.FMT_FP8_E4M3, cb, streams=S), o.params(o.FP8_E4M3, cb, streams=S)
+        bt = zc.Batch([dev(s) for s in srcs], [s.numel() for s in srcs], p)
+        for rep in range(2):                                  # twice: the workspace is reused
+            bt.compress_async()
+            sizes = bt.refresh_info()
+            for i, s in enumerate(srcs):
+                want = o.compress(s.numpy(), s.numel(), po)
+                assert sizes[i] == len(want) and np.array_equal(bt.container(i).cpu().numpy(), want), (S, rep, i)
+        outs = bt.decompress()
+        torch.cuda.synchronize()
+        for out, s in zip(outs, srcs):
+            assert torch.equal(out.cpu()[:s.numel()], s)
+    # the same call with the code built on the host (what ZC_HOST_CODES=1 selects): a fresh process, as the
+    # switch is read once
+    import os, subprocess, sys
+    script = (
+        "import sys, numpy as np, torch\n"
+        "sys.path.insert(0, %r)\n"
+        "from paper_2508_19263_amd import zc, workloads as wl\n"
+        "from oracle import zc_oracle as o\n"
+        "for fmt, ofmt in ((zc.FMT_FP8_E4M3, o.FP8_E4M3), (zc.FMT_BF16, o.BF16)):\n"
+        "    s = wl.fp8_weight(70000, seed=5) if fmt == zc.FMT_FP8_E4M3 else wl.bf16_weight(35000, seed=5).view(torch.uint8).reshape(-1)\n"
+        "    n = 70000 if fmt == zc.FMT_FP8_E4M3 else 35000\n"
+        "    comp, info = zc.compress(s.cuda(), n, zc.params(fmt, 4096))\n"
+        "    want = o.compress(s.numpy(), n, o.params(ofmt, 4096))\n"
+        "    assert np.array_equal(comp.cpu().numpy(), want)\n"
+        "print('host codes ok')\n") % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, ZC_HOST_CODES="1")
+    r = subprocess.run([sys.executable, "-c", script], env=env, capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0 and "host codes ok" in r.stdout, r.stdout + r.stderr
+
+
+def test_device_code_construction_wide_weights():
+    # 2^28 + some BF16 values: 16 x the symbol count no longer fits 32 bits, so the device package-merge runs on
+    # 64-bit weights.  The oracle's code lengths for the tensor's field histograms (counted here with torch) must
+    # be the tables in the container, and the round trip must be exact.
+    n = (1 << 28) + 4096 * 3 + 5
+    g = torch.Generator(device=DEV).manual_seed(7)
+    # exponents geometric around 120 (deep tree, many ties among the rare ones), sign+mantissa skewed
+    ex = (120 + torch.clamp((torch.empty(n, device=DEV).exponential_(0.7, generator=g)).to(torch.int32), max=50)).to(torch.int32)
+    sm = torch.clamp((torch.empty(n, device=DEV).exponential_(0.05, generator=g)).to(torch.int32), max=255)
+    bits = (((sm >> 7) << 15) | (ex << 7) | (sm & 0x7F)).to(torch.int16)
+    del ex, sm
+    src = bits.view(torch.uint8).reshape(-1)
+    p = zc.params(zc.FMT_BF16, 262144, (16, 12, 0), 64)
+    comp, info = zc.compress(src, n, p)
+    v = bits.to(torch.int32) & 0xFFFF
+    h_e = torch.bincount((v >> 7) & 0xFF, minlength=256).cpu().numpy().astype(np.uint64)
+    h_m = torch.bincount(((v >> 8) & 0x80) | (v & 0x7F), minlength=256).cpu().numpy().astype(np.uint64)
+    del v
+    assert int(h_e.sum()) == n and 16 * n >= 1 << 32
+    for f, (h, limit) in enumerate(((h_e, 16), (h_m, 12))):
+        want = np.asarray(o.code_lengths(h, limit), dtype=np.uint8)
+        got = np.frombuffer(bytes(info.code_len[f]), dtype=np.uint8)
+        assert info.mode[f] == zc.MODE_HUFF and np.array_equal(got, want), f
+    out, _ = zc.decompress(comp, info)
+    torch.cuda.synchronize()
+    assert torch.equal(out[:src.numel()], src)
+
+
 def test_tensor_beyond_4_gib():
     # One FP8 tensor of 4.5 GiB + a ragged tail: every byte offset past 2^32 must be computed in 64 bits.
     # The round trip is checked whole on the GPU; sampled chunks (first, the ones on both sides of the
