@@ -19,9 +19,13 @@
  *     Kernels are enqueued on it.  Calls that must read results back (noted
  *     below) synchronise that stream before returning.
  *   - The library never allocates or frees device memory: scratch space comes in
- *     through `d_ws`.  The only state it keeps between calls is one page-locked
- *     host buffer through which descriptors, work lists and tables are uploaded
- *     (allocated on first use, grown when needed, held until the process ends).
+ *     through `d_ws`.  The only state it keeps between calls is page-locked host
+ *     memory: one buffer through which descriptors, work lists and tables are
+ *     uploaded and a few through which sizes and headers are read back (allocated
+ *     on first use, grown when needed, held until the process ends).
+ *   - ZC_HOST_CODES=1 in the environment (read once) makes the compress calls build
+ *     their codes on the host instead of on the device: same containers, one more
+ *     wait per call.
  *   - Errors are returned as zc_status; nothing is thrown.  On error the
  *     destination contents are unspecified but nothing is written outside the
  *     capacities given.
@@ -180,8 +184,7 @@ zc_status zc_compress_batch_async(zc_tensor *tensors, uint32_t n_tensors, const 
  * total_bytes are those of the training tensor's container under it (nothing is written).
  * Synchronises.
  * zc_compress_with_code / zc_compress_batch_with_code code every tensor with that dictionary:
- * no histogram pass and no code construction, one synchronisation (to size the output) instead
- * of two.  The container is an ordinary one (it carries the dictionary's length tables), so
+ * no histogram pass and no code construction.  The container is an ordinary one (it carries the dictionary's length tables), so
  * every decompress entry point reads it.  A dictionary whose Huffman fields do not form a
  * complete prefix code over the whole alphabet is rejected with ZC_ERR_INVALID_ARG.
  * zc_code_stale (host arithmetic only) is the refresh test of Sec. 3.3: 1 when the container
