@@ -777,6 +777,15 @@ uint32_t s64_rings(const zc_info &info)
     return huff < 1 ? 1 : huff;
 }
 
+// Are both element fields stored plainly (flat code, raw, constant)?  Then the rows of a chunk do not depend on
+// each other and the 64-lane kernel may share a chunk among the four wavefronts of a workgroup.
+bool s64_split_ok(const zc_info &info)
+{
+    if (!s64_rings(info)) return false;
+    const TensorDev d = make_desc(info);
+    return d.kind[0] != 0 && d.kind[1] != 0;
+}
+
 // Can the sub-wavefront FP8 kernel (S < 64, e.g. K/V pages) decode this container's full chunks
 // into a destination of dst_bytes?
 bool fp8_sub_ok(const zc_info &info, uint64_t dst_bytes)
@@ -914,7 +923,10 @@ zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *
         const uint32_t n_full = (uint32_t)(info.n_elems / ((uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(info.format)));
         const uint32_t n_fast = (n_full + kWavesPerGroup - 1) / kWavesPerGroup;
         if (fk.ok) LAUNCH_TRY(launch_decode_fp8_fast(fk.exp_kind, fk.sm_kind, info.xor_delta != 0, nullptr, nullptr, n_fast, &d, stream));
-        else LAUNCH_TRY(launch_decode_s64(info.format, rings, info.xor_delta != 0, nullptr, nullptr, n_fast, &d, stream));
+        else {
+            const bool split = s64_split_ok(info);
+            LAUNCH_TRY(launch_decode_s64(info.format, rings, info.xor_delta != 0, split, nullptr, nullptr, split ? n_full : n_fast, &d, stream));
+        }
         first_slot = n_full;
     }
     if (first_slot < slots) {
@@ -1168,10 +1180,12 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
         }
         if (rings) rings = most;
     }
+    bool split = rings != 0;
+    for (uint32_t t = 0; t < n_tensors && split; t++) split = s64_split_ok(tensors[t].info);
     const bool fast = fk.ok || rings != 0 || sub;
     uint64_t all_slots = 0;
     for (uint32_t t = 0; t < n_tensors; t++) all_slots += tensors[t].d_chunk_ids ? tensors[t].n_chunk_ids : tensors[t].info.n_chunks;
-    const uint32_t spg = sub ? sub_slots_per_group(S, all_slots) : kWavesPerGroup;
+    const uint32_t spg = sub ? sub_slots_per_group(S, all_slots) : split ? 1u : kWavesPerGroup;
     std::vector<TensorDev> descs(n_tensors);
     std::vector<WorkItem> fast_work, work;
     for (uint32_t t = 0; t < n_tensors; t++) {
@@ -1213,7 +1227,7 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
     plan->format = fmt; plan->streams = S; plan->n_tensors = n_tensors;
     plan->n_fast_work = (uint32_t)fast_work.size(); plan->n_work = (uint32_t)work.size();
     plan->fast_exp_kind = (uint32_t)fk.exp_kind; plan->fast_sm_kind = (uint32_t)fk.sm_kind; plan->xor_delta = tensors[0].info.xor_delta;
-    plan->fast_kernel = fk.ok ? 1u : (rings ? 2u : (sub ? 3u : 0u)); plan->n_rings = sub ? spg : rings;
+    plan->fast_kernel = fk.ok ? 1u : (rings ? (split ? 4u : 2u) : (sub ? 3u : 0u)); plan->n_rings = sub ? spg : rings;
     plan->scattered = 0;
     for (uint32_t t = 0; t < n_tensors; t++) if (tensors[t].d_chunk_ids) plan->scattered = 1;
     plan->fast_work_offset = descs_bytes; plan->work_offset = descs_bytes + fast_bytes;
@@ -1229,8 +1243,8 @@ zc_status zc_decompress_batch_run(const zc_batch_plan *plan, const void *d_ws, v
     if (plan->n_fast_work && plan->fast_kernel == 1)
         LAUNCH_TRY(launch_decode_fp8_fast((int)plan->fast_exp_kind, (int)plan->fast_sm_kind, plan->xor_delta != 0, (const TensorDev *)ws,
                                           (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, stream));
-    else if (plan->n_fast_work && plan->fast_kernel == 2)
-        LAUNCH_TRY(launch_decode_s64(plan->format, plan->n_rings, plan->xor_delta != 0, (const TensorDev *)ws,
+    else if (plan->n_fast_work && (plan->fast_kernel == 2 || plan->fast_kernel == 4))
+        LAUNCH_TRY(launch_decode_s64(plan->format, plan->n_rings, plan->xor_delta != 0, plan->fast_kernel == 4, (const TensorDev *)ws,
                                      (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, stream));
     else if (plan->n_fast_work && plan->fast_kernel == 3)
         LAUNCH_TRY(launch_decode_fp8_sub(plan->streams, plan->xor_delta != 0, plan->scattered != 0, (const TensorDev *)ws,

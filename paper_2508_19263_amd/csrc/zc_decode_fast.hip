@@ -479,15 +479,19 @@ __device__ __forceinline__ bool stream_range(const TensorDev &d, const uint8_t *
     return true;
 }
 
+// split: the workgroup's four wavefronts share ONE chunk, each taking a quarter of its rows (the first also the
+// block scales).  Only for chunks whose element fields are both stored plainly (flat code, raw or constant):
+// their rows do not depend on each other, and four times the wavefronts hide four times the memory latency,
+// which is what a small set (few chunks per SIMD) is bound by.
 template <int FMT, bool XOR>
-__global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single)
+__global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single, int split)
 {
     using F_ = Fmt<FMT>;
     extern __shared__ __attribute__((aligned(16))) uint32_t rings[];     // [ring][wave][kRing2Words], sized by the host
     __shared__ FieldTab tab[F_::NF];
     __shared__ TensorDev dsh;
     WorkItem it;
-    if (use_single) { it.tensor = 0; it.first = blockIdx.x * kWavesPerGroup; }
+    if (use_single) { it.tensor = 0; it.first = blockIdx.x * (split ? 1u : kWavesPerGroup); }
     else it = work[blockIdx.x];
     if (threadIdx.x == 0) dsh = use_single ? single : descs[it.tensor];
     __syncthreads();
@@ -498,7 +502,7 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
         if (kind[f] == KIND_HUFF) build_field_tab(tab[f], d.comp + d.table_off[f], 1 << (f == 2 ? 8 : F_::SB), d.lmax[f]);
     }
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t chunk = uniform32(it.first + wave);
+    const uint32_t chunk = uniform32(it.first + (split ? 0u : wave));
     const uint32_t cb = uniform32(d.chunk_bytes);
     const uint32_t E = cb * 8 / F_::EB;
     const uint32_t n_full = (uint32_t)(uniform64(d.n_elems) / E);
@@ -534,7 +538,9 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
         pair = p0 == 2 ? (any_long ? 1u : 2u) : p0 == 4 ? 3u : 0u;
     }
     const uint32_t rows = cb / 1024;                          // 64 lanes x 16 bytes per row
-    for (uint32_t row = 0; row < rows; row++) {
+    if (split && (kind[0] == KIND_HUFF || kind[1] == KIND_HUFF)) return;          // the host never asks for this
+    const uint32_t row_begin = split ? wave * rows / kWavesPerGroup : 0u, row_end = split ? (wave + 1) * rows / kWavesPerGroup : rows;
+    for (uint32_t row = row_begin; row < row_end; row++) {
         uint64_t P0 = 0, P1 = 0, Q0 = 0, Q1 = 0;       // Q: symbols 8..15 of a run of 16 symbols of 8 bits
         if (kPairs && pair == 1) huff_run_pair<F_::SB, F_::G, 2, true>(H0, tab[0], H1, tab[1], P0, Q0, P1, Q1, lane);
         else if (kPairs && pair == 2) huff_run_pair<F_::SB, F_::G, 2, false>(H0, tab[0], H1, tab[1], P0, Q0, P1, Q1, lane);
@@ -551,7 +557,7 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
         __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
     }
 
-    if (F_::NF == 3) {
+    if (F_::NF == 3 && !(split && wave != 0)) {
         // block scales: one byte per 32 elements, 16 per run, the chunk's E/32 scales in rows of 1024
         constexpr int F2 = F_::NF - 1;
         const uint32_t n_sc = E / F_::SCALE;
@@ -572,15 +578,16 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
 }
 
 template <int FMT>
-static int launch_s64_x(bool xor_delta, uint32_t lds_bytes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single, hipStream_t st)
+static int launch_s64_x(bool xor_delta, int split, uint32_t lds_bytes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single, hipStream_t st)
 {
-    if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single);
-    else hipLaunchKernelGGL((k_decode_s64<FMT, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single);
+    if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, split);
+    else hipLaunchKernelGGL((k_decode_s64<FMT, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, split);
     return (int)hipGetLastError();
 }
 
-// n_rings: 1 or 2 rings per wavefront (2 only when both element fields are table decoded)
-int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+// n_rings: 1 or 2 rings per wavefront (2 only when both element fields are table decoded); split: one chunk per
+// work item, its rows shared by the four wavefronts (both element fields stored plainly)
+int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                       const TensorDev *single, void *stream)
 {
     if (n_work == 0) return 0;
@@ -589,13 +596,13 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const Tens
     const int use_single = single ? 1 : 0;
     const uint32_t lds = (n_rings >= 2 ? 2u : 1u) * kWavesPerGroup * kRing2Words * 4;
     switch (fmt) {
-    case ZC_FMT_BF16: return launch_s64_x<ZC_FMT_BF16>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
-    case ZC_FMT_FP8_E4M3: return launch_s64_x<ZC_FMT_FP8_E4M3>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
-    case ZC_FMT_FP4_E2M1_MX: return launch_s64_x<ZC_FMT_FP4_E2M1_MX>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
-    case ZC_FMT_FP8_E4M3_BYTES: return launch_s64_x<ZC_FMT_FP8_E4M3_BYTES>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
-    case ZC_FMT_FP4_E2M1_MX_BYTES: return launch_s64_x<ZC_FMT_FP4_E2M1_MX_BYTES>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
-    case ZC_FMT_FP4_E2M1_NV: return launch_s64_x<ZC_FMT_FP4_E2M1_NV>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
-    case ZC_FMT_FP8_E5M2: return launch_s64_x<ZC_FMT_FP8_E5M2>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_BF16: return launch_s64_x<ZC_FMT_BF16>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_FP8_E4M3: return launch_s64_x<ZC_FMT_FP8_E4M3>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_FP4_E2M1_MX: return launch_s64_x<ZC_FMT_FP4_E2M1_MX>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_FP8_E4M3_BYTES: return launch_s64_x<ZC_FMT_FP8_E4M3_BYTES>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_FP4_E2M1_MX_BYTES: return launch_s64_x<ZC_FMT_FP4_E2M1_MX_BYTES>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_FP4_E2M1_NV: return launch_s64_x<ZC_FMT_FP4_E2M1_NV>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
+    case ZC_FMT_FP8_E5M2: return launch_s64_x<ZC_FMT_FP8_E5M2>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
     default: return 1;
     }
 }

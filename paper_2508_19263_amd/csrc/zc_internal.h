@@ -117,7 +117,7 @@ int launch_decode_fp8_fast(int exp_kind, int sm_kind, bool xor_delta, const Tens
 int launch_decode_fp8_sub(uint32_t streams, bool xor_delta, bool scattered, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                           const TensorDev *single, uint32_t slots_per_group, void *stream);
 // any format, 64 lanes per chunk, full chunks (zc_decode_fast.hip); n_rings = element fields that are table decoded (1..2)
-int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                       const TensorDev *single, void *stream);
 // FP8, 64 lanes, full chunks, exponent codes <= 8 bits, sign+mantissa flat or raw (zc_encode_fast.hip)
 int launch_sizes_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream);
