@@ -95,7 +95,7 @@ constexpr uint64_t kBlobBytes = 1024;     // header + code-length tables of one 
 
 zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T, Workspace *w)
 {
-    uint64_t hw = 0, sw = 0, cw = 0, units = 0;
+    uint64_t hw = 0, sw = 0, cw = 0, ww = 0, units = 0;
     const uint32_t cpi = chunks_per_work_item(g.S);
     for (uint32_t t = 0; t < T; t++) {
         uint64_t nc;
@@ -105,9 +105,10 @@ zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T,
         hw += (bytes + kHistBlockBytes - 1) / kHistBlockBytes;
         if (g.nf == 3) sw += (n_elems[t] / scale_block(g.fmt) + kHistBlockBytes - 1) / kHistBlockBytes;
         cw += (nc + cpi - 1) / cpi;
+        ww += is_fp4(g.fmt) ? nc : (nc + cpi - 1) / cpi;          // FP4: one whole chunk per work item
         units += nc * g.nf;
     }
-    if (hw > 0x7FFFFFFFull || cw > 0x7FFFFFFFull || units > 0xFFFFFFFFull) return ZC_ERR_INVALID_ARG;
+    if (hw > 0x7FFFFFFFull || cw > 0x7FFFFFFFull || ww > 0x7FFFFFFFull || units > 0xFFFFFFFFull) return ZC_ERR_INVALID_ARG;
     uint64_t off = 0;
     // what the host writes comes first and is contiguous, so that it goes up in one copy
     w->descs = off; off = align256(off + (uint64_t)T * sizeof(TensorDev));
@@ -115,7 +116,7 @@ zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T,
     w->scale_work = off; off = align256(off + sw * sizeof(WorkItem));
     w->chunk_work = off; off = align256(off + cw * sizeof(WorkItem));
     w->fast_work = off; off = align256(off + cw * sizeof(WorkItem));
-    w->whole_work = off; off = align256(off + cw * sizeof(WorkItem));
+    w->whole_work = off; off = align256(off + ww * sizeof(WorkItem));
     w->other_work = off; off = align256(off + cw * sizeof(WorkItem));
     w->blobs = off; off = align256(off + (uint64_t)T * kBlobBytes);
     w->enc = off; off = align256(off + (uint64_t)T * 768 * 4);      // last: written on the device when the code is built there
@@ -512,6 +513,10 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
                          : (g.S >= 4 && g.chunk_bytes % (16 * g.S) == 0 && tensors[t].n_elems <= 0xF0000000ull);
     };
     const bool whole_shape = g.S == 64 && g.chunk_bytes % 1024 == 0;       // the generic encoder's whole-chunk build
+    // FP4 elements rarely compress, so their fields are stored plainly and a chunk's rows can be shared by the four
+    // wavefronts of a workgroup: one chunk per work item there
+    const int whole_mode = is_fp4(g.fmt) ? 2 : 1;
+    const uint32_t whole_step = whole_mode == 2 ? 1u : kWavesPerGroup;
     uint64_t all_chunks = 0;
     for (uint32_t t = 0; t < T; t++) all_chunks += ncs[t];
     const uint32_t fast_step = g.S == 64 ? kWavesPerGroup : sub_slots_per_group(g.S, all_chunks);    // chunks per fast work item
@@ -528,9 +533,9 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     auto launch_sizes_and_scan = [&]() -> zc_status {
         if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, stream));
         else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 0, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
-        LAUNCH_TRY(launch_sizes(g.fmt, true, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, d_units, stream));
-        LAUNCH_TRY(launch_sizes(g.fmt, false, true, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, d_units, stream));
-        LAUNCH_TRY(launch_sizes(g.fmt, false, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, d_units, stream));
+        LAUNCH_TRY(launch_sizes(g.fmt, whole_mode, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, d_units, stream));
+        LAUNCH_TRY(launch_sizes(g.fmt, 0, true, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, d_units, stream));
+        LAUNCH_TRY(launch_sizes(g.fmt, 0, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, d_units, stream));
         LAUNCH_TRY(launch_scan(d_descs, T, (int)g.nf, d_units, (ScanOut *)(ws + w.scan), stream));
         return ZC_OK;
     };
@@ -538,9 +543,9 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     auto launch_encoders = [&]() -> zc_status {
         if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, stream));
         else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
-        LAUNCH_TRY(launch_encode(g.fmt, true, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
-        LAUNCH_TRY(launch_encode(g.fmt, false, true, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, stream));
-        LAUNCH_TRY(launch_encode(g.fmt, false, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, whole_mode, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, 0, true, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, 0, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, stream));
         return ZC_OK;
     };
     // When every destination can hold the worst case, the sizes need not be known on the host first: the encoder
@@ -583,7 +588,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
             const bool fs = fast_shape(t);
             descs[t].fast_shape = fs ? 1 : 0;
             if (fs) for (uint64_t c = 0; c < whole_chunks; c += fast_step) fast_work.push_back({t, (uint32_t)c});
-            if (whole_shape) for (uint64_t c = 0; c < whole_chunks; c += kWavesPerGroup) whole_work.push_back({t, (uint32_t)c});
+            if (whole_shape) for (uint64_t c = 0; c < whole_chunks; c += whole_step) whole_work.push_back({t, (uint32_t)c});
             else if (fs) for (uint64_t c = 0; c < whole_chunks; c += cpi) other_work.push_back({t, (uint32_t)c});
             for (uint64_t c = (fs || whole_shape) ? whole_chunks : 0; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
             // the header without what depends on the code; k_codes fills that in
@@ -709,7 +714,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         const uint64_t n_fast = descs[t].route ? whole_chunks : 0;
         const uint64_t n_whole = (!descs[t].route && whole_shape) ? whole_chunks : 0;
         for (uint64_t c = 0; c < n_fast; c += fast_step) fast_work.push_back({t, (uint32_t)c});
-        for (uint64_t c = 0; c < n_whole; c += kWavesPerGroup) whole_work.push_back({t, (uint32_t)c});
+        for (uint64_t c = 0; c < n_whole; c += whole_step) whole_work.push_back({t, (uint32_t)c});
         for (uint64_t c = n_fast + n_whole; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
     }
     if (codes_out) *codes_out = codes;

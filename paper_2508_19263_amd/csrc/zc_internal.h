@@ -103,10 +103,12 @@ int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, 
                 int scales_view, uint64_t *d_hist, void *stream);
 int launch_write_headers(const TensorDev *d_descs, uint32_t n_tensors, const uint8_t *d_blobs, uint32_t blob_bytes, int n_fields, void *stream);
 // generic_only: skip tensors whose whole chunks the specialised FP8 kernels take (route 1)
-int launch_sizes(uint32_t fmt, bool whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+// whole: 0 = any chunks, 1 = up to four whole 64-lane chunks per work item, 2 = one such chunk per work item, shared
+// by the workgroup's four wavefronts
+int launch_sizes(uint32_t fmt, int whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                  const uint32_t *d_enc_tables, uint32_t *d_units, void *stream);
 int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, const uint32_t *d_units, ScanOut *d_out, void *stream);
-int launch_encode(uint32_t fmt, bool whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+int launch_encode(uint32_t fmt, int whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                   const uint32_t *d_enc_tables, void *stream);
 int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
                   const TensorDev *single, uint32_t first_slot, void *stream);

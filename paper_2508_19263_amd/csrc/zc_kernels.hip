@@ -253,8 +253,14 @@ __device__ __forceinline__ uint32_t enc_finish(EncField &F, uint8_t *stream, con
 // element array; false: the FP4 scale field.
 // WHOLE: the launch covers only whole chunks of tensors with 64 lanes per chunk (one wavefront per chunk, every
 // run complete), which lets the compiler drop the lane-group masks and every partial-run path.
+// shared (WHOLE only): a work item is ONE chunk for the four wavefronts of the workgroup.  When both element
+// fields are stored plainly (flat code, raw, constant) its rows do not depend on each other: the encoder gives
+// every wavefront a quarter of them, and the size pass needs no element data at all.  Otherwise the first
+// wavefront takes the chunk alone.  The host asks for this where plain element fields are the rule (FP4): four
+// times the wavefronts hide four times the memory latency, which is what bounds a set of few chunks.
 template <int FMT, bool WRITE, bool WHOLE>
-__global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units, int generic_only)
+__global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units, int generic_only,
+                                                int shared_chunk)
 {
     using F_ = Fmt<FMT>;
     __shared__ uint32_t enc[3][256];
@@ -268,7 +274,8 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
     const uint32_t S = WHOLE ? 64u : d.streams;
     const Lanes L = make_lanes(S);
     const uint32_t wave = threadIdx.x >> 6;
-    const uint32_t chunk = it.first + wave * (64 / S) + L.grp;
+    const bool shared = WHOLE && shared_chunk;
+    const uint32_t chunk = shared ? it.first : it.first + wave * (64 / S) + L.grp;
     const uint64_t E = (uint64_t)d.chunk_bytes * 8 / F_::EB;
     const uint64_t first = (uint64_t)chunk * E;
     // WHOLE: the host lists only whole chunks, up to four per work item; a wavefront beyond the last one idles
@@ -292,7 +299,23 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
     const uint32_t nbytes = (uint32_t)(((uint64_t)n * F_::EB + 7) / 8);
     const uint32_t m0 = d.mode[0], m1 = d.mode[1], kind0 = d.kind[0], kind1 = d.kind[1], per0 = d.period[0], per1 = d.period[1];
     if (WHOLE && !valid) return;                    // nothing below synchronises the workgroup
-    for (uint32_t i = 0; i < rows; i++) {
+    // a field whose rows can be placed without knowing the rows before them
+    const bool plain0 = !(m0 == ZC_MODE_HUFF && (kWide || kind0 != 1)), plain1 = !(m1 == ZC_MODE_HUFF && (kWide || kind1 != 1));
+    const bool plain = plain0 && plain1;
+    if (shared && !plain && wave != 0) return;
+    uint32_t row_begin = 0, row_end = rows;
+    if (shared && plain) { row_begin = wave * rows / kWavesPerGroup; row_end = (wave + 1) * rows / kWavesPerGroup; }
+    if (WHOLE && !WRITE && plain) {
+        // size pass: a flat code takes two words per run whatever the data, raw and constant fields are sized below
+        if (m0 == ZC_MODE_HUFF) F0.wpos = 2 * rows;
+        if (m1 == ZC_MODE_HUFF) F1.wpos = 2 * rows;
+        row_end = row_begin;
+        if (shared && wave != 0) return;
+    } else if (shared && plain) {
+        // a flat field's words lie row by row: start where this wavefront's rows start
+        F0.wpos = 2 * S * row_begin; F1.wpos = 2 * S * row_begin;
+    }
+    for (uint32_t i = row_begin; i < row_end; i++) {
         const uint32_t run = i * S + L.s;
         const uint32_t done = run * F_::EPR;                                                       // elements before this run
         const uint32_t nel = WHOLE ? (uint32_t)F_::EPR : (n > done ? (n - done < (uint32_t)F_::EPR ? n - done : (uint32_t)F_::EPR) : 0);
@@ -342,7 +365,7 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
     }
 
     // ---- FP4 block scales: one byte per 32 elements, runs of 16 bytes ----
-    if (F_::NF == 3) {
+    if (F_::NF == 3 && !(shared && wave != 0)) {
         EncField F2 = {0, 0, 0, 0, 0, 0, 0};
         const uint32_t ns = n / F_::SCALE;
         const uint32_t srows = (uint32_t)((E / F_::SCALE + 15) / 16 + S - 1) / S;
@@ -375,14 +398,14 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
 }
 
 template <int FMT, bool WRITE>
-static void launch_encode_f(bool whole, int generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
+static void launch_encode_f(int whole, int generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
 {
-    if (whole) hipLaunchKernelGGL((k_encode<FMT, WRITE, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, generic_only);
-    else hipLaunchKernelGGL((k_encode<FMT, WRITE, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, generic_only);
+    if (whole) hipLaunchKernelGGL((k_encode<FMT, WRITE, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, generic_only, whole == 2 ? 1 : 0);
+    else hipLaunchKernelGGL((k_encode<FMT, WRITE, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, generic_only, 0);
 }
 
 template <bool WRITE>
-static int launch_encode_t(uint32_t fmt, bool whole, int generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
+static int launch_encode_t(uint32_t fmt, int whole, int generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
 {
     if (n_work == 0) return 0;
     switch (fmt) {
@@ -398,13 +421,14 @@ static int launch_encode_t(uint32_t fmt, bool whole, int generic_only, const Ten
     return (int)hipGetLastError();
 }
 
-// whole: every work item is up to four whole chunks of a tensor with 64 lanes per chunk and chunks of whole 1 KiB rows
-int launch_sizes(uint32_t fmt, bool whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream)
+// whole: 1 = every work item is up to four whole chunks of a tensor with 64 lanes per chunk and chunks of whole
+// 1 KiB rows; 2 = every work item is one such chunk, shared by the workgroup's four wavefronts; 0 = any chunks
+int launch_sizes(uint32_t fmt, int whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream)
 {
     return launch_encode_t<false>(fmt, whole, generic_only ? 1 : 0, d_descs, d_work, n_work, d_enc, d_units, (hipStream_t)stream);
 }
 
-int launch_encode(uint32_t fmt, bool whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)
+int launch_encode(uint32_t fmt, int whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)
 {
     return launch_encode_t<true>(fmt, whole, generic_only ? 1 : 0, d_descs, d_work, n_work, d_enc, nullptr, (hipStream_t)stream);
 }
