@@ -483,9 +483,10 @@ __device__ __forceinline__ bool stream_range(const TensorDev &d, const uint8_t *
 // block scales).  Only for chunks whose element fields are both stored plainly (flat code, raw or constant):
 // their rows do not depend on each other, and four times the wavefronts hide four times the memory latency,
 // which is what a small set (few chunks per SIMD) is bound by.
-template <int FMT, bool XOR>
-__global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single, int split)
+template <int FMT, bool XOR, bool SPLIT>
+__global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single)
 {
+    constexpr bool split = SPLIT;
     using F_ = Fmt<FMT>;
     extern __shared__ __attribute__((aligned(16))) uint32_t rings[];     // [ring][wave][kRing2Words], sized by the host
     __shared__ FieldTab tab[F_::NF];
@@ -499,7 +500,7 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     uint32_t kind[F_::NF];
     for (int f = 0; f < F_::NF; f++) {
         kind[f] = uniform32(d.kind[f]);
-        if (kind[f] == KIND_HUFF) build_field_tab(tab[f], d.comp + d.table_off[f], 1 << (f == 2 ? 8 : F_::SB), d.lmax[f]);
+        if (kind[f] == KIND_HUFF && !(SPLIT && f < 2)) build_field_tab(tab[f], d.comp + d.table_off[f], 1 << (f == 2 ? 8 : F_::SB), d.lmax[f]);
     }
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t chunk = uniform32(it.first + (split ? 0u : wave));
@@ -523,8 +524,8 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     char *ring_base = reinterpret_cast<char *>(rings) + wave * (kRing2Words * 4);
     char *ring0 = ring_base, *ring1 = ring_base + (kind[0] == KIND_HUFF ? kWavesPerGroup * kRing2Words * 4 : 0);
     HuffStream H0, H1;
-    if (kind[0] == KIND_HUFF) huff_open(H0, tab[0], r0, ring0, lane);
-    if (kind[1] == KIND_HUFF) huff_open(H1, tab[1], r1, ring1, lane);
+    if (!SPLIT && kind[0] == KIND_HUFF) huff_open(H0, tab[0], r0, ring0, lane);
+    if (!SPLIT && kind[1] == KIND_HUFF) huff_open(H1, tab[1], r1, ring1, lane);
 
     // both fields table decoded on the same refill period: 1 = period 2 with codes beyond the lookup index in
     // either table (a table without them has no empty entry, so the check never fires for it), 2 = period 2,
@@ -532,7 +533,7 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     uint32_t pair = 0;
     // built for BF16 only, where two coded fields occur (checkpoint deltas); in the other kernels the extra code
     // costs the paths they do use 3 - 10 %
-    constexpr bool kPairs = FMT == ZC_FMT_BF16;
+    constexpr bool kPairs = FMT == ZC_FMT_BF16 && !SPLIT;
     if (kPairs && kind[0] == KIND_HUFF && kind[1] == KIND_HUFF && p0 == p1) {
         const bool any_long = uniform32(tab[0].lmax) > (uint32_t)kLutBits || uniform32(tab[1].lmax) > (uint32_t)kLutBits;
         pair = p0 == 2 ? (any_long ? 1u : 2u) : p0 == 4 ? 3u : 0u;
@@ -546,9 +547,9 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
         else if (kPairs && pair == 2) huff_run_pair<F_::SB, F_::G, 2, false>(H0, tab[0], H1, tab[1], P0, Q0, P1, Q1, lane);
         else if (kPairs && pair == 3) huff_run_pair<F_::SB, F_::G, 4, false>(H0, tab[0], H1, tab[1], P0, Q0, P1, Q1, lane);
         else {
-            if (kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, Q0, lane);
+            if (!SPLIT && kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, Q0, lane);
             else plain_run<F_::SB, F_::G>(kind[0], r0, row, lane, K0, P0, Q0);
-            if (kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, Q1, lane);
+            if (!SPLIT && kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, Q1, lane);
             else plain_run<F_::SB, F_::G>(kind[1], r1, row, lane, K1, P1, Q1);
         }
         const uint4 j = join_run4<FMT>(P0, Q0, P1, Q1);
@@ -580,8 +581,11 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
 template <int FMT>
 static int launch_s64_x(bool xor_delta, int split, uint32_t lds_bytes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single, hipStream_t st)
 {
-    if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, split);
-    else hipLaunchKernelGGL((k_decode_s64<FMT, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, split);
+    if (split) {
+        if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single);
+        else hipLaunchKernelGGL((k_decode_s64<FMT, false, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single);
+    } else if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single);
+    else hipLaunchKernelGGL((k_decode_s64<FMT, false, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single);
     return (int)hipGetLastError();
 }
 
