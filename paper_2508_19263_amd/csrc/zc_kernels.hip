@@ -518,18 +518,32 @@ struct DecField {
     uint32_t wpos;         // words of the stream taken so far by the group
     const uint8_t *ptr;    // stream start
     uint32_t words;        // stream length in words (reads beyond it return 0)
+    // The next words of the stream, fetched ahead of use: lane s of the group holds word base + s in `cur` and
+    // word base + S + s in `nxt` (base <= wpos < base + S).  A refill step hands out at most S words, all inside
+    // these two windows, so a lane gets its word from the lane that holds it instead of waiting for memory.
+    uint32_t base, cur, nxt;
 };
+
+__device__ __forceinline__ uint32_t stream_word(const DecField &D, uint32_t pos)
+{
+    return pos < D.words ? reinterpret_cast<const uint32_t *>(D.ptr)[pos] : 0u;
+}
 
 __device__ __forceinline__ void dec_refill(DecField &D, bool active, const Lanes &L)
 {
+    const uint32_t S = (uint32_t)__popcll(L.gmask);
     const bool need = active && D.c >= 32;
     const uint64_t bm = __ballot(need) & L.gmask;
-    if (need) {
-        const uint32_t pos = D.wpos + prefix_count(bm);
-        const uint32_t w = pos < D.words ? reinterpret_cast<const uint32_t *>(D.ptr)[pos] : 0u;
-        D.lo = D.hi; D.hi = w; D.c -= 32;
-    }
+    const uint32_t at = D.wpos + prefix_count(bm) - D.base;                 // 0 .. 2S-1 in the lanes that ask
+    const int holder = (int)((threadIdx.x & 63u) - L.s + (at & (S - 1)));
+    const uint32_t a = (uint32_t)__shfl((int)D.cur, holder, 64), b = (uint32_t)__shfl((int)D.nxt, holder, 64);
+    if (need) { D.lo = D.hi; D.hi = at < S ? a : b; D.c -= 32; }
     D.wpos += (uint32_t)__popcll(bm);
+    if (D.wpos - D.base >= S) {                                             // the first window is used up
+        D.cur = D.nxt;
+        D.base += S;
+        D.nxt = stream_word(D, D.base + S + L.s);
+    }
 }
 
 // decode symbols [j0, j0+R) of a run; symbol j goes to bit (j % PER64)*SB of P0 (j < PER64) or P1
@@ -573,14 +587,19 @@ __device__ __forceinline__ void dec_run(DecField &D, const FieldTab &T, uint32_t
     }
 }
 
-__device__ __forceinline__ DecField open_stream(const TensorDev &d, int f, uint32_t chunk, bool valid)
+__device__ __forceinline__ DecField open_stream(const TensorDev &d, int f, uint32_t chunk, bool valid, const Lanes &L)
 {
-    DecField D = {0, 0, 64, 0, d.comp, 0};
+    DecField D = {0, 0, 64, 0, d.comp, 0, 0, 0, 0};
     if (valid && (d.mode[f] == ZC_MODE_HUFF || d.mode[f] == ZC_MODE_RAW)) {
         const uint32_t *index = reinterpret_cast<const uint32_t *>(d.comp + d.index_off[f]);
         const uint64_t a = index[chunk], b = index[chunk + 1];
         const uint64_t lo = d.payload_off + 16 * a, hi = d.payload_off + 16 * b;
         if (a <= b && hi <= d.total_bytes) { D.ptr = d.comp + lo; D.words = (uint32_t)((hi - lo) / 4); }
+    }
+    if (d.mode[f] == ZC_MODE_HUFF) {
+        const uint32_t S = (uint32_t)__popcll(L.gmask);
+        D.cur = stream_word(D, L.s);
+        D.nxt = stream_word(D, S + L.s);
     }
     return D;
 }
@@ -615,7 +634,7 @@ __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const Wo
     uint8_t *dst = d.dst + (uint64_t)slot * d.chunk_bytes;
     const uint8_t *base = d.base ? d.base + (uint64_t)chunk * d.chunk_bytes : nullptr;
 
-    DecField D0 = open_stream(d, 0, chunk, valid), D1 = open_stream(d, 1, chunk, valid);
+    DecField D0 = open_stream(d, 0, chunk, valid, L), D1 = open_stream(d, 1, chunk, valid, L);
     const uint32_t m0 = d.mode[0], m1 = d.mode[1];
     const uint64_t K0 = splat(d.konst[0], F_::SB), K1 = splat(d.konst[1], F_::SB);
     const uint32_t chunk_runs = (uint32_t)((E + F_::EPR - 1) / F_::EPR);
@@ -651,7 +670,7 @@ __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const Wo
     }
 
     if (F_::NF == 3) {
-        DecField D2 = open_stream(d, F_::NF - 1, chunk, valid);
+        DecField D2 = open_stream(d, F_::NF - 1, chunk, valid, L);
         const uint32_t m2 = d.mode[F_::NF - 1];
         const uint32_t ns = n / F_::SCALE;
         const uint32_t srows = (uint32_t)((E / F_::SCALE + 15) / 16 + S - 1) / S;
