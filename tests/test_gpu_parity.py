@@ -758,6 +758,40 @@ def test_compress_without_sync_and_host_built_codes():
     assert r.returncode == 0 and "host codes ok" in r.stdout, r.stdout + r.stderr
 
 
+def test_device_code_construction_hard_histograms():
+    # exponent histograms that stress the package-merge on the device: Fibonacci counts (the deepest tree, the
+    # limit binds hard), powers of two, all counts equal (every tie rule at once), a single heavy symbol among
+    # many singletons, at limits from the alphabet size up.  The container's length table must be the oracle's
+    # for that histogram, and the tensor must come back bit for bit.
+    def fib(k):
+        a, b, out = 1, 1, []
+        for _ in range(k):
+            out.append(a); a, b = b, a + b
+        return out
+    hists = {"fibonacci": fib(27), "powers": [1 << i for i in range(20)], "equal": [3] * 256, "equal-odd": [5] * 37,
+             "heavy": [1] * 200 + [100000], "two": [7, 9], "ties": [1, 1, 2, 2, 4, 4, 8, 8, 16, 16, 32, 32] * 4}
+    for name, counts in hists.items():
+        counts = np.asarray(counts, dtype=np.int64)
+        syms = (np.arange(len(counts)) * 5 + 3) % 256 if len(counts) < 256 else np.arange(256)      # not the first symbols of the alphabet
+        h = np.zeros(256, np.uint64)
+        h[syms] = counts.astype(np.uint64)
+        ex = torch.repeat_interleave(torch.from_numpy(syms.astype(np.int32)).to(DEV), torch.from_numpy(counts).to(DEV))
+        ex = ex[torch.randperm(ex.numel(), device=DEV, generator=torch.Generator(device=DEV).manual_seed(3))]
+        n = ex.numel()
+        bits = ((ex << 7) | 0x15).to(torch.int16)                    # one sign+mantissa value: a constant field
+        src = bits.view(torch.uint8).reshape(-1)
+        for limit in (8, 9, 11, 13, 16):
+            comp, info = zc.compress(src, n, zc.params(zc.FMT_BF16, 4096, (limit, 0, 0), 64))
+            want = np.asarray(o.code_lengths(h, limit), dtype=np.uint8)
+            got = np.frombuffer(bytes(info.code_len[0]), dtype=np.uint8)
+            assert info.mode[0] == zc.MODE_HUFF and info.mode[1] == zc.MODE_CONST, (name, limit)
+            assert np.array_equal(got, want), (name, limit)
+            assert info.max_len[0] == int(want.max())
+            out, _ = zc.decompress(comp, info)
+            torch.cuda.synchronize()
+            assert torch.equal(out[:src.numel()], src), (name, limit)
+
+
 def test_device_code_construction_wide_weights():
     # 2^28 + some BF16 values: 16 x the symbol count no longer fits 32 bits, so the device package-merge runs on
     # 64-bit weights.  The oracle's code lengths for the tensor's field histograms (counted here with torch) must
