@@ -544,6 +544,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, stream));
         else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
         LAUNCH_TRY(launch_encode(g.fmt, whole_mode, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
+        if (g.fmt == ZC_FMT_BF16) LAUNCH_TRY(launch_encode_bf16(d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
         LAUNCH_TRY(launch_encode(g.fmt, 0, true, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, stream));
         LAUNCH_TRY(launch_encode(g.fmt, 0, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, stream));
         return ZC_OK;
@@ -586,7 +587,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         for (uint32_t t = 0; t < T; t++) {
             const uint64_t whole_chunks = tensors[t].n_elems / g.elems_per_chunk;
             const bool fs = fast_shape(t);
-            descs[t].fast_shape = fs ? 1 : 0;
+            descs[t].fast_shape = (fs || (g.fmt == ZC_FMT_BF16 && whole_shape)) ? 1 : 0;
             if (fs) for (uint64_t c = 0; c < whole_chunks; c += fast_step) fast_work.push_back({t, (uint32_t)c});
             if (whole_shape) for (uint64_t c = 0; c < whole_chunks; c += whole_step) whole_work.push_back({t, (uint32_t)c});
             else if (fs) for (uint64_t c = 0; c < whole_chunks; c += cpi) other_work.push_back({t, (uint32_t)c});
@@ -610,7 +611,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
                               {w.blobs, blobs.data(), blobs.size()}};
         st = host_stage().upload(ws, w.descs, w.enc, all, 8, hs);
         if (st) return st;
-        HIP_TRY(hipMemsetAsync(d_hist, 0, (uint64_t)T * 3 * 256 * 8, hs));
+        LAUNCH_TRY(launch_zero(d_hist, (uint64_t)T * 3 * 256, stream));
         LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
         if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), (int)scale_block(g.fmt), d_hist, stream));
         CodeParams cp;
@@ -679,7 +680,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
                 const uint32_t e0 = u & 15, e1 = u >> 4, l0 = fc[0].len[e0], l1 = fc[0].len[e1];
                 enc[(size_t)t * 768 + 512 + u] = ((l0 + l1) << 16) | (enc[(size_t)t * 768 + e0] & 0xFFFFu) | ((enc[(size_t)t * 768 + e1] & 0xFFFFu) << l0);
             }
-        descs[t].route = fast_ok ? 1 : 0;
+        const bool bf16_ok = g.fmt == ZC_FMT_BF16 && whole_shape && fc[0].mode == ZC_MODE_HUFF && (descs[t].kind[1] == 1 || descs[t].kind[1] == 2);
+        descs[t].route = fast_ok ? 1 : bf16_ok ? 2 : 0;
         return ZC_OK;
     };
     // The worker threads are started once the histogram kernel is queued and before the wait for it, so that
@@ -694,7 +696,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
                                 {w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem)}};
         st = host_stage().upload(ws, w.descs, w.chunk_work, first, 3, hs);
         if (st) return st;
-        HIP_TRY(hipMemsetAsync(d_hist, 0, (uint64_t)T * 3 * 256 * 8, hs));
+        LAUNCH_TRY(launch_zero(d_hist, (uint64_t)T * 3 * 256, stream));
         LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
         if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), (int)scale_block(g.fmt), d_hist, stream));
         HIP_TRY(hipMemcpyAsync(landing.ptr, d_hist, hist_bytes, hipMemcpyDeviceToHost, hs));
@@ -711,8 +713,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     for (uint32_t t = 0; t < T; t++) {
         // the route is known, so every chunk is listed once
         const uint64_t whole_chunks = tensors[t].n_elems / g.elems_per_chunk;
-        const uint64_t n_fast = descs[t].route ? whole_chunks : 0;
-        const uint64_t n_whole = (!descs[t].route && whole_shape) ? whole_chunks : 0;
+        const uint64_t n_fast = descs[t].route == 1 ? whole_chunks : 0;
+        const uint64_t n_whole = (descs[t].route != 1 && whole_shape) ? whole_chunks : 0;
         for (uint64_t c = 0; c < n_fast; c += fast_step) fast_work.push_back({t, (uint32_t)c});
         for (uint64_t c = 0; c < n_whole; c += whole_step) whole_work.push_back({t, (uint32_t)c});
         for (uint64_t c = n_fast + n_whole; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});

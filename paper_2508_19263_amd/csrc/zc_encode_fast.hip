@@ -223,6 +223,135 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
 }
 
 // ---------------------------------------------------------------------------------------
+// BF16 with 64 lanes per chunk and chunks of whole 1 KiB rows, exponent field table coded, sign+mantissa field
+// flat coded or raw: the shape of model weights and checkpoints (Sec. 3.1, 4.1).  The generic encoder spends
+// 240 vector instructions on such a row of 8 values per lane and is bound by them; here the row's eight exponent
+// and eight sign+mantissa bytes are pulled out of the four source words with byte permutes, the R codes of a refill
+// period (R = 2, 4 or 8 for longest codes of 9..16, 5..8 or at most 4 bits) are concatenated in 32 bits before
+// they enter the 64-bit accumulator, and the source is fetched two rows ahead.  Sizes come from the generic size
+// pass (it runs at the speed of its reads already); this kernel only writes.
+template <int R>
+__device__ __forceinline__ void encode_bf16_chunk(const TensorDev *dp, const WorkItem &it, const uint32_t *enc)
+{
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t chunk = uni32(it.first + (threadIdx.x >> 6));
+    const uint32_t cb = uni32(dp->chunk_bytes);
+    const uint64_t n_elems = uni64(dp->n_elems);
+    if (chunk >= (uint32_t)(n_elems / (cb / 2))) return;
+    const bool has_base = uni64((uint64_t)dp->base) != 0;
+    const bool sm_raw = uni32(dp->kind[1]) == 2;
+    uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
+    const uint64_t payload = uni64(dp->payload_off);
+    const uint32_t *index0 = reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[0]));
+    const uint32_t *index1 = reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[1]));
+    const uint64_t a0 = uni32(index0[chunk]), b0 = uni32(index0[chunk + 1]), a1 = uni32(index1[chunk]), b1 = uni32(index1[chunk + 1]);
+    if (a0 > b0 || a1 > b1 || (b0 - a0) * 16 > 0x7FFFFFFFull || (b1 - a1) * 16 != (uint64_t)cb / 2) return;   // index not as the size pass left it
+    const __amdgpu_buffer_rsrc_t src = rsrc_of(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)) + (uint64_t)chunk * cb, cb);
+    const __amdgpu_buffer_rsrc_t bas = rsrc_of(has_base ? reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) + (uint64_t)chunk * cb : nullptr, has_base ? cb : 0);
+    const __amdgpu_buffer_rsrc_t es = rsrc_of(comp + payload + 16 * a0, (uint32_t)((b0 - a0) * 16));
+    const __amdgpu_buffer_rsrc_t ms = rsrc_of(comp + payload + 16 * a1, cb / 2);
+    const char *lut = reinterpret_cast<const char *>(enc);
+
+    uint64_t acc = 0;           // bits not yet written, next free bit = nacc (< 32 between periods)
+    uint32_t nacc = 0;
+    int32_t k = 0;              // unread bits the decoder would hold at this point
+    uint32_t pend = 0, p0 = 0, p1 = 0;     // words the decoder has asked for and we still owe, and where they go
+    uint32_t wpos = 0;          // words of the stream handed out so far
+    const uint32_t rows = cb / 1024;
+    auto fetch = [&](uint32_t row, u32x4 &x, u32x4 &y) {
+        row = row < rows ? row : rows - 1;
+        x = __builtin_amdgcn_raw_buffer_load_b128(src, (int)(lane * 16), (int)(row * 1024), 0);
+        if (has_base) y = __builtin_amdgcn_raw_buffer_load_b128(bas, (int)(lane * 16), (int)(row * 1024), 0);
+    };
+    auto encode_row = [&](const u32x4 &v, uint32_t row) {
+        // ---- the eight exponents (bits 14..7 of a value) and sign+mantissa bytes (bit 15, bits 6..0), four per word
+        uint32_t ex[2], sm[2];
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            const uint32_t lo = v[2 * h], hi = v[2 * h + 1];            // values 4h, 4h+1 | 4h+2, 4h+3
+            const uint32_t el = lo >> 7, eh = hi >> 7;                    // exponents in byte 0 and byte 2
+            ex[h] = __builtin_amdgcn_perm(eh, el, 0x06040200u);          // bytes: el.b0, el.b2, eh.b0, eh.b2
+            const uint32_t ml = ((lo >> 8) & 0x00800080u) | (lo & 0x007F007Fu), mh = ((hi >> 8) & 0x00800080u) | (hi & 0x007F007Fu);
+            sm[h] = __builtin_amdgcn_perm(mh, ml, 0x06040200u);
+        }
+        if (sm_raw) __builtin_amdgcn_raw_buffer_store_b64(u32x2{sm[0], sm[1]}, ms, (int)(lane * 8), (int)(row * 512), 0);
+        else {
+            // flat code: every byte most significant bit first, one word per 4 symbols, rows of 64 words
+#pragma unroll
+            for (int h = 0; h < 2; h++)
+                __builtin_amdgcn_raw_buffer_store_b32(reverse_in_groups<8>(sm[h]), ms, (int)(lane * 4), (int)((row * 2 + h) * 256), 0);
+        }
+        // ---- exponents: one refill step of the decoder, then the R codes of the period
+#pragma unroll
+        for (int g = 0; g < 8 / R; g++) {
+            const bool req = k <= 32;
+            const uint64_t bm = __ballot(req);
+            if (req) {
+                const uint32_t pos = wpos + __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, 0));
+                if (pend == 0) p0 = pos; else p1 = pos;
+                pend++;
+                k += 32;
+            }
+            wpos += (uint32_t)__popcll(bm);
+            uint32_t code = 0, len = 0;
+#pragma unroll
+            for (int j = 0; j < R; j++) {
+                const int jj = g * R + j;
+                const uint32_t e = (ex[jj / 4] >> (8 * (jj % 4))) & 0xFFu;
+                const uint32_t t = *reinterpret_cast<const uint32_t *>(lut + e * 4);
+                code |= (t & 0xFFFFu) << len;
+                len += t >> 16;
+            }
+            acc |= (uint64_t)code << nacc;
+            nacc += len;
+            k -= (int32_t)len;
+            if (nacc >= 32) {
+                __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, es, (int)(p0 * 4), 0, 0);
+                acc >>= 32; nacc -= 32; p0 = p1; pend--;
+            }
+        }
+    };
+    u32x4 xa, ya = {0, 0, 0, 0}, xb, yb = {0, 0, 0, 0};
+    fetch(0, xa, ya);
+    fetch(1, xb, yb);
+    uint32_t row = 0;
+    for (; row + 1 < rows; row += 2) {
+        const u32x4 va = xa ^ ya;
+        fetch(row + 2, xa, ya);
+        encode_row(va, row);
+        const u32x4 vb = xb ^ yb;
+        fetch(row + 3, xb, yb);
+        encode_row(vb, row + 1);
+    }
+    if (row < rows) encode_row(xa ^ ya, row);
+    // the words still owed to the decoder (a partial word and look-ahead words), then zero padding
+    if (pend > 0) { __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, es, (int)(p0 * 4), 0, 0); acc >>= 32; p0 = p1; pend--; }
+    if (pend > 0) { __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, es, (int)(p0 * 4), 0, 0); pend--; }
+    if (lane < ((4 - (wpos & 3)) & 3)) __builtin_amdgcn_raw_buffer_store_b32(0u, es, (int)((wpos + lane) * 4), 0, 0);
+}
+
+__global__ __launch_bounds__(256) void k_encode_bf16(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables)
+{
+    __shared__ uint32_t enc[256];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev *dp = descs + it.tensor;
+    if (dp->route != 2) return;                                  // whole workgroup: the generic encoder takes this tensor
+    enc[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + threadIdx.x];
+    __syncthreads();
+    const uint32_t period = uni32(dp->period[0]);
+    if (period == 2) encode_bf16_chunk<2>(dp, it, enc);
+    else if (period == 4) encode_bf16_chunk<4>(dp, it, enc);
+    else if (period == 8) encode_bf16_chunk<8>(dp, it, enc);
+}
+
+int launch_encode_bf16(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipLaunchKernelGGL(k_encode_bf16, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc);
+    return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
 // The same shape with fewer than 64 lanes per chunk (small chunks such as K/V-cache pages, whose
 // compression sits on the critical path of a decoding step: Sec. 5.2): a wavefront handles 64/S chunks
 // at once, one per S-lane group.  Ballots are masked to the group, stream positions are per group, and

@@ -67,8 +67,9 @@ struct alignas(16) TensorDev {
     uint32_t streams;         // S
     uint8_t mode[4], lmax[4], konst[4], period[4];
     uint8_t kind[4];          // how the specialised kernels treat the field (0 table, 1 flat code, 2 raw, 3 constant)
-    uint8_t fast_shape;       // compress: the tensor's geometry suits the specialised FP8 size/encode kernels
-    uint8_t route;            // compress: 1 = those kernels take its whole chunks (the code suits them too), 0 = the generic ones
+    uint8_t fast_shape;       // compress: the tensor's geometry suits the specialised size/encode kernels of its format
+    uint8_t route;            // compress: who takes the whole chunks.  0 = the generic kernels; 1 = the FP8 size and encode
+                              // kernels; 2 = the generic size pass and the BF16 encoder
     uint8_t pad_[6];
 };
 
@@ -101,6 +102,7 @@ int launch_codes(TensorDev *d_descs, uint32_t n_tensors, const uint64_t *d_hist,
 // ---- kernel launchers (zc_kernels.hip); all return a hipError_t as int ------
 int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                 int scales_view, uint64_t *d_hist, void *stream);
+int launch_zero(uint64_t *d_words, uint64_t n_words, void *stream);
 int launch_write_headers(const TensorDev *d_descs, uint32_t n_tensors, const uint8_t *d_blobs, uint32_t blob_bytes, int n_fields, void *stream);
 // generic_only: skip tensors whose whole chunks the specialised FP8 kernels take (route 1)
 // whole: 0 = any chunks, 1 = up to four whole 64-lane chunks per work item, 2 = one such chunk per work item, shared
@@ -124,6 +126,8 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split
 // FP8, 64 lanes, full chunks, exponent codes <= 8 bits, sign+mantissa flat or raw (zc_encode_fast.hip)
 int launch_sizes_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream);
 int launch_encode_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
+// BF16, 64 lanes, full chunks, exponent field table coded, sign+mantissa flat or raw; work items as for the generic whole-chunk build
+int launch_encode_bf16(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
 int launch_encode_fp8_sub(uint32_t streams, int write, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
                           uint32_t *d_units, uint32_t slots_per_group, void *stream);
 uint32_t chunks_per_work_item(uint32_t streams);

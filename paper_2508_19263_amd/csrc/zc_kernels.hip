@@ -266,7 +266,9 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
     __shared__ uint32_t enc[3][256];
     __shared__ TensorDev dsh;                       // a copy the compiler knows no store of this kernel can change
     const WorkItem it = work[blockIdx.x];
-    if (generic_only && descs[it.tensor].route) return;        // whole workgroup: these chunks belong to the FP8 kernels
+    // whole workgroup: these chunks belong to a specialised kernel (route 1: FP8 size pass and encoder; route 2: BF16
+    // encoder only, its sizes come from here)
+    if (generic_only && (descs[it.tensor].route == 1 || (WRITE && descs[it.tensor].route))) return;
     if (threadIdx.x == 0) dsh = descs[it.tensor];
     for (uint32_t i = threadIdx.x; i < 3 * 256; i += 256) (&enc[0][0])[i] = enc_tables[(uint64_t)it.tensor * 768 + i];
     __syncthreads();
@@ -502,6 +504,21 @@ __global__ __launch_bounds__(256) void k_write_headers(const TensorDev *descs, c
         const uint32_t f = threadIdx.x / 4, w = d.n_chunks + 1 + (threadIdx.x & 3);
         if (w < ((d.n_chunks + 1 + 3) & ~3u)) dst[d.index_off[f] / 4 + w] = 0;
     }
+}
+
+// Zero the histogram counters.  A kernel rather than a memset call, so that a caller who records the queue-only
+// compress calls into a HIP graph gets a plain kernel node.
+__global__ __launch_bounds__(256) void k_zero(uint64_t *p, uint64_t n)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+int launch_zero(uint64_t *d_words, uint64_t n_words, void *stream)
+{
+    if (n_words == 0) return 0;
+    hipLaunchKernelGGL(k_zero, dim3((uint32_t)((n_words + 255) / 256)), dim3(256), 0, (hipStream_t)stream, d_words, n_words);
+    return (int)hipGetLastError();
 }
 
 int launch_write_headers(const TensorDev *d_descs, uint32_t n_tensors, const uint8_t *d_blobs, uint32_t blob_bytes, int n_fields, void *stream)
