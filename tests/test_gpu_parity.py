@@ -33,6 +33,12 @@ def dev(t):
     return t.to(DEV)
 
 
+def o_info(container):
+    """mode and longest code length per field from a container's header (bytes 32..43)."""
+    c = np.asarray(container)
+    return {"mode": [int(c[32 + 4 * f]) for f in range(3)], "lmax": [int(c[34 + 4 * f]) for f in range(3)]}
+
+
 def check_case(fmt, n, cb, S, policy=zc.POLICY_HUFF_ALL, L=(0, 0, 0), data=None, base=None, tag=""):
     """compress on both sides -> identical containers; decode the oracle's container on the
     GPU -> original bytes; decode on the GPU from the header alone -> original bytes."""
@@ -756,6 +762,28 @@ def test_compress_without_sync_and_host_built_codes():
     env = dict(os.environ, ZC_HOST_CODES="1")
     r = subprocess.run([sys.executable, "-c", script], env=env, capture_output=True, text=True, timeout=110)
     assert r.returncode == 0 and "host codes ok" in r.stdout, r.stdout + r.stderr
+
+
+def test_bf16_encoder_every_refill_period():
+    # BF16, 64 lanes, whole chunks, exponent field table coded next to a flat (HUFF_ALL) or raw (AUTO) sign+mantissa
+    # field: the specialised encoder, at longest exponent codes of 1..4 bits (refill period 8), 5..8 (4) and
+    # beyond (2), with and without a base.
+    rng = np.random.default_rng(31)
+    cb, S = 8192, 64
+    n = 7 * (cb // 2) + 333                                 # seven whole chunks and a short one for the generic kernel
+    sm = rng.integers(0, 256, n).astype(np.uint16)          # every sign+mantissa byte occurs: flat code / raw
+    base = torch.from_numpy((rng.integers(0, 2, n, dtype=np.uint16) << 15).view(np.uint8).copy())     # flips signs only
+    for n_exp, skew, lmax in ((2, 0, 1), (5, 0, 3), (12, 0, 4), (40, 0, 6), (200, 0.08, 15)):
+        # equally likely exponents (short codes) or a geometric tail (long ones)
+        pick = rng.integers(0, n_exp, n) if skew == 0 else np.minimum(rng.geometric(skew, n) - 1, n_exp - 1)
+        ex = (pick.astype(np.uint16) * 3 + 60) & 0xFF
+        bits = ((sm >> 7) << 15) | (ex << 7) | (sm & 0x7F)
+        src = torch.from_numpy(bits.astype(np.uint16).view(np.uint8).copy())
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            for b in (None, base):
+                want, _, _ = check_case(zc.FMT_BF16, n, cb, S, policy, data=(src, None), base=b, tag="bf16-periods-%d" % n_exp)
+        info = o_info(want)
+        assert info["mode"][0] == 1 and info["lmax"][0] == lmax, (n_exp, info)      # the case is what it is meant to be
 
 
 def test_device_code_construction_hard_histograms():
