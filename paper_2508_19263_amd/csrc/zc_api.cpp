@@ -680,7 +680,8 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
                 const uint32_t e0 = u & 15, e1 = u >> 4, l0 = fc[0].len[e0], l1 = fc[0].len[e1];
                 enc[(size_t)t * 768 + 512 + u] = ((l0 + l1) << 16) | (enc[(size_t)t * 768 + e0] & 0xFFFFu) | ((enc[(size_t)t * 768 + e1] & 0xFFFFu) << l0);
             }
-        const bool bf16_ok = g.fmt == ZC_FMT_BF16 && whole_shape && fc[0].mode == ZC_MODE_HUFF && (descs[t].kind[1] == 1 || descs[t].kind[1] == 2);
+        const bool bf16_ok = g.fmt == ZC_FMT_BF16 && whole_shape && descs[t].kind[0] == 0 &&
+                             (descs[t].kind[1] == 1 || descs[t].kind[1] == 2 || (descs[t].kind[1] == 0 && (descs[t].period[1] == 2 || descs[t].period[1] == 4)));
         descs[t].route = fast_ok ? 1 : bf16_ok ? 2 : 0;
         return ZC_OK;
     };

@@ -278,8 +278,10 @@ __global__ __launch_bounds__(256) void k_codes_finish(TensorDev *descs, CodePara
         const uint32_t l0 = e0 >> 16, l1 = e1 >> 16;
         enc[512 + u] = ((l0 + l1) << 16) | (e0 & 0xFFFFu) | ((e1 & 0xFFFFu) << l0);
     }
-    // BF16: the specialised encoder takes a table-coded exponent field next to a flat or raw sign+mantissa field
-    const bool bf16 = cp.fmt == ZC_FMT_BF16 && d.fast_shape && d.mode[0] == ZC_MODE_HUFF && (d.kind[1] == 1 || d.kind[1] == 2);
+    // BF16: the specialised encoder takes a table-coded exponent field next to a sign+mantissa field that is flat,
+    // raw, or table coded with a refill period of 2 or 4
+    const bool bf16 = cp.fmt == ZC_FMT_BF16 && d.fast_shape && d.kind[0] == 0 &&
+                      (d.kind[1] == 1 || d.kind[1] == 2 || (d.kind[1] == 0 && (d.period[1] == 2 || d.period[1] == 4)));
     if (threadIdx.x == 0) d.route = fast ? 1 : bf16 ? 2 : 0;
 }
 

@@ -224,13 +224,64 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
 
 // ---------------------------------------------------------------------------------------
 // BF16 with 64 lanes per chunk and chunks of whole 1 KiB rows, exponent field table coded, sign+mantissa field
-// flat coded or raw: the shape of model weights and checkpoints (Sec. 3.1, 4.1).  The generic encoder spends
-// 240 vector instructions on such a row of 8 values per lane and is bound by them; here the row's eight exponent
-// and eight sign+mantissa bytes are pulled out of the four source words with byte permutes, the R codes of a refill
-// period (R = 2, 4 or 8 for longest codes of 9..16, 5..8 or at most 4 bits) are concatenated in 32 bits before
-// they enter the 64-bit accumulator, and the source is fetched two rows ahead.  Sizes come from the generic size
-// pass (it runs at the speed of its reads already); this kernel only writes.
+// flat coded, raw or table coded too: the shape of model weights, checkpoints and checkpoint deltas (Sec. 3.1,
+// 4.1).  The generic encoder spends 240 (one coded field) to 360 (two) vector instructions on such a row of 8
+// values per lane and is bound by them; here the row's eight exponent and eight sign+mantissa bytes are pulled
+// out of the four source words with byte permutes, the R codes of a refill period (R = 2, 4 or 8 for longest
+// codes of 9..16, 5..8 or at most 4 bits) are concatenated in 32 bits before they enter the 64-bit accumulator,
+// and the source is fetched two rows ahead.  Sizes come from the generic size pass (it runs at the speed of its
+// reads already); this kernel only writes.
+
+// what an encoding lane keeps of one table-coded stream; the decoder it mirrors is in lock step with it
+struct LaneStream {
+    uint64_t acc;               // bits not yet written, next free bit = nacc (< 32 between periods)
+    uint32_t nacc;
+    int32_t k;                  // unread bits the decoder would hold at this point
+    uint32_t pend, p0, p1;      // words the decoder has asked for and we still owe, and where they go
+    uint32_t wpos;              // words of the stream handed out so far (the same in all lanes)
+};
+
+// one refill step of the decoder, then the R codes of a period: bytes first .. first+R-1 of the 8 symbol bytes in w
 template <int R>
+__device__ __forceinline__ void code_period(LaneStream &L, const uint32_t w[2], int first, const char *lut, __amdgpu_buffer_rsrc_t out)
+{
+    const bool req = L.k <= 32;
+    const uint64_t bm = __ballot(req);
+    if (req) {
+        const uint32_t pos = L.wpos + __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, 0));
+        if (L.pend == 0) L.p0 = pos; else L.p1 = pos;
+        L.pend++;
+        L.k += 32;
+    }
+    L.wpos += (uint32_t)__popcll(bm);
+    uint32_t code = 0, len = 0;
+#pragma unroll
+    for (int j = 0; j < R; j++) {
+        const int jj = first + j;
+        const uint32_t e = (w[jj / 4] >> (8 * (jj % 4))) & 0xFFu;
+        const uint32_t t = *reinterpret_cast<const uint32_t *>(lut + e * 4);
+        code |= (t & 0xFFFFu) << len;
+        len += t >> 16;
+    }
+    L.acc |= (uint64_t)code << L.nacc;
+    L.nacc += len;
+    L.k -= (int32_t)len;
+    if (L.nacc >= 32) {
+        __builtin_amdgcn_raw_buffer_store_b32((uint32_t)L.acc, out, (int)(L.p0 * 4), 0, 0);
+        L.acc >>= 32; L.nacc -= 32; L.p0 = L.p1; L.pend--;
+    }
+}
+
+// the words still owed to the decoder (a partial word and look-ahead words), then zero padding of the last unit
+__device__ __forceinline__ void close_stream(LaneStream &L, __amdgpu_buffer_rsrc_t out, uint32_t lane)
+{
+    if (L.pend > 0) { __builtin_amdgcn_raw_buffer_store_b32((uint32_t)L.acc, out, (int)(L.p0 * 4), 0, 0); L.acc >>= 32; L.p0 = L.p1; L.pend--; }
+    if (L.pend > 0) { __builtin_amdgcn_raw_buffer_store_b32((uint32_t)L.acc, out, (int)(L.p0 * 4), 0, 0); L.pend--; }
+    if (lane < ((4 - (L.wpos & 3)) & 3)) __builtin_amdgcn_raw_buffer_store_b32(0u, out, (int)((L.wpos + lane) * 4), 0, 0);
+}
+
+// R0: refill period of the exponent field; R1: of the sign+mantissa field when it is table coded, 0 when it is flat or raw
+template <int R0, int R1>
 __device__ __forceinline__ void encode_bf16_chunk(const TensorDev *dp, const WorkItem &it, const uint32_t *enc)
 {
     const uint32_t lane = threadIdx.x & 63;
@@ -245,18 +296,16 @@ __device__ __forceinline__ void encode_bf16_chunk(const TensorDev *dp, const Wor
     const uint32_t *index0 = reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[0]));
     const uint32_t *index1 = reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[1]));
     const uint64_t a0 = uni32(index0[chunk]), b0 = uni32(index0[chunk + 1]), a1 = uni32(index1[chunk]), b1 = uni32(index1[chunk + 1]);
-    if (a0 > b0 || a1 > b1 || (b0 - a0) * 16 > 0x7FFFFFFFull || (b1 - a1) * 16 != (uint64_t)cb / 2) return;   // index not as the size pass left it
+    // the index must be as the size pass left it
+    if (a0 > b0 || a1 > b1 || (b0 - a0) * 16 > 0x7FFFFFFFull || (b1 - a1) * 16 > 0x7FFFFFFFull) return;
+    if (R1 == 0 && (b1 - a1) * 16 != (uint64_t)cb / 2) return;
     const __amdgpu_buffer_rsrc_t src = rsrc_of(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)) + (uint64_t)chunk * cb, cb);
     const __amdgpu_buffer_rsrc_t bas = rsrc_of(has_base ? reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) + (uint64_t)chunk * cb : nullptr, has_base ? cb : 0);
     const __amdgpu_buffer_rsrc_t es = rsrc_of(comp + payload + 16 * a0, (uint32_t)((b0 - a0) * 16));
-    const __amdgpu_buffer_rsrc_t ms = rsrc_of(comp + payload + 16 * a1, cb / 2);
-    const char *lut = reinterpret_cast<const char *>(enc);
+    const __amdgpu_buffer_rsrc_t ms = rsrc_of(comp + payload + 16 * a1, (uint32_t)((b1 - a1) * 16));
+    const char *lut0 = reinterpret_cast<const char *>(enc), *lut1 = reinterpret_cast<const char *>(enc + 256);
 
-    uint64_t acc = 0;           // bits not yet written, next free bit = nacc (< 32 between periods)
-    uint32_t nacc = 0;
-    int32_t k = 0;              // unread bits the decoder would hold at this point
-    uint32_t pend = 0, p0 = 0, p1 = 0;     // words the decoder has asked for and we still owe, and where they go
-    uint32_t wpos = 0;          // words of the stream handed out so far
+    LaneStream E = {0, 0, 0, 0, 0, 0, 0}, M = E;
     const uint32_t rows = cb / 1024;
     auto fetch = [&](uint32_t row, u32x4 &x, u32x4 &y) {
         row = row < rows ? row : rows - 1;
@@ -274,41 +323,20 @@ __device__ __forceinline__ void encode_bf16_chunk(const TensorDev *dp, const Wor
             const uint32_t ml = ((lo >> 8) & 0x00800080u) | (lo & 0x007F007Fu), mh = ((hi >> 8) & 0x00800080u) | (hi & 0x007F007Fu);
             sm[h] = __builtin_amdgcn_perm(mh, ml, 0x06040200u);
         }
-        if (sm_raw) __builtin_amdgcn_raw_buffer_store_b64(u32x2{sm[0], sm[1]}, ms, (int)(lane * 8), (int)(row * 512), 0);
-        else {
-            // flat code: every byte most significant bit first, one word per 4 symbols, rows of 64 words
+        if (R1 == 0) {
+            if (sm_raw) __builtin_amdgcn_raw_buffer_store_b64(u32x2{sm[0], sm[1]}, ms, (int)(lane * 8), (int)(row * 512), 0);
+            else {
+                // flat code: every byte most significant bit first, one word per 4 symbols, rows of 64 words
 #pragma unroll
-            for (int h = 0; h < 2; h++)
-                __builtin_amdgcn_raw_buffer_store_b32(reverse_in_groups<8>(sm[h]), ms, (int)(lane * 4), (int)((row * 2 + h) * 256), 0);
+                for (int h = 0; h < 2; h++)
+                    __builtin_amdgcn_raw_buffer_store_b32(reverse_in_groups<8>(sm[h]), ms, (int)(lane * 4), (int)((row * 2 + h) * 256), 0);
+            }
         }
-        // ---- exponents: one refill step of the decoder, then the R codes of the period
 #pragma unroll
-        for (int g = 0; g < 8 / R; g++) {
-            const bool req = k <= 32;
-            const uint64_t bm = __ballot(req);
-            if (req) {
-                const uint32_t pos = wpos + __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, 0));
-                if (pend == 0) p0 = pos; else p1 = pos;
-                pend++;
-                k += 32;
-            }
-            wpos += (uint32_t)__popcll(bm);
-            uint32_t code = 0, len = 0;
+        for (int g = 0; g < 8 / R0; g++) code_period<R0>(E, ex, g * R0, lut0, es);
+        if (R1 != 0) {
 #pragma unroll
-            for (int j = 0; j < R; j++) {
-                const int jj = g * R + j;
-                const uint32_t e = (ex[jj / 4] >> (8 * (jj % 4))) & 0xFFu;
-                const uint32_t t = *reinterpret_cast<const uint32_t *>(lut + e * 4);
-                code |= (t & 0xFFFFu) << len;
-                len += t >> 16;
-            }
-            acc |= (uint64_t)code << nacc;
-            nacc += len;
-            k -= (int32_t)len;
-            if (nacc >= 32) {
-                __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, es, (int)(p0 * 4), 0, 0);
-                acc >>= 32; nacc -= 32; p0 = p1; pend--;
-            }
+            for (int g = 0; g < 8 / (R1 ? R1 : 8); g++) code_period<(R1 ? R1 : 8)>(M, sm, g * R1, lut1, ms);
         }
     };
     u32x4 xa, ya = {0, 0, 0, 0}, xb, yb = {0, 0, 0, 0};
@@ -324,24 +352,32 @@ __device__ __forceinline__ void encode_bf16_chunk(const TensorDev *dp, const Wor
         encode_row(vb, row + 1);
     }
     if (row < rows) encode_row(xa ^ ya, row);
-    // the words still owed to the decoder (a partial word and look-ahead words), then zero padding
-    if (pend > 0) { __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, es, (int)(p0 * 4), 0, 0); acc >>= 32; p0 = p1; pend--; }
-    if (pend > 0) { __builtin_amdgcn_raw_buffer_store_b32((uint32_t)acc, es, (int)(p0 * 4), 0, 0); pend--; }
-    if (lane < ((4 - (wpos & 3)) & 3)) __builtin_amdgcn_raw_buffer_store_b32(0u, es, (int)((wpos + lane) * 4), 0, 0);
+    close_stream(E, es, lane);
+    if (R1 != 0) close_stream(M, ms, lane);
 }
 
 __global__ __launch_bounds__(256) void k_encode_bf16(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables)
 {
-    __shared__ uint32_t enc[256];
+    __shared__ uint32_t enc[512];
     const WorkItem it = work[blockIdx.x];
     const TensorDev *dp = descs + it.tensor;
     if (dp->route != 2) return;                                  // whole workgroup: the generic encoder takes this tensor
     enc[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + threadIdx.x];
+    enc[256 + threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + 256 + threadIdx.x];
     __syncthreads();
-    const uint32_t period = uni32(dp->period[0]);
-    if (period == 2) encode_bf16_chunk<2>(dp, it, enc);
-    else if (period == 4) encode_bf16_chunk<4>(dp, it, enc);
-    else if (period == 8) encode_bf16_chunk<8>(dp, it, enc);
+    const uint32_t r0 = uni32(dp->period[0]), r1 = uni32(dp->kind[1]) == 0 ? uni32(dp->period[1]) : 0u;
+    switch (r0 * 16 + r1) {
+    case 0x20: encode_bf16_chunk<2, 0>(dp, it, enc); break;
+    case 0x40: encode_bf16_chunk<4, 0>(dp, it, enc); break;
+    case 0x80: encode_bf16_chunk<8, 0>(dp, it, enc); break;
+    case 0x22: encode_bf16_chunk<2, 2>(dp, it, enc); break;
+    case 0x42: encode_bf16_chunk<4, 2>(dp, it, enc); break;
+    case 0x82: encode_bf16_chunk<8, 2>(dp, it, enc); break;
+    case 0x24: encode_bf16_chunk<2, 4>(dp, it, enc); break;
+    case 0x44: encode_bf16_chunk<4, 4>(dp, it, enc); break;
+    case 0x84: encode_bf16_chunk<8, 4>(dp, it, enc); break;
+    default: break;                                              // the route is only given for these combinations
+    }
 }
 
 int launch_encode_bf16(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)

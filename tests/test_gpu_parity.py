@@ -784,6 +784,15 @@ def test_bf16_encoder_every_refill_period():
                 want, _, _ = check_case(zc.FMT_BF16, n, cb, S, policy, data=(src, None), base=b, tag="bf16-periods-%d" % n_exp)
         info = o_info(want)
         assert info["mode"][0] == 1 and info["lmax"][0] == lmax, (n_exp, info)      # the case is what it is meant to be
+        # the same exponents beside a table-coded sign+mantissa field: longest code 7 (refill period 4), then 12 (2)
+        for tail in (40, 200):
+            draw = rng.integers(0, tail, n) if tail == 40 else np.minimum(rng.geometric(0.12, n) - 1, tail - 1)
+            sm2 = (draw.astype(np.uint16) * 7 + 1) & 0xFF
+            bits2 = ((sm2 >> 7) << 15) | (ex << 7) | (sm2 & 0x7F)
+            src2 = torch.from_numpy(bits2.astype(np.uint16).view(np.uint8).copy())
+            want2, _, _ = check_case(zc.FMT_BF16, n, cb, S, zc.POLICY_HUFF_ALL, data=(src2, None), tag="bf16-periods-%d-sm%d" % (n_exp, tail))
+            info2 = o_info(want2)
+            assert info2["mode"][1] == 1 and (5 <= info2["lmax"][1] <= 8 if tail == 40 else info2["lmax"][1] >= 9), (n_exp, tail, info2)
 
 
 def test_device_code_construction_hard_histograms():
