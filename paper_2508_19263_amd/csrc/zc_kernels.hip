@@ -444,8 +444,12 @@ __global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fie
 {
     __shared__ uint32_t wave_sum[16];
     __shared__ uint32_t carry_s;
-    const TensorDev &d = descs[blockIdx.x];
-    const uint32_t *u = units + d.units_off;
+    // copies of what is needed from the descriptor: the stores below could alias it as far as the compiler knows
+    const TensorDev &dg = descs[blockIdx.x];
+    struct { uint8_t *comp; uint32_t n_chunks, index_off[kMaxFields]; uint64_t payload_off; } d;
+    d.comp = dg.comp; d.n_chunks = dg.n_chunks; d.payload_off = dg.payload_off;
+    for (int f = 0; f < kMaxFields; f++) d.index_off[f] = dg.index_off[f];
+    const uint32_t *u = units + dg.units_off;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (threadIdx.x == 0) carry_s = 0;
     __syncthreads();
@@ -453,10 +457,15 @@ __global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fie
     for (int f = 0; f < n_fields; f++) {
         uint32_t *index = d.comp ? reinterpret_cast<uint32_t *>(d.comp + d.index_off[f]) : nullptr;
         field_start[f] = carry_s;
-        for (uint32_t c0 = 0; c0 < d.n_chunks; c0 += 1024) {
-            const uint32_t c = c0 + threadIdx.x;
-            const uint32_t v = c < d.n_chunks ? u[(uint64_t)f * d.n_chunks + c] : 0;
-            uint32_t x = v;                                   // inclusive scan inside the wave
+        // eight consecutive chunks per thread and pass: a tensor of pages has tens of thousands of chunks, and every
+        // pass costs three workgroup barriers
+        constexpr uint32_t K = 8;
+        for (uint32_t c0 = 0; c0 < d.n_chunks; c0 += 1024 * K) {
+            const uint32_t c = c0 + threadIdx.x * K;
+            uint32_t v[K], t = 0;
+#pragma unroll
+            for (uint32_t j = 0; j < K; j++) { v[j] = c + j < d.n_chunks ? u[(uint64_t)f * d.n_chunks + c + j] : 0; t += v[j]; }
+            uint32_t x = t;                                   // inclusive scan of the threads' sums inside the wave
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
                 const uint32_t y = __shfl_up(x, o, 64);
@@ -466,7 +475,11 @@ __global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fie
             __syncthreads();
             uint32_t before = carry_s;
             for (uint32_t w = 0; w < wave; w++) before += wave_sum[w];
-            if (index && c < d.n_chunks) index[c] = before + x - v;
+            uint32_t at = before + x - t;                     // units before this thread's first chunk
+            if (index) {
+#pragma unroll
+                for (uint32_t j = 0; j < K; j++) { if (c + j < d.n_chunks) index[c + j] = at; at += v[j]; }
+            }
             __syncthreads();
             if (threadIdx.x == 1023) carry_s = before + x;
             __syncthreads();
