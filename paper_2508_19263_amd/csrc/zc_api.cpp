@@ -809,6 +809,21 @@ bool fp8_sub_ok(const zc_info &info, uint64_t dst_bytes)
     return true;
 }
 
+// The same question for the sub-wavefront BF16 kernel: exponent field table decoded, sign+mantissa flat or raw.
+bool bf16_sub_ok(const zc_info &info, uint64_t dst_bytes)
+{
+    if (info.format != ZC_FMT_BF16 || info.streams < 4 || info.streams > 32) return false;
+    if (info.chunk_bytes % (16 * info.streams) || info.chunk_bytes > (1u << 24)) return false;
+    const TensorDev d = make_desc(info);
+    if (info.mode[0] != ZC_MODE_HUFF || d.kind[0] != 0 || (d.kind[1] != 1 && d.kind[1] != 2)) return false;
+    if (info.total_bytes - info.payload_offset > 0xF0000000ull || dst_bytes > 0xF0000000ull) return false;
+    if (info.xor_delta && info.n_elems * 2 > 0xF0000000ull) return false;
+    return true;
+}
+
+// either of the two
+bool sub_ok(const zc_info &info, uint64_t dst_bytes) { return fp8_sub_ok(info, dst_bytes) || bf16_sub_ok(info, dst_bytes); }
+
 // slots one workgroup of the sub-wavefront kernel takes: enough passes to amortise its table
 // build, few enough to leave >= ~2048 workgroups
 uint32_t sub_slots_per_group(uint32_t streams, uint64_t slots)
@@ -919,12 +934,13 @@ zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *
     uint32_t first_slot = 0;
     const uint32_t rings = s64_rings(info);
     const uint64_t elems_per_chunk = (uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(info.format);
-    if (fp8_sub_ok(info, need) && (!by_ids || info.n_elems % elems_per_chunk == 0)) {
+    if (sub_ok(info, need) && (!by_ids || info.n_elems % elems_per_chunk == 0)) {
         // small chunks (pages): several per wavefront.  An id list may name a short last chunk, which
         // this kernel does not take, so lists go here only when every chunk is whole.
         const uint32_t n_fast = by_ids ? n_ids : (uint32_t)(info.n_elems / elems_per_chunk);
         const uint32_t spg = sub_slots_per_group(info.streams, n_fast);
-        LAUNCH_TRY(launch_decode_fp8_sub(info.streams, info.xor_delta != 0, by_ids, nullptr, nullptr, (n_fast + spg - 1) / spg, &d, spg, stream));
+        if (info.format == ZC_FMT_BF16) LAUNCH_TRY(launch_decode_bf16_sub(info.streams, info.xor_delta != 0, nullptr, nullptr, (n_fast + spg - 1) / spg, &d, spg, stream));
+        else LAUNCH_TRY(launch_decode_fp8_sub(info.streams, info.xor_delta != 0, by_ids, nullptr, nullptr, (n_fast + spg - 1) / spg, &d, spg, stream));
         first_slot = n_fast;
     } else if ((fk.ok || rings) && !by_ids) {
         // full chunks through a specialised kernel, a short last chunk through the generic one
@@ -1172,9 +1188,10 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
     bool sub = S < 64;
     for (uint32_t t = 0; t < n_tensors && sub; t++) {
         const zc_info &info = tensors[t].info;
-        const uint64_t need = tensors[t].d_chunk_ids ? (uint64_t)tensors[t].n_chunk_ids * info.chunk_bytes : info.n_elems;
-        if (!fp8_sub_ok(info, need) || info.xor_delta != tensors[0].info.xor_delta) sub = false;
-        if (tensors[t].d_chunk_ids && info.n_elems % info.chunk_bytes) sub = false;
+        const uint64_t raw_bytes = info.n_elems * (uint64_t)elem_bits(fmt) / 8, per_chunk = (uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(fmt);
+        const uint64_t need = tensors[t].d_chunk_ids ? (uint64_t)tensors[t].n_chunk_ids * info.chunk_bytes : raw_bytes;
+        if (!sub_ok(info, need) || info.xor_delta != tensors[0].info.xor_delta) sub = false;
+        if (tensors[t].d_chunk_ids && info.n_elems % per_chunk) sub = false;
     }
     // otherwise the 64-lane full-chunk kernel, when every tensor qualifies
     uint32_t rings = 0;
@@ -1235,7 +1252,7 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
     plan->format = fmt; plan->streams = S; plan->n_tensors = n_tensors;
     plan->n_fast_work = (uint32_t)fast_work.size(); plan->n_work = (uint32_t)work.size();
     plan->fast_exp_kind = (uint32_t)fk.exp_kind; plan->fast_sm_kind = (uint32_t)fk.sm_kind; plan->xor_delta = tensors[0].info.xor_delta;
-    plan->fast_kernel = fk.ok ? 1u : (rings ? (split ? 4u : 2u) : (sub ? 3u : 0u)); plan->n_rings = sub ? spg : rings;
+    plan->fast_kernel = fk.ok ? 1u : (rings ? (split ? 4u : 2u) : (sub ? (fmt == ZC_FMT_BF16 ? 5u : 3u) : 0u)); plan->n_rings = sub ? spg : rings;
     plan->scattered = 0;
     for (uint32_t t = 0; t < n_tensors; t++) if (tensors[t].d_chunk_ids) plan->scattered = 1;
     plan->fast_work_offset = descs_bytes; plan->work_offset = descs_bytes + fast_bytes;
@@ -1257,6 +1274,9 @@ zc_status zc_decompress_batch_run(const zc_batch_plan *plan, const void *d_ws, v
     else if (plan->n_fast_work && plan->fast_kernel == 3)
         LAUNCH_TRY(launch_decode_fp8_sub(plan->streams, plan->xor_delta != 0, plan->scattered != 0, (const TensorDev *)ws,
                                          (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, plan->n_rings, stream));
+    else if (plan->n_fast_work && plan->fast_kernel == 5)
+        LAUNCH_TRY(launch_decode_bf16_sub(plan->streams, plan->xor_delta != 0, (const TensorDev *)ws,
+                                          (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, plan->n_rings, stream));
     else if (plan->n_fast_work) return ZC_ERR_INVALID_ARG;
     if (plan->n_work)
         LAUNCH_TRY(launch_decode(plan->format, (const TensorDev *)ws, (const WorkItem *)(ws + plan->work_offset), plan->n_work,

@@ -120,6 +120,9 @@ int launch_decode_fp8_fast(int exp_kind, int sm_kind, bool xor_delta, const Tens
 // FP8, fewer than 64 lanes per chunk (pages), optional id list (zc_decode_fast.hip)
 int launch_decode_fp8_sub(uint32_t streams, bool xor_delta, bool scattered, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                           const TensorDev *single, uint32_t slots_per_group, void *stream);
+// BF16, fewer than 64 lanes per chunk (pages), exponent field table decoded, sign+mantissa flat or raw, optional id list
+int launch_decode_bf16_sub(uint32_t streams, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+                           const TensorDev *single, uint32_t slots_per_group, void *stream);
 // any format, 64 lanes per chunk, full chunks (zc_decode_fast.hip); n_rings = element fields that are table decoded (1..2)
 int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                       const TensorDev *single, void *stream);

@@ -169,6 +169,51 @@ def test_config5_kv_pages_random_access():
                 assert rc == o.OK and np.array_equal(pg, pages[ids.tolist().index(i)].numpy())
 
 
+def test_bf16_kv_pages_random_access():
+    # the same cache in BF16: pages of 16 tokens x 128 values = 4 KiB; whole-tensor decode, a random quarter of the
+    # pages decoded densely (also through the batch calls), a delta against the previous step's cache, ids out of range
+    k, v = wl.bf16_kv_pair(batch=1, heads=4, tokens=1024, seed=15)
+    for name, t in (("K", k), ("V", v)):
+        flat = t.reshape(-1)
+        n = flat.numel()
+        raw = flat.view(torch.uint8).reshape(-1)
+        for S in (8, 32, 4):
+            for limit in ((0, 0, 0), (8, 0, 0)):              # longest exponent codes beyond and within 8 bits
+                want, _, _ = check_case(zc.FMT_BF16, n, 4096, S, zc.POLICY_AUTO, limit, data=(raw, None), tag="bf16-pages-" + name)
+            n_pages = n * 2 // 4096
+            ids = wl.page_sample(n_pages, 0.25, seed=S)
+            comp = torch.from_numpy(want).to(DEV)
+            info = zc.read_info(comp)
+            out, _ = zc.decompress_chunks(comp, info, ids.to(DEV))
+            torch.cuda.synchronize()
+            pages = raw.reshape(n_pages, 4096)[ids.long()]
+            assert torch.equal(out.cpu().reshape(-1, 4096), pages)
+            for i in ids[:3].tolist():
+                rc, pg, _ = o.decompress_chunk(want, i, 4096)
+                assert rc == o.OK and np.array_equal(pg, pages[ids.tolist().index(i)].numpy())
+            # ids beyond the tensor leave their slots alone
+            bad = torch.tensor([1, n_pages + 7, 0], dtype=torch.int32)
+            outb = torch.full((3 * 4096,), 0x5A, dtype=torch.uint8, device=DEV)
+            zc.decompress_chunks(comp, info, bad.to(DEV), out=outb)
+            torch.cuda.synchronize()
+            outb = outb.cpu().reshape(3, 4096)
+            assert torch.equal(outb[0], raw[4096:8192]) and torch.equal(outb[2], raw[:4096]) and bool((outb[1] == 0x5A).all())
+    # delta of V against K (any base will do), ragged length, page-sized chunks
+    a, b = k.reshape(-1).view(torch.uint8).reshape(-1)[:41 * 4096 + 6], v.reshape(-1).view(torch.uint8).reshape(-1)[:41 * 4096 + 6]
+    check_case(zc.FMT_BF16, a.numel() // 2, 4096, 16, data=(a, None), base=b, tag="bf16-pages-delta")
+    # the batch calls with an id list per tensor
+    srcs = [k.reshape(-1).view(torch.uint8).reshape(-1), v.reshape(-1).view(torch.uint8).reshape(-1)]
+    bt = zc.Batch([dev(x) for x in srcs], [x.numel() // 2 for x in srcs], zc.params(zc.FMT_BF16, 4096, streams=8, policy=zc.POLICY_AUTO))
+    bt.compress()
+    idl = [wl.page_sample(x.numel() // 4096, 0.25, seed=40 + i) for i, x in enumerate(srcs)]
+    bt.set_chunk_ids([dev(i) for i in idl])
+    bt.plan_decompress()
+    bt.run_decompress()
+    torch.cuda.synchronize()
+    for x, i, out in zip(srcs, idl, bt.out):
+        assert torch.equal(out.cpu().reshape(-1, 4096), x.reshape(-1, 4096)[i.long()])
+
+
 def test_random_access_with_short_last_chunk_and_bad_ids():
     n, cb = 10 * 4096 + 100, 4096
     x = wl.fp8_weight(n, seed=9)
