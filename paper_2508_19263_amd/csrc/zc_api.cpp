@@ -507,11 +507,14 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     // lanes per chunk (pages) for the sub-wavefront kernels as long as the tensor fits their 32-bit offsets.
     // Whether the code suits them too (exponent refill period 4, i.e. a longest code of 5..8 bits, sign+mantissa
     // flat coded or raw) is known once the code is: descs[t].route.
+    // The page kernels (4..32 lanes) also have BF16 builds: exponent field table coded, sign+mantissa flat or raw.
     auto fast_shape = [&](uint32_t t) {
+        if (g.fmt == ZC_FMT_BF16) return g.S >= 4 && g.S < 64 && g.chunk_bytes % (16 * g.S) == 0 && tensors[t].n_elems * 2 <= 0xF0000000ull;
         if (g.fmt != ZC_FMT_FP8_E4M3) return false;
         return g.S == 64 ? g.chunk_bytes % 1024 == 0
                          : (g.S >= 4 && g.chunk_bytes % (16 * g.S) == 0 && tensors[t].n_elems <= 0xF0000000ull);
     };
+    const bool bf16 = g.fmt == ZC_FMT_BF16;
     const bool whole_shape = g.S == 64 && g.chunk_bytes % 1024 == 0;       // the generic encoder's whole-chunk build
     // FP4 elements rarely compress, so their fields are stored plainly and a chunk's rows can be shared by the four
     // wavefronts of a workgroup: one chunk per work item there
@@ -532,21 +535,23 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     // stream sizes (a5) and their exclusive scan into the chunk index (a6)
     auto launch_sizes_and_scan = [&]() -> zc_status {
         if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, stream));
-        else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 0, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
-        LAUNCH_TRY(launch_sizes(g.fmt, whole_mode, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, d_units, stream));
-        LAUNCH_TRY(launch_sizes(g.fmt, 0, true, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, d_units, stream));
-        LAUNCH_TRY(launch_sizes(g.fmt, 0, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, d_units, stream));
+        else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 0, bf16, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
+        // generic kernels: the whole-chunk list leaves route 1 to the FP8 kernels (route 2 there is the BF16 encoder,
+        // whose sizes come from this pass); the list of page-shaped tensors leaves both routes to the page kernels
+        LAUNCH_TRY(launch_sizes(g.fmt, whole_mode, 0x2, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, d_units, stream));
+        LAUNCH_TRY(launch_sizes(g.fmt, 0, 0x6, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, d_units, stream));
+        LAUNCH_TRY(launch_sizes(g.fmt, 0, 0, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, d_units, stream));
         LAUNCH_TRY(launch_scan(d_descs, T, (int)g.nf, d_units, (ScanOut *)(ws + w.scan), stream));
         return ZC_OK;
     };
     // chunked encode (a7)
     auto launch_encoders = [&]() -> zc_status {
         if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, stream));
-        else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
-        LAUNCH_TRY(launch_encode(g.fmt, whole_mode, true, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
-        if (g.fmt == ZC_FMT_BF16) LAUNCH_TRY(launch_encode_bf16(d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
-        LAUNCH_TRY(launch_encode(g.fmt, 0, true, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, stream));
-        LAUNCH_TRY(launch_encode(g.fmt, 0, false, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, stream));
+        else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, bf16, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, whole_mode, 0x6, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
+        if (bf16) LAUNCH_TRY(launch_encode_bf16(d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, 0, 0x6, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, 0, 0, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, stream));
         return ZC_OK;
     };
     // When every destination can hold the worst case, the sizes need not be known on the host first: the encoder
@@ -587,7 +592,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         for (uint32_t t = 0; t < T; t++) {
             const uint64_t whole_chunks = tensors[t].n_elems / g.elems_per_chunk;
             const bool fs = fast_shape(t);
-            descs[t].fast_shape = (fs || (g.fmt == ZC_FMT_BF16 && whole_shape)) ? 1 : 0;
+            descs[t].fast_shape = (fs || (bf16 && whole_shape)) ? 1 : 0;
             if (fs) for (uint64_t c = 0; c < whole_chunks; c += fast_step) fast_work.push_back({t, (uint32_t)c});
             if (whole_shape) for (uint64_t c = 0; c < whole_chunks; c += whole_step) whole_work.push_back({t, (uint32_t)c});
             else if (fs) for (uint64_t c = 0; c < whole_chunks; c += cpi) other_work.push_back({t, (uint32_t)c});
@@ -674,15 +679,22 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
                 enc[(size_t)t * 768 + f * 256 + v] = ((uint32_t)fc[f].len[v] << 16) | reverse_bits(fc[f].code[v], fc[f].len[v]);
         }
         // the FP8 kernels' table (slot of the unused third field) maps a pair of exponents to the two codes concatenated
-        const bool fast_ok = fast_shape(t) && fc[0].mode == ZC_MODE_HUFF && descs[t].period[0] == 4 && (descs[t].kind[1] == 1 || descs[t].kind[1] == 2);
+        const bool fast_ok = !bf16 && fast_shape(t) && fc[0].mode == ZC_MODE_HUFF && descs[t].period[0] == 4 && (descs[t].kind[1] == 1 || descs[t].kind[1] == 2);
         if (fast_ok)
             for (uint32_t u = 0; u < 256; u++) {
                 const uint32_t e0 = u & 15, e1 = u >> 4, l0 = fc[0].len[e0], l1 = fc[0].len[e1];
                 enc[(size_t)t * 768 + 512 + u] = ((l0 + l1) << 16) | (enc[(size_t)t * 768 + e0] & 0xFFFFu) | ((enc[(size_t)t * 768 + e1] & 0xFFFFu) << l0);
             }
-        const bool bf16_ok = g.fmt == ZC_FMT_BF16 && whole_shape && descs[t].kind[0] == 0 &&
-                             (descs[t].kind[1] == 1 || descs[t].kind[1] == 2 || (descs[t].kind[1] == 0 && (descs[t].period[1] == 2 || descs[t].period[1] == 4)));
-        descs[t].route = fast_ok ? 1 : bf16_ok ? 2 : 0;
+        // BF16: the 64-lane encoder takes a table-coded exponent field next to a sign+mantissa field that is flat, raw, or
+        // table coded with a refill period of 2 or 4; the page kernels want the latter flat or raw and, with two
+        // exponents per refill step, no 1-bit code (the bound on their staging ring needs 4 bits per step)
+        uint32_t lmin = 16;
+        for (int v = 0; v < 256; v++) if (fc[0].len[v] && fc[0].len[v] < lmin) lmin = fc[0].len[v];
+        const bool plain_sm = descs[t].kind[1] == 1 || descs[t].kind[1] == 2;
+        const bool bf16_ok = bf16 && descs[t].kind[0] == 0 &&
+                             (whole_shape ? (plain_sm || (descs[t].kind[1] == 0 && (descs[t].period[1] == 2 || descs[t].period[1] == 4)))
+                                          : (fast_shape(t) && plain_sm && (descs[t].period[0] != 2 || lmin >= 2)));
+        descs[t].route = (!bf16 && fast_ok) ? 1 : bf16_ok ? 2 : 0;
         return ZC_OK;
     };
     // The worker threads are started once the histogram kernel is queued and before the wait for it, so that
@@ -714,7 +726,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     for (uint32_t t = 0; t < T; t++) {
         // the route is known, so every chunk is listed once
         const uint64_t whole_chunks = tensors[t].n_elems / g.elems_per_chunk;
-        const uint64_t n_fast = descs[t].route == 1 ? whole_chunks : 0;
+        const uint64_t n_fast = (descs[t].route == 1 || (descs[t].route == 2 && !whole_shape)) ? whole_chunks : 0;
         const uint64_t n_whole = (descs[t].route != 1 && whole_shape) ? whole_chunks : 0;
         for (uint64_t c = 0; c < n_fast; c += fast_step) fast_work.push_back({t, (uint32_t)c});
         for (uint64_t c = 0; c < n_whole; c += whole_step) whole_work.push_back({t, (uint32_t)c});

@@ -404,11 +404,20 @@ int launch_encode_bf16(const TensorDev *d_descs, const WorkItem *d_work, uint32_
 // mirrors held at most 32 unread bits and the word adds 32), i.e. at most 16 steps of four symbols of at
 // least one bit each, during which the group hands out at most 16*S positions; with the segment rounding
 // and the 4*S positions of the row in progress the ring never holds more than 24*S words.
-template <int S, bool WRITE>
+//
+// BF: 0 = FP8 as described.  2, 4, 8 = BF16 with that refill period of the exponent field (longest code 9..16,
+// 5..8, at most 4 bits): a row is then 8 values per lane, 8 exponent bytes coded in 8/BF periods through the
+// 256-entry table of the field, and the same 8 bytes of sign+mantissa per lane as FP8 has, so everything but the
+// field split and the period is shared.  The bound on the ring needs at least 4 bits per step; with two symbols
+// per step (BF = 2) that takes a shortest code of 2 bits, which the host (or k_codes_finish) checks before it
+// gives a tensor to this kernel.
+template <int S, bool WRITE, int BF>
 __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units,
                                                         uint32_t slots_per_group)
 {
     static_assert(S >= 4 && S <= 32, "the zero padding of a stream's last unit takes up to 3 lanes of the group");
+    static_assert(BF == 0 || BF == 2 || BF == 4 || BF == 8, "FP8, or BF16 with a refill period of 2, 4 or 8");
+    constexpr int kPeriods = BF ? 8 / (BF ? BF : 1) : 4;      // refill steps per row
     constexpr uint32_t kGroups = 64 / S;
     constexpr uint32_t kNowhere = 0xFFFFFFF0u;
     constexpr uint32_t kSeg = 4 * S, kRing = 32 * S;             // words per group
@@ -417,14 +426,14 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
     __shared__ __attribute__((aligned(16))) uint32_t pairs_of_rows[WRITE ? kWavesPerGroup * 256 : 4];   // 4*S words per group
     const WorkItem it = work[blockIdx.x];
     const TensorDev *dp = descs + it.tensor;
-    if (!dp->route) return;                                      // whole workgroup: the code does not suit this kernel
-    pair[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + 512 + threadIdx.x];
+    if (dp->route != (BF ? 2 : 1) || (BF && dp->period[0] != BF)) return;      // whole workgroup: not this kernel's tensor
+    pair[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + (BF ? 0 : 512) + threadIdx.x];
     __syncthreads();
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t s = lane & (S - 1), grp = lane / S;
     const uint64_t gmask = ((1ull << S) - 1) << (lane - s);
-    const uint32_t cb = uni32(dp->chunk_bytes);                  // one element per byte
-    const uint64_t n_elems = uni64(dp->n_elems);
+    const uint32_t cb = uni32(dp->chunk_bytes);                  // FP8: one element per byte; BF16: two bytes per element
+    const uint64_t n_elems = uni64(dp->n_elems) * (BF ? 2 : 1);  // in bytes
     const uint32_t n_full = (uint32_t)(n_elems / cb), nc = uni32(dp->n_chunks);
     const bool has_base = uni64((uint64_t)dp->base) != 0;
     const bool sm_raw = uni32(dp->kind[1]) == 2;
@@ -487,13 +496,24 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
             if (has_base) y = __builtin_amdgcn_raw_buffer_load_b128(bas, (int)at, 0, 0);
         };
         auto encode_row = [&](const u32x4 &v, uint32_t row) {
+            uint32_t ex[2] = {0, 0};                                // BF16: the row's eight exponent bytes
+            if (BF) {
+#pragma unroll
+                for (int h = 0; h < 2; h++) ex[h] = __builtin_amdgcn_perm(v[2 * h + 1] >> 7, v[2 * h] >> 7, 0x06040200u);
+            }
             if (WRITE) {
                 uint32_t m[2];
 #pragma unroll
                 for (int h = 0; h < 2; h++) {
-                    const uint32_t lo = pack_nibbles_of_bytes(((v[2 * h] >> 4) & 0x08080808u) | (v[2 * h] & 0x07070707u));
-                    const uint32_t hi = pack_nibbles_of_bytes(((v[2 * h + 1] >> 4) & 0x08080808u) | (v[2 * h + 1] & 0x07070707u));
-                    m[h] = lo | (hi << 16);
+                    if (BF) {
+                        const uint32_t lo = v[2 * h], hi = v[2 * h + 1];
+                        const uint32_t ml = ((lo >> 8) & 0x00800080u) | (lo & 0x007F007Fu), mh = ((hi >> 8) & 0x00800080u) | (hi & 0x007F007Fu);
+                        m[h] = __builtin_amdgcn_perm(mh, ml, 0x06040200u);
+                    } else {
+                        const uint32_t lo = pack_nibbles_of_bytes(((v[2 * h] >> 4) & 0x08080808u) | (v[2 * h] & 0x07070707u));
+                        const uint32_t hi = pack_nibbles_of_bytes(((v[2 * h + 1] >> 4) & 0x08080808u) | (v[2 * h + 1] & 0x07070707u));
+                        m[h] = lo | (hi << 16);
+                    }
                 }
                 if (sm_raw) {
                     // the packed nibbles as they are: 8 bytes per lane
@@ -504,10 +524,7 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
                     // lane stores 16 contiguous bytes; an odd last row is stored word by word.
                     uint32_t w[2];
 #pragma unroll
-                    for (int h = 0; h < 2; h++) {
-                        w[h] = ((m[h] >> 1) & 0x55555555u) | ((m[h] & 0x55555555u) << 1);
-                        w[h] = ((w[h] >> 2) & 0x33333333u) | ((w[h] & 0x33333333u) << 2);
-                    }
+                    for (int h = 0; h < 2; h++) w[h] = BF ? reverse_in_groups<8>(m[h]) : reverse_in_groups<4>(m[h]);
                     if ((row & 1) == 0 && row + 1 == rows) {
 #pragma unroll
                         for (int h = 0; h < 2; h++)
@@ -523,7 +540,7 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
                 }
             }
 #pragma unroll
-            for (int g = 0; g < 4; g++) {
+            for (int g = 0; g < kPeriods; g++) {
                 const bool req = k <= 32;
                 if (WRITE) {
                     const uint64_t bm = __ballot(req) & gmask;
@@ -534,8 +551,17 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
                     wpos += (uint32_t)__popcll(bm);
                 } else q += req ? 1u : 0u;
                 k += req ? 32 : 0;
-                uint32_t code, len;
-                group_code(v[g], pair_lut, two, code, len);
+                uint32_t code = 0, len = 0;
+                if (BF) {
+#pragma unroll
+                    for (int j = 0; j < (BF ? BF : 1); j++) {
+                        const int jj = g * BF + j;
+                        const uint32_t e = (ex[(jj / 4) & 1] >> (8 * (jj % 4))) & 0xFFu;
+                        const uint32_t t = *reinterpret_cast<const uint32_t *>(pair_lut + e * 4);
+                        code |= (t & 0xFFFFu) << len;
+                        len += t >> 16;
+                    }
+                } else group_code(v[g & 3], pair_lut, two, code, len);
                 k -= (int32_t)len;
                 if (WRITE) {
                     acc |= (uint64_t)code << nacc;
@@ -594,26 +620,31 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
 }
 
 template <int S, bool WRITE>
-static void launch_sub_t(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, uint32_t slots_per_group, hipStream_t st)
+static void launch_sub_t(bool bf16, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, uint32_t slots_per_group, hipStream_t st)
 {
-    hipLaunchKernelGGL((k_encode_fp8_sub<S, WRITE>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, slots_per_group);
+    if (!bf16) { hipLaunchKernelGGL((k_encode_fp8_sub<S, WRITE, 0>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, slots_per_group); return; }
+    // one launch per refill period: a workgroup whose tensor has another one returns at once
+    hipLaunchKernelGGL((k_encode_fp8_sub<S, WRITE, 2>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, slots_per_group);
+    hipLaunchKernelGGL((k_encode_fp8_sub<S, WRITE, 4>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, slots_per_group);
+    hipLaunchKernelGGL((k_encode_fp8_sub<S, WRITE, 8>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, slots_per_group);
 }
 
-// streams: 4, 8, 16 or 32.  write == 0: size pass (d_units), else encode.
-int launch_encode_fp8_sub(uint32_t streams, int write, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
+// streams: 4, 8, 16 or 32.  write == 0: size pass (d_units), else encode.  bf16: the BF16 builds (tensors of route 2)
+// instead of the FP8 one (route 1).
+int launch_encode_fp8_sub(uint32_t streams, int write, bool bf16, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
                           uint32_t *d_units, uint32_t slots_per_group, void *stream)
 {
     if (n_work == 0) return 0;
     hipStream_t st = (hipStream_t)stream;
     switch (streams * 2 + (write ? 1 : 0)) {
-    case 8: launch_sub_t<4, false>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
-    case 9: launch_sub_t<4, true>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
-    case 16: launch_sub_t<8, false>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
-    case 17: launch_sub_t<8, true>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
-    case 32: launch_sub_t<16, false>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
-    case 33: launch_sub_t<16, true>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
-    case 64: launch_sub_t<32, false>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
-    case 65: launch_sub_t<32, true>(d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 8: launch_sub_t<4, false>(bf16, d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 9: launch_sub_t<4, true>(bf16, d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 16: launch_sub_t<8, false>(bf16, d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 17: launch_sub_t<8, true>(bf16, d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 32: launch_sub_t<16, false>(bf16, d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 33: launch_sub_t<16, true>(bf16, d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 64: launch_sub_t<32, false>(bf16, d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
+    case 65: launch_sub_t<32, true>(bf16, d_descs, d_work, n_work, d_enc, d_units, slots_per_group, st); break;
     default: return 1;
     }
     return (int)hipGetLastError();

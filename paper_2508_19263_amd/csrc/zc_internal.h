@@ -69,7 +69,8 @@ struct alignas(16) TensorDev {
     uint8_t kind[4];          // how the specialised kernels treat the field (0 table, 1 flat code, 2 raw, 3 constant)
     uint8_t fast_shape;       // compress: the tensor's geometry suits the specialised size/encode kernels of its format
     uint8_t route;            // compress: who takes the whole chunks.  0 = the generic kernels; 1 = the FP8 size and encode
-                              // kernels; 2 = the generic size pass and the BF16 encoder
+                              // kernels; 2 = BF16: with 64 lanes per chunk the generic size pass and the BF16 encoder, with
+                              // fewer the BF16 builds of the page size/encode kernel
     uint8_t pad_[6];
 };
 
@@ -104,13 +105,13 @@ int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, 
                 int scales_view, uint64_t *d_hist, void *stream);
 int launch_zero(uint64_t *d_words, uint64_t n_words, void *stream);
 int launch_write_headers(const TensorDev *d_descs, uint32_t n_tensors, const uint8_t *d_blobs, uint32_t blob_bytes, int n_fields, void *stream);
-// generic_only: skip tensors whose whole chunks the specialised FP8 kernels take (route 1)
+// skip_routes: bit r set = leave tensors of route r to the specialised kernel that takes their whole chunks
 // whole: 0 = any chunks, 1 = up to four whole 64-lane chunks per work item, 2 = one such chunk per work item, shared
 // by the workgroup's four wavefronts
-int launch_sizes(uint32_t fmt, int whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+int launch_sizes(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                  const uint32_t *d_enc_tables, uint32_t *d_units, void *stream);
 int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, const uint32_t *d_units, ScanOut *d_out, void *stream);
-int launch_encode(uint32_t fmt, int whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+int launch_encode(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                   const uint32_t *d_enc_tables, void *stream);
 int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
                   const TensorDev *single, uint32_t first_slot, void *stream);
@@ -131,7 +132,7 @@ int launch_sizes_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t 
 int launch_encode_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
 // BF16, 64 lanes, full chunks, exponent field table coded, sign+mantissa flat or raw; work items as for the generic whole-chunk build
 int launch_encode_bf16(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
-int launch_encode_fp8_sub(uint32_t streams, int write, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
+int launch_encode_fp8_sub(uint32_t streams, int write, bool bf16, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
                           uint32_t *d_units, uint32_t slots_per_group, void *stream);
 uint32_t chunks_per_work_item(uint32_t streams);
 

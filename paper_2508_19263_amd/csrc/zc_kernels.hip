@@ -259,16 +259,15 @@ __device__ __forceinline__ uint32_t enc_finish(EncField &F, uint8_t *stream, con
 // wavefront takes the chunk alone.  The host asks for this where plain element fields are the rule (FP4): four
 // times the wavefronts hide four times the memory latency, which is what bounds a set of few chunks.
 template <int FMT, bool WRITE, bool WHOLE>
-__global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units, int generic_only,
+__global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units, int skip_routes,
                                                 int shared_chunk)
 {
     using F_ = Fmt<FMT>;
     __shared__ uint32_t enc[3][256];
     __shared__ TensorDev dsh;                       // a copy the compiler knows no store of this kernel can change
     const WorkItem it = work[blockIdx.x];
-    // whole workgroup: these chunks belong to a specialised kernel (route 1: FP8 size pass and encoder; route 2: BF16
-    // encoder only, its sizes come from here)
-    if (generic_only && (descs[it.tensor].route == 1 || (WRITE && descs[it.tensor].route))) return;
+    // whole workgroup: these chunks belong to a specialised kernel (bit r of skip_routes: leave tensors of route r alone)
+    if ((skip_routes >> descs[it.tensor].route) & 1) return;
     if (threadIdx.x == 0) dsh = descs[it.tensor];
     for (uint32_t i = threadIdx.x; i < 3 * 256; i += 256) (&enc[0][0])[i] = enc_tables[(uint64_t)it.tensor * 768 + i];
     __syncthreads();
@@ -400,24 +399,24 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
 }
 
 template <int FMT, bool WRITE>
-static void launch_encode_f(int whole, int generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
+static void launch_encode_f(int whole, int skip_routes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
 {
-    if (whole) hipLaunchKernelGGL((k_encode<FMT, WRITE, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, generic_only, whole == 2 ? 1 : 0);
-    else hipLaunchKernelGGL((k_encode<FMT, WRITE, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, generic_only, 0);
+    if (whole) hipLaunchKernelGGL((k_encode<FMT, WRITE, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, skip_routes, whole == 2 ? 1 : 0);
+    else hipLaunchKernelGGL((k_encode<FMT, WRITE, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, d_enc, d_units, skip_routes, 0);
 }
 
 template <bool WRITE>
-static int launch_encode_t(uint32_t fmt, int whole, int generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
+static int launch_encode_t(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, hipStream_t st)
 {
     if (n_work == 0) return 0;
     switch (fmt) {
-    case ZC_FMT_BF16: launch_encode_f<ZC_FMT_BF16, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
-    case ZC_FMT_FP8_E4M3: launch_encode_f<ZC_FMT_FP8_E4M3, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
-    case ZC_FMT_FP4_E2M1_MX: launch_encode_f<ZC_FMT_FP4_E2M1_MX, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
-    case ZC_FMT_FP8_E4M3_BYTES: launch_encode_f<ZC_FMT_FP8_E4M3_BYTES, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
-    case ZC_FMT_FP4_E2M1_MX_BYTES: launch_encode_f<ZC_FMT_FP4_E2M1_MX_BYTES, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
-    case ZC_FMT_FP4_E2M1_NV: launch_encode_f<ZC_FMT_FP4_E2M1_NV, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
-    case ZC_FMT_FP8_E5M2: launch_encode_f<ZC_FMT_FP8_E5M2, WRITE>(whole, generic_only, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_BF16: launch_encode_f<ZC_FMT_BF16, WRITE>(whole, skip_routes, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP8_E4M3: launch_encode_f<ZC_FMT_FP8_E4M3, WRITE>(whole, skip_routes, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP4_E2M1_MX: launch_encode_f<ZC_FMT_FP4_E2M1_MX, WRITE>(whole, skip_routes, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP8_E4M3_BYTES: launch_encode_f<ZC_FMT_FP8_E4M3_BYTES, WRITE>(whole, skip_routes, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP4_E2M1_MX_BYTES: launch_encode_f<ZC_FMT_FP4_E2M1_MX_BYTES, WRITE>(whole, skip_routes, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP4_E2M1_NV: launch_encode_f<ZC_FMT_FP4_E2M1_NV, WRITE>(whole, skip_routes, d_descs, d_work, n_work, d_enc, d_units, st); break;
+    case ZC_FMT_FP8_E5M2: launch_encode_f<ZC_FMT_FP8_E5M2, WRITE>(whole, skip_routes, d_descs, d_work, n_work, d_enc, d_units, st); break;
     default: return 1;
     }
     return (int)hipGetLastError();
@@ -425,14 +424,14 @@ static int launch_encode_t(uint32_t fmt, int whole, int generic_only, const Tens
 
 // whole: 1 = every work item is up to four whole chunks of a tensor with 64 lanes per chunk and chunks of whole
 // 1 KiB rows; 2 = every work item is one such chunk, shared by the workgroup's four wavefronts; 0 = any chunks
-int launch_sizes(uint32_t fmt, int whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream)
+int launch_sizes(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream)
 {
-    return launch_encode_t<false>(fmt, whole, generic_only ? 1 : 0, d_descs, d_work, n_work, d_enc, d_units, (hipStream_t)stream);
+    return launch_encode_t<false>(fmt, whole, skip_routes, d_descs, d_work, n_work, d_enc, d_units, (hipStream_t)stream);
 }
 
-int launch_encode(uint32_t fmt, int whole, bool generic_only, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)
+int launch_encode(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)
 {
-    return launch_encode_t<true>(fmt, whole, generic_only ? 1 : 0, d_descs, d_work, n_work, d_enc, nullptr, (hipStream_t)stream);
+    return launch_encode_t<true>(fmt, whole, skip_routes, d_descs, d_work, n_work, d_enc, nullptr, (hipStream_t)stream);
 }
 
 // ---------------------------------------------------------------------------- scan

@@ -810,34 +810,40 @@ def test_compress_without_sync_and_host_built_codes():
 
 
 def test_bf16_encoder_every_refill_period():
-    # BF16, 64 lanes, whole chunks, exponent field table coded next to a flat (HUFF_ALL) or raw (AUTO) sign+mantissa
-    # field: the specialised encoder, at longest exponent codes of 1..4 bits (refill period 8), 5..8 (4) and
-    # beyond (2), with and without a base.
+    # BF16, whole chunks, exponent field table coded next to a flat (HUFF_ALL) or raw (AUTO) sign+mantissa field: the
+    # specialised encoders (64 lanes per chunk, and the page kernel's BF16 builds with 8), at longest exponent codes
+    # of 1..4 bits (refill period 8), 5..8 (4) and beyond (2), with and without a base.  The last case has a 1-bit
+    # code next to long ones, which the page kernel leaves to the generic encoder.
     rng = np.random.default_rng(31)
-    cb, S = 8192, 64
-    n = 7 * (cb // 2) + 333                                 # seven whole chunks and a short one for the generic kernel
-    sm = rng.integers(0, 256, n).astype(np.uint16)          # every sign+mantissa byte occurs: flat code / raw
-    base = torch.from_numpy((rng.integers(0, 2, n, dtype=np.uint16) << 15).view(np.uint8).copy())     # flips signs only
-    for n_exp, skew, lmax in ((2, 0, 1), (5, 0, 3), (12, 0, 4), (40, 0, 6), (200, 0.08, 15)):
-        # equally likely exponents (short codes) or a geometric tail (long ones)
-        pick = rng.integers(0, n_exp, n) if skew == 0 else np.minimum(rng.geometric(skew, n) - 1, n_exp - 1)
-        ex = (pick.astype(np.uint16) * 3 + 60) & 0xFF
-        bits = ((sm >> 7) << 15) | (ex << 7) | (sm & 0x7F)
-        src = torch.from_numpy(bits.astype(np.uint16).view(np.uint8).copy())
-        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
-            for b in (None, base):
-                want, _, _ = check_case(zc.FMT_BF16, n, cb, S, policy, data=(src, None), base=b, tag="bf16-periods-%d" % n_exp)
-        info = o_info(want)
-        assert info["mode"][0] == 1 and info["lmax"][0] == lmax, (n_exp, info)      # the case is what it is meant to be
-        # the same exponents beside a table-coded sign+mantissa field: longest code 7 (refill period 4), then 12 (2)
-        for tail in (40, 200):
-            draw = rng.integers(0, tail, n) if tail == 40 else np.minimum(rng.geometric(0.12, n) - 1, tail - 1)
-            sm2 = (draw.astype(np.uint16) * 7 + 1) & 0xFF
-            bits2 = ((sm2 >> 7) << 15) | (ex << 7) | (sm2 & 0x7F)
-            src2 = torch.from_numpy(bits2.astype(np.uint16).view(np.uint8).copy())
-            want2, _, _ = check_case(zc.FMT_BF16, n, cb, S, zc.POLICY_HUFF_ALL, data=(src2, None), tag="bf16-periods-%d-sm%d" % (n_exp, tail))
-            info2 = o_info(want2)
-            assert info2["mode"][1] == 1 and (5 <= info2["lmax"][1] <= 8 if tail == 40 else info2["lmax"][1] >= 9), (n_exp, tail, info2)
+    for S, cb in ((64, 8192), (8, 1024)):
+        n = 7 * (cb // 2) + 333                                 # seven whole chunks and a short one for the generic kernel
+        sm = rng.integers(0, 256, n).astype(np.uint16)          # every sign+mantissa byte occurs: flat code / raw
+        base = torch.from_numpy((rng.integers(0, 2, n, dtype=np.uint16) << 15).view(np.uint8).copy())     # flips signs only
+        for n_exp, skew, lmax in ((2, 0, 1), (5, 0, 3), (12, 0, 4), (40, 0, 6), (200, 0.08, None), (201, 0.08, None)):
+            # equally likely exponents (short codes) or a geometric tail (long ones), the last with one exponent that
+            # takes 60 % of the values (a 1-bit code) in front of that tail
+            pick = rng.integers(0, n_exp, n) if skew == 0 else np.minimum(rng.geometric(skew, n) - 1, 199)
+            if n_exp == 201:
+                pick = np.where(rng.random(n) < 0.6, 200, pick)
+            ex = (pick.astype(np.uint16) * 3 + 60) & 0xFF
+            bits = ((sm >> 7) << 15) | (ex << 7) | (sm & 0x7F)
+            src = torch.from_numpy(bits.astype(np.uint16).view(np.uint8).copy())
+            for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+                for b in (None, base):
+                    want, _, _ = check_case(zc.FMT_BF16, n, cb, S, policy, data=(src, None), base=b, tag="bf16-periods-%d" % n_exp)
+            info = o_info(want)
+            assert info["mode"][0] == 1 and (info["lmax"][0] == lmax if lmax else info["lmax"][0] >= 9), (n_exp, info)   # the case is what it is meant to be
+            if S != 64:
+                continue
+            # the same exponents beside a table-coded sign+mantissa field: longest code 5..8 (refill period 4), then beyond (2)
+            for tail in (40, 200):
+                draw = rng.integers(0, tail, n) if tail == 40 else np.minimum(rng.geometric(0.12, n) - 1, tail - 1)
+                sm2 = (draw.astype(np.uint16) * 7 + 1) & 0xFF
+                bits2 = ((sm2 >> 7) << 15) | (ex << 7) | (sm2 & 0x7F)
+                src2 = torch.from_numpy(bits2.astype(np.uint16).view(np.uint8).copy())
+                want2, _, _ = check_case(zc.FMT_BF16, n, cb, S, zc.POLICY_HUFF_ALL, data=(src2, None), tag="bf16-periods-%d-sm%d" % (n_exp, tail))
+                info2 = o_info(want2)
+                assert info2["mode"][1] == 1 and (5 <= info2["lmax"][1] <= 8 if tail == 40 else info2["lmax"][1] >= 9), (n_exp, tail, info2)
 
 
 def test_device_code_construction_hard_histograms():
