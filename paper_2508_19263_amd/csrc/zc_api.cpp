@@ -432,9 +432,6 @@ TensorDev make_desc(const zc_info &info)
     return d;
 }
 
-// shared by zc_compress_batch and zc_stats: histogram -> codes (-> sizes -> scan [-> encode])
-// dict: precomputed dictionary to code with (no histogram pass), or null.  train: stop after the
-// code construction with smoothed counts (codes_out receives the dictionary).
 uint32_t sub_slots_per_group(uint32_t streams, uint64_t slots);
 void order_for_xcds(std::vector<WorkItem> &items);
 
@@ -446,120 +443,178 @@ bool device_codes_enabled()
     return on;
 }
 
-zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, void *d_ws, uint64_t ws_bytes, void *stream,
-                       bool stats_only, std::vector<FieldCode> *codes_out, std::vector<ScanOut> *scan_out,
-                       const zc_info *dict = nullptr, bool train = false, bool no_sync = false)
-{
-    Geometry g;
-    zc_status st = check_params(params, &g);
-    if (st) return st;
-    if (T == 0) return ZC_OK;
-    if (!tensors || !d_ws || !aligned16(d_ws)) return ZC_ERR_INVALID_ARG;
-    std::vector<uint64_t> counts(T);
-    for (uint32_t t = 0; t < T; t++) {
-        zc_tensor &x = tensors[t];
-        counts[t] = x.n_elems;
-        if (x.n_elems && (!x.d_src || !aligned16(x.d_src))) return ZC_ERR_INVALID_ARG;
-        if (x.d_xor_base && !aligned16(x.d_xor_base)) return ZC_ERR_INVALID_ARG;
-        if (g.nf == 3 && x.n_elems && (!x.d_scales || !aligned16(x.d_scales))) return ZC_ERR_INVALID_ARG;
-        if (!stats_only && (!x.d_comp || !aligned16(x.d_comp))) return ZC_ERR_INVALID_ARG;
-    }
-    Workspace w;
-    st = plan_workspace(g, counts.data(), T, &w);
-    if (st) return st;
-    if (ws_bytes < w.total) return ZC_ERR_BUFFER_TOO_SMALL;
-    uint8_t *ws = (uint8_t *)d_ws;
-    hipStream_t hs = (hipStream_t)stream;
-    const uint32_t cpi = chunks_per_work_item(g.S);
+// One compress-side call (compress, statistics, dictionary training), from the argument checks to the last
+// kernel queued.  The members are what its steps share; run() is the sequence.
+class CompressCall {
+public:
+    // dict: precomputed dictionary to code with (no histogram pass), or null.  train: stop after the code
+    // construction with smoothed counts (codes_out receives the dictionary).  no_sync: queue everything, wait for
+    // nothing, read nothing back.
+    CompressCall(zc_tensor *tensors, uint32_t T, const zc_params *params, void *d_ws, uint64_t ws_bytes, void *stream,
+                 bool stats_only, std::vector<FieldCode> *codes_out, std::vector<ScanOut> *scan_out,
+                 const zc_info *dict, bool train, bool no_sync)
+        : tensors(tensors), T(T), params(params), ws((uint8_t *)d_ws), ws_bytes(ws_bytes), stream(stream), hs((hipStream_t)stream),
+          stats_only(stats_only), codes_out(codes_out), scan_out(scan_out), dict(dict), train(train), no_sync(no_sync) {}
 
-    // descriptors and work lists
-    std::vector<TensorDev> descs(T);
-    std::vector<WorkItem> hist_work, scale_work;
-    std::vector<uint64_t> ncs(T);
-    uint64_t units_off = 0;
-    for (uint32_t t = 0; t < T; t++) {
-        zc_tensor &x = tensors[t];
-        uint64_t nc;
-        check_count(g, x.n_elems, &nc);
-        ncs[t] = nc;
-        uint64_t table_off[3] = {0, 0, 0}, index_off[3] = {0, 0, 0}, payload_off;
-        layout(g.fmt, nc, table_off, index_off, &payload_off);
-        if (!stats_only && x.comp_capacity < payload_off) return ZC_ERR_BUFFER_TOO_SMALL;
-        TensorDev &d = descs[t];
-        std::memset(&d, 0, sizeof(d));
-        d.src = (const uint8_t *)x.d_src; d.base = (const uint8_t *)x.d_xor_base; d.scales = (const uint8_t *)x.d_scales;
-        d.comp = stats_only ? nullptr : (uint8_t *)x.d_comp;
-        d.n_elems = x.n_elems; d.n_chunks = (uint32_t)nc; d.chunk_bytes = g.chunk_bytes; d.streams = g.S;
-        d.payload_off = payload_off;
-        for (uint32_t f = 0; f < g.nf; f++) { d.table_off[f] = (uint32_t)table_off[f]; d.index_off[f] = (uint32_t)index_off[f]; }
-        d.dst_bytes = stats_only ? 0 : x.comp_capacity;         // compress: bytes that may be written at comp
-        d.units_off = (uint32_t)units_off;
-        units_off += nc * g.nf;
-        const uint64_t bytes = (x.n_elems * (uint64_t)elem_bits(g.fmt) + 7) / 8;
-        for (uint64_t b = 0; b * kHistBlockBytes < bytes; b++) hist_work.push_back({t, (uint32_t)b});
-        if (g.nf == 3) for (uint64_t b = 0; b * kHistBlockBytes < x.n_elems / scale_block(g.fmt); b++) scale_work.push_back({t, (uint32_t)b});
+    zc_status run()
+    {
+        zc_status st = check_params(params, &g);
+        if (st) return st;
+        if (T == 0) return ZC_OK;
+        st = prepare();
+        if (st) return st;
+        if (!dict && !stats_only && !train && device_codes_enabled()) return run_with_device_codes();
+        return run_with_host_codes();
     }
-    TensorDev *d_descs = (TensorDev *)(ws + w.descs);
-    uint64_t *d_hist = (uint64_t *)(ws + w.hist);
-    const uint32_t *d_enc = (const uint32_t *)(ws + w.enc);
-    uint32_t *d_units = (uint32_t *)(ws + w.units);
+
+private:
+    // ---- arguments
+    zc_tensor *const tensors;
+    const uint32_t T;
+    const zc_params *const params;
+    uint8_t *const ws;
+    const uint64_t ws_bytes;
+    void *const stream;
+    const hipStream_t hs;
+    const bool stats_only;
+    std::vector<FieldCode> *const codes_out;
+    std::vector<ScanOut> *const scan_out;
+    const zc_info *const dict;
+    const bool train, no_sync;
+    // ---- what prepare() derives from them
+    Geometry g;
+    Workspace w;
+    uint32_t cpi = 0;                       // chunks per work item of the generic kernels
+    std::vector<TensorDev> descs;
+    std::vector<uint64_t> ncs;              // chunks per tensor
+    std::vector<WorkItem> hist_work, scale_work;
+    bool bf16 = false;
+    bool whole_shape = false;               // 64 lanes, chunks of whole 1 KiB rows: the generic encoder's whole-chunk build
+    int whole_mode = 1;                     // 2: one whole chunk per work item, shared by its four wavefronts
+    uint32_t whole_step = 0, fast_step = 0; // chunks per work item of the whole-chunk list and of the fast list
+    bool roomy = false;                     // every destination can hold the worst case
+    // Work lists of the size pass and the encoder.  fast: whole chunks for the FP8 kernels and the page kernels'
+    // BF16 builds; whole: whole chunks for the generic encoder's 64-lane build (and the BF16 encoder); other: whole
+    // chunks for the generic encoder where neither applies to the geometry but a specialised kernel might have taken
+    // them (device-built codes only: the route is not known when the lists are written); slow: everything else (a
+    // short last chunk, odd geometries).
+    std::vector<WorkItem> fast_work, whole_work, other_work, slow_work;
+
+    TensorDev *d_descs() const { return (TensorDev *)(ws + w.descs); }
+    uint64_t *d_hist() const { return (uint64_t *)(ws + w.hist); }
+    uint32_t *d_enc() const { return (uint32_t *)(ws + w.enc); }
+    uint32_t *d_units() const { return (uint32_t *)(ws + w.units); }
+    const WorkItem *d_list(uint64_t off) const { return (const WorkItem *)(ws + off); }
+
     // Geometry the specialised FP8 size/encode kernels take: 64 lanes and chunks of whole 1 KiB rows, or 4..32
     // lanes per chunk (pages) for the sub-wavefront kernels as long as the tensor fits their 32-bit offsets.
-    // Whether the code suits them too (exponent refill period 4, i.e. a longest code of 5..8 bits, sign+mantissa
-    // flat coded or raw) is known once the code is: descs[t].route.
-    // The page kernels (4..32 lanes) also have BF16 builds: exponent field table coded, sign+mantissa flat or raw.
-    auto fast_shape = [&](uint32_t t) {
+    // The page kernels also have BF16 builds.  Whether the code suits them too is known once the code is:
+    // descs[t].route.
+    bool fast_shape(uint32_t t) const
+    {
         if (g.fmt == ZC_FMT_BF16) return g.S >= 4 && g.S < 64 && g.chunk_bytes % (16 * g.S) == 0 && tensors[t].n_elems * 2 <= 0xF0000000ull;
         if (g.fmt != ZC_FMT_FP8_E4M3) return false;
         return g.S == 64 ? g.chunk_bytes % 1024 == 0
                          : (g.S >= 4 && g.chunk_bytes % (16 * g.S) == 0 && tensors[t].n_elems <= 0xF0000000ull);
-    };
-    const bool bf16 = g.fmt == ZC_FMT_BF16;
-    const bool whole_shape = g.S == 64 && g.chunk_bytes % 1024 == 0;       // the generic encoder's whole-chunk build
-    // FP4 elements rarely compress, so their fields are stored plainly and a chunk's rows can be shared by the four
-    // wavefronts of a workgroup: one chunk per work item there
-    const int whole_mode = is_fp4(g.fmt) ? 2 : 1;
-    const uint32_t whole_step = whole_mode == 2 ? 1u : kWavesPerGroup;
-    uint64_t all_chunks = 0;
-    for (uint32_t t = 0; t < T; t++) all_chunks += ncs[t];
-    const uint32_t fast_step = g.S == 64 ? kWavesPerGroup : sub_slots_per_group(g.S, all_chunks);    // chunks per fast work item
-    bool roomy = !stats_only;
-    for (uint32_t t = 0; t < T && roomy; t++) roomy = tensors[t].comp_capacity >= zc_compress_bound(tensors[t].n_elems, params);
-    if (no_sync && !roomy) return ZC_ERR_BUFFER_TOO_SMALL;
+    }
 
-    // Work lists of the size pass and the encoder.  fast: whole chunks for the FP8 kernels (route 1); whole: whole
-    // chunks for the generic encoder's 64-lane build; other: whole chunks for the generic encoder where neither
-    // of those applies to the geometry but the FP8 kernels might have (route 0 only); slow: everything else (a short
-    // last chunk, odd geometries).
-    std::vector<WorkItem> fast_work, whole_work, other_work, slow_work;
+    // argument checks, workspace layout, descriptors, histogram work lists
+    zc_status prepare()
+    {
+        if (!tensors || !ws || !aligned16(ws)) return ZC_ERR_INVALID_ARG;
+        std::vector<uint64_t> counts(T);
+        for (uint32_t t = 0; t < T; t++) {
+            zc_tensor &x = tensors[t];
+            counts[t] = x.n_elems;
+            if (x.n_elems && (!x.d_src || !aligned16(x.d_src))) return ZC_ERR_INVALID_ARG;
+            if (x.d_xor_base && !aligned16(x.d_xor_base)) return ZC_ERR_INVALID_ARG;
+            if (g.nf == 3 && x.n_elems && (!x.d_scales || !aligned16(x.d_scales))) return ZC_ERR_INVALID_ARG;
+            if (!stats_only && (!x.d_comp || !aligned16(x.d_comp))) return ZC_ERR_INVALID_ARG;
+        }
+        zc_status st = plan_workspace(g, counts.data(), T, &w);
+        if (st) return st;
+        if (ws_bytes < w.total) return ZC_ERR_BUFFER_TOO_SMALL;
+        cpi = chunks_per_work_item(g.S);
+        descs.resize(T);
+        ncs.resize(T);
+        uint64_t units_off = 0, all_chunks = 0;
+        for (uint32_t t = 0; t < T; t++) {
+            zc_tensor &x = tensors[t];
+            uint64_t nc;
+            check_count(g, x.n_elems, &nc);
+            ncs[t] = nc;
+            all_chunks += nc;
+            uint64_t table_off[3] = {0, 0, 0}, index_off[3] = {0, 0, 0}, payload_off;
+            layout(g.fmt, nc, table_off, index_off, &payload_off);
+            if (!stats_only && x.comp_capacity < payload_off) return ZC_ERR_BUFFER_TOO_SMALL;
+            TensorDev &d = descs[t];
+            std::memset(&d, 0, sizeof(d));
+            d.src = (const uint8_t *)x.d_src; d.base = (const uint8_t *)x.d_xor_base; d.scales = (const uint8_t *)x.d_scales;
+            d.comp = stats_only ? nullptr : (uint8_t *)x.d_comp;
+            d.n_elems = x.n_elems; d.n_chunks = (uint32_t)nc; d.chunk_bytes = g.chunk_bytes; d.streams = g.S;
+            d.payload_off = payload_off;
+            for (uint32_t f = 0; f < g.nf; f++) { d.table_off[f] = (uint32_t)table_off[f]; d.index_off[f] = (uint32_t)index_off[f]; }
+            d.dst_bytes = stats_only ? 0 : x.comp_capacity;         // compress: bytes that may be written at comp
+            d.units_off = (uint32_t)units_off;
+            units_off += nc * g.nf;
+            const uint64_t bytes = (x.n_elems * (uint64_t)elem_bits(g.fmt) + 7) / 8;
+            for (uint64_t b = 0; b * kHistBlockBytes < bytes; b++) hist_work.push_back({t, (uint32_t)b});
+            if (g.nf == 3) for (uint64_t b = 0; b * kHistBlockBytes < x.n_elems / scale_block(g.fmt); b++) scale_work.push_back({t, (uint32_t)b});
+        }
+        bf16 = g.fmt == ZC_FMT_BF16;
+        whole_shape = g.S == 64 && g.chunk_bytes % 1024 == 0;
+        // FP4 elements rarely compress, so their fields are stored plainly and a chunk's rows can be shared by the four
+        // wavefronts of a workgroup: one chunk per work item there
+        whole_mode = is_fp4(g.fmt) ? 2 : 1;
+        whole_step = whole_mode == 2 ? 1u : kWavesPerGroup;
+        fast_step = g.S == 64 ? kWavesPerGroup : sub_slots_per_group(g.S, all_chunks);
+        roomy = !stats_only;
+        for (uint32_t t = 0; t < T && roomy; t++) roomy = tensors[t].comp_capacity >= zc_compress_bound(tensors[t].n_elems, params);
+        if (no_sync && !roomy) return ZC_ERR_BUFFER_TOO_SMALL;
+        return ZC_OK;
+    }
+
+    // field split + histogram (a1-a3)
+    zc_status queue_histogram()
+    {
+        LAUNCH_TRY(launch_zero(d_hist(), (uint64_t)T * 3 * 256, stream));
+        LAUNCH_TRY(launch_hist(g.fmt, d_descs(), d_list(w.hist_work), (uint32_t)hist_work.size(), 0, d_hist(), stream));
+        if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs(), d_list(w.scale_work), (uint32_t)scale_work.size(), (int)scale_block(g.fmt), d_hist(), stream));
+        return ZC_OK;
+    }
+
     // stream sizes (a5) and their exclusive scan into the chunk index (a6)
-    auto launch_sizes_and_scan = [&]() -> zc_status {
-        if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, stream));
-        else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 0, bf16, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
+    zc_status queue_sizes_and_scan()
+    {
+        if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs(), d_list(w.fast_work), (uint32_t)fast_work.size(), d_enc(), d_units(), stream));
+        else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 0, bf16, d_descs(), d_list(w.fast_work), (uint32_t)fast_work.size(), d_enc(), d_units(), fast_step, stream));
         // generic kernels: the whole-chunk list leaves route 1 to the FP8 kernels (route 2 there is the BF16 encoder,
         // whose sizes come from this pass); the list of page-shaped tensors leaves both routes to the page kernels
-        LAUNCH_TRY(launch_sizes(g.fmt, whole_mode, 0x2, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, d_units, stream));
-        LAUNCH_TRY(launch_sizes(g.fmt, 0, 0x6, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, d_units, stream));
-        LAUNCH_TRY(launch_sizes(g.fmt, 0, 0, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, d_units, stream));
-        LAUNCH_TRY(launch_scan(d_descs, T, (int)g.nf, d_units, (ScanOut *)(ws + w.scan), stream));
+        LAUNCH_TRY(launch_sizes(g.fmt, whole_mode, 0x2, d_descs(), d_list(w.whole_work), (uint32_t)whole_work.size(), d_enc(), d_units(), stream));
+        LAUNCH_TRY(launch_sizes(g.fmt, 0, 0x6, d_descs(), d_list(w.other_work), (uint32_t)other_work.size(), d_enc(), d_units(), stream));
+        LAUNCH_TRY(launch_sizes(g.fmt, 0, 0, d_descs(), d_list(w.chunk_work), (uint32_t)slow_work.size(), d_enc(), d_units(), stream));
+        LAUNCH_TRY(launch_scan(d_descs(), T, (int)g.nf, d_units(), (ScanOut *)(ws + w.scan), stream));
         return ZC_OK;
-    };
+    }
+
     // chunked encode (a7)
-    auto launch_encoders = [&]() -> zc_status {
-        if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, stream));
-        else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, bf16, d_descs, (const WorkItem *)(ws + w.fast_work), (uint32_t)fast_work.size(), d_enc, d_units, fast_step, stream));
-        LAUNCH_TRY(launch_encode(g.fmt, whole_mode, 0x6, d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
-        if (bf16) LAUNCH_TRY(launch_encode_bf16(d_descs, (const WorkItem *)(ws + w.whole_work), (uint32_t)whole_work.size(), d_enc, stream));
-        LAUNCH_TRY(launch_encode(g.fmt, 0, 0x6, d_descs, (const WorkItem *)(ws + w.other_work), (uint32_t)other_work.size(), d_enc, stream));
-        LAUNCH_TRY(launch_encode(g.fmt, 0, 0, d_descs, (const WorkItem *)(ws + w.chunk_work), (uint32_t)slow_work.size(), d_enc, stream));
+    zc_status queue_encoders()
+    {
+        if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs(), d_list(w.fast_work), (uint32_t)fast_work.size(), d_enc(), stream));
+        else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, bf16, d_descs(), d_list(w.fast_work), (uint32_t)fast_work.size(), d_enc(), d_units(), fast_step, stream));
+        LAUNCH_TRY(launch_encode(g.fmt, whole_mode, 0x6, d_descs(), d_list(w.whole_work), (uint32_t)whole_work.size(), d_enc(), stream));
+        if (bf16) LAUNCH_TRY(launch_encode_bf16(d_descs(), d_list(w.whole_work), (uint32_t)whole_work.size(), d_enc(), stream));
+        LAUNCH_TRY(launch_encode(g.fmt, 0, 0x6, d_descs(), d_list(w.other_work), (uint32_t)other_work.size(), d_enc(), stream));
+        LAUNCH_TRY(launch_encode(g.fmt, 0, 0, d_descs(), d_list(w.chunk_work), (uint32_t)slow_work.size(), d_enc(), stream));
         return ZC_OK;
-    };
-    // When every destination can hold the worst case, the sizes need not be known on the host first: the encoder
-    // is queued right behind the scan and the sizes are read back meanwhile (or, for a call that does not
-    // synchronise, not at all: they are in the containers' headers).  Otherwise the host waits for the sizes and
-    // checks them before anything is written.  `landing`: page-locked, first the ScanOut of every tensor, then
-    // extra_bytes copied from d_extra.
-    auto encode_and_read_sizes = [&](LandingLease &landing, const void *d_extra, uint64_t extra_bytes) -> zc_status {
+    }
+
+    // The tail of every call that reads sizes back.  When every destination can hold the worst case, the sizes
+    // need not be known on the host first: the encoder is queued right behind the scan and the sizes are read back
+    // meanwhile.  Otherwise the host waits for the sizes and checks them before anything is written.  `landing`:
+    // page-locked, first the ScanOut of every tensor, then extra_bytes copied from d_extra.
+    zc_status encode_and_read_sizes(LandingLease &landing, const void *d_extra, uint64_t extra_bytes)
+    {
         const uint64_t scan_bytes = (uint64_t)T * sizeof(ScanOut);
         HIP_TRY(hipMemcpyAsync(landing.ptr, ws + w.scan, scan_bytes, hipMemcpyDeviceToHost, hs));
         if (extra_bytes) HIP_TRY(hipMemcpyAsync(landing.ptr + scan_bytes, d_extra, extra_bytes, hipMemcpyDeviceToHost, hs));
@@ -568,7 +623,7 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
             hipEvent_t copied;
             HIP_TRY(hipEventCreateWithFlags(&copied, hipEventDisableTiming));
             const hipError_t e1 = hipEventRecord(copied, hs);
-            const zc_status s1 = e1 == hipSuccess ? launch_encoders() : ZC_ERR_DEVICE;
+            const zc_status s1 = e1 == hipSuccess ? queue_encoders() : ZC_ERR_DEVICE;
             const hipError_t e2 = e1 == hipSuccess ? hipEventSynchronize(copied) : e1;
             (void)hipEventDestroy(copied);
             if (s1) return s1;
@@ -582,14 +637,23 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         }
         if (scan_out) scan_out->assign(scan, scan + T);
         if (stats_only || roomy) return ZC_OK;
-        return launch_encoders();
-    };
+        return queue_encoders();
+    }
 
-    if (!dict && !stats_only && !train && device_codes_enabled()) {
-        // ---- the code is built on the device (a4): nothing between the histogram and the encoder waits for the host
+    // a call that waits for nothing: the sizes stay in the containers' headers
+    zc_status queue_encoders_without_sizes()
+    {
+        for (uint32_t t = 0; t < T; t++) tensors[t].out_bytes = 0;
+        return queue_encoders();
+    }
+
+    // ---- the code is built on the device (a4): nothing between the histogram and the encoder waits for the host
+    zc_status run_with_device_codes()
+    {
         std::vector<uint8_t> blobs((size_t)T * kBlobBytes, 0);
         const FieldCode no_code[3] = {};
         for (uint32_t t = 0; t < T; t++) {
+            // the route is not known yet: whole chunks are listed for every kernel that may take them
             const uint64_t whole_chunks = tensors[t].n_elems / g.elems_per_chunk;
             const bool fs = fast_shape(t);
             descs[t].fast_shape = (fs || (bf16 && whole_shape)) ? 1 : 0;
@@ -614,22 +678,18 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
                               {w.whole_work, whole_work.data(), whole_work.size() * sizeof(WorkItem)},
                               {w.other_work, other_work.data(), other_work.size() * sizeof(WorkItem)},
                               {w.blobs, blobs.data(), blobs.size()}};
-        st = host_stage().upload(ws, w.descs, w.enc, all, 8, hs);
+        zc_status st = host_stage().upload(ws, w.descs, w.enc, all, 8, hs);
         if (st) return st;
-        LAUNCH_TRY(launch_zero(d_hist, (uint64_t)T * 3 * 256, stream));
-        LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
-        if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), (int)scale_block(g.fmt), d_hist, stream));
+        st = queue_histogram();
+        if (st) return st;
         CodeParams cp;
         cp.fmt = g.fmt; cp.policy = params->policy; cp.nf = g.nf; cp.blob_bytes = (uint32_t)kBlobBytes; cp.run_len = (uint32_t)run_len(g.fmt, 0);
         for (int f = 0; f < kMaxFields; f++) cp.limit[f] = f < (int)g.nf ? g.limit[f] : 0;
-        LAUNCH_TRY(launch_codes(d_descs, T, d_hist, cp, ws + w.blobs, (uint32_t *)(ws + w.enc), stream));
-        LAUNCH_TRY(launch_write_headers(d_descs, T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
-        st = launch_sizes_and_scan();
+        LAUNCH_TRY(launch_codes(d_descs(), T, d_hist(), cp, ws + w.blobs, d_enc(), stream));
+        LAUNCH_TRY(launch_write_headers(d_descs(), T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
+        st = queue_sizes_and_scan();
         if (st) return st;
-        if (no_sync) {
-            for (uint32_t t = 0; t < T; t++) tensors[t].out_bytes = 0;
-            return launch_encoders();
-        }
+        if (no_sync) return queue_encoders_without_sizes();
         LandingLease landing((uint64_t)T * (sizeof(ScanOut) + kBlobBytes));
         if (!landing.ptr) return ZC_ERR_DEVICE;
         st = encode_and_read_sizes(landing, ws + w.blobs, (uint64_t)T * kBlobBytes);
@@ -648,38 +708,34 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
     }
 
     // ---- the code is built on the host: a dictionary, statistics, training
-    // The histograms land in page-locked memory; what the code construction fills is allocated (and its pages
-    // touched) while the histogram kernel runs.
-    const uint64_t hist_bytes = dict ? 0 : (uint64_t)T * 768 * 8;
-    LandingLease landing(hist_bytes);
-    if (hist_bytes && !landing.ptr) return ZC_ERR_DEVICE;
-    const uint64_t *hist = reinterpret_cast<const uint64_t *>(landing.ptr);
-    std::vector<FieldCode> codes;
-    std::vector<uint32_t> enc;
-    std::vector<uint8_t> blobs;
-    auto allocate_tables = [&]() {
-        codes.resize((size_t)T * 3);
-        enc.assign((size_t)T * 768, 0);
-        blobs.assign((size_t)T * kBlobBytes, 0);
-    };
+    std::vector<FieldCode> codes;           // three per tensor
+    std::vector<uint32_t> enc;              // 768 encode-table entries per tensor
+    std::vector<uint8_t> blobs;             // header + code-length tables per tensor
+    const uint64_t *hist = nullptr;         // the device histograms, landed
+
     // code construction on the host (a4), one tensor
-    auto build_one = [&](uint32_t t) -> zc_status {
+    zc_status build_one(uint32_t t)
+    {
         FieldCode *fc = &codes[(size_t)t * 3];
         const zc_status s1 = dict ? codes_from_dictionary(g, tensors[t].n_elems, *dict, fc)
                                   : build_codes(g, params->policy, tensors[t].n_elems, &hist[(size_t)t * 768], fc, train);
         if (s1) return s1;
         fill_info(g, params->policy, tensors[t].d_xor_base != nullptr, tensors[t].n_elems, ncs[t], fc, 0, &tensors[t].info);
         serialize_blob(tensors[t].info, &blobs[(size_t)t * kBlobBytes]);
+        TensorDev &d = descs[t];
         for (uint32_t f = 0; f < g.nf; f++) {
-            descs[t].mode[f] = (uint8_t)fc[f].mode; descs[t].lmax[f] = (uint8_t)fc[f].lmax; descs[t].konst[f] = (uint8_t)fc[f].konst;
-            descs[t].period[f] = (uint8_t)refill_period(run_len(g.fmt, (int)f), (int)fc[f].lmax);
-            descs[t].kind[f] = field_kind(fc[f].mode, (uint32_t)sym_bits(g.fmt, (int)f), fc[f].len);
+            d.mode[f] = (uint8_t)fc[f].mode; d.lmax[f] = (uint8_t)fc[f].lmax; d.konst[f] = (uint8_t)fc[f].konst;
+            d.period[f] = (uint8_t)refill_period(run_len(g.fmt, (int)f), (int)fc[f].lmax);
+            d.kind[f] = field_kind(fc[f].mode, (uint32_t)sym_bits(g.fmt, (int)f), fc[f].len);
             const int A = 1 << sym_bits(g.fmt, (int)f);
             for (int v = 0; v < A; v++)
                 enc[(size_t)t * 768 + f * 256 + v] = ((uint32_t)fc[f].len[v] << 16) | reverse_bits(fc[f].code[v], fc[f].len[v]);
         }
-        // the FP8 kernels' table (slot of the unused third field) maps a pair of exponents to the two codes concatenated
-        const bool fast_ok = !bf16 && fast_shape(t) && fc[0].mode == ZC_MODE_HUFF && descs[t].period[0] == 4 && (descs[t].kind[1] == 1 || descs[t].kind[1] == 2);
+        // FP8: the specialised kernels are written for an exponent refill period of 4 (longest code 5..8 bits) and a flat
+        // or raw sign+mantissa field; their table (slot of the unused third field) maps a pair of exponents to the two
+        // codes concatenated
+        const bool plain_sm = d.kind[1] == 1 || d.kind[1] == 2;
+        const bool fast_ok = !bf16 && fast_shape(t) && fc[0].mode == ZC_MODE_HUFF && d.period[0] == 4 && plain_sm;
         if (fast_ok)
             for (uint32_t u = 0; u < 256; u++) {
                 const uint32_t e0 = u & 15, e1 = u >> 4, l0 = fc[0].len[e0], l1 = fc[0].len[e1];
@@ -690,53 +746,64 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
         // exponents per refill step, no 1-bit code (the bound on their staging ring needs 4 bits per step)
         uint32_t lmin = 16;
         for (int v = 0; v < 256; v++) if (fc[0].len[v] && fc[0].len[v] < lmin) lmin = fc[0].len[v];
-        const bool plain_sm = descs[t].kind[1] == 1 || descs[t].kind[1] == 2;
-        const bool bf16_ok = bf16 && descs[t].kind[0] == 0 &&
-                             (whole_shape ? (plain_sm || (descs[t].kind[1] == 0 && (descs[t].period[1] == 2 || descs[t].period[1] == 4)))
-                                          : (fast_shape(t) && plain_sm && (descs[t].period[0] != 2 || lmin >= 2)));
-        descs[t].route = (!bf16 && fast_ok) ? 1 : bf16_ok ? 2 : 0;
+        const bool bf16_ok = bf16 && d.kind[0] == 0 &&
+                             (whole_shape ? (plain_sm || (d.kind[1] == 0 && (d.period[1] == 2 || d.period[1] == 4)))
+                                          : (fast_shape(t) && plain_sm && (d.period[0] != 2 || lmin >= 2)));
+        d.route = fast_ok ? 1 : bf16_ok ? 2 : 0;
         return ZC_OK;
-    };
-    // The worker threads are started once the histogram kernel is queued and before the wait for it, so that
-    // their start-up (tens of microseconds each) is hidden behind it; they sleep until run() opens the gate.
-    // With a dictionary there is nothing to wait for and little to do per tensor: one thread.
-    const uint32_t n_threads = (!dict && T >= 8) ? std::min<uint32_t>(std::min<uint32_t>(8, T / 2), std::max(1u, std::thread::hardware_concurrency())) : 1;
-    std::optional<CodeCrew> crew;
-    // field split + histogram (a1-a3); not needed when the code comes from a dictionary
-    if (!dict) {
-        const Piece first[3] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
-                                {w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem)},
-                                {w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem)}};
-        st = host_stage().upload(ws, w.descs, w.chunk_work, first, 3, hs);
-        if (st) return st;
-        LAUNCH_TRY(launch_zero(d_hist, (uint64_t)T * 3 * 256, stream));
-        LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.hist_work), (uint32_t)hist_work.size(), 0, d_hist, stream));
-        if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs, (const WorkItem *)(ws + w.scale_work), (uint32_t)scale_work.size(), (int)scale_block(g.fmt), d_hist, stream));
-        HIP_TRY(hipMemcpyAsync(landing.ptr, d_hist, hist_bytes, hipMemcpyDeviceToHost, hs));
-        crew.emplace(T, n_threads, build_one);
-        allocate_tables();
-        HIP_TRY(hipStreamSynchronize(hs));
-    } else {
-        crew.emplace(T, n_threads, build_one);
-        allocate_tables();
     }
 
-    st = crew->run();
-    if (st) return st;
-    for (uint32_t t = 0; t < T; t++) {
-        // the route is known, so every chunk is listed once
-        const uint64_t whole_chunks = tensors[t].n_elems / g.elems_per_chunk;
-        const uint64_t n_fast = (descs[t].route == 1 || (descs[t].route == 2 && !whole_shape)) ? whole_chunks : 0;
-        const uint64_t n_whole = (descs[t].route != 1 && whole_shape) ? whole_chunks : 0;
-        for (uint64_t c = 0; c < n_fast; c += fast_step) fast_work.push_back({t, (uint32_t)c});
-        for (uint64_t c = 0; c < n_whole; c += whole_step) whole_work.push_back({t, (uint32_t)c});
-        for (uint64_t c = n_fast + n_whole; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
-    }
-    if (codes_out) *codes_out = codes;
-    order_for_xcds(fast_work);
-    order_for_xcds(whole_work);
-    order_for_xcds(slow_work);
+    zc_status run_with_host_codes()
     {
+        // The histograms land in page-locked memory; what the code construction fills is allocated (and its pages
+        // touched) while the histogram kernel runs.
+        const uint64_t hist_bytes = dict ? 0 : (uint64_t)T * 768 * 8;
+        LandingLease landing(hist_bytes);
+        if (hist_bytes && !landing.ptr) return ZC_ERR_DEVICE;
+        hist = reinterpret_cast<const uint64_t *>(landing.ptr);
+        auto allocate_tables = [&]() {
+            codes.resize((size_t)T * 3);
+            enc.assign((size_t)T * 768, 0);
+            blobs.assign((size_t)T * kBlobBytes, 0);
+        };
+        // The worker threads are started once the histogram kernel is queued and before the wait for it, so that
+        // their start-up (tens of microseconds each) is hidden behind it; they sleep until run() opens the gate.
+        // With a dictionary there is nothing to wait for and little to do per tensor: one thread.
+        const uint32_t n_threads = (!dict && T >= 8) ? std::min<uint32_t>(std::min<uint32_t>(8, T / 2), std::max(1u, std::thread::hardware_concurrency())) : 1;
+        std::optional<CodeCrew> crew;
+        const auto one = [this](uint32_t t) { return build_one(t); };
+        zc_status st;
+        if (!dict) {
+            const Piece first[3] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
+                                    {w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem)},
+                                    {w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem)}};
+            st = host_stage().upload(ws, w.descs, w.chunk_work, first, 3, hs);
+            if (st) return st;
+            st = queue_histogram();
+            if (st) return st;
+            HIP_TRY(hipMemcpyAsync(landing.ptr, d_hist(), hist_bytes, hipMemcpyDeviceToHost, hs));
+            crew.emplace(T, n_threads, one);
+            allocate_tables();
+            HIP_TRY(hipStreamSynchronize(hs));
+        } else {
+            crew.emplace(T, n_threads, one);
+            allocate_tables();
+        }
+        st = crew->run();
+        if (st) return st;
+        for (uint32_t t = 0; t < T; t++) {
+            // the route is known, so every chunk is listed once
+            const uint64_t whole_chunks = tensors[t].n_elems / g.elems_per_chunk;
+            const uint64_t n_fast = (descs[t].route == 1 || (descs[t].route == 2 && !whole_shape)) ? whole_chunks : 0;
+            const uint64_t n_whole = (descs[t].route != 1 && whole_shape) ? whole_chunks : 0;
+            for (uint64_t c = 0; c < n_fast; c += fast_step) fast_work.push_back({t, (uint32_t)c});
+            for (uint64_t c = 0; c < n_whole; c += whole_step) whole_work.push_back({t, (uint32_t)c});
+            for (uint64_t c = n_fast + n_whole; c < ncs[t]; c += cpi) slow_work.push_back({t, (uint32_t)c});
+        }
+        if (codes_out) *codes_out = codes;
+        order_for_xcds(fast_work);
+        order_for_xcds(whole_work);
+        order_for_xcds(slow_work);
         // everything the kernels from here on read from the host, in one copy (the histogram work lists ride
         // along so that the copied range has no holes)
         const Piece all[8] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
@@ -749,19 +816,25 @@ zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, 
                               {w.enc, enc.data(), enc.size() * 4}};
         st = host_stage().upload(ws, w.descs, w.host_end, all, 8, hs);
         if (st) return st;
+        if (!stats_only) LAUNCH_TRY(launch_write_headers(d_descs(), T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
+        st = queue_sizes_and_scan();
+        if (st) return st;
+        if (no_sync) return queue_encoders_without_sizes();
+        LandingLease scan_landing((uint64_t)T * sizeof(ScanOut));
+        if (!scan_landing.ptr) return ZC_ERR_DEVICE;
+        st = encode_and_read_sizes(scan_landing, nullptr, 0);
+        for (uint32_t t = 0; t < T; t++) tensors[t].info.total_bytes = tensors[t].out_bytes;
+        return st;
     }
-    if (!stats_only) LAUNCH_TRY(launch_write_headers(d_descs, T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
-    st = launch_sizes_and_scan();
-    if (st) return st;
-    if (no_sync) {
-        for (uint32_t t = 0; t < T; t++) tensors[t].out_bytes = 0;
-        return launch_encoders();
-    }
-    LandingLease scan_landing((uint64_t)T * sizeof(ScanOut));
-    if (!scan_landing.ptr) return ZC_ERR_DEVICE;
-    st = encode_and_read_sizes(scan_landing, nullptr, 0);
-    for (uint32_t t = 0; t < T; t++) tensors[t].info.total_bytes = tensors[t].out_bytes;
-    return st;
+};
+
+// shared by every compress-side entry point: histogram -> codes (-> sizes -> scan [-> encode])
+zc_status run_compress(zc_tensor *tensors, uint32_t T, const zc_params *params, void *d_ws, uint64_t ws_bytes, void *stream,
+                       bool stats_only, std::vector<FieldCode> *codes_out, std::vector<ScanOut> *scan_out,
+                       const zc_info *dict = nullptr, bool train = false, bool no_sync = false)
+{
+    CompressCall call(tensors, T, params, d_ws, ws_bytes, stream, stats_only, codes_out, scan_out, dict, train, no_sync);
+    return call.run();
 }
 
 // Can the specialised FP8 kernel decode this container's full chunks?
