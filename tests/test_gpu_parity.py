@@ -279,6 +279,58 @@ def test_batch_round_trip_and_parity():
         assert torch.equal(outs[i].cpu()[:n], srcs[i])
 
 
+def test_batch_other_formats_and_mixed_tensors():
+    # the batch calls on MXFP4 (chunks shared by four wavefronts in both directions), on BF16 with a delta, and on
+    # a BF16 batch whose tensors take different kernels (compressible exponents, constant tensor, uniform noise,
+    # a tensor shorter than a chunk): every container is the oracle's, every tensor comes back
+    cb = 16384
+    mats = [wl.mxfp4_weight(64, 512 * (3 + i), seed=60 + i) for i in range(3)]
+    ns = [64 * 512 * (3 + i) for i in range(3)]
+    p = zc.params(zc.FMT_FP4_E2M1_MX, cb, streams=64, policy=zc.POLICY_AUTO)
+    po = o.params(o.FP4_E2M1_MX, cb, streams=64, policy=o.POLICY_AUTO)
+    b = zc.Batch([dev(m[0]) for m in mats], ns, p, scales=[dev(m[1]) for m in mats])
+    sizes = b.compress()
+    for i, n in enumerate(ns):
+        want = o.compress(mats[i][0].numpy(), n, po, scales=mats[i][1].numpy())
+        assert sizes[i] == len(want) and np.array_equal(b.container(i).cpu().numpy(), want), i
+    outs = b.decompress()
+    torch.cuda.synchronize()
+    for i, n in enumerate(ns):
+        assert torch.equal(outs[i].cpu()[:n // 2], mats[i][0]) and torch.equal(b.scales_out[i].cpu()[:n // 32], mats[i][1])
+    # BF16: a delta batch
+    pairs = [wl.bf16_checkpoint_pair(40000 + 777 * i, seed=70 + i) for i in range(3)]
+    raw = [[x.view(torch.uint8).reshape(-1) for x in pr] for pr in pairs]
+    ns = [pr[0].numel() for pr in pairs]
+    p, po = zc.params(zc.FMT_BF16, 8192), o.params(o.BF16, 8192)
+    b = zc.Batch([dev(r[1]) for r in raw], ns, p, xor_bases=[dev(r[0]) for r in raw])
+    sizes = b.compress()
+    for i, n in enumerate(ns):
+        want = o.compress(raw[i][1].numpy(), n, po, xor_base=raw[i][0].numpy())
+        assert sizes[i] == len(want) and np.array_equal(b.container(i).cpu().numpy(), want), i
+    outs = b.decompress()
+    torch.cuda.synchronize()
+    for i in range(3):
+        assert torch.equal(outs[i].cpu()[:raw[i][1].numel()], raw[i][1])
+    # BF16: tensors of different character in one batch
+    rng = np.random.default_rng(8)
+    srcs = [wl.bf16_weight(5 * 4096 + 11, seed=80).view(torch.uint8).reshape(-1),
+            torch.full((3 * 4096 * 2,), 0x3C, dtype=torch.uint8),
+            torch.from_numpy(rng.integers(0, 256, 4 * 4096 * 2, dtype=np.uint8)),
+            wl.bf16_weight(100, seed=81).view(torch.uint8).reshape(-1)]
+    ns = [s.numel() // 2 for s in srcs]
+    for policy, opolicy in ((zc.POLICY_HUFF_ALL, o.POLICY_HUFF_ALL), (zc.POLICY_AUTO, o.POLICY_AUTO)):
+        p, po = zc.params(zc.FMT_BF16, 8192, policy=policy), o.params(o.BF16, 8192, policy=opolicy)
+        b = zc.Batch([dev(s) for s in srcs], ns, p)
+        sizes = b.compress()
+        for i, n in enumerate(ns):
+            want = o.compress(srcs[i].numpy(), n, po)
+            assert sizes[i] == len(want) and np.array_equal(b.container(i).cpu().numpy(), want), (policy, i)
+        outs = b.decompress()
+        torch.cuda.synchronize()
+        for i in range(len(srcs)):
+            assert torch.equal(outs[i].cpu()[:srcs[i].numel()], srcs[i]), (policy, i)
+
+
 def test_errors():
     x = wl.fp8_weight(9000, seed=22).to(DEV)
     p = zc.params(zc.FMT_FP8_E4M3, 4096)
