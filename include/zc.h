@@ -245,8 +245,9 @@ zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors,
  * once: _plan validates, queues the upload of the descriptors and the work lists to d_ws on the
  * stream (from a page-locked buffer of the library's: no wait) and fills *plan (host); _run only
  * enqueues the decode kernels on d_ws as left by _plan, on the same stream or one ordered after it
- * (never synchronises).  The plan is plain data; it stays valid while d_ws, the containers
- * and the destination pointers are unchanged. */
+ * (never synchronises; it makes kernel launches and nothing else, so it may be recorded into a HIP
+ * graph by stream capture and replayed, _plan having completed before the capture).  The plan is
+ * plain data; it stays valid while d_ws, the containers and the destination pointers are unchanged. */
 typedef struct {
     uint32_t format, streams, n_tensors;
     uint32_t n_fast_work, n_work;               /* work items of the specialised / generic kernel */

@@ -1012,3 +1012,47 @@ def test_fp8_e5m2():
     check_case(F, u.numel(), 16384, 64, zc.POLICY_AUTO, data=(u, None), tag="e5m2-uniform")
     c = torch.full((2 * 16384 + 5,), 0x3C, dtype=torch.uint8)
     check_case(F, c.numel(), 16384, 64, data=(c, None), tag="e5m2-constant")
+
+
+def test_planned_decode_replays_from_a_captured_graph():
+    # A serving loop that decodes the same containers every step can record the planned decode once:
+    # zc_decompress_batch_run only launches kernels.  Every replay is checked against the source, with the
+    # outputs poisoned and eager work of this process in between (whole tensors, then a page list).
+    for fmt, cb, S, n_tensors, n in ((zc.FMT_FP8_E4M3, 262144, 64, 3, 5 * 262144 + 4099), (zc.FMT_FP8_E4M3, 2048, 8, 4, 96 * 2048),
+                                     (zc.FMT_BF16, 262144, 64, 2, 3 * 131072 + 77)):
+        srcs = [make_input(fmt, n, 300 + i)[0] for i in range(n_tensors)]
+        raws = [s.view(torch.uint8).reshape(-1) for s in srcs]
+        b = zc.Batch([dev(s) for s in srcs], [n] * n_tensors, zc.params(fmt, cb, streams=S))
+        b.compress()
+        ids = None
+        for use_ids in (False, True):
+            if use_ids:
+                if fmt != zc.FMT_FP8_E4M3 or cb != 2048:
+                    continue
+                ids = [wl.page_sample(n // cb, 0.5, seed=7 + i) for i in range(n_tensors)]
+                b.set_chunk_ids([i.to(DEV) for i in ids])
+            b.plan_decompress()
+            torch.cuda.synchronize()
+            side = torch.cuda.Stream()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(side):
+                b.run_decompress()                      # warm-up on the capture stream
+                side.synchronize()
+                with torch.cuda.graph(g, stream=side):
+                    b.run_decompress()
+            torch.cuda.synchronize()
+            for replay in range(4):
+                for o in b.out:
+                    o.fill_(0xA5)
+                junk = torch.arange(1 << 16, device=DEV).float().cumsum(0)      # unrelated eager work
+                torch.cuda.synchronize()
+                g.replay()
+                torch.cuda.synchronize()
+                for i in range(n_tensors):
+                    got = b.out[i].cpu()
+                    if use_ids:
+                        assert torch.equal(got.reshape(-1, cb), raws[i].reshape(-1, cb)[ids[i].long()]), (fmt, cb, replay, i)
+                    else:
+                        assert torch.equal(got[:raws[i].numel()], raws[i]), (fmt, cb, replay, i)
+                assert torch.isfinite(junk[-1])
+        b.set_chunk_ids(None)
