@@ -1,5 +1,6 @@
-// C ABI of the codec: argument checks, container layout, host-side code construction
-// between the histogram and the encode kernels, and kernel launches.  See include/zc.h.
+// C ABI of the codec: argument checks, container layout, work lists, kernel launches, and the host-side code
+// construction that dictionaries, statistics and ZC_HOST_CODES=1 use (a plain compress call builds its codes
+// on the device).  See include/zc.h.
 #include <hip/hip_runtime.h>
 
 #include <cmath>

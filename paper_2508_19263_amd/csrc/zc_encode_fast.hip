@@ -45,9 +45,11 @@ __device__ __forceinline__ void group_code(uint32_t w, const char *pair_lut, uin
     const uint32_t u = t | (t >> 4);                    // bytes 0 and 2: e0 | e1 << 4, e2 | e3 << 4
     const uint32_t a = *reinterpret_cast<const uint32_t *>(pair_lut + byte_times4<0>(u, two));
     const uint32_t b = *reinterpret_cast<const uint32_t *>(pair_lut + byte_times4<2>(u, two));
-    const uint32_t la = a >> 16;
-    code = (a & 0xFFFFu) | ((b & 0xFFFFu) << la);
-    len = la + (b >> 16);
+    // halves of the entries as operands: code = a.lo | b.lo << a.hi, len = a.hi + b.hi (a.hi <= 16)
+    uint32_t sh;
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1 src1_sel:WORD_0" : "=v"(sh) : "v"(a), "v"(b));
+    asm("v_or_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0" : "=v"(code) : "v"(sh), "v"(a));
+    asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1 src1_sel:WORD_1" : "=v"(len) : "v"(a), "v"(b));
 }
 
 }  // namespace
@@ -129,10 +131,15 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
     uint32_t *const ring = stage + (threadIdx.x >> 6) * kRing;
     const uint32_t two = 2;
 
-    uint64_t acc = 0;           // bits not yet written, next free bit = nacc (< 32 between groups)
+    // What a lane keeps of its stream.  The decoder it mirrors asks for a word whenever it holds k <= 32 unread
+    // bits; the word's position is fixed then, its content is complete later.  Requests minus writes is
+    // (k + nacc) / 32: never above 2 (a request needs k <= 32 and nacc < 32), and a write (nacc >= 32 while
+    // k >= 1) finds 2.  So one position is due (p0) and at most one more is waiting (p1): a request always sets
+    // p1, a write moves it to p0.  The first request of all (every lane, position = lane) is p0's start value.
+    uint32_t lo = 0;            // bits not yet written, next free bit = nacc (< 32 between groups)
     uint32_t nacc = 0;
     int32_t k = 0;              // unread bits the decoder would hold at this point
-    uint32_t pend = 0, p0 = 0, p1 = 0;     // words the decoder has asked for and we still owe, and where they go
+    uint32_t p0 = lane, p1 = lane;
     uint32_t wpos = 0;          // words of the stream handed out so far
     uint32_t flushed = 0;       // words of the stream that have left the ring
     const uint32_t rows = E / 1024;
@@ -143,23 +150,29 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
         if (has_base) y = __builtin_amdgcn_raw_buffer_load_b128(bas, (int)(lane * 16), (int)(row * 1024), 0);
     };
     auto encode_row = [&](const u32x4 &v, uint32_t row) {
-        // ---- sign+mantissa nibbles of the run, packed (symbol j at bits 4j)
-        uint32_t m[2];
-#pragma unroll
-        for (int h = 0; h < 2; h++) {
-            const uint32_t lo = pack_nibbles_of_bytes(((v[2 * h] >> 4) & 0x08080808u) | (v[2 * h] & 0x07070707u));
-            const uint32_t hi = pack_nibbles_of_bytes(((v[2 * h + 1] >> 4) & 0x08080808u) | (v[2 * h + 1] & 0x07070707u));
-            m[h] = lo | (hi << 16);
-        }
+        // ---- sign+mantissa nibbles of the run
         if (sm_raw) {
-            __builtin_amdgcn_raw_buffer_store_b64(u32x2{m[0], m[1]}, ms, (int)(lane * 8), (int)(row * 512), 0);
-        } else {
-            // flat code: each symbol written most significant bit first, one word per 8 symbols, rows of 64 words
+            // symbol j at bits 4j: nibbles of the even and of the odd bytes of two words, gathered with byte permutes
+            uint32_t m[2];
 #pragma unroll
             for (int h = 0; h < 2; h++) {
-                uint32_t w = ((m[h] >> 1) & 0x55555555u) | ((m[h] & 0x55555555u) << 1);
-                w = ((w >> 2) & 0x33333333u) | ((w & 0x33333333u) << 2);
-                __builtin_amdgcn_raw_buffer_store_b32(w, ms, (int)(lane * 4), (int)((row * 2 + h) * 256), 0);
+                const uint32_t x0 = ((v[2 * h] >> 4) & 0x08080808u) | (v[2 * h] & 0x07070707u);
+                const uint32_t x1 = ((v[2 * h + 1] >> 4) & 0x08080808u) | (v[2 * h + 1] & 0x07070707u);
+                const uint32_t even = __builtin_amdgcn_perm(x1, x0, 0x06040200u), odd = __builtin_amdgcn_perm(x1, x0, 0x07050301u);
+                m[h] = even | (odd << 4);
+            }
+            __builtin_amdgcn_raw_buffer_store_b64(u32x2{m[0], m[1]}, ms, (int)(lane * 8), (int)(row * 512), 0);
+        } else {
+            // flat code: each symbol most significant bit first, one word per 8 symbols, rows of 64 words.  A bit
+            // reversal of the source word puts s, m2, m1, m0 of every byte in this order already (bits 0, 5, 6, 7
+            // of the reversed byte) and reverses the bytes, which the permutes undo.
+#pragma unroll
+            for (int h = 0; h < 2; h++) {
+                const uint32_t r0 = __brev(v[2 * h]), r1 = __brev(v[2 * h + 1]);
+                const uint32_t x0 = ((r0 >> 4) & 0x0E0E0E0Eu) | (r0 & 0x01010101u);       // bytes: symbols 3, 2, 1, 0
+                const uint32_t x1 = ((r1 >> 4) & 0x0E0E0E0Eu) | (r1 & 0x01010101u);       // bytes: symbols 7, 6, 5, 4
+                const uint32_t even = __builtin_amdgcn_perm(x1, x0, 0x05070103u), odd = __builtin_amdgcn_perm(x1, x0, 0x04060002u);
+                __builtin_amdgcn_raw_buffer_store_b32(even | (odd << 4), ms, (int)(lane * 4), (int)((row * 2 + h) * 256), 0);
             }
         }
         // ---- exponent: one refill step of the decoder, then the four codes of a source word
@@ -167,21 +180,19 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
         for (int g = 0; g < 4; g++) {
             const bool req = k <= 32;
             const uint64_t bm = __ballot(req);
-            if (req) {
-                const uint32_t pos = wpos + __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, 0));
-                if (pend == 0) p0 = pos; else p1 = pos;
-                pend++;
-                k += 32;
-            }
+            const uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, wpos));
+            p1 = req ? pos : p1;
+            k += req ? 32 : 0;
             wpos += (uint32_t)__popcll(bm);
             uint32_t code, len;
             group_code(v[g], pair_lut, two, code, len);
-            acc |= (uint64_t)code << nacc;
+            const uint64_t placed = (uint64_t)code << nacc;       // nothing is left above bit nacc
+            lo |= (uint32_t)placed;
             nacc += len;
             k -= (int32_t)len;
             if (nacc >= 32) {
-                ring[p0 & (kRing - 1)] = (uint32_t)acc;
-                acc >>= 32; nacc -= 32; p0 = p1; pend--;
+                ring[p0 & (kRing - 1)] = lo;
+                lo = (uint32_t)(placed >> 32); nacc -= 32; p0 = p1;
             }
         }
         // Whole segments that are complete leave the ring, 16 bytes per lane: all of them, so that after every
@@ -190,7 +201,7 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
         // rounding and the 256 positions of the next row the ring never holds more than 1536 words.
 #pragma unroll 1
         for (int guard = 0; guard < (int)(kRing / kSeg); guard++) {
-            if (wpos < flushed + kSeg || __ballot(pend > 0 && p0 < flushed + kSeg) != 0) break;
+            if (wpos < flushed + kSeg || __ballot(k + (int32_t)nacc >= 32 && p0 < flushed + kSeg) != 0) break;
             const u32x4 w = *reinterpret_cast<const u32x4 *>(ring + ((flushed + 4 * lane) & (kRing - 1)));
             __builtin_amdgcn_raw_buffer_store_b128(w, es, (int)((flushed + 4 * lane) * 4), 0, 0);
             flushed += kSeg;
@@ -211,8 +222,9 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
     if (row < rows) encode_row(xa ^ ya, row);
     // the words still owed to the decoder (a partial word and look-ahead words) and the zero padding of the
     // last 16-byte unit go into the ring too; then everything left in it leaves in 16-byte pieces
-    if (pend > 0) { ring[p0 & (kRing - 1)] = (uint32_t)acc; acc >>= 32; p0 = p1; pend--; }
-    if (pend > 0) { ring[p0 & (kRing - 1)] = (uint32_t)acc; pend--; }
+    const uint32_t pend = ((uint32_t)k + nacc) >> 5;
+    if (pend > 0) ring[p0 & (kRing - 1)] = lo;
+    if (pend > 1) ring[p1 & (kRing - 1)] = 0;
     if (lane < ((4 - (wpos & 3)) & 3)) ring[(wpos + lane) & (kRing - 1)] = 0;
     const uint32_t end = (wpos + 3) & ~3u;                      // words of the stream with its padding
 #pragma unroll 1
