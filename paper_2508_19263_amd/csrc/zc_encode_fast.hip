@@ -31,10 +31,34 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t rsrc_of(const void *p, uint32_
 template <int B>
 __device__ __forceinline__ uint32_t byte_times4(uint32_t x, uint32_t two)
 {
+    static_assert(B >= 0 && B < 4, "byte of a word");
     uint32_t r;
     if (B == 0) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(r) : "v"(two), "v"(x));
-    else asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(two), "v"(x));
+    else if (B == 1) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(two), "v"(x));
+    else if (B == 2) asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(r) : "v"(two), "v"(x));
+    else asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(r) : "v"(two), "v"(x));
     return r;
+}
+// the same with the byte's number as a value that is constant once the caller's loop is unrolled
+__device__ __forceinline__ uint32_t byte_times4(uint32_t x, int b, uint32_t two)
+{
+    switch (b & 3) {
+    case 0: return byte_times4<0>(x, two);
+    case 1: return byte_times4<1>(x, two);
+    case 2: return byte_times4<2>(x, two);
+    default: return byte_times4<3>(x, two);
+    }
+}
+
+// Two entries of an encode table (bits 15..0 the code, first bit lowest; bits 20..16 its length) joined into
+// the code of both symbols and its length, with the halves of the entries as operands:
+// code = a.lo | b.lo << a.hi (a.hi <= 16), len = a.hi + b.hi.
+__device__ __forceinline__ void join_codes(uint32_t a, uint32_t b, uint32_t &code, uint32_t &len)
+{
+    uint32_t sh;
+    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1 src1_sel:WORD_0" : "=v"(sh) : "v"(a), "v"(b));
+    asm("v_or_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0" : "=v"(code) : "v"(sh), "v"(a));
+    asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1 src1_sel:WORD_1" : "=v"(len) : "v"(a), "v"(b));
 }
 
 // code and length of the four exponents of one source word: bits 15..0 of an entry are the
@@ -45,11 +69,7 @@ __device__ __forceinline__ void group_code(uint32_t w, const char *pair_lut, uin
     const uint32_t u = t | (t >> 4);                    // bytes 0 and 2: e0 | e1 << 4, e2 | e3 << 4
     const uint32_t a = *reinterpret_cast<const uint32_t *>(pair_lut + byte_times4<0>(u, two));
     const uint32_t b = *reinterpret_cast<const uint32_t *>(pair_lut + byte_times4<2>(u, two));
-    // halves of the entries as operands: code = a.lo | b.lo << a.hi, len = a.hi + b.hi (a.hi <= 16)
-    uint32_t sh;
-    asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1 src1_sel:WORD_0" : "=v"(sh) : "v"(a), "v"(b));
-    asm("v_or_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0" : "=v"(code) : "v"(sh), "v"(a));
-    asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1 src1_sel:WORD_1" : "=v"(len) : "v"(a), "v"(b));
+    join_codes(a, b, code, len);
 }
 
 }  // namespace
@@ -132,14 +152,14 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
     const uint32_t two = 2;
 
     // What a lane keeps of its stream.  The decoder it mirrors asks for a word whenever it holds k <= 32 unread
-    // bits; the word's position is fixed then, its content is complete later.  Requests minus writes is
-    // (k + nacc) / 32: never above 2 (a request needs k <= 32 and nacc < 32), and a write (nacc >= 32 while
-    // k >= 1) finds 2.  So one position is due (p0) and at most one more is waiting (p1): a request always sets
-    // p1, a write moves it to p0.  The first request of all (every lane, position = lane) is p0's start value.
+    // bits; the word's position is fixed then, its content is complete later.  Words asked for and not yet
+    // written number (k + nacc) / 32: never above 2 (a request needs k <= 32 and nacc < 32).  So one position is
+    // due (p0) and at most one more is waiting (p1): a request sets p1, and p0 too when nothing is owed (k == 0:
+    // at the start, and after a group that took exactly the 32 bits the decoder held); a write moves p1 to p0.
     uint32_t lo = 0;            // bits not yet written, next free bit = nacc (< 32 between groups)
     uint32_t nacc = 0;
     int32_t k = 0;              // unread bits the decoder would hold at this point
-    uint32_t p0 = lane, p1 = lane;
+    uint32_t p0 = 0, p1 = 0;
     uint32_t wpos = 0;          // words of the stream handed out so far
     uint32_t flushed = 0;       // words of the stream that have left the ring
     const uint32_t rows = E / 1024;
@@ -181,6 +201,7 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
             const bool req = k <= 32;
             const uint64_t bm = __ballot(req);
             const uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, wpos));
+            p0 = k == 0 ? pos : p0;
             p1 = req ? pos : p1;
             k += req ? 32 : 0;
             wpos += (uint32_t)__popcll(bm);
@@ -244,51 +265,65 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
 // and the source is fetched two rows ahead.  Sizes come from the generic size pass (it runs at the speed of its
 // reads already); this kernel only writes.
 
-// what an encoding lane keeps of one table-coded stream; the decoder it mirrors is in lock step with it
+// What an encoding lane keeps of one table-coded stream; the decoder it mirrors is in lock step with it.  That
+// decoder asks for a word whenever it holds k <= 32 unread bits; the word's position is fixed then, its content
+// is complete later.  Words asked for and not yet written number (k + nacc) / 32: never above 2 (a request
+// needs k <= 32 and nacc < 32).  So one position is due (p0) and at most one more is waiting (p1): a request
+// sets p1, and p0 too when nothing is owed (k == 0: at the start, and after a period that took exactly the 32
+// bits the decoder held); a write moves p1 to p0.
 struct LaneStream {
-    uint64_t acc;               // bits not yet written, next free bit = nacc (< 32 between periods)
+    uint32_t lo;                // bits not yet written, next free bit = nacc (< 32 between periods)
     uint32_t nacc;
     int32_t k;                  // unread bits the decoder would hold at this point
-    uint32_t pend, p0, p1;      // words the decoder has asked for and we still owe, and where they go
+    uint32_t p0, p1;            // where the word in progress goes, and the one after it
     uint32_t wpos;              // words of the stream handed out so far (the same in all lanes)
+    __device__ LaneStream() : lo(0), nacc(0), k(0), p0(0), p1(0), wpos(0) {}
 };
 
 // one refill step of the decoder, then the R codes of a period: bytes first .. first+R-1 of the 8 symbol bytes in w
 template <int R>
 __device__ __forceinline__ void code_period(LaneStream &L, const uint32_t w[2], int first, const char *lut, __amdgpu_buffer_rsrc_t out)
 {
+    static_assert(R == 2 || R == 4 || R == 8, "symbols are joined in pairs, then pairs of pairs");
     const bool req = L.k <= 32;
     const uint64_t bm = __ballot(req);
-    if (req) {
-        const uint32_t pos = L.wpos + __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, 0));
-        if (L.pend == 0) L.p0 = pos; else L.p1 = pos;
-        L.pend++;
-        L.k += 32;
-    }
+    const uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, L.wpos));
+    L.p0 = L.k == 0 ? pos : L.p0;
+    L.p1 = req ? pos : L.p1;
+    L.k += req ? 32 : 0;
     L.wpos += (uint32_t)__popcll(bm);
-    uint32_t code = 0, len = 0;
+    const uint32_t two = 2;
+    uint32_t code[R / 2], len[R / 2];
 #pragma unroll
-    for (int j = 0; j < R; j++) {
-        const int jj = first + j;
-        const uint32_t e = (w[jj / 4] >> (8 * (jj % 4))) & 0xFFu;
-        const uint32_t t = *reinterpret_cast<const uint32_t *>(lut + e * 4);
-        code |= (t & 0xFFFFu) << len;
-        len += t >> 16;
+    for (int j = 0; j < R / 2; j++) {
+        const int jj = first + 2 * j;
+        const uint32_t a = *reinterpret_cast<const uint32_t *>(lut + byte_times4(w[jj / 4], jj % 4, two));
+        const uint32_t b = *reinterpret_cast<const uint32_t *>(lut + byte_times4(w[(jj + 1) / 4], (jj + 1) % 4, two));
+        join_codes(a, b, code[j], len[j]);
     }
-    L.acc |= (uint64_t)code << L.nacc;
-    L.nacc += len;
-    L.k -= (int32_t)len;
+#pragma unroll
+    for (int n = R / 2; n > 1; n /= 2)
+#pragma unroll
+        for (int j = 0; j < n / 2; j++) {
+            code[j] = code[2 * j] | (code[2 * j + 1] << len[2 * j]);
+            len[j] = len[2 * j] + len[2 * j + 1];
+        }
+    const uint64_t placed = (uint64_t)code[0] << L.nacc;          // nothing is left above bit nacc
+    L.lo |= (uint32_t)placed;
+    L.nacc += len[0];
+    L.k -= (int32_t)len[0];
     if (L.nacc >= 32) {
-        __builtin_amdgcn_raw_buffer_store_b32((uint32_t)L.acc, out, (int)(L.p0 * 4), 0, 0);
-        L.acc >>= 32; L.nacc -= 32; L.p0 = L.p1; L.pend--;
+        __builtin_amdgcn_raw_buffer_store_b32(L.lo, out, (int)(L.p0 * 4), 0, 0);
+        L.lo = (uint32_t)(placed >> 32); L.nacc -= 32; L.p0 = L.p1;
     }
 }
 
-// the words still owed to the decoder (a partial word and look-ahead words), then zero padding of the last unit
+// the words still owed to the decoder (a partial word and a look-ahead word), then zero padding of the last unit
 __device__ __forceinline__ void close_stream(LaneStream &L, __amdgpu_buffer_rsrc_t out, uint32_t lane)
 {
-    if (L.pend > 0) { __builtin_amdgcn_raw_buffer_store_b32((uint32_t)L.acc, out, (int)(L.p0 * 4), 0, 0); L.acc >>= 32; L.p0 = L.p1; L.pend--; }
-    if (L.pend > 0) { __builtin_amdgcn_raw_buffer_store_b32((uint32_t)L.acc, out, (int)(L.p0 * 4), 0, 0); L.pend--; }
+    const uint32_t owed = ((uint32_t)L.k + L.nacc) >> 5;
+    if (owed > 0) __builtin_amdgcn_raw_buffer_store_b32(L.lo, out, (int)(L.p0 * 4), 0, 0);
+    if (owed > 1) __builtin_amdgcn_raw_buffer_store_b32(0u, out, (int)(L.p1 * 4), 0, 0);
     if (lane < ((4 - (L.wpos & 3)) & 3)) __builtin_amdgcn_raw_buffer_store_b32(0u, out, (int)((L.wpos + lane) * 4), 0, 0);
 }
 
@@ -317,7 +352,7 @@ __device__ __forceinline__ void encode_bf16_chunk(const TensorDev *dp, const Wor
     const __amdgpu_buffer_rsrc_t ms = rsrc_of(comp + payload + 16 * a1, (uint32_t)((b1 - a1) * 16));
     const char *lut0 = reinterpret_cast<const char *>(enc), *lut1 = reinterpret_cast<const char *>(enc + 256);
 
-    LaneStream E = {0, 0, 0, 0, 0, 0, 0}, M = E;
+    LaneStream E, M;
     const uint32_t rows = cb / 1024;
     auto fetch = [&](uint32_t row, u32x4 &x, u32x4 &y) {
         row = row < rows ? row : rows - 1;

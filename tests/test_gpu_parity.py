@@ -1056,3 +1056,66 @@ def test_planned_decode_replays_from_a_captured_graph():
                         assert torch.equal(got[:raws[i].numel()], raws[i]), (fmt, cb, replay, i)
                 assert torch.isfinite(junk[-1])
         b.set_chunk_ids(None)
+
+
+def test_encoders_refill_periods_of_exactly_one_word():
+    # A lane whose first refill periods each take exactly the 32 bits the decoder holds owes no word when it asks
+    # for the next one: the state the specialised encoders' position queue must tell from "one word owed".
+    # Built on purpose: symbols with the longest code (read from the oracle's table) fill the first periods of a
+    # few lanes, for two rows on end, for one row, and for one period only.
+    rng = np.random.default_rng(77)
+
+    def pack(fmt, ex, sm):
+        if fmt == zc.FMT_FP8_E4M3:
+            return torch.from_numpy((((sm & 8) << 4) | (ex << 3) | (sm & 7)).astype(np.uint8))
+        return torch.from_numpy((((sm >> 7) << 15) | (ex.astype(np.uint16) << 7) | (sm & 0x7F)).astype(np.uint16).view(np.uint8).copy())
+
+    def patch(ex, rare, S, per_lane, target):
+        per_row = per_lane * S
+        for lane, rows in ((5 % S, 2), (S - 1, 1)):
+            for r in range(rows):
+                at = r * per_row + lane * per_lane
+                ex[at:at + per_lane] = rare[rng.integers(0, len(rare), per_lane)]
+        at = (S // 2) * per_lane
+        ex[at:at + 32 // target] = rare[0]
+
+    # the tensor's own code: a length limit of 8 that binds, so everything rare has an 8-bit code and stays there
+    for fmt, S, cb, per_lane, limit, draw in ((zc.FMT_FP8_E4M3, 64, 8192, 16, (0, 0, 0), lambda n: np.minimum(rng.geometric(0.5, n) - 1, 14)),
+                                              (zc.FMT_FP8_E4M3, 8, 1024, 16, (0, 0, 0), lambda n: np.minimum(rng.geometric(0.5, n) - 1, 14)),
+                                              (zc.FMT_BF16, 64, 8192, 8, (8, 0, 0), lambda n: np.minimum(rng.geometric(0.5, n) - 1, 39) * 3 + 50),
+                                              (zc.FMT_BF16, 8, 1024, 8, (8, 0, 0), lambda n: np.minimum(rng.geometric(0.5, n) - 1, 39) * 3 + 50)):
+        n = 6 * (cb * 8 // zc.elem_bits(fmt)) + 37
+        A = 16 if fmt == zc.FMT_FP8_E4M3 else 256
+        ex, sm = draw(n), rng.integers(0, 256, n)
+        po = o.params(fmt, cb, limit, S, zc.POLICY_HUFF_ALL)
+        ln = np.asarray(o.compress(pack(fmt, ex, sm).numpy(), n, po)[64:64 + A])
+        rare = np.flatnonzero(ln == 8)
+        assert ln.max() == 8 and len(rare) >= 2, ln
+        patch(ex, rare, S, per_lane, 8)
+        src = pack(fmt, ex, sm)
+        ln = np.asarray(o.compress(src.numpy(), n, po)[64:64 + A])
+        assert (ln[rare] == 8).all(), ln                         # the case is what it is meant to be
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            check_case(fmt, n, cb, S, policy, L=limit, data=(src, None), tag="word-periods-own-code")
+
+    # BF16 with 16-bit codes (two make a word): a dictionary trained on few exponents gives every other one the
+    # longest code, whatever the tensor it is then used on holds
+    n_train = 1 << 18
+    train = pack(zc.FMT_BF16, np.minimum(rng.geometric(0.3, n_train) - 1, 20) + 100, rng.integers(0, 256, n_train))
+    for S, cb in ((64, 8192), (8, 1024)):
+        n = 6 * (cb // 2) + 37
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            p, po = zc.params(zc.FMT_BF16, cb, streams=S, policy=policy), o.params(zc.FMT_BF16, cb, streams=S, policy=policy)
+            code = zc.train_code(dev(train), n_train, p)
+            ln, md = o.train_code(train.numpy(), n_train, po)
+            assert list(code.code_len[0]) == ln[0].tolist() and ln[0].max() == 16
+            rare = np.flatnonzero(ln[0] == 16)
+            ex = np.minimum(rng.geometric(0.3, n) - 1, 20) + 100
+            patch(ex, rare, S, 8, 16)
+            src = pack(zc.FMT_BF16, ex, rng.integers(0, 256, n))
+            want = o.compress_with_code(src.numpy(), n, po, ln, md)
+            comp, info = zc.compress_with_code(dev(src), n, p, code)
+            assert np.array_equal(comp.cpu().numpy(), want), (S, policy)
+            out, _ = zc.decompress(comp, info)
+            torch.cuda.synchronize()
+            assert torch.equal(out.cpu()[:src.numel()], src)
