@@ -99,15 +99,22 @@ __device__ __forceinline__ uint4 join_run(uint64_t P0, uint64_t P1)
 {
     constexpr int FMT = Fmt<FMT_>::BASE;
     uint32_t w[4];
+    if (FMT == ZC_FMT_BF16) {
+        // two values per word: a byte permute pairs every exponent byte (high) with its sign+mantissa byte (low);
+        // then, in both halves at once, the exponent moves down one bit, the low 7 bits stay and the sign moves up 8
+        const uint32_t e[2] = {(uint32_t)P0, (uint32_t)(P0 >> 32)}, m[2] = {(uint32_t)P1, (uint32_t)(P1 >> 32)};
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const uint32_t a = __builtin_amdgcn_perm(e[i / 2], m[i / 2], (i & 1) ? 0x07030602u : 0x05010400u);
+            const uint32_t u = ((a >> 1) & 0x7F807F80u) | (a & ~0x7F807F80u);      // bit 15 of each half is still the exponent's top bit
+            w[i] = (u & 0x7FFF7FFFu) | ((a << 8) & ~0x7FFF7FFFu);
+        }
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
 #pragma unroll
     for (int i = 0; i < 4; i++) {
         uint32_t e = (uint32_t)(P0 >> (16 * i)) & 0xFFFFu, m = (uint32_t)(P1 >> (16 * i)) & 0xFFFFu;
-        if (FMT == ZC_FMT_BF16) {
-            uint32_t e0 = e & 0xFFu, e1 = e >> 8, m0 = m & 0xFFu, m1 = m >> 8;
-            uint32_t lo = ((m0 & 0x80u) << 8) | (e0 << 7) | (m0 & 0x7Fu);
-            uint32_t hi = ((m1 & 0x80u) << 8) | (e1 << 7) | (m1 & 0x7Fu);
-            w[i] = lo | (hi << 16);
-        } else if (FMT == ZC_FMT_FP8_E4M3) {
+        if (FMT == ZC_FMT_FP8_E4M3) {
             uint32_t eb = spread_nibbles_to_bytes(e), mb = spread_nibbles_to_bytes(m);
             w[i] = ((mb & 0x08080808u) << 4) | (eb << 3) | (mb & 0x07070707u);
         } else {
