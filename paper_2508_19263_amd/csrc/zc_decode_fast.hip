@@ -321,6 +321,7 @@ __device__ __forceinline__ uint32_t long_code(const FieldTab &T, const HuffStrea
 template <int SB, int G, int R, bool LONG>
 __device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uint64_t &P0, uint64_t &P1, uint32_t lane)
 {
+    static_assert(!LONG || R == 2, "codes beyond the lookup index come with a refill period of 2 only; the second look relies on it");
     constexpr int PER64 = 64 / SB;
     const uint32_t mask = T.mask;
     const char *lut = reinterpret_cast<const char *>(T.lut);
@@ -337,13 +338,16 @@ __device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uin
         }
         if (LONG) {
             // An empty entry stands for a code longer than the index; it shifts by nothing, so the entries after
-            // it are empty too and the last one tells.  Rare: the whole step is then done again with the search.
+            // it are empty too and the last one tells.  Then the long code is searched for, and only what it
+            // spoiled is done again: the lookup of the symbol after it.
             if (__any(e[R - 1] == 0)) {
                 x = x0;
 #pragma unroll
                 for (int j = 0; j < R; j++) {
-                    e[j] = *reinterpret_cast<const uint16_t *>(lut + ((x & mask) << 1));
-                    if (e[j] == 0) e[j] = long_code(T, H, x);
+                    if (e[j] == 0) {
+                        e[j] = long_code(T, H, x);
+                        if (j + 1 < R) e[j + 1] = *reinterpret_cast<const uint16_t *>(lut + (((x >> (e[j] & 31u)) & mask) << 1));
+                    }
                     x >>= (e[j] & 31u);
                 }
             }
@@ -394,6 +398,7 @@ template <int SB, int G, int R, bool LONG>
 __device__ __forceinline__ void huff_run_pair(HuffStream &A, const FieldTab &TA, HuffStream &B, const FieldTab &TB,
                                               uint64_t &PA0, uint64_t &PA1, uint64_t &PB0, uint64_t &PB1, uint32_t lane)
 {
+    static_assert(!LONG || R == 2, "codes beyond the lookup index come with a refill period of 2 only; the second look relies on it");
     constexpr int PER64 = 64 / SB;
     constexpr int kPer32 = 32 / SB;
     const uint32_t ma = TA.mask, mb = TB.mask;
@@ -413,13 +418,18 @@ __device__ __forceinline__ void huff_run_pair(HuffStream &A, const FieldTab &TA,
         if (LONG) {
             // as in huff_run_r: one test per step for both fields, the step done again with the search when it hits
             if (__any(ea[R - 1] == 0 || eb[R - 1] == 0)) {
+                // only what a long code spoiled is done again: the lookup of the symbol after it
                 xa = xa0; xb = xb0;
 #pragma unroll
                 for (int j = 0; j < R; j++) {
-                    ea[j] = *reinterpret_cast<const uint16_t *>(la + ((xa & ma) << 1));
-                    eb[j] = *reinterpret_cast<const uint16_t *>(lb + ((xb & mb) << 1));
-                    if (ea[j] == 0) ea[j] = long_code(TA, A, xa);
-                    if (eb[j] == 0) eb[j] = long_code(TB, B, xb);
+                    if (ea[j] == 0) {
+                        ea[j] = long_code(TA, A, xa);
+                        if (j + 1 < R) ea[j + 1] = *reinterpret_cast<const uint16_t *>(la + (((xa >> (ea[j] & 31u)) & ma) << 1));
+                    }
+                    if (eb[j] == 0) {
+                        eb[j] = long_code(TB, B, xb);
+                        if (j + 1 < R) eb[j + 1] = *reinterpret_cast<const uint16_t *>(lb + (((xb >> (eb[j] & 31u)) & mb) << 1));
+                    }
                     xa >>= (ea[j] & 31u); xb >>= (eb[j] & 31u);
                 }
             }
