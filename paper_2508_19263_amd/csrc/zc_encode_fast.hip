@@ -265,6 +265,32 @@ __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, cons
 // and the source is fetched two rows ahead.  Sizes come from the generic size pass (it runs at the speed of its
 // reads already); this kernel only writes.
 
+// The R codes of one refill period of a BF16 field joined into one code (at most 32 bits) and its length: bytes
+// first .. first+R-1 of the 8 symbol bytes in w, looked up in the field's 256-entry table, joined in pairs, then
+// pairs of pairs.
+template <int R>
+__device__ __forceinline__ void codes_of_period(const uint32_t w[2], int first, const char *lut, uint32_t &code_out, uint32_t &len_out)
+{
+    static_assert(R == 2 || R == 4 || R == 8, "symbols are joined in pairs, then pairs of pairs");
+    const uint32_t two = 2;
+    uint32_t code[R / 2], len[R / 2];
+#pragma unroll
+    for (int j = 0; j < R / 2; j++) {
+        const int jj = first + 2 * j;
+        const uint32_t a = *reinterpret_cast<const uint32_t *>(lut + byte_times4(w[jj / 4], jj % 4, two));
+        const uint32_t b = *reinterpret_cast<const uint32_t *>(lut + byte_times4(w[(jj + 1) / 4], (jj + 1) % 4, two));
+        join_codes(a, b, code[j], len[j]);
+    }
+#pragma unroll
+    for (int n = R / 2; n > 1; n /= 2)
+#pragma unroll
+        for (int j = 0; j < n / 2; j++) {
+            code[j] = code[2 * j] | (code[2 * j + 1] << len[2 * j]);
+            len[j] = len[2 * j] + len[2 * j + 1];
+        }
+    code_out = code[0]; len_out = len[0];
+}
+
 // What an encoding lane keeps of one table-coded stream; the decoder it mirrors is in lock step with it.  That
 // decoder asks for a word whenever it holds k <= 32 unread bits; the word's position is fixed then, its content
 // is complete later.  Words asked for and not yet written number (k + nacc) / 32: never above 2 (a request
@@ -284,7 +310,6 @@ struct LaneStream {
 template <int R>
 __device__ __forceinline__ void code_period(LaneStream &L, const uint32_t w[2], int first, const char *lut, __amdgpu_buffer_rsrc_t out)
 {
-    static_assert(R == 2 || R == 4 || R == 8, "symbols are joined in pairs, then pairs of pairs");
     const bool req = L.k <= 32;
     const uint64_t bm = __ballot(req);
     const uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, L.wpos));
@@ -292,26 +317,12 @@ __device__ __forceinline__ void code_period(LaneStream &L, const uint32_t w[2], 
     L.p1 = req ? pos : L.p1;
     L.k += req ? 32 : 0;
     L.wpos += (uint32_t)__popcll(bm);
-    const uint32_t two = 2;
-    uint32_t code[R / 2], len[R / 2];
-#pragma unroll
-    for (int j = 0; j < R / 2; j++) {
-        const int jj = first + 2 * j;
-        const uint32_t a = *reinterpret_cast<const uint32_t *>(lut + byte_times4(w[jj / 4], jj % 4, two));
-        const uint32_t b = *reinterpret_cast<const uint32_t *>(lut + byte_times4(w[(jj + 1) / 4], (jj + 1) % 4, two));
-        join_codes(a, b, code[j], len[j]);
-    }
-#pragma unroll
-    for (int n = R / 2; n > 1; n /= 2)
-#pragma unroll
-        for (int j = 0; j < n / 2; j++) {
-            code[j] = code[2 * j] | (code[2 * j + 1] << len[2 * j]);
-            len[j] = len[2 * j] + len[2 * j + 1];
-        }
-    const uint64_t placed = (uint64_t)code[0] << L.nacc;          // nothing is left above bit nacc
+    uint32_t code, len;
+    codes_of_period<R>(w, first, lut, code, len);
+    const uint64_t placed = (uint64_t)code << L.nacc;             // nothing is left above bit nacc
     L.lo |= (uint32_t)placed;
-    L.nacc += len[0];
-    L.k -= (int32_t)len[0];
+    L.nacc += len;
+    L.k -= (int32_t)len;
     if (L.nacc >= 32) {
         __builtin_amdgcn_raw_buffer_store_b32(L.lo, out, (int)(L.p0 * 4), 0, 0);
         L.lo = (uint32_t)(placed >> 32); L.nacc -= 32; L.p0 = L.p1;
@@ -514,17 +525,19 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
         }
         const uint32_t in_off = alive ? chunk * cb : kNowhere;
 
-        uint64_t acc = 0;           // bits not yet written, next free bit = nacc (< 32 between groups)
+        // the lane's stream: as in the 64-lane encoders, one position due (p0) and at most one more waiting (p1);
+        // words asked for and not yet written number (k + nacc) / 32
+        uint32_t lo = 0;            // bits not yet written, next free bit = nacc (< 32 between groups)
         uint32_t nacc = 0;
         int32_t k = 0;              // unread bits the decoder would hold at this point
-        uint32_t pend = 0, p0 = 0, p1 = 0;
+        uint32_t p0 = 0, p1 = 0;
         uint32_t wpos = 0, q = 0;
         uint32_t flushed = 0;       // words of the stream that have left the ring
         // whole segments that are complete leave the ring, 16 bytes per lane
         auto flush_segments = [&]() {
 #pragma unroll 1
             for (int guard = 0; guard < 8; guard++) {
-                const bool owes = pend > 0 && p0 < flushed + kSeg;
+                const bool owes = k + (int32_t)nacc >= 32 && p0 < flushed + kSeg;
                 const bool ready = wpos >= flushed + kSeg && (__ballot(owes) & gmask) == 0;
                 if (!__any(ready)) break;
                 if (ready) {
@@ -549,29 +562,38 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
                 for (int h = 0; h < 2; h++) ex[h] = __builtin_amdgcn_perm(v[2 * h + 1] >> 7, v[2 * h] >> 7, 0x06040200u);
             }
             if (WRITE) {
-                uint32_t m[2];
+                // m: the row's sign+mantissa symbols (FP8: nibble j at bits 4j; BF16: bytes), or, when the field has a
+                // flat code, w: every symbol most significant bit first.  FP8 gathers the nibbles of the even and of
+                // the odd bytes of two words with byte permutes; for the flat code it starts from the bit-reversed
+                // words, whose bytes hold s, m2, m1, m0 in this order already (bits 0, 5, 6, 7) and come reversed.
+                uint32_t m[2], w[2];
 #pragma unroll
                 for (int h = 0; h < 2; h++) {
                     if (BF) {
-                        const uint32_t lo = v[2 * h], hi = v[2 * h + 1];
-                        const uint32_t ml = ((lo >> 8) & 0x00800080u) | (lo & 0x007F007Fu), mh = ((hi >> 8) & 0x00800080u) | (hi & 0x007F007Fu);
+                        const uint32_t lo2 = v[2 * h], hi2 = v[2 * h + 1];
+                        const uint32_t ml = ((lo2 >> 8) & 0x00800080u) | (lo2 & 0x007F007Fu), mh = ((hi2 >> 8) & 0x00800080u) | (hi2 & 0x007F007Fu);
                         m[h] = __builtin_amdgcn_perm(mh, ml, 0x06040200u);
+                        w[h] = reverse_in_groups<8>(m[h]);
+                    } else if (sm_raw) {
+                        const uint32_t x0 = ((v[2 * h] >> 4) & 0x08080808u) | (v[2 * h] & 0x07070707u);
+                        const uint32_t x1 = ((v[2 * h + 1] >> 4) & 0x08080808u) | (v[2 * h + 1] & 0x07070707u);
+                        m[h] = __builtin_amdgcn_perm(x1, x0, 0x06040200u) | (__builtin_amdgcn_perm(x1, x0, 0x07050301u) << 4);
+                        w[h] = 0;
                     } else {
-                        const uint32_t lo = pack_nibbles_of_bytes(((v[2 * h] >> 4) & 0x08080808u) | (v[2 * h] & 0x07070707u));
-                        const uint32_t hi = pack_nibbles_of_bytes(((v[2 * h + 1] >> 4) & 0x08080808u) | (v[2 * h + 1] & 0x07070707u));
-                        m[h] = lo | (hi << 16);
+                        const uint32_t r0 = __brev(v[2 * h]), r1 = __brev(v[2 * h + 1]);
+                        const uint32_t x0 = ((r0 >> 4) & 0x0E0E0E0Eu) | (r0 & 0x01010101u);       // bytes: symbols 3, 2, 1, 0
+                        const uint32_t x1 = ((r1 >> 4) & 0x0E0E0E0Eu) | (r1 & 0x01010101u);       // bytes: symbols 7, 6, 5, 4
+                        w[h] = __builtin_amdgcn_perm(x1, x0, 0x05070103u) | (__builtin_amdgcn_perm(x1, x0, 0x04060002u) << 4);
+                        m[h] = 0;
                     }
                 }
                 if (sm_raw) {
-                    // the packed nibbles as they are: 8 bytes per lane
+                    // the packed symbols as they are: 8 bytes per lane
                     __builtin_amdgcn_raw_buffer_store_b64(u32x2{m[0], m[1]}, ps, (int)(alive ? m_off + (row * S + s) * 8 : kNowhere), 0, 0);
                 } else {
-                    // flat code: every symbol most significant bit first, one word per 8 symbols, rows of S words.
-                    // Two source rows make 4*S words of the stream: they are exchanged through LDS so that every
-                    // lane stores 16 contiguous bytes; an odd last row is stored word by word.
-                    uint32_t w[2];
-#pragma unroll
-                    for (int h = 0; h < 2; h++) w[h] = BF ? reverse_in_groups<8>(m[h]) : reverse_in_groups<4>(m[h]);
+                    // flat code: one word per 8 (BF16: 4) symbols, rows of S words.  Two source rows make 4*S words of
+                    // the stream: they are exchanged through LDS so that every lane stores 16 contiguous bytes; an
+                    // odd last row is stored word by word.
                     if ((row & 1) == 0 && row + 1 == rows) {
 #pragma unroll
                         for (int h = 0; h < 2; h++)
@@ -591,34 +613,25 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
                 const bool req = k <= 32;
                 if (WRITE) {
                     const uint64_t bm = __ballot(req) & gmask;
-                    const uint32_t pos = wpos + __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, 0));
-                    p0 = (req && pend == 0) ? pos : p0;
-                    p1 = (req && pend != 0) ? pos : p1;
-                    pend += req ? 1u : 0u;
+                    const uint32_t pos = __builtin_amdgcn_mbcnt_hi((uint32_t)(bm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bm, wpos));
+                    p0 = k == 0 ? pos : p0;              // nothing owed: the word asked for is the one due
+                    p1 = req ? pos : p1;
                     wpos += (uint32_t)__popcll(bm);
                 } else q += req ? 1u : 0u;
                 k += req ? 32 : 0;
                 uint32_t code = 0, len = 0;
-                if (BF) {
-#pragma unroll
-                    for (int j = 0; j < (BF ? BF : 1); j++) {
-                        const int jj = g * BF + j;
-                        const uint32_t e = (ex[(jj / 4) & 1] >> (8 * (jj % 4))) & 0xFFu;
-                        const uint32_t t = *reinterpret_cast<const uint32_t *>(pair_lut + e * 4);
-                        code |= (t & 0xFFFFu) << len;
-                        len += t >> 16;
-                    }
-                } else group_code(v[g & 3], pair_lut, two, code, len);
+                if (BF) codes_of_period<(BF ? BF : 2)>(ex, g * BF, pair_lut, code, len);
+                else group_code(v[g & 3], pair_lut, two, code, len);
                 k -= (int32_t)len;
                 if (WRITE) {
-                    acc |= (uint64_t)code << nacc;
+                    const uint64_t placed = (uint64_t)code << nacc;       // nothing is left above bit nacc
+                    lo |= (uint32_t)placed;
                     nacc += len;
                     const bool full = nacc >= 32;
-                    if (full) ring[p0 & (kRing - 1)] = (uint32_t)acc;
-                    acc = full ? acc >> 32 : acc;
-                    nacc = full ? nacc - 32 : nacc;
+                    if (full) ring[p0 & (kRing - 1)] = lo;
+                    lo = full ? (uint32_t)(placed >> 32) : lo;
+                    nacc &= 31u;                         // nacc < 64: minus 32 where a word was written
                     p0 = full ? p1 : p0;
-                    pend -= full ? 1u : 0u;
                 }
             }
             if (WRITE) flush_segments();
@@ -639,13 +652,9 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
         if (WRITE) {
             // the words still owed to the decoder (a partial word and look-ahead words) and the zero padding of
             // the last 16-byte unit go into the ring too; then everything left in it leaves in 16-byte pieces
-#pragma unroll
-            for (int t = 0; t < 2; t++) {
-                if (pend > 0) ring[p0 & (kRing - 1)] = (uint32_t)acc;
-                acc = pend > 0 ? acc >> 32 : acc;
-                p0 = pend > 0 ? p1 : p0;
-                pend -= pend > 0 ? 1u : 0u;
-            }
+            const uint32_t owed = ((uint32_t)k + nacc) >> 5;
+            if (owed > 0) ring[p0 & (kRing - 1)] = lo;
+            if (owed > 1) ring[p1 & (kRing - 1)] = 0;
             if (s < ((4 - (wpos & 3)) & 3)) ring[(wpos + s) & (kRing - 1)] = 0;
             const uint32_t end = alive ? (wpos + 3) & ~3u : 0u;  // words of the stream with its padding
 #pragma unroll 1
