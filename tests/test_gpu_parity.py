@@ -517,11 +517,23 @@ def test_damaged_payload_and_index_do_not_escape_the_buffers():
     # The decoders' own range checks must turn a damaged stream into wrong output, never into an
     # access outside the container or the destination: canaries around both stay intact.
     rng = np.random.default_rng(91)
-    cases = [(zc.FMT_FP8_E4M3, 8 * 65536, 65536, 64, None), (zc.FMT_FP8_E4M3, 64 * 2048, 2048, 8, None),
-             (zc.FMT_BF16, 6 * 8192, 16384, 64, None), (zc.FMT_FP8_E4M3, 9 * 4096 + 11, 4096, 16, None)]
-    for fmt, n, cb, S, _ in cases:
-        src, _sc = make_input(fmt, n, 17)
-        comp, info = zc.compress(dev(src), n, zc.params(fmt, cb, streams=S))
+    H, A = zc.POLICY_HUFF_ALL, zc.POLICY_AUTO
+    cases = [(zc.FMT_FP8_E4M3, 8 * 65536, 65536, 64, H, False), (zc.FMT_FP8_E4M3, 64 * 2048, 2048, 8, H, False),
+             (zc.FMT_BF16, 6 * 8192, 16384, 64, H, False), (zc.FMT_FP8_E4M3, 9 * 4096 + 11, 4096, 16, H, False),
+             # BF16 pages (the page decoder's BF16 kernel), a BF16 delta with both fields table decoded and long
+             # codes (the paired decode), an FP8 page delta
+             (zc.FMT_BF16, 24 * 2048, 4096, 8, A, False), (zc.FMT_BF16, 5 * 131072, 262144, 64, H, True),
+             (zc.FMT_FP8_E4M3, 64 * 2048, 2048, 8, A, True)]
+    for fmt, n, cb, S, policy, delta in cases:
+        if delta and fmt == zc.FMT_BF16:
+            w0, w1 = wl.bf16_checkpoint_pair(n, seed=23)
+            src, base = w1.view(torch.uint8).reshape(-1), w0.view(torch.uint8).reshape(-1)
+        else:
+            src, _sc = make_input(fmt, n, 17)
+            base = make_input(fmt, n, 18)[0] if delta else None
+        comp, info = zc.compress(dev(src), n, zc.params(fmt, cb, streams=S, policy=policy), xor_base=dev(base))
+        if fmt == zc.FMT_BF16 and delta:
+            assert info.mode[0] == zc.MODE_HUFF and info.mode[1] == zc.MODE_HUFF and info.max_len[1] > 11
         raw = src.numel() * src.element_size()
         pay = int(info.payload_offset)
         for what in ("payload", "index"):
@@ -536,8 +548,8 @@ def test_damaged_payload_and_index_do_not_escape_the_buffers():
                 lo = int(info.index_offset[0])
                 body[lo:pay] = torch.from_numpy(rng.integers(0, 256, pay - lo).astype(np.uint8)).to(DEV)
             out = torch.full((guard + raw + guard,), 0xC3, dtype=torch.uint8, device=DEV)
-            print("damaged", what, "fmt", fmt, "n", n, "chunk", cb, "S", S, flush=True)
-            zc.decompress(body, info, out=out[guard:guard + raw])
+            print("damaged", what, "fmt", fmt, "n", n, "chunk", cb, "S", S, "policy", policy, "delta", delta, flush=True)
+            zc.decompress(body, info, out=out[guard:guard + raw], xor_base=dev(base))
             torch.cuda.synchronize()
             assert bool((out[:guard] == 0xC3).all()) and bool((out[guard + raw:] == 0xC3).all())
             assert bool((buf[:guard] == 0x5A).all()) and bool((buf[guard + comp.numel():] == 0x5A).all())
