@@ -429,6 +429,59 @@ def test_config2_full_size_tensors_in_the_benchmark_launch_configuration():
             assert rc == o.OK and np.array_equal(chunk, gpu_out[c * 262144:(c + 1) * 262144]), (name, c)
 
 
+def test_configs_3_4_5_full_size_tensors_in_the_benchmark_launch_configuration():
+    # One tensor each of configurations 3, 4 (W1 alone and the delta) and 5 at its real size, generated on the
+    # GPU as bench.py does and compressed / decoded in a batch with the parameters bench.py times.  The
+    # oracle compresses the same bytes: identical containers; sampled chunks of the oracle's container,
+    # decoded one by one on the CPU, equal the GPU output; the K/V page list decodes to the sampled pages.
+    rng = np.random.default_rng(8)
+
+    def compare(tag, fmt, srcs, n, cb, S, limit, bases=None, scales=None, ids=None):
+        p, po = zc.params(fmt, cb, limit, S), o.params(fmt, cb, limit, S)
+        b = zc.Batch(srcs, [n] * len(srcs), p, xor_bases=bases, scales=scales)
+        sizes = b.compress()
+        b.plan_decompress()
+        outs = b.run_decompress()
+        torch.cuda.synchronize()
+        print("full-size", tag, n, flush=True)
+        host = srcs[0].view(torch.uint8).reshape(-1).cpu().numpy()
+        hb = None if bases is None else bases[0].view(torch.uint8).reshape(-1).cpu().numpy()
+        hs = None if scales is None else scales[0].cpu().numpy()
+        want = o.compress(host, n, po, xor_base=hb, scales=hs)
+        assert sizes[0] == len(want) and np.array_equal(b.container(0).cpu().numpy(), want), tag
+        for i, s_ in enumerate(srcs):
+            assert torch.equal(outs[i][:s_.numel() * s_.element_size()], s_.view(torch.uint8).reshape(-1)), (tag, i)
+        gpu_out = outs[0].cpu().numpy()
+        n_chunks = len(host) // cb
+        n_sc = 0 if scales is None else cb * 8 // zc.elem_bits(fmt) // zc.scale_block(fmt)
+        for c in sorted(set([0, n_chunks - 1] + rng.integers(0, n_chunks, 4).tolist())):
+            rc, chunk, sc = o.decompress_chunk(want, c, cb, xor_base_chunk=None if hb is None else hb[c * cb:(c + 1) * cb], n_scales=n_sc)
+            assert rc == o.OK and np.array_equal(chunk, gpu_out[c * cb:(c + 1) * cb]), (tag, c)
+            if n_sc:
+                assert np.array_equal(sc, b.scales_out[0].cpu().numpy()[c * n_sc:(c + 1) * n_sc]), (tag, c)
+        if ids is not None:
+            b.set_chunk_ids(ids)
+            b.plan_decompress()
+            outs = b.run_decompress()
+            torch.cuda.synchronize()
+            for i, s_ in enumerate(srcs):
+                assert torch.equal(outs[i].view(-1, cb), s_.view(torch.uint8).view(-1, cb)[ids[i].long()]), (tag, "pages", i)
+
+    m = [wl.mxfp4_weight(8192, 28672, device=DEV, seed=300 + i) for i in range(2)]
+    compare("c3", zc.FMT_FP4_E2M1_MX, [x[0] for x in m], 8192 * 28672, 262144, 64, (0, 0, 0), scales=[x[1] for x in m])
+    del m
+    pairs = [wl.bf16_checkpoint_pair(4096 * 16384, device=DEV, seed=400 + i) for i in range(2)]
+    w0, w1 = [q[0] for q in pairs], [q[1] for q in pairs]
+    compare("c4-w1", zc.FMT_BF16, w1, 4096 * 16384, 262144, 64, (16, 16, 0))
+    compare("c4-delta", zc.FMT_BF16, w1, 4096 * 16384, 262144, 64, (16, 16, 0), bases=w0)
+    del pairs, w0, w1
+    k, v = wl.fp8_kv_pair(device=DEV, seed=500)
+    kv = [k.reshape(-1), v.reshape(-1)]
+    n_pages = kv[0].numel() // 2048
+    ids = [wl.page_sample(n_pages, 0.25, device=DEV, seed=600 + i) for i in range(2)]
+    compare("c5", zc.FMT_FP8_E4M3, kv, kv[0].numel(), 2048, 8, (0, 0, 0), ids=ids)
+
+
 def test_full_chunk_kernel_all_formats_and_kinds():
     # the 64-lane full-chunk decoder: every format, table-decoded / flat / raw / constant fields,
     # one or two LDS rings, delta, chunks that are whole multiples of its row size
