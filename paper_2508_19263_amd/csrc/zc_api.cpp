@@ -86,13 +86,17 @@ uint64_t get64(const uint8_t *p) { uint64_t v; std::memcpy(&v, p, 8); return v; 
 
 // ---- workspace carving ------------------------------------------------------
 struct Workspace {
-    uint64_t descs, hist_work, scale_work, chunk_work, fast_work, whole_work, other_work, hist, enc, units, scan, blobs, total, host_end;
+    uint64_t descs, hist_work, scale_work, chunk_work, fast_work, whole_work, other_work, hist, enc, units, scan, blobs, lane_counts, total, host_end;
     uint32_t n_hist_work, n_scale_work, n_chunk_work;
     uint64_t n_units;
 };
 
 uint64_t align256(uint64_t x) { return (x + 255) / 256 * 256; }
 constexpr uint64_t kBlobBytes = 1024;     // header + code-length tables of one tensor (<= 64 + 3*256)
+
+// The geometry for which the histogram pass also counts exponents per chunk lane, so that the size pass need
+// not read the source again (k_hist_fp8_lanes, k_sizes_fp8_counts)
+bool lane_counts_shape(const Geometry &g) { return g.fmt == ZC_FMT_FP8_E4M3 && g.S == 64 && g.chunk_bytes == kHistBlockBytes; }
 
 zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T, Workspace *w)
 {
@@ -125,6 +129,9 @@ zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T,
     w->hist = off; off = align256(off + (uint64_t)T * 3 * 256 * 8);
     w->units = off; off = align256(off + units * 4);
     w->scan = off; off = align256(off + (uint64_t)T * sizeof(ScanOut));
+    // FP8 with 64 lanes and chunks of one histogram block: 16 exponent counts of 16 bits per chunk lane
+    w->lane_counts = off;
+    if (lane_counts_shape(g)) off = align256(off + units / 2 * (64 * 16 * 2));
     w->total = off;
     w->n_hist_work = (uint32_t)hw; w->n_scale_work = (uint32_t)sw; w->n_chunk_work = (uint32_t)cw; w->n_units = units;
     return ZC_OK;
@@ -464,7 +471,7 @@ public:
         if (T == 0) return ZC_OK;
         st = prepare();
         if (st) return st;
-        if (!dict && !stats_only && !train && device_codes_enabled()) return run_with_device_codes();
+        if (uses_device_codes()) return run_with_device_codes();
         return run_with_host_codes();
     }
 
@@ -489,6 +496,8 @@ private:
     std::vector<TensorDev> descs;
     std::vector<uint64_t> ncs;              // chunks per tensor
     std::vector<WorkItem> hist_work, scale_work;
+    std::vector<WorkItem> lane_hist_work;   // whole chunks whose histogram pass also counts per lane (lanes)
+    bool lanes = false;                     // the code is built on the device and the geometry is lane_counts_shape()
     bool bf16 = false;
     bool whole_shape = false;               // 64 lanes, chunks of whole 1 KiB rows: the generic encoder's whole-chunk build
     int whole_mode = 1;                     // 2: one whole chunk per work item, shared by its four wavefronts
@@ -505,6 +514,8 @@ private:
     uint64_t *d_hist() const { return (uint64_t *)(ws + w.hist); }
     uint32_t *d_enc() const { return (uint32_t *)(ws + w.enc); }
     uint32_t *d_units() const { return (uint32_t *)(ws + w.units); }
+    uint16_t *d_lane_counts() const { return (uint16_t *)(ws + w.lane_counts); }
+    bool uses_device_codes() const { return !dict && !stats_only && !train && device_codes_enabled(); }
     const WorkItem *d_list(uint64_t off) const { return (const WorkItem *)(ws + off); }
 
     // Geometry the specialised FP8 size/encode kernels take: 64 lanes and chunks of whole 1 KiB rows, or 4..32
@@ -536,6 +547,7 @@ private:
         if (st) return st;
         if (ws_bytes < w.total) return ZC_ERR_BUFFER_TOO_SMALL;
         cpi = chunks_per_work_item(g.S);
+        lanes = uses_device_codes() && lane_counts_shape(g);
         descs.resize(T);
         ncs.resize(T);
         uint64_t units_off = 0, all_chunks = 0;
@@ -559,7 +571,10 @@ private:
             d.units_off = (uint32_t)units_off;
             units_off += nc * g.nf;
             const uint64_t bytes = (x.n_elems * (uint64_t)elem_bits(g.fmt) + 7) / 8;
-            for (uint64_t b = 0; b * kHistBlockBytes < bytes; b++) hist_work.push_back({t, (uint32_t)b});
+            // a histogram block is a chunk here when lanes is set: whole chunks go to the kernel that counts per lane too
+            const uint64_t lane_blocks = lanes ? x.n_elems / g.elems_per_chunk : 0;
+            for (uint64_t b = 0; b < lane_blocks; b++) lane_hist_work.push_back({t, (uint32_t)b});
+            for (uint64_t b = lane_blocks; b * kHistBlockBytes < bytes; b++) hist_work.push_back({t, (uint32_t)b});
             if (g.nf == 3) for (uint64_t b = 0; b * kHistBlockBytes < x.n_elems / scale_block(g.fmt); b++) scale_work.push_back({t, (uint32_t)b});
         }
         bf16 = g.fmt == ZC_FMT_BF16;
@@ -580,6 +595,7 @@ private:
     {
         LAUNCH_TRY(launch_zero(d_hist(), (uint64_t)T * 3 * 256, stream));
         LAUNCH_TRY(launch_hist(g.fmt, d_descs(), d_list(w.hist_work), (uint32_t)hist_work.size(), 0, d_hist(), stream));
+        LAUNCH_TRY(launch_hist_fp8_lanes(d_descs(), d_list(w.hist_work) + hist_work.size(), (uint32_t)lane_hist_work.size(), d_hist(), d_lane_counts(), stream));
         if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs(), d_list(w.scale_work), (uint32_t)scale_work.size(), (int)scale_block(g.fmt), d_hist(), stream));
         return ZC_OK;
     }
@@ -587,7 +603,8 @@ private:
     // stream sizes (a5) and their exclusive scan into the chunk index (a6)
     zc_status queue_sizes_and_scan()
     {
-        if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs(), d_list(w.fast_work), (uint32_t)fast_work.size(), d_enc(), d_units(), stream));
+        if (g.S == 64 && lanes) LAUNCH_TRY(launch_sizes_fp8_counts(d_descs(), d_list(w.fast_work), (uint32_t)fast_work.size(), d_enc(), d_lane_counts(), d_units(), stream));
+        else if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs(), d_list(w.fast_work), (uint32_t)fast_work.size(), d_enc(), d_units(), stream));
         else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 0, bf16, d_descs(), d_list(w.fast_work), (uint32_t)fast_work.size(), d_enc(), d_units(), fast_step, stream));
         // generic kernels: the whole-chunk list leaves route 1 to the FP8 kernels (route 2 there is the BF16 encoder,
         // whose sizes come from this pass); the list of page-shaped tensors leaves both routes to the page kernels
@@ -671,15 +688,17 @@ private:
         order_for_xcds(whole_work);
         order_for_xcds(other_work);
         order_for_xcds(slow_work);
-        const Piece all[8] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
+        order_for_xcds(lane_hist_work);
+        const Piece all[9] = {{w.descs, descs.data(), T * sizeof(TensorDev)},
                               {w.hist_work, hist_work.data(), hist_work.size() * sizeof(WorkItem)},
+                              {w.hist_work + hist_work.size() * sizeof(WorkItem), lane_hist_work.data(), lane_hist_work.size() * sizeof(WorkItem)},
                               {w.scale_work, scale_work.data(), scale_work.size() * sizeof(WorkItem)},
                               {w.chunk_work, slow_work.data(), slow_work.size() * sizeof(WorkItem)},
                               {w.fast_work, fast_work.data(), fast_work.size() * sizeof(WorkItem)},
                               {w.whole_work, whole_work.data(), whole_work.size() * sizeof(WorkItem)},
                               {w.other_work, other_work.data(), other_work.size() * sizeof(WorkItem)},
                               {w.blobs, blobs.data(), blobs.size()}};
-        zc_status st = host_stage().upload(ws, w.descs, w.enc, all, 8, hs);
+        zc_status st = host_stage().upload(ws, w.descs, w.enc, all, 9, hs);
         if (st) return st;
         st = queue_histogram();
         if (st) return st;

@@ -132,6 +132,10 @@ __global__ __launch_bounds__(kCodeThreads) void k_codes(TensorDev *descs, const 
         for (int i = 0; i < k; i++) atomicAdd(&h[sym[i]], c);
     }
     __syncthreads();
+    // FP8: chunks counted by k_hist_fp8_lanes left their field histograms in the second slot (exponents at 0..15,
+    // sign+mantissa at 16..31); the byte histogram above then covers only what that kernel did not take
+    if (fmt == ZC_FMT_FP8_E4M3 && f < 2 && tid < 16) h[tid] += hist3[256 + 16 * f + tid];
+    __syncthreads();
 
     // ---- leaves in (frequency, symbol) order
     const unsigned long long hv = tid < A ? h[tid] : 0ull;

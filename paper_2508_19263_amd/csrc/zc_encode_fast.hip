@@ -120,6 +120,129 @@ __global__ __launch_bounds__(256) void k_sizes_fp8(const TensorDev *descs, const
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Histogram and stream sizes of FP8 chunks in two reads of the source instead of three.  With 64 lanes per chunk
+// a lane owns every 64th 16-byte run, and the number of words its stream takes follows from its bit total alone
+// (shown at k_sizes_fp8_counts).  So the histogram pass, which reads the chunk anyway, also counts the exponents
+// per lane (16 counts of 16 bits per lane, 2 KiB per chunk of 256 KiB), and once the code is known the size pass
+// reads those counts instead of the source.
+//
+// k_hist_fp8_lanes: one workgroup per whole chunk of kHistBlockBytes (= the chunk size; the host uses this
+// kernel for no other).  Thread t takes the runs t, t+256, ...: all of chunk lane t % 64.  Counters are private
+// per thread, [field][symbol][thread] in LDS, so that a wavefront's 64 additions fall into 32 banks twice and
+// never collide, whatever the data.  Both field histograms of the chunk are added to the tensor's second
+// histogram slot (exponents at 0..15, sign+mantissa at 16..31; the first slot keeps the byte histogram of what
+// k_hist counts, a short last chunk), the per-lane exponent counts go to lane_counts.
+__global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, const WorkItem *work, uint64_t *hist, uint16_t *lane_counts)
+{
+    static_assert(kHistBlockBytes / 64 < 65536, "a lane's count of one exponent fits 16 bits");
+    __shared__ uint32_t cnt[2 * 16 * 256];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev &d = descs[it.tensor];
+    const uint32_t tid = threadIdx.x;
+    const uint64_t start = (uint64_t)it.first * kHistBlockBytes;
+    if (d.chunk_bytes != kHistBlockBytes || start + kHistBlockBytes > d.n_elems) return;      // whole workgroup; the host never asks for this
+    for (uint32_t i = tid; i < 2 * 16 * 256; i += 256) cnt[i] = 0;
+    __syncthreads();
+    const uint8_t *p = d.src + start;
+    const uint8_t *base = d.base ? d.base + start : nullptr;
+    char *const mine = reinterpret_cast<char *>(cnt + tid);       // symbol s of field f at mine + (f * 16 + s) * 1024
+    auto count = [&](const uint4 &v) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            const uint32_t x = ((w[i] >> 4) & 0x08080808u) | (w[i] & 0x07070707u);       // sign+mantissa value of every byte
+            // (value of byte k) << 10: the counter's byte offset
+            const uint32_t e0 = (w[i] << 7) & 0x3C00u, e1 = (w[i] >> 1) & 0x3C00u, e2 = (w[i] >> 9) & 0x3C00u, e3 = (w[i] >> 17) & 0x3C00u;
+            const uint32_t m0 = (x << 10) & 0x3C00u, m1 = (x << 2) & 0x3C00u, m2 = (x >> 6) & 0x3C00u, m3 = (x >> 14) & 0x3C00u;
+            atomicAdd(reinterpret_cast<uint32_t *>(mine + e0), 1u); atomicAdd(reinterpret_cast<uint32_t *>(mine + 16384 + m0), 1u);
+            atomicAdd(reinterpret_cast<uint32_t *>(mine + e1), 1u); atomicAdd(reinterpret_cast<uint32_t *>(mine + 16384 + m1), 1u);
+            atomicAdd(reinterpret_cast<uint32_t *>(mine + e2), 1u); atomicAdd(reinterpret_cast<uint32_t *>(mine + 16384 + m2), 1u);
+            atomicAdd(reinterpret_cast<uint32_t *>(mine + e3), 1u); atomicAdd(reinterpret_cast<uint32_t *>(mine + 16384 + m3), 1u);
+        }
+    };
+    // four 16-byte loads per thread in flight at a time
+    constexpr uint32_t kStep = 256 * 16;
+    for (uint32_t off = tid * 16; off < kHistBlockBytes; off += 4 * kStep) {
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) v[k] = *reinterpret_cast<const uint4 *>(p + off + k * kStep);
+        if (base) {
+#pragma unroll
+            for (int k = 0; k < 4; k++) v[k] = xor4(v[k], *reinterpret_cast<const uint4 *>(base + off + k * kStep));
+        }
+#pragma unroll
+        for (int k = 0; k < 4; k++) count(v[k]);
+    }
+    __syncthreads();
+    // chunk lane l was fed by threads l, l+64, l+128, l+192; thread t writes the counts of exponents 4*(t/64) .. +3 of lane t%64
+    {
+        const uint32_t lane = tid & 63, s0 = (tid >> 6) * 4;
+        uint32_t c[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const uint32_t *row = cnt + (s0 + j) * 256 + lane;
+            c[j] = row[0] + row[64] + row[128] + row[192];
+        }
+        const uint64_t chunk_global = (uint64_t)(d.units_off / 2) + it.first;      // two fields: units_off counts two entries per chunk
+        uint2 packed = make_uint2(c[0] | (c[1] << 16), c[2] | (c[3] << 16));
+        *reinterpret_cast<uint2 *>(lane_counts + (chunk_global * 64 + lane) * 16 + s0) = packed;
+    }
+    // the chunk's two field histograms: row r (field r/16, symbol r%16) is summed by 8 threads, 32 entries each
+    {
+        const uint32_t row = tid >> 3, part = tid & 7;
+        uint32_t sum = 0;
+#pragma unroll 8
+        for (uint32_t i = 0; i < 32; i++) sum += cnt[row * 256 + part * 32 + ((i + tid) & 31)];
+        sum += __shfl_xor(sum, 1, 64); sum += __shfl_xor(sum, 2, 64); sum += __shfl_xor(sum, 4, 64);
+        if (part == 0 && sum) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + 1) * 256 + row]), (unsigned long long)sum);
+    }
+}
+
+// Stream sizes of full chunks from the per-lane exponent counts.  The decoder of a lane asks for a word at a
+// refill step (every 4 symbols) when it holds k <= 32 unread bits, one word per step at most.  With B(g) the bits
+// of the lane's symbols before step g, the words asked for up to and including step g are min(g + 1,
+// floor(B(g) / 32) + 2): by induction, since B grows by at most 32 per step (four codes of at most 8 bits).  The
+// lane's total is that expression at its last step, where B is its bit total minus its last four codes.
+__global__ __launch_bounds__(256) void k_sizes_fp8_counts(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables,
+                                                          const uint16_t *lane_counts, uint32_t *units)
+{
+    __shared__ uint32_t len16[16];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev *dp = descs + it.tensor;
+    if (!dp->route) return;                                      // whole workgroup: the code does not suit this kernel
+    if (threadIdx.x < 16) len16[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + threadIdx.x] >> 16;
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t chunk = uni32(it.first + (threadIdx.x >> 6));
+    const uint32_t E = uni32(dp->chunk_bytes);
+    const uint64_t n_elems = uni64(dp->n_elems);
+    if (E != kHistBlockBytes || chunk >= (uint32_t)(n_elems / E)) return;
+    const uint64_t chunk_global = (uint64_t)(uni32(dp->units_off) / 2) + chunk;
+    const uint4 *mine = reinterpret_cast<const uint4 *>(lane_counts + (chunk_global * 64 + lane) * 16);
+    const uint4 c0 = mine[0], c1 = mine[1];
+    const uint32_t c[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+    uint32_t bits = 0;
+#pragma unroll
+    for (int j = 0; j < 8; j++) bits += (c[j] & 0xFFFFu) * len16[2 * j] + (c[j] >> 16) * len16[2 * j + 1];
+    // the lane's last four symbols: the last word of its run in the chunk's last row
+    const uint64_t at = (uint64_t)chunk * E + (E - 1024) + lane * 16 + 12;
+    uint32_t w = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)) + at);
+    if (uni64((uint64_t)dp->base) != 0) w ^= *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) + at);
+    const uint32_t last = len16[(w >> 3) & 15] + len16[(w >> 11) & 15] + len16[(w >> 19) & 15] + len16[(w >> 27) & 15];
+    const uint32_t steps = E / 256;                              // 4 per row of 1 KiB
+    uint32_t q = ((bits - last) >> 5) + 2;
+    q = q < steps ? q : steps;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+    if (lane == 0) {
+        uint32_t *my = units + uni32(dp->units_off);
+        const uint32_t nc = uni32(dp->n_chunks);
+        my[chunk] = (q + 3) / 4;
+        my[nc + chunk] = E / 32;                            // 4 bits per element, 16-byte units (flat code and raw alike)
+    }
+}
+
 __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables)
 {
     constexpr uint32_t kSeg = 256, kRing = 2048;                // words: 16 bytes per lane; 32 words per lane
@@ -710,6 +833,21 @@ int launch_sizes_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t 
 {
     if (n_work == 0) return 0;
     hipLaunchKernelGGL(k_sizes_fp8, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_units);
+    return (int)hipGetLastError();
+}
+
+int launch_hist_fp8_lanes(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint16_t *d_lane_counts, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipLaunchKernelGGL(k_hist_fp8_lanes, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
+    return (int)hipGetLastError();
+}
+
+int launch_sizes_fp8_counts(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, const uint16_t *d_lane_counts,
+                            uint32_t *d_units, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipLaunchKernelGGL(k_sizes_fp8_counts, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
     return (int)hipGetLastError();
 }
 

@@ -129,6 +129,12 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split
                       const TensorDev *single, void *stream);
 // FP8, 64 lanes, full chunks, exponent codes <= 8 bits, sign+mantissa flat or raw (zc_encode_fast.hip)
 int launch_sizes_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream);
+// FP8, 64 lanes, chunks of kHistBlockBytes: the histogram pass that also counts exponents per chunk lane (one work
+// item per whole chunk; 16 u16 per lane, 2 KiB per chunk, at lane_counts[(units_off / 2 + chunk) * 1024]), and the
+// size pass that reads those counts instead of the source (same work list as launch_sizes_fp8)
+int launch_hist_fp8_lanes(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint16_t *d_lane_counts, void *stream);
+int launch_sizes_fp8_counts(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, const uint16_t *d_lane_counts,
+                            uint32_t *d_units, void *stream);
 int launch_encode_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
 // BF16, 64 lanes, full chunks, exponent field table coded, sign+mantissa flat or raw; work items as for the generic whole-chunk build
 int launch_encode_bf16(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);

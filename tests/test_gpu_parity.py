@@ -1184,3 +1184,42 @@ def test_encoders_refill_periods_of_exactly_one_word():
             out, _ = zc.decompress(comp, info)
             torch.cuda.synchronize()
             assert torch.equal(out.cpu()[:src.numel()], src)
+
+
+def test_fp8_chunks_of_one_histogram_block():
+    # FP8, 64 lanes, 256 KiB chunks: the histogram pass counts exponents per chunk lane and the size pass works
+    # from those counts.  Whole chunks next to a short last one, less than one chunk, a delta, a code the FP8
+    # kernels do not take (longest exponent code below 5 bits: the generic size pass must do those chunks), the
+    # longest code of 8 bits in whole-word groups, lanes of very different rates, and a batch that mixes them.
+    rng = np.random.default_rng(123)
+    cb = 262144
+    cases = []
+    n = 3 * cb + 70001
+    cases.append(("weights", wl.fp8_weight(n, seed=5), None))
+    cases.append(("delta", wl.fp8_weight(n, seed=6), wl.fp8_weight(n, seed=7)))
+    cases.append(("short-tensor", wl.fp8_weight(cb - 16, seed=8), None))
+    cases.append(("exactly-two", wl.fp8_weight(2 * cb, seed=9), None))
+    e = rng.choice(4, size=n, p=[0.6, 0.25, 0.1, 0.05]).astype(np.uint8) + 5
+    cases.append(("short-codes", torch.from_numpy(((e << 3) | rng.integers(0, 8, n).astype(np.uint8) | (rng.integers(0, 2, n).astype(np.uint8) << 7)).astype(np.uint8)), None))
+    ex = np.minimum(rng.geometric(0.5, n) - 1, 14)
+    j = np.arange(n)
+    ex = np.where(((j // 16) % 64 == 5) & (j < 2 * cb), 14, ex)          # lane 5 of the first two chunks: 8-bit codes only
+    ex = np.where(((j // 16) % 64 >= 32) & (j >= 2 * cb), 0, ex)          # half of the lanes of the third: 1-bit codes only
+    sm = rng.integers(0, 16, n)
+    cases.append(("long-codes", torch.from_numpy((((sm & 8) << 4) | (ex << 3) | (sm & 7)).astype(np.uint8)), None))
+    for tag, src, base in cases:
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            check_case(zc.FMT_FP8_E4M3, src.numel(), cb, 64, policy, data=(src, None), base=base, tag="one-block-" + tag)
+    # one batch of all tensors without a base
+    plain = [c for c in cases if c[2] is None]
+    p, po = zc.params(zc.FMT_FP8_E4M3, cb, streams=64), o.params(o.FP8_E4M3, cb, streams=64)
+    b = zc.Batch([dev(c[1]) for c in plain], [c[1].numel() for c in plain], p)
+    for rep in range(2):                                   # twice: the workspace is reused
+        sizes = b.compress()
+        for i, c in enumerate(plain):
+            want = o.compress(c[1].numpy(), c[1].numel(), po)
+            assert sizes[i] == len(want) and np.array_equal(b.container(i).cpu().numpy(), want), (c[0], rep)
+    outs = b.decompress()
+    torch.cuda.synchronize()
+    for i, c in enumerate(plain):
+        assert torch.equal(outs[i].cpu()[:c[1].numel()], c[1]), c[0]
