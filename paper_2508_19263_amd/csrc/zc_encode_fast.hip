@@ -127,38 +127,42 @@ __global__ __launch_bounds__(256) void k_sizes_fp8(const TensorDev *descs, const
 // per lane (16 counts of 16 bits per lane, 2 KiB per chunk of 256 KiB), and once the code is known the size pass
 // reads those counts instead of the source.
 //
-// k_hist_fp8_lanes: one workgroup per whole chunk of kHistBlockBytes (= the chunk size; the host uses this
-// kernel for no other).  Thread t takes the runs t, t+256, ...: all of chunk lane t % 64.  Counters are private
-// per thread, [field][symbol][thread] in LDS, so that a wavefront's 64 additions fall into 32 banks twice and
-// never collide, whatever the data.  Both field histograms of the chunk are added to the tensor's second
-// histogram slot (exponents at 0..15, sign+mantissa at 16..31; the first slot keeps the byte histogram of what
-// k_hist counts, a short last chunk), the per-lane exponent counts go to lane_counts.
+// k_hist_fp8_lanes: one workgroup per whole chunk of kHistBlockBytes (= the chunk size; the host uses this kernel
+// for no other).  Thread t takes the runs t, t+256, ...: all of chunk lane t % 64, which it shares with three
+// threads of the other wavefronts.  Every chunk lane has a histogram of all 256 byte values in LDS (16-bit
+// counters, two to a word, [value / 2][lane]: one atomic addition per byte; a wavefront's 64 additions fall into
+// 32 banks twice and never collide, whatever the data; a lane holds 4096 bytes, so nothing overflows).  At the
+// end the lanes' histograms are folded into exponent counts per lane, which go to lane_counts, and into the
+// chunk's two field histograms, which are added to the tensor's second histogram slot (exponents at 0..15,
+// sign+mantissa at 16..31; the first slot keeps the byte histogram of what k_hist counts, a short last chunk).
 __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, const WorkItem *work, uint64_t *hist, uint16_t *lane_counts)
 {
-    static_assert(kHistBlockBytes / 64 < 65536, "a lane's count of one exponent fits 16 bits");
-    __shared__ uint32_t cnt[2 * 16 * 256];
+    static_assert(kHistBlockBytes / 64 < 65536, "a lane's count of one byte value fits 16 bits");
+    __shared__ uint32_t cnt[128 * 64];                            // 32 KiB
+    __shared__ uint32_t lane_e[64 * 17];                          // exponent counts per lane, rows padded against bank conflicts
     const WorkItem it = work[blockIdx.x];
     const TensorDev &d = descs[it.tensor];
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, quarter = tid >> 6;
     const uint64_t start = (uint64_t)it.first * kHistBlockBytes;
     if (d.chunk_bytes != kHistBlockBytes || start + kHistBlockBytes > d.n_elems) return;      // whole workgroup; the host never asks for this
-    for (uint32_t i = tid; i < 2 * 16 * 256; i += 256) cnt[i] = 0;
+    for (uint32_t i = tid; i < 128 * 64; i += 256) cnt[i] = 0;
+    for (uint32_t i = tid; i < 64 * 17; i += 256) lane_e[i] = 0;
     __syncthreads();
     const uint8_t *p = d.src + start;
     const uint8_t *base = d.base ? d.base + start : nullptr;
-    char *const mine = reinterpret_cast<char *>(cnt + tid);       // symbol s of field f at mine + (f * 16 + s) * 1024
+    const uint32_t l4 = lane * 4, one = 1;
+    char *const lds = reinterpret_cast<char *>(cnt);
     auto count = [&](const uint4 &v) {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            const uint32_t x = ((w[i] >> 4) & 0x08080808u) | (w[i] & 0x07070707u);       // sign+mantissa value of every byte
-            // (value of byte k) << 10: the counter's byte offset
-            const uint32_t e0 = (w[i] << 7) & 0x3C00u, e1 = (w[i] >> 1) & 0x3C00u, e2 = (w[i] >> 9) & 0x3C00u, e3 = (w[i] >> 17) & 0x3C00u;
-            const uint32_t m0 = (x << 10) & 0x3C00u, m1 = (x << 2) & 0x3C00u, m2 = (x >> 6) & 0x3C00u, m3 = (x >> 14) & 0x3C00u;
-            atomicAdd(reinterpret_cast<uint32_t *>(mine + e0), 1u); atomicAdd(reinterpret_cast<uint32_t *>(mine + 16384 + m0), 1u);
-            atomicAdd(reinterpret_cast<uint32_t *>(mine + e1), 1u); atomicAdd(reinterpret_cast<uint32_t *>(mine + 16384 + m1), 1u);
-            atomicAdd(reinterpret_cast<uint32_t *>(mine + e2), 1u); atomicAdd(reinterpret_cast<uint32_t *>(mine + 16384 + m2), 1u);
-            atomicAdd(reinterpret_cast<uint32_t *>(mine + e3), 1u); atomicAdd(reinterpret_cast<uint32_t *>(mine + 16384 + m3), 1u);
+            // byte value b: word (b / 2) * 64 + lane, i.e. byte offset (b >> 1) << 8 | lane << 2; half b & 1
+            const uint32_t a0 = ((w[i] << 7) & 0x7F00u) | l4, a1 = ((w[i] >> 1) & 0x7F00u) | l4, a2 = ((w[i] >> 9) & 0x7F00u) | l4, a3 = ((w[i] >> 17) & 0x7F00u) | l4;
+            const uint32_t h0 = (w[i] << 4) & 16u, h1 = (w[i] >> 4) & 16u, h2 = (w[i] >> 12) & 16u, h3 = (w[i] >> 20) & 16u;
+            atomicAdd(reinterpret_cast<uint32_t *>(lds + a0), one << h0);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds + a1), one << h1);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds + a2), one << h2);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds + a3), one << h3);
         }
     };
     // four 16-byte loads per thread in flight at a time
@@ -175,27 +179,45 @@ __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, 
         for (int k = 0; k < 4; k++) count(v[k]);
     }
     __syncthreads();
-    // chunk lane l was fed by threads l, l+64, l+128, l+192; thread t writes the counts of exponents 4*(t/64) .. +3 of lane t%64
-    {
-        const uint32_t lane = tid & 63, s0 = (tid >> 6) * 4;
-        uint32_t c[4];
+    // Thread (lane, quarter) folds words 32*quarter .. +31 of its lane.  Word j holds the byte values 2j and 2j+1 =
+    // s eeee mmm with s = j >> 6, e = (j >> 2) & 15, m = 2 * (j & 3) and that plus one: a quarter is one sign,
+    // eight exponents and all eight mantissas.
+    uint32_t ce[8], cm[8];
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const uint32_t *row = cnt + (s0 + j) * 256 + lane;
-            c[j] = row[0] + row[64] + row[128] + row[192];
-        }
-        const uint64_t chunk_global = (uint64_t)(d.units_off / 2) + it.first;      // two fields: units_off counts two entries per chunk
-        uint2 packed = make_uint2(c[0] | (c[1] << 16), c[2] | (c[3] << 16));
-        *reinterpret_cast<uint2 *>(lane_counts + (chunk_global * 64 + lane) * 16 + s0) = packed;
+    for (int i = 0; i < 8; i++) { ce[i] = 0; cm[i] = 0; }
+#pragma unroll
+    for (int jj = 0; jj < 32; jj++) {
+        const uint32_t c = cnt[(quarter * 32 + jj) * 64 + lane];
+        const uint32_t lo = c & 0xFFFFu, hi = c >> 16;
+        ce[jj >> 2] += lo + hi;
+        cm[2 * (jj & 3)] += lo;
+        cm[2 * (jj & 3) + 1] += hi;
     }
-    // the chunk's two field histograms: row r (field r/16, symbol r%16) is summed by 8 threads, 32 entries each
+    const uint32_t e0 = (quarter & 1) * 8, s = quarter >> 1;      // the quarter's first exponent and its sign
+#pragma unroll
+    for (int i = 0; i < 8; i++) atomicAdd(&lane_e[lane * 17 + e0 + i], ce[i]);     // two quarters (the two signs) per counter
+    // the chunk's field histograms: every lane of this wavefront holds partial counts of the same 16 symbols
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) { ce[i] += __shfl_xor(ce[i], o, 64); cm[i] += __shfl_xor(cm[i], o, 64); }
+    }
+    if (lane == 0) {
+        unsigned long long *slot = reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + 1) * 256]);
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            if (ce[i]) atomicAdd(slot + e0 + i, (unsigned long long)ce[i]);
+            if (cm[i]) atomicAdd(slot + 16 + s * 8 + i, (unsigned long long)cm[i]);
+        }
+    }
+    __syncthreads();
+    // thread t writes the counts of exponents 4*(t/64) .. +3 of lane t%64
     {
-        const uint32_t row = tid >> 3, part = tid & 7;
-        uint32_t sum = 0;
-#pragma unroll 8
-        for (uint32_t i = 0; i < 32; i++) sum += cnt[row * 256 + part * 32 + ((i + tid) & 31)];
-        sum += __shfl_xor(sum, 1, 64); sum += __shfl_xor(sum, 2, 64); sum += __shfl_xor(sum, 4, 64);
-        if (part == 0 && sum) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + 1) * 256 + row]), (unsigned long long)sum);
+        const uint32_t s0 = quarter * 4;
+        const uint32_t *row = lane_e + lane * 17 + s0;
+        const uint64_t chunk_global = (uint64_t)(d.units_off / 2) + it.first;      // two fields: units_off counts two entries per chunk
+        const uint2 packed = make_uint2(row[0] | (row[1] << 16), row[2] | (row[3] << 16));
+        *reinterpret_cast<uint2 *>(lane_counts + (chunk_global * 64 + lane) * 16 + s0) = packed;
     }
 }
 
