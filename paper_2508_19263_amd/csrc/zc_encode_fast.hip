@@ -130,39 +130,37 @@ __global__ __launch_bounds__(256) void k_sizes_fp8(const TensorDev *descs, const
 // k_hist_fp8_lanes: one workgroup per whole chunk of kHistBlockBytes (= the chunk size; the host uses this kernel
 // for no other).  Thread t takes the runs t, t+256, ...: all of chunk lane t % 64, which it shares with three
 // threads of the other wavefronts.  Every chunk lane has a histogram of all 256 byte values in LDS (16-bit
-// counters, two to a word, [value / 2][lane]: one atomic addition per byte; a wavefront's 64 additions fall into
-// 32 banks twice and never collide, whatever the data; a lane holds 4096 bytes, so nothing overflows).  At the
-// end the lanes' histograms are folded into exponent counts per lane, which go to lane_counts, and into the
-// chunk's two field histograms, which are added to the tensor's second histogram slot (exponents at 0..15,
+// counters, lanes l and l + 32 in the two halves of word [value][l % 32]: one atomic addition of a constant per
+// byte; each half of a wavefront falls into 32 different banks, so nothing collides, whatever the data; a lane
+// holds 4096 bytes, so nothing overflows).  At the end the lanes' histograms are folded into exponent counts
+// per lane, which go to lane_counts, and into the chunk's two field histograms, which are added to the tensor's second histogram slot (exponents at 0..15,
 // sign+mantissa at 16..31; the first slot keeps the byte histogram of what k_hist counts, a short last chunk).
 __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, const WorkItem *work, uint64_t *hist, uint16_t *lane_counts)
 {
     static_assert(kHistBlockBytes / 64 < 65536, "a lane's count of one byte value fits 16 bits");
-    __shared__ uint32_t cnt[128 * 64];                            // 32 KiB
+    __shared__ uint32_t cnt[256 * 32];                            // 32 KiB
     __shared__ uint32_t lane_e[64 * 17];                          // exponent counts per lane, rows padded against bank conflicts
     const WorkItem it = work[blockIdx.x];
     const TensorDev &d = descs[it.tensor];
     const uint32_t tid = threadIdx.x, lane = tid & 63, quarter = tid >> 6;
     const uint64_t start = (uint64_t)it.first * kHistBlockBytes;
     if (d.chunk_bytes != kHistBlockBytes || start + kHistBlockBytes > d.n_elems) return;      // whole workgroup; the host never asks for this
-    for (uint32_t i = tid; i < 128 * 64; i += 256) cnt[i] = 0;
+    for (uint32_t i = tid; i < 256 * 32; i += 256) cnt[i] = 0;
     for (uint32_t i = tid; i < 64 * 17; i += 256) lane_e[i] = 0;
     __syncthreads();
     const uint8_t *p = d.src + start;
     const uint8_t *base = d.base ? d.base + start : nullptr;
-    const uint32_t l4 = lane * 4, one = 1;
+    // byte value b of lane l: word b * 32 + l % 32, half l / 32 (the same for everything a thread counts)
+    const uint32_t l4 = (lane & 31) * 4, inc = lane < 32 ? 1u : 0x10000u;
     char *const lds = reinterpret_cast<char *>(cnt);
     auto count = [&](const uint4 &v) {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            // byte value b: word (b / 2) * 64 + lane, i.e. byte offset (b >> 1) << 8 | lane << 2; half b & 1
-            const uint32_t a0 = ((w[i] << 7) & 0x7F00u) | l4, a1 = ((w[i] >> 1) & 0x7F00u) | l4, a2 = ((w[i] >> 9) & 0x7F00u) | l4, a3 = ((w[i] >> 17) & 0x7F00u) | l4;
-            const uint32_t h0 = (w[i] << 4) & 16u, h1 = (w[i] >> 4) & 16u, h2 = (w[i] >> 12) & 16u, h3 = (w[i] >> 20) & 16u;
-            atomicAdd(reinterpret_cast<uint32_t *>(lds + a0), one << h0);
-            atomicAdd(reinterpret_cast<uint32_t *>(lds + a1), one << h1);
-            atomicAdd(reinterpret_cast<uint32_t *>(lds + a2), one << h2);
-            atomicAdd(reinterpret_cast<uint32_t *>(lds + a3), one << h3);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds + (((w[i] << 7) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds + (((w[i] >> 1) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds + (((w[i] >> 9) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds + (((w[i] >> 17) & 0x7F80u) | l4)), inc);
         }
     };
     // four 16-byte loads per thread in flight at a time
@@ -179,19 +177,17 @@ __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, 
         for (int k = 0; k < 4; k++) count(v[k]);
     }
     __syncthreads();
-    // Thread (lane, quarter) folds words 32*quarter .. +31 of its lane.  Word j holds the byte values 2j and 2j+1 =
-    // s eeee mmm with s = j >> 6, e = (j >> 2) & 15, m = 2 * (j & 3) and that plus one: a quarter is one sign,
-    // eight exponents and all eight mantissas.
+    // Thread (lane, quarter) folds the byte values 64*quarter .. +63 of its lane: value = s eeee mmm, so a quarter
+    // is one sign, eight exponents and all eight mantissas.
     uint32_t ce[8], cm[8];
 #pragma unroll
     for (int i = 0; i < 8; i++) { ce[i] = 0; cm[i] = 0; }
+    const uint32_t half_shift = lane < 32 ? 0u : 16u;
 #pragma unroll
-    for (int jj = 0; jj < 32; jj++) {
-        const uint32_t c = cnt[(quarter * 32 + jj) * 64 + lane];
-        const uint32_t lo = c & 0xFFFFu, hi = c >> 16;
-        ce[jj >> 2] += lo + hi;
-        cm[2 * (jj & 3)] += lo;
-        cm[2 * (jj & 3) + 1] += hi;
+    for (int v = 0; v < 64; v++) {
+        const uint32_t c = (cnt[(quarter * 64 + v) * 32 + (lane & 31)] >> half_shift) & 0xFFFFu;
+        ce[v >> 3] += c;
+        cm[v & 7] += c;
     }
     const uint32_t e0 = (quarter & 1) * 8, s = quarter >> 1;      // the quarter's first exponent and its sign
 #pragma unroll
