@@ -163,18 +163,19 @@ __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, 
             atomicAdd(reinterpret_cast<uint32_t *>(lds + (((w[i] >> 17) & 0x7F80u) | l4)), inc);
         }
     };
-    // four 16-byte loads per thread in flight at a time
-    constexpr uint32_t kStep = 256 * 16;
-    for (uint32_t off = tid * 16; off < kHistBlockBytes; off += 4 * kStep) {
-        uint4 v[4];
+    // eight 16-byte loads per thread in flight at a time
+    constexpr uint32_t kStep = 256 * 16, kDepth = 8;
+    static_assert(kHistBlockBytes % (kStep * kDepth) == 0, "whole rounds");
+    for (uint32_t off = tid * 16; off < kHistBlockBytes; off += kDepth * kStep) {
+        uint4 v[kDepth];
 #pragma unroll
-        for (int k = 0; k < 4; k++) v[k] = *reinterpret_cast<const uint4 *>(p + off + k * kStep);
+        for (uint32_t k = 0; k < kDepth; k++) v[k] = *reinterpret_cast<const uint4 *>(p + off + k * kStep);
         if (base) {
 #pragma unroll
-            for (int k = 0; k < 4; k++) v[k] = xor4(v[k], *reinterpret_cast<const uint4 *>(base + off + k * kStep));
+            for (uint32_t k = 0; k < kDepth; k++) v[k] = xor4(v[k], *reinterpret_cast<const uint4 *>(base + off + k * kStep));
         }
 #pragma unroll
-        for (int k = 0; k < 4; k++) count(v[k]);
+        for (uint32_t k = 0; k < kDepth; k++) count(v[k]);
     }
     __syncthreads();
     // Thread (lane, quarter) folds the byte values 64*quarter .. +63 of its lane: value = s eeee mmm, so a quarter
