@@ -133,8 +133,9 @@ __global__ __launch_bounds__(256) void k_sizes_fp8(const TensorDev *descs, const
 // counters, lanes l and l + 32 in the two halves of word [value][l % 32]: one atomic addition of a constant per
 // byte; each half of a wavefront falls into 32 different banks, so nothing collides, whatever the data; a lane
 // holds 4096 bytes, so nothing overflows).  At the end the lanes' histograms are folded into exponent counts
-// per lane, which go to lane_counts, and into the chunk's two field histograms, which are added to the tensor's second histogram slot (exponents at 0..15,
-// sign+mantissa at 16..31; the first slot keeps the byte histogram of what k_hist counts, a short last chunk).
+// per lane, which go to lane_counts, and into the chunk's two field histograms, which are added to the tensor's
+// second histogram slot (exponents at 0..15, sign+mantissa at 16..31; the first slot keeps the byte histogram
+// of what k_hist counts, a short last chunk).
 __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, const WorkItem *work, uint64_t *hist, uint16_t *lane_counts)
 {
     static_assert(kHistBlockBytes / 64 < 65536, "a lane's count of one byte value fits 16 bits");
