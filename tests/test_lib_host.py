@@ -65,6 +65,16 @@ def test_bounds_and_workspace():
             assert zc.compress_bound(n, p) >= 64
             assert zc.workspace_bytes([n], p) > 0
             assert zc.compress_bound(n, p) > 0 and o.compress_bound(n, po) > 0
+    # the workspace grows with the tensors, and FP8 with 64 lanes and 256 KiB chunks reserves 2 KiB per chunk on top
+    # (the exponent counts per chunk lane that its size pass works from)
+    for fmt, cb in ((zc.FMT_BF16, 65536), (zc.FMT_FP8_E4M3, 262144), (zc.FMT_FP8_E4M3, 131072)):
+        sizes = [zc.workspace_bytes([n], zc.params(fmt, cb)) for n in (1 << 20, 1 << 24, 1 << 26)]
+        assert sizes[0] < sizes[1] < sizes[2]
+        assert zc.workspace_bytes([1 << 24, 1 << 24], zc.params(fmt, cb)) > sizes[1]
+    n = 1 << 28
+    with_counts = zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E4M3, 262144))
+    without = zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E5M2, 262144))           # same element size, fields and work lists
+    assert with_counts - without == (n // 262144) * 2048
     assert zc.compress_bound(100, zc.params(zc.FMT_FP8_E4M3, 100)) == 0       # chunk not a multiple of 16
     assert zc.compress_bound(100, zc.params(9, 4096)) == 0
     assert zc.compress_bound(33, zc.params(zc.FMT_FP4_E2M1_MX, 256)) == 0     # FP4 needs whole 32-blocks
