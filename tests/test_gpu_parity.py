@@ -1219,6 +1219,13 @@ def test_fp8_chunks_of_one_histogram_block():
         for i, c in enumerate(plain):
             want = o.compress(c[1].numpy(), c[1].numel(), po)
             assert sizes[i] == len(want) and np.array_equal(b.container(i).cpu().numpy(), want), (c[0], rep)
+    # and queued without a wait: the sizes are read from the headers afterwards
+    b.arena.fill_(0x77)
+    b.compress_async()
+    sizes = b.refresh_info()
+    for i, c in enumerate(plain):
+        want = o.compress(c[1].numpy(), c[1].numel(), po)
+        assert sizes[i] == len(want) and np.array_equal(b.container(i).cpu().numpy(), want), (c[0], "async")
     outs = b.decompress()
     torch.cuda.synchronize()
     for i, c in enumerate(plain):
