@@ -809,6 +809,23 @@ def test_random_parameter_sweep():
         check_case(fmt, n, cb, S, policy, L, data=(src, sc), base=base, tag="sweep-%d" % case)
 
 
+def test_random_sweep_fp8_chunks_of_one_histogram_block():
+    # the same kind of sweep over the one shape whose size pass works from per-lane counts: FP8, 64 lanes, 256 KiB
+    rng = np.random.default_rng(20251127)
+    cb = 262144
+    for case in range(24):
+        n = int(rng.integers(0, 5 * cb + 2)) if rng.integers(0, 3) else int(rng.integers(1, 5)) * cb
+        policy = int(rng.integers(0, 2))
+        L = (int(rng.integers(4, 17)) if rng.integers(0, 2) else 0, int(rng.integers(4, 17)) if rng.integers(0, 2) else 0, 0)
+        src, _ = _random_source(rng, zc.FMT_FP8_E4M3, n)
+        base = None
+        if rng.integers(0, 3) == 0 and n:
+            base = torch.from_numpy(rng.integers(0, 256, src.numel(), dtype=np.uint8) & np.uint8(rng.choice([0x01, 0x81, 0xFF])))
+        if src.numel() == 0:
+            src = torch.zeros(0, dtype=torch.uint8)
+        check_case(zc.FMT_FP8_E4M3, n, cb, 64, policy, L, data=(src, None), base=base, tag="sweep-one-block-%d" % case)
+
+
 def test_bf16_two_coded_fields_whole_chunks():
     # BF16 with both fields table decoded on 64-lane whole chunks (the shape of a checkpoint delta), at every
     # refill period the two fields can share: limits 16 (period 2, codes beyond the lookup index), 11
