@@ -140,14 +140,12 @@ __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, 
 {
     static_assert(kHistBlockBytes / 64 < 65536, "a lane's count of one byte value fits 16 bits");
     __shared__ uint32_t cnt[256 * 32];                            // 32 KiB
-    __shared__ uint32_t lane_e[64 * 17];                          // exponent counts per lane, rows padded against bank conflicts
     const WorkItem it = work[blockIdx.x];
     const TensorDev &d = descs[it.tensor];
     const uint32_t tid = threadIdx.x, lane = tid & 63, quarter = tid >> 6;
     const uint64_t start = (uint64_t)it.first * kHistBlockBytes;
     if (d.chunk_bytes != kHistBlockBytes || start + kHistBlockBytes > d.n_elems) return;      // whole workgroup; the host never asks for this
     for (uint32_t i = tid; i < 256 * 32; i += 256) cnt[i] = 0;
-    for (uint32_t i = tid; i < 64 * 17; i += 256) lane_e[i] = 0;
     __syncthreads();
     const uint8_t *p = d.src + start;
     const uint8_t *base = d.base ? d.base + start : nullptr;
@@ -192,8 +190,11 @@ __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, 
         cm[v & 7] += c;
     }
     const uint32_t e0 = (quarter & 1) * 8, s = quarter >> 1;      // the quarter's first exponent and its sign
+    __syncthreads();                                             // every thread has read its part of cnt: the array is free
+    // the exponent counts of (lane, quarter), in rows of 9 words against bank conflicts
+    uint32_t *const part = cnt;
 #pragma unroll
-    for (int i = 0; i < 8; i++) atomicAdd(&lane_e[lane * 17 + e0 + i], ce[i]);     // two quarters (the two signs) per counter
+    for (int i = 0; i < 8; i++) part[(quarter * 64 + lane) * 9 + i] = ce[i];
     // the chunk's field histograms: every lane of this wavefront holds partial counts of the same 16 symbols
 #pragma unroll
     for (int i = 0; i < 8; i++) {
@@ -209,12 +210,14 @@ __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, 
         }
     }
     __syncthreads();
-    // thread t writes the counts of exponents 4*(t/64) .. +3 of lane t%64
+    // thread t writes the counts of exponents 4*(t/64) .. +3 of lane t%64: those came from the quarters with the
+    // same exponent half (quarter & 1 == t/128), one per sign
     {
-        const uint32_t s0 = quarter * 4;
-        const uint32_t *row = lane_e + lane * 17 + s0;
+        const uint32_t s0 = quarter * 4, half = quarter >> 1, i0 = s0 & 7;
+        const uint32_t *pa = part + ((half + 0) * 64 + lane) * 9 + i0, *pb = part + ((half + 2) * 64 + lane) * 9 + i0;
+        const uint32_t c0 = pa[0] + pb[0], c1 = pa[1] + pb[1], c2 = pa[2] + pb[2], c3 = pa[3] + pb[3];
         const uint64_t chunk_global = (uint64_t)(d.units_off / 2) + it.first;      // two fields: units_off counts two entries per chunk
-        const uint2 packed = make_uint2(row[0] | (row[1] << 16), row[2] | (row[3] << 16));
+        const uint2 packed = make_uint2(c0 | (c1 << 16), c2 | (c3 << 16));
         *reinterpret_cast<uint2 *>(lane_counts + (chunk_global * 64 + lane) * 16 + s0) = packed;
     }
 }
