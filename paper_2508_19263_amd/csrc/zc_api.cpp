@@ -611,7 +611,7 @@ private:
         LAUNCH_TRY(launch_sizes(g.fmt, whole_mode, 0x2, d_descs(), d_list(w.whole_work), (uint32_t)whole_work.size(), d_enc(), d_units(), stream));
         LAUNCH_TRY(launch_sizes(g.fmt, 0, 0x6, d_descs(), d_list(w.other_work), (uint32_t)other_work.size(), d_enc(), d_units(), stream));
         LAUNCH_TRY(launch_sizes(g.fmt, 0, 0, d_descs(), d_list(w.chunk_work), (uint32_t)slow_work.size(), d_enc(), d_units(), stream));
-        LAUNCH_TRY(launch_scan(d_descs(), T, (int)g.nf, d_units(), (ScanOut *)(ws + w.scan), stream));
+        LAUNCH_TRY(launch_scan(d_descs(), T, (int)g.nf, d_units(), (ScanOut *)(ws + w.scan), stats_only ? nullptr : ws + w.blobs, (uint32_t)kBlobBytes, stream));
         return ZC_OK;
     }
 
@@ -706,7 +706,6 @@ private:
         cp.fmt = g.fmt; cp.policy = params->policy; cp.nf = g.nf; cp.blob_bytes = (uint32_t)kBlobBytes; cp.run_len = (uint32_t)run_len(g.fmt, 0);
         for (int f = 0; f < kMaxFields; f++) cp.limit[f] = f < (int)g.nf ? g.limit[f] : 0;
         LAUNCH_TRY(launch_codes(d_descs(), T, d_hist(), cp, ws + w.blobs, d_enc(), stream));
-        LAUNCH_TRY(launch_write_headers(d_descs(), T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
         st = queue_sizes_and_scan();
         if (st) return st;
         if (no_sync) return queue_encoders_without_sizes();
@@ -836,7 +835,6 @@ private:
                               {w.enc, enc.data(), enc.size() * 4}};
         st = host_stage().upload(ws, w.descs, w.host_end, all, 8, hs);
         if (st) return st;
-        if (!stats_only) LAUNCH_TRY(launch_write_headers(d_descs(), T, ws + w.blobs, (uint32_t)kBlobBytes, (int)g.nf, stream));
         st = queue_sizes_and_scan();
         if (st) return st;
         if (no_sync) return queue_encoders_without_sizes();

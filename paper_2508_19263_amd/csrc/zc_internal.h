@@ -104,13 +104,14 @@ int launch_codes(TensorDev *d_descs, uint32_t n_tensors, const uint64_t *d_hist,
 int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                 int scales_view, uint64_t *d_hist, void *stream);
 int launch_zero(uint64_t *d_words, uint64_t n_words, void *stream);
-int launch_write_headers(const TensorDev *d_descs, uint32_t n_tensors, const uint8_t *d_blobs, uint32_t blob_bytes, int n_fields, void *stream);
 // skip_routes: bit r set = leave tensors of route r to the specialised kernel that takes their whole chunks
 // whole: 0 = any chunks, 1 = up to four whole 64-lane chunks per work item, 2 = one such chunk per work item, shared
 // by the workgroup's four wavefronts
 int launch_sizes(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                  const uint32_t *d_enc_tables, uint32_t *d_units, void *stream);
-int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, const uint32_t *d_units, ScanOut *d_out, void *stream);
+// d_blobs: per tensor the header and code-length tables to put at the start of its container (blob_bytes apart), or null
+int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, const uint32_t *d_units, ScanOut *d_out, const uint8_t *d_blobs,
+                uint32_t blob_bytes, void *stream);
 int launch_encode(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                   const uint32_t *d_enc_tables, void *stream);
 int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,

@@ -436,10 +436,12 @@ int launch_encode(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_d
 
 // ---------------------------------------------------------------------------- scan
 // One workgroup per tensor: exclusive scan of the stream sizes (16-byte units) in
-// field-major order.  Writes the chunk index and the total size into the container
-// (when there is one) and the per-field totals for the host.
+// field-major order.  Writes the container's prologue (header and code-length tables as prepared in the
+// tensor's blob, when blobs is given), the chunk index with the zero padding behind it and the total size into
+// the container (when there is one), and the per-field totals for the host.
 
-__global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fields, const uint32_t *units, ScanOut *out)
+__global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fields, const uint32_t *units, ScanOut *out,
+                                               const uint8_t *blobs, uint32_t blob_bytes)
 {
     __shared__ uint32_t wave_sum[16];
     __shared__ uint32_t carry_s;
@@ -451,7 +453,16 @@ __global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fie
     const uint32_t *u = units + dg.units_off;
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (threadIdx.x == 0) carry_s = 0;
-    __syncthreads();
+    if (d.comp && blobs) {
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(blobs + (uint64_t)blockIdx.x * blob_bytes);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(d.comp);
+        for (uint32_t i = threadIdx.x; i < d.index_off[0] / 4; i += 1024) dst[i] = src[i];
+        if (threadIdx.x < 4 * (uint32_t)n_fields) {
+            const uint32_t f = threadIdx.x / 4, w = d.n_chunks + 1 + (threadIdx.x & 3);
+            if (w < ((d.n_chunks + 1 + 3) & ~3u)) dst[d.index_off[f] / 4 + w] = 0;
+        }
+    }
+    __syncthreads();                                             // the total size below overwrites a word of the prologue
     uint32_t field_start[kMaxFields + 1];
     for (int f = 0; f < n_fields; f++) {
         uint32_t *index = d.comp ? reinterpret_cast<uint32_t *>(d.comp + d.index_off[f]) : nullptr;
@@ -496,26 +507,12 @@ __global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fie
     }
 }
 
-int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, const uint32_t *d_units, ScanOut *d_out, void *stream)
+int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, const uint32_t *d_units, ScanOut *d_out, const uint8_t *d_blobs,
+                uint32_t blob_bytes, void *stream)
 {
     if (n_tensors == 0) return 0;
-    hipLaunchKernelGGL(k_scan, dim3(n_tensors), dim3(1024), 0, (hipStream_t)stream, d_descs, n_fields, d_units, d_out);
+    hipLaunchKernelGGL(k_scan, dim3(n_tensors), dim3(1024), 0, (hipStream_t)stream, d_descs, n_fields, d_units, d_out, d_blobs, blob_bytes);
     return (int)hipGetLastError();
-}
-
-// container prologue: header and code-length tables (prepared on the host) and the zero
-// padding behind each chunk index
-__global__ __launch_bounds__(256) void k_write_headers(const TensorDev *descs, const uint8_t *blobs, uint32_t blob_bytes, int n_fields)
-{
-    const TensorDev &d = descs[blockIdx.x];
-    if (!d.comp) return;
-    const uint32_t *src = reinterpret_cast<const uint32_t *>(blobs + (uint64_t)blockIdx.x * blob_bytes);
-    uint32_t *dst = reinterpret_cast<uint32_t *>(d.comp);
-    for (uint32_t i = threadIdx.x; i < d.index_off[0] / 4; i += 256) dst[i] = src[i];
-    if (threadIdx.x < 4 * (uint32_t)n_fields) {
-        const uint32_t f = threadIdx.x / 4, w = d.n_chunks + 1 + (threadIdx.x & 3);
-        if (w < ((d.n_chunks + 1 + 3) & ~3u)) dst[d.index_off[f] / 4 + w] = 0;
-    }
 }
 
 // Zero the histogram counters.  A kernel rather than a memset call, so that a caller who records the queue-only
@@ -530,13 +527,6 @@ int launch_zero(uint64_t *d_words, uint64_t n_words, void *stream)
 {
     if (n_words == 0) return 0;
     hipLaunchKernelGGL(k_zero, dim3((uint32_t)((n_words + 255) / 256)), dim3(256), 0, (hipStream_t)stream, d_words, n_words);
-    return (int)hipGetLastError();
-}
-
-int launch_write_headers(const TensorDev *d_descs, uint32_t n_tensors, const uint8_t *d_blobs, uint32_t blob_bytes, int n_fields, void *stream)
-{
-    if (n_tensors == 0) return 0;
-    hipLaunchKernelGGL(k_write_headers, dim3(n_tensors), dim3(256), 0, (hipStream_t)stream, d_descs, d_blobs, blob_bytes, n_fields);
     return (int)hipGetLastError();
 }
 
