@@ -1247,3 +1247,14 @@ def test_fp8_chunks_of_one_histogram_block():
     torch.cuda.synchronize()
     for i, c in enumerate(plain):
         assert torch.equal(outs[i].cpu()[:c[1].numel()], c[1]), c[0]
+
+
+def test_large_chunks():
+    # chunks of several MiB: thousands of rows per wavefront through the staging and refill rings, chunk indices
+    # with few entries, a short last chunk that is itself larger than most tensors of the other tests
+    for fmt, cb, S, policy in ((zc.FMT_FP8_E4M3, 4 << 20, 64, zc.POLICY_HUFF_ALL), (zc.FMT_FP8_E4M3, 1 << 20, 64, zc.POLICY_AUTO),
+                               (zc.FMT_BF16, 2 << 20, 64, zc.POLICY_HUFF_ALL), (zc.FMT_FP4_E2M1_MX, 1 << 20, 64, zc.POLICY_HUFF_ALL),
+                               (zc.FMT_FP8_E4M3, 1 << 20, 16, zc.POLICY_HUFF_ALL), (zc.FMT_BF16, 1 << 20, 8, zc.POLICY_AUTO)):
+        E = cb * 8 // zc.elem_bits(fmt)
+        n = 2 * E + E // 3 // 32 * 32
+        check_case(fmt, n, cb, S, policy, tag="large-chunks")
