@@ -782,19 +782,24 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
             }
             if (WRITE) flush_segments();
         };
-        u32x4 xa, ya = {0, 0, 0, 0}, xb, yb = {0, 0, 0, 0};
-        fetch(0, xa, ya);
-        fetch(1, xb, yb);
+        // Four register sets used in turn, each refilled four rows ahead: a page is a few rows, a row a few hundred
+        // cycles of work, and the wavefront shares its SIMD with three others at most (the staging rings fill
+        // the LDS), so a load issued two rows ahead was not back in time.
+        u32x4 x[4], y[4] = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+#pragma unroll
+        for (uint32_t k = 0; k < 4; k++) fetch(k, x[k], y[k]);
         uint32_t row = 0;
-        for (; row + 1 < rows; row += 2) {
-            const u32x4 va = xa ^ ya;
-            fetch(row + 2, xa, ya);
-            encode_row(va, row);
-            const u32x4 vb = xb ^ yb;
-            fetch(row + 3, xb, yb);
-            encode_row(vb, row + 1);
+        for (; row + 3 < rows; row += 4) {
+#pragma unroll
+            for (uint32_t k = 0; k < 4; k++) {
+                const u32x4 v = x[k] ^ y[k];
+                fetch(row + 4 + k, x[k], y[k]);
+                encode_row(v, row + k);
+            }
         }
-        if (row < rows) encode_row(xa ^ ya, row);
+#pragma unroll
+        for (uint32_t k = 0; k < 3; k++)
+            if (row + k < rows) encode_row(x[k] ^ y[k], row + k);
         if (WRITE) {
             // the words still owed to the decoder (a partial word and look-ahead words) and the zero padding of
             // the last 16-byte unit go into the ring too; then everything left in it leaves in 16-byte pieces
