@@ -784,7 +784,7 @@ def test_random_parameter_sweep():
     rng = np.random.default_rng(20250827)
     fmts = (zc.FMT_BF16, zc.FMT_FP8_E4M3, zc.FMT_FP4_E2M1_MX, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP4_E2M1_MX_BYTES, zc.FMT_FP4_E2M1_NV,
             zc.FMT_FP8_E5M2)
-    for case in range(182):
+    for case in range(700):
         fmt = fmts[case % len(fmts)]
         S = int(2 ** rng.integers(0, 7))
         unit = 256 if zc.scale_block(fmt) else 16
