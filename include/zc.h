@@ -20,8 +20,9 @@
  *     below) synchronise that stream before returning.
  *   - The library never allocates or frees device memory: scratch space comes in
  *     through `d_ws`.  The only state it keeps between calls is page-locked host
- *     memory: one buffer through which descriptors, work lists and tables are
- *     uploaded and a few through which sizes and headers are read back (allocated
+ *     memory: a few buffers through which descriptors, work lists and tables are
+ *     uploaded (used in turn, so that calls queued back to back do not wait for each
+ *     other's copies) and a few through which sizes and headers are read back (allocated
  *     on first use, grown when needed, held until the process ends).
  *   - ZC_HOST_CODES=1 in the environment (read once) makes the compress calls build
  *     their codes on the host instead of on the device: same containers, one more

@@ -141,9 +141,10 @@ zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T,
 #define LAUNCH_TRY(expr) do { if ((expr) != 0) return ZC_ERR_DEVICE; } while (0)
 
 // ---- pinned staging for what the host sends to the workspace ------------------
-// One page-locked buffer per process: the pieces of an upload are packed into it at their workspace
-// offsets and leave in a single asynchronous copy that needs no wait (the buffer outlives the call).
-// The next user waits for the previous copy's event before it overwrites the buffer.
+// A few page-locked buffers per process, used in turn: the pieces of an upload are packed into one at their
+// workspace offsets and leave in a single asynchronous copy that needs no wait (the buffer outlives the call).
+// A buffer's next user waits for the event of the copy that last left it, so calls queued back to back block
+// only when more than kSlots uploads are still ahead of the device.
 struct Piece { uint64_t off; const void *src; uint64_t bytes; };
 
 class HostStage {
@@ -153,30 +154,36 @@ public:
     {
         if (hi <= lo) return ZC_OK;
         std::lock_guard<std::mutex> lock(m_);
-        if (pending_ && hipEventSynchronize(ev_) != hipSuccess) return ZC_ERR_DEVICE;
-        pending_ = false;
+        Slot &k = slot_[next_];
+        next_ = (next_ + 1) % kSlots;
+        if (k.pending && hipEventSynchronize(k.ev) != hipSuccess) return ZC_ERR_DEVICE;
+        k.pending = false;
         const uint64_t need = hi - lo;
-        if (need > cap_) {
-            if (buf_) (void)hipHostFree(buf_);
-            buf_ = nullptr; cap_ = 0;
+        if (need > k.cap) {
+            // the first call sizes every slot that is still empty, so that the calls after it find theirs ready
             const uint64_t want = need + need / 2 + 4096;
-            if (hipHostMalloc((void **)&buf_, want, hipHostMallocDefault) != hipSuccess) return ZC_ERR_DEVICE;
-            cap_ = want;
+            for (Slot &q : slot_) {
+                if (&q != &k && q.buf) continue;
+                if (q.buf) (void)hipHostFree(q.buf);
+                q.buf = nullptr; q.cap = 0;
+                if (hipHostMalloc((void **)&q.buf, want, hipHostMallocDefault) != hipSuccess) return ZC_ERR_DEVICE;
+                q.cap = want;
+            }
         }
-        if (!ev_ && hipEventCreateWithFlags(&ev_, hipEventDisableTiming) != hipSuccess) return ZC_ERR_DEVICE;
+        if (!k.ev && hipEventCreateWithFlags(&k.ev, hipEventDisableTiming) != hipSuccess) return ZC_ERR_DEVICE;
         for (int i = 0; i < n; i++)
-            if (pieces[i].bytes) std::memcpy(buf_ + (pieces[i].off - lo), pieces[i].src, pieces[i].bytes);
-        HIP_TRY(hipMemcpyAsync(d_ws + lo, buf_, need, hipMemcpyHostToDevice, hs));
-        HIP_TRY(hipEventRecord(ev_, hs));
-        pending_ = true;
+            if (pieces[i].bytes) std::memcpy(k.buf + (pieces[i].off - lo), pieces[i].src, pieces[i].bytes);
+        HIP_TRY(hipMemcpyAsync(d_ws + lo, k.buf, need, hipMemcpyHostToDevice, hs));
+        HIP_TRY(hipEventRecord(k.ev, hs));
+        k.pending = true;
         return ZC_OK;
     }
 private:
+    static constexpr int kSlots = 4;
+    struct Slot { uint8_t *buf = nullptr; uint64_t cap = 0; hipEvent_t ev = nullptr; bool pending = false; };
     std::mutex m_;
-    uint8_t *buf_ = nullptr;
-    uint64_t cap_ = 0;
-    hipEvent_t ev_ = nullptr;
-    bool pending_ = false;
+    Slot slot_[kSlots];
+    int next_ = 0;
 };
 
 HostStage &host_stage() { static HostStage s; return s; }
