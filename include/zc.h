@@ -23,10 +23,13 @@
  *     memory: a few buffers through which descriptors, work lists and tables are
  *     uploaded (used in turn, so that calls queued back to back do not wait for each
  *     other's copies) and a few through which sizes and headers are read back (allocated
- *     on first use, grown when needed, held until the process ends).
- *   - ZC_HOST_CODES=1 in the environment (read once) makes the compress calls build
- *     their codes on the host instead of on the device: same containers, one more
- *     wait per call.
+ *     on first use, grown when needed, held until zc_release_host_buffers() or the end of
+ *     the process).  No environment variable is read.
+ *   - HIP graphs: only zc_decompress_batch_run may be recorded by stream capture (it
+ *     launches kernels and nothing else).  Every other entry point that takes a stream
+ *     copies from or to the library's page-locked buffers, may wait on an event and may
+ *     allocate page-locked memory, none of which a capture allows; a captured copy would
+ *     also replay whatever a later call left in the buffer.
  *   - Errors are returned as zc_status; nothing is thrown.  On error the
  *     destination contents are unspecified but nothing is written outside the
  *     capacities given.
@@ -81,13 +84,19 @@ typedef enum {
 typedef enum { ZC_MODE_EMPTY = 0, ZC_MODE_HUFF = 1, ZC_MODE_RAW = 2, ZC_MODE_CONST = 3 } zc_mode;
 
 typedef struct {
-    uint32_t struct_size;       /* = sizeof(zc_params) */
+    uint32_t struct_size;       /* = sizeof(zc_params): the struct may grow at its end, older sizes stay valid */
     uint32_t format;            /* zc_format */
     uint32_t chunk_bytes;       /* element bytes per chunk; multiple of 16 (FP4: of 256) */
     uint32_t max_code_len[3];   /* per field, 1..16 with 2^L >= alphabet; 0 = 16 for 8-bit symbols, else 8 */
     uint32_t streams_per_chunk; /* lanes per chunk: 1,2,4,...,64; 0 = 64 */
     uint32_t policy;            /* zc_policy */
+    uint32_t flags;             /* ZC_FLAG_* bits; absent (read as 0) when struct_size is the 32 bytes of the first layout */
 } zc_params;
+
+/* zc_params.flags.  HOST_CODES: the compress calls build their codes on the host instead of on the device: the
+ * same containers, one more wait per call (the histogram is read back).  What statistics and dictionary
+ * training do anyway; meant for checking one construction against the other. */
+enum { ZC_FLAG_HOST_CODES = 1 };
 
 /* Parsed, validated container header plus the code-length tables: everything the
  * host needs to launch a decode.  Filled by zc_compress / zc_read_info; may be
@@ -215,11 +224,32 @@ int zc_code_stale(const zc_info *code, const zc_info *written, double slack);
  * the device; with check_index != 0 also the chunk index).  d_comp: device; out: host. */
 zc_status zc_read_info(const void *d_comp, uint64_t comp_bytes, int check_index, zc_info *out, void *stream);
 
-/* Decompress a whole tensor: per chunk, table-driven decode of every field and
- * re-interleave into the original bit patterns (XORed with the base for a delta
- * container).  info: host, from zc_compress / zc_read_info, or NULL (then the header is
+/* The same validation for a container held in HOST memory; no device is touched.  host_bytes: the first
+ * have_bytes bytes of a container of container_bytes bytes (have_bytes <= container_bytes; the header and the
+ * code-length tables lie in the first 1 KiB, the chunk index ends at payload_offset).  Checked: magic, version,
+ * format and geometry, the layout offsets, a total size that is at most container_bytes, every field's mode,
+ * symbol width and code-length table (a complete prefix code whose longest length is the one recorded), and
+ * with check_index != 0 that the chunk index of every field is non-decreasing, continues where the field before
+ * ended and ends at the container's size.  ZC_ERR_CORRUPT when any of it fails (Sec. 3.1: the per-chunk
+ * metadata is what decoding relies on); ZC_ERR_INVALID_ARG when check_index is asked for and have_bytes does
+ * not reach the end of the index. */
+zc_status zc_validate_container(const void *host_bytes, uint64_t have_bytes, uint64_t container_bytes, int check_index, zc_info *out);
+
+/* Wait for the uploads still in flight from the library's page-locked buffers, then free those buffers and
+ * the read-back buffers no call holds.  The next call that needs one allocates it again.  Must not run
+ * concurrently with other calls into the library on the streams it waits for. */
+zc_status zc_release_host_buffers(void);
+
+/* Decompress a whole tensor (the inverse of Sec. 3.1 / 3.2 / 3.4's split-and-code, exact as Sec. 1 and
+ * 2.2 require; Sec. 5.1, 5.2: paid on every load, so it is the path to keep fast): per chunk,
+ * table-driven decode of every field and re-interleave into the original bit patterns (XORed
+ * with the base for a delta container, Sec. 3.1 / 4.1).  info: host, from zc_compress / zc_read_info, or NULL (then the header is
  * read with a blocking copy first).  Does not synchronise when info is given.
- * d_scales_out: FP4 only.  d_xor_base: required iff the container is a delta. */
+ * d_scales_out: FP4 only.  d_xor_base: required iff the container is a delta.
+ * A zc_info whose sizes cannot belong to a container (total_bytes below payload_offset or above
+ * comp_bytes, chunk_bytes 0, a chunk count that does not follow from n_elems) is refused with
+ * ZC_ERR_INVALID_ARG; this includes the zc_info the *_async compress calls leave behind, whose
+ * total_bytes is 0 until zc_read_info has filled it in. */
 zc_status zc_decompress(const void *d_comp, uint64_t comp_bytes, const zc_info *info,
                         void *d_dst, uint64_t dst_capacity, void *d_scales_out,
                         const void *d_xor_base, void *stream);
@@ -238,7 +268,9 @@ zc_status zc_decompress_chunks(const void *d_comp, uint64_t comp_bytes, const zc
  * d_scales_out) must be set.  All tensors must share format and streams.  A tensor with
  * d_chunk_ids set decodes only those chunks, densely (random-access page decode of a whole
  * K/V cache in one launch).  The per-tensor descriptors and the work list go to d_ws in a copy
- * queued on the stream ahead of the kernels; the call never waits. */
+ * queued on the stream ahead of the kernels; the call never waits.  Every info must describe a
+ * written container (see zc_decompress): one left by an *_async compress call is refused with
+ * ZC_ERR_INVALID_ARG until zc_read_info has filled it in. */
 zc_status zc_decompress_batch(const zc_tensor *tensors, uint32_t n_tensors,
                               void *d_ws, uint64_t ws_bytes, void *stream);
 

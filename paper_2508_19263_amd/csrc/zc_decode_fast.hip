@@ -18,7 +18,7 @@
 #include <type_traits>
 
 #include "zc_internal.h"
-#include "zc_device.cuh"
+#include "zc_device.h"
 
 namespace zc {
 

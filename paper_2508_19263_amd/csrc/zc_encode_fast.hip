@@ -10,7 +10,7 @@
 #include <hip/hip_runtime.h>
 
 #include "zc_internal.h"
-#include "zc_device.cuh"
+#include "zc_device.h"
 
 namespace zc {
 

@@ -1,5 +1,5 @@
-// Internal declarations shared by the host side (zc_api.cpp, zc_codebook.cpp) and the
-// kernels (zc_kernels.hip) of the HIP library.  Not part of the C ABI.
+// Internal declarations shared by the host side (zc_container.cpp, zc_compress.cpp, zc_decompress.cpp,
+// zc_codebook.cpp) and the kernels (*.hip) of the HIP library.  Not part of the C ABI.
 #pragma once
 #include <stdint.h>
 #include <stddef.h>
@@ -75,6 +75,22 @@ struct alignas(16) TensorDev {
 };
 
 struct WorkItem { uint32_t tensor, first; };   // `first`: first chunk / block of the item
+
+#ifdef __HIPCC__
+#define ZC_HOST_DEVICE __host__ __device__
+#else
+#define ZC_HOST_DEVICE
+#endif
+// Workgroups are handed to the 8 XCDs (each with an L2 of its own) in turn, so workgroup p runs on XCD p % 8.
+// Work lists are ordered so that every XCD walks one contiguous eighth of the list: position p of the ordered list
+// holds the item at this position of the natural list of n items.
+ZC_HOST_DEVICE inline uint64_t xcd_order_source(uint64_t p, uint64_t n)
+{
+    constexpr uint64_t kXcds = 8;
+    if (n < 2 * kXcds) return p;
+    const uint64_t q = n / kXcds, r = n % kXcds, k = p % kXcds;
+    return k * q + (k < r ? k : r) + p / kXcds;
+}
 
 // histogram block: bytes of input handled by one workgroup pass
 constexpr uint32_t kHistBlockBytes = 256 * 1024;

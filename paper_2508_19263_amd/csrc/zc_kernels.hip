@@ -16,7 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include "zc_internal.h"
-#include "zc_device.cuh"
+#include "zc_device.h"
 
 namespace zc {
 
@@ -515,8 +515,9 @@ int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, cons
     return (int)hipGetLastError();
 }
 
-// Zero the histogram counters.  A kernel rather than a memset call, so that a caller who records the queue-only
-// compress calls into a HIP graph gets a plain kernel node.
+// Zero the histogram counters.  A kernel rather than a memset call: the compress sequence then consists of kernel
+// launches only once its descriptors and work lists are in the workspace (memset nodes recorded into a HIP graph
+// have given wrong results on replays, so none is ever queued by this library).
 __global__ __launch_bounds__(256) void k_zero(uint64_t *p, uint64_t n)
 {
     const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;

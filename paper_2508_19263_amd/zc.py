@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libzc.so")
 
 FMT_BF16, FMT_FP8_E4M3, FMT_FP4_E2M1_MX, FMT_FP8_E4M3_BYTES, FMT_FP4_E2M1_MX_BYTES, FMT_FP4_E2M1_NV, FMT_FP8_E5M2 = 1, 2, 3, 4, 5, 6, 7
 POLICY_HUFF_ALL, POLICY_AUTO = 0, 1
+FLAG_HOST_CODES = 1
 MODE_EMPTY, MODE_HUFF, MODE_RAW, MODE_CONST = 0, 1, 2, 3
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_BUFFER_TOO_SMALL, ERR_CORRUPT, ERR_DEVICE = range(6)
 
@@ -22,12 +23,13 @@ EXPORTS = ["zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_compres
            "zc_decompress", "zc_decompress_chunks", "zc_decompress_batch", "zc_decompress_batch_plan",
            "zc_decompress_batch_run", "zc_stats", "zc_build_code", "zc_train_code", "zc_compress_with_code",
            "zc_compress_batch_with_code", "zc_compress_batch_with_code_async", "zc_compress_batch_async", "zc_code_stale",
-           "zc_status_string"]
+           "zc_validate_container", "zc_release_host_buffers", "zc_status_string"]
 
 
 class Params(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("format", C.c_uint32), ("chunk_bytes", C.c_uint32),
-                ("max_code_len", C.c_uint32 * 3), ("streams_per_chunk", C.c_uint32), ("policy", C.c_uint32)]
+                ("max_code_len", C.c_uint32 * 3), ("streams_per_chunk", C.c_uint32), ("policy", C.c_uint32),
+                ("flags", C.c_uint32)]
 
 
 class Info(C.Structure):
@@ -119,6 +121,10 @@ def lib():
         L.zc_decompress_batch_run.argtypes = [C.POINTER(BatchPlan), vp, vp]
         L.zc_stats.restype = C.c_int
         L.zc_stats.argtypes = [vp, u64, C.POINTER(Params), vp, vp, C.POINTER(StatsOut), vp, u64, vp]
+        L.zc_validate_container.restype = C.c_int
+        L.zc_validate_container.argtypes = [vp, u64, u64, C.c_int, C.POINTER(Info)]
+        L.zc_release_host_buffers.restype = C.c_int
+        L.zc_release_host_buffers.argtypes = []
         L.zc_build_code.restype = C.c_int
         L.zc_build_code.argtypes = [C.POINTER(u64), u32, u32, C.POINTER(C.c_uint8), C.POINTER(C.c_uint16)]
         _lib = L
@@ -129,10 +135,10 @@ def status_string(status):
     return lib().zc_status_string(status).decode()
 
 
-def params(fmt, chunk_bytes, max_code_len=(0, 0, 0), streams=0, policy=POLICY_HUFF_ALL):
+def params(fmt, chunk_bytes, max_code_len=(0, 0, 0), streams=0, policy=POLICY_HUFF_ALL, flags=0):
     p = Params()
     p.struct_size = C.sizeof(Params)
-    p.format, p.chunk_bytes, p.streams_per_chunk, p.policy = fmt, chunk_bytes, streams, policy
+    p.format, p.chunk_bytes, p.streams_per_chunk, p.policy, p.flags = fmt, chunk_bytes, streams, policy, flags
     for i in range(3):
         p.max_code_len[i] = max_code_len[i]
     return p
@@ -240,8 +246,23 @@ def read_info(comp, check_index=False):
     return info
 
 
-def decompress(comp, info=None, out=None, scales_out=None, xor_base=None):
-    """Returns (elements as uint8 tensor, scales or None)."""
+def validate_container(host_bytes, check_index=True, container_bytes=None):
+    """Host only: validate a container held in host memory (bytes, bytearray or a numpy uint8 array); returns its
+    Info.  container_bytes: size of the whole container when host_bytes is only its beginning."""
+    buf = (C.c_uint8 * len(host_bytes)).from_buffer_copy(bytes(host_bytes))
+    info = Info()
+    total = len(host_bytes) if container_bytes is None else container_bytes
+    _check(lib().zc_validate_container(buf, len(host_bytes), total, 1 if check_index else 0, C.byref(info)), "zc_validate_container")
+    return info
+
+
+def release_host_buffers():
+    _check(lib().zc_release_host_buffers(), "zc_release_host_buffers")
+
+
+def decompress(comp, info=None, out=None, scales_out=None, xor_base=None, read_header_in_call=False):
+    """Returns (elements as uint8 tensor, scales or None).  read_header_in_call: pass no Info to the library, which
+    then reads the header itself (a blocking copy) before it queues the decode."""
     if info is None:
         info = read_info(comp)
     raw = (info.n_elems * elem_bits(info.format) + 7) // 8
@@ -249,8 +270,8 @@ def decompress(comp, info=None, out=None, scales_out=None, xor_base=None):
         out = torch.empty(raw, dtype=torch.uint8, device=comp.device)
     if info.n_fields == 3 and scales_out is None:
         scales_out = torch.empty(max(info.n_elems // scale_block(info.format), 1), dtype=torch.uint8, device=comp.device)
-    st = lib().zc_decompress(_ptr(comp), comp.numel(), C.byref(info), _ptr(out), out.numel() * out.element_size(),
-                             _ptr(scales_out), _ptr(xor_base), _stream())
+    st = lib().zc_decompress(_ptr(comp), comp.numel(), None if read_header_in_call else C.byref(info), _ptr(out),
+                             out.numel() * out.element_size(), _ptr(scales_out), _ptr(xor_base), _stream())
     _check(st, "zc_decompress")
     return out, scales_out
 

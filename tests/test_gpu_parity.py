@@ -1,4 +1,6 @@
 """GPU parity: the HIP library against the CPU oracle, byte for byte, through the C ABI."""
+from ctypes import byref as C_byref
+
 import numpy as np
 import pytest
 import torch
@@ -359,6 +361,65 @@ def test_errors():
     comp, info = zc.compress(w1.to(DEV), 5000, zc.params(zc.FMT_BF16, 4096), xor_base=w0.to(DEV))
     with pytest.raises(zc.ZcError):
         zc.decompress(comp, info)
+
+
+def test_decompress_reads_the_header_itself():
+    # zc_decompress / zc_decompress_chunks without a zc_info: the library reads and validates the header first
+    for fmt, n, cb, S in ((zc.FMT_FP8_E4M3, 5 * 4096 + 77, 4096, 64), (zc.FMT_BF16, 3 * 2048 + 5, 4096, 8),
+                          (zc.FMT_FP4_E2M1_MX, 32 * 700, 1024, 64)):
+        src, sc = make_input(fmt, n, 41)
+        comp, info = zc.compress(dev(src), n, zc.params(fmt, cb, streams=S), scales=dev(sc))
+        out, sco = zc.decompress(comp, read_header_in_call=True)
+        torch.cuda.synchronize()
+        assert torch.equal(out.cpu()[:src.numel()], src.view(torch.uint8).reshape(-1))
+        if sc is not None:
+            assert torch.equal(sco.cpu()[:sc.numel()], sc)
+    bad = comp.clone(); bad[1] = 0x00
+    with pytest.raises(zc.ZcError) as e:
+        zc.decompress(bad, info, read_header_in_call=True)
+    assert e.value.status == zc.ERR_CORRUPT
+
+
+def test_container_description_that_was_never_filled_in_is_refused():
+    # the *_async compress calls leave info.total_bytes at 0; a decode call handed that description must say so
+    # instead of returning success with nothing decoded
+    srcs = [wl.fp8_weight(6 * 2048, seed=61), wl.fp8_weight(9 * 2048, seed=62)]
+    p = zc.params(zc.FMT_FP8_E4M3, 2048, streams=8)
+    code = zc.train_code(dev(srcs[0]), srcs[0].numel(), p)
+    bt = zc.Batch([dev(s) for s in srcs], [s.numel() for s in srcs], p)
+    bt.compress(code=code)                                  # fills info
+    bt.compress_async(code)                                 # leaves total_bytes 0
+    torch.cuda.synchronize()
+    assert bt.arr[0].info.total_bytes == 0
+    bt.prepare_outputs()
+    for o_ in bt.out:
+        o_.fill_(0xEE)
+    st = zc.lib().zc_decompress_batch(bt.arr, bt.n, zc._ptr(bt.ws), bt.ws.numel(), zc._stream())
+    assert st == zc.ERR_INVALID_ARG
+    plan = zc.BatchPlan()
+    st = zc.lib().zc_decompress_batch_plan(bt.arr, bt.n, zc._ptr(bt.ws_plan), bt.ws_plan.numel(), C_byref(plan), zc._stream())
+    assert st == zc.ERR_INVALID_ARG
+    stale = bt.arr[0].info
+    with pytest.raises(zc.ZcError) as e:
+        zc.decompress(bt.comp[0], stale)
+    assert e.value.status == zc.ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert all(bool((o_ == 0xEE).all()) for o_ in bt.out)
+    # other descriptions that cannot belong to a container
+    good = zc.read_info(bt.comp[0])
+    for field, value in (("chunk_bytes", 0), ("chunk_bytes", 2040), ("n_chunks", good.n_chunks + 1), ("streams", 3),
+                         ("payload_offset", 0), ("total_bytes", bt.comp[0].numel() + 16)):
+        broken = zc.Info.from_buffer_copy(good)
+        setattr(broken, field, value)
+        with pytest.raises(zc.ZcError) as e:
+            zc.decompress(bt.comp[0], broken)
+        assert e.value.status == zc.ERR_INVALID_ARG, field
+    # once the headers have been read back the same batch decodes
+    bt.refresh_info()
+    outs = bt.decompress()
+    torch.cuda.synchronize()
+    for out, s_ in zip(outs, srcs):
+        assert torch.equal(out.cpu()[:s_.numel()], s_)
 
 
 def test_determinism_and_poisoned_buffers():
@@ -923,24 +984,20 @@ def test_compress_without_sync_and_host_built_codes():
         torch.cuda.synchronize()
         for out, s in zip(outs, srcs):
             assert torch.equal(out.cpu()[:s.numel()], s)
-    # the same call with the code built on the host (what ZC_HOST_CODES=1 selects): a fresh process, as the
-    # switch is read once
-    import os, subprocess, sys
-    script = (
-        "import sys, numpy as np, torch\n"
-        "sys.path.insert(0, %r)\n"
-        "from paper_2508_19263_amd import zc, workloads as wl\n"
-        "from oracle import zc_oracle as o\n"
-        "for fmt, ofmt in ((zc.FMT_FP8_E4M3, o.FP8_E4M3), (zc.FMT_BF16, o.BF16)):\n"
-        "    s = wl.fp8_weight(70000, seed=5) if fmt == zc.FMT_FP8_E4M3 else wl.bf16_weight(35000, seed=5).view(torch.uint8).reshape(-1)\n"
-        "    n = 70000 if fmt == zc.FMT_FP8_E4M3 else 35000\n"
-        "    comp, info = zc.compress(s.cuda(), n, zc.params(fmt, 4096))\n"
-        "    want = o.compress(s.numpy(), n, o.params(ofmt, 4096))\n"
-        "    assert np.array_equal(comp.cpu().numpy(), want)\n"
-        "print('host codes ok')\n") % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    env = dict(os.environ, ZC_HOST_CODES="1")
-    r = subprocess.run([sys.executable, "-c", script], env=env, capture_output=True, text=True, timeout=110)
-    assert r.returncode == 0 and "host codes ok" in r.stdout, r.stdout + r.stderr
+    # the same containers with the code built on the host (ZC_FLAG_HOST_CODES), also through the older, shorter
+    # layout of zc_params (no flags field: device-built codes)
+    for fmt, ofmt, n in ((zc.FMT_FP8_E4M3, o.FP8_E4M3, 70000), (zc.FMT_BF16, o.BF16, 35000)):
+        s = wl.fp8_weight(n, seed=5) if fmt == zc.FMT_FP8_E4M3 else wl.bf16_weight(n, seed=5).view(torch.uint8).reshape(-1)
+        want = o.compress(s.numpy(), n, o.params(ofmt, 4096))
+        comp, info = zc.compress(dev(s), n, zc.params(fmt, 4096, flags=zc.FLAG_HOST_CODES))
+        assert np.array_equal(comp.cpu().numpy(), want)
+        short = zc.params(fmt, 4096)
+        short.struct_size = 32
+        comp, info = zc.compress(dev(s), n, short)
+        assert np.array_equal(comp.cpu().numpy(), want)
+    bad = zc.params(zc.FMT_FP8_E4M3, 4096, flags=2)               # an unknown flag bit
+    with pytest.raises(zc.ZcError):
+        zc.compress(dev(srcs[0]), srcs[0].numel(), bad)
 
 
 def test_bf16_encoder_every_refill_period():

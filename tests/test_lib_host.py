@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_sizes_match_the_header():
     # sizes computed from the header's field lists by hand: see include/zc.h
-    assert C.sizeof(zc.Params) == 4 * 8
+    assert C.sizeof(zc.Params) == 4 * 9                                      # 32 bytes of the first layout + flags
     assert C.sizeof(zc.Info) == 8 * 4 + 3 * 8 + 6 * 8 + 12 + 768 + 4      # +4: tail padding to 8
     assert C.sizeof(zc.FieldStats) == 16 + 8 + 2048 + 256 + 8 + 8 + 8 + 8 + 8
     assert C.sizeof(zc.Tensor) == 11 * 8 + C.sizeof(zc.Info)

@@ -1,5 +1,6 @@
-"""Host code under AddressSanitizer and UndefinedBehaviorSanitizer: the oracle (random round trips of every format)
-and the library's host-side code construction (random histograms).  GPU code is not involved."""
+"""Host code under AddressSanitizer and UndefinedBehaviorSanitizer: the oracle (random round trips of every format),
+the library's host-side code construction (random histograms) and its container validation (damaged containers).
+GPU code is not involved."""
 import os
 import shutil
 import subprocess
@@ -35,3 +36,12 @@ def test_host_code_construction_under_sanitizers(tmp_path):
     csrc = os.path.join(ROOT, "paper_2508_19263_amd", "csrc")
     _build_and_run(tmp_path, "g++", ["-std=c++17", "-I" + csrc, os.path.join(HERE, "sanitize", "host_code_lengths.cpp"),
                                      os.path.join(csrc, "zc_codebook.cpp")], "host_code_lengths")
+
+
+def test_host_container_validation_under_sanitizers(tmp_path):
+    # the validator and the code construction it links against are the library's; the containers are the oracle's
+    csrc = os.path.join(ROOT, "paper_2508_19263_amd", "csrc")
+    _build_and_run(tmp_path, "g++", ["-std=c++17", "-I" + csrc, "-I" + os.path.join(ROOT, "include"),
+                                     os.path.join(HERE, "sanitize", "host_container_validation.cpp"),
+                                     os.path.join(csrc, "zc_container.cpp"), os.path.join(csrc, "zc_codebook.cpp"),
+                                     "-x", "c", os.path.join(ROOT, "oracle", "zc_oracle.c"), "-lm"], "host_container_validation")
