@@ -185,6 +185,25 @@ zc_status zc_compress_batch(zc_tensor *tensors, uint32_t n_tensors, const zc_par
 zc_status zc_compress_batch_async(zc_tensor *tensors, uint32_t n_tensors, const zc_params *params,
                                   void *d_ws, uint64_t ws_bytes, void *stream);
 
+/* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  zc_compress_batch_async for ONE tensor without a workspace argument and without any allocation,
+ * copy or wait: the call launches kernels on `stream` and nothing else (no hipMalloc, hipHostMalloc or hipFree,
+ * no page-locked staging, no heap memory).  The scratch that the other compress calls take through d_ws is a
+ * file-scope device array of ZC_NOALLOC_SCRATCH_BYTES inside the library (every GPU the library runs on holds
+ * its own copy until the process ends), and descriptor, header and work lists are written into it by a kernel
+ * from its arguments.  Codes are built on the device; the container is byte for byte what zc_compress writes.
+ * Limits: zc_workspace_bytes(&n_elems, 1, params) must not exceed ZC_NOALLOC_SCRATCH_BYTES (which admits e.g.
+ * 504 MiB of FP8 in 256 KiB chunks or 901 MiB of FP8 K/V pages of 2 KiB in one call) and dst_capacity
+ * must be at least zc_compress_bound(n_elems, params), else ZC_ERR_BUFFER_TOO_SMALL and nothing is queued;
+ * ZC_FLAG_HOST_CODES is refused (ZC_ERR_INVALID_ARG).  out size and code are not returned: once the stream has
+ * reached this point the container's header holds them (zc_read_info).  All calls on one GPU share that GPU's
+ * array: a second call may be queued behind the first on the SAME stream (stream order keeps them apart), but
+ * calls on different streams, or from threads that do not order their work, race on it. */
+#define ZC_NOALLOC_SCRATCH_BYTES (4u << 20)
+zc_status zc_compress_noalloc(const void *d_src, uint64_t n_elems, const zc_params *params,
+                              const void *d_xor_base, const void *d_scales,
+                              void *d_dst, uint64_t dst_capacity, void *stream);
+
 /* Static dictionaries (Sec. 3.3, 5.2: a code computed ahead of time on representative data and
  * reused while the exponent distribution stays stable, e.g. across K/V-cache time steps).
  * zc_train_code builds a dictionary from a representative tensor: its per-field histogram with

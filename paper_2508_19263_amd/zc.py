@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libzc.so")
 FMT_BF16, FMT_FP8_E4M3, FMT_FP4_E2M1_MX, FMT_FP8_E4M3_BYTES, FMT_FP4_E2M1_MX_BYTES, FMT_FP4_E2M1_NV, FMT_FP8_E5M2 = 1, 2, 3, 4, 5, 6, 7
 POLICY_HUFF_ALL, POLICY_AUTO = 0, 1
 FLAG_HOST_CODES = 1
+NOALLOC_SCRATCH_BYTES = 4 << 20
 MODE_EMPTY, MODE_HUFF, MODE_RAW, MODE_CONST = 0, 1, 2, 3
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_BUFFER_TOO_SMALL, ERR_CORRUPT, ERR_DEVICE = range(6)
 
@@ -23,7 +24,7 @@ EXPORTS = ["zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_compres
            "zc_decompress", "zc_decompress_chunks", "zc_decompress_batch", "zc_decompress_batch_plan",
            "zc_decompress_batch_run", "zc_stats", "zc_build_code", "zc_train_code", "zc_compress_with_code",
            "zc_compress_batch_with_code", "zc_compress_batch_with_code_async", "zc_compress_batch_async", "zc_code_stale",
-           "zc_validate_container", "zc_release_host_buffers", "zc_status_string"]
+           "zc_validate_container", "zc_release_host_buffers", "zc_compress_noalloc", "zc_status_string"]
 
 
 class Params(C.Structure):
@@ -95,6 +96,8 @@ def lib():
         L.zc_compress.argtypes = [vp, u64, C.POINTER(Params), vp, vp, vp, u64, C.POINTER(u64), C.POINTER(Info), vp, u64, vp]
         L.zc_compress_batch.restype = C.c_int
         L.zc_compress_batch.argtypes = [C.POINTER(Tensor), u32, C.POINTER(Params), vp, u64, vp]
+        L.zc_compress_noalloc.restype = C.c_int
+        L.zc_compress_noalloc.argtypes = [vp, u64, C.POINTER(Params), vp, vp, vp, u64, vp]
         L.zc_code_stale.restype = C.c_int
         L.zc_code_stale.argtypes = [C.POINTER(Info), C.POINTER(Info), C.c_double]
         L.zc_train_code.restype = C.c_int
@@ -205,6 +208,14 @@ def compress(src, n_elems, p, xor_base=None, scales=None, dst=None, ws=None):
                            C.byref(size), C.byref(info), _ptr(ws), ws.numel(), _stream())
     _check(st, "zc_compress")
     return dst.view(torch.uint8).reshape(-1)[:size.value], info
+
+
+def compress_noalloc(src, n_elems, p, dst, xor_base=None, scales=None):
+    """Queue the compression of one tensor into dst (at least compress_bound bytes) without a workspace and
+    without any allocation; the container's size is in its header once the stream gets there (read_info)."""
+    st = lib().zc_compress_noalloc(_ptr(src), n_elems, C.byref(p), _ptr(xor_base), _ptr(scales), _ptr(dst),
+                                   dst.numel() * dst.element_size(), _stream())
+    _check(st, "zc_compress_noalloc")
 
 
 def train_code(src, n_elems, p, xor_base=None, scales=None, ws=None):
