@@ -622,6 +622,282 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split
 }
 
 // ---------------------------------------------------------------------------------------
+// BF16 with 64 lanes per chunk and whole chunks, exponent field table decoded and the sign+mantissa field either
+// table decoded on the same refill period (checkpoint deltas, Sec. 3.1 / 4.1) or stored plainly (weights): the
+// same streams and rings as above with the per-symbol work cut down for this format.
+//   - Table entries are laid out so that a value is assembled without shifting fields around: an exponent entry is
+//     (e << 7) | length, a sign+mantissa entry (s << 15) | (length << 8) | mantissa.  Two entries packed into one
+//     register are the two halves of an output word, and one bit-field insert with the exponent mask 0x7F80 per
+//     half merges the fields; the lengths sit in bits the insert drops.
+//   - With two symbols per refill step the lookups index from the window shifted left by one (entries are 2 bytes),
+//     so a lookup is an AND and a load; a step's lengths are added to the bit position with one three-operand add.
+constexpr uint32_t kExpMask2 = 0x7F807F80u;            // the exponent bits of both halves of an output word
+
+__device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (a & mask) | (b & ~mask); }   // v_bfi_b32
+
+// shift amount taken from byte 1 of `by` (the hardware uses its low 5 bits)
+__device__ __forceinline__ uint32_t shr_by_byte1(uint32_t v, uint32_t by)
+{
+    uint32_t r;
+    asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD" : "=v"(r) : "v"(by), "v"(v));
+    return r;
+}
+__device__ __forceinline__ uint32_t add_byte1(uint32_t a, uint32_t b)      // a + byte 1 of b
+{
+    uint32_t r;
+    asm("v_add_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// FieldTab::lut entries (length | symbol << 8) rewritten for this path, in place; 0 (a code longer than the index) stays 0
+template <int FIELD>
+__device__ __forceinline__ uint32_t bf16_entry(uint32_t e)
+{
+    const uint32_t len = e & 31u, sym = e >> 8;
+    if (FIELD == 0) return (sym << 7) | len;
+    return ((sym & 0x80u) << 8) | (len << 8) | (sym & 0x7Fu);
+}
+template <int FIELD>
+__device__ void bf16_relayout(FieldTab &T)
+{
+    const uint32_t n = T.mask + 1;
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) T.lut[i] = (uint16_t)bf16_entry<FIELD>(T.lut[i]);
+    __syncthreads();
+}
+
+// The stream ring of huff_open / huff_ring_service / huff_refill with its size as a parameter: RW words per wavefront
+// and field, refilled SEG = RW / 4 words at a time (SEG / 64 words per lane).  A segment that has been asked for is
+// written into the ring only when the next one is asked for, i.e. once a whole segment has been consumed since:
+// that is the time its load has to arrive.  Invariant when ring_service is called: words [wbase, wbase + RW) are in
+// the ring except the newest SEG, which may still be in flight or in registers; wpos - wbase < 2 * SEG, and at
+// most SEG words are handed out before the next call, so every word asked for is below wbase + 3 * SEG: present.
+template <uint32_t RW>
+__device__ __forceinline__ void ring_open(HuffStream &H, const FieldTab &T, __amdgpu_buffer_rsrc_t rs, char *ring, uint32_t lane)
+{
+    constexpr uint32_t SEG = RW / 4, B = SEG / 16;       // bytes per lane and segment: 4 or 8
+    static_assert(B == 4 || B == 8, "one 4- or 8-byte load per lane and segment");
+    H.rs = rs; H.ring = ring;
+#pragma unroll
+    for (int i = 0; i < 4; i++) H.lim[i] = uniform32(T.limit[kLutBits + 1 + i]);
+#pragma unroll
+    for (uint32_t q = 0; q < 4; q++) {
+        if (B == 8) *reinterpret_cast<u32x2 *>(ring + q * SEG * 4 + lane * 8) = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(lane * 8 + q * SEG * 4), 0, 0);
+        else *reinterpret_cast<uint32_t *>(ring + q * SEG * 4 + lane * 4) = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(lane * 4 + q * SEG * 4), 0, 0);
+    }
+    H.W = (uint64_t)(*reinterpret_cast<const uint32_t *>(ring + lane * 4)) << 32;   // step 0: word `lane`
+    H.c = 32; H.wpos = 64; H.wbase = 0; H.pslot = 0; H.pending = false;
+    H.pv = u32x2{0, 0};
+}
+
+template <uint32_t RW>
+__device__ __forceinline__ void ring_service(HuffStream &H, uint32_t lane)
+{
+    constexpr uint32_t SEG = RW / 4, B = SEG / 16;
+    if (H.wpos - H.wbase >= SEG) {                       // the oldest segment is used up: its place takes the segment after the newest
+        if (H.pending) {
+            if (B == 8) *reinterpret_cast<u32x2 *>(H.ring + H.pslot * 4 + lane * 8) = H.pv;
+            else *reinterpret_cast<uint32_t *>(H.ring + H.pslot * 4 + lane * 4) = H.pv.x;
+        }
+        // the newest segment [wbase + 3 SEG, wbase + 4 SEG) is complete now; the one asked for goes where the oldest was
+        if (B == 8) H.pv = __builtin_amdgcn_raw_buffer_load_b64(H.rs, (int)(lane * 8 + (H.wbase + RW) * 4), 0, 0);
+        else H.pv.x = __builtin_amdgcn_raw_buffer_load_b32(H.rs, (int)(lane * 4 + (H.wbase + RW) * 4), 0, 0);
+        H.pslot = H.wbase & (RW - 1);
+        H.wbase += SEG;
+        H.pending = true;
+    }
+}
+
+template <uint32_t RW>
+__device__ __forceinline__ void ring_refill(HuffStream &H)
+{
+    const bool need = H.c >= 32;
+    const uint64_t bm = __ballot(need);
+    const uint32_t w = *reinterpret_cast<const uint32_t *>(H.ring + ((prefix_count64(bm) * 4 + H.wpos * 4) & (RW * 4 - 1)));
+    H.W = need ? ((H.W >> 32) | ((uint64_t)w << 32)) : H.W;
+    H.c = need ? H.c - 32 : H.c;
+    H.wpos += (uint32_t)__popcll(bm);
+}
+
+// One refill period of R symbols of field FIELD: the entries of symbols 2i and 2i+1, packed into out[first / 2 + i].
+template <int FIELD, int R, bool LONG, uint32_t RW>
+__device__ __forceinline__ void bf16_period(HuffStream &H, const FieldTab &T, const char *lut, uint32_t mask2, int first, uint32_t out[4])
+{
+    static_assert(!LONG || R == 2, "codes beyond the lookup index come with a refill period of 2 only");
+    const uint32_t x = (uint32_t)(H.W >> H.c);             // the next 32 unread bits
+    uint32_t e[R];
+    if (R == 2) {
+        // entries are two bytes: index from the window shifted left once; bits [1..] of (y >> n) are bits [0..] of (x >> n)
+        uint32_t y = x << 1;
+        e[0] = *reinterpret_cast<const uint16_t *>(lut + (y & mask2));
+        y = FIELD == 0 ? y >> (e[0] & 31u) : shr_by_byte1(y, e[0]);
+        e[1] = *reinterpret_cast<const uint16_t *>(lut + (y & mask2));
+        if (LONG) {
+            // an empty entry stands for a code longer than the index; it shifts by nothing, so the entry after it is
+            // empty too and the last one tells
+            if (__any(e[1] == 0)) {
+                uint32_t x1 = x;
+                if (e[0] == 0) {
+                    e[0] = bf16_entry<FIELD>(long_code(T, H, x));
+                    x1 = FIELD == 0 ? x >> (e[0] & 31u) : shr_by_byte1(x, e[0]);
+                    e[1] = *reinterpret_cast<const uint16_t *>(lut + ((x1 << 1) & mask2));
+                } else x1 = FIELD == 0 ? x >> (e[0] & 31u) : shr_by_byte1(x, e[0]);
+                if (e[1] == 0) e[1] = bf16_entry<FIELD>(long_code(T, H, x1));
+            }
+        }
+    } else {
+        uint32_t xx = x;
+#pragma unroll
+        for (int j = 0; j < R; j++) {
+            e[j] = *reinterpret_cast<const uint16_t *>(lut + ((xx << 1) & mask2));
+            xx = FIELD == 0 ? xx >> (e[j] & 31u) : shr_by_byte1(xx, e[j]);
+        }
+    }
+    // the lengths: bits 4..0 of an exponent entry (the exponents above them leave the low 7 bits of a sum alone),
+    // byte 1 of a sign+mantissa entry (the sign above the length leaves the low 7 bits of a sum alone); a period's
+    // lengths add up to 32 at most and c was 32 at most
+    uint32_t c = H.c;
+#pragma unroll
+    for (int j = 0; j < R; j += 2) {
+        if (FIELD == 0) c = c + e[j] + e[j + 1];
+        else c = add_byte1(add_byte1(c, e[j]), e[j + 1]);
+        out[(first + j) / 2] = __builtin_amdgcn_perm(e[j + 1], e[j], 0x05040100u);       // low halves of both
+    }
+    H.c = c & 0x7Fu;
+    ring_refill<RW>(H);
+}
+
+// The rows of one chunk.  R: refill period of the exponent field (and of the sign+mantissa field when PAIR).
+// PAIR: the sign+mantissa field is table decoded on the same period; else it is flat coded, raw or constant.
+template <int R, bool LONG, bool PAIR, bool XOR>
+__device__ __forceinline__ void bf16_rows(const FieldTab *tab, uint32_t kind1, uint32_t konst1, __amdgpu_buffer_rsrc_t r0, __amdgpu_buffer_rsrc_t r1,
+                                          __amdgpu_buffer_rsrc_t ds, __amdgpu_buffer_rsrc_t bs, char *ring0, char *ring1, uint32_t rows, uint32_t lane)
+{
+    // two table-decoded fields: rings of 256 words, serviced at every refill step, so that eight workgroups fit a
+    // compute unit's LDS; one field: 512 words, serviced every other step
+    constexpr uint32_t RW = PAIR ? 256u : 512u;
+    HuffStream A, B;
+    ring_open<RW>(A, tab[0], r0, ring0, lane);
+    if (PAIR) ring_open<RW>(B, tab[1], r1, ring1, lane);
+    const char *la = reinterpret_cast<const char *>(tab[0].lut), *lb = reinterpret_cast<const char *>(tab[1].lut);
+    const uint32_t ma2 = uniform32(tab[0].mask) << 1, mb2 = PAIR ? uniform32(tab[1].mask) << 1 : 0u;
+    const uint32_t k1 = konst1 | (konst1 << 8) | (konst1 << 16) | (konst1 << 24);
+    // What a row takes from global memory besides its stream words (plain sign+mantissa bytes, the base of a delta)
+    // is asked for one row ahead, so that the loads are in flight while the row before is decoded.  A row past the
+    // end is outside the buffer resources: such loads return zeros and touch nothing.
+    auto fetch_m = [&](uint32_t row, uint32_t m[2]) {
+        m[0] = k1; m[1] = k1;
+        if (kind1 == KIND_FLAT) {
+#pragma unroll
+            for (int h = 0; h < 2; h++) m[h] = __builtin_amdgcn_raw_buffer_load_b32(r1, (int)(lane * 4), (int)((row * 2 + h) * 256), 0);
+        } else if (kind1 == KIND_RAW) {
+            const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r1, (int)(lane * 8), (int)(row * 512), 0);
+            m[0] = v.x; m[1] = v.y;
+        }
+    };
+    uint32_t m_next[2] = {0, 0};
+    u32x4 base_next = {0, 0, 0, 0};
+    if (!PAIR) fetch_m(0, m_next);
+    if (XOR) base_next = __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), 0, 0);
+    for (uint32_t row = 0; row < rows; row++) {
+        uint32_t ea[4], mb[4];
+        const uint32_t m[2] = {m_next[0], m_next[1]};
+        const u32x4 base = base_next;
+        if (!PAIR) fetch_m(row + 1, m_next);
+        if (XOR) base_next = __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)((row + 1) * 1024), 0);
+#pragma unroll
+        for (int g = 0; g < 8 / R; g++) {
+            if (PAIR || (g & 1) == 0) { ring_service<RW>(A, lane); if (PAIR) ring_service<RW>(B, lane); }
+            bf16_period<0, R, LONG, RW>(A, tab[0], la, ma2, g * R, ea);
+            if (PAIR) bf16_period<1, R, LONG, RW>(B, tab[1], lb, mb2, g * R, mb);
+        }
+        if (!PAIR) {
+            // eight sign+mantissa bytes of the lane (a flat code is the byte, most significant bit first), then two per
+            // output word: byte b -> (s << 15) | ... | m (bits 14..7 are dropped by the insert)
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const uint32_t mm = kind1 == KIND_FLAT ? reverse_in_groups<8>(m[i / 2]) : m[i / 2];
+                const uint32_t t = __builtin_amdgcn_perm(0, mm, (i & 1) ? 0x0C030C02u : 0x0C010C00u);      // bytes 2i, 2i+1 into bytes 0 and 2
+                mb[i] = t | (t << 8);
+            }
+        }
+        u32x4 v;
+#pragma unroll
+        for (int i = 0; i < 4; i++) v[i] = bfi(kExpMask2, ea[i], mb[i]);
+        if (XOR) v ^= base;
+        __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
+    }
+}
+
+
+// One wavefront per whole chunk, four chunks per workgroup, as k_decode_s64; the host sends a set of tensors here
+// only when every one of them has the shape bf16_rows is written for.
+template <bool XOR>
+__global__ __launch_bounds__(256) void k_decode_bf16_s64(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single)
+{
+    extern __shared__ __attribute__((aligned(16))) uint32_t rings[];     // [ring][wave][kRing2Words], sized by the host
+    __shared__ FieldTab tab[2];
+    __shared__ TensorDev dsh;
+    WorkItem it;
+    if (use_single) { it.tensor = 0; it.first = blockIdx.x * kWavesPerGroup; }
+    else it = work[blockIdx.x];
+    if (threadIdx.x == 0) dsh = use_single ? single : descs[it.tensor];
+    __syncthreads();
+    const TensorDev &d = dsh;
+    const uint32_t kind0 = uniform32(d.kind[0]), kind1 = uniform32(d.kind[1]);
+    const uint32_t p0 = uniform32(d.period[0]), p1 = uniform32(d.period[1]);
+    const bool pair = kind1 == KIND_HUFF;
+    if (kind0 != KIND_HUFF || (p0 != 2 && p0 != 4 && p0 != 8) || (pair && p1 != p0)) return;       // whole workgroup; the host never asks for this
+    build_field_tab(tab[0], d.comp + d.table_off[0], 256, d.lmax[0]);
+    bf16_relayout<0>(tab[0]);
+    if (pair) {
+        build_field_tab(tab[1], d.comp + d.table_off[1], 256, d.lmax[1]);
+        bf16_relayout<1>(tab[1]);
+    }
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t chunk = uniform32(it.first + wave);
+    const uint32_t cb = uniform32(d.chunk_bytes);
+    const uint32_t n_full = (uint32_t)(uniform64(d.n_elems) / (cb / 2));
+    if (chunk >= n_full) return;
+    const uint8_t *comp = reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.comp));
+    const uint64_t payload = uniform64(d.payload_off), total = uniform64(d.total_bytes);
+    const uint8_t *sp[2];
+    uint32_t sb[2];
+    for (int f = 0; f < 2; f++)
+        if (!stream_range(d, comp, f, chunk, payload, total, sp[f], sb[f])) return;      // damaged index: leave the chunk alone
+    const __amdgpu_buffer_rsrc_t r0 = make_rsrc(sp[0], sb[0]), r1 = make_rsrc(sp[1], sb[1]);
+    const __amdgpu_buffer_rsrc_t ds = make_rsrc(reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.dst)) + (uint64_t)chunk * cb, cb);
+    const __amdgpu_buffer_rsrc_t bs = make_rsrc(XOR ? reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.base)) + (uint64_t)chunk * cb : comp, XOR ? cb : 0);
+    // one field: 512 words per wavefront; two: 256 words per wavefront and field (the same 8 KiB per workgroup)
+    char *ring0 = reinterpret_cast<char *>(rings) + wave * (pair ? 1024 : 2048), *ring1 = ring0 + kWavesPerGroup * 1024;
+    const uint32_t rows = cb / 1024, konst1 = uniform32(d.konst[1]);
+    const bool any_long = uniform32(tab[0].lmax) > (uint32_t)kLutBits || (pair && uniform32(tab[1].lmax) > (uint32_t)kLutBits);
+    switch (p0 * 4 + (pair ? 2 : 0) + ((any_long && p0 == 2) ? 1 : 0)) {
+    case 2 * 4 + 0: bf16_rows<2, false, false, XOR>(tab, kind1, konst1, r0, r1, ds, bs, ring0, ring1, rows, lane); break;
+    case 2 * 4 + 1: bf16_rows<2, true, false, XOR>(tab, kind1, konst1, r0, r1, ds, bs, ring0, ring1, rows, lane); break;
+    case 2 * 4 + 2: bf16_rows<2, false, true, XOR>(tab, kind1, konst1, r0, r1, ds, bs, ring0, ring1, rows, lane); break;
+    case 2 * 4 + 3: bf16_rows<2, true, true, XOR>(tab, kind1, konst1, r0, r1, ds, bs, ring0, ring1, rows, lane); break;
+    case 4 * 4 + 0: bf16_rows<4, false, false, XOR>(tab, kind1, konst1, r0, r1, ds, bs, ring0, ring1, rows, lane); break;
+    case 4 * 4 + 2: bf16_rows<4, false, true, XOR>(tab, kind1, konst1, r0, r1, ds, bs, ring0, ring1, rows, lane); break;
+    case 8 * 4 + 0: bf16_rows<8, false, false, XOR>(tab, kind1, konst1, r0, r1, ds, bs, ring0, ring1, rows, lane); break;
+    default: bf16_rows<8, false, true, XOR>(tab, kind1, konst1, r0, r1, ds, bs, ring0, ring1, rows, lane); break;
+    }
+}
+
+// n_rings: 1, or 2 when some tensor's sign+mantissa field is table decoded too
+int launch_decode_bf16_s64(uint32_t n_rings, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev *single, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    const TensorDev s = single ? *single : TensorDev{};
+    const int use_single = single ? 1 : 0;
+    const uint32_t lds = kWavesPerGroup * 2048;
+    (void)n_rings;
+    if (xor_delta) hipLaunchKernelGGL((k_decode_bf16_s64<true>), dim3(n_work), dim3(256), lds, st, d_descs, d_work, s, use_single);
+    else hipLaunchKernelGGL((k_decode_bf16_s64<false>), dim3(n_work), dim3(256), lds, st, d_descs, d_work, s, use_single);
+    return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
 // FP8 with fewer than 64 lanes per chunk (small chunks such as K/V-cache pages): a wavefront
 // decodes 64/S chunks at once, one per S-lane group, optionally picked from an id list and
 // written densely.  Same per-lane work as k_decode_fp8; what differs is that every stream
