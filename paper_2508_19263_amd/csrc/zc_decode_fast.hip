@@ -243,9 +243,15 @@ __global__ __launch_bounds__(256) void k_decode_fp8(const TensorDev *descs, cons
 
 enum FieldKind : uint32_t { KIND_HUFF = 0, KIND_FLAT = 1, KIND_RAW = 2, KIND_CONST = 3 };
 
-// ring of this kernel: 512 words per wavefront and field, refilled 128 words (8 bytes per lane) at
-// a time; serviced every 2 refill steps (2 * 64 words <= one segment), which keeps the LDS
-// footprint small enough for 8 workgroups per CU
+// Stream ring of these kernels: RW words per wavefront and table-decoded field, refilled a quarter (SEG = RW / 4
+// words) at a time.  RW is 512 (8 bytes per lane and segment, serviced every two refill steps) when one field of a
+// chunk is table decoded and 256 (4 bytes per lane, serviced at every step) when two are, so that a workgroup's
+// rings take 8 KiB either way and eight workgroups fit the LDS of a compute unit.
+// A segment that has been asked for is written into the ring only when the next one is asked for, i.e. after a whole
+// segment has been consumed since: that is the time its load has to arrive.  Invariant when huff_ring_service is
+// called: words [wbase, wbase + RW) are in the ring except the newest SEG, which may still be in flight or in
+// registers; wpos - wbase < 2 * SEG, and at most SEG words are handed out before the next call, so every word asked
+// for lies below wbase + 3 * SEG: present.
 constexpr uint32_t kRing2Words = 512, kRing2Segment = 128;
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -254,6 +260,7 @@ struct HuffStream {
     uint32_t c;
     uint32_t wpos, wbase;  // words handed out so far; first word still in the ring
     uint32_t pslot;
+    uint32_t rw;           // ring words: 512 or 256 (the same in all lanes)
     bool pending;
     u32x2 pv;
     char *ring;            // this wavefront's ring in LDS
@@ -261,43 +268,47 @@ struct HuffStream {
     uint32_t lim[4];       // FieldTab::limit of lengths 12..15 (uniform): the code lengths beyond the lookup index
 };
 
-__device__ __forceinline__ void huff_open(HuffStream &H, const FieldTab &T, __amdgpu_buffer_rsrc_t rs, char *ring, uint32_t lane)
+__device__ __forceinline__ void huff_open(HuffStream &H, const FieldTab &T, __amdgpu_buffer_rsrc_t rs, char *ring, uint32_t lane, uint32_t rw = kRing2Words)
 {
-    H.rs = rs; H.ring = ring;
+    H.rs = rs; H.ring = ring; H.rw = rw;
 #pragma unroll
     for (int i = 0; i < 4; i++) H.lim[i] = uniform32(T.limit[kLutBits + 1 + i]);
+    const uint32_t seg_bytes = rw;                       // SEG words of 4 bytes = RW bytes
 #pragma unroll
-    for (uint32_t q = 0; q < kRing2Words / kRing2Segment; q++) {
-        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(lane * 8 + q * kRing2Segment * 4), 0, 0);
-        *reinterpret_cast<u32x2 *>(ring + q * kRing2Segment * 4 + lane * 8) = v;
+    for (uint32_t q = 0; q < 4; q++) {
+        if (rw == kRing2Words) *reinterpret_cast<u32x2 *>(ring + q * seg_bytes + lane * 8) = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(lane * 8 + q * seg_bytes), 0, 0);
+        else *reinterpret_cast<uint32_t *>(ring + q * seg_bytes + lane * 4) = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(lane * 4 + q * seg_bytes), 0, 0);
     }
     H.W = (uint64_t)(*reinterpret_cast<const uint32_t *>(ring + lane * 4)) << 32;   // step 0: word `lane`
     H.c = 32; H.wpos = 64; H.wbase = 0; H.pslot = 0; H.pending = false;
     H.pv = u32x2{0, 0};
 }
 
-// Invariant when this is called: words [wbase, wbase + 512) are in the ring except the newest
-// 128 while their load is in flight, and wpos - wbase < 256; at most 2 refill steps (128 words)
-// follow before the next call, so every word they can ask for is present.
 __device__ __forceinline__ void huff_ring_service(HuffStream &H, uint32_t lane)
 {
-    if (H.pending) {
-        *reinterpret_cast<u32x2 *>(H.ring + H.pslot * 4 + lane * 8) = H.pv;
-        H.pending = false;
-    }
-    if (H.wpos - H.wbase >= kRing2Segment) {
-        H.pv = __builtin_amdgcn_raw_buffer_load_b64(H.rs, (int)(lane * 8 + (H.wbase + kRing2Words) * 4), 0, 0);
-        H.pslot = H.wbase & (kRing2Words - 1);
-        H.wbase += kRing2Segment;
+    const uint32_t seg = H.rw / 4;
+    if (H.wpos - H.wbase >= seg) {                       // the oldest segment is used up: its place takes the segment after the newest
+        const bool wide = H.rw == kRing2Words;
+        if (H.pending) {
+            if (wide) *reinterpret_cast<u32x2 *>(H.ring + H.pslot * 4 + lane * 8) = H.pv;
+            else *reinterpret_cast<uint32_t *>(H.ring + H.pslot * 4 + lane * 4) = H.pv.x;
+        }
+        if (wide) H.pv = __builtin_amdgcn_raw_buffer_load_b64(H.rs, (int)(lane * 8 + (H.wbase + H.rw) * 4), 0, 0);
+        else H.pv.x = __builtin_amdgcn_raw_buffer_load_b32(H.rs, (int)(lane * 4 + (H.wbase + H.rw) * 4), 0, 0);
+        H.pslot = H.wbase & (H.rw - 1);
+        H.wbase += seg;
         H.pending = true;
     }
 }
+
+// is the ring serviced before refill step g of a run?  (every step with the small ring, every other one with the large)
+__device__ __forceinline__ bool huff_service_due(const HuffStream &H, int g) { return (g & 1) == 0 || H.rw != kRing2Words; }
 
 __device__ __forceinline__ void huff_refill(HuffStream &H)
 {
     const bool need = H.c >= 32;
     const uint64_t bm = __ballot(need);
-    const uint32_t w = *reinterpret_cast<const uint32_t *>(H.ring + ((prefix_count64(bm) * 4 + H.wpos * 4) & (kRing2Words * 4 - 1)));
+    const uint32_t w = *reinterpret_cast<const uint32_t *>(H.ring + ((prefix_count64(bm) * 4 + H.wpos * 4) & (H.rw * 4 - 1)));
     H.W = need ? ((H.W >> 32) | ((uint64_t)w << 32)) : H.W;
     H.c = need ? H.c - 32 : H.c;
     H.wpos += (uint32_t)__popcll(bm);
@@ -323,39 +334,51 @@ __device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uin
 {
     static_assert(!LONG || R == 2, "codes beyond the lookup index come with a refill period of 2 only; the second look relies on it");
     constexpr int PER64 = 64 / SB;
-    const uint32_t mask = T.mask;
+    const uint32_t mask2 = T.mask << 1;                  // entries are two bytes
     const char *lut = reinterpret_cast<const char *>(T.lut);
     uint32_t q[4] = {(uint32_t)P0, (uint32_t)(P0 >> 32), (uint32_t)P1, (uint32_t)(P1 >> 32)};
 #pragma unroll
     for (int g = 0; g < G / R; g++) {
-        if ((g & 1) == 0) huff_ring_service(H, lane);
+        if (huff_service_due(H, g)) huff_ring_service(H, lane);
         const uint32_t x0 = (uint32_t)(H.W >> H.c);
-        uint32_t x = x0, used = 0, e[R];
+        uint32_t e[R];
+        if (R == 2) {
+            // index from the window shifted left once: bits [1..] of (y >> n) are bits [0..] of (x >> n)
+            uint32_t y = x0 << 1;
+            e[0] = *reinterpret_cast<const uint16_t *>(lut + (y & mask2));
+            y >>= (e[0] & 31u);
+            e[1] = *reinterpret_cast<const uint16_t *>(lut + (y & mask2));
+        } else {
+            uint32_t x = x0;
 #pragma unroll
-        for (int j = 0; j < R; j++) {
-            e[j] = *reinterpret_cast<const uint16_t *>(lut + ((x & mask) << 1));
-            x >>= (e[j] & 31u);
+            for (int j = 0; j < R; j++) {
+                e[j] = *reinterpret_cast<const uint16_t *>(lut + ((x << 1) & mask2));
+                x >>= (e[j] & 31u);
+            }
         }
         if (LONG) {
-            // An empty entry stands for a code longer than the index; it shifts by nothing, so the entries after
-            // it are empty too and the last one tells.  Then the long code is searched for, and only what it
-            // spoiled is done again: the lookup of the symbol after it.
+            // An empty entry stands for a code longer than the index; it shifts by nothing, so the entry after it is
+            // empty too and the last one tells.  Then the long code is searched for, and only what it spoiled is
+            // done again: the lookup of the symbol after it.
             if (__any(e[R - 1] == 0)) {
-                x = x0;
+                uint32_t x = x0;
 #pragma unroll
                 for (int j = 0; j < R; j++) {
                     if (e[j] == 0) {
                         e[j] = long_code(T, H, x);
-                        if (j + 1 < R) e[j + 1] = *reinterpret_cast<const uint16_t *>(lut + (((x >> (e[j] & 31u)) & mask) << 1));
+                        if (j + 1 < R) e[j + 1] = *reinterpret_cast<const uint16_t *>(lut + (((x >> (e[j] & 31u)) << 1) & mask2));
                     }
                     x >>= (e[j] & 31u);
                 }
             }
         }
+        // lengths in bits 4..0 of the entries, symbols in byte 1: the low 7 bits of a sum are the sum of the lengths
+        // (at most 32 per period, and c was at most 32)
+        uint32_t c = H.c;
 #pragma unroll
         for (int j = 0; j < R; j++) {
             const int jj = g * R + j;
-            used += e[j];
+            c += e[j];
             constexpr int kPer32 = 32 / SB;
             const int word = jj / kPer32, pos = jj % kPer32;
             if (SB == 8) {
@@ -364,7 +387,7 @@ __device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uin
                 q[word] = __builtin_amdgcn_perm(e[j], q[word], sel);
             } else q[word] |= (e[j] >> 8) << (pos * SB);
         }
-        H.c += used & 0xFFu;           // the low bytes hold the lengths; their sum is at most 32
+        H.c = c & 0x7Fu;
         huff_refill(H);
     }
     P0 = (uint64_t)q[0] | ((uint64_t)q[1] << 32);
@@ -389,70 +412,6 @@ __device__ __forceinline__ void huff_run(HuffStream &H, const FieldTab &T, uint3
     // only refill periods of 2 can come with codes longer than the 11-bit index (longest code > 11 bits)
     if (period == 2 && T.lmax > (uint32_t)kLutBits) huff_run_r<SB, G, 2, true>(H, T, P0, P1, lane);
     else huff_run_l<SB, G, false>(H, T, period, P0, P1, lane);
-}
-
-// Both element fields table decoded with the same refill period: one run of each, symbol by symbol side by
-// side, so that the two lookups of a step are in flight together (each stream alone is one dependent chain of
-// lookup -> shift -> lookup, and the wavefront spends most of that chain waiting for LDS).
-template <int SB, int G, int R, bool LONG>
-__device__ __forceinline__ void huff_run_pair(HuffStream &A, const FieldTab &TA, HuffStream &B, const FieldTab &TB,
-                                              uint64_t &PA0, uint64_t &PA1, uint64_t &PB0, uint64_t &PB1, uint32_t lane)
-{
-    static_assert(!LONG || R == 2, "codes beyond the lookup index come with a refill period of 2 only; the second look relies on it");
-    constexpr int PER64 = 64 / SB;
-    constexpr int kPer32 = 32 / SB;
-    const uint32_t ma = TA.mask, mb = TB.mask;
-    const char *la = reinterpret_cast<const char *>(TA.lut), *lb = reinterpret_cast<const char *>(TB.lut);
-    uint32_t qa[4] = {0, 0, 0, 0}, qb[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int g = 0; g < G / R; g++) {
-        if ((g & 1) == 0) { huff_ring_service(A, lane); huff_ring_service(B, lane); }
-        const uint32_t xa0 = (uint32_t)(A.W >> A.c), xb0 = (uint32_t)(B.W >> B.c);
-        uint32_t xa = xa0, xb = xb0, ua = 0, ub = 0, ea[R], eb[R];
-#pragma unroll
-        for (int j = 0; j < R; j++) {
-            ea[j] = *reinterpret_cast<const uint16_t *>(la + ((xa & ma) << 1));
-            eb[j] = *reinterpret_cast<const uint16_t *>(lb + ((xb & mb) << 1));
-            xa >>= (ea[j] & 31u); xb >>= (eb[j] & 31u);
-        }
-        if (LONG) {
-            // as in huff_run_r: one test per step for both fields, the step done again with the search when it hits
-            if (__any(ea[R - 1] == 0 || eb[R - 1] == 0)) {
-                // only what a long code spoiled is done again: the lookup of the symbol after it
-                xa = xa0; xb = xb0;
-#pragma unroll
-                for (int j = 0; j < R; j++) {
-                    if (ea[j] == 0) {
-                        ea[j] = long_code(TA, A, xa);
-                        if (j + 1 < R) ea[j + 1] = *reinterpret_cast<const uint16_t *>(la + (((xa >> (ea[j] & 31u)) & ma) << 1));
-                    }
-                    if (eb[j] == 0) {
-                        eb[j] = long_code(TB, B, xb);
-                        if (j + 1 < R) eb[j + 1] = *reinterpret_cast<const uint16_t *>(lb + (((xb >> (eb[j] & 31u)) & mb) << 1));
-                    }
-                    xa >>= (ea[j] & 31u); xb >>= (eb[j] & 31u);
-                }
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < R; j++) {
-            const int jj = g * R + j;
-            ua += ea[j]; ub += eb[j];
-            const int word = jj / kPer32, pos = jj % kPer32;
-            if (SB == 8) {
-                const uint32_t sel = pos == 0 ? 0x03020105u : pos == 1 ? 0x03020500u : pos == 2 ? 0x03050100u : 0x05020100u;
-                qa[word] = __builtin_amdgcn_perm(ea[j], qa[word], sel);
-                qb[word] = __builtin_amdgcn_perm(eb[j], qb[word], sel);
-            } else {
-                qa[word] |= (ea[j] >> 8) << (pos * SB);
-                qb[word] |= (eb[j] >> 8) << (pos * SB);
-            }
-        }
-        A.c += ua & 0xFFu; B.c += ub & 0xFFu;
-        huff_refill(A); huff_refill(B);
-    }
-    PA0 = (uint64_t)qa[0] | ((uint64_t)qa[1] << 32); PB0 = (uint64_t)qb[0] | ((uint64_t)qb[1] << 32);
-    if (G > PER64) { PA1 = (uint64_t)qa[2] | ((uint64_t)qa[3] << 32); PB1 = (uint64_t)qb[2] | ((uint64_t)qb[3] << 32); }
 }
 
 // one field of one run when it is not table decoded.  words_per_run = G*SB/32.
@@ -530,38 +489,25 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     const uint32_t p0 = uniform32(d.period[0]), p1 = uniform32(d.period[1]);
     const uint64_t K0 = splat(uniform32(d.konst[0]), F_::SB), K1 = splat(uniform32(d.konst[1]), F_::SB);
 
-    // rings: field 0 uses ring 0; field 1 uses ring 1 if field 0 is table decoded too, else ring 0
-    char *ring_base = reinterpret_cast<char *>(rings) + wave * (kRing2Words * 4);
-    char *ring0 = ring_base, *ring1 = ring_base + (kind[0] == KIND_HUFF ? kWavesPerGroup * kRing2Words * 4 : 0);
+    // rings: the workgroup has 8 KiB.  One table-decoded element field: 512 words per wavefront; two: 256 words per
+    // wavefront and field, field 0's in the first half.  The scale field, decoded after the elements, takes over the
+    // wavefront's first ring as it is (the other wavefronts may still be using theirs).
+    const bool two = kind[0] == KIND_HUFF && kind[1] == KIND_HUFF;
+    const uint32_t rw = two ? 256u : kRing2Words;
+    char *ring0 = reinterpret_cast<char *>(rings) + wave * (rw * 4), *ring1 = ring0 + (two ? kWavesPerGroup * 256 * 4 : 0);
     HuffStream H0, H1;
-    if (!SPLIT && kind[0] == KIND_HUFF) huff_open(H0, tab[0], r0, ring0, lane);
-    if (!SPLIT && kind[1] == KIND_HUFF) huff_open(H1, tab[1], r1, ring1, lane);
+    if (!SPLIT && kind[0] == KIND_HUFF) huff_open(H0, tab[0], r0, ring0, lane, rw);
+    if (!SPLIT && kind[1] == KIND_HUFF) huff_open(H1, tab[1], r1, ring1, lane, rw);
 
-    // both fields table decoded on the same refill period: 1 = period 2 with codes beyond the lookup index in
-    // either table (a table without them has no empty entry, so the check never fires for it), 2 = period 2,
-    // 3 = period 4 (codes of at most 8 bits)
-    uint32_t pair = 0;
-    // built for BF16 only, where two coded fields occur (checkpoint deltas); in the other kernels the extra code
-    // costs the paths they do use 3 - 10 %
-    constexpr bool kPairs = FMT == ZC_FMT_BF16 && !SPLIT;
-    if (kPairs && kind[0] == KIND_HUFF && kind[1] == KIND_HUFF && p0 == p1) {
-        const bool any_long = uniform32(tab[0].lmax) > (uint32_t)kLutBits || uniform32(tab[1].lmax) > (uint32_t)kLutBits;
-        pair = p0 == 2 ? (any_long ? 1u : 2u) : p0 == 4 ? 3u : 0u;
-    }
     const uint32_t rows = cb / 1024;                          // 64 lanes x 16 bytes per row
     if (split && (kind[0] == KIND_HUFF || kind[1] == KIND_HUFF)) return;          // the host never asks for this
     const uint32_t row_begin = split ? wave * rows / kWavesPerGroup : 0u, row_end = split ? (wave + 1) * rows / kWavesPerGroup : rows;
     for (uint32_t row = row_begin; row < row_end; row++) {
         uint64_t P0 = 0, P1 = 0, Q0 = 0, Q1 = 0;       // Q: symbols 8..15 of a run of 16 symbols of 8 bits
-        if (kPairs && pair == 1) huff_run_pair<F_::SB, F_::G, 2, true>(H0, tab[0], H1, tab[1], P0, Q0, P1, Q1, lane);
-        else if (kPairs && pair == 2) huff_run_pair<F_::SB, F_::G, 2, false>(H0, tab[0], H1, tab[1], P0, Q0, P1, Q1, lane);
-        else if (kPairs && pair == 3) huff_run_pair<F_::SB, F_::G, 4, false>(H0, tab[0], H1, tab[1], P0, Q0, P1, Q1, lane);
-        else {
-            if (!SPLIT && kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, Q0, lane);
-            else plain_run<F_::SB, F_::G>(kind[0], r0, row, lane, K0, P0, Q0);
-            if (!SPLIT && kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, Q1, lane);
-            else plain_run<F_::SB, F_::G>(kind[1], r1, row, lane, K1, P1, Q1);
-        }
+        if (!SPLIT && kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, Q0, lane);
+        else plain_run<F_::SB, F_::G>(kind[0], r0, row, lane, K0, P0, Q0);
+        if (!SPLIT && kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, Q1, lane);
+        else plain_run<F_::SB, F_::G>(kind[1], r1, row, lane, K1, P1, Q1);
         const uint4 j = join_run4<FMT>(P0, Q0, P1, Q1);
         u32x4 v = {j.x, j.y, j.z, j.w};
         if (XOR) v ^= __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)(row * 1024), 0);
@@ -577,7 +523,7 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
         const uint32_t p2 = uniform32(d.period[F2]);
         const uint64_t K2 = splat(uniform32(d.konst[F2]), 8);
         HuffStream H2;
-        if (kind[F2] == KIND_HUFF) huff_open(H2, tab[F2], r2, ring_base, lane);      // the element rings are free again
+        if (kind[F2] == KIND_HUFF) huff_open(H2, tab[F2], r2, ring0, lane, rw);      // this wavefront's first element ring is free again
         for (uint32_t row = 0; row < n_sc / 1024; row++) {
             uint64_t P0 = 0, P1 = 0;
             if (kind[F2] == KIND_HUFF) huff_run<8, 16>(H2, tab[F2], p2, P0, P1, lane);
@@ -608,7 +554,8 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split
     hipStream_t st = (hipStream_t)stream;
     const TensorDev s = single ? *single : TensorDev{};
     const int use_single = single ? 1 : 0;
-    const uint32_t lds = (n_rings >= 2 ? 2u : 1u) * kWavesPerGroup * kRing2Words * 4;
+    const uint32_t lds = kWavesPerGroup * kRing2Words * 4;          // 8 KiB whatever the number of table-decoded fields
+    (void)n_rings;
     switch (fmt) {
     case ZC_FMT_BF16: return launch_s64_x<ZC_FMT_BF16>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
     case ZC_FMT_FP8_E4M3: return launch_s64_x<ZC_FMT_FP8_E4M3>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
