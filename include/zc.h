@@ -320,6 +320,15 @@ zc_status zc_stats(const void *d_src, uint64_t n_elems, const zc_params *params,
                    const void *d_xor_base, const void *d_scales, zc_stats_out *out,
                    void *d_ws, uint64_t ws_bytes, void *stream);
 
+/* Measurement aid, not part of the method: a plain copy of `bytes` bytes (a multiple of 16) from d_src to d_dst
+ * (device, 16-byte aligned, not overlapping), 16 bytes per lane.  chunk_bytes == 0: linear through memory, the
+ * best this machine gives a kernel that only moves bytes.  chunk_bytes != 0 (a multiple of 1024 that divides
+ * `bytes`): one wavefront per chunk of that size, each walking through its own chunk 1 KiB at a time, which is how
+ * the 64-lane decoders and encoders touch memory: the ceiling of that access pattern.  Queued on the stream, never
+ * waits.  Benchmarks report the codec's traffic next to these, and counter runs use the linear copy as the kernel
+ * of known traffic. */
+zc_status zc_copy_reference(const void *d_src, void *d_dst, uint64_t bytes, uint32_t chunk_bytes, void *stream);
+
 /* Length-limited canonical Huffman code for one histogram (host only; exposed so that the
  * code construction can be checked without a GPU).  hist: `alphabet` counts;
  * len_out/code_out: `alphabet` entries.  Returns ZC_ERR_INVALID_ARG if 2^limit < number of

@@ -190,6 +190,15 @@ zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *
 
 extern "C" {
 
+zc_status zc_copy_reference(const void *d_src, void *d_dst, uint64_t bytes, uint32_t chunk_bytes, void *stream)
+{
+    if (!d_src || !d_dst || !aligned16(d_src) || !aligned16(d_dst) || bytes % 16) return ZC_ERR_INVALID_ARG;
+    if (chunk_bytes && (chunk_bytes % 1024 || bytes % chunk_bytes || bytes / chunk_bytes > 0x7FFFFFFFull)) return ZC_ERR_INVALID_ARG;
+    if (chunk_bytes) LAUNCH_TRY(launch_copy_chunked(d_src, d_dst, bytes, chunk_bytes, stream));
+    else LAUNCH_TRY(launch_copy(d_src, d_dst, bytes, stream));
+    return ZC_OK;
+}
+
 zc_status zc_read_info(const void *d_comp, uint64_t comp_bytes, int check_index_too, zc_info *out, void *stream)
 {
     if (!d_comp || !out) return ZC_ERR_INVALID_ARG;

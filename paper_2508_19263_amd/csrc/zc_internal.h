@@ -120,6 +120,8 @@ int launch_codes(TensorDev *d_descs, uint32_t n_tensors, const uint64_t *d_hist,
 int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                 int scales_view, uint64_t *d_hist, void *stream);
 int launch_zero(uint64_t *d_words, uint64_t n_words, void *stream);
+int launch_copy(const void *d_src, void *d_dst, uint64_t bytes, void *stream);
+int launch_copy_chunked(const void *d_src, void *d_dst, uint64_t bytes, uint32_t chunk_bytes, void *stream);
 // skip_routes: bit r set = leave tensors of route r to the specialised kernel that takes their whole chunks
 // whole: 0 = any chunks, 1 = up to four whole 64-lane chunks per work item, 2 = one such chunk per work item, shared
 // by the workgroup's four wavefronts

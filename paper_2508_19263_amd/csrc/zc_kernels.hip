@@ -531,6 +531,56 @@ int launch_zero(uint64_t *d_words, uint64_t n_words, void *stream)
     return (int)hipGetLastError();
 }
 
+// Plain copy, linear through memory, 16 bytes per thread and a workgroup per 4 KiB: the launch shape that moves the
+// most bytes per second on this machine (workgroups that loop over the buffer, and hipMemcpy, reach 75 - 85 % of
+// it).  The yardstick next to which the codec's throughput is reported, and the kernel of known traffic that scales
+// the hardware's byte counters.
+__global__ __launch_bounds__(256) void k_copy(const uint4 *src, uint4 *dst, uint64_t n16)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
+}
+
+// The same bytes moved the way the 64-lane decoders and encoders move them: one wavefront per chunk, walking through
+// its own chunk 1 KiB (16 bytes per lane) at a time, four loads in flight, thousands of chunks at once.  What this
+// reaches is the ceiling of every kernel here that streams one chunk per wavefront.
+__global__ __launch_bounds__(256) void k_copy_chunked(const uint8_t *src, uint8_t *dst, uint64_t n_chunks, uint32_t chunk_bytes)
+{
+    const uint64_t chunk = (uint64_t)blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
+    if (chunk >= n_chunks) return;
+    const uint32_t lane = threadIdx.x & 63, rows = chunk_bytes / 1024;
+    const uint4 *s = reinterpret_cast<const uint4 *>(src + chunk * chunk_bytes) + lane;
+    uint4 *d = reinterpret_cast<uint4 *>(dst + chunk * chunk_bytes) + lane;
+    uint32_t row = 0;
+    for (; row + 4 <= rows; row += 4) {
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; k++) v[k] = s[(uint64_t)(row + k) * 64];
+#pragma unroll
+        for (int k = 0; k < 4; k++) d[(uint64_t)(row + k) * 64] = v[k];
+    }
+    for (; row < rows; row++) d[(uint64_t)row * 64] = s[(uint64_t)row * 64];
+}
+
+int launch_copy_chunked(const void *d_src, void *d_dst, uint64_t bytes, uint32_t chunk_bytes, void *stream)
+{
+    const uint64_t n_chunks = bytes / chunk_bytes;
+    if (n_chunks == 0) return 0;
+    hipLaunchKernelGGL(k_copy_chunked, dim3((uint32_t)((n_chunks + kWavesPerGroup - 1) / kWavesPerGroup)), dim3(256), 0, (hipStream_t)stream,
+                       (const uint8_t *)d_src, (uint8_t *)d_dst, n_chunks, chunk_bytes);
+    return (int)hipGetLastError();
+}
+
+int launch_copy(const void *d_src, void *d_dst, uint64_t bytes, void *stream)
+{
+    const uint64_t n16 = bytes / 16;
+    if (n16 == 0) return 0;
+    const uint64_t blocks = (n16 + 255) / 256;
+    if (blocks > 0x7FFFFFFFull) return (int)hipErrorInvalidValue;
+    hipLaunchKernelGGL(k_copy, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream, (const uint4 *)d_src, (uint4 *)d_dst, n16);
+    return (int)hipGetLastError();
+}
+
 // ------------------------------------------------------------------------- decoder
 struct DecField {
     uint32_t lo, hi;       // 64 stream bits, next unread bit = bit c of {hi, lo}

@@ -24,7 +24,7 @@ EXPORTS = ["zc_compress_bound", "zc_workspace_bytes", "zc_compress", "zc_compres
            "zc_decompress", "zc_decompress_chunks", "zc_decompress_batch", "zc_decompress_batch_plan",
            "zc_decompress_batch_run", "zc_stats", "zc_build_code", "zc_train_code", "zc_compress_with_code",
            "zc_compress_batch_with_code", "zc_compress_batch_with_code_async", "zc_compress_batch_async", "zc_code_stale",
-           "zc_validate_container", "zc_release_host_buffers", "zc_compress_noalloc", "zc_status_string"]
+           "zc_validate_container", "zc_release_host_buffers", "zc_compress_noalloc", "zc_copy_reference", "zc_status_string"]
 
 
 class Params(C.Structure):
@@ -98,6 +98,8 @@ def lib():
         L.zc_compress_batch.argtypes = [C.POINTER(Tensor), u32, C.POINTER(Params), vp, u64, vp]
         L.zc_compress_noalloc.restype = C.c_int
         L.zc_compress_noalloc.argtypes = [vp, u64, C.POINTER(Params), vp, vp, vp, u64, vp]
+        L.zc_copy_reference.restype = C.c_int
+        L.zc_copy_reference.argtypes = [vp, vp, u64, u32, vp]
         L.zc_code_stale.restype = C.c_int
         L.zc_code_stale.argtypes = [C.POINTER(Info), C.POINTER(Info), C.c_double]
         L.zc_train_code.restype = C.c_int
@@ -265,6 +267,12 @@ def validate_container(host_bytes, check_index=True, container_bytes=None):
     total = len(host_bytes) if container_bytes is None else container_bytes
     _check(lib().zc_validate_container(buf, len(host_bytes), total, 1 if check_index else 0, C.byref(info)), "zc_validate_container")
     return info
+
+
+def copy_reference(src, dst, chunk_bytes=0):
+    """Queue the library's plain copy kernel (the bandwidth yardstick) from src to dst, both CUDA tensors of equal size;
+    chunk_bytes != 0: one wavefront per chunk, as the 64-lane codec kernels walk through memory."""
+    _check(lib().zc_copy_reference(_ptr(src), _ptr(dst), src.numel() * src.element_size(), chunk_bytes, _stream()), "zc_copy_reference")
 
 
 def release_host_buffers():
