@@ -305,7 +305,8 @@ typedef struct {
     uint32_t n_fast_work, n_work;               /* work items of the specialised / generic kernel */
     uint32_t fast_kernel;                       /* 0 none, 1 FP8 specialised, 2 64-lane full-chunk kernel, 3 FP8 small chunks,
                                                    4 = 2 with every chunk shared by four wavefronts (no table-decoded element field),
-                                                   5 BF16 small chunks, 6 BF16 with 64 lanes (table-decoded exponents) */
+                                                   5 BF16 small chunks, 6 BF16 with 64 lanes (table-decoded exponents),
+                                                   7 FP8 E5M2 with 64 lanes (table-decoded exponents, flat 3-bit sign+mantissa code) */
     uint32_t fast_exp_kind, fast_sm_kind, n_rings /* kernels 3, 5: slots per workgroup */, xor_delta;
     uint32_t scattered;                         /* some tensor decodes an id list */
     uint64_t fast_work_offset, work_offset;     /* byte offsets of the two work lists in d_ws */

@@ -729,8 +729,8 @@ __device__ __forceinline__ void bf16_rows(const FieldTab *tab, uint32_t kind1, u
     const uint32_t ma2 = uniform32(tab[0].mask) << 1, mb2 = PAIR ? uniform32(tab[1].mask) << 1 : 0u;
     const uint32_t k1 = konst1 | (konst1 << 8) | (konst1 << 16) | (konst1 << 24);
     // What a row takes from global memory besides its stream words (plain sign+mantissa bytes, the base of a delta)
-    // is asked for one row ahead, so that the loads are in flight while the row before is decoded.  A row past the
-    // end is outside the buffer resources: such loads return zeros and touch nothing.
+    // is asked for one row ahead, so that the loads are in flight while the row before is decoded.  Row offsets go
+    // into the scalar operand of the loads, which the hardware does not range check, so they never leave the chunk.
     auto fetch_m = [&](uint32_t row, uint32_t m[2]) {
         m[0] = k1; m[1] = k1;
         if (kind1 == KIND_FLAT) {
@@ -749,8 +749,9 @@ __device__ __forceinline__ void bf16_rows(const FieldTab *tab, uint32_t kind1, u
         uint32_t ea[4], mb[4];
         const uint32_t m[2] = {m_next[0], m_next[1]};
         const u32x4 base = base_next;
-        if (!PAIR) fetch_m(row + 1, m_next);
-        if (XOR) base_next = __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)((row + 1) * 1024), 0);
+        const uint32_t ahead = row + 1 < rows ? row + 1 : row;      // the row after the last is the last again
+        if (!PAIR) fetch_m(ahead, m_next);
+        if (XOR) base_next = __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)(ahead * 1024), 0);
 #pragma unroll
         for (int g = 0; g < 8 / R; g++) {
             if (PAIR || (g & 1) == 0) { ring_service<RW>(A, lane); if (PAIR) ring_service<RW>(B, lane); }
@@ -841,6 +842,120 @@ int launch_decode_bf16_s64(uint32_t n_rings, bool xor_delta, const TensorDev *d_
     (void)n_rings;
     if (xor_delta) hipLaunchKernelGGL((k_decode_bf16_s64<true>), dim3(n_work), dim3(256), lds, st, d_descs, d_work, s, use_single);
     else hipLaunchKernelGGL((k_decode_bf16_s64<false>), dim3(n_work), dim3(256), lds, st, d_descs, d_work, s, use_single);
+    return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// FP8 E5M2 (s eeeee mm) with 64 lanes per chunk and whole chunks, in the shape weights take: the exponent field
+// table decoded (16 symbols per run), the sign+mantissa field coded with the flat 3-bit code that its eight nearly
+// equally likely values get (lengths 3 for the values 0..7, nothing else in the table).  The exponent stream goes
+// through the ring and huff_run_r as in k_decode_s64, with table entries that hold the exponent at its place in the
+// output byte.  The sign+mantissa stream needs no table and no refill logic: every lane takes 24 bits per refill
+// step, so all lanes ask for words at the same steps, the stream is rounds of 64 words in lane order, and a lane's
+// bits are its words of every round one after the other: a row (16 values, 48 bits) starts at bit 48 * row of
+// them.  What a row takes from global memory is asked for one row ahead.
+
+// 32-bit word whose bytes are the next four 3-bit codes of v (first code in bits 2..0): a code is s, m1, m0 with the
+// sign first in stream order, a byte of the result is s << 7 | m1 << 1 | m0
+__device__ __forceinline__ uint32_t e5m2_sm_bytes(uint32_t v)
+{
+    const uint32_t a = (v & 0x7u) | ((v & 0x38u) << 5) | ((v & 0x1C0u) << 10) | ((v & 0xE00u) << 15);      // one code per byte
+    return ((a << 7) & 0x80808080u) | (a & 0x02020202u) | ((a >> 2) & 0x01010101u);
+}
+
+template <int R, bool LONG, bool XOR>
+__device__ __forceinline__ void e5m2_rows(const FieldTab &T, __amdgpu_buffer_rsrc_t r0, __amdgpu_buffer_rsrc_t r1, __amdgpu_buffer_rsrc_t ds,
+                                          __amdgpu_buffer_rsrc_t bs, char *ring, uint32_t rows, uint32_t lane)
+{
+    HuffStream H;
+    huff_open(H, T, r0, ring, lane);
+    // sign+mantissa words of the lane: word q of the lane is word 64 * q + lane of the stream; two rows take three
+    auto fetch_sm = [&](uint32_t pair, uint32_t w[3]) {
+#pragma unroll
+        for (int k = 0; k < 3; k++) w[k] = __builtin_amdgcn_raw_buffer_load_b32(r1, (int)(lane * 4 + (pair * 3 + k) * 256), 0, 0);   // range checked
+    };
+    uint32_t sm_next[3];
+    u32x4 base_next = {0, 0, 0, 0};
+    fetch_sm(0, sm_next);
+    if (XOR) base_next = __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), 0, 0);
+    uint32_t sm[3] = {0, 0, 0};
+    for (uint32_t row = 0; row < rows; row++) {
+        if ((row & 1) == 0) {
+            sm[0] = sm_next[0]; sm[1] = sm_next[1]; sm[2] = sm_next[2];
+            fetch_sm(row / 2 + 1, sm_next);                     // past the stream's end the loads return zeros (checked offsets)
+        }
+        const u32x4 base = base_next;
+        // (the scalar offset of a buffer access is not range checked: the row after the last is the last again)
+        if (XOR) base_next = __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)((row + 1 < rows ? row + 1 : row) * 1024), 0);
+        uint64_t P = 0, Q = 0;
+        huff_run_r<8, 16, R, LONG>(H, T, P, Q, lane);          // bytes: exponent << 2
+        // the row's 48 sign+mantissa bits: an even row starts at bit 0 of the pair's three words, an odd one at bit 48
+        const uint32_t lo = (row & 1) ? __builtin_amdgcn_alignbit(sm[2], sm[1], 16) : sm[0];
+        const uint32_t hi = (row & 1) ? sm[2] >> 16 : sm[1];
+        u32x4 v;
+        v[0] = e5m2_sm_bytes(lo) | (uint32_t)P;
+        v[1] = e5m2_sm_bytes(lo >> 12) | (uint32_t)(P >> 32);
+        v[2] = e5m2_sm_bytes(__builtin_amdgcn_alignbit(hi, lo, 24)) | (uint32_t)Q;
+        v[3] = e5m2_sm_bytes(hi >> 4) | (uint32_t)(Q >> 32);
+        if (XOR) v ^= base;
+        __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
+    }
+}
+
+template <bool XOR>
+__global__ __launch_bounds__(256) void k_decode_e5m2(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t rings[kWavesPerGroup * kRing2Words];
+    __shared__ FieldTab tab;
+    __shared__ TensorDev dsh;
+    __shared__ uint32_t flat3;
+    WorkItem it;
+    if (use_single) { it.tensor = 0; it.first = blockIdx.x * kWavesPerGroup; }
+    else it = work[blockIdx.x];
+    if (threadIdx.x == 0) { dsh = use_single ? single : descs[it.tensor]; flat3 = 1; }
+    __syncthreads();
+    const TensorDev &d = dsh;
+    const uint32_t p0 = uniform32(d.period[0]);
+    // the sign+mantissa table must be the flat 3-bit code
+    if (d.comp[d.table_off[1] + threadIdx.x] != (threadIdx.x < 8 ? 3 : 0)) flat3 = 0;
+    build_field_tab(tab, d.comp + d.table_off[0], 256, d.lmax[0]);
+    if (uniform32(d.kind[0]) != KIND_HUFF || uniform32(d.mode[1]) != ZC_MODE_HUFF || !flat3 || (p0 != 2 && p0 != 4 && p0 != 8)) return;      // whole workgroup; the host never asks for this
+    // entries: the symbol byte becomes the exponent at its place in the output byte
+    for (uint32_t i = threadIdx.x; i <= tab.mask; i += blockDim.x) { const uint32_t e = tab.lut[i]; tab.lut[i] = (uint16_t)((e & 0xFFu) | ((e >> 8) << 10)); }
+    if (threadIdx.x < 32) tab.sorted[threadIdx.x] = (uint8_t)(tab.sorted[threadIdx.x] << 2);       // what a code beyond the index resolves to (at most 32 exponents are coded)
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t chunk = uniform32(it.first + wave);
+    const uint32_t cb = uniform32(d.chunk_bytes);
+    const uint32_t n_full = (uint32_t)(uniform64(d.n_elems) / cb);
+    if (chunk >= n_full) return;
+    const uint8_t *comp = reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.comp));
+    const uint64_t payload = uniform64(d.payload_off), total = uniform64(d.total_bytes);
+    const uint8_t *sp[2];
+    uint32_t sb[2];
+    for (int f = 0; f < 2; f++)
+        if (!stream_range(d, comp, f, chunk, payload, total, sp[f], sb[f])) return;      // damaged index: leave the chunk alone
+    if (sb[1] < cb / 8 * 3) return;                         // a flat 3-bit stream of this chunk cannot be shorter
+    const __amdgpu_buffer_rsrc_t r0 = make_rsrc(sp[0], sb[0]), r1 = make_rsrc(sp[1], sb[1]);
+    const __amdgpu_buffer_rsrc_t ds = make_rsrc(reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.dst)) + (uint64_t)chunk * cb, cb);
+    const __amdgpu_buffer_rsrc_t bs = make_rsrc(XOR ? reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.base)) + (uint64_t)chunk * cb : comp, XOR ? cb : 0);
+    char *ring = reinterpret_cast<char *>(rings) + wave * (kRing2Words * 4);
+    const uint32_t rows = cb / 1024;
+    const bool any_long = uniform32(tab.lmax) > (uint32_t)kLutBits;
+    if (p0 == 2 && any_long) e5m2_rows<2, true, XOR>(tab, r0, r1, ds, bs, ring, rows, lane);
+    else if (p0 == 2) e5m2_rows<2, false, XOR>(tab, r0, r1, ds, bs, ring, rows, lane);
+    else if (p0 == 4) e5m2_rows<4, false, XOR>(tab, r0, r1, ds, bs, ring, rows, lane);
+    else e5m2_rows<8, false, XOR>(tab, r0, r1, ds, bs, ring, rows, lane);
+}
+
+int launch_decode_e5m2(bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev *single, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    const TensorDev s = single ? *single : TensorDev{};
+    const int use_single = single ? 1 : 0;
+    if (xor_delta) hipLaunchKernelGGL((k_decode_e5m2<true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single);
+    else hipLaunchKernelGGL((k_decode_e5m2<false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single);
     return (int)hipGetLastError();
 }
 

@@ -56,6 +56,18 @@ uint32_t bf16_s64_rings(const zc_info &info)
     return 1;
 }
 
+// Can the E5M2 kernel decode this container's full chunks?  64 lanes, chunks of whole rows, exponent field table
+// decoded on a refill period of 2, 4 or 8, sign+mantissa field coded with the flat 3-bit code over the values 0..7.
+bool e5m2_s64_ok(const zc_info &info)
+{
+    if (info.format != ZC_FMT_FP8_E5M2 || !s64_rings(info)) return false;
+    const TensorDev d = make_desc(info);
+    if (d.kind[0] != 0 || (d.period[0] != 2 && d.period[0] != 4 && d.period[0] != 8)) return false;
+    if (info.mode[1] != ZC_MODE_HUFF) return false;
+    for (int v = 0; v < 256; v++) if (info.code_len[1][v] != (v < 8 ? 3 : 0)) return false;
+    return true;
+}
+
 // Are both element fields stored plainly (flat code, raw, constant)?  Then the rows of a chunk do not depend on
 // each other and the 64-lane kernel may share a chunk among the four wavefronts of a workgroup.
 bool s64_split_ok(const zc_info &info)
@@ -170,6 +182,7 @@ zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *
         const uint32_t n_full = (uint32_t)(info.n_elems / ((uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(info.format)));
         const uint32_t n_fast = (n_full + kWavesPerGroup - 1) / kWavesPerGroup;
         if (fk.ok) LAUNCH_TRY(launch_decode_fp8_fast(fk.exp_kind, fk.sm_kind, info.xor_delta != 0, nullptr, nullptr, n_fast, &d, stream));
+        else if (e5m2_s64_ok(info)) LAUNCH_TRY(launch_decode_e5m2(info.xor_delta != 0, nullptr, nullptr, n_fast, &d, stream));
         else if (bf16_s64_rings(info)) LAUNCH_TRY(launch_decode_bf16_s64(bf16_s64_rings(info), info.xor_delta != 0, nullptr, nullptr, n_fast, &d, stream));
         else {
             const bool split = s64_split_ok(info);
@@ -271,6 +284,8 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
     }
     bool split = rings != 0;
     for (uint32_t t = 0; t < n_tensors && split; t++) split = s64_split_ok(tensors[t].info);
+    bool e5m2 = rings != 0;
+    for (uint32_t t = 0; t < n_tensors && e5m2; t++) e5m2 = e5m2_s64_ok(tensors[t].info);
     // BF16 sets whose every tensor has the shape of the BF16 kernel go there instead
     uint32_t bf16_rings = rings ? 1 : 0;
     for (uint32_t t = 0; t < n_tensors && bf16_rings; t++) {
@@ -319,7 +334,7 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
     plan->format = fmt; plan->streams = S; plan->n_tensors = n_tensors;
     plan->n_fast_work = (uint32_t)fast_work.size(); plan->n_work = (uint32_t)work.size();
     plan->fast_exp_kind = (uint32_t)fk.exp_kind; plan->fast_sm_kind = (uint32_t)fk.sm_kind; plan->xor_delta = tensors[0].info.xor_delta;
-    plan->fast_kernel = fk.ok ? 1u : (rings ? (bf16_rings ? 6u : split ? 4u : 2u) : (sub ? (fmt == ZC_FMT_BF16 ? 5u : 3u) : 0u));
+    plan->fast_kernel = fk.ok ? 1u : (rings ? (e5m2 ? 7u : bf16_rings ? 6u : split ? 4u : 2u) : (sub ? (fmt == ZC_FMT_BF16 ? 5u : 3u) : 0u));
     plan->n_rings = sub ? spg : (bf16_rings ? bf16_rings : rings);
     plan->scattered = 0;
     for (uint32_t t = 0; t < n_tensors; t++) if (tensors[t].d_chunk_ids) plan->scattered = 1;
@@ -342,6 +357,8 @@ zc_status zc_decompress_batch_run(const zc_batch_plan *plan, const void *d_ws, v
     else if (plan->n_fast_work && plan->fast_kernel == 6)
         LAUNCH_TRY(launch_decode_bf16_s64(plan->n_rings, plan->xor_delta != 0, (const TensorDev *)ws,
                                           (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, stream));
+    else if (plan->n_fast_work && plan->fast_kernel == 7)
+        LAUNCH_TRY(launch_decode_e5m2(plan->xor_delta != 0, (const TensorDev *)ws, (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, stream));
     else if (plan->n_fast_work && plan->fast_kernel == 3)
         LAUNCH_TRY(launch_decode_fp8_sub(plan->streams, plan->xor_delta != 0, plan->scattered != 0, (const TensorDev *)ws,
                                          (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, plan->n_rings, stream));

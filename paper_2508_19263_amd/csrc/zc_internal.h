@@ -150,6 +150,9 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split
 // decoded on the same period, flat coded, raw or constant (zc_decode_fast.hip)
 int launch_decode_bf16_s64(uint32_t n_rings, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                            const TensorDev *single, void *stream);
+// FP8 E5M2, 64 lanes per chunk, full chunks, exponent field table decoded (refill period 2, 4 or 8), sign+mantissa field
+// coded with the flat 3-bit code over the values 0..7 (zc_decode_fast.hip)
+int launch_decode_e5m2(bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev *single, void *stream);
 // FP8, 64 lanes, full chunks, exponent codes <= 8 bits, sign+mantissa flat or raw (zc_encode_fast.hip)
 int launch_sizes_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream);
 // FP8, 64 lanes, chunks of kHistBlockBytes: the histogram pass that also counts exponents per chunk lane (one work

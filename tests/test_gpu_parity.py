@@ -1153,6 +1153,58 @@ def test_fp8_e5m2():
     check_case(F, c.numel(), 16384, 64, data=(c, None), tag="e5m2-constant")
 
 
+def test_fp8_e5m2_weight_shape_kernel():
+    # E5M2 weights: exponent field table decoded, sign+mantissa field with the flat 3-bit code over 0..7, which the E5M2
+    # kernel decodes without a table.  Every refill period of the exponent field (2 with and without codes beyond the
+    # lookup index, 4, 8), chunks of an odd and an even number of rows, a delta, a ragged tail, the batch route.
+    F = zc.FMT_FP8_E5M2
+    rng = np.random.default_rng(53)
+
+    def e5m2_like(n, n_exp, geometric):
+        sm = rng.integers(0, 8, n).astype(np.uint8)                       # uniform: the code comes out flat
+        ex = (np.minimum(rng.geometric(geometric, n) - 1, n_exp - 1) if geometric else rng.integers(0, n_exp, n)).astype(np.uint8)
+        return torch.from_numpy(((sm >> 2) << 7 | (ex << 2) | (sm & 3)).astype(np.uint8))
+
+    for cb in (3072, 16384):
+        n = 9 * cb + 777
+        for tag, x, L, period, long_codes in (("p2-long", e5m2_like(n, 32, 0.45), (16, 0, 0), 2, True), ("p2", e5m2_like(n, 32, 0.45), (11, 0, 0), 2, False),
+                                              ("p4", e5m2_like(n, 32, 0.45), (8, 8, 0), 4, False), ("p8", e5m2_like(n, 6, 0), (0, 0, 0), 8, False)):
+            want, _, _ = check_case(F, n, cb, 64, L=L, data=(x, None), tag="e5m2-kernel-" + tag)
+            info = zc.validate_container(want)
+            assert info.mode[1] == zc.MODE_HUFF and list(info.code_len[1][:9]) == [3] * 8 + [0], tag
+            lmax = info.max_len[0]
+            assert (lmax > 11) == long_codes and {2: 9 <= lmax, 4: 5 <= lmax <= 8, 8: lmax <= 4}[period], (tag, lmax)
+        base = e5m2_like(n, 32, 0.3)
+        want, _, _ = check_case(F, n, cb, 64, data=(e5m2_like(n, 32, 0.45), None), base=base, tag="e5m2-kernel-delta")
+        assert list(zc.validate_container(want).code_len[1][:9]) == [3] * 8 + [0]
+    # a set of tensors in one launch
+    srcs = [wl.fp8_e5m2_weight(5 * 65536 + 65536 * i, seed=60 + i) for i in range(3)]
+    p, po = zc.params(F, 65536), o.params(F, 65536)
+    bt = zc.Batch([dev(s_) for s_ in srcs], [s_.numel() for s_ in srcs], p)
+    sizes = bt.compress()
+    for i, s_ in enumerate(srcs):
+        assert np.array_equal(bt.container(i).cpu().numpy(), o.compress(s_.numpy(), s_.numel(), po))
+    plan = bt.plan_decompress()
+    assert plan.fast_kernel == 7
+    outs = bt.run_decompress()
+    torch.cuda.synchronize()
+    for out, s_ in zip(outs, srcs):
+        assert torch.equal(out.cpu()[:s_.numel()], s_)
+    # damaged streams stay inside the buffers
+    comp, info = zc.compress(dev(srcs[0]), srcs[0].numel(), p)
+    guard = 4096
+    buf = torch.full((guard + comp.numel() + guard,), 0x5A, dtype=torch.uint8, device=DEV)
+    body = buf[guard:guard + comp.numel()]
+    body.copy_(comp)
+    pay = int(info.payload_offset)
+    body[pay:] = torch.from_numpy(rng.integers(0, 256, comp.numel() - pay).astype(np.uint8)).to(DEV)
+    out = torch.full((guard + srcs[0].numel() + guard,), 0xC3, dtype=torch.uint8, device=DEV)
+    zc.decompress(body, info, out=out[guard:guard + srcs[0].numel()])
+    torch.cuda.synchronize()
+    assert bool((out[:guard] == 0xC3).all()) and bool((out[guard + srcs[0].numel():] == 0xC3).all())
+    assert bool((buf[:guard] == 0x5A).all()) and bool((buf[guard + comp.numel():] == 0x5A).all())
+
+
 def test_planned_decode_replays_from_a_captured_graph():
     # A serving loop that decodes the same containers every step can record the planned decode once:
     # zc_decompress_batch_run only launches kernels.  Every replay is checked against the source, with the
