@@ -414,25 +414,41 @@ __device__ __forceinline__ void huff_run(HuffStream &H, const FieldTab &T, uint3
     else huff_run_l<SB, G, false>(H, T, period, P0, P1, lane);
 }
 
-// one field of one run when it is not table decoded.  words_per_run = G*SB/32.
+// One field of one run when it is not table decoded, in two steps so that the loads of a row can be in flight while the
+// row before it is decoded: plain_fetch asks for the run's words (G*SB/32 of them; all offsets are in the range-checked
+// operand, so a row past the end reads zeros), plain_finish turns them into the packed symbols.
 template <int SB, int G>
-__device__ __forceinline__ void plain_run(uint32_t kind, __amdgpu_buffer_rsrc_t rs, uint32_t row, uint32_t lane, uint64_t konst, uint64_t &P0, uint64_t &P1)
+__device__ __forceinline__ void plain_fetch(uint32_t kind, __amdgpu_buffer_rsrc_t rs, uint32_t row, uint32_t lane, uint32_t w[G * SB / 32])
 {
-    constexpr int WPR = G * SB / 32;           // 2 for element fields, 4 for the scale field
-    uint32_t w[WPR];
+    constexpr int WPR = G * SB / 32;           // 2 for element fields, 4 for the scale field and for 16 symbols of 8 bits
     if (kind == KIND_FLAT) {
         // regular schedule: every lane takes one word per 32/SB symbols, rows of 64 words
 #pragma unroll
-        for (int h = 0; h < WPR; h++) w[h] = reverse_in_groups<SB>(__builtin_amdgcn_raw_buffer_load_b32(rs, (int)(((row * WPR + h) * 64 + lane) * 4), 0, 0));
+        for (int h = 0; h < WPR; h++) w[h] = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(((row * WPR + h) * 64 + lane) * 4), 0, 0);
     } else if (kind == KIND_RAW) {
 #pragma unroll
         for (int h = 0; h < WPR; h++) w[h] = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(((row * 64 + lane) * WPR + h) * 4), 0, 0);
-    } else {
-        P0 = konst; P1 = konst;
-        return;
     }
+}
+
+template <int SB, int G>
+__device__ __forceinline__ void plain_finish(uint32_t kind, const uint32_t w_in[G * SB / 32], uint64_t konst, uint64_t &P0, uint64_t &P1)
+{
+    constexpr int WPR = G * SB / 32;
+    if (kind != KIND_FLAT && kind != KIND_RAW) { P0 = konst; P1 = konst; return; }
+    uint32_t w[WPR];
+#pragma unroll
+    for (int h = 0; h < WPR; h++) w[h] = kind == KIND_FLAT ? reverse_in_groups<SB>(w_in[h]) : w_in[h];
     P0 = (uint64_t)w[0] | ((uint64_t)w[1] << 32);
     if (WPR == 4) P1 = (uint64_t)w[2] | ((uint64_t)w[3] << 32);
+}
+
+template <int SB, int G>
+__device__ __forceinline__ void plain_run(uint32_t kind, __amdgpu_buffer_rsrc_t rs, uint32_t row, uint32_t lane, uint64_t konst, uint64_t &P0, uint64_t &P1)
+{
+    uint32_t w[G * SB / 32] = {};
+    plain_fetch<SB, G>(kind, rs, row, lane, w);
+    plain_finish<SB, G>(kind, w, konst, P0, P1);
 }
 
 __device__ __forceinline__ bool stream_range(const TensorDev &d, const uint8_t *comp, int f, uint32_t chunk, uint64_t payload, uint64_t total,
@@ -502,15 +518,33 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     const uint32_t rows = cb / 1024;                          // 64 lanes x 16 bytes per row
     if (split && (kind[0] == KIND_HUFF || kind[1] == KIND_HUFF)) return;          // the host never asks for this
     const uint32_t row_begin = split ? wave * rows / kWavesPerGroup : 0u, row_end = split ? (wave + 1) * rows / kWavesPerGroup : rows;
+    // what a row takes from global memory besides its stream words (plainly stored fields, the base of a delta) is asked
+    // for one row ahead
+    constexpr int WPR = F_::G * F_::SB / 32;
+    uint32_t w0_next[WPR] = {}, w1_next[WPR] = {};
+    u32x4 base_next = {0, 0, 0, 0};
+    if (row_begin < row_end) {
+        if (SPLIT || kind[0] != KIND_HUFF) plain_fetch<F_::SB, F_::G>(kind[0], r0, row_begin, lane, w0_next);
+        if (SPLIT || kind[1] != KIND_HUFF) plain_fetch<F_::SB, F_::G>(kind[1], r1, row_begin, lane, w1_next);
+        if (XOR) base_next = __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)(row_begin * 1024), 0);
+    }
     for (uint32_t row = row_begin; row < row_end; row++) {
         uint64_t P0 = 0, P1 = 0, Q0 = 0, Q1 = 0;       // Q: symbols 8..15 of a run of 16 symbols of 8 bits
+        uint32_t w0[WPR], w1[WPR];
+#pragma unroll
+        for (int h = 0; h < WPR; h++) { w0[h] = w0_next[h]; w1[h] = w1_next[h]; }
+        const u32x4 base = base_next;
+        if (SPLIT || kind[0] != KIND_HUFF) plain_fetch<F_::SB, F_::G>(kind[0], r0, row + 1, lane, w0_next);
+        if (SPLIT || kind[1] != KIND_HUFF) plain_fetch<F_::SB, F_::G>(kind[1], r1, row + 1, lane, w1_next);
+        // (the scalar offset of a buffer access is not range checked: the row after the last is the last again)
+        if (XOR) base_next = __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)((row + 1 < rows ? row + 1 : row) * 1024), 0);
         if (!SPLIT && kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, Q0, lane);
-        else plain_run<F_::SB, F_::G>(kind[0], r0, row, lane, K0, P0, Q0);
+        else plain_finish<F_::SB, F_::G>(kind[0], w0, K0, P0, Q0);
         if (!SPLIT && kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, Q1, lane);
-        else plain_run<F_::SB, F_::G>(kind[1], r1, row, lane, K1, P1, Q1);
+        else plain_finish<F_::SB, F_::G>(kind[1], w1, K1, P1, Q1);
         const uint4 j = join_run4<FMT>(P0, Q0, P1, Q1);
         u32x4 v = {j.x, j.y, j.z, j.w};
-        if (XOR) v ^= __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)(row * 1024), 0);
+        if (XOR) v ^= base;
         __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
     }
 
