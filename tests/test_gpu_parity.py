@@ -462,12 +462,12 @@ def test_fp8_fast_path_variants():
 
 
 def test_config2_full_size_tensors_in_the_benchmark_launch_configuration():
-    # Three tensors of config 2 at their real sizes (k: 4 MiB, q: 16 MiB, gate: 56 MiB), generated
+    # One full layer of config 2 at its real sizes (q, o: 16 MiB; k, v: 4 MiB; gate, up, down: 56 MiB), generated
     # on the GPU exactly as bench.py does, compressed and decoded as one batch (the launch
     # configuration bench.py times).  The oracle compresses the same bytes: containers must be
     # identical; then sampled chunks of the oracle's container are decoded one by one on the CPU
     # and compared with the GPU output.
-    shapes = [("k", 4096 * 1024), ("q", 4096 * 4096), ("gate", 4096 * 14336)]
+    shapes = [(name, r * c) for name, r, c in wl.LAYER_8B]
     dev_srcs = [wl.fp8_weight(n, device=DEV, seed=2000 + i) for i, (_, n) in enumerate(shapes)]
     counts = [n for _, n in shapes]
     p = zc.params(zc.FMT_FP8_E4M3, 262144, streams=64)
