@@ -846,6 +846,9 @@ __global__ __launch_bounds__(256) void k_decode_bf16_s64(const TensorDev *descs,
     uint32_t sb[2];
     for (int f = 0; f < 2; f++)
         if (!stream_range(d, comp, f, chunk, payload, total, sp[f], sb[f])) return;      // damaged index: leave the chunk alone
+    // a plainly stored sign+mantissa field takes a byte per value; its rows are addressed through the scalar offset,
+    // which is not range checked, so a stream shorter than that (a damaged index) must not be read at all
+    if ((kind1 == KIND_FLAT || kind1 == KIND_RAW) && sb[1] < cb / 2) return;
     const __amdgpu_buffer_rsrc_t r0 = make_rsrc(sp[0], sb[0]), r1 = make_rsrc(sp[1], sb[1]);
     const __amdgpu_buffer_rsrc_t ds = make_rsrc(reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.dst)) + (uint64_t)chunk * cb, cb);
     const __amdgpu_buffer_rsrc_t bs = make_rsrc(XOR ? reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.base)) + (uint64_t)chunk * cb : comp, XOR ? cb : 0);
