@@ -94,7 +94,7 @@ def test_empty_tensor():
 
 
 def test_config1_bf16_full():
-    # BASELINE config 1: 1,048,576 BF16 values N(0, 0.02), seed 0, max length 16, 64 KiB chunks
+    # configuration 1: 1,048,576 BF16 values N(0, 0.02), seed 0, max length 16, 64 KiB chunks
     n = 1 << 20
     x = wl.bf16_weight(n, seed=0).view(torch.uint8)
     want, _, _ = check_case(zc.FMT_BF16, n, 65536, 64, L=(16, 16, 0), data=(x, None), tag="config1")
