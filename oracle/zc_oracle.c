@@ -32,7 +32,9 @@
  * split/rebuild identity, numpy.bincount, Kraft equality, entropy bounds,
  * brute-force optimal codes on <= 8 symbols, textbook heap Huffman cost,
  * hand-worked code tables and streams, an independent bit-by-bit reader for
- * the one-lane case, chunk independence, exact round trips.
+ * the one-lane case, chunk independence, exact round trips; for the statistics
+ * (tests/test_oracle_stats.py) hand-made fields with exact entropies and
+ * -sum p log2 p recomputed with numpy from numpy.bincount of the symbols.
  * Parity unpinned: the ratios the paper reports on real checkpoints (the data
  * is not available); they are quoted as context only.
  */
