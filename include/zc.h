@@ -95,11 +95,11 @@ typedef struct {
 
 /* Choosing the geometry.  Every geometry above gives a valid container; these give the fast kernels:
  *   - 64 lanes: chunk_bytes a multiple of 1024 (whole rows of 16 bytes per lane).  Other chunk sizes, and the
- *     short last chunk of a tensor, go through the generic kernels: about 2.8 x slower to decode on MI355X when
- *     every chunk does (48 KiB + 16 against 48 KiB), 1.3 x for a set of tensors with one short chunk each.
+ *     short last chunk of a tensor, go through the generic kernels: about 2.4 x slower to decode on MI355X when
+ *     every chunk does (48 KiB + 16 against 48 KiB), 1.15 x for a set of tensors with one short chunk each.
  *   - chunks below 16 KiB (K/V pages, Sec. 3.3): 4 to 32 lanes with chunk_bytes a multiple of 16 * lanes.  A
  *     wavefront then decodes 64 / lanes chunks at once; with 64 lanes it decodes one small chunk at a time (a 2 KiB
- *     page: 3.9 x slower from an id list) and every lane's look-ahead words eat the gain (ratio 1.00 against 0.86).
+ *     page: 3.6 x slower from an id list) and every lane's look-ahead words eat the gain (ratio 1.00 against 0.86).
  *   - max_code_len of the exponent field: up to 8 keeps four symbols per refill step for FP8 (the default); 9 to 16
  *     halves the step and costs about 40 % of decode speed for 0.2 % of size on FP8 weights.  For BF16 and for byte
  *     symbols a limit of 11 keeps every code inside the decoders' lookup index (5 to 7 % faster, 0.5 % larger). */

@@ -674,6 +674,32 @@ __device__ __forceinline__ DecField open_stream(const TensorDev &d, int f, uint3
     return D;
 }
 
+// A field with a flat code (every symbol coded by its own bits, most significant first) on rows where every lane of the
+// wavefront holds a whole run: each lane takes one word per 32 / SB symbols and no look-ahead, so the words of row i
+// are (i * WPR + h) * S + lane of the group, h < WPR, and need no table.  The first row that is not whole (the last
+// of a short chunk) goes through the table again: flat_leave puts the stream state where that row starts.
+template <int SB, int G>
+__device__ __forceinline__ void flat_row(const DecField &D, uint32_t row, uint32_t S, uint32_t s, uint64_t &P, uint64_t &Q)
+{
+    constexpr int WPR = G * SB / 32;
+    uint32_t w[WPR];
+#pragma unroll
+    for (int h = 0; h < WPR; h++) w[h] = reverse_in_groups<SB>(stream_word(D, (row * WPR + h) * S + s));
+    P = (uint64_t)w[0] | ((uint64_t)w[1] << 32);
+    if (WPR == 4) Q = (uint64_t)w[2] | ((uint64_t)w[3] << 32);
+}
+
+template <int SB, int G>
+__device__ __forceinline__ void flat_leave(DecField &D, uint32_t row, uint32_t S, uint32_t s)
+{
+    constexpr int WPR = G * SB / 32;
+    D.c = 64; D.lo = 0; D.hi = 0;                    // nothing unread: the row's first step takes a word
+    D.wpos = row * WPR * S;
+    D.base = D.wpos;
+    D.cur = stream_word(D, D.base + s);
+    D.nxt = stream_word(D, D.base + S + s);
+}
+
 template <int FMT>
 __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single,
                                                 uint32_t first_slot)
@@ -709,6 +735,8 @@ __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const Wo
     const uint64_t K0 = splat(d.konst[0], F_::SB), K1 = splat(d.konst[1], F_::SB);
     const uint32_t chunk_runs = (uint32_t)((E + F_::EPR - 1) / F_::EPR);
     const uint32_t rows = (chunk_runs + S - 1) / S;
+    // flat-coded fields are read directly while the rows are whole (the same in all lanes: `full` is a wavefront vote)
+    bool direct0 = m0 == ZC_MODE_HUFF && d.kind[0] == 1, direct1 = m1 == ZC_MODE_HUFF && d.kind[1] == 1;
     for (uint32_t i = 0; i < rows; i++) {
         const uint32_t run = i * S + L.s;
         const uint32_t done = run * F_::EPR;                                                       // elements before this run
@@ -717,14 +745,20 @@ __global__ __launch_bounds__(256) void k_decode(const TensorDev *descs, const Wo
         const bool full = __all(nsym == (uint32_t)F_::G);
         constexpr bool kWide = F_::G * F_::SB > 64;
         uint64_t P0 = 0, P1 = 0, Q0 = 0, Q1 = 0;       // Q: symbols 8..15 of a run of 16 symbols of 8 bits
-        if (m0 == ZC_MODE_HUFF) {
+        if (!full) {
+            if (direct0) { flat_leave<F_::SB, F_::G>(D0, i, S, L.s); direct0 = false; }
+            if (direct1) { flat_leave<F_::SB, F_::G>(D1, i, S, L.s); direct1 = false; }
+        }
+        if (direct0) flat_row<F_::SB, F_::G>(D0, i, S, L.s, P0, Q0);
+        else if (m0 == ZC_MODE_HUFF) {
             if (full) dec_run<F_::SB, F_::G, true>(D0, tab[0], d.period[0], P0, Q0, nsym, L);
             else dec_run<F_::SB, F_::G, false>(D0, tab[0], d.period[0], P0, Q0, nsym, L);
         } else if (m0 == ZC_MODE_RAW) {
             if (kWide) { if (nsym && 4 * run + 3 < D0.words) { P0 = reinterpret_cast<const uint64_t *>(D0.ptr)[2 * run]; Q0 = reinterpret_cast<const uint64_t *>(D0.ptr)[2 * run + 1]; } }
             else if (nsym && 2 * run + 1 < D0.words) P0 = reinterpret_cast<const uint64_t *>(D0.ptr)[run];
         } else { P0 = K0; Q0 = K0; }
-        if (m1 == ZC_MODE_HUFF) {
+        if (direct1) flat_row<F_::SB, F_::G>(D1, i, S, L.s, P1, Q1);
+        else if (m1 == ZC_MODE_HUFF) {
             if (full) dec_run<F_::SB, F_::G, true>(D1, tab[1], d.period[1], P1, Q1, nsym, L);
             else dec_run<F_::SB, F_::G, false>(D1, tab[1], d.period[1], P1, Q1, nsym, L);
         } else if (m1 == ZC_MODE_RAW) {
