@@ -847,7 +847,7 @@ def test_random_parameter_sweep():
     rng = np.random.default_rng(20250827)
     fmts = (zc.FMT_BF16, zc.FMT_FP8_E4M3, zc.FMT_FP4_E2M1_MX, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP4_E2M1_MX_BYTES, zc.FMT_FP4_E2M1_NV,
             zc.FMT_FP8_E5M2)
-    for case in range(700):
+    for case in range(2100):
         fmt = fmts[case % len(fmts)]
         S = int(2 ** rng.integers(0, 7))
         unit = 256 if zc.scale_block(fmt) else 16
@@ -870,6 +870,30 @@ def test_random_parameter_sweep():
         if src.numel() == 0:
             src = torch.zeros(0, dtype=torch.uint8)
         check_case(fmt, n, cb, S, policy, L, data=(src, sc), base=base, tag="sweep-%d" % case)
+
+
+def test_random_sweep_whole_row_chunks_and_pages():
+    # the same kind of sweep over the geometries the specialised kernels take: 64 lanes with chunks of whole 1 KiB
+    # rows (1 to 32 of them), or 4 to 32 lanes with chunks of whole 16-byte runs per lane, for the formats that have
+    # kernels of their own or go through the 64-lane kernel with 8-bit symbols
+    rng = np.random.default_rng(20261128)
+    fmts = (zc.FMT_BF16, zc.FMT_FP8_E5M2, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP8_E4M3, zc.FMT_BF16, zc.FMT_FP8_E5M2)
+    for case in range(1800):
+        fmt = fmts[case % len(fmts)]
+        S = 64 if rng.integers(0, 4) else int(2 ** rng.integers(2, 6))
+        cb = 1024 * int(rng.integers(1, 33)) if S == 64 else 16 * S * int(rng.integers(1, 17))
+        E = cb * 8 // zc.elem_bits(fmt)
+        n = int(rng.integers(1, 6)) * E if rng.integers(0, 3) else int(rng.integers(0, 5 * E + 2))
+        policy = int(rng.integers(0, 2))
+        lo = 4 if fmt == zc.FMT_FP8_E4M3 else 8
+        L = (int(rng.integers(lo, 17)) if rng.integers(0, 2) else 0, int(rng.integers(lo, 17)) if rng.integers(0, 2) else 0, 0)
+        src, sc = _random_source(rng, fmt, n)
+        base = None
+        if rng.integers(0, 3) == 0 and n:
+            base = torch.from_numpy(rng.integers(0, 256, src.numel(), dtype=np.uint8) & np.uint8(rng.choice([0x01, 0x81, 0xFF, 0x03])))
+        if src.numel() == 0:
+            src = torch.zeros(0, dtype=torch.uint8)
+        check_case(fmt, n, cb, S, policy, L, data=(src, sc), base=base, tag="rows-%d" % case)
 
 
 def test_random_sweep_fp8_chunks_of_one_histogram_block():
