@@ -896,6 +896,61 @@ def test_random_sweep_whole_row_chunks_and_pages():
         check_case(fmt, n, cb, S, policy, L, data=(src, sc), base=base, tag="rows-%d" % case)
 
 
+def test_random_sweep_of_batches():
+    # random sets of tensors (1 to 8, whole and ragged lengths, empty ones) through zc_compress_batch and
+    # zc_decompress_batch: every container against the oracle's, every round trip bit for bit.  What a set shares
+    # (geometry, policy) and what it mixes (lengths, data) decide which kernels and work lists the plan uses.
+    rng = np.random.default_rng(20261129)
+    fmts = (zc.FMT_BF16, zc.FMT_FP8_E4M3, zc.FMT_FP4_E2M1_MX, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP8_E5M2, zc.FMT_FP4_E2M1_NV)
+    for case in range(360):
+        fmt = fmts[case % len(fmts)]
+        blk = zc.scale_block(fmt)
+        shape = int(rng.integers(0, 3))
+        if shape == 0:
+            S, cb = 64, 1024 * int(rng.integers(1, 17))
+        elif shape == 1:
+            S = int(2 ** rng.integers(2, 6))
+            cb = 16 * S * int(rng.integers(1, 9))
+        else:
+            S, cb = int(2 ** rng.integers(0, 7)), 16 * int(rng.integers(1, 200))
+        if blk:
+            cb = 16384 if shape == 0 else max(cb // 256 * 256, 256)
+        E = cb * 8 // zc.elem_bits(fmt)
+        policy = int(rng.integers(0, 2))
+        use_base = rng.integers(0, 4) == 0 and not blk
+        ns, srcs, scs, bases = [], [], [], []
+        for _ in range(int(rng.integers(1, 9))):
+            n = int(rng.integers(1, 5)) * E if rng.integers(0, 2) else int(rng.integers(0, 4 * E + 2))
+            if blk:
+                n = n // blk * blk
+            src, sc = _random_source(rng, fmt, n)
+            if src.numel() == 0:
+                src = torch.zeros(0, dtype=torch.uint8)
+            ns.append(n)
+            srcs.append(src)
+            scs.append(sc)
+            bases.append(torch.from_numpy(rng.integers(0, 256, src.numel(), dtype=np.uint8) & np.uint8(0x81)) if use_base else None)
+        print("batch", case, "fmt", fmt, "S", S, "chunk", cb, "n", ns, "policy", policy, "base", bool(use_base), flush=True)
+        p, po = zc.params(fmt, cb, (0, 0, 0), S, policy), o.params(fmt, cb, (0, 0, 0), S, policy)
+        b = zc.Batch([dev(x) for x in srcs], ns, p, xor_bases=[dev(x) for x in bases] if use_base else None,
+                     scales=[dev(x) for x in scs] if blk else None)
+        sizes = b.compress()
+        for t in range(len(ns)):
+            # an empty tensor has no base as far as either side can tell (its device pointer is null)
+            want = o.compress(srcs[t].numpy(), ns[t], po, xor_base=bases[t].numpy() if use_base and ns[t] else None,
+                              scales=scs[t].numpy() if blk else None)
+            got = b.container(t).cpu().numpy()
+            assert sizes[t] == len(want), (t, sizes[t], len(want))
+            assert np.array_equal(got, want), (t, int(np.argmax(got != want)))
+        b.decompress()
+        torch.cuda.synchronize()
+        for t in range(len(ns)):
+            nb = (ns[t] * zc.elem_bits(fmt) + 7) // 8
+            assert torch.equal(b.out[t].cpu()[:nb], srcs[t].view(torch.uint8).reshape(-1)[:nb]), t
+            if blk and ns[t]:
+                assert torch.equal(b.scales_out[t].cpu()[:ns[t] // blk], scs[t]), t
+
+
 def test_random_sweep_fp8_chunks_of_one_histogram_block():
     # the same kind of sweep over the one shape whose size pass works from per-lane counts: FP8, 64 lanes, 256 KiB
     rng = np.random.default_rng(20251127)
