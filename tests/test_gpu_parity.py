@@ -951,6 +951,73 @@ def test_random_sweep_of_batches():
                 assert torch.equal(b.scales_out[t].cpu()[:ns[t] // blk], scs[t]), t
 
 
+def test_random_sweep_of_the_other_entry_points():
+    # statistics, dictionary training and use, the call that allocates nothing and chunk lists (repeated and
+    # out-of-range ids included) on random geometries and data, each against the oracle
+    rng = np.random.default_rng(20261130)
+    fmts = (zc.FMT_BF16, zc.FMT_FP8_E4M3, zc.FMT_FP4_E2M1_MX, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP8_E5M2, zc.FMT_FP4_E2M1_NV,
+            zc.FMT_FP4_E2M1_MX_BYTES)
+    host = lambda x: None if x is None else x.numpy()
+    for case in range(280):
+        fmt = fmts[case % len(fmts)]
+        blk = zc.scale_block(fmt)
+        shape = int(rng.integers(0, 3))
+        if shape == 0:
+            S, cb = 64, 1024 * int(rng.integers(1, 9))
+        elif shape == 1:
+            S = int(2 ** rng.integers(2, 6))
+            cb = 16 * S * int(rng.integers(1, 9))
+        else:
+            S, cb = int(2 ** rng.integers(0, 7)), 16 * int(rng.integers(1, 120))
+        if blk:
+            cb = 16384 if shape == 0 else max(cb // 256 * 256, 256)
+        E = cb * 8 // zc.elem_bits(fmt)
+        policy = int(rng.integers(0, 2))
+
+        def tensor():
+            n = int(rng.integers(1, 6)) * E if rng.integers(0, 2) else int(rng.integers(1, 5 * E + 2))
+            if blk:
+                n = max(n // blk * blk, blk)
+            return (n,) + _random_source(rng, fmt, n)
+
+        (n_a, a, sa), (n_b, b, sb) = tensor(), tensor()
+        print("entry points", case, "fmt", fmt, "S", S, "chunk", cb, "n", n_a, n_b, "policy", policy, flush=True)
+        p, po = zc.params(fmt, cb, (0, 0, 0), S, policy), o.params(fmt, cb, (0, 0, 0), S, policy)
+        compare_stats(zc.stats(dev(a), n_a, p, scales=dev(sa)), o.stats(a.numpy(), n_a, po, scales=host(sa)))
+        # a dictionary trained on one tensor codes the other
+        code = zc.train_code(dev(a), n_a, p, scales=dev(sa))
+        ln, md = o.train_code(a.numpy(), n_a, po, scales=host(sa))
+        for f in range(code.n_fields):
+            assert list(code.code_len[f]) == ln[f].tolist() and code.mode[f] == md[f], f
+        comp, info = zc.compress_with_code(dev(b), n_b, p, code, scales=dev(sb))
+        assert np.array_equal(comp.cpu().numpy(), o.compress_with_code(b.numpy(), n_b, po, ln, md, scales=host(sb)))
+        # the call that allocates nothing writes the container a plain compress writes
+        want = o.compress(b.numpy(), n_b, po, scales=host(sb))
+        dst = torch.empty(max(zc.compress_bound(n_b, p), 16), dtype=torch.uint8, device=DEV)
+        zc.compress_noalloc(dev(b), n_b, p, dst, scales=dev(sb))
+        torch.cuda.synchronize()
+        assert zc.read_info(dst, check_index=True).total_bytes == len(want) and np.array_equal(dst[:len(want)].cpu().numpy(), want)
+        # a chunk list over the dictionary's container
+        nc = info.n_chunks
+        k = int(rng.integers(1, 2 * nc + 2))
+        ids = rng.integers(0, nc + (2 if rng.integers(0, 3) == 0 else 0), k).astype(np.int32)
+        out = torch.full((k * cb,), 0xA5, dtype=torch.uint8, device=DEV)
+        spc = E // blk if blk else 0                 # scale bytes of a whole chunk
+        sc_out = torch.full((max(k * spc, 1),), 0xA5, dtype=torch.uint8, device=DEV) if blk else None
+        zc.decompress_chunks(comp, info, torch.from_numpy(ids).to(DEV), out=out, scales_out=sc_out)
+        torch.cuda.synchronize()
+        rows, flat = out.cpu().numpy().reshape(k, cb), b.numpy().reshape(-1).view(np.uint8)
+        for i, c in enumerate(ids):
+            if c >= nc:
+                assert (rows[i] == 0xA5).all(), ("a slot of an id out of range was written", i, c)
+                continue
+            lo, hi = int(c) * cb, min(int(c) * cb + cb, flat.size)
+            assert np.array_equal(rows[i][:hi - lo], flat[lo:hi]), (i, c)
+            if blk:
+                s_lo, s_hi = int(c) * spc, min(int(c) * spc + spc, n_b // blk)
+                assert np.array_equal(sc_out.cpu().numpy()[i * spc:i * spc + (s_hi - s_lo)], sb.numpy()[s_lo:s_hi]), ("scales", i, c)
+
+
 def test_random_sweep_fp8_chunks_of_one_histogram_block():
     # the same kind of sweep over the one shape whose size pass works from per-lane counts: FP8, 64 lanes, 256 KiB
     rng = np.random.default_rng(20251127)
