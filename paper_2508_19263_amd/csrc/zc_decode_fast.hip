@@ -517,7 +517,8 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
 
     const uint32_t rows = cb / 1024;                          // 64 lanes x 16 bytes per row
     if (split && (kind[0] == KIND_HUFF || kind[1] == KIND_HUFF)) return;          // the host never asks for this
-    const uint32_t row_begin = split ? wave * rows / kWavesPerGroup : 0u, row_end = split ? (wave + 1) * rows / kWavesPerGroup : rows;
+    uint32_t row_begin = 0, row_end = rows;
+    if (split) shared_chunk_rows(rows, F_::NF == 3 ? E / F_::SCALE / 1024 : 0u, wave, row_begin, row_end);
     // what a row takes from global memory besides its stream words (plainly stored fields, the base of a delta) is asked
     // for one row ahead
     constexpr int WPR = F_::G * F_::SB / 32;

@@ -267,6 +267,20 @@ __device__ __forceinline__ uint64_t splat(uint32_t v, int sb)
 }
 
 
+// Rows of a chunk that the four wavefronts of a workgroup share (fields stored plainly, so rows do not depend on each
+// other).  The first wavefront also takes the chunk's block scales, scale_rows rows of 1024 of them, whose table-driven
+// coding costs about kScaleRowCost element rows each: it gets fewer element rows, the others a third of the rest each.
+constexpr uint32_t kScaleRowCost = 3;
+__device__ __forceinline__ void shared_chunk_rows(uint32_t rows, uint32_t scale_rows, uint32_t wave, uint32_t &begin, uint32_t &end)
+{
+    const uint32_t extra = scale_rows * kScaleRowCost;
+    const uint32_t first = rows > 3 * extra ? (rows - 3 * extra) / 4 : 0u;         // first + extra = (rows - first) / 3
+    const uint32_t rest = rows - first;
+    begin = wave == 0 ? 0u : first + (wave - 1) * rest / 3;
+    end = wave == 0 ? first : first + wave * rest / 3;
+}
+
+
 // reverse the bit order inside every SB-bit group of a word (a flat code is the symbol value
 // written most significant bit first into an LSB-first string)
 template <int SB>

@@ -305,7 +305,7 @@ __global__ __launch_bounds__(256) void k_encode(const TensorDev *descs, const Wo
     const bool plain = plain0 && plain1;
     if (shared && !plain && wave != 0) return;
     uint32_t row_begin = 0, row_end = rows;
-    if (shared && plain) { row_begin = wave * rows / kWavesPerGroup; row_end = (wave + 1) * rows / kWavesPerGroup; }
+    if (shared && plain) shared_chunk_rows(rows, F_::NF == 3 ? (uint32_t)((E / F_::SCALE + 1023) / 1024) : 0u, wave, row_begin, row_end);
     if (WHOLE && !WRITE && plain) {
         // size pass: a flat code takes two words per run whatever the data, raw and constant fields are sized below
         if (m0 == ZC_MODE_HUFF) F0.wpos = 2 * rows;
