@@ -268,7 +268,10 @@ struct HuffStream {
     uint32_t lim[4];       // FieldTab::limit of lengths 12..15 (uniform): the code lengths beyond the lookup index
 };
 
-__device__ __forceinline__ void huff_open(HuffStream &H, const FieldTab &T, __amdgpu_buffer_rsrc_t rs, char *ring, uint32_t lane, uint32_t rw = kRing2Words)
+// first: does this lane own a symbol at step 0?  (always, in a chunk of whole rows; a chunk shorter than one row
+// hands its first words to the lanes that do, in lane order)
+__device__ __forceinline__ void huff_open(HuffStream &H, const FieldTab &T, __amdgpu_buffer_rsrc_t rs, char *ring, uint32_t lane, uint32_t rw = kRing2Words,
+                                          bool first = true)
 {
     H.rs = rs; H.ring = ring; H.rw = rw;
 #pragma unroll
@@ -279,8 +282,9 @@ __device__ __forceinline__ void huff_open(HuffStream &H, const FieldTab &T, __am
         if (rw == kRing2Words) *reinterpret_cast<u32x2 *>(ring + q * seg_bytes + lane * 8) = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)(lane * 8 + q * seg_bytes), 0, 0);
         else *reinterpret_cast<uint32_t *>(ring + q * seg_bytes + lane * 4) = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(lane * 4 + q * seg_bytes), 0, 0);
     }
-    H.W = (uint64_t)(*reinterpret_cast<const uint32_t *>(ring + lane * 4)) << 32;   // step 0: word `lane`
-    H.c = 32; H.wpos = 64; H.wbase = 0; H.pslot = 0; H.pending = false;
+    const uint64_t takers = __ballot(first);
+    H.W = (uint64_t)(*reinterpret_cast<const uint32_t *>(ring + prefix_count64(takers) * 4)) << 32;   // step 0: word `lane` when all take one
+    H.c = 32; H.wpos = (uint32_t)__popcll(takers); H.wbase = 0; H.pslot = 0; H.pending = false;
     H.pv = u32x2{0, 0};
 }
 
@@ -304,9 +308,10 @@ __device__ __forceinline__ void huff_ring_service(HuffStream &H, uint32_t lane)
 // is the ring serviced before refill step g of a run?  (every step with the small ring, every other one with the large)
 __device__ __forceinline__ bool huff_service_due(const HuffStream &H, int g) { return (g & 1) == 0 || H.rw != kRing2Words; }
 
-__device__ __forceinline__ void huff_refill(HuffStream &H)
+// owner: does this lane own a symbol at the step the words are for?  (always, inside whole rows)
+__device__ __forceinline__ void huff_refill(HuffStream &H, bool owner = true)
 {
-    const bool need = H.c >= 32;
+    const bool need = owner && H.c >= 32;
     const uint64_t bm = __ballot(need);
     const uint32_t w = *reinterpret_cast<const uint32_t *>(H.ring + ((prefix_count64(bm) * 4 + H.wpos * 4) & (H.rw * 4 - 1)));
     H.W = need ? ((H.W >> 32) | ((uint64_t)w << 32)) : H.W;
@@ -329,8 +334,11 @@ __device__ __forceinline__ uint32_t long_code(const FieldTab &T, const HuffStrea
 
 // decode one run of G symbols (SB bits each) into P0 (symbols 0..64/SB-1) and P1 (the rest).
 // LONG: the code has words longer than the lookup index.
+// nsym: symbols of this run the lane owns, nsym_next: of its next run (both G inside whole rows).  The words of a
+// refill step are taken at the end of the step before it, by the lanes that own a symbol at the step they are for;
+// a lane decodes all G symbols whatever it owns, and what it does not own is never stored.
 template <int SB, int G, int R, bool LONG>
-__device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uint64_t &P0, uint64_t &P1, uint32_t lane)
+__device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uint64_t &P0, uint64_t &P1, uint32_t lane, uint32_t nsym = G, uint32_t nsym_next = G)
 {
     static_assert(!LONG || R == 2, "codes beyond the lookup index come with a refill period of 2 only; the second look relies on it");
     constexpr int PER64 = 64 / SB;
@@ -388,30 +396,58 @@ __device__ __forceinline__ void huff_run_r(HuffStream &H, const FieldTab &T, uin
             } else q[word] |= (e[j] >> 8) << (pos * SB);
         }
         H.c = c & 0x7Fu;
-        huff_refill(H);
+        huff_refill(H, g + 1 < G / R ? (uint32_t)((g + 1) * R) < nsym : nsym_next > 0);
     }
     P0 = (uint64_t)q[0] | ((uint64_t)q[1] << 32);
     if (G > PER64) P1 = (uint64_t)q[2] | ((uint64_t)q[3] << 32);
 }
 
 template <int SB, int G, bool LONG>
-__device__ __forceinline__ void huff_run_l(HuffStream &H, const FieldTab &T, uint32_t period, uint64_t &P0, uint64_t &P1, uint32_t lane)
+__device__ __forceinline__ void huff_run_l(HuffStream &H, const FieldTab &T, uint32_t period, uint64_t &P0, uint64_t &P1, uint32_t lane,
+                                           uint32_t nsym = G, uint32_t nsym_next = G)
 {
     switch (period) {
-    case 2: huff_run_r<SB, G, 2, LONG>(H, T, P0, P1, lane); break;
-    case 4: huff_run_r<SB, G, 4, LONG>(H, T, P0, P1, lane); break;
-    case 8: huff_run_r<SB, G, 8, LONG>(H, T, P0, P1, lane); break;
-    case 16: if (G >= 16) huff_run_r<SB, G, (G >= 16 ? 16 : G), LONG>(H, T, P0, P1, lane); break;
-    default: if (G >= 32) huff_run_r<SB, G, (G >= 32 ? 32 : G), LONG>(H, T, P0, P1, lane); break;
+    case 2: huff_run_r<SB, G, 2, LONG>(H, T, P0, P1, lane, nsym, nsym_next); break;
+    case 4: huff_run_r<SB, G, 4, LONG>(H, T, P0, P1, lane, nsym, nsym_next); break;
+    case 8: huff_run_r<SB, G, 8, LONG>(H, T, P0, P1, lane, nsym, nsym_next); break;
+    case 16: if (G >= 16) huff_run_r<SB, G, (G >= 16 ? 16 : G), LONG>(H, T, P0, P1, lane, nsym, nsym_next); break;
+    default: if (G >= 32) huff_run_r<SB, G, (G >= 32 ? 32 : G), LONG>(H, T, P0, P1, lane, nsym, nsym_next); break;
     }
 }
 
 template <int SB, int G>
-__device__ __forceinline__ void huff_run(HuffStream &H, const FieldTab &T, uint32_t period, uint64_t &P0, uint64_t &P1, uint32_t lane)
+__device__ __forceinline__ void huff_run(HuffStream &H, const FieldTab &T, uint32_t period, uint64_t &P0, uint64_t &P1, uint32_t lane,
+                                         uint32_t nsym = G, uint32_t nsym_next = G)
 {
     // only refill periods of 2 can come with codes longer than the 11-bit index (longest code > 11 bits)
-    if (period == 2 && T.lmax > (uint32_t)kLutBits) huff_run_r<SB, G, 2, true>(H, T, P0, P1, lane);
-    else huff_run_l<SB, G, false>(H, T, period, P0, P1, lane);
+    if (period == 2 && T.lmax > (uint32_t)kLutBits) huff_run_r<SB, G, 2, true>(H, T, P0, P1, lane, nsym, nsym_next);
+    else huff_run_l<SB, G, false>(H, T, period, P0, P1, lane, nsym, nsym_next);
+}
+
+// One plainly stored field of the run a lane owns in the row after a chunk's last whole row (the row a short last
+// chunk, or a chunk size that is not whole rows, ends with): nsym of its G symbols exist.  Flat code: every step of
+// 32 / SB symbols hands one word to each lane that owns a symbol there, in lane order, after the words of the whole
+// rows; raw: the run's words lie where they would in a whole row.  What the lane does not own is never stored.
+template <int SB, int G>
+__device__ __forceinline__ void plain_tail(uint32_t kind, __amdgpu_buffer_rsrc_t rs, uint32_t whole_rows, uint32_t lane, uint32_t nsym, uint64_t konst,
+                                           uint64_t &P0, uint64_t &P1)
+{
+    constexpr int WPR = G * SB / 32;
+    if (kind != KIND_FLAT && kind != KIND_RAW) { P0 = konst; P1 = konst; return; }
+    uint32_t w[WPR];
+    uint32_t at = whole_rows * WPR * 64;                  // words of the stream before this row
+#pragma unroll
+    for (int h = 0; h < WPR; h++) {
+        if (kind == KIND_FLAT) {
+            const bool owner = (uint32_t)(h * (32 / SB)) < nsym;
+            const uint64_t bm = __ballot(owner);
+            const uint32_t v = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(owner ? (at + prefix_count64(bm)) * 4 : 0xFFFFFFF0u), 0, 0);
+            w[h] = reverse_in_groups<SB>(v);
+            at += (uint32_t)__popcll(bm);
+        } else w[h] = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(((whole_rows * 64 + lane) * WPR + h) * 4), 0, 0);
+    }
+    P0 = (uint64_t)w[0] | ((uint64_t)w[1] << 32);
+    if (WPR == 4) P1 = (uint64_t)w[2] | ((uint64_t)w[3] << 32);
 }
 
 // One field of one run when it is not table decoded, in two steps so that the loads of a row can be in flight while the
@@ -468,16 +504,22 @@ __device__ __forceinline__ bool stream_range(const TensorDev &d, const uint8_t *
 // block scales).  Only for chunks whose element fields are both stored plainly (flat code, raw or constant):
 // their rows do not depend on each other, and four times the wavefronts hide four times the memory latency,
 // which is what a small set (few chunks per SIMD) is bound by.
-template <int FMT, bool XOR, bool SPLIT>
-__global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single)
+//
+// TAIL: the launch is over chunks that need not be whole rows: the short last chunk of a tensor, or every chunk of a
+// tensor whose chunk size is not a multiple of 1 KiB.  Their whole rows are decoded as above; the row after them, in
+// which a lane owns a whole run, part of one or nothing, takes its stream words by the same rule with the lanes that
+// own nothing left out, and is stored byte by byte where a run is cut.  Formats with two fields only.
+template <int FMT, bool XOR, bool SPLIT, bool TAIL>
+__global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single, uint32_t first_slot)
 {
     constexpr bool split = SPLIT;
     using F_ = Fmt<FMT>;
+    static_assert(!TAIL || (F_::NF == 2 && !SPLIT), "the tail build has no scale field and no shared chunks");
     extern __shared__ __attribute__((aligned(16))) uint32_t rings[];     // [ring][wave][kRing2Words], sized by the host
     __shared__ FieldTab tab[F_::NF];
     __shared__ TensorDev dsh;
     WorkItem it;
-    if (use_single) { it.tensor = 0; it.first = blockIdx.x * (split ? 1u : kWavesPerGroup); }
+    if (use_single) { it.tensor = 0; it.first = first_slot + blockIdx.x * (split ? 1u : kWavesPerGroup); }
     else it = work[blockIdx.x];
     if (threadIdx.x == 0) dsh = use_single ? single : descs[it.tensor];
     __syncthreads();
@@ -491,8 +533,14 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     const uint32_t chunk = uniform32(it.first + (split ? 0u : wave));
     const uint32_t cb = uniform32(d.chunk_bytes);
     const uint32_t E = cb * 8 / F_::EB;
-    const uint32_t n_full = (uint32_t)(uniform64(d.n_elems) / E);
-    if (chunk >= n_full) return;
+    const uint64_t n_elems = uniform64(d.n_elems);
+    const uint32_t n_full = (uint32_t)(n_elems / E);
+    if (TAIL ? chunk >= uniform32(d.n_chunks) : chunk >= n_full) return;
+    // this chunk's elements and bytes: all of cb unless it is the tensor's short last chunk
+    const uint64_t before = (uint64_t)chunk * E;
+    const uint32_t n = (!TAIL || n_elems - before >= E) ? E : (uint32_t)(n_elems - before);
+    const uint32_t nbytes = n * F_::EB / 8;                   // two-field formats have whole bytes per element
+    if (TAIL && n_elems <= before) return;
     const uint8_t *comp = reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.comp));
     const uint64_t payload = uniform64(d.payload_off), total = uniform64(d.total_bytes);
     const uint8_t *sp[F_::NF];
@@ -500,8 +548,18 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     for (int f = 0; f < F_::NF; f++)
         if (!stream_range(d, comp, f, chunk, payload, total, sp[f], sb[f])) return;      // damaged index: leave the chunk alone
     const __amdgpu_buffer_rsrc_t r0 = make_rsrc(sp[0], sb[0]), r1 = make_rsrc(sp[1], sb[1]);
-    const __amdgpu_buffer_rsrc_t ds = make_rsrc(reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.dst)) + (uint64_t)chunk * cb, cb);
-    const __amdgpu_buffer_rsrc_t bs = make_rsrc(XOR ? reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.base)) + (uint64_t)chunk * cb : comp, XOR ? cb : 0);
+    uint8_t *const dst_chunk = reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.dst)) + (uint64_t)chunk * cb;
+    const uint8_t *const base_chunk = XOR ? reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.base)) + (uint64_t)chunk * cb : comp;
+    const __amdgpu_buffer_rsrc_t ds = make_rsrc(dst_chunk, nbytes);
+    const __amdgpu_buffer_rsrc_t bs = make_rsrc(base_chunk, XOR ? nbytes : 0);
+    // the row after the whole rows: symbols of this lane's run in it (0 in every lane when the chunk is whole rows)
+    const uint32_t whole_rows = nbytes / 1024;
+    uint32_t tail_sym = 0, tail_bytes = 0;
+    if (TAIL) {
+        const uint32_t at = whole_rows * 1024 + lane * 16;
+        tail_bytes = nbytes > at ? (nbytes - at < 16u ? nbytes - at : 16u) : 0u;
+        tail_sym = (tail_bytes * 8 / F_::EB + F_::GRP - 1) / F_::GRP;         // a last partial group of values is one symbol
+    }
     const uint32_t p0 = uniform32(d.period[0]), p1 = uniform32(d.period[1]);
     const uint64_t K0 = splat(uniform32(d.konst[0]), F_::SB), K1 = splat(uniform32(d.konst[1]), F_::SB);
 
@@ -512,10 +570,11 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     const uint32_t rw = two ? 256u : kRing2Words;
     char *ring0 = reinterpret_cast<char *>(rings) + wave * (rw * 4), *ring1 = ring0 + (two ? kWavesPerGroup * 256 * 4 : 0);
     HuffStream H0, H1;
-    if (!SPLIT && kind[0] == KIND_HUFF) huff_open(H0, tab[0], r0, ring0, lane, rw);
-    if (!SPLIT && kind[1] == KIND_HUFF) huff_open(H1, tab[1], r1, ring1, lane, rw);
+    const bool first = !TAIL || whole_rows > 0 || tail_sym > 0;                  // does this lane own a symbol at step 0?
+    if (!SPLIT && kind[0] == KIND_HUFF) huff_open(H0, tab[0], r0, ring0, lane, rw, first);
+    if (!SPLIT && kind[1] == KIND_HUFF) huff_open(H1, tab[1], r1, ring1, lane, rw, first);
 
-    const uint32_t rows = cb / 1024;                          // 64 lanes x 16 bytes per row
+    const uint32_t rows = TAIL ? whole_rows : cb / 1024;      // 64 lanes x 16 bytes per row
     if (split && (kind[0] == KIND_HUFF || kind[1] == KIND_HUFF)) return;          // the host never asks for this
     uint32_t row_begin = 0, row_end = rows;
     if (split) shared_chunk_rows(rows, F_::NF == 3 ? E / F_::SCALE / 1024 : 0u, wave, row_begin, row_end);
@@ -539,14 +598,29 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
         if (SPLIT || kind[1] != KIND_HUFF) plain_fetch<F_::SB, F_::G>(kind[1], r1, row + 1, lane, w1_next);
         // (the scalar offset of a buffer access is not range checked: the row after the last is the last again)
         if (XOR) base_next = __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(lane * 16), (int)((row + 1 < rows ? row + 1 : row) * 1024), 0);
-        if (!SPLIT && kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, Q0, lane);
+        // the words a lane takes at the end of a row are for its next run: after the last whole row, the tail's
+        const uint32_t next_sym = (TAIL && row + 1 == rows) ? tail_sym : (uint32_t)F_::G;
+        if (!SPLIT && kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, Q0, lane, F_::G, next_sym);
         else plain_finish<F_::SB, F_::G>(kind[0], w0, K0, P0, Q0);
-        if (!SPLIT && kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, Q1, lane);
+        if (!SPLIT && kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, Q1, lane, F_::G, next_sym);
         else plain_finish<F_::SB, F_::G>(kind[1], w1, K1, P1, Q1);
         const uint4 j = join_run4<FMT>(P0, Q0, P1, Q1);
         u32x4 v = {j.x, j.y, j.z, j.w};
         if (XOR) v ^= base;
         __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
+    }
+    if (TAIL && nbytes % 1024) {
+        uint64_t P0 = 0, P1 = 0, Q0 = 0, Q1 = 0;
+        if (kind[0] == KIND_HUFF) huff_run<F_::SB, F_::G>(H0, tab[0], p0, P0, Q0, lane, tail_sym, 0u);
+        else plain_tail<F_::SB, F_::G>(kind[0], r0, whole_rows, lane, tail_sym, K0, P0, Q0);
+        if (kind[1] == KIND_HUFF) huff_run<F_::SB, F_::G>(H1, tab[1], p1, P1, Q1, lane, tail_sym, 0u);
+        else plain_tail<F_::SB, F_::G>(kind[1], r1, whole_rows, lane, tail_sym, K1, P1, Q1);
+        if (tail_bytes) {
+            const uint32_t at = whole_rows * 1024 + lane * 16;
+            uint4 v = join_run4<FMT>(P0, Q0, P1, Q1);
+            if (XOR) v = xor4(v, load_run(base_chunk + at, tail_bytes));
+            store_run(dst_chunk + at, v, tail_bytes);
+        }
     }
 
     if (F_::NF == 3 && !(split && wave != 0)) {
@@ -573,10 +647,21 @@ template <int FMT>
 static int launch_s64_x(bool xor_delta, int split, uint32_t lds_bytes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single, hipStream_t st)
 {
     if (split) {
-        if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single);
-        else hipLaunchKernelGGL((k_decode_s64<FMT, false, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single);
-    } else if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single);
-    else hipLaunchKernelGGL((k_decode_s64<FMT, false, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single);
+        if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, true, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, 0u);
+        else hipLaunchKernelGGL((k_decode_s64<FMT, false, true, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, 0u);
+    } else {
+        if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, false, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, 0u);
+        else hipLaunchKernelGGL((k_decode_s64<FMT, false, false, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, 0u);
+    }
+    return (int)hipGetLastError();
+}
+
+template <int FMT>
+static int launch_s64_tail_x(bool xor_delta, uint32_t lds_bytes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single,
+                             uint32_t first_slot, hipStream_t st)
+{
+    if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, false, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, first_slot);
+    else hipLaunchKernelGGL((k_decode_s64<FMT, false, false, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, first_slot);
     return (int)hipGetLastError();
 }
 
@@ -589,8 +674,9 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split
     hipStream_t st = (hipStream_t)stream;
     const TensorDev s = single ? *single : TensorDev{};
     const int use_single = single ? 1 : 0;
-    const uint32_t lds = kWavesPerGroup * kRing2Words * 4;          // 8 KiB whatever the number of table-decoded fields
+    // the rings of a workgroup take 8 KiB whether one or two fields are table decoded (see huff_open)
     (void)n_rings;
+    const uint32_t lds = kWavesPerGroup * kRing2Words * 4;
     switch (fmt) {
     case ZC_FMT_BF16: return launch_s64_x<ZC_FMT_BF16>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
     case ZC_FMT_FP8_E4M3: return launch_s64_x<ZC_FMT_FP8_E4M3>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
@@ -599,6 +685,25 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split
     case ZC_FMT_FP4_E2M1_MX_BYTES: return launch_s64_x<ZC_FMT_FP4_E2M1_MX_BYTES>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
     case ZC_FMT_FP4_E2M1_NV: return launch_s64_x<ZC_FMT_FP4_E2M1_NV>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
     case ZC_FMT_FP8_E5M2: return launch_s64_x<ZC_FMT_FP8_E5M2>(xor_delta, split ? 1 : 0, lds, d_descs, d_work, n_work, s, use_single, st);
+    default: return 1;
+    }
+}
+
+// The tail build over work items of up to four chunks each (64 lanes, two-field formats), chunks that need not be whole
+// rows.  single: one tensor, work items from chunk first_slot on.
+int launch_decode_s64_tail(uint32_t fmt, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev *single,
+                           uint32_t first_slot, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    const TensorDev s = single ? *single : TensorDev{};
+    const int use_single = single ? 1 : 0;
+    const uint32_t lds = kWavesPerGroup * kRing2Words * 4;
+    switch (fmt) {
+    case ZC_FMT_BF16: return launch_s64_tail_x<ZC_FMT_BF16>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, first_slot, st);
+    case ZC_FMT_FP8_E4M3: return launch_s64_tail_x<ZC_FMT_FP8_E4M3>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, first_slot, st);
+    case ZC_FMT_FP8_E4M3_BYTES: return launch_s64_tail_x<ZC_FMT_FP8_E4M3_BYTES>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, first_slot, st);
+    case ZC_FMT_FP8_E5M2: return launch_s64_tail_x<ZC_FMT_FP8_E5M2>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, first_slot, st);
     default: return 1;
     }
 }

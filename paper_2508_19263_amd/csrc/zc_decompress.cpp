@@ -68,6 +68,14 @@ bool e5m2_s64_ok(const zc_info &info)
     return true;
 }
 
+// Can the 64-lane kernel's build for chunks that are not whole rows decode this container's chunks (a short last chunk,
+// or every chunk when the chunk size is not a multiple of 1 KiB)?  64 lanes, a format of two fields, no empty field.
+bool s64_tail_ok(const zc_info &info)
+{
+    if (info.streams != 64 || info.n_fields != 2 || is_fp4(info.format)) return false;
+    return info.mode[0] != ZC_MODE_EMPTY && info.mode[1] != ZC_MODE_EMPTY;
+}
+
 // Are both element fields stored plainly (flat code, raw, constant)?  Then the rows of a chunk do not depend on
 // each other and the 64-lane kernel may share a chunk among the four wavefronts of a workgroup.
 bool s64_split_ok(const zc_info &info)
@@ -191,8 +199,10 @@ zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *
         first_slot = n_full;
     }
     if (first_slot < slots) {
+        // what is left: chunks that are not whole rows, id lists with 64 lanes, geometries no specialised kernel takes
         const uint32_t n_work = (slots - first_slot + cpi - 1) / cpi;
-        LAUNCH_TRY(launch_decode(info.format, nullptr, nullptr, n_work, cpi, &d, first_slot, stream));
+        if (!by_ids && s64_tail_ok(info)) LAUNCH_TRY(launch_decode_s64_tail(info.format, info.xor_delta != 0, nullptr, nullptr, n_work, &d, first_slot, stream));
+        else LAUNCH_TRY(launch_decode(info.format, nullptr, nullptr, n_work, cpi, &d, first_slot, stream));
     }
     return ZC_OK;
 }
@@ -338,6 +348,10 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
     plan->n_rings = sub ? spg : (bf16_rings ? bf16_rings : rings);
     plan->scattered = 0;
     for (uint32_t t = 0; t < n_tensors; t++) if (tensors[t].d_chunk_ids) plan->scattered = 1;
+    // the second list goes through the 64-lane kernel's build for chunks that are not whole rows when every tensor allows it
+    plan->tail_kernel = plan->scattered ? 0u : 1u;
+    for (uint32_t t = 0; t < n_tensors && plan->tail_kernel; t++)
+        if (tensors[t].info.n_elems && (!s64_tail_ok(tensors[t].info) || tensors[t].info.xor_delta != tensors[0].info.xor_delta)) plan->tail_kernel = 0;
     plan->fast_work_offset = descs_bytes; plan->work_offset = descs_bytes + fast_bytes;
     return ZC_OK;
 }
@@ -366,7 +380,10 @@ zc_status zc_decompress_batch_run(const zc_batch_plan *plan, const void *d_ws, v
         LAUNCH_TRY(launch_decode_bf16_sub(plan->streams, plan->xor_delta != 0, (const TensorDev *)ws,
                                           (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, plan->n_rings, stream));
     else if (plan->n_fast_work) return ZC_ERR_INVALID_ARG;
-    if (plan->n_work)
+    if (plan->n_work && plan->tail_kernel == 1 && plan->streams == 64)
+        LAUNCH_TRY(launch_decode_s64_tail(plan->format, plan->xor_delta != 0, (const TensorDev *)ws, (const WorkItem *)(ws + plan->work_offset), plan->n_work,
+                                          nullptr, 0, stream));
+    else if (plan->n_work)
         LAUNCH_TRY(launch_decode(plan->format, (const TensorDev *)ws, (const WorkItem *)(ws + plan->work_offset), plan->n_work,
                                  chunks_per_work_item(plan->streams), nullptr, 0, stream));
     return ZC_OK;

@@ -146,6 +146,8 @@ int launch_decode_bf16_sub(uint32_t streams, bool xor_delta, const TensorDev *d_
 // any format, 64 lanes per chunk, full chunks (zc_decode_fast.hip); n_rings = element fields that are table decoded (1..2)
 int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                       const TensorDev *single, void *stream);
+int launch_decode_s64_tail(uint32_t fmt, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev *single,
+                           uint32_t first_slot, void *stream);
 // BF16, 64 lanes per chunk, full chunks, exponent field table decoded (refill period 2, 4 or 8), sign+mantissa field table
 // decoded on the same period, flat coded, raw or constant (zc_decode_fast.hip)
 int launch_decode_bf16_s64(uint32_t n_rings, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,

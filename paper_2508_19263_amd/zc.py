@@ -65,7 +65,7 @@ class Tensor(C.Structure):
 class BatchPlan(C.Structure):
     _fields_ = [("format", C.c_uint32), ("streams", C.c_uint32), ("n_tensors", C.c_uint32), ("n_fast_work", C.c_uint32),
                 ("n_work", C.c_uint32), ("fast_kernel", C.c_uint32), ("fast_exp_kind", C.c_uint32), ("fast_sm_kind", C.c_uint32),
-                ("n_rings", C.c_uint32), ("xor_delta", C.c_uint32), ("scattered", C.c_uint32),
+                ("n_rings", C.c_uint32), ("xor_delta", C.c_uint32), ("scattered", C.c_uint32), ("tail_kernel", C.c_uint32),
                 ("fast_work_offset", C.c_uint64), ("work_offset", C.c_uint64)]
 
 
