@@ -178,11 +178,11 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
         run("c2_fp8_byte_symbols_limit_11", zc.FMT_FP8_E4M3_BYTES, set2, n2, 262144, 64, limit=(11, 11, 0), policy=zc.POLICY_AUTO, decode_kernel=S64, compress_kernels="k_hist + k_codes + k_encode (sizes) + k_scan + k_encode")
         run("c2_fp8_plain_symbols_auto", zc.FMT_FP8_E4M3, set2, n2, 262144, 64, policy=zc.POLICY_AUTO, decode_kernel="k_decode_fp8", compress_kernels="k_hist_fp8_lanes + k_codes + k_sizes_fp8_counts + k_scan + k_encode_fp8")
         # the generic paths beside their specialised neighbours: a chunk size that is not whole rows of 1 KiB takes the
-        # generic decoder and encoder (any lane count, ragged chunks)
-        run("c2_fp8_chunks_of_48KiB_plus_16_generic_kernels", zc.FMT_FP8_E4M3, set2, n2, 48 * 1024 + 16, 64, decode_kernel="k_decode", compress_kernels="k_hist + k_codes + k_encode<false> + k_scan + k_encode<true>")
+        # chunks that are not whole rows: the generic encoder, the 64-lane decoder's build for such chunks
+        run("c2_fp8_chunks_of_48KiB_plus_16", zc.FMT_FP8_E4M3, set2, n2, 48 * 1024 + 16, 64, decode_kernel="k_decode_s64<TAIL>", compress_kernels="k_hist + k_codes + k_encode<false> + k_scan + k_encode<true>")
         run("c2_fp8_chunks_of_48KiB_specialised_kernels", zc.FMT_FP8_E4M3, set2, n2, 48 * 1024, 64, decode_kernel="k_decode_fp8", compress_kernels="k_hist + k_codes + k_sizes_fp8 + k_scan + k_encode_fp8")
         ragged = [t[:t.numel() - 4096 - 7 * 16] for t in set2]
-        run("c2_fp8_ragged_tails", zc.FMT_FP8_E4M3, ragged, [t.numel() for t in ragged], 262144, 64, decode_kernel="k_decode_fp8 + k_decode (last chunks)", compress_kernels="k_hist_fp8_lanes + k_hist + k_codes + sizes + k_scan + k_encode_fp8 + k_encode (last chunks)")
+        run("c2_fp8_ragged_tails", zc.FMT_FP8_E4M3, ragged, [t.numel() for t in ragged], 262144, 64, decode_kernel="k_decode_fp8 + k_decode_s64<TAIL> (last chunks)", compress_kernels="k_hist_fp8_lanes + k_hist + k_codes + sizes + k_scan + k_encode_fp8 + k_encode (last chunks)")
         del set2, ragged
         set2 = [t for _, t in wl.fp8_weight_set(32, device=dev, e5m2=True)]
         run("c2_shapes_in_fp8_e5m2", zc.FMT_FP8_E5M2, set2, [t.numel() for t in set2], 262144, 64, decode_kernel=S64, compress_kernels="k_hist + k_codes + k_encode (sizes) + k_scan + k_encode")
