@@ -181,6 +181,11 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
         # chunks that are not whole rows: the generic encoder, the 64-lane decoder's build for such chunks
         run("c2_fp8_chunks_of_48KiB_plus_16", zc.FMT_FP8_E4M3, set2, n2, 48 * 1024 + 16, 64, decode_kernel="k_decode_s64<TAIL>", compress_kernels="k_hist + k_codes + k_encode<false> + k_scan + k_encode<true>")
         run("c2_fp8_chunks_of_48KiB_specialised_kernels", zc.FMT_FP8_E4M3, set2, n2, 48 * 1024, 64, decode_kernel="k_decode_fp8", compress_kernels="k_hist + k_codes + k_sizes_fp8 + k_scan + k_encode_fp8")
+        # random access to the chunks of weights (Sec. 3.1): a seeded quarter of every tensor's 256 KiB chunks, in random order
+        chunk_ids = [wl.page_sample(t.numel() // 262144, 0.25, device=dev, seed=900 + i) for i, t in enumerate(set2)]
+        run("c2_fp8_chunk_list", zc.FMT_FP8_E4M3, set2, n2, 262144, 64, ids=chunk_ids, decode_kernel="k_decode_fp8; the list: k_decode_s64<TAIL>",
+            compress_kernels="k_hist_fp8_lanes + k_codes + k_sizes_fp8_counts + k_scan + k_encode_fp8")
+        del chunk_ids
         ragged = [t[:t.numel() - 4096 - 7 * 16] for t in set2]
         run("c2_fp8_ragged_tails", zc.FMT_FP8_E4M3, ragged, [t.numel() for t in ragged], 262144, 64, decode_kernel="k_decode_fp8 + k_decode_s64<TAIL> (last chunks)", compress_kernels="k_hist_fp8_lanes + k_hist + k_codes + sizes + k_scan + k_encode_fp8 + k_encode (last chunks)")
         del set2, ragged

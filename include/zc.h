@@ -99,7 +99,7 @@ typedef struct {
  *     the short last chunk of a tensor costs a set of tensors a second, small launch (1.1 x for 224 tensors).
  *   - chunks below 16 KiB (K/V pages, Sec. 3.3): 4 to 32 lanes with chunk_bytes a multiple of 16 * lanes.  A
  *     wavefront then decodes 64 / lanes chunks at once; with 64 lanes it decodes one small chunk at a time (a 2 KiB
- *     page: 3.5 x slower from an id list) and every lane's look-ahead words eat the gain (ratio 1.00 against 0.86).
+ *     page: 2.3 x slower from an id list) and every lane's look-ahead words eat the gain (ratio 1.00 against 0.86).
  *   - max_code_len of the exponent field: up to 8 keeps four symbols per refill step for FP8 (the default); 9 to 16
  *     halves the step and costs about 40 % of decode speed for 0.2 % of size on FP8 weights.  For BF16 and for byte
  *     symbols a limit of 11 keeps every code inside the decoders' lookup index (5 to 7 % faster, 0.5 % larger). */
@@ -320,8 +320,9 @@ typedef struct {
                                                    7 FP8 E5M2 with 64 lanes (table-decoded exponents, flat 3-bit sign+mantissa code) */
     uint32_t fast_exp_kind, fast_sm_kind, n_rings /* kernels 3, 5: slots per workgroup */, xor_delta;
     uint32_t scattered;                         /* some tensor decodes an id list */
-    uint32_t tail_kernel;                       /* the second work list (chunks that are not whole rows): 0 generic kernel,
-                                                   1 the 64-lane kernel's build for such chunks (two-field formats) */
+    uint32_t tail_kernel;                       /* the second work list (chunks that are not whole rows, id lists with 64 lanes):
+                                                   0 generic kernel, 1 the 64-lane kernel's build for such chunks (two-field formats),
+                                                   2 = 1 leaving whole chunks to the FP8 kernel's build for id lists */
     uint64_t fast_work_offset, work_offset;     /* byte offsets of the two work lists in d_ws */
 } zc_batch_plan;
 zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors, void *d_ws, uint64_t ws_bytes,

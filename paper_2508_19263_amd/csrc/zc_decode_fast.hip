@@ -94,7 +94,9 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v)
 
 // EK: 0 = one symbol per lookup (codes <= 8 bits, 256 entries), 1 = two symbols per lookup
 //     (codes <= 6 bits, 4096 entries).  MK: 0 = flat 4-bit code, 1 = raw.  XOR: delta container.
-template <int EK, int MK, bool XOR>
+// IDS: a build that also takes tensors with a list of chunk ids (slot i of the output takes chunk ids[i]; whole chunks
+// only: a short last chunk that a list names is left to the 64-lane kernel's build for such chunks).
+template <int EK, int MK, bool XOR, bool IDS>
 __global__ __launch_bounds__(256) void k_decode_fp8(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single)
 {
     constexpr uint32_t kEntries = EK ? 4096u : 256u;
@@ -128,7 +130,15 @@ __global__ __launch_bounds__(256) void k_decode_fp8(const TensorDev *descs, cons
     __syncthreads();
 
     const uint32_t lane = threadIdx.x & 63;
-    const uint32_t chunk = uniform32(it.first + (threadIdx.x >> 6));
+    const uint32_t slot = uniform32(it.first + (threadIdx.x >> 6));
+    uint32_t chunk = slot;
+    if (IDS) {
+        const uint32_t *ids = reinterpret_cast<const uint32_t *>(uniform64((uint64_t)d.ids));
+        if (ids) {
+            if (slot >= uniform32(d.n_ids)) return;
+            chunk = uniform32(ids[slot]);
+        }
+    }
     const uint32_t E = uniform32(d.chunk_bytes);     // one element per byte
     const uint32_t n_full = (uint32_t)(uniform64(d.n_elems) / E);
     if (chunk >= n_full) return;                            // partial or absent chunk: not ours
@@ -145,7 +155,7 @@ __global__ __launch_bounds__(256) void k_decode_fp8(const TensorDev *descs, cons
     if ((b1 - a1) * 16 < (uint64_t)E / 2 || (b0 - a0) * 16 > 0x7FFFFFFFull) return;
     const __amdgpu_buffer_rsrc_t es = make_rsrc(comp + payload + 16 * a0, (uint32_t)((b0 - a0) * 16));
     const __amdgpu_buffer_rsrc_t ms = make_rsrc(comp + payload + 16 * a1, E / 2);
-    const __amdgpu_buffer_rsrc_t ds = make_rsrc(reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.dst)) + (uint64_t)chunk * E, E);
+    const __amdgpu_buffer_rsrc_t ds = make_rsrc(reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.dst)) + (uint64_t)slot * E, E);       // slot == chunk without a list
     const __amdgpu_buffer_rsrc_t bs = make_rsrc(XOR ? reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.base)) + (uint64_t)chunk * E : comp, XOR ? E : 0);
 
     // Ring invariant at the top of every row: words [wbase, wbase + 1024) of the stream are in the
@@ -505,12 +515,13 @@ __device__ __forceinline__ bool stream_range(const TensorDev &d, const uint8_t *
 // their rows do not depend on each other, and four times the wavefronts hide four times the memory latency,
 // which is what a small set (few chunks per SIMD) is bound by.
 //
-// TAIL: the launch is over chunks that need not be whole rows: the short last chunk of a tensor, or every chunk of a
-// tensor whose chunk size is not a multiple of 1 KiB.  Their whole rows are decoded as above; the row after them, in
+// TAIL: the launch is over chunks that need not be whole rows: the short last chunk of a tensor, every chunk of a
+// tensor whose chunk size is not a multiple of 1 KiB, or the chunks a list of ids names (which may include either).  Their whole rows are decoded as above; the row after them, in
 // which a lane owns a whole run, part of one or nothing, takes its stream words by the same rule with the lanes that
 // own nothing left out, and is stored byte by byte where a run is cut.  Formats with two fields only.
 template <int FMT, bool XOR, bool SPLIT, bool TAIL>
-__global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single, uint32_t first_slot)
+__global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single, uint32_t first_slot,
+                                                    uint32_t skip_whole)
 {
     constexpr bool split = SPLIT;
     using F_ = Fmt<FMT>;
@@ -530,12 +541,22 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
         if (kind[f] == KIND_HUFF && !(SPLIT && f < 2)) build_field_tab(tab[f], d.comp + d.table_off[f], 1 << (f == 2 ? 8 : F_::SB), d.lmax[f]);
     }
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t chunk = uniform32(it.first + (split ? 0u : wave));
+    const uint32_t slot = uniform32(it.first + (split ? 0u : wave));
+    uint32_t chunk = slot;
+    if (TAIL) {
+        // a list of chunk ids: slot i of the output takes chunk ids[i]; an id out of range leaves its slot alone
+        const uint32_t *ids = reinterpret_cast<const uint32_t *>(uniform64((uint64_t)d.ids));
+        if (ids) {
+            if (slot >= uniform32(d.n_ids)) return;
+            chunk = uniform32(ids[slot]);
+        }
+    }
     const uint32_t cb = uniform32(d.chunk_bytes);
     const uint32_t E = cb * 8 / F_::EB;
     const uint64_t n_elems = uniform64(d.n_elems);
     const uint32_t n_full = (uint32_t)(n_elems / E);
     if (TAIL ? chunk >= uniform32(d.n_chunks) : chunk >= n_full) return;
+    if (TAIL && skip_whole && chunk < n_full && cb % 1024 == 0) return;        // a specialised kernel took the whole chunks of this launch
     // this chunk's elements and bytes: all of cb unless it is the tensor's short last chunk
     const uint64_t before = (uint64_t)chunk * E;
     const uint32_t n = (!TAIL || n_elems - before >= E) ? E : (uint32_t)(n_elems - before);
@@ -548,7 +569,7 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
     for (int f = 0; f < F_::NF; f++)
         if (!stream_range(d, comp, f, chunk, payload, total, sp[f], sb[f])) return;      // damaged index: leave the chunk alone
     const __amdgpu_buffer_rsrc_t r0 = make_rsrc(sp[0], sb[0]), r1 = make_rsrc(sp[1], sb[1]);
-    uint8_t *const dst_chunk = reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.dst)) + (uint64_t)chunk * cb;
+    uint8_t *const dst_chunk = reinterpret_cast<uint8_t *>(uniform64((uint64_t)d.dst)) + (uint64_t)slot * cb;       // slot == chunk without an id list
     const uint8_t *const base_chunk = XOR ? reinterpret_cast<const uint8_t *>(uniform64((uint64_t)d.base)) + (uint64_t)chunk * cb : comp;
     const __amdgpu_buffer_rsrc_t ds = make_rsrc(dst_chunk, nbytes);
     const __amdgpu_buffer_rsrc_t bs = make_rsrc(base_chunk, XOR ? nbytes : 0);
@@ -647,21 +668,21 @@ template <int FMT>
 static int launch_s64_x(bool xor_delta, int split, uint32_t lds_bytes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single, hipStream_t st)
 {
     if (split) {
-        if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, true, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, 0u);
-        else hipLaunchKernelGGL((k_decode_s64<FMT, false, true, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, 0u);
+        if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, true, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, 0u, 0u);
+        else hipLaunchKernelGGL((k_decode_s64<FMT, false, true, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, 0u, 0u);
     } else {
-        if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, false, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, 0u);
-        else hipLaunchKernelGGL((k_decode_s64<FMT, false, false, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, 0u);
+        if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, false, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, 0u, 0u);
+        else hipLaunchKernelGGL((k_decode_s64<FMT, false, false, false>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, 0u, 0u);
     }
     return (int)hipGetLastError();
 }
 
 template <int FMT>
 static int launch_s64_tail_x(bool xor_delta, uint32_t lds_bytes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single,
-                             uint32_t first_slot, hipStream_t st)
+                             uint32_t first_slot, uint32_t skip_whole, hipStream_t st)
 {
-    if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, false, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, first_slot);
-    else hipLaunchKernelGGL((k_decode_s64<FMT, false, false, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, first_slot);
+    if (xor_delta) hipLaunchKernelGGL((k_decode_s64<FMT, true, false, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, first_slot, skip_whole);
+    else hipLaunchKernelGGL((k_decode_s64<FMT, false, false, true>), dim3(n_work), dim3(256), lds_bytes, st, d_descs, d_work, s, use_single, first_slot, skip_whole);
     return (int)hipGetLastError();
 }
 
@@ -690,9 +711,10 @@ int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split
 }
 
 // The tail build over work items of up to four chunks each (64 lanes, two-field formats), chunks that need not be whole
-// rows.  single: one tensor, work items from chunk first_slot on.
+// rows.  single: one tensor, work items from chunk first_slot on.  skip_whole: leave whole chunks alone (a specialised
+// kernel with an id list has taken them; only what it leaves, a short last chunk, is decoded here).
 int launch_decode_s64_tail(uint32_t fmt, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev *single,
-                           uint32_t first_slot, void *stream)
+                           uint32_t first_slot, bool skip_whole, void *stream)
 {
     if (n_work == 0) return 0;
     hipStream_t st = (hipStream_t)stream;
@@ -700,10 +722,10 @@ int launch_decode_s64_tail(uint32_t fmt, bool xor_delta, const TensorDev *d_desc
     const int use_single = single ? 1 : 0;
     const uint32_t lds = kWavesPerGroup * kRing2Words * 4;
     switch (fmt) {
-    case ZC_FMT_BF16: return launch_s64_tail_x<ZC_FMT_BF16>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, first_slot, st);
-    case ZC_FMT_FP8_E4M3: return launch_s64_tail_x<ZC_FMT_FP8_E4M3>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, first_slot, st);
-    case ZC_FMT_FP8_E4M3_BYTES: return launch_s64_tail_x<ZC_FMT_FP8_E4M3_BYTES>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, first_slot, st);
-    case ZC_FMT_FP8_E5M2: return launch_s64_tail_x<ZC_FMT_FP8_E5M2>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, first_slot, st);
+    case ZC_FMT_BF16: return launch_s64_tail_x<ZC_FMT_BF16>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, first_slot, skip_whole ? 1u : 0u, st);
+    case ZC_FMT_FP8_E4M3: return launch_s64_tail_x<ZC_FMT_FP8_E4M3>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, first_slot, skip_whole ? 1u : 0u, st);
+    case ZC_FMT_FP8_E4M3_BYTES: return launch_s64_tail_x<ZC_FMT_FP8_E4M3_BYTES>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, first_slot, skip_whole ? 1u : 0u, st);
+    case ZC_FMT_FP8_E5M2: return launch_s64_tail_x<ZC_FMT_FP8_E5M2>(xor_delta, lds, d_descs, d_work, n_work, s, use_single, first_slot, skip_whole ? 1u : 0u, st);
     default: return 1;
     }
 }
@@ -1471,25 +1493,31 @@ int launch_decode_bf16_sub(uint32_t streams, bool xor_delta, const TensorDev *d_
 }
 
 template <int EK, int MK>
-static int launch_fp8_x(bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single, hipStream_t st)
+static int launch_fp8_x(bool xor_delta, bool with_ids, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev &s, int use_single, hipStream_t st)
 {
-    if (xor_delta) hipLaunchKernelGGL((k_decode_fp8<EK, MK, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single);
-    else hipLaunchKernelGGL((k_decode_fp8<EK, MK, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single);
+    if (with_ids) {
+        if (xor_delta) hipLaunchKernelGGL((k_decode_fp8<EK, MK, true, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single);
+        else hipLaunchKernelGGL((k_decode_fp8<EK, MK, false, true>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single);
+    } else {
+        if (xor_delta) hipLaunchKernelGGL((k_decode_fp8<EK, MK, true, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single);
+        else hipLaunchKernelGGL((k_decode_fp8<EK, MK, false, false>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, s, use_single);
+    }
     return (int)hipGetLastError();
 }
 
-// exp_kind: 0 = single lookups, 1 = pair lookups; sm_kind: 0 = flat code, 1 = raw
-int launch_decode_fp8_fast(int exp_kind, int sm_kind, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+// exp_kind: 0 = single lookups, 1 = pair lookups; sm_kind: 0 = flat code, 1 = raw; with_ids: some tensor has a list of
+// chunk ids (the build that looks for one)
+int launch_decode_fp8_fast(int exp_kind, int sm_kind, bool xor_delta, bool with_ids, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                            const TensorDev *single, void *stream)
 {
     if (n_work == 0) return 0;
     hipStream_t st = (hipStream_t)stream;
     const TensorDev s = single ? *single : TensorDev{};
     const int use_single = single ? 1 : 0;
-    if (exp_kind == 0 && sm_kind == 0) return launch_fp8_x<0, 0>(xor_delta, d_descs, d_work, n_work, s, use_single, st);
-    if (exp_kind == 0 && sm_kind == 1) return launch_fp8_x<0, 1>(xor_delta, d_descs, d_work, n_work, s, use_single, st);
-    if (exp_kind == 1 && sm_kind == 0) return launch_fp8_x<1, 0>(xor_delta, d_descs, d_work, n_work, s, use_single, st);
-    return launch_fp8_x<1, 1>(xor_delta, d_descs, d_work, n_work, s, use_single, st);
+    if (exp_kind == 0 && sm_kind == 0) return launch_fp8_x<0, 0>(xor_delta, with_ids, d_descs, d_work, n_work, s, use_single, st);
+    if (exp_kind == 0 && sm_kind == 1) return launch_fp8_x<0, 1>(xor_delta, with_ids, d_descs, d_work, n_work, s, use_single, st);
+    if (exp_kind == 1 && sm_kind == 0) return launch_fp8_x<1, 0>(xor_delta, with_ids, d_descs, d_work, n_work, s, use_single, st);
+    return launch_fp8_x<1, 1>(xor_delta, with_ids, d_descs, d_work, n_work, s, use_single, st);
 }
 
 }  // namespace zc

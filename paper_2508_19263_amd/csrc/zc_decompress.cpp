@@ -189,7 +189,7 @@ zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *
         // full chunks through a specialised kernel, a short last chunk through the generic one
         const uint32_t n_full = (uint32_t)(info.n_elems / ((uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(info.format)));
         const uint32_t n_fast = (n_full + kWavesPerGroup - 1) / kWavesPerGroup;
-        if (fk.ok) LAUNCH_TRY(launch_decode_fp8_fast(fk.exp_kind, fk.sm_kind, info.xor_delta != 0, nullptr, nullptr, n_fast, &d, stream));
+        if (fk.ok) LAUNCH_TRY(launch_decode_fp8_fast(fk.exp_kind, fk.sm_kind, info.xor_delta != 0, false, nullptr, nullptr, n_fast, &d, stream));
         else if (e5m2_s64_ok(info)) LAUNCH_TRY(launch_decode_e5m2(info.xor_delta != 0, nullptr, nullptr, n_fast, &d, stream));
         else if (bf16_s64_rings(info)) LAUNCH_TRY(launch_decode_bf16_s64(bf16_s64_rings(info), info.xor_delta != 0, nullptr, nullptr, n_fast, &d, stream));
         else {
@@ -197,11 +197,19 @@ zc_status decode_common(const void *d_comp, uint64_t comp_bytes, const zc_info *
             LAUNCH_TRY(launch_decode_s64(info.format, rings, info.xor_delta != 0, split, nullptr, nullptr, split ? n_full : n_fast, &d, stream));
         }
         first_slot = n_full;
+    } else if (fk.ok && by_ids) {
+        // a list over a container the FP8 kernel takes: the whole chunks it names through that kernel's build for lists;
+        // the short last chunk, if there is one (the list may name it), through the 64-lane kernel's build for such chunks
+        LAUNCH_TRY(launch_decode_fp8_fast(fk.exp_kind, fk.sm_kind, info.xor_delta != 0, true, nullptr, nullptr, (n_ids + kWavesPerGroup - 1) / kWavesPerGroup, &d, stream));
+        if (info.n_elems % elems_per_chunk)
+            LAUNCH_TRY(launch_decode_s64_tail(info.format, info.xor_delta != 0, nullptr, nullptr, (n_ids + cpi - 1) / cpi, &d, 0, true, stream));
+        first_slot = slots;
     }
     if (first_slot < slots) {
-        // what is left: chunks that are not whole rows, id lists with 64 lanes, geometries no specialised kernel takes
+        // what is left: chunks that are not whole rows and id lists with 64 lanes (the 64-lane kernel's build for those, for
+        // the formats of two fields), geometries no specialised kernel takes
         const uint32_t n_work = (slots - first_slot + cpi - 1) / cpi;
-        if (!by_ids && s64_tail_ok(info)) LAUNCH_TRY(launch_decode_s64_tail(info.format, info.xor_delta != 0, nullptr, nullptr, n_work, &d, first_slot, stream));
+        if (s64_tail_ok(info)) LAUNCH_TRY(launch_decode_s64_tail(info.format, info.xor_delta != 0, nullptr, nullptr, n_work, &d, first_slot, false, stream));
         else LAUNCH_TRY(launch_decode(info.format, nullptr, nullptr, n_work, cpi, &d, first_slot, stream));
     }
     return ZC_OK;
@@ -322,12 +330,19 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
         descs[t].dst_bytes = x.d_chunk_ids ? (uint64_t)x.n_chunk_ids * info.chunk_bytes : raw;
         const uint32_t slots = x.d_chunk_ids ? x.n_chunk_ids : info.n_chunks;
         uint32_t first_generic = 0;
+        const uint64_t per_chunk = (uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(fmt);
         if (fast && (sub || !x.d_chunk_ids)) {
-            const uint32_t n_full = (uint32_t)(info.n_elems / ((uint64_t)info.chunk_bytes * 8 / (uint64_t)elem_bits(fmt)));
+            const uint32_t n_full = (uint32_t)(info.n_elems / per_chunk);
             const uint32_t n_fast = x.d_chunk_ids ? slots : n_full;        // lists reach here only when every chunk is whole
             for (uint32_t c = 0; c < n_fast; c += spg) fast_work.push_back({t, c});
             first_generic = n_fast;
-        }                                                                   // an id list with 64-lane chunks goes through the generic kernel
+        } else if (fk.ok && x.d_chunk_ids) {
+            // a list over a container the FP8 kernel takes: every slot to that kernel's build for lists, which takes the
+            // whole chunks; every slot to the second list too when the tensor has a short last chunk the list may name
+            // (the build for such chunks then skips the whole ones)
+            for (uint32_t c = 0; c < slots; c += spg) fast_work.push_back({t, c});
+            if (info.n_elems % per_chunk == 0) first_generic = slots;
+        }                                                                   // any other id list with 64-lane chunks goes to the second list
         for (uint32_t c = first_generic; c < slots; c += cpi) work.push_back({t, c});
     }
     order_for_xcds(fast_work);
@@ -348,10 +363,13 @@ zc_status zc_decompress_batch_plan(const zc_tensor *tensors, uint32_t n_tensors,
     plan->n_rings = sub ? spg : (bf16_rings ? bf16_rings : rings);
     plan->scattered = 0;
     for (uint32_t t = 0; t < n_tensors; t++) if (tensors[t].d_chunk_ids) plan->scattered = 1;
-    // the second list goes through the 64-lane kernel's build for chunks that are not whole rows when every tensor allows it
-    plan->tail_kernel = plan->scattered ? 0u : 1u;
+    // the second list (chunks that are not whole rows, id lists with 64 lanes) goes through the 64-lane kernel's build for
+    // such chunks when every tensor allows it
+    plan->tail_kernel = 1;
     for (uint32_t t = 0; t < n_tensors && plan->tail_kernel; t++)
         if (tensors[t].info.n_elems && (!s64_tail_ok(tensors[t].info) || tensors[t].info.xor_delta != tensors[0].info.xor_delta)) plan->tail_kernel = 0;
+    // lists over containers the FP8 kernel takes: that kernel has the whole chunks of the second list
+    if (plan->tail_kernel && fk.ok && plan->scattered) plan->tail_kernel = 2;
     plan->fast_work_offset = descs_bytes; plan->work_offset = descs_bytes + fast_bytes;
     return ZC_OK;
 }
@@ -363,7 +381,7 @@ zc_status zc_decompress_batch_run(const zc_batch_plan *plan, const void *d_ws, v
     if (!d_ws || !elem_bits(plan->format) || plan->streams == 0 || plan->streams > 64 || (plan->streams & (plan->streams - 1))) return ZC_ERR_INVALID_ARG;
     const uint8_t *ws = (const uint8_t *)d_ws;
     if (plan->n_fast_work && plan->fast_kernel == 1)
-        LAUNCH_TRY(launch_decode_fp8_fast((int)plan->fast_exp_kind, (int)plan->fast_sm_kind, plan->xor_delta != 0, (const TensorDev *)ws,
+        LAUNCH_TRY(launch_decode_fp8_fast((int)plan->fast_exp_kind, (int)plan->fast_sm_kind, plan->xor_delta != 0, plan->scattered != 0, (const TensorDev *)ws,
                                           (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, stream));
     else if (plan->n_fast_work && (plan->fast_kernel == 2 || plan->fast_kernel == 4))
         LAUNCH_TRY(launch_decode_s64(plan->format, plan->n_rings, plan->xor_delta != 0, plan->fast_kernel == 4, (const TensorDev *)ws,
@@ -380,9 +398,9 @@ zc_status zc_decompress_batch_run(const zc_batch_plan *plan, const void *d_ws, v
         LAUNCH_TRY(launch_decode_bf16_sub(plan->streams, plan->xor_delta != 0, (const TensorDev *)ws,
                                           (const WorkItem *)(ws + plan->fast_work_offset), plan->n_fast_work, nullptr, plan->n_rings, stream));
     else if (plan->n_fast_work) return ZC_ERR_INVALID_ARG;
-    if (plan->n_work && plan->tail_kernel == 1 && plan->streams == 64)
+    if (plan->n_work && (plan->tail_kernel == 1 || plan->tail_kernel == 2) && plan->streams == 64)
         LAUNCH_TRY(launch_decode_s64_tail(plan->format, plan->xor_delta != 0, (const TensorDev *)ws, (const WorkItem *)(ws + plan->work_offset), plan->n_work,
-                                          nullptr, 0, stream));
+                                          nullptr, 0, plan->tail_kernel == 2, stream));
     else if (plan->n_work)
         LAUNCH_TRY(launch_decode(plan->format, (const TensorDev *)ws, (const WorkItem *)(ws + plan->work_offset), plan->n_work,
                                  chunks_per_work_item(plan->streams), nullptr, 0, stream));

@@ -135,7 +135,7 @@ int launch_encode(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_d
 int launch_decode(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t chunks_per_item,
                   const TensorDev *single, uint32_t first_slot, void *stream);
 // specialised FP8 decode of full chunks (zc_decode_fast.hip); exp_kind 0 = single, 1 = pair lookups; sm_kind 0 = flat, 1 = raw
-int launch_decode_fp8_fast(int exp_kind, int sm_kind, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+int launch_decode_fp8_fast(int exp_kind, int sm_kind, bool xor_delta, bool with_ids, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                            const TensorDev *single, void *stream);
 // FP8, fewer than 64 lanes per chunk (pages), optional id list (zc_decode_fast.hip)
 int launch_decode_fp8_sub(uint32_t streams, bool xor_delta, bool scattered, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
@@ -147,7 +147,7 @@ int launch_decode_bf16_sub(uint32_t streams, bool xor_delta, const TensorDev *d_
 int launch_decode_s64(uint32_t fmt, uint32_t n_rings, bool xor_delta, bool split, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                       const TensorDev *single, void *stream);
 int launch_decode_s64_tail(uint32_t fmt, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const TensorDev *single,
-                           uint32_t first_slot, void *stream);
+                           uint32_t first_slot, bool skip_whole, void *stream);
 // BF16, 64 lanes per chunk, full chunks, exponent field table decoded (refill period 2, 4 or 8), sign+mantissa field table
 // decoded on the same period, flat coded, raw or constant (zc_decode_fast.hip)
 int launch_decode_bf16_s64(uint32_t n_rings, bool xor_delta, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,

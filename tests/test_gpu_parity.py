@@ -1018,6 +1018,51 @@ def test_random_sweep_of_the_other_entry_points():
                 assert np.array_equal(sc_out.cpu().numpy()[i * spc:i * spc + (s_hi - s_lo)], sb.numpy()[s_lo:s_hi]), ("scales", i, c)
 
 
+def test_random_sweep_of_chunk_lists_over_batches():
+    # sets of tensors decoded through lists of chunk ids (repeated ids, ids out of range, the short last chunk) in one
+    # batch call: 64 lanes with whole rows (the specialised kernels' builds for lists), with odd chunk sizes, and pages
+    rng = np.random.default_rng(20261201)
+    fmts = (zc.FMT_FP8_E4M3, zc.FMT_BF16, zc.FMT_FP8_E4M3, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP8_E5M2, zc.FMT_FP8_E4M3)
+    for case in range(240):
+        fmt = fmts[case % len(fmts)]
+        shape = int(rng.integers(0, 3))
+        if shape == 0:
+            S, cb = 64, 1024 * int(rng.integers(1, 9))
+        elif shape == 1:
+            S = int(2 ** rng.integers(2, 6))
+            cb = 16 * S * int(rng.integers(1, 9))
+        else:
+            S, cb = 64, 16 * int(rng.integers(1, 200))
+        E = cb * 8 // zc.elem_bits(fmt)
+        policy = int(rng.integers(0, 2))
+        whole_only = rng.integers(0, 2)
+        ns, srcs, ids = [], [], []
+        for _ in range(int(rng.integers(1, 7))):
+            n = int(rng.integers(1, 6)) * E if (whole_only or rng.integers(0, 2)) else int(rng.integers(1, 5 * E + 2))
+            ns.append(n)
+            srcs.append(_random_source(rng, fmt, n)[0])
+            nc = (n + E - 1) // E
+            ids.append(rng.integers(0, nc + (2 if rng.integers(0, 4) == 0 else 0), int(rng.integers(1, 2 * nc + 2))).astype(np.int32))
+        print("chunk lists", case, "fmt", fmt, "S", S, "chunk", cb, "n", ns, "policy", policy, flush=True)
+        b = zc.Batch([dev(x) for x in srcs], ns, zc.params(fmt, cb, (0, 0, 0), S, policy))
+        b.compress()
+        b.set_chunk_ids([torch.from_numpy(i).to(DEV) for i in ids])
+        for out in b.out:
+            out.fill_(0xA5)
+        b.decompress()
+        torch.cuda.synchronize()
+        for t in range(len(ns)):
+            flat = srcs[t].numpy().reshape(-1).view(np.uint8)
+            nc = (ns[t] + E - 1) // E
+            rows = b.out[t].cpu().numpy()[:len(ids[t]) * cb].reshape(len(ids[t]), cb)
+            for i, c in enumerate(ids[t]):
+                if c >= nc:
+                    assert (rows[i] == 0xA5).all(), ("a slot of an id out of range was written", t, i, c)
+                    continue
+                lo, hi = int(c) * cb, min(int(c) * cb + cb, flat.size)
+                assert np.array_equal(rows[i][:hi - lo], flat[lo:hi]), (t, i, c)
+
+
 def test_random_sweep_fp8_chunks_of_one_histogram_block():
     # the same kind of sweep over the one shape whose size pass works from per-lane counts: FP8, 64 lanes, 256 KiB
     rng = np.random.default_rng(20251127)
