@@ -639,7 +639,10 @@ def test_damaged_payload_and_index_do_not_escape_the_buffers():
              (zc.FMT_BF16, 24 * 2048, 4096, 8, A, False), (zc.FMT_BF16, 5 * 131072, 262144, 64, H, True),
              (zc.FMT_FP8_E4M3, 64 * 2048, 2048, 8, A, True),
              # the E5M2 kernel, and the BF16 64-lane kernel with a raw sign+mantissa field
-             (zc.FMT_FP8_E5M2, 8 * 65536, 65536, 64, H, False), (zc.FMT_BF16, 6 * 8192, 16384, 64, A, False)]
+             (zc.FMT_FP8_E5M2, 8 * 65536, 65536, 64, H, False), (zc.FMT_BF16, 6 * 8192, 16384, 64, A, False),
+             # 64 lanes with a short last chunk, and with a chunk size that is not whole rows (the build for such chunks)
+             (zc.FMT_FP8_E4M3, 5 * 65536 + 1234, 65536, 64, H, False), (zc.FMT_BF16, 3 * 12296 + 777, 24592, 64, H, False),
+             (zc.FMT_FP8_E4M3_BYTES, 4 * 49168 + 50, 49168, 64, A, False)]
     for fmt, n, cb, S, policy, delta in cases:
         if delta and fmt == zc.FMT_BF16:
             w0, w1 = wl.bf16_checkpoint_pair(n, seed=23)
