@@ -174,8 +174,8 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
         # config 2 again with byte-grouped symbols (two exponents per symbol; the flat sign+mantissa field raw)
         set2 = [t for _, t in wl.fp8_weight_set(32, device=dev)]
         n2 = [t.numel() for t in set2]
-        run("c2_fp8_byte_symbols", zc.FMT_FP8_E4M3_BYTES, set2, n2, 262144, 64, policy=zc.POLICY_AUTO, decode_kernel=S64, compress_kernels="k_hist + k_codes + k_encode (sizes) + k_scan + k_encode")
-        run("c2_fp8_byte_symbols_limit_11", zc.FMT_FP8_E4M3_BYTES, set2, n2, 262144, 64, limit=(11, 11, 0), policy=zc.POLICY_AUTO, decode_kernel=S64, compress_kernels="k_hist + k_codes + k_encode (sizes) + k_scan + k_encode")
+        run("c2_fp8_byte_symbols", zc.FMT_FP8_E4M3_BYTES, set2, n2, 262144, 64, policy=zc.POLICY_AUTO, decode_kernel=S64, compress_kernels="k_hist + k_codes + k_encode (sizes) + k_scan + k_encode_bf16<BYTES>")
+        run("c2_fp8_byte_symbols_limit_11", zc.FMT_FP8_E4M3_BYTES, set2, n2, 262144, 64, limit=(11, 11, 0), policy=zc.POLICY_AUTO, decode_kernel=S64, compress_kernels="k_hist + k_codes + k_encode (sizes) + k_scan + k_encode_bf16<BYTES>")
         run("c2_fp8_plain_symbols_auto", zc.FMT_FP8_E4M3, set2, n2, 262144, 64, policy=zc.POLICY_AUTO, decode_kernel="k_decode_fp8", compress_kernels="k_hist_fp8_lanes + k_codes + k_sizes_fp8_counts + k_scan + k_encode_fp8")
         # the generic paths beside their specialised neighbours: a chunk size that is not whole rows of 1 KiB takes the
         # chunks that are not whole rows: the generic encoder, the 64-lane decoder's build for such chunks

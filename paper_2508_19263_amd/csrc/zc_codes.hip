@@ -282,8 +282,8 @@ __global__ __launch_bounds__(256) void k_codes_finish(TensorDev *descs, CodePara
         const uint32_t l0 = e0 >> 16, l1 = e1 >> 16;
         enc[512 + u] = ((l0 + l1) << 16) | (e0 & 0xFFFFu) | ((e1 & 0xFFFFu) << l0);
     }
-    // BF16: the 64-lane encoder takes a table-coded exponent field next to a sign+mantissa field that is flat, raw, or
-    // table coded with a refill period of 2 or 4; the page kernels (fewer lanes) want the latter flat or raw and, with
+    // BF16, and FP8 in byte symbols: the 64-lane encoder takes a table-coded exponent field next to a sign+mantissa field
+    // that is flat, raw, or table coded with a refill period of 2 or 4; the BF16 page kernels (fewer lanes) want the latter flat or raw and, with
     // two exponents per refill step, no 1-bit code (the bound on their staging ring needs 4 bits per step)
     __shared__ uint32_t lmin_s;
     if (threadIdx.x == 0) lmin_s = 16;
@@ -292,9 +292,10 @@ __global__ __launch_bounds__(256) void k_codes_finish(TensorDev *descs, CodePara
     if (my_len) atomicMin(&lmin_s, my_len);
     __syncthreads();
     const bool plain_sm = d.kind[1] == 1 || d.kind[1] == 2;
-    const bool bf16 = cp.fmt == ZC_FMT_BF16 && d.fast_shape && d.kind[0] == 0 &&
-                      (d.streams == 64 ? (plain_sm || (d.kind[1] == 0 && (d.period[1] == 2 || d.period[1] == 4)))
-                                       : (plain_sm && (d.period[0] != 2 || lmin_s >= 2)));
+    const bool bf16 = d.fast_shape && d.kind[0] == 0 &&
+                      (d.streams == 64 ? ((cp.fmt == ZC_FMT_BF16 || cp.fmt == ZC_FMT_FP8_E4M3_BYTES) &&
+                                          (plain_sm || (d.kind[1] == 0 && (d.period[1] == 2 || d.period[1] == 4))))
+                                       : (cp.fmt == ZC_FMT_BF16 && plain_sm && (d.period[0] != 2 || lmin_s >= 2)));
     if (threadIdx.x == 0) d.route = fast ? 1 : bf16 ? 2 : 0;
 }
 

@@ -97,6 +97,7 @@ CompressShape compress_shape(const Geometry &g, bool device_codes, uint64_t all_
     sh.lanes = device_codes && lane_counts_shape(g);
     sh.bf16 = g.fmt == ZC_FMT_BF16;
     sh.whole_shape = g.S == 64 && g.chunk_bytes % 1024 == 0;
+    sh.rows8 = sh.whole_shape && (g.fmt == ZC_FMT_BF16 || g.fmt == ZC_FMT_FP8_E4M3_BYTES);
     // FP4 elements rarely compress, so their fields are stored plainly and a chunk's rows can be shared by the four
     // wavefronts of a workgroup: one chunk per work item there
     sh.whole_mode = is_fp4(g.fmt) ? 2 : 1;
@@ -158,7 +159,7 @@ zc_status CompressQueue::queue_encoders() const
     if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs(), d_list(w.fast_work), n_fast, d_enc(), stream));
     else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, sh.bf16, d_descs(), d_list(w.fast_work), n_fast, d_enc(), d_units(), sh.fast_step, stream));
     LAUNCH_TRY(launch_encode(g.fmt, sh.whole_mode, 0x6, d_descs(), d_list(w.whole_work), n_whole, d_enc(), stream));
-    if (sh.bf16) LAUNCH_TRY(launch_encode_bf16(d_descs(), d_list(w.whole_work), n_whole, d_enc(), stream));
+    if (sh.rows8) LAUNCH_TRY(launch_encode_bf16(g.fmt, d_descs(), d_list(w.whole_work), n_whole, d_enc(), stream));
     LAUNCH_TRY(launch_encode(g.fmt, 0, 0x6, d_descs(), d_list(w.other_work), n_other, d_enc(), stream));
     LAUNCH_TRY(launch_encode(g.fmt, 0, 0, d_descs(), d_list(w.chunk_work), n_slow, d_enc(), stream));
     return ZC_OK;
@@ -491,7 +492,7 @@ private:
         const FieldCode no_code[3] = {};
         for (uint32_t t = 0; t < T; t++) {
             const bool fs = fast_shape(t);
-            descs[t].fast_shape = (fs || (sh.bf16 && sh.whole_shape)) ? 1 : 0;
+            descs[t].fast_shape = (fs || sh.rows8) ? 1 : 0;
             const TensorLists L = device_code_lists(g, sh, tensors[t].n_elems, ncs[t], fs);
             append(fast_work, t, L.fast);
             append(whole_work, t, L.whole);
@@ -597,14 +598,14 @@ private:
                 const uint32_t e0 = u & 15, e1 = u >> 4, l0 = fc[0].len[e0], l1 = fc[0].len[e1];
                 enc[(size_t)t * 768 + 512 + u] = ((l0 + l1) << 16) | (enc[(size_t)t * 768 + e0] & 0xFFFFu) | ((enc[(size_t)t * 768 + e1] & 0xFFFFu) << l0);
             }
-        // BF16: the 64-lane encoder takes a table-coded exponent field next to a sign+mantissa field that is flat, raw, or
-        // table coded with a refill period of 2 or 4; the page kernels want the latter flat or raw and, with two
+        // BF16 (and FP8 in byte symbols): the 64-lane encoder takes a table-coded exponent field next to a sign+mantissa field
+        // that is flat, raw, or table coded with a refill period of 2 or 4; the BF16 page kernels want the latter flat or raw and, with two
         // exponents per refill step, no 1-bit code (the bound on their staging ring needs 4 bits per step)
         uint32_t lmin = 16;
         for (int v = 0; v < 256; v++) if (fc[0].len[v] && fc[0].len[v] < lmin) lmin = fc[0].len[v];
-        const bool bf16_ok = sh.bf16 && d.kind[0] == 0 &&
-                             (sh.whole_shape ? (plain_sm || (d.kind[1] == 0 && (d.period[1] == 2 || d.period[1] == 4)))
-                                          : (fast_shape(t) && plain_sm && (d.period[0] != 2 || lmin >= 2)));
+        const bool bf16_ok = d.kind[0] == 0 &&
+                             (sh.whole_shape ? (sh.rows8 && (plain_sm || (d.kind[1] == 0 && (d.period[1] == 2 || d.period[1] == 4))))
+                                          : (sh.bf16 && fast_shape(t) && plain_sm && (d.period[0] != 2 || lmin >= 2)));
         d.route = fast_ok ? 1 : bf16_ok ? 2 : 0;
         return ZC_OK;
     }

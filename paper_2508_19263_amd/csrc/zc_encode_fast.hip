@@ -484,15 +484,18 @@ __device__ __forceinline__ void close_stream(LaneStream &L, __amdgpu_buffer_rsrc
     if (lane < ((4 - (L.wpos & 3)) & 3)) __builtin_amdgcn_raw_buffer_store_b32(0u, out, (int)((L.wpos + lane) * 4), 0, 0);
 }
 
-// R0: refill period of the exponent field; R1: of the sign+mantissa field when it is table coded, 0 when it is flat or raw
-template <int R0, int R1>
+// R0: refill period of the exponent field; R1: of the sign+mantissa field when it is table coded, 0 when it is flat or raw.
+// BYTES: the source is FP8 coded in byte symbols (Sec. 3.2, Fig. 7: the exponents of two consecutive values in one byte,
+// their sign+mantissa values in another), 16 values per run; otherwise BF16, 8 values per run.  Either way a run is 8
+// symbols of 8 bits in each field, which is all the rest of the kernel knows.
+template <int R0, int R1, bool BYTES>
 __device__ __forceinline__ void encode_bf16_chunk(const TensorDev *dp, const WorkItem &it, const uint32_t *enc)
 {
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t chunk = uni32(it.first + (threadIdx.x >> 6));
     const uint32_t cb = uni32(dp->chunk_bytes);
     const uint64_t n_elems = uni64(dp->n_elems);
-    if (chunk >= (uint32_t)(n_elems / (cb / 2))) return;
+    if (chunk >= (uint32_t)(n_elems / (BYTES ? cb : cb / 2))) return;
     const bool has_base = uni64((uint64_t)dp->base) != 0;
     const bool sm_raw = uni32(dp->kind[1]) == 2;
     uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
@@ -521,11 +524,20 @@ __device__ __forceinline__ void encode_bf16_chunk(const TensorDev *dp, const Wor
         uint32_t ex[2], sm[2];
 #pragma unroll
         for (int h = 0; h < 2; h++) {
-            const uint32_t lo = v[2 * h], hi = v[2 * h + 1];            // values 4h, 4h+1 | 4h+2, 4h+3
-            const uint32_t el = lo >> 7, eh = hi >> 7;                    // exponents in byte 0 and byte 2
-            ex[h] = __builtin_amdgcn_perm(eh, el, 0x06040200u);          // bytes: el.b0, el.b2, eh.b0, eh.b2
-            const uint32_t ml = ((lo >> 8) & 0x00800080u) | (lo & 0x007F007Fu), mh = ((hi >> 8) & 0x00800080u) | (hi & 0x007F007Fu);
-            sm[h] = __builtin_amdgcn_perm(mh, ml, 0x06040200u);
+            const uint32_t lo = v[2 * h], hi = v[2 * h + 1];            // BF16: values 4h, 4h+1 | 4h+2, 4h+3; FP8: 8h .. 8h+3 | 8h+4 .. 8h+7
+            if (BYTES) {
+                // a value is s eeee mmm: the exponent nibbles and the sign+mantissa nibbles of the even and of the odd
+                // bytes, gathered with byte permutes, make the pair symbols (first value in the low four bits)
+                const uint32_t e0 = (lo >> 3) & 0x0F0F0F0Fu, e1 = (hi >> 3) & 0x0F0F0F0Fu;
+                ex[h] = __builtin_amdgcn_perm(e1, e0, 0x06040200u) | (__builtin_amdgcn_perm(e1, e0, 0x07050301u) << 4);
+                const uint32_t m0 = ((lo >> 4) & 0x08080808u) | (lo & 0x07070707u), m1 = ((hi >> 4) & 0x08080808u) | (hi & 0x07070707u);
+                sm[h] = __builtin_amdgcn_perm(m1, m0, 0x06040200u) | (__builtin_amdgcn_perm(m1, m0, 0x07050301u) << 4);
+            } else {
+                const uint32_t el = lo >> 7, eh = hi >> 7;                    // exponents in byte 0 and byte 2
+                ex[h] = __builtin_amdgcn_perm(eh, el, 0x06040200u);          // bytes: el.b0, el.b2, eh.b0, eh.b2
+                const uint32_t ml = ((lo >> 8) & 0x00800080u) | (lo & 0x007F007Fu), mh = ((hi >> 8) & 0x00800080u) | (hi & 0x007F007Fu);
+                sm[h] = __builtin_amdgcn_perm(mh, ml, 0x06040200u);
+            }
         }
         if (R1 == 0) {
             if (sm_raw) __builtin_amdgcn_raw_buffer_store_b64(u32x2{sm[0], sm[1]}, ms, (int)(lane * 8), (int)(row * 512), 0);
@@ -560,6 +572,7 @@ __device__ __forceinline__ void encode_bf16_chunk(const TensorDev *dp, const Wor
     if (R1 != 0) close_stream(M, ms, lane);
 }
 
+template <bool BYTES>
 __global__ __launch_bounds__(256) void k_encode_bf16(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables)
 {
     __shared__ uint32_t enc[512];
@@ -571,23 +584,25 @@ __global__ __launch_bounds__(256) void k_encode_bf16(const TensorDev *descs, con
     __syncthreads();
     const uint32_t r0 = uni32(dp->period[0]), r1 = uni32(dp->kind[1]) == 0 ? uni32(dp->period[1]) : 0u;
     switch (r0 * 16 + r1) {
-    case 0x20: encode_bf16_chunk<2, 0>(dp, it, enc); break;
-    case 0x40: encode_bf16_chunk<4, 0>(dp, it, enc); break;
-    case 0x80: encode_bf16_chunk<8, 0>(dp, it, enc); break;
-    case 0x22: encode_bf16_chunk<2, 2>(dp, it, enc); break;
-    case 0x42: encode_bf16_chunk<4, 2>(dp, it, enc); break;
-    case 0x82: encode_bf16_chunk<8, 2>(dp, it, enc); break;
-    case 0x24: encode_bf16_chunk<2, 4>(dp, it, enc); break;
-    case 0x44: encode_bf16_chunk<4, 4>(dp, it, enc); break;
-    case 0x84: encode_bf16_chunk<8, 4>(dp, it, enc); break;
+    case 0x20: encode_bf16_chunk<2, 0, BYTES>(dp, it, enc); break;
+    case 0x40: encode_bf16_chunk<4, 0, BYTES>(dp, it, enc); break;
+    case 0x80: encode_bf16_chunk<8, 0, BYTES>(dp, it, enc); break;
+    case 0x22: encode_bf16_chunk<2, 2, BYTES>(dp, it, enc); break;
+    case 0x42: encode_bf16_chunk<4, 2, BYTES>(dp, it, enc); break;
+    case 0x82: encode_bf16_chunk<8, 2, BYTES>(dp, it, enc); break;
+    case 0x24: encode_bf16_chunk<2, 4, BYTES>(dp, it, enc); break;
+    case 0x44: encode_bf16_chunk<4, 4, BYTES>(dp, it, enc); break;
+    case 0x84: encode_bf16_chunk<8, 4, BYTES>(dp, it, enc); break;
     default: break;                                              // the route is only given for these combinations
     }
 }
 
-int launch_encode_bf16(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)
+// fmt: ZC_FMT_BF16, or ZC_FMT_FP8_E4M3_BYTES (the same encoder over FP8 values split into byte symbols)
+int launch_encode_bf16(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)
 {
     if (n_work == 0) return 0;
-    hipLaunchKernelGGL(k_encode_bf16, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc);
+    if (fmt == ZC_FMT_FP8_E4M3_BYTES) hipLaunchKernelGGL(k_encode_bf16<true>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc);
+    else hipLaunchKernelGGL(k_encode_bf16<false>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc);
     return (int)hipGetLastError();
 }
 

@@ -111,7 +111,7 @@ zc_status compress_single_device_setup(const zc_tensor &x, const zc_params *para
     SetupArgs a;
     std::memset(&a, 0, sizeof(a));
     if (!compress_desc(g, x, nc, 0, false, &a.desc)) return ZC_ERR_BUFFER_TOO_SMALL;
-    a.desc.fast_shape = (fs || (q.sh.bf16 && q.sh.whole_shape)) ? 1 : 0;
+    a.desc.fast_shape = (fs || q.sh.rows8) ? 1 : 0;
     {
         // the header without what depends on the code; k_codes fills that in
         const FieldCode no_code[3] = {};
