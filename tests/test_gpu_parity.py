@@ -1066,6 +1066,48 @@ def test_random_sweep_of_chunk_lists_over_batches():
                 assert np.array_equal(rows[i][:hi - lo], flat[lo:hi]), (t, i, c)
 
 
+def test_concurrent_callers_on_their_own_streams():
+    # four host threads, each with a stream, a workspace and a set of tensors of its own, call the batch and the
+    # single-tensor entry points at the same time: the library's page-locked staging is the only thing they share
+    import threading
+    errors = []
+
+    def caller(k, rounds):
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                fmt, cb, S = [(zc.FMT_FP8_E4M3, 65536, 64), (zc.FMT_BF16, 16384, 64), (zc.FMT_FP8_E4M3, 2048, 8), (zc.FMT_FP8_E4M3_BYTES, 32768, 64)][k]
+                srcs = []
+                for i in range(6):
+                    n = (3 + i) * cb + (1000 + 38 * i if i % 2 else 0)
+                    t = wl.bf16_weight(n // 2, seed=100 * k + i).view(torch.uint8) if fmt == zc.FMT_BF16 else wl.fp8_weight(n, seed=100 * k + i)
+                    srcs.append(t.to(DEV))
+                counts = [x.numel() // 2 if fmt == zc.FMT_BF16 else x.numel() for x in srcs]
+                p = zc.params(fmt, cb, (0, 0, 0), S, zc.POLICY_HUFF_ALL)
+                b = zc.Batch(srcs, counts, p)
+                want = [len(o.compress(x.cpu().numpy(), n, o.params(fmt, cb, (0, 0, 0), S, zc.POLICY_HUFF_ALL))) for x, n in zip(srcs, counts)]
+                for r in range(rounds):
+                    assert b.compress() == want, (k, r)
+                    b.decompress()
+                    stream.synchronize()
+                    for out, x in zip(b.out, srcs):
+                        assert torch.equal(out[:x.numel()], x.reshape(-1)), (k, r)
+                    if r % 8 == 0:
+                        comp, info = zc.compress(srcs[1], counts[1], p)
+                        out, _ = zc.decompress(comp, info)
+                        stream.synchronize()
+                        assert comp.numel() == want[1] and torch.equal(out[:srcs[1].numel()], srcs[1].reshape(-1)), (k, r)
+        except Exception as e:                       # noqa: BLE001 - reported by the main thread
+            errors.append((k, repr(e)))
+
+    threads = [threading.Thread(target=caller, args=(k, 40)) for k in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+
+
 def test_random_sweep_fp8_chunks_of_one_histogram_block():
     # the same kind of sweep over the one shape whose size pass works from per-lane counts: FP8, 64 lanes, 256 KiB
     rng = np.random.default_rng(20251127)
