@@ -516,9 +516,10 @@ __device__ __forceinline__ bool stream_range(const TensorDev &d, const uint8_t *
 // which is what a small set (few chunks per SIMD) is bound by.
 //
 // TAIL: the launch is over chunks that need not be whole rows: the short last chunk of a tensor, every chunk of a
-// tensor whose chunk size is not a multiple of 1 KiB, or the chunks a list of ids names (which may include either).  Their whole rows are decoded as above; the row after them, in
-// which a lane owns a whole run, part of one or nothing, takes its stream words by the same rule with the lanes that
-// own nothing left out, and is stored byte by byte where a run is cut.  Formats with two fields only.
+// tensor whose chunk size is not a multiple of 1 KiB, or the chunks a list of ids names (which may include either).
+// Their whole rows are decoded as above; the row after them, in which a lane owns a whole run, part of one or
+// nothing, takes its stream words by the same rule with the lanes that own nothing left out, and is stored byte by
+// byte where a run is cut.  Formats with two fields only.  skip_whole: leave whole chunks to the kernel that has them.
 template <int FMT, bool XOR, bool SPLIT, bool TAIL>
 __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, const WorkItem *work, TensorDev single, int use_single, uint32_t first_slot,
                                                     uint32_t skip_whole)
