@@ -478,6 +478,39 @@ private:
         return q.queue_encoders();
     }
 
+    // A dictionary call over FP8 pages, every tensor of so few whole pages that one workgroup sizes, places and encodes
+    // them (the pages a decoding step appends to a K/V cache, Sec. 5.2): one kernel instead of size pass, scan and encoder.
+    bool pages_fit_one_workgroup() const
+    {
+        if (!dict || stats_only || g.fmt != ZC_FMT_FP8_E4M3 || g.S < 4 || g.S > 32) return false;
+        for (uint32_t t = 0; t < T; t++)
+            if (descs[t].route != 1 || ncs[t] == 0 || ncs[t] > compress_pages_fused_limit() || tensors[t].n_elems % g.elems_per_chunk) return false;
+        return true;
+    }
+    zc_status run_fused_pages()
+    {
+        LAUNCH_TRY(launch_compress_pages_fused(g.S, q.d_descs(), T, q.d_enc(), ws + w.blobs, (uint32_t)kBlobBytes, (ScanOut *)(ws + w.scan), stream));
+        if (no_sync) {
+            for (uint32_t t = 0; t < T; t++) tensors[t].out_bytes = 0;
+            return ZC_OK;
+        }
+        // the sizes are known when the kernel, encoder included, is through; a destination below the worst case only
+        // loses what lies beyond it (the encoder's stores are range checked) and the call reports that it was too small
+        LandingLease landing((uint64_t)T * sizeof(ScanOut));
+        if (!landing.ptr) return ZC_ERR_DEVICE;
+        HIP_TRY(hipMemcpyAsync(landing.ptr, ws + w.scan, (uint64_t)T * sizeof(ScanOut), hipMemcpyDeviceToHost, hs));
+        HIP_TRY(hipStreamSynchronize(hs));
+        const ScanOut *scan = reinterpret_cast<const ScanOut *>(landing.ptr);
+        zc_status st = ZC_OK;
+        for (uint32_t t = 0; t < T; t++) {
+            tensors[t].out_bytes = descs[t].payload_off + 16ull * scan[t].total_units;
+            tensors[t].info.total_bytes = tensors[t].out_bytes;
+            if (tensors[t].out_bytes > tensors[t].comp_capacity) st = ZC_ERR_BUFFER_TOO_SMALL;
+        }
+        if (scan_out) scan_out->assign(scan, scan + T);
+        return st;
+    }
+
     // a call that waits for nothing: the sizes stay in the containers' headers
     zc_status queue_encoders_without_sizes()
     {
@@ -675,6 +708,7 @@ private:
                               {w.enc, enc.data(), enc.size() * 4}};
         st = stage_upload(ws, w.descs, w.host_end, all, 8, stream);
         if (st) return st;
+        if (pages_fit_one_workgroup()) return run_fused_pages();
         st = q.queue_sizes_and_scan();
         if (st) return st;
         if (no_sync) return queue_encoders_without_sizes();

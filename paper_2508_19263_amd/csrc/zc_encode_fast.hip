@@ -630,9 +630,13 @@ int launch_encode_bf16(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d
 // field split and the period is shared.  The bound on the ring needs at least 4 bits per step; with two symbols
 // per step (BF = 2) that takes a shortest code of 2 bits, which the host (or k_codes_finish) checks before it
 // gives a tensor to this kernel.
+// The chunks [first, first + slots_per_group) of one tensor, by one workgroup.  pair: the field's table in LDS; stage,
+// pairs_of_rows: the workgroup's staging memory (WRITE only); index0, index1: the chunk index of both fields (WRITE:
+// read; in the container, or wherever the caller keeps it); my: where the sizes go (!WRITE), field 0's at my[chunk],
+// field 1's at my[n_chunks + chunk].
 template <int S, bool WRITE, int BF>
-__global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units,
-                                                        uint32_t slots_per_group)
+__device__ __forceinline__ void encode_pages(const TensorDev *dp, uint32_t first_chunk, uint32_t slots_per_group, const uint32_t *pair, uint32_t *stage,
+                                             uint32_t *pairs_of_rows, const uint32_t *index0, const uint32_t *index1, uint32_t *my)
 {
     static_assert(S >= 4 && S <= 32, "the zero padding of a stream's last unit takes up to 3 lanes of the group");
     static_assert(BF == 0 || BF == 2 || BF == 4 || BF == 8, "FP8, or BF16 with a refill period of 2, 4 or 8");
@@ -640,14 +644,6 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
     constexpr uint32_t kGroups = 64 / S;
     constexpr uint32_t kNowhere = 0xFFFFFFF0u;
     constexpr uint32_t kSeg = 4 * S, kRing = 32 * S;             // words per group
-    __shared__ uint32_t pair[256];
-    __shared__ __attribute__((aligned(16))) uint32_t stage[WRITE ? kWavesPerGroup * kGroups * kRing : 4];
-    __shared__ __attribute__((aligned(16))) uint32_t pairs_of_rows[WRITE ? kWavesPerGroup * 256 : 4];   // 4*S words per group
-    const WorkItem it = work[blockIdx.x];
-    const TensorDev *dp = descs + it.tensor;
-    if (dp->route != (BF ? 2 : 1) || (BF && dp->period[0] != BF)) return;      // whole workgroup: not this kernel's tensor
-    pair[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + (BF ? 0 : 512) + threadIdx.x];
-    __syncthreads();
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t s = lane & (S - 1), grp = lane / S;
     const uint64_t gmask = ((1ull << S) - 1) << (lane - s);
@@ -663,9 +659,6 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
     const __amdgpu_buffer_rsrc_t bas = rsrc_of(has_base ? reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) : nullptr, has_base ? (uint32_t)n_elems : 0u);
     const uint64_t pay_cap = (WRITE && cap > payload) ? (cap - payload > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : cap - payload) : 0;
     const __amdgpu_buffer_rsrc_t ps = rsrc_of(WRITE ? comp + payload : nullptr, (uint32_t)pay_cap);
-    const uint32_t *index0 = WRITE ? reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[0])) : nullptr;
-    const uint32_t *index1 = WRITE ? reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[1])) : nullptr;
-    uint32_t *my = units + uni32(dp->units_off);
     const char *pair_lut = reinterpret_cast<const char *>(pair);
     const uint32_t two = 2;
     const uint32_t rows = cb / (16 * S);
@@ -674,7 +667,7 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
 
     for (uint32_t pass = 0; pass * kWavesPerGroup * kGroups < slots_per_group; pass++) {
         const uint32_t local = (pass * kWavesPerGroup + wave) * kGroups + grp;
-        const uint32_t chunk = it.first + local;
+        const uint32_t chunk = first_chunk + local;
         bool alive = local < slots_per_group && chunk < n_full;  // a short last chunk goes to the generic kernel
         uint32_t e_off = kNowhere, e_len = 0, m_off = kNowhere;
         if (WRITE && alive) {
@@ -840,6 +833,117 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
         }
     }
 }
+
+template <int S, bool WRITE, int BF>
+__global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units,
+                                                        uint32_t slots_per_group)
+{
+    constexpr uint32_t kGroups = 64 / S, kRing = 32 * S;
+    __shared__ uint32_t pair[256];
+    __shared__ __attribute__((aligned(16))) uint32_t stage[WRITE ? kWavesPerGroup * kGroups * kRing : 4];
+    __shared__ __attribute__((aligned(16))) uint32_t pairs_of_rows[WRITE ? kWavesPerGroup * 256 : 4];   // 4*S words per group
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev *dp = descs + it.tensor;
+    if (dp->route != (BF ? 2 : 1) || (BF && dp->period[0] != BF)) return;      // whole workgroup: not this kernel's tensor
+    pair[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + (BF ? 0 : 512) + threadIdx.x];
+    __syncthreads();
+    uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
+    const uint32_t *index0 = WRITE ? reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[0])) : nullptr;
+    const uint32_t *index1 = WRITE ? reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[1])) : nullptr;
+    encode_pages<S, WRITE, BF>(dp, it.first, slots_per_group, pair, stage, pairs_of_rows, index0, index1, units + uni32(dp->units_off));
+}
+
+// Stream sizes, their scan into the chunk index and the encoder in ONE launch, one workgroup per tensor, for tensors of
+// so few pages that a workgroup holds all their sizes: the K/V pages a decoding step appends (Sec. 5.2: their
+// compression sits on the critical path), coded with a dictionary, so that the code and with it the route are known
+// when the call is made.  A page's sign+mantissa stream lies behind ALL exponent streams of its tensor, which keeps
+// workgroups from placing streams before every page of the tensor is sized; inside one workgroup that is a barrier.
+// The source is read twice, the second time from the cache.  Writes what k_scan writes: the container's prologue
+// from the tensor's blob, both chunk indices, the total size, and the totals for the host.
+constexpr uint32_t kFusedMaxPages = 512;
+
+template <int S>
+__global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *descs, const uint32_t *enc_tables, const uint8_t *blobs, uint32_t blob_bytes,
+                                                              ScanOut *out)
+{
+    constexpr uint32_t kGroups = 64 / S, kRing = 32 * S, kPerPass = kWavesPerGroup * kGroups;
+    __shared__ uint32_t pair[256];
+    __shared__ __attribute__((aligned(16))) uint32_t stage[kWavesPerGroup * kGroups * kRing];
+    __shared__ __attribute__((aligned(16))) uint32_t pairs_of_rows[kWavesPerGroup * 256];
+    __shared__ uint32_t sizes[2 * kFusedMaxPages];               // field 0's at [chunk], field 1's at [n_chunks + chunk]
+    __shared__ uint32_t idx0[kFusedMaxPages + 1], idx1[kFusedMaxPages + 1];
+    const TensorDev *dp = descs + blockIdx.x;
+    const uint32_t nc = uni32(dp->n_chunks), tid = threadIdx.x;
+    uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
+    // whole workgroup; the host sends only tensors of route 1 with 1 .. kFusedMaxPages whole pages here
+    if (dp->route != 1 || nc == 0 || nc > kFusedMaxPages || !comp || uni64(dp->n_elems) != (uint64_t)nc * uni32(dp->chunk_bytes)) return;
+    pair[tid] = enc_tables[(uint64_t)blockIdx.x * 768 + 512 + tid];
+    const uint32_t i0 = uni32(dp->index_off[0]), i1 = uni32(dp->index_off[1]);
+    {
+        // the prologue (header and code-length tables) as prepared in the blob, and zeros behind both indices
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(blobs + (uint64_t)blockIdx.x * blob_bytes);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(comp);
+        for (uint32_t i = tid; i < i0 / 4; i += 256) dst[i] = src[i];
+        if (tid < 8) {
+            const uint32_t w = nc + 1 + (tid & 3);
+            if (w < ((nc + 1 + 3) & ~3u)) dst[(tid < 4 ? i0 : i1) / 4 + w] = 0;
+        }
+    }
+    __syncthreads();
+    const uint32_t slots = (nc + kPerPass - 1) / kPerPass * kPerPass;
+    encode_pages<S, false, 0>(dp, 0, slots, pair, stage, pairs_of_rows, nullptr, nullptr, sizes);
+    __syncthreads();
+    if (tid < 64) {
+        // exclusive scan of up to 512 sizes per field by one wavefront, eight consecutive chunks per lane
+        uint32_t carry = 0;
+        for (int f = 0; f < 2; f++) {
+            uint32_t *idx = f ? idx1 : idx0;
+            uint32_t v[8], t = 0;
+#pragma unroll
+            for (uint32_t j = 0; j < 8; j++) { v[j] = tid * 8 + j < nc ? sizes[f * nc + tid * 8 + j] : 0u; t += v[j]; }
+            uint32_t x = t;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t y = __shfl_up(x, o, 64);
+                if (tid >= (uint32_t)o) x += y;
+            }
+            uint32_t at = carry + x - t;
+#pragma unroll
+            for (uint32_t j = 0; j < 8; j++) { if (tid * 8 + j < nc) idx[tid * 8 + j] = at; at += v[j]; }
+            carry += __shfl(x, 63, 64);
+            if (tid == 0) idx[nc] = carry;
+        }
+    }
+    __syncthreads();
+    {
+        uint32_t *g0 = reinterpret_cast<uint32_t *>(comp + i0), *g1 = reinterpret_cast<uint32_t *>(comp + i1);
+        for (uint32_t c = tid; c <= nc; c += 256) { g0[c] = idx0[c]; g1[c] = idx1[c]; }
+        if (tid == 0) {
+            ScanOut o = {{idx0[nc], idx1[nc] - idx0[nc], 0}, idx1[nc]};
+            out[blockIdx.x] = o;
+            *reinterpret_cast<uint64_t *>(comp + 48) = uni64(dp->payload_off) + 16ull * idx1[nc];
+        }
+    }
+    encode_pages<S, true, 0>(dp, 0, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr);
+}
+
+// streams: 4, 8, 16 or 32; one workgroup per tensor
+int launch_compress_pages_fused(uint32_t streams, const TensorDev *d_descs, uint32_t n_tensors, const uint32_t *d_enc, const uint8_t *d_blobs,
+                                uint32_t blob_bytes, ScanOut *d_out, void *stream)
+{
+    if (n_tensors == 0) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    switch (streams) {
+    case 4: hipLaunchKernelGGL(k_compress_pages_fused<4>, dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out); break;
+    case 8: hipLaunchKernelGGL(k_compress_pages_fused<8>, dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out); break;
+    case 16: hipLaunchKernelGGL(k_compress_pages_fused<16>, dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out); break;
+    case 32: hipLaunchKernelGGL(k_compress_pages_fused<32>, dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out); break;
+    default: return 1;
+    }
+    return (int)hipGetLastError();
+}
+
+uint32_t compress_pages_fused_limit() { return kFusedMaxPages; }
 
 template <int S, bool WRITE>
 static void launch_sub_t(bool bf16, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, uint32_t slots_per_group, hipStream_t st)
