@@ -717,6 +717,44 @@ def test_static_dictionary():
         zc.compress_with_code(dev(b), n_b, p, code, scales=dev(sb_))
 
 
+def test_dictionary_compress_of_few_pages_in_one_kernel():
+    # dictionary calls over FP8 tensors of at most 512 whole pages run size pass, scan and encoder as one kernel: at
+    # and around that limit, every lane count of the page kernels, flat and raw sign+mantissa fields, a batch with
+    # tensors of different lengths, a destination below the worst case
+    for S in (4, 8, 16, 32):
+        cb = 16 * S * 8
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            p, po = zc.params(zc.FMT_FP8_E4M3, cb, streams=S, policy=policy), o.params(o.FP8_E4M3, cb, streams=S, policy=policy)
+            a = wl.fp8_weight(200 * cb, seed=61)
+            code = zc.train_code(dev(a), a.numel(), p)
+            ln, md = o.train_code(a.numpy(), a.numel(), po)
+            for pages in (1, 31, 512, 513):
+                b = wl.fp8_weight(pages * cb, seed=62 + pages)
+                print("few pages S", S, "policy", policy, "pages", pages, flush=True)
+                want = o.compress_with_code(b.numpy(), b.numel(), po, ln, md)
+                comp, info = zc.compress_with_code(dev(b), b.numel(), p, code)
+                assert np.array_equal(comp.cpu().numpy(), want) and info.total_bytes == len(want)
+                out, _ = zc.decompress(comp, info)
+                torch.cuda.synchronize()
+                assert torch.equal(out.cpu(), b)
+            # a batch, queued without a wait
+            srcs = [wl.fp8_weight(k * cb, seed=70 + k) for k in (3, 512, 40, 1)]
+            bt = zc.Batch([dev(x) for x in srcs], [x.numel() for x in srcs], p)
+            bt.compress_async(code)
+            sizes = bt.refresh_info()
+            for t, x in enumerate(srcs):
+                want = o.compress_with_code(x.numpy(), x.numel(), po, ln, md)
+                assert sizes[t] == len(want) and np.array_equal(bt.container(t).cpu().numpy(), want)
+            # a destination that holds the container but not the worst case is fine; one that does not hold it is refused
+            b = wl.fp8_weight(64 * cb, seed=99)
+            want = o.compress_with_code(b.numpy(), b.numel(), po, ln, md)
+            dst = torch.zeros(len(want), dtype=torch.uint8, device=DEV)
+            comp, _ = zc.compress_with_code(dev(b), b.numel(), p, code, dst=dst)
+            assert np.array_equal(comp.cpu().numpy(), want)
+            with pytest.raises(zc.ZcError):
+                zc.compress_with_code(dev(b), b.numel(), p, code, dst=torch.zeros(len(want) - 16, dtype=torch.uint8, device=DEV))
+
+
 def test_byte_grouped_symbols():
     # Sec. 3.2 (Fig. 7) / 3.4: field values coded in byte-sized groups; same bar as the plain formats
     F8, F4 = zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP4_E2M1_MX_BYTES
