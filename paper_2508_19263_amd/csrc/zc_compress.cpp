@@ -478,18 +478,23 @@ private:
         return q.queue_encoders();
     }
 
-    // A dictionary call over FP8 pages, every tensor of so few whole pages that one workgroup sizes, places and encodes
+    // A dictionary call over FP8 or BF16 pages, every tensor of so few whole pages that one workgroup sizes, places and encodes
     // them (the pages a decoding step appends to a K/V cache, Sec. 5.2): one kernel instead of size pass, scan and encoder.
     bool pages_fit_one_workgroup() const
     {
-        if (!dict || stats_only || g.fmt != ZC_FMT_FP8_E4M3 || g.S < 4 || g.S > 32) return false;
+        if (!dict || stats_only || (g.fmt != ZC_FMT_FP8_E4M3 && g.fmt != ZC_FMT_BF16) || g.S < 4 || g.S > 32) return false;
+        if (g.fmt == ZC_FMT_BF16 && sh.whole_shape) return false;       // route 2 then means the 64-lane encoder
+        const uint32_t route = g.fmt == ZC_FMT_BF16 ? 2u : 1u;          // the page kernels' route of the format
         for (uint32_t t = 0; t < T; t++)
-            if (descs[t].route != 1 || ncs[t] == 0 || ncs[t] > compress_pages_fused_limit() || tensors[t].n_elems % g.elems_per_chunk) return false;
+            if (descs[t].route != route || ncs[t] == 0 || ncs[t] > compress_pages_fused_limit() || tensors[t].n_elems % g.elems_per_chunk) return false;
         return true;
     }
     zc_status run_fused_pages()
     {
-        LAUNCH_TRY(launch_compress_pages_fused(g.S, q.d_descs(), T, q.d_enc(), ws + w.blobs, (uint32_t)kBlobBytes, (ScanOut *)(ws + w.scan), stream));
+        uint32_t periods = 0;                                           // BF16: one build per refill period of the exponent field
+        if (sh.bf16)
+            for (uint32_t t = 0; t < T; t++) periods |= descs[t].period[0];
+        LAUNCH_TRY(launch_compress_pages_fused(g.S, periods, q.d_descs(), T, q.d_enc(), ws + w.blobs, (uint32_t)kBlobBytes, (ScanOut *)(ws + w.scan), stream));
         if (no_sync) {
             for (uint32_t t = 0; t < T; t++) tensors[t].out_bytes = 0;
             return ZC_OK;

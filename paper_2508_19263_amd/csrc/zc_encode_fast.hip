@@ -862,7 +862,9 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
 // from the tensor's blob, both chunk indices, the total size, and the totals for the host.
 constexpr uint32_t kFusedMaxPages = 512;
 
-template <int S>
+// BF as in the page encoder: 0 = FP8, else BF16 with that refill period of the exponent field (a workgroup whose
+// tensor has another one returns at once: the host launches one build per period that occurs in the call).
+template <int S, int BF>
 __global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *descs, const uint32_t *enc_tables, const uint8_t *blobs, uint32_t blob_bytes,
                                                               ScanOut *out)
 {
@@ -875,9 +877,10 @@ __global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *d
     const TensorDev *dp = descs + blockIdx.x;
     const uint32_t nc = uni32(dp->n_chunks), tid = threadIdx.x;
     uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
-    // whole workgroup; the host sends only tensors of route 1 with 1 .. kFusedMaxPages whole pages here
-    if (dp->route != 1 || nc == 0 || nc > kFusedMaxPages || !comp || uni64(dp->n_elems) != (uint64_t)nc * uni32(dp->chunk_bytes)) return;
-    pair[tid] = enc_tables[(uint64_t)blockIdx.x * 768 + 512 + tid];
+    // whole workgroup; the host sends only tensors of the page kernels' route with 1 .. kFusedMaxPages whole pages here
+    if (dp->route != (BF ? 2 : 1) || (BF && dp->period[0] != BF) || nc == 0 || nc > kFusedMaxPages || !comp) return;
+    if (uni64(dp->n_elems) * (BF ? 2 : 1) != (uint64_t)nc * uni32(dp->chunk_bytes)) return;
+    pair[tid] = enc_tables[(uint64_t)blockIdx.x * 768 + (BF ? 0 : 512) + tid];
     const uint32_t i0 = uni32(dp->index_off[0]), i1 = uni32(dp->index_off[1]);
     {
         // the prologue (header and code-length tables) as prepared in the blob, and zeros behind both indices
@@ -891,7 +894,7 @@ __global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *d
     }
     __syncthreads();
     const uint32_t slots = (nc + kPerPass - 1) / kPerPass * kPerPass;
-    encode_pages<S, false, 0>(dp, 0, slots, pair, stage, pairs_of_rows, nullptr, nullptr, sizes);
+    encode_pages<S, false, BF>(dp, 0, slots, pair, stage, pairs_of_rows, nullptr, nullptr, sizes);
     __syncthreads();
     if (tid < 64) {
         // exclusive scan of up to 512 sizes per field by one wavefront, eight consecutive chunks per lane
@@ -924,20 +927,32 @@ __global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *d
             *reinterpret_cast<uint64_t *>(comp + 48) = uni64(dp->payload_off) + 16ull * idx1[nc];
         }
     }
-    encode_pages<S, true, 0>(dp, 0, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr);
+    encode_pages<S, true, BF>(dp, 0, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr);
 }
 
-// streams: 4, 8, 16 or 32; one workgroup per tensor
-int launch_compress_pages_fused(uint32_t streams, const TensorDev *d_descs, uint32_t n_tensors, const uint32_t *d_enc, const uint8_t *d_blobs,
+template <int S>
+static void launch_fused_s(uint32_t bf16_periods, const TensorDev *d_descs, uint32_t n_tensors, const uint32_t *d_enc, const uint8_t *d_blobs, uint32_t blob_bytes,
+                           ScanOut *d_out, hipStream_t st)
+{
+    if (!bf16_periods) { hipLaunchKernelGGL((k_compress_pages_fused<S, 0>), dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out); return; }
+    if (bf16_periods & 2) hipLaunchKernelGGL((k_compress_pages_fused<S, 2>), dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out);
+    if (bf16_periods & 4) hipLaunchKernelGGL((k_compress_pages_fused<S, 4>), dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out);
+    if (bf16_periods & 8) hipLaunchKernelGGL((k_compress_pages_fused<S, 8>), dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out);
+}
+
+// streams: 4, 8, 16 or 32; one workgroup per tensor.  bf16_periods: 0 for FP8 tensors (route 1); for BF16 tensors (route 2)
+// the refill periods of the exponent field that occur among them, or-ed together (2, 4, 8): one launch per period.
+int launch_compress_pages_fused(uint32_t streams, uint32_t bf16_periods, const TensorDev *d_descs, uint32_t n_tensors, const uint32_t *d_enc, const uint8_t *d_blobs,
                                 uint32_t blob_bytes, ScanOut *d_out, void *stream)
 {
     if (n_tensors == 0) return 0;
+    if (bf16_periods & ~14u) return 1;
     hipStream_t st = (hipStream_t)stream;
     switch (streams) {
-    case 4: hipLaunchKernelGGL(k_compress_pages_fused<4>, dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out); break;
-    case 8: hipLaunchKernelGGL(k_compress_pages_fused<8>, dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out); break;
-    case 16: hipLaunchKernelGGL(k_compress_pages_fused<16>, dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out); break;
-    case 32: hipLaunchKernelGGL(k_compress_pages_fused<32>, dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out); break;
+    case 4: launch_fused_s<4>(bf16_periods, d_descs, n_tensors, d_enc, d_blobs, blob_bytes, d_out, st); break;
+    case 8: launch_fused_s<8>(bf16_periods, d_descs, n_tensors, d_enc, d_blobs, blob_bytes, d_out, st); break;
+    case 16: launch_fused_s<16>(bf16_periods, d_descs, n_tensors, d_enc, d_blobs, blob_bytes, d_out, st); break;
+    case 32: launch_fused_s<32>(bf16_periods, d_descs, n_tensors, d_enc, d_blobs, blob_bytes, d_out, st); break;
     default: return 1;
     }
     return (int)hipGetLastError();

@@ -166,7 +166,7 @@ int launch_sizes_fp8_counts(const TensorDev *d_descs, const WorkItem *d_work, ui
 int launch_encode_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
 // BF16, 64 lanes, full chunks, exponent field table coded, sign+mantissa flat or raw; work items as for the generic whole-chunk build
 int launch_encode_bf16(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
-int launch_compress_pages_fused(uint32_t streams, const TensorDev *d_descs, uint32_t n_tensors, const uint32_t *d_enc, const uint8_t *d_blobs,
+int launch_compress_pages_fused(uint32_t streams, uint32_t bf16_periods, const TensorDev *d_descs, uint32_t n_tensors, const uint32_t *d_enc, const uint8_t *d_blobs,
                                 uint32_t blob_bytes, ScanOut *d_out, void *stream);
 uint32_t compress_pages_fused_limit();      // most pages per tensor the fused kernel takes
 int launch_encode_fp8_sub(uint32_t streams, int write, bool bf16, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,

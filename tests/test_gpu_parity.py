@@ -718,7 +718,7 @@ def test_static_dictionary():
 
 
 def test_dictionary_compress_of_few_pages_in_one_kernel():
-    # dictionary calls over FP8 tensors of at most 512 whole pages run size pass, scan and encoder as one kernel: at
+    # dictionary calls over FP8 or BF16 tensors of at most 512 whole pages run size pass, scan and encoder as one kernel: at
     # and around that limit, every lane count of the page kernels, flat and raw sign+mantissa fields, a batch with
     # tensors of different lengths, a destination below the worst case
     for S in (4, 8, 16, 32):
@@ -753,6 +753,41 @@ def test_dictionary_compress_of_few_pages_in_one_kernel():
             assert np.array_equal(comp.cpu().numpy(), want)
             with pytest.raises(zc.ZcError):
                 zc.compress_with_code(dev(b), b.numel(), p, code, dst=torch.zeros(len(want) - 16, dtype=torch.uint8, device=DEV))
+    # BF16 pages: the same kernel in its builds for an exponent refill period of 8, 4 and 2 (longest code up to 4, up to 8,
+    # beyond), flat and raw sign+mantissa field, a delta; the dictionary with a 1-bit code next to long ones (last case)
+    # is not this kernel's and takes the three-kernel way
+    rng = np.random.default_rng(77)
+
+    def bf16_pages(n, n_exp, skew):
+        sm = rng.integers(0, 256, n).astype(np.uint16)
+        pick = rng.integers(0, n_exp, n) if skew == 0 else np.minimum(rng.geometric(skew, n) - 1, 199)
+        if n_exp == 201:
+            pick = np.where(rng.random(n) < 0.6, 200, pick)
+        ex = (pick.astype(np.uint16) * 3 + 60) & 0xFF
+        return torch.from_numpy((((sm >> 7) << 15) | (ex << 7) | (sm & 0x7F)).astype(np.uint16).view(np.uint8).copy())
+
+    for S in (4, 8, 16, 32):
+        cb = 16 * S * 6
+        for n_exp, skew in ((12, 0), (40, 0), (200, 0.08), (201, 0.08)):
+            for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+                p, po = zc.params(zc.FMT_BF16, cb, streams=S, policy=policy), o.params(o.BF16, cb, streams=S, policy=policy)
+                a = bf16_pages(300 * cb // 2, n_exp, skew)
+                code = zc.train_code(dev(a), a.numel() // 2, p)
+                ln, md = o.train_code(a.numpy(), a.numel() // 2, po)
+                for pages in (1, 37, 512, 513):
+                    b = bf16_pages(pages * cb // 2, n_exp, skew)
+                    print("few bf16 pages S", S, "exponents", n_exp, "policy", policy, "pages", pages, flush=True)
+                    want = o.compress_with_code(b.numpy(), b.numel() // 2, po, ln, md)
+                    comp, info = zc.compress_with_code(dev(b), b.numel() // 2, p, code)
+                    assert np.array_equal(comp.cpu().numpy(), want) and info.total_bytes == len(want)
+                    out, _ = zc.decompress(comp, info)
+                    torch.cuda.synchronize()
+                    assert torch.equal(out.cpu(), b)
+                b = bf16_pages(20 * cb // 2, n_exp, skew)
+                base = torch.from_numpy((rng.integers(0, 2, b.numel() // 2, dtype=np.uint16) << 15).view(np.uint8).copy())   # flips signs only
+                want = o.compress_with_code(b.numpy(), b.numel() // 2, po, ln, md, xor_base=base.numpy())
+                comp, info = zc.compress_with_code(dev(b), b.numel() // 2, p, code, xor_base=dev(base))
+                assert np.array_equal(comp.cpu().numpy(), want)
 
 
 def test_byte_grouped_symbols():
