@@ -392,6 +392,13 @@ class Batch:
             self.arr[i].d_dst = self.out[i].data_ptr()
             self.arr[i].d_scales_out = self.scales_out[i].data_ptr() if self.scales_out else None
 
+    def set_outputs(self, outs, scales_out=None):
+        """Decode into the caller's buffers (one uint8 CUDA tensor per tensor, each large enough) from the next plan on."""
+        self.out, self.scales_out = list(outs), scales_out
+        for i in range(self.n):
+            self.arr[i].d_dst = self.out[i].data_ptr()
+            self.arr[i].d_scales_out = scales_out[i].data_ptr() if scales_out else None
+
     def set_chunk_ids(self, ids):
         """ids: one int32 CUDA tensor of chunk ids per tensor (or None to decode whole tensors again).
         The next plan/decompress decodes only those chunks, densely, into fresh output buffers."""
