@@ -66,6 +66,7 @@ typedef struct {
     uint32_t max_code_len[3];    /* per field; 0 = default */
     uint32_t streams_per_chunk;  /* S; 0 = 64 */
     uint32_t policy;
+    uint32_t payload_order;      /* 0: the streams of field 0 first, then field 1, ...; 1: the last field first */
 } zco_params;
 
 /* element format of a (possibly byte-grouped) format, and field values per coded symbol */
@@ -504,7 +505,7 @@ static void decode_raw(const uint8_t *in, uint64_t n, int sym_bits, uint8_t *sym
  *      4  u16  version = 1
  *      6  u8   format          7  u8  policy
  *      8  u8   S (lanes)       9  u8  number of fields
- *     10  u8   flags (bit 0: XOR delta against a base tensor)
+ *     10  u8   flags (bit 0: XOR delta against a base tensor; bit 1: payload in reverse field order)
  *     11  u8   0
  *     12  u32  chunk_bytes
  *     16  u64  n_elems
@@ -518,6 +519,13 @@ static void decode_raw(const uint8_t *in, uint64_t n, int sym_bits, uint8_t *sym
  *   per field: chunk index, n_chunks + 1 u32 offsets in 16-byte units from the
  *      payload start, padded to 16.  Field-major: all streams of field 0, then
  *      field 1, ...; the first offset of a field equals the last of the one before.
+ *      With flag bit 1 the fields follow each other in the payload from the last
+ *      to the first (tables and indices stay where they are).  The paper leaves
+ *      the arrangement of the compressed streams open (Sec. 3.1 asks for blocks
+ *      that can be reached at random); the reverse order puts a sign+mantissa
+ *      field of fixed stream size in front, so that where an exponent stream goes
+ *      depends only on the exponent streams of the chunks before it (Sec. 5.2:
+ *      K/V pages are compressed on the critical path, in one pass over them).
  *   payload: the (field, chunk) streams back to back.
  */
 #define ZCO_MAGIC 0x0031435Au
@@ -537,7 +545,7 @@ static int check_params(const zco_params *p, uint64_t n_elems, int *S)
     if (*S != 1 && *S != 2 && *S != 4 && *S != 8 && *S != 16 && *S != 32 && *S != 64) return ZCO_ERR_ARG;
     if (p->chunk_bytes == 0 || p->chunk_bytes % 16) return ZCO_ERR_ARG;
     if (scale_block((int)p->format) && (p->chunk_bytes % 256 || n_elems % (uint64_t)scale_block((int)p->format))) return ZCO_ERR_ARG;
-    if (p->policy > 1) return ZCO_ERR_ARG;
+    if (p->policy > 1 || p->payload_order > 1) return ZCO_ERR_ARG;
     return ZCO_OK;
 }
 
@@ -660,9 +668,10 @@ static int compress_impl(const uint8_t *src, uint64_t n_elems, const zco_params 
     if (payload_off > cap) { rc = ZCO_ERR_SMALL; goto done; }
     memset(dst, 0, (size_t)payload_off);
 
-    /* 4. streams, field-major */
+    /* 4. streams, field-major, the fields in the payload's order */
     uint64_t units = 0;                                   /* payload size so far, 16-byte units */
-    for (int f = 0; f < nf; f++) {
+    for (int k = 0; k < nf; k++) {
+        int f = p->payload_order ? nf - 1 - k : k;
         int sb = zco_sym_bits(fmt, f), G = run_len(fmt, f);
         for (uint64_t c = 0; c < nc; c++) {
             uint64_t first, n = chunk_symbols(p, f, n_elems, c, &first), bytes = 0;
@@ -684,7 +693,7 @@ static int compress_impl(const uint8_t *src, uint64_t n_elems, const zco_params 
     /* 5. header and tables */
     put32(dst + 0, ZCO_MAGIC);
     dst[4] = 1; dst[5] = 0; dst[6] = (uint8_t)fmt; dst[7] = (uint8_t)p->policy;
-    dst[8] = (uint8_t)S; dst[9] = (uint8_t)nf; dst[10] = xor_base ? 1 : 0;
+    dst[8] = (uint8_t)S; dst[9] = (uint8_t)nf; dst[10] = (uint8_t)((xor_base ? 1 : 0) | (p->payload_order ? 2 : 0));
     put32(dst + 12, p->chunk_bytes);
     put64(dst + 16, n_elems);
     put32(dst + 24, (uint32_t)nc);
@@ -748,7 +757,7 @@ int zco_train_code(const uint8_t *src, uint64_t n_elems, const zco_params *p, co
 
 /* parsed view of a container */
 typedef struct {
-    int fmt, policy, S, nf, xor_flag;
+    int fmt, policy, S, nf, xor_flag, reversed;
     uint32_t chunk_bytes;
     uint64_t n_elems, nc, total, payload_off, table_off[3], index_off[3];
     uint8_t mode[3], sym_bits[3], lmax[3], konst[3];
@@ -757,7 +766,7 @@ typedef struct {
 static int parse(const uint8_t *c, uint64_t bytes, zco_view *v)
 {
     if (bytes < ZCO_HEADER_BYTES || get32(c) != ZCO_MAGIC || c[4] != 1 || c[5] != 0) return ZCO_ERR_CORRUPT;
-    v->fmt = c[6]; v->policy = c[7]; v->S = c[8]; v->nf = c[9]; v->xor_flag = c[10] & 1;
+    v->fmt = c[6]; v->policy = c[7]; v->S = c[8]; v->nf = c[9]; v->xor_flag = c[10] & 1; v->reversed = (c[10] >> 1) & 1;
     v->chunk_bytes = get32(c + 12); v->n_elems = get64(c + 16); v->nc = get32(c + 24);
     v->total = get64(c + 48); v->payload_off = get64(c + 56);
     zco_params p; memset(&p, 0, sizeof(p));
@@ -776,8 +785,9 @@ static int parse(const uint8_t *c, uint64_t bytes, zco_view *v)
     if (off != v->payload_off || off > v->total) return ZCO_ERR_CORRUPT;
     /* chunk offsets must not decrease and must end inside the container */
     uint32_t prev = 0;
-    for (int f = 0; f < v->nf; f++)
+    for (int k = 0; k < v->nf; k++)
         for (uint64_t i = 0; i <= v->nc; i++) {
+            int f = v->reversed ? v->nf - 1 - k : k;
             uint32_t o = get32(c + v->index_off[f] + 4 * i);
             if (o < prev || (i == 0 && o != prev)) return ZCO_ERR_CORRUPT;
             prev = o;

@@ -30,7 +30,7 @@ def build(force=False):
 
 class Params(C.Structure):
     _fields_ = [("format", C.c_uint32), ("chunk_bytes", C.c_uint32), ("max_code_len", C.c_uint32 * 3),
-                ("streams_per_chunk", C.c_uint32), ("policy", C.c_uint32)]
+                ("streams_per_chunk", C.c_uint32), ("policy", C.c_uint32), ("payload_order", C.c_uint32)]
 
 
 class FieldStats(C.Structure):
@@ -103,9 +103,9 @@ def _bytes(a):
     return np.ascontiguousarray(a).view(np.uint8).reshape(-1)
 
 
-def params(fmt, chunk_bytes, max_code_len=(0, 0, 0), streams=0, policy=POLICY_HUFF_ALL):
+def params(fmt, chunk_bytes, max_code_len=(0, 0, 0), streams=0, policy=POLICY_HUFF_ALL, payload_order=0):
     p = Params()
-    p.format, p.chunk_bytes, p.streams_per_chunk, p.policy = fmt, chunk_bytes, streams, policy
+    p.format, p.chunk_bytes, p.streams_per_chunk, p.policy, p.payload_order = fmt, chunk_bytes, streams, policy, payload_order
     for i in range(3):
         p.max_code_len[i] = max_code_len[i]
     return p

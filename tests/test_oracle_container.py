@@ -169,6 +169,56 @@ def test_header_layout_and_index():
         assert np.array_equal(comp[pay + 16 * idx0[c]:pay + 16 * idx0[c + 1]], s)
 
 
+def test_reverse_payload_order():
+    # the container with its fields in reverse order in the payload: the same tables, the same streams byte for byte
+    # (each is what encode_stream / the raw packing gives for the chunk's symbols), only where they lie differs: the
+    # last field's streams first, every index still counting 16-byte units from the payload start
+    u32 = lambda c, off: int(np.frombuffer(c[off:off + 4].tobytes(), "<u4")[0])
+    u64 = lambda c, off: int(np.frombuffer(c[off:off + 8].tobytes(), "<u8")[0])
+    cases = [(o.FP8_E4M3, 5 * 2048 + 333, 2048, 8, o.POLICY_HUFF_ALL), (o.FP8_E4M3, 5 * 2048 + 333, 2048, 8, o.POLICY_AUTO),
+             (o.BF16, 3 * 1024 + 77, 2048, 64, o.POLICY_HUFF_ALL), (o.FP4_E2M1_MX, 9 * 1024 + 96, 512, 16, o.POLICY_HUFF_ALL),
+             (o.FP8_E4M3, 0, 2048, 8, o.POLICY_HUFF_ALL), (o.FP8_E4M3, 7, 2048, 8, o.POLICY_HUFF_ALL)]
+    for fmt, n, cb, S, policy in cases:
+        src, sc = make_input(fmt, n, 31)
+        a = o.compress(src, n, o.params(fmt, cb, streams=S, policy=policy), scales=sc)
+        b = o.compress(src, n, o.params(fmt, cb, streams=S, policy=policy, payload_order=1), scales=sc)
+        nf = int(a[9])
+        pay = u64(a, 56)
+        assert len(a) == len(b) and u64(b, 56) == pay and a[10] == 0 and b[10] == 2
+        nc = u32(a, 24)
+        tab = 64 + sum(((1 << int(a[33 + 4 * f])) + 15) // 16 * 16 for f in range(nf))
+        assert np.array_equal(a[11:tab], b[11:tab])                          # header fields and code-length tables
+        ia = [[u32(a, tab + f * ((4 * (nc + 1) + 15) & ~15) + 4 * i) for i in range(nc + 1)] for f in range(nf)]
+        ib = [[u32(b, tab + f * ((4 * (nc + 1) + 15) & ~15) + 4 * i) for i in range(nc + 1)] for f in range(nf)]
+        for f in range(nf):
+            for c in range(nc):
+                sa = a[pay + 16 * ia[f][c]:pay + 16 * ia[f][c + 1]]
+                sb = b[pay + 16 * ib[f][c]:pay + 16 * ib[f][c + 1]]
+                assert np.array_equal(sa, sb), (fmt, f, c)
+        # order: the last field starts the payload, each field starts where the one after it ended
+        assert ib[nf - 1][0] == 0 and pay + 16 * ib[0][nc] == len(b)
+        for f in range(nf - 1):
+            assert ib[f][0] == ib[f + 1][nc]
+        rc, out, sco = o.decompress(b, len(src), n_scales=0 if sc is None else len(sc))
+        assert rc == o.OK and np.array_equal(out, src) and (sc is None or np.array_equal(sco, sc))
+        if nc > 1:
+            rc, out, _ = o.decompress_chunk(b, 1, cb, n_scales=0 if sc is None else cb // 16)
+            assert rc == o.OK and np.array_equal(out[:cb], src[cb:2 * cb])
+        # an index in the other order is damage: the flag and the offsets must agree
+        if n > cb:
+            bad = b.copy(); bad[10] = 0
+            assert o.decompress(bad, len(src), n_scales=0 if sc is None else len(sc))[0] == o.ERR_CORRUPT
+    # with one field of fixed stream size in front, the place of exponent stream c depends on the exponent streams
+    # before it alone: FP8 pages whose sign+mantissa field is flat or raw
+    src, _ = make_input(o.FP8_E4M3, 6 * 2048, 32)
+    b = o.compress(src, len(src), o.params(o.FP8_E4M3, 2048, streams=8, policy=o.POLICY_AUTO, payload_order=1))
+    assert b[36] == o.MODE_RAW
+    tab = 64 + 32
+    i1 = [u32(b, tab + 32 + 4 * i) for i in range(7)]
+    assert i1 == [64 * i for i in range(7)]                                  # 2048 nibbles = 1 KiB = 64 units per page
+    assert u32(b, tab) == 6 * 64
+
+
 def test_corrupt_containers_are_rejected():
     x, _ = make_input(o.FP8_E4M3, 9000, 22)
     comp = o.compress(x, 9000, o.params(o.FP8_E4M3, 4096))
