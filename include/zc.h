@@ -106,15 +106,22 @@ typedef struct {
 
 /* zc_params.flags.  HOST_CODES: the compress calls build their codes on the host instead of on the device: the
  * same containers, one more wait per call (the histogram is read back).  What statistics and dictionary
- * training do anyway; meant for checking one construction against the other. */
-enum { ZC_FLAG_HOST_CODES = 1 };
+ * training do anyway; meant for checking one construction against the other.
+ * REVERSE_FIELDS: the container keeps its fields in reverse order in the payload (the streams of the last field first;
+ * tables and indices stay where they are; header flag bit 1, zc_info.payload_order = 1).  The paper fixes no arrangement
+ * of the streams (Sec. 3.1 asks only that blocks can be reached at random).  With the sign+mantissa streams of FP8 and
+ * BF16 pages in front (they have one fixed size when flat or raw), the place of an exponent stream depends on the
+ * exponent streams before it alone, and a dictionary call compresses K/V pages in ONE pass over them (Sec. 5.2: that
+ * compression is on the critical path) instead of a size pass, a scan and an encoder.  Every decode entry point takes
+ * both orders. */
+enum { ZC_FLAG_HOST_CODES = 1, ZC_FLAG_REVERSE_FIELDS = 2 };
 
 /* Parsed, validated container header plus the code-length tables: everything the
  * host needs to launch a decode.  Filled by zc_compress / zc_read_info; may be
  * cached by the caller for as long as the container bytes do not change. */
 typedef struct {
     uint32_t format, policy, streams, n_fields, xor_delta, chunk_bytes;
-    uint32_t n_chunks, reserved;
+    uint32_t n_chunks, payload_order;   /* payload_order: 0 = field 0's streams first, 1 = the last field's first */
     uint64_t n_elems;
     uint64_t total_bytes;       /* size of the container */
     uint64_t payload_offset;

@@ -149,7 +149,7 @@ zc_status CompressQueue::queue_sizes_and_scan() const
     LAUNCH_TRY(launch_sizes(g.fmt, sh.whole_mode, 0x2, d_descs(), d_list(w.whole_work), n_whole, d_enc(), d_units(), stream));
     LAUNCH_TRY(launch_sizes(g.fmt, 0, 0x6, d_descs(), d_list(w.other_work), n_other, d_enc(), d_units(), stream));
     LAUNCH_TRY(launch_sizes(g.fmt, 0, 0, d_descs(), d_list(w.chunk_work), n_slow, d_enc(), d_units(), stream));
-    LAUNCH_TRY(launch_scan(d_descs(), T, (int)g.nf, d_units(), (ScanOut *)(ws + w.scan), stats_only ? nullptr : ws + w.blobs, (uint32_t)kBlobBytes, stream));
+    LAUNCH_TRY(launch_scan(d_descs(), T, (int)g.nf, g.reversed, d_units(), (ScanOut *)(ws + w.scan), stats_only ? nullptr : ws + w.blobs, (uint32_t)kBlobBytes, stream));
     return ZC_OK;
 }
 
@@ -494,7 +494,7 @@ private:
         uint32_t periods = 0;                                           // BF16: one build per refill period of the exponent field
         if (sh.bf16)
             for (uint32_t t = 0; t < T; t++) periods |= descs[t].period[0];
-        LAUNCH_TRY(launch_compress_pages_fused(g.S, periods, q.d_descs(), T, q.d_enc(), ws + w.blobs, (uint32_t)kBlobBytes, (ScanOut *)(ws + w.scan), stream));
+        LAUNCH_TRY(launch_compress_pages_fused(g.S, periods, g.reversed, q.d_descs(), T, q.d_enc(), ws + w.blobs, (uint32_t)kBlobBytes, (ScanOut *)(ws + w.scan), stream));
         if (no_sync) {
             for (uint32_t t = 0; t < T; t++) tensors[t].out_bytes = 0;
             return ZC_OK;
@@ -602,7 +602,7 @@ private:
             layout(g.fmt, ncs[t], info.table_offset, info.index_offset, &info.payload_offset);
             uint8_t *blob = &blobs[(size_t)t * kBlobBytes];
             std::memcpy(blob, &blobs[0], kBlobBytes);
-            blob[10] = (uint8_t)(info.xor_delta ? 1 : 0);
+            blob[10] = (uint8_t)((info.xor_delta ? 1 : 0) | (g.reversed ? 2 : 0));
             put64(blob + 16, info.n_elems); put32(blob + 24, info.n_chunks); put64(blob + 48, 0); put64(blob + 56, info.payload_offset);
             std::memcpy(&enc[(size_t)t * 768], &enc[0], 768 * sizeof(uint32_t));
             TensorDev &d = descs[t];

@@ -22,8 +22,9 @@ zc_status check_params(const zc_params *given, Geometry *g)
     std::memcpy(&local, given, given->struct_size);
     const zc_params *p = &local;
     if (!elem_bits(p->format)) return ZC_ERR_UNSUPPORTED;
-    if (p->flags & ~(uint32_t)ZC_FLAG_HOST_CODES) return ZC_ERR_INVALID_ARG;
+    if (p->flags & ~(uint32_t)(ZC_FLAG_HOST_CODES | ZC_FLAG_REVERSE_FIELDS)) return ZC_ERR_INVALID_ARG;
     g->host_codes = (p->flags & ZC_FLAG_HOST_CODES) != 0;
+    g->reversed = (p->flags & ZC_FLAG_REVERSE_FIELDS) != 0;
     g->fmt = p->format;
     g->S = p->streams_per_chunk ? p->streams_per_chunk : 64;
     if (g->S > 64 || (g->S & (g->S - 1))) return ZC_ERR_INVALID_ARG;
@@ -74,6 +75,7 @@ void fill_info(const Geometry &g, uint32_t policy, bool xor_delta, uint64_t n_el
     std::memset(info, 0, sizeof(*info));
     info->format = g.fmt; info->policy = policy; info->streams = g.S; info->n_fields = g.nf;
     info->xor_delta = xor_delta; info->chunk_bytes = g.chunk_bytes; info->n_chunks = (uint32_t)nc;
+    info->payload_order = g.reversed ? 1 : 0;
     info->n_elems = n_elems; info->total_bytes = total;
     layout(g.fmt, nc, info->table_offset, info->index_offset, &info->payload_offset);
     for (uint32_t f = 0; f < g.nf; f++) {
@@ -90,7 +92,7 @@ void serialize_blob(const zc_info &info, uint8_t *blob)
     std::memset(blob, 0, kBlobBytes);
     put32(blob, kMagic);
     blob[4] = 1; blob[6] = (uint8_t)info.format; blob[7] = (uint8_t)info.policy;
-    blob[8] = (uint8_t)info.streams; blob[9] = (uint8_t)info.n_fields; blob[10] = (uint8_t)(info.xor_delta ? 1 : 0);
+    blob[8] = (uint8_t)info.streams; blob[9] = (uint8_t)info.n_fields; blob[10] = (uint8_t)((info.xor_delta ? 1 : 0) | (info.payload_order ? 2 : 0));
     put32(blob + 12, info.chunk_bytes);
     put64(blob + 16, info.n_elems);
     put32(blob + 24, info.n_chunks);
@@ -156,7 +158,7 @@ zc_status parse_info(const uint8_t *c, uint64_t have, uint64_t comp_bytes, zc_in
     if (have < kHeaderBytes || comp_bytes < kHeaderBytes) return ZC_ERR_CORRUPT;
     if (get32(c) != kMagic || c[4] != 1 || c[5] != 0) return ZC_ERR_CORRUPT;
     std::memset(out, 0, sizeof(*out));
-    out->format = c[6]; out->policy = c[7]; out->streams = c[8]; out->n_fields = c[9]; out->xor_delta = c[10] & 1;
+    out->format = c[6]; out->policy = c[7]; out->streams = c[8]; out->n_fields = c[9]; out->xor_delta = c[10] & 1; out->payload_order = (c[10] >> 1) & 1;
     out->chunk_bytes = get32(c + 12); out->n_elems = get64(c + 16); out->n_chunks = get32(c + 24);
     out->total_bytes = get64(c + 48); out->payload_offset = get64(c + 56);
     zc_params p;
@@ -265,7 +267,8 @@ zc_status zc_validate_container(const void *host_bytes, uint64_t have_bytes, uin
     if (out->payload_offset > have_bytes) return ZC_ERR_INVALID_ARG;   // the whole index must be there to be checked
     uint32_t prev = 0;
     std::vector<uint32_t> idx((size_t)out->n_chunks + 1);
-    for (uint32_t f = 0; f < out->n_fields; f++) {
+    for (uint32_t k = 0; k < out->n_fields; k++) {
+        const uint32_t f = field_at(k, out->n_fields, out->payload_order != 0);
         std::memcpy(idx.data(), c + out->index_offset[f], idx.size() * 4);
         st = check_index_field(idx.data(), out->n_chunks, &prev);
         if (st) return st;

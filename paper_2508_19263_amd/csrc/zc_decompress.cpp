@@ -121,7 +121,8 @@ zc_status check_index(const zc_info &info, const uint8_t *d_comp, hipStream_t hs
 {
     uint32_t prev = 0;
     std::vector<uint32_t> idx((size_t)info.n_chunks + 1);
-    for (uint32_t f = 0; f < info.n_fields; f++) {
+    for (uint32_t k = 0; k < info.n_fields; k++) {
+        const uint32_t f = field_at(k, info.n_fields, info.payload_order != 0);
         HIP_TRY(hipMemcpyAsync(idx.data(), d_comp + info.index_offset[f], idx.size() * 4, hipMemcpyDeviceToHost, hs));
         HIP_TRY(hipStreamSynchronize(hs));
         const zc_status st = check_index_field(idx.data(), info.n_chunks, &prev);

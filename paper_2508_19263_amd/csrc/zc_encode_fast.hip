@@ -866,7 +866,7 @@ constexpr uint32_t kFusedMaxPages = 512;
 // tensor has another one returns at once: the host launches one build per period that occurs in the call).
 template <int S, int BF>
 __global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *descs, const uint32_t *enc_tables, const uint8_t *blobs, uint32_t blob_bytes,
-                                                              ScanOut *out)
+                                                              ScanOut *out, int reversed)
 {
     constexpr uint32_t kGroups = 64 / S, kRing = 32 * S, kPerPass = kWavesPerGroup * kGroups;
     __shared__ uint32_t pair[256];
@@ -899,7 +899,8 @@ __global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *d
     if (tid < 64) {
         // exclusive scan of up to 512 sizes per field by one wavefront, eight consecutive chunks per lane
         uint32_t carry = 0;
-        for (int f = 0; f < 2; f++) {
+        for (int k = 0; k < 2; k++) {
+            const int f = reversed ? 1 - k : k;              // the payload's order of the two fields
             uint32_t *idx = f ? idx1 : idx0;
             uint32_t v[8], t = 0;
 #pragma unroll
@@ -922,9 +923,10 @@ __global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *d
         uint32_t *g0 = reinterpret_cast<uint32_t *>(comp + i0), *g1 = reinterpret_cast<uint32_t *>(comp + i1);
         for (uint32_t c = tid; c <= nc; c += 256) { g0[c] = idx0[c]; g1[c] = idx1[c]; }
         if (tid == 0) {
-            ScanOut o = {{idx0[nc], idx1[nc] - idx0[nc], 0}, idx1[nc]};
+            const uint32_t total = reversed ? idx0[nc] : idx1[nc];
+            ScanOut o = {{idx0[nc] - idx0[0], idx1[nc] - idx1[0], 0}, total};
             out[blockIdx.x] = o;
-            *reinterpret_cast<uint64_t *>(comp + 48) = uni64(dp->payload_off) + 16ull * idx1[nc];
+            *reinterpret_cast<uint64_t *>(comp + 48) = uni64(dp->payload_off) + 16ull * total;
         }
     }
     encode_pages<S, true, BF>(dp, 0, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr);
@@ -932,27 +934,28 @@ __global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *d
 
 template <int S>
 static void launch_fused_s(uint32_t bf16_periods, const TensorDev *d_descs, uint32_t n_tensors, const uint32_t *d_enc, const uint8_t *d_blobs, uint32_t blob_bytes,
-                           ScanOut *d_out, hipStream_t st)
+                           ScanOut *d_out, int rev, hipStream_t st)
 {
-    if (!bf16_periods) { hipLaunchKernelGGL((k_compress_pages_fused<S, 0>), dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out); return; }
-    if (bf16_periods & 2) hipLaunchKernelGGL((k_compress_pages_fused<S, 2>), dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out);
-    if (bf16_periods & 4) hipLaunchKernelGGL((k_compress_pages_fused<S, 4>), dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out);
-    if (bf16_periods & 8) hipLaunchKernelGGL((k_compress_pages_fused<S, 8>), dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out);
+    if (!bf16_periods) { hipLaunchKernelGGL((k_compress_pages_fused<S, 0>), dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out, rev); return; }
+    if (bf16_periods & 2) hipLaunchKernelGGL((k_compress_pages_fused<S, 2>), dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out, rev);
+    if (bf16_periods & 4) hipLaunchKernelGGL((k_compress_pages_fused<S, 4>), dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out, rev);
+    if (bf16_periods & 8) hipLaunchKernelGGL((k_compress_pages_fused<S, 8>), dim3(n_tensors), dim3(256), 0, st, d_descs, d_enc, d_blobs, blob_bytes, d_out, rev);
 }
 
 // streams: 4, 8, 16 or 32; one workgroup per tensor.  bf16_periods: 0 for FP8 tensors (route 1); for BF16 tensors (route 2)
 // the refill periods of the exponent field that occur among them, or-ed together (2, 4, 8): one launch per period.
-int launch_compress_pages_fused(uint32_t streams, uint32_t bf16_periods, const TensorDev *d_descs, uint32_t n_tensors, const uint32_t *d_enc, const uint8_t *d_blobs,
-                                uint32_t blob_bytes, ScanOut *d_out, void *stream)
+int launch_compress_pages_fused(uint32_t streams, uint32_t bf16_periods, bool reversed, const TensorDev *d_descs, uint32_t n_tensors, const uint32_t *d_enc,
+                                const uint8_t *d_blobs, uint32_t blob_bytes, ScanOut *d_out, void *stream)
 {
+    const int rev = reversed ? 1 : 0;
     if (n_tensors == 0) return 0;
     if (bf16_periods & ~14u) return 1;
     hipStream_t st = (hipStream_t)stream;
     switch (streams) {
-    case 4: launch_fused_s<4>(bf16_periods, d_descs, n_tensors, d_enc, d_blobs, blob_bytes, d_out, st); break;
-    case 8: launch_fused_s<8>(bf16_periods, d_descs, n_tensors, d_enc, d_blobs, blob_bytes, d_out, st); break;
-    case 16: launch_fused_s<16>(bf16_periods, d_descs, n_tensors, d_enc, d_blobs, blob_bytes, d_out, st); break;
-    case 32: launch_fused_s<32>(bf16_periods, d_descs, n_tensors, d_enc, d_blobs, blob_bytes, d_out, st); break;
+    case 4: launch_fused_s<4>(bf16_periods, d_descs, n_tensors, d_enc, d_blobs, blob_bytes, d_out, rev, st); break;
+    case 8: launch_fused_s<8>(bf16_periods, d_descs, n_tensors, d_enc, d_blobs, blob_bytes, d_out, rev, st); break;
+    case 16: launch_fused_s<16>(bf16_periods, d_descs, n_tensors, d_enc, d_blobs, blob_bytes, d_out, rev, st); break;
+    case 32: launch_fused_s<32>(bf16_periods, d_descs, n_tensors, d_enc, d_blobs, blob_bytes, d_out, rev, st); break;
     default: return 1;
     }
     return (int)hipGetLastError();

@@ -17,6 +17,7 @@ struct Geometry {
     uint64_t elems_per_chunk;
     int limit[kMaxFields];
     bool host_codes;            // ZC_FLAG_HOST_CODES
+    bool reversed;              // ZC_FLAG_REVERSE_FIELDS: the last field's streams come first in the payload
 };
 
 zc_status check_params(const zc_params *p, Geometry *g);
@@ -43,6 +44,8 @@ struct FieldCode {
     uint64_t n_symbols, payload_bits;
 };
 
+// the field whose streams come k-th in the payload
+inline uint32_t field_at(uint32_t k, uint32_t n_fields, bool reversed) { return reversed ? n_fields - 1 - k : k; }
 void fill_info(const Geometry &g, uint32_t policy, bool xor_delta, uint64_t n_elems, uint64_t nc, const FieldCode fc[3], uint64_t total, zc_info *info);
 // header + tables exactly as they sit at the start of the container
 void serialize_blob(const zc_info &info, uint8_t *blob);

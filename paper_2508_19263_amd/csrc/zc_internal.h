@@ -128,7 +128,7 @@ int launch_copy_chunked(const void *d_src, void *d_dst, uint64_t bytes, uint32_t
 int launch_sizes(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                  const uint32_t *d_enc_tables, uint32_t *d_units, void *stream);
 // d_blobs: per tensor the header and code-length tables to put at the start of its container (blob_bytes apart), or null
-int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, const uint32_t *d_units, ScanOut *d_out, const uint8_t *d_blobs,
+int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, bool reversed, const uint32_t *d_units, ScanOut *d_out, const uint8_t *d_blobs,
                 uint32_t blob_bytes, void *stream);
 int launch_encode(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                   const uint32_t *d_enc_tables, void *stream);
@@ -166,8 +166,8 @@ int launch_sizes_fp8_counts(const TensorDev *d_descs, const WorkItem *d_work, ui
 int launch_encode_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
 // BF16, 64 lanes, full chunks, exponent field table coded, sign+mantissa flat or raw; work items as for the generic whole-chunk build
 int launch_encode_bf16(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
-int launch_compress_pages_fused(uint32_t streams, uint32_t bf16_periods, const TensorDev *d_descs, uint32_t n_tensors, const uint32_t *d_enc, const uint8_t *d_blobs,
-                                uint32_t blob_bytes, ScanOut *d_out, void *stream);
+int launch_compress_pages_fused(uint32_t streams, uint32_t bf16_periods, bool reversed, const TensorDev *d_descs, uint32_t n_tensors, const uint32_t *d_enc,
+                                const uint8_t *d_blobs, uint32_t blob_bytes, ScanOut *d_out, void *stream);
 uint32_t compress_pages_fused_limit();      // most pages per tensor the fused kernel takes
 int launch_encode_fp8_sub(uint32_t streams, int write, bool bf16, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
                           uint32_t *d_units, uint32_t slots_per_group, void *stream);

@@ -436,11 +436,11 @@ int launch_encode(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_d
 
 // ---------------------------------------------------------------------------- scan
 // One workgroup per tensor: exclusive scan of the stream sizes (16-byte units) in
-// field-major order.  Writes the container's prologue (header and code-length tables as prepared in the
+// field-major order, the fields in the payload's order (reversed: the last field first).  Writes the container's prologue (header and code-length tables as prepared in the
 // tensor's blob, when blobs is given), the chunk index with the zero padding behind it and the total size into
 // the container (when there is one), and the per-field totals for the host.
 
-__global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fields, const uint32_t *units, ScanOut *out,
+__global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fields, int reversed, const uint32_t *units, ScanOut *out,
                                                const uint8_t *blobs, uint32_t blob_bytes)
 {
     __shared__ uint32_t wave_sum[16];
@@ -463,10 +463,11 @@ __global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fie
         }
     }
     __syncthreads();                                             // the total size below overwrites a word of the prologue
-    uint32_t field_start[kMaxFields + 1];
-    for (int f = 0; f < n_fields; f++) {
+    uint32_t field_units[kMaxFields] = {0, 0, 0};
+    for (int k = 0; k < n_fields; k++) {
+        const int f = reversed ? n_fields - 1 - k : k;
         uint32_t *index = d.comp ? reinterpret_cast<uint32_t *>(d.comp + d.index_off[f]) : nullptr;
-        field_start[f] = carry_s;
+        const uint32_t field_start = carry_s;
         // eight consecutive chunks per thread and pass: a tensor of pages has tens of thousands of chunks, and every
         // pass costs three workgroup barriers
         constexpr uint32_t K = 8;
@@ -495,23 +496,23 @@ __global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fie
             __syncthreads();
         }
         if (index && threadIdx.x == 0) index[d.n_chunks] = carry_s;
+        field_units[f] = carry_s - field_start;
         __syncthreads();
     }
-    field_start[n_fields] = carry_s;
     if (threadIdx.x == 0) {
         ScanOut o = {{0, 0, 0}, 0};
-        for (int f = 0; f < n_fields; f++) o.field_units[f] = field_start[f + 1] - field_start[f];
+        for (int f = 0; f < n_fields; f++) o.field_units[f] = field_units[f];
         o.total_units = carry_s;
         out[blockIdx.x] = o;
         if (d.comp) *reinterpret_cast<uint64_t *>(d.comp + 48) = d.payload_off + 16ull * carry_s;
     }
 }
 
-int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, const uint32_t *d_units, ScanOut *d_out, const uint8_t *d_blobs,
+int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, bool reversed, const uint32_t *d_units, ScanOut *d_out, const uint8_t *d_blobs,
                 uint32_t blob_bytes, void *stream)
 {
     if (n_tensors == 0) return 0;
-    hipLaunchKernelGGL(k_scan, dim3(n_tensors), dim3(1024), 0, (hipStream_t)stream, d_descs, n_fields, d_units, d_out, d_blobs, blob_bytes);
+    hipLaunchKernelGGL(k_scan, dim3(n_tensors), dim3(1024), 0, (hipStream_t)stream, d_descs, n_fields, reversed ? 1 : 0, d_units, d_out, d_blobs, blob_bytes);
     return (int)hipGetLastError();
 }
 

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libzc.so")
 FMT_BF16, FMT_FP8_E4M3, FMT_FP4_E2M1_MX, FMT_FP8_E4M3_BYTES, FMT_FP4_E2M1_MX_BYTES, FMT_FP4_E2M1_NV, FMT_FP8_E5M2 = 1, 2, 3, 4, 5, 6, 7
 POLICY_HUFF_ALL, POLICY_AUTO = 0, 1
 FLAG_HOST_CODES = 1
+FLAG_REVERSE_FIELDS = 2
 NOALLOC_SCRATCH_BYTES = 4 << 20
 MODE_EMPTY, MODE_HUFF, MODE_RAW, MODE_CONST = 0, 1, 2, 3
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_BUFFER_TOO_SMALL, ERR_CORRUPT, ERR_DEVICE = range(6)
@@ -35,7 +36,7 @@ class Params(C.Structure):
 
 class Info(C.Structure):
     _fields_ = [("format", C.c_uint32), ("policy", C.c_uint32), ("streams", C.c_uint32), ("n_fields", C.c_uint32),
-                ("xor_delta", C.c_uint32), ("chunk_bytes", C.c_uint32), ("n_chunks", C.c_uint32), ("reserved", C.c_uint32),
+                ("xor_delta", C.c_uint32), ("chunk_bytes", C.c_uint32), ("n_chunks", C.c_uint32), ("payload_order", C.c_uint32),
                 ("n_elems", C.c_uint64), ("total_bytes", C.c_uint64), ("payload_offset", C.c_uint64),
                 ("table_offset", C.c_uint64 * 3), ("index_offset", C.c_uint64 * 3),
                 ("mode", C.c_uint8 * 3), ("sym_bits", C.c_uint8 * 3), ("max_len", C.c_uint8 * 3), ("const_symbol", C.c_uint8 * 3),

@@ -12,7 +12,7 @@
 #include "zc.h"
 
 extern "C" {
-typedef struct { uint32_t format, chunk_bytes, max_code_len[3], streams_per_chunk, policy; } zco_params;
+typedef struct { uint32_t format, chunk_bytes, max_code_len[3], streams_per_chunk, policy, payload_order; } zco_params;
 int zco_compress(const uint8_t *src, uint64_t n_elems, const zco_params *p, const uint8_t *xor_base, const uint8_t *scales, uint8_t *dst, uint64_t cap, uint64_t *out_bytes);
 uint64_t zco_compress_bound(uint64_t n_elems, const zco_params *p);
 }
@@ -28,6 +28,7 @@ int main()
         p.chunk_bytes = p.format == 3 ? 1024 : 2048;
         p.streams_per_chunk = 1u << (rng() % 7);
         p.policy = rng() % 2;
+        p.payload_order = rng() % 2;
         const uint64_t n = p.format == 3 ? 32 * (1 + rng() % 400) : 1 + rng() % 20000;
         const uint64_t bytes = p.format == 1 ? 2 * n : p.format == 2 ? n : n / 2;
         std::vector<uint8_t> src(bytes), sc(n / 32 + 1);

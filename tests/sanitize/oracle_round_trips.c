@@ -5,7 +5,7 @@
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
-typedef struct { uint32_t format, chunk_bytes, max_code_len[3], streams_per_chunk, policy; } zco_params;
+typedef struct { uint32_t format, chunk_bytes, max_code_len[3], streams_per_chunk, policy, payload_order; } zco_params;
 int zco_compress(const uint8_t *src, uint64_t n_elems, const zco_params *p, const uint8_t *xor_base, const uint8_t *scales, uint8_t *dst, uint64_t cap, uint64_t *out_bytes);
 int zco_decompress(const uint8_t *comp, uint64_t comp_bytes, const uint8_t *xor_base, uint8_t *dst, uint64_t dst_cap, uint8_t *scales_out);
 uint64_t zco_compress_bound(uint64_t n_elems, const zco_params *p);
@@ -19,7 +19,7 @@ int main(void) {
         int fmt = 1 + rnd() % 7;
         int unit = sblock[fmt] ? 256 : 16;
         zco_params p; memset(&p, 0, sizeof p);
-        p.format = fmt; p.chunk_bytes = unit * (1 + rnd() % 20); p.streams_per_chunk = 1u << (rnd() % 7); p.policy = rnd() % 2;
+        p.format = fmt; p.chunk_bytes = unit * (1 + rnd() % 20); p.streams_per_chunk = 1u << (rnd() % 7); p.policy = rnd() % 2; p.payload_order = rnd() % 2;
         uint64_t E = (uint64_t)p.chunk_bytes * 8 / ebits[fmt];
         uint64_t n = rnd() % (4 * E + 2);
         if (sblock[fmt]) n = n / sblock[fmt] * sblock[fmt];

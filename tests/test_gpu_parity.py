@@ -41,12 +41,12 @@ def o_info(container):
     return {"mode": [int(c[32 + 4 * f]) for f in range(3)], "lmax": [int(c[34 + 4 * f]) for f in range(3)]}
 
 
-def check_case(fmt, n, cb, S, policy=zc.POLICY_HUFF_ALL, L=(0, 0, 0), data=None, base=None, tag=""):
+def check_case(fmt, n, cb, S, policy=zc.POLICY_HUFF_ALL, L=(0, 0, 0), data=None, base=None, tag="", order=0):
     """compress on both sides -> identical containers; decode the oracle's container on the
     GPU -> original bytes; decode on the GPU from the header alone -> original bytes."""
     src, sc = data if data is not None else make_input(fmt, n, seed=n % 1000 + S)
-    print("case", tag, "fmt", fmt, "n", n, "chunk", cb, "S", S, "policy", policy, "L", L, flush=True)
-    p, po = zc.params(fmt, cb, L, S, policy), o.params(fmt, cb, L, S, policy)
+    print("case", tag, "fmt", fmt, "n", n, "chunk", cb, "S", S, "policy", policy, "L", L, "order", order, flush=True)
+    p, po = zc.params(fmt, cb, L, S, policy, flags=zc.FLAG_REVERSE_FIELDS if order else 0), o.params(fmt, cb, L, S, policy, payload_order=order)
     want = o.compress(src.numpy(), n, po, xor_base=None if base is None else base.numpy(),
                       scales=None if sc is None else sc.numpy())
     comp, info = zc.compress(dev(src), n, p, xor_base=dev(base), scales=dev(sc))
@@ -945,7 +945,7 @@ def test_random_parameter_sweep():
             base = torch.from_numpy(rng.integers(0, 256, src.numel(), dtype=np.uint8) & np.uint8(rng.choice([0x01, 0x81, 0xFF])))
         if src.numel() == 0:
             src = torch.zeros(0, dtype=torch.uint8)
-        check_case(fmt, n, cb, S, policy, L, data=(src, sc), base=base, tag="sweep-%d" % case)
+        check_case(fmt, n, cb, S, policy, L, data=(src, sc), base=base, tag="sweep-%d" % case, order=int(case % 4 == 1))
 
 
 def test_random_sweep_whole_row_chunks_and_pages():
@@ -969,7 +969,7 @@ def test_random_sweep_whole_row_chunks_and_pages():
             base = torch.from_numpy(rng.integers(0, 256, src.numel(), dtype=np.uint8) & np.uint8(rng.choice([0x01, 0x81, 0xFF, 0x03])))
         if src.numel() == 0:
             src = torch.zeros(0, dtype=torch.uint8)
-        check_case(fmt, n, cb, S, policy, L, data=(src, sc), base=base, tag="rows-%d" % case)
+        check_case(fmt, n, cb, S, policy, L, data=(src, sc), base=base, tag="rows-%d" % case, order=int(case % 3 == 0))
 
 
 def test_random_sweep_of_batches():
@@ -1006,8 +1006,9 @@ def test_random_sweep_of_batches():
             srcs.append(src)
             scs.append(sc)
             bases.append(torch.from_numpy(rng.integers(0, 256, src.numel(), dtype=np.uint8) & np.uint8(0x81)) if use_base else None)
-        print("batch", case, "fmt", fmt, "S", S, "chunk", cb, "n", ns, "policy", policy, "base", bool(use_base), flush=True)
-        p, po = zc.params(fmt, cb, (0, 0, 0), S, policy), o.params(fmt, cb, (0, 0, 0), S, policy)
+        order = 1 if case % 3 == 1 else 0
+        print("batch", case, "fmt", fmt, "S", S, "chunk", cb, "n", ns, "policy", policy, "base", bool(use_base), "order", order, flush=True)
+        p, po = zc.params(fmt, cb, (0, 0, 0), S, policy, flags=zc.FLAG_REVERSE_FIELDS if order else 0), o.params(fmt, cb, (0, 0, 0), S, policy, payload_order=order)
         b = zc.Batch([dev(x) for x in srcs], ns, p, xor_bases=[dev(x) for x in bases] if use_base else None,
                      scales=[dev(x) for x in scs] if blk else None)
         sizes = b.compress()
@@ -1057,8 +1058,9 @@ def test_random_sweep_of_the_other_entry_points():
             return (n,) + _random_source(rng, fmt, n)
 
         (n_a, a, sa), (n_b, b, sb) = tensor(), tensor()
-        print("entry points", case, "fmt", fmt, "S", S, "chunk", cb, "n", n_a, n_b, "policy", policy, flush=True)
-        p, po = zc.params(fmt, cb, (0, 0, 0), S, policy), o.params(fmt, cb, (0, 0, 0), S, policy)
+        order = 1 if case % 2 else 0
+        print("entry points", case, "fmt", fmt, "S", S, "chunk", cb, "n", n_a, n_b, "policy", policy, "order", order, flush=True)
+        p, po = zc.params(fmt, cb, (0, 0, 0), S, policy, flags=zc.FLAG_REVERSE_FIELDS if order else 0), o.params(fmt, cb, (0, 0, 0), S, policy, payload_order=order)
         compare_stats(zc.stats(dev(a), n_a, p, scales=dev(sa)), o.stats(a.numpy(), n_a, po, scales=host(sa)))
         # a dictionary trained on one tensor codes the other
         code = zc.train_code(dev(a), n_a, p, scales=dev(sa))
