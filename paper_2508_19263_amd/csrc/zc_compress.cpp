@@ -516,6 +516,57 @@ private:
         return st;
     }
 
+    // A dictionary call over FP8 or BF16 tensors of whole pages whose containers keep their fields in reverse order: the
+    // sign+mantissa streams have their places by count alone and the exponent streams theirs from a running sum that the
+    // workgroups hand on while they run, so one kernel reads the pages once (Sec. 5.2).  BF16: one refill period for all.
+    bool pages_in_one_pass() const
+    {
+        if (!dict || stats_only || !g.reversed || (g.fmt != ZC_FMT_FP8_E4M3 && g.fmt != ZC_FMT_BF16) || g.S < 4 || g.S > 32) return false;
+        const uint32_t route = g.fmt == ZC_FMT_BF16 ? 2u : 1u;
+        for (uint32_t t = 0; t < T; t++) {
+            if (descs[t].route != route || ncs[t] == 0 || tensors[t].n_elems % g.elems_per_chunk) return false;
+            if (descs[t].period[0] != descs[0].period[0] || ncs[t] * (g.chunk_bytes / 32) >= 0x80000000ull) return false;
+        }
+        return true;
+    }
+    // pages per work item of that kernel: whole passes of a workgroup, few enough that its second read of them comes
+    // from the caches, enough to spread what an item costs besides (C5 on MI355X, 8 lanes: 1.74 / 1.52 / 1.56 / 1.75 ms
+    // with 64 / 128 / 256 / 512 KiB per item; 16 lanes: 2.33 / 1.76 / 1.56 / 1.58 ms with 32 / 64 / 128 / 256 KiB)
+    uint32_t chained_step() const
+    {
+        const uint32_t per_pass = kWavesPerGroup * (64 / g.S);
+        uint32_t passes = 131072 / (per_pass * g.chunk_bytes);     // about 128 KiB per item
+        if (passes < 1) passes = 1;
+        while (passes * per_pass > compress_pages_chained_limit()) passes--;
+        return passes * per_pass;
+    }
+    zc_status run_pages_in_one_pass()
+    {
+        // the chain's words take the place of the stream sizes (one word of 8 bytes per work item: a tensor has at most
+        // as many items as chunks, and two sizes of 4 bytes per chunk), its counter that of the first histogram
+        uint64_t *status = reinterpret_cast<uint64_t *>(ws + w.units), *counter = reinterpret_cast<uint64_t *>(ws + w.hist);
+        LAUNCH_TRY(launch_compress_pages_chained(g.S, sh.bf16 ? descs[0].period[0] : 0u, q.d_descs(), q.d_list(w.fast_work), q.n_fast, chained_step(), q.d_enc(),
+                                                 ws + w.blobs, (uint32_t)kBlobBytes, status, counter, (ScanOut *)(ws + w.scan), stream));
+        if (no_sync) {
+            for (uint32_t t = 0; t < T; t++) tensors[t].out_bytes = 0;
+            return ZC_OK;
+        }
+        LandingLease landing((uint64_t)T * sizeof(ScanOut));
+        if (!landing.ptr) return ZC_ERR_DEVICE;
+        HIP_TRY(hipMemcpyAsync(landing.ptr, ws + w.scan, (uint64_t)T * sizeof(ScanOut), hipMemcpyDeviceToHost, hs));
+        HIP_TRY(hipStreamSynchronize(hs));
+        const ScanOut *scan = reinterpret_cast<const ScanOut *>(landing.ptr);
+        zc_status st = ZC_OK;
+        for (uint32_t t = 0; t < T; t++) {
+            if (scan[t].total_units == 0xFFFFFFFFu) return ZC_ERR_DEVICE;      // a workgroup gave up waiting in the chain
+            tensors[t].out_bytes = descs[t].payload_off + 16ull * scan[t].total_units;
+            tensors[t].info.total_bytes = tensors[t].out_bytes;
+            if (tensors[t].out_bytes > tensors[t].comp_capacity) st = ZC_ERR_BUFFER_TOO_SMALL;
+        }
+        if (scan_out) scan_out->assign(scan, scan + T);
+        return st;
+    }
+
     // a call that waits for nothing: the sizes stay in the containers' headers
     zc_status queue_encoders_without_sizes()
     {
@@ -687,17 +738,18 @@ private:
         }
         st = crew->run();
         if (st) return st;
+        const bool chained = !pages_fit_one_workgroup() && pages_in_one_pass();
         for (uint32_t t = 0; t < T; t++) {
             // the route is known, so every chunk is listed once
             const uint64_t whole_chunks = tensors[t].n_elems / g.elems_per_chunk;
             const uint32_t n_fast = (descs[t].route == 1 || (descs[t].route == 2 && !sh.whole_shape)) ? (uint32_t)whole_chunks : 0;
             const uint32_t n_whole = (descs[t].route != 1 && sh.whole_shape) ? (uint32_t)whole_chunks : 0;
-            append(fast_work, t, {0, n_fast, sh.fast_step});
+            append(fast_work, t, {0, n_fast, chained ? chained_step() : sh.fast_step});
             append(whole_work, t, {0, n_whole, sh.whole_step});
             append(slow_work, t, {n_fast + n_whole, (uint32_t)ncs[t], sh.cpi});
         }
         if (codes_out) *codes_out = codes;
-        order_for_xcds(fast_work);
+        if (!chained) order_for_xcds(fast_work);                   // the chain runs through the items in the list's order
         order_for_xcds(whole_work);
         order_for_xcds(slow_work);
         set_list_sizes();
@@ -714,6 +766,7 @@ private:
         st = stage_upload(ws, w.descs, w.host_end, all, 8, stream);
         if (st) return st;
         if (pages_fit_one_workgroup()) return run_fused_pages();
+        if (chained) return run_pages_in_one_pass();
         st = q.queue_sizes_and_scan();
         if (st) return st;
         if (no_sync) return queue_encoders_without_sizes();

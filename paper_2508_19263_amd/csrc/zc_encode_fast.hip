@@ -633,10 +633,12 @@ int launch_encode_bf16(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d
 // The chunks [first, first + slots_per_group) of one tensor, by one workgroup.  pair: the field's table in LDS; stage,
 // pairs_of_rows: the workgroup's staging memory (WRITE only); index0, index1: the chunk index of both fields (WRITE:
 // read; in the container, or wherever the caller keeps it); my: where the sizes go (!WRITE), field 0's at my[chunk],
-// field 1's at my[n_chunks + chunk].
+// field 1's at my[my_stride + chunk].  rel: what is subtracted from a chunk's number where it indexes index0, index1 and my
+// (0 for arrays over the whole tensor, first_chunk for arrays over this call's chunks).
 template <int S, bool WRITE, int BF>
 __device__ __forceinline__ void encode_pages(const TensorDev *dp, uint32_t first_chunk, uint32_t slots_per_group, const uint32_t *pair, uint32_t *stage,
-                                             uint32_t *pairs_of_rows, const uint32_t *index0, const uint32_t *index1, uint32_t *my)
+                                             uint32_t *pairs_of_rows, const uint32_t *index0, const uint32_t *index1, uint32_t *my, uint32_t my_stride,
+                                             uint32_t rel = 0)
 {
     static_assert(S >= 4 && S <= 32, "the zero padding of a stream's last unit takes up to 3 lanes of the group");
     static_assert(BF == 0 || BF == 2 || BF == 4 || BF == 8, "FP8, or BF16 with a refill period of 2, 4 or 8");
@@ -649,7 +651,7 @@ __device__ __forceinline__ void encode_pages(const TensorDev *dp, uint32_t first
     const uint64_t gmask = ((1ull << S) - 1) << (lane - s);
     const uint32_t cb = uni32(dp->chunk_bytes);                  // FP8: one element per byte; BF16: two bytes per element
     const uint64_t n_elems = uni64(dp->n_elems) * (BF ? 2 : 1);  // in bytes
-    const uint32_t n_full = (uint32_t)(n_elems / cb), nc = uni32(dp->n_chunks);
+    const uint32_t n_full = (uint32_t)(n_elems / cb);
     const bool has_base = uni64((uint64_t)dp->base) != 0;
     const bool sm_raw = uni32(dp->kind[1]) == 2;
     uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
@@ -671,7 +673,8 @@ __device__ __forceinline__ void encode_pages(const TensorDev *dp, uint32_t first
         bool alive = local < slots_per_group && chunk < n_full;  // a short last chunk goes to the generic kernel
         uint32_t e_off = kNowhere, e_len = 0, m_off = kNowhere;
         if (WRITE && alive) {
-            const uint64_t a0 = index0[chunk], b0 = index0[chunk + 1], a1 = index1[chunk], b1 = index1[chunk + 1];
+            const uint32_t at = chunk - rel;
+            const uint64_t a0 = index0[at], b0 = index0[at + 1], a1 = index1[at], b1 = index1[at + 1];
             // the index must be as the size pass left it, and inside the 32-bit offset space of the payload
             if (a0 <= b0 && a1 <= b1 && 16 * b1 <= pay_cap && 16 * b0 <= pay_cap && (b1 - a1) * 16 == cb / 2) {
                 e_off = (uint32_t)(16 * a0); e_len = (uint32_t)(16 * (b0 - a0)); m_off = (uint32_t)(16 * a1);
@@ -827,8 +830,8 @@ __device__ __forceinline__ void encode_pages(const TensorDev *dp, uint32_t first
 #pragma unroll
             for (int o = S / 2; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
             if (alive && s == 0) {
-                my[chunk] = (q + 3) / 4;
-                my[nc + chunk] = cb / 32;                            // 4 bits per element, 16-byte units (flat code and raw alike)
+                my[chunk - rel] = (q + 3) / 4;
+                my[my_stride + chunk - rel] = cb / 32;               // 4 bits per element, 16-byte units (flat code and raw alike)
             }
         }
     }
@@ -850,7 +853,7 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
     uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
     const uint32_t *index0 = WRITE ? reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[0])) : nullptr;
     const uint32_t *index1 = WRITE ? reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[1])) : nullptr;
-    encode_pages<S, WRITE, BF>(dp, it.first, slots_per_group, pair, stage, pairs_of_rows, index0, index1, units + uni32(dp->units_off));
+    encode_pages<S, WRITE, BF>(dp, it.first, slots_per_group, pair, stage, pairs_of_rows, index0, index1, units + uni32(dp->units_off), uni32(dp->n_chunks));
 }
 
 // Stream sizes, their scan into the chunk index and the encoder in ONE launch, one workgroup per tensor, for tensors of
@@ -894,7 +897,7 @@ __global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *d
     }
     __syncthreads();
     const uint32_t slots = (nc + kPerPass - 1) / kPerPass * kPerPass;
-    encode_pages<S, false, BF>(dp, 0, slots, pair, stage, pairs_of_rows, nullptr, nullptr, sizes);
+    encode_pages<S, false, BF>(dp, 0, slots, pair, stage, pairs_of_rows, nullptr, nullptr, sizes, nc);
     __syncthreads();
     if (tid < 64) {
         // exclusive scan of up to 512 sizes per field by one wavefront, eight consecutive chunks per lane
@@ -929,7 +932,7 @@ __global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *d
             *reinterpret_cast<uint64_t *>(comp + 48) = uni64(dp->payload_off) + 16ull * total;
         }
     }
-    encode_pages<S, true, BF>(dp, 0, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr);
+    encode_pages<S, true, BF>(dp, 0, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr, 0);
 }
 
 template <int S>
@@ -962,6 +965,192 @@ int launch_compress_pages_fused(uint32_t streams, uint32_t bf16_periods, bool re
 }
 
 uint32_t compress_pages_fused_limit() { return kFusedMaxPages; }
+
+// ---------------------------------------------------------------------------------------
+// K/V pages in ONE pass over the source (Sec. 5.2: their compression is on the critical path), for containers that
+// keep their fields in reverse order in the payload (ZC_FLAG_REVERSE_FIELDS) and dictionary calls, so that code and
+// route are known at the launch.  The sign+mantissa streams of pages are flat or raw, cb / 32 units each, and lie in
+// front: page c's at c * cb / 32.  The exponent stream of page c then starts at n_chunks * cb / 32 plus the units of
+// the exponent streams of the pages before it: a running sum over the pages of the tensor, which the workgroups hand
+// on to each other while they run (a chained scan with look-back: every workgroup publishes the sum over its own
+// pages at once, then adds up what the workgroups before it have published until it meets one that already knows its
+// whole prefix, and publishes its own).
+//
+// A workgroup takes the next unclaimed work item (a counter in memory, so that items are claimed in the order in
+// which workgroups start: whoever waits for item j knows that the workgroup of every item before j is running),
+// sizes the item's pages (the encoder's dry run), joins the chain, writes the item's index entries and encodes the
+// pages, reading them a second time from the caches (an item is tens of KiB).  The first item of a tensor writes
+// the container's prologue, the last one the end of both indices, the total size and the totals for the host.
+// A wait in the chain is bounded: a workgroup that gives up (it never should) marks the tensor's totals invalid, and
+// the call reports a device error instead of hanging.
+constexpr uint32_t kChainItemPages = 256;                    // most pages of one work item
+constexpr uint64_t kChainAggregate = 1ull << 32, kChainPrefix = 2ull << 32;
+constexpr uint32_t kChainSpinLimit = 1u << 20;      // about a tenth of a second
+
+__device__ __forceinline__ uint64_t chain_read(uint64_t *p)
+{
+    return __hip_atomic_fetch_add(p, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);     // a read-modify-write is served where all XCDs meet
+}
+__device__ __forceinline__ void chain_publish(uint64_t *p, uint64_t v)
+{
+    __hip_atomic_exchange(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int S, int BF>
+__global__ __launch_bounds__(256) void k_compress_pages_chained(const TensorDev *descs, const WorkItem *work, uint32_t n_work, uint32_t slots_per_item,
+                                                                const uint32_t *enc_tables, const uint8_t *blobs, uint32_t blob_bytes, uint64_t *status,
+                                                                uint64_t *counter, ScanOut *out)
+{
+    constexpr uint32_t kGroups = 64 / S, kRing = 32 * S;
+    __shared__ uint32_t pair[256];
+    __shared__ __attribute__((aligned(16))) uint32_t stage[kWavesPerGroup * kGroups * kRing];
+    __shared__ __attribute__((aligned(16))) uint32_t pairs_of_rows[kWavesPerGroup * 256];
+    __shared__ uint32_t sizes[2 * kChainItemPages];               // exponent units of the item's pages; the other half is written and not used
+    __shared__ uint32_t idx0[kChainItemPages + 1], idx1[kChainItemPages + 1];
+    __shared__ uint32_t claimed, before_s;
+    const uint32_t tid = threadIdx.x;
+    if (tid == 0) claimed = (uint32_t)__hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    const uint32_t item = uni32(claimed);
+    // whole workgroup; an item is whole passes of the workgroup (the launcher checks it too), so that no page of the next item is touched
+    if (item >= n_work || slots_per_item == 0 || slots_per_item > kChainItemPages || slots_per_item % (kWavesPerGroup * kGroups)) return;
+    const WorkItem it = work[item];
+    const TensorDev *dp = descs + it.tensor;
+    const uint32_t nc = uni32(dp->n_chunks), first = uni32(it.first), cb = uni32(dp->chunk_bytes);
+    uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
+    const uint32_t count = first < nc ? (nc - first < slots_per_item ? nc - first : slots_per_item) : 0;
+    const uint32_t per_page = cb / 32;                          // units of a sign+mantissa stream
+    // what the host checked before it chose this kernel; a tensor that is not as promised is left alone, but its
+    // place in the chain is filled so that nobody waits for it
+    const bool mine = dp->route == (BF ? 2 : 1) && (!BF || dp->period[0] == BF) && comp && count > 0 &&
+                      uni64(dp->n_elems) * (BF ? 2 : 1) == (uint64_t)nc * cb && (uint64_t)nc * per_page < 0x80000000ull;
+    if (!mine) {
+        if (tid == 0) chain_publish(status + item, kChainPrefix);
+        return;
+    }
+    pair[tid] = enc_tables[(uint64_t)it.tensor * 768 + (BF ? 0 : 512) + tid];
+    sizes[tid] = 0;                                             // kChainItemPages == 256: a slot without a page counts nothing
+    const uint32_t i0 = uni32(dp->index_off[0]), i1 = uni32(dp->index_off[1]);
+    if (first == 0) {
+        // the prologue (header and code-length tables) as prepared in the blob, and zeros behind both indices
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(blobs + (uint64_t)it.tensor * blob_bytes);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(comp);
+        for (uint32_t i = tid; i < i0 / 4; i += 256) if (i != 12 && i != 13) dst[i] = src[i];       // words 12, 13: the total size, the last item's to write
+        if (tid < 8) {
+            const uint32_t w = nc + 1 + (tid & 3);
+            if (w < ((nc + 1 + 3) & ~3u)) dst[(tid < 4 ? i0 : i1) / 4 + w] = 0;
+        }
+    }
+    __syncthreads();
+    const uint32_t slots = (count + kWavesPerGroup * kGroups - 1) / (kWavesPerGroup * kGroups) * (kWavesPerGroup * kGroups);
+    encode_pages<S, false, BF>(dp, first, slots, pair, stage, pairs_of_rows, nullptr, nullptr, sizes, kChainItemPages, first);
+    __syncthreads();
+    if (tid < 64) {
+        // exclusive scan of up to 256 sizes by one wavefront, four consecutive pages per lane
+        uint32_t v[4], t = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) { v[j] = tid * 4 + j < count ? sizes[tid * 4 + j] : 0u; t += v[j]; }
+        uint32_t x = t;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t y = __shfl_up(x, o, 64);
+            if (tid >= (uint32_t)o) x += y;
+        }
+        const uint32_t sum = __shfl(x, 63, 64);                 // units of the item's exponent streams
+        uint32_t before = 0;
+        if (tid == 0) {
+            if (first == 0) chain_publish(status + item, kChainPrefix | sum);
+            else {
+                chain_publish(status + item, kChainAggregate | sum);
+                bool lost = false;
+                for (uint32_t j = item; j-- > 0 && !lost;) {
+                    uint64_t s = 0;
+                    uint32_t spins = 0;
+                    while (((s = chain_read(status + j)) >> 32) == 0) {
+                        if (++spins > kChainSpinLimit) { lost = true; break; }
+                        __builtin_amdgcn_s_sleep(4);
+                    }
+                    if ((uint32_t)s == 0xFFFFFFFFu) lost = true;  // an item before this one gave up
+                    before += (uint32_t)s;
+                    if ((s >> 32) == 2) break;                  // that item knew everything before it
+                }
+                if (lost) before = 0xFFFFFFFFu;                 // the last item passes it on to the host
+                chain_publish(status + item, kChainPrefix | (lost ? 0xFFFFFFFFull : (uint64_t)(before + sum)));
+            }
+            before_s = before;
+        }
+        before = __shfl(before, 0, 64);
+        const uint32_t base0 = nc * per_page + (before == 0xFFFFFFFFu ? 0u : before);
+        uint32_t at = base0 + x - t;
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) { if (tid * 4 + j < count) idx0[tid * 4 + j] = at; at += v[j]; }
+        if (tid == 63) idx0[count] = base0 + sum;
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) if (tid * 4 + j <= count) idx1[tid * 4 + j] = (first + tid * 4 + j) * per_page;
+        if (tid == 63) idx1[count] = (first + count) * per_page;
+    }
+    __syncthreads();
+    {
+        uint32_t *g0 = reinterpret_cast<uint32_t *>(comp + i0), *g1 = reinterpret_cast<uint32_t *>(comp + i1);
+        const bool last = first + count == nc;
+        for (uint32_t c = tid; c < count + (last ? 1u : 0u); c += 256) { g0[first + c] = idx0[c]; g1[first + c] = idx1[c]; }
+        if (last && tid == 0) {
+            const bool lost = before_s == 0xFFFFFFFFu;
+            const uint32_t total = idx0[count];
+            ScanOut o = {{total - nc * per_page, nc * per_page, 0}, lost ? 0xFFFFFFFFu : total};
+            out[it.tensor] = o;
+            *reinterpret_cast<uint64_t *>(comp + 48) = uni64(dp->payload_off) + 16ull * total;
+        }
+    }
+    encode_pages<S, true, BF>(dp, first, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr, 0, first);
+}
+
+__global__ void k_chain_reset(uint64_t *status, uint32_t n_work, uint64_t *counter)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_work) status[i] = 0;
+    if (i == 0) *counter = 0;
+}
+
+template <int S>
+static void launch_chained_s(uint32_t bf16_period, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t slots_per_item, const uint32_t *d_enc,
+                             const uint8_t *d_blobs, uint32_t blob_bytes, uint64_t *d_status, uint64_t *d_counter, ScanOut *d_out, hipStream_t st)
+{
+#define ZC_CHAINED(BF) hipLaunchKernelGGL((k_compress_pages_chained<S, BF>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, n_work, slots_per_item, d_enc, d_blobs, \
+                                          blob_bytes, d_status, d_counter, d_out)
+    switch (bf16_period) {
+    case 0: ZC_CHAINED(0); break;
+    case 2: ZC_CHAINED(2); break;
+    case 4: ZC_CHAINED(4); break;
+    default: ZC_CHAINED(8); break;
+    }
+#undef ZC_CHAINED
+}
+
+// streams: 4, 8, 16 or 32.  bf16_period: 0 for FP8 tensors (route 1), else the one refill period of the exponent field that
+// every BF16 tensor of the call has (route 2).  Work items in natural order (tensor by tensor, pages ascending), each
+// slots_per_item pages (a multiple of the pages a workgroup takes per pass, at most compress_pages_chained_limit()).
+// d_status: n_work words, d_counter: one word; both are reset here.
+int launch_compress_pages_chained(uint32_t streams, uint32_t bf16_period, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t slots_per_item,
+                                  const uint32_t *d_enc, const uint8_t *d_blobs, uint32_t blob_bytes, uint64_t *d_status, uint64_t *d_counter, ScanOut *d_out,
+                                  void *stream)
+{
+    if (n_work == 0) return 0;
+    if (slots_per_item == 0 || slots_per_item > kChainItemPages || (bf16_period != 0 && bf16_period != 2 && bf16_period != 4 && bf16_period != 8)) return 1;
+    if (streams < 4 || streams > 32 || slots_per_item % (kWavesPerGroup * (64 / streams))) return 1;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(k_chain_reset, dim3((n_work + 255) / 256), dim3(256), 0, st, d_status, n_work, d_counter);
+    switch (streams) {
+    case 4: launch_chained_s<4>(bf16_period, d_descs, d_work, n_work, slots_per_item, d_enc, d_blobs, blob_bytes, d_status, d_counter, d_out, st); break;
+    case 8: launch_chained_s<8>(bf16_period, d_descs, d_work, n_work, slots_per_item, d_enc, d_blobs, blob_bytes, d_status, d_counter, d_out, st); break;
+    case 16: launch_chained_s<16>(bf16_period, d_descs, d_work, n_work, slots_per_item, d_enc, d_blobs, blob_bytes, d_status, d_counter, d_out, st); break;
+    case 32: launch_chained_s<32>(bf16_period, d_descs, d_work, n_work, slots_per_item, d_enc, d_blobs, blob_bytes, d_status, d_counter, d_out, st); break;
+    default: return 1;
+    }
+    return (int)hipGetLastError();
+}
+
+uint32_t compress_pages_chained_limit() { return kChainItemPages; }
 
 template <int S, bool WRITE>
 static void launch_sub_t(bool bf16, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, uint32_t slots_per_group, hipStream_t st)

@@ -790,6 +790,82 @@ def test_dictionary_compress_of_few_pages_in_one_kernel():
                 assert np.array_equal(comp.cpu().numpy(), want)
 
 
+def test_dictionary_compress_of_pages_in_one_pass():
+    # containers with their fields in reverse order (ZC_FLAG_REVERSE_FIELDS): a dictionary call over whole pages sizes,
+    # places and encodes them in one kernel whose workgroups hand the running sum of the exponent streams on to each
+    # other.  Tensors of more pages than one workgroup takes (so that the chain has many links), around the item
+    # size, several tensors per call, every lane count, flat and raw sign+mantissa fields, a delta, a call that
+    # waits for nothing, a destination that is too small; BF16 pages at each refill period of the exponent field
+    R = zc.FLAG_REVERSE_FIELDS
+    for S in (4, 8, 16, 32):
+        cb = 16 * S * 8
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            p, po = zc.params(zc.FMT_FP8_E4M3, cb, streams=S, policy=policy, flags=R), o.params(o.FP8_E4M3, cb, streams=S, policy=policy, payload_order=1)
+            a = wl.fp8_weight(200 * cb, seed=161)
+            code = zc.train_code(dev(a), a.numel(), p)
+            ln, md = o.train_code(a.numpy(), a.numel(), po)
+            for pages in (513, 600, 1024, 4099):
+                b = wl.fp8_weight(pages * cb, seed=162 + pages)
+                print("one pass S", S, "policy", policy, "pages", pages, flush=True)
+                want = o.compress_with_code(b.numpy(), b.numel(), po, ln, md)
+                comp, info = zc.compress_with_code(dev(b), b.numel(), p, code)
+                got = comp.cpu().numpy()
+                assert got.shape == want.shape and np.array_equal(got, want), int(np.argmax(got[:len(want)] != want[:len(got)]))
+                assert info.total_bytes == len(want) and info.payload_order == 1
+                out, _ = zc.decompress(comp, zc.read_info(comp, check_index=True))
+                torch.cuda.synchronize()
+                assert torch.equal(out.cpu(), b)
+            # several tensors, queued without a wait; one of few pages keeps the call away from the one-workgroup kernel
+            srcs = [wl.fp8_weight(k * cb, seed=170 + k) for k in (700, 3, 2048, 515, 1)]
+            bt = zc.Batch([dev(x) for x in srcs], [x.numel() for x in srcs], p)
+            bt.compress_async(code)
+            sizes = bt.refresh_info()
+            for t, x in enumerate(srcs):
+                want = o.compress_with_code(x.numpy(), x.numel(), po, ln, md)
+                assert sizes[t] == len(want) and np.array_equal(bt.container(t).cpu().numpy(), want), t
+            bt.decompress()
+            torch.cuda.synchronize()
+            for t, x in enumerate(srcs):
+                assert torch.equal(bt.out[t].cpu()[:x.numel()], x)
+            # a delta
+            b, base = wl.fp8_weight(900 * cb, seed=180), torch.from_numpy((np.random.default_rng(S).integers(0, 2, 900 * cb, dtype=np.uint8) << 7))
+            want = o.compress_with_code(b.numpy(), b.numel(), po, ln, md, xor_base=base.numpy())
+            comp, _ = zc.compress_with_code(dev(b), b.numel(), p, code, xor_base=dev(base))
+            assert np.array_equal(comp.cpu().numpy(), want)
+            # a destination that holds the container but not the worst case is fine; one that does not hold it is refused
+            b = wl.fp8_weight(640 * cb, seed=199)
+            want = o.compress_with_code(b.numpy(), b.numel(), po, ln, md)
+            comp, _ = zc.compress_with_code(dev(b), b.numel(), p, code, dst=torch.zeros(len(want), dtype=torch.uint8, device=DEV))
+            assert np.array_equal(comp.cpu().numpy(), want)
+            with pytest.raises(zc.ZcError):
+                zc.compress_with_code(dev(b), b.numel(), p, code, dst=torch.zeros(len(want) - 16, dtype=torch.uint8, device=DEV))
+    rng = np.random.default_rng(78)
+
+    def bf16_pages(n, n_exp, skew):
+        sm = rng.integers(0, 256, n).astype(np.uint16)
+        pick = rng.integers(0, n_exp, n) if skew == 0 else np.minimum(rng.geometric(skew, n) - 1, 199)
+        ex = (pick.astype(np.uint16) * 3 + 60) & 0xFF
+        return torch.from_numpy((((sm >> 7) << 15) | (ex << 7) | (sm & 0x7F)).astype(np.uint16).view(np.uint8).copy())
+
+    for S in (4, 8, 16, 32):
+        cb = 16 * S * 6
+        for n_exp, skew in ((12, 0), (40, 0), (200, 0.08)):
+            for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+                p, po = zc.params(zc.FMT_BF16, cb, streams=S, policy=policy, flags=R), o.params(o.BF16, cb, streams=S, policy=policy, payload_order=1)
+                a = bf16_pages(300 * cb // 2, n_exp, skew)
+                code = zc.train_code(dev(a), a.numel() // 2, p)
+                ln, md = o.train_code(a.numpy(), a.numel() // 2, po)
+                for pages in (513, 1500):
+                    b = bf16_pages(pages * cb // 2, n_exp, skew)
+                    print("one pass bf16 S", S, "exponents", n_exp, "policy", policy, "pages", pages, flush=True)
+                    want = o.compress_with_code(b.numpy(), b.numel() // 2, po, ln, md)
+                    comp, info = zc.compress_with_code(dev(b), b.numel() // 2, p, code)
+                    assert np.array_equal(comp.cpu().numpy(), want) and info.total_bytes == len(want)
+                    out, _ = zc.decompress(comp, info)
+                    torch.cuda.synchronize()
+                    assert torch.equal(out.cpu(), b)
+
+
 def test_byte_grouped_symbols():
     # Sec. 3.2 (Fig. 7) / 3.4: field values coded in byte-sized groups; same bar as the plain formats
     F8, F4 = zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP4_E2M1_MX_BYTES
