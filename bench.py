@@ -125,8 +125,8 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
     out = {}
 
     def run(name, fmt, srcs, counts, chunk, streams, bases=None, scales=None, limit=(0, 0, 0), ids=None, dictionary=False,
-            policy=zc.POLICY_HUFF_ALL, decode_kernel="", compress_kernels=""):
-        p = zc.params(fmt, chunk, limit, streams, policy)
+            policy=zc.POLICY_HUFF_ALL, decode_kernel="", compress_kernels="", flags=0):
+        p = zc.params(fmt, chunk, limit, streams, policy, flags=flags)
         b = zc.Batch(srcs, counts, p, xor_bases=bases, scales=scales)
         sizes = b.compress()
         b.plan_decompress()
@@ -189,8 +189,10 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
             r.update({"static_dictionary_compress_ms": _median(ts), "static_dictionary_compress_ms_min": ts[0],
                       "static_dictionary_compress_GBps": raw / _median(ts) / 1e6,
                       "static_dictionary_ratio_total": dsizes / raw, "static_dictionary_round_trip_bit_exact": bool(oks),
-                      # a dictionary leaves one read of the source for the sizes and one for the encoder
-                      "roofline_static_dictionary_compress": _roofline("k_encode_fp8_sub (size pass) + k_scan + k_encode_fp8_sub", 2 * raw + dsizes, _median(ts), copy_gbps)})
+                      # a dictionary leaves one read of the source for the sizes and one for the encoder; with the fields in
+                      # reverse order one kernel does both and the second read comes from the caches
+                      "roofline_static_dictionary_compress": (_roofline("k_compress_pages_chained", raw + dsizes, _median(ts), copy_gbps) if flags & zc.FLAG_REVERSE_FIELDS
+                                                              else _roofline("k_encode_fp8_sub (size pass) + k_scan + k_encode_fp8_sub", 2 * raw + dsizes, _median(ts), copy_gbps))})
             if not oks:
                 raise RuntimeError("dictionary round trip of %s is not bit exact" % name)
             del halves
@@ -255,6 +257,9 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
     ids = [wl.page_sample(n_pages, 0.25, device=dev, seed=600 + i) for i in range(len(kv))]
     page_c = "k_hist + k_codes + k_encode_fp8_sub (sizes) + k_scan + k_encode_fp8_sub"
     run("c5_fp8_kv_pages", zc.FMT_FP8_E4M3, kv, [t.numel() for t in kv], 2048, 8, ids=ids, dictionary=True, decode_kernel="k_decode_fp8_sub<8>", compress_kernels=page_c)
+    # the same with the fields in reverse order in the payload (ZC_FLAG_REVERSE_FIELDS): the dictionary call is one pass
+    run("c5_fp8_kv_pages_reverse_fields", zc.FMT_FP8_E4M3, kv, [t.numel() for t in kv], 2048, 8, ids=ids, dictionary=True, decode_kernel="k_decode_fp8_sub<8>", compress_kernels=page_c,
+        flags=zc.FLAG_REVERSE_FIELDS)
     if extras:
         # lanes per page: the tuning of configuration 5 (S = 8 is what the other rows use), and 64 lanes per page, which
         # takes the generic kernels

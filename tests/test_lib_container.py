@@ -19,6 +19,27 @@ def containers():
     yield zc.FMT_FP4_E2M1_MX, o.compress(p.numpy(), 8 * 2048, o.params(o.FP4_E2M1_MX, 1024), scales=s.numpy())
 
 
+def reversed_containers():
+    n = 9 * 4096 + 100
+    yield zc.FMT_FP8_E4M3, o.compress(wl.fp8_weight(n, seed=3).numpy(), n, o.params(o.FP8_E4M3, 4096, payload_order=1))
+    p, s = wl.mxfp4_weight(8, 2048, seed=5)
+    yield zc.FMT_FP4_E2M1_MX, o.compress(p.numpy(), 8 * 2048, o.params(o.FP4_E2M1_MX, 1024, payload_order=1), scales=s.numpy())
+
+
+def test_payload_order_is_read_from_the_header_and_checked_against_the_index():
+    for (fmt, c), (_, r) in zip([x for x in containers() if x[0] != zc.FMT_BF16], reversed_containers()):
+        assert zc.validate_container(c).payload_order == 0
+        info = zc.validate_container(r)
+        assert info.payload_order == 1 and info.format == fmt and info.total_bytes == len(r) == len(c)
+        # the flag and the index must agree
+        for good, flag in ((c, 2), (r, 0)):
+            bad = good.copy()
+            bad[10] = flag
+            with pytest.raises(zc.ZcError) as e:
+                zc.validate_container(bad)
+            assert e.value.status == zc.ERR_CORRUPT
+
+
 def test_oracle_containers_validate_and_describe_themselves():
     for fmt, c in containers():
         info = zc.validate_container(c)
