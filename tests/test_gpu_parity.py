@@ -1384,7 +1384,7 @@ def test_compress_without_sync_and_host_built_codes():
         short.struct_size = 32
         comp, info = zc.compress(dev(s), n, short)
         assert np.array_equal(comp.cpu().numpy(), want)
-    bad = zc.params(zc.FMT_FP8_E4M3, 4096, flags=2)               # an unknown flag bit
+    bad = zc.params(zc.FMT_FP8_E4M3, 4096, flags=4)               # an unknown flag bit
     with pytest.raises(zc.ZcError):
         zc.compress(dev(srcs[0]), srcs[0].numel(), bad)
 
