@@ -141,7 +141,10 @@ zc_status CompressQueue::queue_codes(uint32_t policy) const
 // stream sizes (a5) and their exclusive scan into the chunk index (a6)
 zc_status CompressQueue::queue_sizes_and_scan() const
 {
-    if (g.S == 64 && sh.lanes) LAUNCH_TRY(launch_sizes_fp8_counts(d_descs(), d_list(w.fast_work), n_fast, d_enc(), d_lane_counts(), d_units(), stream));
+    if (chained)
+        LAUNCH_TRY(launch_compress_pages_chained(g.S, 0, d_descs(), d_list(w.fast_work), n_fast, chain_step, d_enc(), ws + w.blobs, (uint32_t)kBlobBytes,
+                                                 (uint64_t *)(ws + chain_status), (uint64_t *)(ws + chain_counter), (ScanOut *)(ws + w.scan), stream));
+    else if (g.S == 64 && sh.lanes) LAUNCH_TRY(launch_sizes_fp8_counts(d_descs(), d_list(w.fast_work), n_fast, d_enc(), d_lane_counts(), d_units(), stream));
     else if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs(), d_list(w.fast_work), n_fast, d_enc(), d_units(), stream));
     else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 0, sh.bf16, d_descs(), d_list(w.fast_work), n_fast, d_enc(), d_units(), sh.fast_step, stream));
     // generic kernels: the whole-chunk list leaves route 1 to the FP8 kernels (route 2 there is the BF16 encoder,
@@ -149,14 +152,17 @@ zc_status CompressQueue::queue_sizes_and_scan() const
     LAUNCH_TRY(launch_sizes(g.fmt, sh.whole_mode, 0x2, d_descs(), d_list(w.whole_work), n_whole, d_enc(), d_units(), stream));
     LAUNCH_TRY(launch_sizes(g.fmt, 0, 0x6, d_descs(), d_list(w.other_work), n_other, d_enc(), d_units(), stream));
     LAUNCH_TRY(launch_sizes(g.fmt, 0, 0, d_descs(), d_list(w.chunk_work), n_slow, d_enc(), d_units(), stream));
-    LAUNCH_TRY(launch_scan(d_descs(), T, (int)g.nf, g.reversed, d_units(), (ScanOut *)(ws + w.scan), stats_only ? nullptr : ws + w.blobs, (uint32_t)kBlobBytes, stream));
+    // the chained kernel has placed and written the tensors of its route (1) itself
+    LAUNCH_TRY(launch_scan(d_descs(), T, (int)g.nf, g.reversed, chained ? 0x2 : 0, d_units(), (ScanOut *)(ws + w.scan), stats_only ? nullptr : ws + w.blobs,
+                           (uint32_t)kBlobBytes, stream));
     return ZC_OK;
 }
 
 // chunked encode (a7)
 zc_status CompressQueue::queue_encoders() const
 {
-    if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs(), d_list(w.fast_work), n_fast, d_enc(), stream));
+    if (chained) {}                                             // encoded where they were sized
+    else if (g.S == 64) LAUNCH_TRY(launch_encode_fp8(d_descs(), d_list(w.fast_work), n_fast, d_enc(), stream));
     else LAUNCH_TRY(launch_encode_fp8_sub(g.S, 1, sh.bf16, d_descs(), d_list(w.fast_work), n_fast, d_enc(), d_units(), sh.fast_step, stream));
     LAUNCH_TRY(launch_encode(g.fmt, sh.whole_mode, 0x6, d_descs(), d_list(w.whole_work), n_whole, d_enc(), stream));
     if (sh.rows8) LAUNCH_TRY(launch_encode_bf16(g.fmt, d_descs(), d_list(w.whole_work), n_whole, d_enc(), stream));
@@ -469,6 +475,7 @@ private:
         } else HIP_TRY(hipStreamSynchronize(hs));
         const ScanOut *scan = reinterpret_cast<const ScanOut *>(landing.ptr);
         for (uint32_t t = 0; t < T; t++) {
+            if (scan[t].total_units == 0xFFFFFFFFu) return ZC_ERR_DEVICE;      // a workgroup of the one-pass kernel gave up waiting in its chain
             const uint64_t total = descs[t].payload_off + 16ull * scan[t].total_units;
             tensors[t].out_bytes = total;
             if (!stats_only && total > tensors[t].comp_capacity) return ZC_ERR_BUFFER_TOO_SMALL;
@@ -575,15 +582,32 @@ private:
     }
 
     // ---- the code is built on the device (a4): nothing between the histogram and the encoder waits for the host
+    // Codes built on the device and FP8 pages in a container with reversed payload order: the one-pass kernel takes every
+    // tensor whose code turns out to suit it (decided on the device; the others go through the generic kernels as
+    // before).  Its chain lives where the histograms were: they are dead once the codes are built.
+    void choose_chained_device_path()
+    {
+        if (!g.reversed || g.fmt != ZC_FMT_FP8_E4M3 || g.S < 4 || g.S > 32 || stats_only) return;
+        uint64_t items = 0;
+        const uint32_t step = chained_step();
+        for (uint32_t t = 0; t < T; t++) {
+            if (!fast_shape(t) || ncs[t] == 0 || tensors[t].n_elems % g.elems_per_chunk || ncs[t] * (g.chunk_bytes / 32) >= 0x80000000ull) return;
+            items += (ncs[t] + step - 1) / step;
+        }
+        if (items + 1 > (uint64_t)T * 3 * 256) return;
+        q.chained = true; q.chain_step = step; q.chain_counter = w.hist; q.chain_status = w.hist + 8;
+    }
+
     zc_status run_with_device_codes()
     {
+        choose_chained_device_path();
         std::vector<uint8_t> blobs((size_t)T * kBlobBytes, 0);
         const FieldCode no_code[3] = {};
         for (uint32_t t = 0; t < T; t++) {
             const bool fs = fast_shape(t);
             descs[t].fast_shape = (fs || sh.rows8) ? 1 : 0;
             const TensorLists L = device_code_lists(g, sh, tensors[t].n_elems, ncs[t], fs);
-            append(fast_work, t, L.fast);
+            append(fast_work, t, q.chained ? ListRange{0, (uint32_t)ncs[t], q.chain_step} : L.fast);
             append(whole_work, t, L.whole);
             append(other_work, t, L.other);
             append(slow_work, t, L.slow);
@@ -592,7 +616,7 @@ private:
             fill_info(g, params->policy, tensors[t].d_xor_base != nullptr, tensors[t].n_elems, ncs[t], no_code, 0, &blank);
             serialize_blob(blank, &blobs[(size_t)t * kBlobBytes]);
         }
-        order_for_xcds(fast_work);
+        if (!q.chained) order_for_xcds(fast_work);                 // the chain runs through the items in the list's order
         order_for_xcds(whole_work);
         order_for_xcds(other_work);
         order_for_xcds(slow_work);

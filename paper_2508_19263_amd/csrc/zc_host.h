@@ -125,6 +125,12 @@ struct CompressQueue {
     uint32_t T;
     bool stats_only;
     uint32_t n_hist, n_lane_hist, n_scale, n_fast, n_whole, n_other, n_slow;     // entries of the work lists
+    // pages in one pass (containers with reversed payload order): the fast list is in natural order, chain_step pages per
+    // item, and one kernel sizes, places and encodes the tensors whose code suits it; the chain's words and its counter
+    // lie at these offsets of the workspace
+    bool chained = false;
+    uint32_t chain_step = 0;
+    uint64_t chain_status = 0, chain_counter = 0;
 
     TensorDev *d_descs() const { return (TensorDev *)(ws + w.descs); }
     uint64_t *d_hist() const { return (uint64_t *)(ws + w.hist); }

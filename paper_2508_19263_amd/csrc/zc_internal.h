@@ -128,7 +128,7 @@ int launch_copy_chunked(const void *d_src, void *d_dst, uint64_t bytes, uint32_t
 int launch_sizes(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                  const uint32_t *d_enc_tables, uint32_t *d_units, void *stream);
 // d_blobs: per tensor the header and code-length tables to put at the start of its container (blob_bytes apart), or null
-int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, bool reversed, const uint32_t *d_units, ScanOut *d_out, const uint8_t *d_blobs,
+int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, bool reversed, int skip_routes, const uint32_t *d_units, ScanOut *d_out, const uint8_t *d_blobs,
                 uint32_t blob_bytes, void *stream);
 int launch_encode(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
                   const uint32_t *d_enc_tables, void *stream);

@@ -440,11 +440,13 @@ int launch_encode(uint32_t fmt, int whole, int skip_routes, const TensorDev *d_d
 // tensor's blob, when blobs is given), the chunk index with the zero padding behind it and the total size into
 // the container (when there is one), and the per-field totals for the host.
 
-__global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fields, int reversed, const uint32_t *units, ScanOut *out,
+__global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fields, int reversed, int skip_routes, const uint32_t *units, ScanOut *out,
                                                const uint8_t *blobs, uint32_t blob_bytes)
 {
     __shared__ uint32_t wave_sum[16];
     __shared__ uint32_t carry_s;
+    // whole workgroup: a tensor of such a route has been placed and written by another kernel (bit r: route r)
+    if ((skip_routes >> descs[blockIdx.x].route) & 1) return;
     // copies of what is needed from the descriptor: the stores below could alias it as far as the compiler knows
     const TensorDev &dg = descs[blockIdx.x];
     struct { uint8_t *comp; uint32_t n_chunks, index_off[kMaxFields]; uint64_t payload_off; } d;
@@ -508,11 +510,12 @@ __global__ __launch_bounds__(1024) void k_scan(const TensorDev *descs, int n_fie
     }
 }
 
-int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, bool reversed, const uint32_t *d_units, ScanOut *d_out, const uint8_t *d_blobs,
-                uint32_t blob_bytes, void *stream)
+int launch_scan(const TensorDev *d_descs, uint32_t n_tensors, int n_fields, bool reversed, int skip_routes, const uint32_t *d_units, ScanOut *d_out,
+                const uint8_t *d_blobs, uint32_t blob_bytes, void *stream)
 {
     if (n_tensors == 0) return 0;
-    hipLaunchKernelGGL(k_scan, dim3(n_tensors), dim3(1024), 0, (hipStream_t)stream, d_descs, n_fields, reversed ? 1 : 0, d_units, d_out, d_blobs, blob_bytes);
+    hipLaunchKernelGGL(k_scan, dim3(n_tensors), dim3(1024), 0, (hipStream_t)stream, d_descs, n_fields, reversed ? 1 : 0, skip_routes, d_units, d_out, d_blobs,
+                       blob_bytes);
     return (int)hipGetLastError();
 }
 

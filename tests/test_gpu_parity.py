@@ -839,6 +839,31 @@ def test_dictionary_compress_of_pages_in_one_pass():
             assert np.array_equal(comp.cpu().numpy(), want)
             with pytest.raises(zc.ZcError):
                 zc.compress_with_code(dev(b), b.numel(), p, code, dst=torch.zeros(len(want) - 16, dtype=torch.uint8, device=DEV))
+    # codes of their own, built on the device: the same kernel takes the tensors whose code suits it (decided on the device),
+    # the generic kernels the others of the same call: here a tensor with a constant exponent field and, with the
+    # limit raised to 12 bits, one whose exponent code is longer than the page kernels take
+    for S, L in ((8, (0, 0, 0)), (16, (12, 0, 0)), (4, (0, 0, 0))):
+        cb = 16 * S * 8
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            p, po = zc.params(zc.FMT_FP8_E4M3, cb, L, S, policy, flags=R), o.params(o.FP8_E4M3, cb, L, S, policy, payload_order=1)
+            steep = np.random.default_rng(5).choice(16, size=800 * cb, p=np.exp2(-np.arange(1, 17, dtype=float)) / np.exp2(-np.arange(1, 17, dtype=float)).sum())
+            srcs = [wl.fp8_weight(2000 * cb, seed=210), torch.full((700 * cb,), 0x38, dtype=torch.uint8), wl.fp8_weight(3 * cb, seed=211),
+                    torch.from_numpy((steep.astype(np.uint8) << 3) | np.random.default_rng(6).integers(0, 8, 800 * cb).astype(np.uint8)), wl.fp8_weight(1031 * cb, seed=212)]
+            print("one pass, own codes S", S, "L", L, "policy", policy, flush=True)
+            bt = zc.Batch([dev(x) for x in srcs], [x.numel() for x in srcs], p)
+            sizes = bt.compress()
+            for t, x in enumerate(srcs):
+                want = o.compress(x.numpy(), x.numel(), po)
+                got = bt.container(t).cpu().numpy()
+                assert sizes[t] == len(want) and np.array_equal(got, want), (t, int(np.argmax(got[:len(want)] != want[:len(got)])))
+            bt.decompress()
+            torch.cuda.synchronize()
+            for t, x in enumerate(srcs):
+                assert torch.equal(bt.out[t].cpu()[:x.numel()], x), t
+            bt.compress_async()
+            assert bt.refresh_info() == sizes
+            for t, x in enumerate(srcs):
+                assert np.array_equal(bt.container(t).cpu().numpy(), o.compress(x.numpy(), x.numel(), po)), t
     rng = np.random.default_rng(78)
 
     def bf16_pages(n, n_exp, skew):
