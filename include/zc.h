@@ -102,7 +102,12 @@ typedef struct {
  *     page: 2.3 x slower from an id list) and every lane's look-ahead words eat the gain (ratio 1.00 against 0.86).
  *   - max_code_len of the exponent field: up to 8 keeps four symbols per refill step for FP8 (the default); 9 to 16
  *     halves the step and costs about 40 % of decode speed for 0.2 % of size on FP8 weights.  For BF16 and for byte
- *     symbols a limit of 11 keeps every code inside the decoders' lookup index (5 to 7 % faster, 0.5 % larger). */
+ *     symbols a limit of 11 keeps every code inside the decoders' lookup index (5 to 7 % faster, 0.5 % larger).
+ * Where the tensors lie: measured on MI355X, a decode call whose output tensors all lie within one stretch of a few tens
+ * of GiB of device memory that was allocated in one go runs about 14 % slower than the same call with its outputs in
+ * two such stretches (2.5 - 2.6 against 2.2 ms for 7 GB of FP8 weights); a plain linear copy shows no such difference.
+ * Nothing in the addresses tells which is which; outputs spread over more of the memory (a larger model, or two
+ * buffers allocated far apart) get the faster case. */
 
 /* zc_params.flags.  HOST_CODES: the compress calls build their codes on the host instead of on the device: the
  * same containers, one more wait per call (the histogram is read back).  What statistics and dictionary
