@@ -266,8 +266,8 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
     page_c = "k_hist + k_codes + k_encode_fp8_sub (sizes) + k_scan + k_encode_fp8_sub"
     run("c5_fp8_kv_pages", zc.FMT_FP8_E4M3, kv, [t.numel() for t in kv], 2048, 8, ids=ids, dictionary=True, decode_kernel="k_decode_fp8_sub<8>", compress_kernels=page_c)
     # the same with the fields in reverse order in the payload (ZC_FLAG_REVERSE_FIELDS): the dictionary call is one pass
-    run("c5_fp8_kv_pages_reverse_fields", zc.FMT_FP8_E4M3, kv, [t.numel() for t in kv], 2048, 8, ids=ids, dictionary=True, decode_kernel="k_decode_fp8_sub<8>", compress_kernels=page_c,
-        flags=zc.FLAG_REVERSE_FIELDS)
+    run("c5_fp8_kv_pages_reverse_fields", zc.FMT_FP8_E4M3, kv, [t.numel() for t in kv], 2048, 8, ids=ids, dictionary=True, decode_kernel="k_decode_fp8_sub<8>",
+        compress_kernels="k_hist + k_codes + k_compress_pages_chained (sizes, scan and encoder in one pass over the source)", flags=zc.FLAG_REVERSE_FIELDS)
     if extras:
         # lanes per page: the tuning of configuration 5 (S = 8 is what the other rows use), and 64 lanes per page, which
         # takes the generic kernels

@@ -142,7 +142,7 @@ zc_status CompressQueue::queue_codes(uint32_t policy) const
 zc_status CompressQueue::queue_sizes_and_scan() const
 {
     if (chained)
-        LAUNCH_TRY(launch_compress_pages_chained(g.S, 0, d_descs(), d_list(w.fast_work), n_fast, chain_step, d_enc(), ws + w.blobs, (uint32_t)kBlobBytes,
+        LAUNCH_TRY(launch_compress_pages_chained(g.S, 0, chain_hold, d_descs(), d_list(w.fast_work), n_fast, chain_step, d_enc(), ws + w.blobs, (uint32_t)kBlobBytes,
                                                  (uint64_t *)(ws + chain_status), (uint64_t *)(ws + chain_counter), (ScanOut *)(ws + w.scan), stream));
     else if (g.S == 64 && sh.lanes) LAUNCH_TRY(launch_sizes_fp8_counts(d_descs(), d_list(w.fast_work), n_fast, d_enc(), d_lane_counts(), d_units(), stream));
     else if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs(), d_list(w.fast_work), n_fast, d_enc(), d_units(), stream));
@@ -536,13 +536,24 @@ private:
         }
         return true;
     }
-    // pages per work item of that kernel: whole passes of a workgroup, few enough that its second read of them comes
-    // from the caches, enough to spread what an item costs besides (C5 on MI355X, 8 lanes: 1.74 / 1.52 / 1.56 / 1.75 ms
-    // with 64 / 128 / 256 / 512 KiB per item; 16 lanes: 2.33 / 1.76 / 1.56 / 1.58 ms with 32 / 64 / 128 / 256 KiB)
+    // Words of LDS per page if that kernel is to keep the exponent streams there until their places are known (the
+    // source is then read once), or 0: the plain size of a page's exponent field (BF16, whose exponents usually code to
+    // a third: half of that), when a workgroup has room for a pass of such pages.  A page whose stream does not fit after
+    // all is coded a second time, so this is a matter of speed only.
+    uint32_t chained_hold() const
+    {
+        const uint32_t words = g.chunk_bytes / (g.fmt == ZC_FMT_BF16 ? 16 : 8), per_pass = kWavesPerGroup * (64 / g.S);
+        return (words % 4 == 0 && words >= 16 && words * per_pass <= compress_pages_held_words()) ? words : 0u;
+    }
+    // pages per work item of that kernel: whole passes of a workgroup.  As many as the LDS holds where the streams are
+    // kept there; else few enough that the second read of them comes from the caches, enough to spread what an item
+    // costs besides (C5 on MI355X, 8 lanes: 1.74 / 1.52 / 1.56 / 1.75 ms with 64 / 128 / 256 / 512 KiB per item; 16 lanes:
+    // 2.33 / 1.76 / 1.56 / 1.58 ms with 32 / 64 / 128 / 256 KiB)
     uint32_t chained_step() const
     {
         const uint32_t per_pass = kWavesPerGroup * (64 / g.S);
         uint32_t passes = 131072 / (per_pass * g.chunk_bytes);     // about 128 KiB per item
+        if (chained_hold()) passes = compress_pages_held_words() / (chained_hold() * per_pass);
         if (passes < 1) passes = 1;
         while (passes * per_pass > compress_pages_chained_limit()) passes--;
         return passes * per_pass;
@@ -552,7 +563,7 @@ private:
         // the chain's words take the place of the stream sizes (one word of 8 bytes per work item: a tensor has at most
         // as many items as chunks, and two sizes of 4 bytes per chunk), its counter that of the first histogram
         uint64_t *status = reinterpret_cast<uint64_t *>(ws + w.units), *counter = reinterpret_cast<uint64_t *>(ws + w.hist);
-        LAUNCH_TRY(launch_compress_pages_chained(g.S, sh.bf16 ? descs[0].period[0] : 0u, q.d_descs(), q.d_list(w.fast_work), q.n_fast, chained_step(), q.d_enc(),
+        LAUNCH_TRY(launch_compress_pages_chained(g.S, sh.bf16 ? descs[0].period[0] : 0u, chained_hold(), q.d_descs(), q.d_list(w.fast_work), q.n_fast, chained_step(), q.d_enc(),
                                                  ws + w.blobs, (uint32_t)kBlobBytes, status, counter, (ScanOut *)(ws + w.scan), stream));
         if (no_sync) {
             for (uint32_t t = 0; t < T; t++) tensors[t].out_bytes = 0;
@@ -595,7 +606,7 @@ private:
             items += (ncs[t] + step - 1) / step;
         }
         if (items + 1 > (uint64_t)T * 3 * 256) return;
-        q.chained = true; q.chain_step = step; q.chain_counter = w.hist; q.chain_status = w.hist + 8;
+        q.chained = true; q.chain_hold = chained_hold(); q.chain_step = step; q.chain_counter = w.hist; q.chain_status = w.hist + 8;
     }
 
     zc_status run_with_device_codes()

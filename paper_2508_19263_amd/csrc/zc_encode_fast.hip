@@ -607,13 +607,22 @@ int launch_encode_bf16(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d
 }
 
 // ---------------------------------------------------------------------------------------
+// what encode_pages does with the exponent streams: count their words, write them through a ring, or keep them in LDS
+constexpr int kPagesSize = 0, kPagesWrite = 1, kPagesHold = 2;
+// words of LDS a workgroup has for the exponent streams it keeps until their places are known (the memory of its rings)
+constexpr uint32_t kHeldWords = kWavesPerGroup * 64 * 32;
+
 // The same shape with fewer than 64 lanes per chunk (small chunks such as K/V-cache pages, whose
 // compression sits on the critical path of a decoding step: Sec. 5.2): a wavefront handles 64/S chunks
 // at once, one per S-lane group.  Ballots are masked to the group, stream positions are per group, and
 // the buffer resources span the tensor and the container's payload with the group's offsets in the
 // vector offset; a lane with nothing to write aims past the end of the resource, where the hardware
-// drops the store.  WRITE = false is the size pass.  A workgroup takes slots_per_group chunks in passes
-// of 4 wavefronts x 64/S.
+// drops the store.  MODE: the size pass; the encoder; or the encoder for callers that learn a page's place only after
+// it is coded (kPagesHold): the sign+mantissa stream goes to chunk * chunk_bytes / 2 of the payload (reverse field
+// order), the exponent stream of the workgroup's i-th chunk stays in words [i * hold, (i + 1) * hold) of `stage`
+// (slots_per_group * hold <= kHeldWords), its units go to `my` as in the size pass, and the result is non-zero in
+// the lanes of a group whose stream did not fit (the caller then codes the pages again with kPagesWrite).
+// A workgroup takes slots_per_group chunks in passes of 4 wavefronts x 64/S.
 //
 // The words of the exponent stream are not stored one by one (a lane's word goes to a position that was
 // handed out earlier, so such stores are scattered 4-byte writes): they are collected in a ring of 32*S
@@ -633,15 +642,17 @@ int launch_encode_bf16(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d
 // The chunks [first, first + slots_per_group) of one tensor, by one workgroup.  pair: the field's table in LDS; stage,
 // pairs_of_rows: the workgroup's staging memory (WRITE only); index0, index1: the chunk index of both fields (WRITE:
 // read; in the container, or wherever the caller keeps it); my: where the sizes go (!WRITE), field 0's at my[chunk],
-// field 1's at my[my_stride + chunk].  rel: what is subtracted from a chunk's number where it indexes index0, index1 and my
+// field 1's at my[my_stride + chunk] unless my_stride is 0.  rel: what is subtracted from a chunk's number where it indexes index0, index1 and my
 // (0 for arrays over the whole tensor, first_chunk for arrays over this call's chunks).
-template <int S, bool WRITE, int BF>
-__device__ __forceinline__ void encode_pages(const TensorDev *dp, uint32_t first_chunk, uint32_t slots_per_group, const uint32_t *pair, uint32_t *stage,
-                                             uint32_t *pairs_of_rows, const uint32_t *index0, const uint32_t *index1, uint32_t *my, uint32_t my_stride,
-                                             uint32_t rel = 0)
+template <int S, int MODE, int BF>
+__device__ __forceinline__ uint32_t encode_pages(const TensorDev *dp, uint32_t first_chunk, uint32_t slots_per_group, const uint32_t *pair, uint32_t *stage,
+                                                 uint32_t *pairs_of_rows, const uint32_t *index0, const uint32_t *index1, uint32_t *my, uint32_t my_stride,
+                                                 uint32_t rel = 0, uint32_t hold = 0)
 {
     static_assert(S >= 4 && S <= 32, "the zero padding of a stream's last unit takes up to 3 lanes of the group");
     static_assert(BF == 0 || BF == 2 || BF == 4 || BF == 8, "FP8, or BF16 with a refill period of 2, 4 or 8");
+    static_assert(MODE == kPagesSize || MODE == kPagesWrite || MODE == kPagesHold, "size pass, encoder, or encoder that keeps the exponent streams in LDS");
+    constexpr bool WRITE = MODE != kPagesSize, HOLD = MODE == kPagesHold;
     constexpr int kPeriods = BF ? 8 / (BF ? BF : 1) : 4;      // refill steps per row
     constexpr uint32_t kGroups = 64 / S;
     constexpr uint32_t kNowhere = 0xFFFFFFF0u;
@@ -656,7 +667,7 @@ __device__ __forceinline__ void encode_pages(const TensorDev *dp, uint32_t first
     const bool sm_raw = uni32(dp->kind[1]) == 2;
     uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
     const uint64_t payload = uni64(dp->payload_off), cap = uni64(dp->dst_bytes);
-    if (n_elems > 0xFFFFFFF0ull) return;                         // the host never launches this
+    if (n_elems > 0xFFFFFFF0ull) return 0;                       // the host never launches this
     const __amdgpu_buffer_rsrc_t src = rsrc_of(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)), (uint32_t)n_elems);
     const __amdgpu_buffer_rsrc_t bas = rsrc_of(has_base ? reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) : nullptr, has_base ? (uint32_t)n_elems : 0u);
     const uint64_t pay_cap = (WRITE && cap > payload) ? (cap - payload > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : cap - payload) : 0;
@@ -664,15 +675,21 @@ __device__ __forceinline__ void encode_pages(const TensorDev *dp, uint32_t first
     const char *pair_lut = reinterpret_cast<const char *>(pair);
     const uint32_t two = 2;
     const uint32_t rows = cb / (16 * S);
-    uint32_t *const ring = stage + (WRITE ? (wave * kGroups + grp) * kRing : 0);
+    uint32_t *ring = stage + (WRITE && !HOLD ? (wave * kGroups + grp) * kRing : 0);
+    constexpr uint32_t kRingMask = HOLD ? 0xFFFFFFFFu : kRing - 1;  // kept streams do not wrap: words beyond their memory are dropped
+    uint32_t did_not_fit = 0;
     uint32_t *const two_rows = pairs_of_rows + (WRITE ? wave * 256 + grp * 4 * S : 0);
 
     for (uint32_t pass = 0; pass * kWavesPerGroup * kGroups < slots_per_group; pass++) {
         const uint32_t local = (pass * kWavesPerGroup + wave) * kGroups + grp;
+        if (HOLD) ring = stage + (local < slots_per_group ? local : 0) * hold;
         const uint32_t chunk = first_chunk + local;
         bool alive = local < slots_per_group && chunk < n_full;  // a short last chunk goes to the generic kernel
         uint32_t e_off = kNowhere, e_len = 0, m_off = kNowhere;
-        if (WRITE && alive) {
+        if (HOLD && alive) {
+            m_off = chunk * (cb / 2);
+            if ((uint64_t)m_off + cb / 2 > pay_cap) alive = false;
+        } else if (WRITE && alive) {
             const uint32_t at = chunk - rel;
             const uint64_t a0 = index0[at], b0 = index0[at + 1], a1 = index1[at], b1 = index1[at + 1];
             // the index must be as the size pass left it, and inside the 32-bit offset space of the payload
@@ -681,6 +698,7 @@ __device__ __forceinline__ void encode_pages(const TensorDev *dp, uint32_t first
             } else alive = false;
         }
         const uint32_t in_off = alive ? chunk * cb : kNowhere;
+        const uint32_t lim = HOLD && alive ? hold : 0u;         // kept streams: a group without a page writes nothing
 
         // the lane's stream: as in the 64-lane encoders, one position due (p0) and at most one more waiting (p1);
         // words asked for and not yet written number (k + nacc) / 32
@@ -785,13 +803,13 @@ __device__ __forceinline__ void encode_pages(const TensorDev *dp, uint32_t first
                     lo |= (uint32_t)placed;
                     nacc += len;
                     const bool full = nacc >= 32;
-                    if (full) ring[p0 & (kRing - 1)] = lo;
+                    if (full && (!HOLD || p0 < lim)) ring[p0 & kRingMask] = lo;
                     lo = full ? (uint32_t)(placed >> 32) : lo;
                     nacc &= 31u;                         // nacc < 64: minus 32 where a word was written
                     p0 = full ? p1 : p0;
                 }
             }
-            if (WRITE) flush_segments();
+            if (WRITE && !HOLD) flush_segments();
         };
         // Four register sets used in turn, each refilled four rows ahead: a page is a few rows, a row a few hundred
         // cycles of work, and the wavefront shares its SIMD with three others at most (the staging rings fill
@@ -811,7 +829,16 @@ __device__ __forceinline__ void encode_pages(const TensorDev *dp, uint32_t first
 #pragma unroll
         for (uint32_t k = 0; k < 3; k++)
             if (row + k < rows) encode_row(x[k] ^ y[k], row + k);
-        if (WRITE) {
+        if (HOLD) {
+            // the words still owed to the decoder and the zero padding of the last 16-byte unit, as below
+            const uint32_t owed = ((uint32_t)k + nacc) >> 5;
+            if (owed > 0 && p0 < lim) ring[p0] = lo;
+            if (owed > 1 && p1 < lim) ring[p1] = 0;
+            if (s < ((4 - (wpos & 3)) & 3) && wpos + s < lim) ring[wpos + s] = 0;
+            const uint32_t end = alive ? (wpos + 3) & ~3u : 0u;  // words of the stream with its padding
+            if (end > hold) did_not_fit = 1;
+            if (local < slots_per_group && s == 0) my[chunk - rel] = end / 4;
+        } else if (WRITE) {
             // the words still owed to the decoder (a partial word and look-ahead words) and the zero padding of
             // the last 16-byte unit go into the ring too; then everything left in it leaves in 16-byte pieces
             const uint32_t owed = ((uint32_t)k + nacc) >> 5;
@@ -831,10 +858,11 @@ __device__ __forceinline__ void encode_pages(const TensorDev *dp, uint32_t first
             for (int o = S / 2; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
             if (alive && s == 0) {
                 my[chunk - rel] = (q + 3) / 4;
-                my[my_stride + chunk - rel] = cb / 32;               // 4 bits per element, 16-byte units (flat code and raw alike)
+                if (my_stride) my[my_stride + chunk - rel] = cb / 32;    // 4 bits per element, 16-byte units (flat code and raw alike)
             }
         }
     }
+    return did_not_fit;
 }
 
 template <int S, bool WRITE, int BF>
@@ -853,7 +881,7 @@ __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, 
     uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
     const uint32_t *index0 = WRITE ? reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[0])) : nullptr;
     const uint32_t *index1 = WRITE ? reinterpret_cast<const uint32_t *>(comp + uni32(dp->index_off[1])) : nullptr;
-    encode_pages<S, WRITE, BF>(dp, it.first, slots_per_group, pair, stage, pairs_of_rows, index0, index1, units + uni32(dp->units_off), uni32(dp->n_chunks));
+    encode_pages<S, WRITE ? kPagesWrite : kPagesSize, BF>(dp, it.first, slots_per_group, pair, stage, pairs_of_rows, index0, index1, units + uni32(dp->units_off), uni32(dp->n_chunks));
 }
 
 // Stream sizes, their scan into the chunk index and the encoder in ONE launch, one workgroup per tensor, for tensors of
@@ -897,7 +925,7 @@ __global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *d
     }
     __syncthreads();
     const uint32_t slots = (nc + kPerPass - 1) / kPerPass * kPerPass;
-    encode_pages<S, false, BF>(dp, 0, slots, pair, stage, pairs_of_rows, nullptr, nullptr, sizes, nc);
+    encode_pages<S, kPagesSize, BF>(dp, 0, slots, pair, stage, pairs_of_rows, nullptr, nullptr, sizes, nc);
     __syncthreads();
     if (tid < 64) {
         // exclusive scan of up to 512 sizes per field by one wavefront, eight consecutive chunks per lane
@@ -932,7 +960,7 @@ __global__ __launch_bounds__(256) void k_compress_pages_fused(const TensorDev *d
             *reinterpret_cast<uint64_t *>(comp + 48) = uni64(dp->payload_off) + 16ull * total;
         }
     }
-    encode_pages<S, true, BF>(dp, 0, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr, 0);
+    encode_pages<S, kPagesWrite, BF>(dp, 0, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr, 0);
 }
 
 template <int S>
@@ -978,14 +1006,17 @@ uint32_t compress_pages_fused_limit() { return kFusedMaxPages; }
 //
 // A workgroup takes the next unclaimed work item (a counter in memory, so that items are claimed in the order in
 // which workgroups start: whoever waits for item j knows that the workgroup of every item before j is running),
-// sizes the item's pages (the encoder's dry run), joins the chain, writes the item's index entries and encodes the
-// pages, reading them a second time from the caches (an item is tens of KiB).  The first item of a tensor writes
-// the container's prologue, the last one the end of both indices, the total size and the totals for the host.
-// A wait in the chain is bounded: a workgroup that gives up (it never should) marks the tensor's totals invalid, and
-// the call reports a device error instead of hanging.
+// codes the item's pages, joins the chain, writes the item's index entries and the exponent streams.  HOLD: the
+// exponent streams wait in LDS for their place, `hold` words per page (an item is as many pages as fit), and the
+// source is read once; should a stream not fit its words, the workgroup codes the item again through the rings once
+// the places are known.  !HOLD (pages too large for that): an item is several passes, sized with the
+// encoder's dry run and encoded in a second run that reads the pages from the caches (an item is tens of KiB).
+// The first item of a tensor writes the container's prologue, the last one the end of both indices, the total size
+// and the totals for the host.  A wait in the chain is bounded: a workgroup that gives up (it never should) marks the
+// tensor's totals invalid, and the call reports a device error instead of hanging.
 constexpr uint32_t kChainItemPages = 256;                    // most pages of one work item
 constexpr uint64_t kChainAggregate = 1ull << 32, kChainPrefix = 2ull << 32;
-constexpr uint32_t kChainSpinLimit = 1u << 20;      // about a tenth of a second
+constexpr uint32_t kChainSpinLimit = 1u << 17;               // rounds of 64 reads: some tenths of a second
 
 __device__ __forceinline__ uint64_t chain_read(uint64_t *p)
 {
@@ -996,24 +1027,60 @@ __device__ __forceinline__ void chain_publish(uint64_t *p, uint64_t v)
     __hip_atomic_exchange(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-template <int S, int BF>
+// By one whole wavefront: the units of all items before `item` back to the start of its tensor.  The 64 lanes read the
+// 64 items before it at once and add up those down to the nearest one that knows its whole prefix, waiting only for
+// items between that one and `item` that have published nothing yet; if none of the 64 knows its prefix the next 64
+// follow.  The first item of a tensor publishes a prefix without looking back, so the walk ends there at the latest.
+// 0xFFFFFFFF: gave up waiting, or an item before this one had.
+__device__ __forceinline__ uint32_t chain_look_back(uint64_t *status, uint32_t item)
+{
+    const uint32_t lane = threadIdx.x & 63;
+    uint32_t before = 0, hi = item, spins = 0;
+    for (;;) {
+        const bool real = lane < hi;
+        const uint64_t st = real ? chain_read(status + (hi - 1 - lane)) : kChainPrefix;     // in front of item 0: nothing, and known
+        const uint32_t flag = (uint32_t)(st >> 32);
+        const uint64_t knows = __ballot(flag == 2), silent = __ballot(flag == 0);
+        const uint32_t stop = knows ? (uint32_t)__builtin_ctzll(knows) : 64u;
+        const uint64_t needed = stop < 63 ? (2ull << stop) - 1 : ~0ull;
+        if (silent & needed) {
+            if (++spins > kChainSpinLimit) return 0xFFFFFFFFu;
+            __builtin_amdgcn_s_sleep(8);
+            continue;
+        }
+        const bool in = lane <= stop;
+        if (__any(in && real && (uint32_t)st == 0xFFFFFFFFu)) return 0xFFFFFFFFu;
+        uint32_t v = in ? (uint32_t)st : 0u;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += (uint32_t)__shfl_xor((int)v, o, 64);
+        before += v;
+        if (stop < 64) return before;
+        hi -= 64;                                               // no lane knew: all 64 were real items, so hi >= 64
+    }
+}
+
+template <int S, int BF, bool HOLD>
 __global__ __launch_bounds__(256) void k_compress_pages_chained(const TensorDev *descs, const WorkItem *work, uint32_t n_work, uint32_t slots_per_item,
                                                                 const uint32_t *enc_tables, const uint8_t *blobs, uint32_t blob_bytes, uint64_t *status,
-                                                                uint64_t *counter, ScanOut *out)
+                                                                uint64_t *counter, ScanOut *out, uint32_t hold)
 {
     constexpr uint32_t kGroups = 64 / S, kRing = 32 * S;
+    static_assert(kWavesPerGroup * kGroups * kRing == kHeldWords, "the rings and the kept streams share their memory");
     __shared__ uint32_t pair[256];
-    __shared__ __attribute__((aligned(16))) uint32_t stage[kWavesPerGroup * kGroups * kRing];
+    __shared__ __attribute__((aligned(16))) uint32_t stage[kHeldWords];
     __shared__ __attribute__((aligned(16))) uint32_t pairs_of_rows[kWavesPerGroup * 256];
-    __shared__ uint32_t sizes[2 * kChainItemPages];               // exponent units of the item's pages; the other half is written and not used
-    __shared__ uint32_t idx0[kChainItemPages + 1], idx1[kChainItemPages + 1];
+    __shared__ uint32_t sizes[kChainItemPages + 1];               // exponent units of the item's pages, then (idx1) the index of the other field
+    __shared__ uint32_t idx0[kChainItemPages + 1];
     __shared__ uint32_t claimed, before_s;
+    uint32_t *const idx1 = sizes;
     const uint32_t tid = threadIdx.x;
+    // an item is whole passes of the workgroup (the launcher checks it too), so that no page of the next item is touched
+    if (slots_per_item == 0 || slots_per_item > kChainItemPages || slots_per_item % (kWavesPerGroup * kGroups)) return;
+    if (HOLD && (hold == 0 || hold % 4 || (uint64_t)slots_per_item * hold > kHeldWords)) return;
     if (tid == 0) claimed = (uint32_t)__hip_atomic_fetch_add(counter, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     const uint32_t item = uni32(claimed);
-    // whole workgroup; an item is whole passes of the workgroup (the launcher checks it too), so that no page of the next item is touched
-    if (item >= n_work || slots_per_item == 0 || slots_per_item > kChainItemPages || slots_per_item % (kWavesPerGroup * kGroups)) return;
+    if (item >= n_work) return;                                 // whole workgroup
     const WorkItem it = work[item];
     const TensorDev *dp = descs + it.tensor;
     const uint32_t nc = uni32(dp->n_chunks), first = uni32(it.first), cb = uni32(dp->chunk_bytes);
@@ -1043,8 +1110,10 @@ __global__ __launch_bounds__(256) void k_compress_pages_chained(const TensorDev 
     }
     __syncthreads();
     const uint32_t slots = (count + kWavesPerGroup * kGroups - 1) / (kWavesPerGroup * kGroups) * (kWavesPerGroup * kGroups);
-    encode_pages<S, false, BF>(dp, first, slots, pair, stage, pairs_of_rows, nullptr, nullptr, sizes, kChainItemPages, first);
-    __syncthreads();
+    // HOLD: the sign+mantissa streams are written here, the exponent streams stay in `stage`
+    const uint32_t did_not_fit = encode_pages<S, HOLD ? kPagesHold : kPagesSize, BF>(dp, first, slots, pair, stage, pairs_of_rows, nullptr, nullptr, sizes,
+                                                                                     0, first, hold);
+    const bool again = __syncthreads_or((int)did_not_fit) != 0;
     if (tid < 64) {
         // exclusive scan of up to 256 sizes by one wavefront, four consecutive pages per lane
         uint32_t v[4], t = 0;
@@ -1058,28 +1127,14 @@ __global__ __launch_bounds__(256) void k_compress_pages_chained(const TensorDev 
         }
         const uint32_t sum = __shfl(x, 63, 64);                 // units of the item's exponent streams
         uint32_t before = 0;
-        if (tid == 0) {
-            if (first == 0) chain_publish(status + item, kChainPrefix | sum);
-            else {
-                chain_publish(status + item, kChainAggregate | sum);
-                bool lost = false;
-                for (uint32_t j = item; j-- > 0 && !lost;) {
-                    uint64_t s = 0;
-                    uint32_t spins = 0;
-                    while (((s = chain_read(status + j)) >> 32) == 0) {
-                        if (++spins > kChainSpinLimit) { lost = true; break; }
-                        __builtin_amdgcn_s_sleep(4);
-                    }
-                    if ((uint32_t)s == 0xFFFFFFFFu) lost = true;  // an item before this one gave up
-                    before += (uint32_t)s;
-                    if ((s >> 32) == 2) break;                  // that item knew everything before it
-                }
-                if (lost) before = 0xFFFFFFFFu;                 // the last item passes it on to the host
-                chain_publish(status + item, kChainPrefix | (lost ? 0xFFFFFFFFull : (uint64_t)(before + sum)));
-            }
-            before_s = before;
+        if (first == 0) {
+            if (tid == 0) chain_publish(status + item, kChainPrefix | sum);
+        } else {
+            if (tid == 0) chain_publish(status + item, kChainAggregate | sum);
+            before = chain_look_back(status, item);             // 0xFFFFFFFF: lost; the last item passes it on to the host
+            if (tid == 0) chain_publish(status + item, kChainPrefix | (before == 0xFFFFFFFFu ? 0xFFFFFFFFull : (uint64_t)(before + sum)));
         }
-        before = __shfl(before, 0, 64);
+        if (tid == 0) before_s = before;
         const uint32_t base0 = nc * per_page + (before == 0xFFFFFFFFu ? 0u : before);
         uint32_t at = base0 + x - t;
 #pragma unroll
@@ -1102,7 +1157,28 @@ __global__ __launch_bounds__(256) void k_compress_pages_chained(const TensorDev 
             *reinterpret_cast<uint64_t *>(comp + 48) = uni64(dp->payload_off) + 16ull * total;
         }
     }
-    encode_pages<S, true, BF>(dp, first, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr, 0, first);
+    if (HOLD && !again) {
+        // every page's stream from LDS to its place, 16 bytes per lane
+        const uint32_t lane = tid & 63, s = lane & (S - 1);
+        const uint64_t payload = uni64(dp->payload_off), cap = uni64(dp->dst_bytes);
+        const uint64_t pay_cap = cap > payload ? (cap - payload > 0xFFFFFFF0ull ? 0xFFFFFFF0ull : cap - payload) : 0;
+        const __amdgpu_buffer_rsrc_t ps = rsrc_of(comp + payload, (uint32_t)pay_cap);
+        for (uint32_t pass = 0; pass * kWavesPerGroup * kGroups < count; pass++) {
+            const uint32_t local = (pass * kWavesPerGroup + (tid >> 6)) * kGroups + lane / S;
+            const bool alive = local < count;
+            const uint32_t *held = stage + (alive ? local : 0) * hold;
+            const uint32_t end = alive ? 4 * (idx0[local + 1] - idx0[local]) : 0u;       // words; at most `hold`, or `again` were set
+            const uint64_t e_off = alive ? 16ull * idx0[local] : 0;
+            const bool fits = alive && e_off + 4ull * end <= pay_cap;
+#pragma unroll 1
+            for (uint32_t at = 4 * s; __any(at < end); at += 4 * S) {
+                const u32x4 w = *reinterpret_cast<const u32x4 *>(held + (at < end ? at : 0u));
+                __builtin_amdgcn_raw_buffer_store_b128(w, ps, (int)(fits && at < end ? (uint32_t)e_off + at * 4 : 0xFFFFFFF0u), 0, 0);
+            }
+        }
+        return;
+    }
+    encode_pages<S, kPagesWrite, BF>(dp, first, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr, 0, first);
 }
 
 __global__ void k_chain_reset(uint64_t *status, uint32_t n_work, uint64_t *counter)
@@ -1112,12 +1188,12 @@ __global__ void k_chain_reset(uint64_t *status, uint32_t n_work, uint64_t *count
     if (i == 0) *counter = 0;
 }
 
-template <int S>
-static void launch_chained_s(uint32_t bf16_period, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t slots_per_item, const uint32_t *d_enc,
+template <int S, bool HOLD>
+static void launch_chained_s(uint32_t hold, uint32_t bf16_period, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t slots_per_item, const uint32_t *d_enc,
                              const uint8_t *d_blobs, uint32_t blob_bytes, uint64_t *d_status, uint64_t *d_counter, ScanOut *d_out, hipStream_t st)
 {
-#define ZC_CHAINED(BF) hipLaunchKernelGGL((k_compress_pages_chained<S, BF>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, n_work, slots_per_item, d_enc, d_blobs, \
-                                          blob_bytes, d_status, d_counter, d_out)
+#define ZC_CHAINED(BF) hipLaunchKernelGGL((k_compress_pages_chained<S, BF, HOLD>), dim3(n_work), dim3(256), 0, st, d_descs, d_work, n_work, slots_per_item, d_enc, \
+                                          d_blobs, blob_bytes, d_status, d_counter, d_out, hold)
     switch (bf16_period) {
     case 0: ZC_CHAINED(0); break;
     case 2: ZC_CHAINED(2); break;
@@ -1130,25 +1206,33 @@ static void launch_chained_s(uint32_t bf16_period, const TensorDev *d_descs, con
 // streams: 4, 8, 16 or 32.  bf16_period: 0 for FP8 tensors (route 1), else the one refill period of the exponent field that
 // every BF16 tensor of the call has (route 2).  Work items in natural order (tensor by tensor, pages ascending), each
 // slots_per_item pages (a multiple of the pages a workgroup takes per pass, at most compress_pages_chained_limit()).
-// d_status: n_work words, d_counter: one word; both are reset here.
-int launch_compress_pages_chained(uint32_t streams, uint32_t bf16_period, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t slots_per_item,
-                                  const uint32_t *d_enc, const uint8_t *d_blobs, uint32_t blob_bytes, uint64_t *d_status, uint64_t *d_counter, ScanOut *d_out,
-                                  void *stream)
+// hold: 0, or the words of LDS per page (a multiple of 4) of the build that keeps the exponent streams there and reads
+// the source once; slots_per_item * hold is then at most compress_pages_held_words().  d_status: n_work words,
+// d_counter: one word; both are reset here.
+int launch_compress_pages_chained(uint32_t streams, uint32_t bf16_period, uint32_t hold, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+                                  uint32_t slots_per_item, const uint32_t *d_enc, const uint8_t *d_blobs, uint32_t blob_bytes, uint64_t *d_status,
+                                  uint64_t *d_counter, ScanOut *d_out, void *stream)
 {
     if (n_work == 0) return 0;
     if (slots_per_item == 0 || slots_per_item > kChainItemPages || (bf16_period != 0 && bf16_period != 2 && bf16_period != 4 && bf16_period != 8)) return 1;
     if (streams < 4 || streams > 32 || slots_per_item % (kWavesPerGroup * (64 / streams))) return 1;
+    if (hold % 4 || (uint64_t)slots_per_item * hold > kHeldWords) return 1;
     hipStream_t st = (hipStream_t)stream;
     hipLaunchKernelGGL(k_chain_reset, dim3((n_work + 255) / 256), dim3(256), 0, st, d_status, n_work, d_counter);
+#define ZC_CHAINED_S(S, HOLD) launch_chained_s<S, HOLD>(hold, bf16_period, d_descs, d_work, n_work, slots_per_item, d_enc, d_blobs, blob_bytes, d_status, d_counter, d_out, st)
     switch (streams) {
-    case 4: launch_chained_s<4>(bf16_period, d_descs, d_work, n_work, slots_per_item, d_enc, d_blobs, blob_bytes, d_status, d_counter, d_out, st); break;
-    case 8: launch_chained_s<8>(bf16_period, d_descs, d_work, n_work, slots_per_item, d_enc, d_blobs, blob_bytes, d_status, d_counter, d_out, st); break;
-    case 16: launch_chained_s<16>(bf16_period, d_descs, d_work, n_work, slots_per_item, d_enc, d_blobs, blob_bytes, d_status, d_counter, d_out, st); break;
-    case 32: launch_chained_s<32>(bf16_period, d_descs, d_work, n_work, slots_per_item, d_enc, d_blobs, blob_bytes, d_status, d_counter, d_out, st); break;
+    case 4: if (hold) ZC_CHAINED_S(4, true); else ZC_CHAINED_S(4, false); break;
+    case 8: if (hold) ZC_CHAINED_S(8, true); else ZC_CHAINED_S(8, false); break;
+    case 16: if (hold) ZC_CHAINED_S(16, true); else ZC_CHAINED_S(16, false); break;
+    case 32: if (hold) ZC_CHAINED_S(32, true); else ZC_CHAINED_S(32, false); break;
     default: return 1;
     }
+#undef ZC_CHAINED_S
     return (int)hipGetLastError();
 }
+
+// words of LDS a workgroup of the `hold` build has for the exponent streams of a work item
+uint32_t compress_pages_held_words() { return kHeldWords; }
 
 uint32_t compress_pages_chained_limit() { return kChainItemPages; }
 

@@ -129,6 +129,7 @@ struct CompressQueue {
     // item, and one kernel sizes, places and encodes the tensors whose code suits it; the chain's words and its counter
     // lie at these offsets of the workspace
     bool chained = false;
+    uint32_t chain_hold = 0;                                   // words of LDS per page where that kernel keeps the exponent streams, else 0
     uint32_t chain_step = 0;
     uint64_t chain_status = 0, chain_counter = 0;
 

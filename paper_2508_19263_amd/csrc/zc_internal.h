@@ -170,10 +170,11 @@ int launch_compress_pages_fused(uint32_t streams, uint32_t bf16_periods, bool re
                                 const uint8_t *d_blobs, uint32_t blob_bytes, ScanOut *d_out, void *stream);
 uint32_t compress_pages_fused_limit();      // most pages per tensor the fused kernel takes
 // pages in one pass over the source: containers with their fields in reverse order, dictionary calls; see the kernel
-int launch_compress_pages_chained(uint32_t streams, uint32_t bf16_period, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint32_t slots_per_item,
-                                  const uint32_t *d_enc, const uint8_t *d_blobs, uint32_t blob_bytes, uint64_t *d_status, uint64_t *d_counter, ScanOut *d_out,
-                                  void *stream);
+int launch_compress_pages_chained(uint32_t streams, uint32_t bf16_period, uint32_t hold, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work,
+                                  uint32_t slots_per_item, const uint32_t *d_enc, const uint8_t *d_blobs, uint32_t blob_bytes, uint64_t *d_status,
+                                  uint64_t *d_counter, ScanOut *d_out, void *stream);
 uint32_t compress_pages_chained_limit();    // most pages per work item of that kernel
+uint32_t compress_pages_held_words();       // words of LDS for the exponent streams of a work item in its `hold` build
 int launch_encode_fp8_sub(uint32_t streams, int write, bool bf16, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
                           uint32_t *d_units, uint32_t slots_per_group, void *stream);
 uint32_t chunks_per_work_item(uint32_t streams);

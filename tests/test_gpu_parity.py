@@ -839,6 +839,47 @@ def test_dictionary_compress_of_pages_in_one_pass():
             assert np.array_equal(comp.cpu().numpy(), want)
             with pytest.raises(zc.ZcError):
                 zc.compress_with_code(dev(b), b.numel(), p, code, dst=torch.zeros(len(want) - 16, dtype=torch.uint8, device=DEV))
+    # Where the pages are small enough the kernel keeps every page's exponent stream in LDS until its place is known and
+    # reads the source once.  Pages of 2 KiB (a stream may take 256 words there), coded with a dictionary that was
+    # trained on other data, so that the streams of some pages (the whole tensor, every third page, one page) are
+    # longer than the plain field and do not fit: their work items are coded a second time.  Pages of 4 and 8 KiB,
+    # which the kernel sizes first and reads twice.
+    rng = np.random.default_rng(91)
+    for S in (8, 16, 32):
+        cb = 2048
+        p, po = zc.params(zc.FMT_FP8_E4M3, cb, streams=S, flags=R), o.params(o.FP8_E4M3, cb, streams=S, payload_order=1)
+        a = wl.fp8_weight(300 * cb, seed=230)
+        code = zc.train_code(dev(a), a.numel(), p)
+        ln, md = o.train_code(a.numpy(), a.numel(), po)
+        rare = torch.from_numpy((rng.integers(0, 3, 700 * cb).astype(np.uint8) << 3) | rng.integers(0, 8, 700 * cb).astype(np.uint8))   # exponents the dictionary gives its longest codes
+        usual = wl.fp8_weight(700 * cb, seed=231)
+        third = usual.clone().reshape(700, cb)
+        third[::3] = rare.reshape(700, cb)[::3]
+        one = usual.clone().reshape(700, cb)
+        one[333] = rare.reshape(700, cb)[333]
+        for name, b in (("rare", rare), ("every third page", third.reshape(-1)), ("one page", one.reshape(-1)), ("usual", usual)):
+            print("one pass, streams kept in LDS, S", S, name, flush=True)
+            want = o.compress_with_code(b.numpy(), b.numel(), po, ln, md)
+            comp, info = zc.compress_with_code(dev(b), b.numel(), p, code)
+            got = comp.cpu().numpy()
+            assert got.shape == want.shape and np.array_equal(got, want), int(np.argmax(got[:len(want)] != want[:len(got)]))
+            out, _ = zc.decompress(comp, zc.read_info(comp, check_index=True))
+            torch.cuda.synchronize()
+            assert torch.equal(out.cpu(), b)
+        bt = zc.Batch([dev(x) for x in (usual, rare, third.reshape(-1))], [700 * cb] * 3, p)
+        bt.compress_async(code)
+        sizes = bt.refresh_info()
+        for t, x in enumerate((usual, rare, third.reshape(-1))):
+            want = o.compress_with_code(x.numpy(), x.numel(), po, ln, md)
+            assert sizes[t] == len(want) and np.array_equal(bt.container(t).cpu().numpy(), want), t
+        for cb in (4096, 8192):
+            p, po = zc.params(zc.FMT_FP8_E4M3, cb, streams=S, flags=R), o.params(o.FP8_E4M3, cb, streams=S, payload_order=1)
+            b = wl.fp8_weight(517 * cb, seed=232)
+            print("one pass, pages sized first, S", S, "page", cb, flush=True)
+            code = zc.train_code(dev(a), a.numel(), p)
+            ln, md = o.train_code(a.numpy(), a.numel(), po)
+            comp, info = zc.compress_with_code(dev(b), b.numel(), p, code)
+            assert np.array_equal(comp.cpu().numpy(), o.compress_with_code(b.numpy(), b.numel(), po, ln, md))
     # codes of their own, built on the device: the same kernel takes the tensors whose code suits it (decided on the device),
     # the generic kernels the others of the same call: here a tensor with a constant exponent field and, with the
     # limit raised to 12 bits, one whose exponent code is longer than the page kernels take
