@@ -241,8 +241,10 @@ zc_status zc_compress_noalloc(const void *d_src, uint64_t n_elems, const zc_para
  * complete prefix code over the whole alphabet is rejected with ZC_ERR_INVALID_ARG.
  * K/V pages (FP8 or BF16, 4 to 32 lanes, every tensor whole pages): a call whose tensors have at most 512 pages each runs as
  * one kernel, one workgroup per tensor; with ZC_FLAG_REVERSE_FIELDS a call over tensors of any number of pages runs as
- * one kernel that reads the pages once (on MI355X 1.5 against 1.8 ms for 2.1 GB of FP8 pages); otherwise a size pass,
- * a scan and an encoder are queued.  The containers are the same whichever way they were written.
+ * one kernel that reads the pages once (on MI355X 1.4 against 1.7 ms for 2.1 GB of FP8 pages; fastest for FP8 pages of
+ * at most 2 KiB and BF16 pages of at most 4 KiB, whose coded exponents wait on chip for their place, and with a
+ * dictionary that suits the data: a page whose coded exponents are longer than the plain ones is coded twice);
+ * otherwise a size pass, a scan and an encoder are queued.  The containers are the same whichever way they were written.
  * zc_code_stale (host arithmetic only) is the refresh test of Sec. 3.3: 1 when the container
  * described by *written (from a *_with_code call) is larger, as a fraction of its raw size, than
  * the training tensor's was by more than `slack` (absolute, e.g. 0.02), 0 when not, -1 on
