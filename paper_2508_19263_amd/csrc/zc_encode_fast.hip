@@ -195,18 +195,30 @@ __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, 
     uint32_t *const part = cnt;
 #pragma unroll
     for (int i = 0; i < 8; i++) part[(quarter * 64 + lane) * 9 + i] = ce[i];
-    // the chunk's field histograms: every lane of this wavefront holds partial counts of the same 16 symbols
+    // the chunk's field histograms: every lane of this wavefront holds partial counts of the same 16 symbols.  They are
+    // summed over the lanes in a butterfly that halves what a lane carries at every step (8, 4, 2 and 1 exchanges, then
+    // two more of the one value left), so that lane j < 16 ends with the total of symbol j.
+    {
+        uint32_t c[16];
 #pragma unroll
-    for (int i = 0; i < 8; i++) {
+        for (int i = 0; i < 8; i++) { c[i] = ce[i]; c[8 + i] = cm[i]; }
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) { ce[i] += __shfl_xor(ce[i], o, 64); cm[i] += __shfl_xor(cm[i], o, 64); }
-    }
-    if (lane == 0) {
-        unsigned long long *slot = reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + 1) * 256]);
+        for (int step = 0; step < 4; step++) {
+            const int n = 8 >> step;                             // values kept per lane after this step
+            const bool upper = (lane >> step) & 1;
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-            if (ce[i]) atomicAdd(slot + e0 + i, (unsigned long long)ce[i]);
-            if (cm[i]) atomicAdd(slot + 16 + s * 8 + i, (unsigned long long)cm[i]);
+            for (int i = 0; i < n; i++) {
+                const uint32_t give = upper ? c[i] : c[n + i], keep = upper ? c[n + i] : c[i];
+                c[i] = keep + (uint32_t)__shfl_xor((int)give, 1 << step, 64);
+            }
+        }
+        c[0] += (uint32_t)__shfl_xor((int)c[0], 16, 64);
+        c[0] += (uint32_t)__shfl_xor((int)c[0], 32, 64);
+        // bit `step` of the lane chose the half it kept at that step, i.e. bit 3 - step of the symbol
+        const uint32_t sym = ((lane & 1) << 3) | ((lane & 2) << 1) | ((lane & 4) >> 1) | ((lane & 8) >> 3);
+        if (lane < 16 && c[0]) {
+            unsigned long long *slot = reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + 1) * 256]);
+            atomicAdd(slot + (sym < 8 ? e0 + sym : 16 + s * 8 + (sym - 8)), (unsigned long long)c[0]);
         }
     }
     __syncthreads();
