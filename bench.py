@@ -193,7 +193,7 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
             for hb, code, sub in halves:
                 hb.plan_decompress()
                 hb.run_decompress()
-                oks = oks and all(torch.equal(o.view(torch.uint8)[:s.numel()], s.view(torch.uint8).reshape(-1)) for o, s in zip(hb.out, sub))
+                oks = oks and all(torch.equal(o.view(torch.uint8)[:s.numel() * s.element_size()], s.view(torch.uint8).reshape(-1)) for o, s in zip(hb.out, sub))
             r.update({"static_dictionary_compress_ms": _median(ts), "static_dictionary_compress_ms_min": ts[0],
                       "static_dictionary_compress_GBps": raw / _median(ts) / 1e6,
                       "static_dictionary_ratio_total": dsizes / raw, "static_dictionary_round_trip_bit_exact": bool(oks),
@@ -319,6 +319,9 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
         ids = [wl.page_sample(n_pages, 0.25, device=dev, seed=800 + i) for i in range(len(kv))]
         # AUTO: the sign+mantissa bytes do not compress and are stored as they are (Sec. 3.1)
         run("bf16_kv_pages", zc.FMT_BF16, kv, [t.numel() for t in kv], 4096, 8, ids=ids, policy=zc.POLICY_AUTO, decode_kernel="k_decode_bf16_sub<8>", compress_kernels="k_hist + k_codes + k_encode_fp8_sub<BF16> (sizes) + k_scan + k_encode_fp8_sub<BF16>")
+        # with the fields in reverse order a dictionary call codes, places and writes these pages in one read of them
+        run("bf16_kv_pages_reverse_fields", zc.FMT_BF16, kv, [t.numel() for t in kv], 4096, 8, ids=ids, policy=zc.POLICY_AUTO, dictionary=True, flags=zc.FLAG_REVERSE_FIELDS,
+            decode_kernel="k_decode_bf16_sub<8>", compress_kernels="k_hist + k_codes + k_encode_fp8_sub<BF16> (sizes) + k_scan + k_encode_fp8_sub<BF16>")
     return out
 
 
