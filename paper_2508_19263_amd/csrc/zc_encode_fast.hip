@@ -278,6 +278,166 @@ __global__ __launch_bounds__(256) void k_sizes_fp8_counts(const TensorDev *descs
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// The same two reads instead of three for the formats whose fields are 8-bit symbols, 8 per 16-byte run (BF16;
+// FP8 in byte symbols), with 64 lanes and chunks of kHistBlockBytes: weights, checkpoints and checkpoint deltas
+// (Sec. 3.1, 4.1).  A lane's field has 256 possible symbols, so its counts are 512 bytes per field and lane, 64 KiB
+// per chunk: a quarter of the chunk, written once here and read once by k_sizes_rows8_counts, against a whole
+// second read of the source (and of the base of a delta) by the generic size pass.
+//
+// k_hist_rows8_lanes: one workgroup of eight wavefronts per whole chunk.  Thread t takes the runs t, t + 512, ...:
+// all of chunk lane t % 64.  LDS holds, per field, a histogram of the 256 symbols per lane in the layout of
+// k_hist_fp8_lanes (16-bit counters, lanes l and l + 32 in the halves of word [symbol][l % 32]: conflict-free
+// whatever the data; a lane holds 2,048 symbols of a field).  At the end the arrays go to lane_counts as they are
+// (field, symbol, word: 64 KiB at lane_counts + chunk * 16384 words), and their sums over the lanes are added to the
+// tensor's two histograms, where k_hist adds its own.
+template <int FMT>
+__global__ __launch_bounds__(512) void k_hist_rows8_lanes(const TensorDev *descs, const WorkItem *work, uint64_t *hist, uint32_t *lane_counts)
+{
+    static_assert(Fmt<FMT>::G == 8 && Fmt<FMT>::SB == 8 && Fmt<FMT>::NF == 2, "two fields of eight 8-bit symbols per run");
+    static_assert(kHistBlockBytes / 16 / 64 * 8 < 65536, "a lane's count of one symbol fits 16 bits");
+    __shared__ __attribute__((aligned(16))) uint32_t cnt[2 * 256 * 32];      // 64 KiB
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev &d = descs[it.tensor];
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    const uint64_t start = (uint64_t)it.first * kHistBlockBytes, nbytes = d.n_elems * (uint64_t)Fmt<FMT>::EB / 8;
+    if (d.chunk_bytes != kHistBlockBytes || start + kHistBlockBytes > nbytes) return;          // whole workgroup; the host never asks for this
+    uint4 *const cnt4 = reinterpret_cast<uint4 *>(cnt);
+    for (uint32_t i = tid; i < 2 * 256 * 32 / 4; i += 512) cnt4[i] = make_uint4(0, 0, 0, 0);
+    __syncthreads();
+    const uint8_t *p = d.src + start;
+    const uint8_t *base = d.base ? d.base + start : nullptr;
+    const uint32_t l4 = (lane & 31) * 4, inc = lane < 32 ? 1u : 0x10000u;
+    char *const lds0 = reinterpret_cast<char *>(cnt), *const lds1 = lds0 + 256 * 32 * 4;
+    auto count = [&](const uint4 &v) {
+        uint64_t P0, P1;
+        split_run<FMT>(v, P0, P1);
+        const uint32_t w0[2] = {(uint32_t)P0, (uint32_t)(P0 >> 32)}, w1[2] = {(uint32_t)P1, (uint32_t)(P1 >> 32)};
+#pragma unroll
+        for (int i = 0; i < 2; i++) {
+            atomicAdd(reinterpret_cast<uint32_t *>(lds0 + (((w0[i] << 7) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds0 + (((w0[i] >> 1) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds0 + (((w0[i] >> 9) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds0 + (((w0[i] >> 17) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds1 + (((w1[i] << 7) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds1 + (((w1[i] >> 1) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds1 + (((w1[i] >> 9) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds1 + (((w1[i] >> 17) & 0x7F80u) | l4)), inc);
+        }
+    };
+    // eight 16-byte loads per thread in flight at a time
+    constexpr uint32_t kStep = 512 * 16, kDepth = 8;
+    static_assert(kHistBlockBytes % (kStep * kDepth) == 0, "whole rounds");
+    for (uint32_t off = tid * 16; off < kHistBlockBytes; off += kDepth * kStep) {
+        uint4 v[kDepth];
+#pragma unroll
+        for (uint32_t k = 0; k < kDepth; k++) v[k] = *reinterpret_cast<const uint4 *>(p + off + k * kStep);
+        if (base) {
+#pragma unroll
+            for (uint32_t k = 0; k < kDepth; k++) v[k] = xor4(v[k], *reinterpret_cast<const uint4 *>(base + off + k * kStep));
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < kDepth; k++) count(v[k]);
+    }
+    __syncthreads();
+    // the counts per lane, as they lie
+    const uint64_t chunk_global = (uint64_t)(d.units_off / 2) + it.first;          // two fields: units_off counts two entries per chunk
+    uint4 *const out = reinterpret_cast<uint4 *>(lane_counts + chunk_global * (2 * 256 * 32));
+    for (uint32_t i = tid; i < 2 * 256 * 32 / 4; i += 512) out[i] = cnt4[i];
+    // thread (field, symbol) sums the symbol's 64 lanes, starting at a different word per thread (different banks)
+    const uint32_t f = tid >> 8, bin = tid & 255;
+    uint32_t sum = 0;
+#pragma unroll 8
+    for (uint32_t r = 0; r < 32; r++) {
+        const uint32_t c = cnt[(f * 256 + bin) * 32 + ((r + bin) & 31)];
+        sum += (c & 0xFFFFu) + (c >> 16);
+    }
+    if (sum) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + f) * 256 + bin]), (unsigned long long)sum);
+}
+
+// Stream sizes of whole chunks from those counts, for the tensors the 64-lane encoder of these formats takes (route 2:
+// exponent field table coded, sign+mantissa field flat, raw or table coded).  A table-coded field: as in
+// k_sizes_fp8_counts, with R symbols per refill step (R codes are at most 32 bits, which is all the argument there
+// needs): a lane's words are min(steps, floor((bits - bits of its last R codes) / 32) + 2), its bits the counts times
+// the code lengths.  A flat or raw field takes its plain size.  One wavefront per chunk, work items as for the
+// generic whole-chunk size pass.  A wavefront reads a field's counts 16 bytes per lane (eight symbols' rows of 32
+// words per load), so a lane gathers parts of eight chunk lanes' bit totals; LDS additions bring them together.
+template <int FMT>
+__global__ __launch_bounds__(256) void k_sizes_rows8_counts(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables,
+                                                            const uint32_t *lane_counts, uint32_t *units)
+{
+    __shared__ uint32_t lens[2][256];
+    __shared__ uint32_t total[kWavesPerGroup][2][64];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev *dp = descs + it.tensor;
+    if (dp->route != 2) return;                                  // whole workgroup: the generic size pass takes this tensor
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    lens[0][tid] = enc_tables[(uint64_t)it.tensor * 768 + tid] >> 16;
+    lens[1][tid] = enc_tables[(uint64_t)it.tensor * 768 + 256 + tid] >> 16;
+    total[wave][0][lane] = 0;
+    total[wave][1][lane] = 0;
+    __syncthreads();
+    const uint32_t chunk = uni32(it.first + wave);
+    const uint32_t cb = uni32(dp->chunk_bytes);
+    const uint64_t nbytes = uni64(dp->n_elems) * (uint64_t)Fmt<FMT>::EB / 8;
+    const bool mine = cb == kHistBlockBytes && chunk < (uint32_t)(nbytes / cb);
+    const uint64_t chunk_global = (uint64_t)(uni32(dp->units_off) / 2) + (mine ? chunk : 0u);
+    const uint32_t kind[2] = {uni32(dp->kind[0]), uni32(dp->kind[1])};       // 0 table coded, 1 flat code, 2 raw, 3 constant
+    const bool coded[2] = {kind[0] == 0, kind[1] == 0};
+    if (mine) {
+#pragma unroll
+        for (int f = 0; f < 2; f++) {
+            if (!coded[f]) continue;
+            const uint4 *rows = reinterpret_cast<const uint4 *>(lane_counts + chunk_global * (2 * 256 * 32) + f * (256 * 32)) + lane;
+            uint32_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll 4
+            for (uint32_t i = 0; i < 32; i++) {
+                const uint4 c = rows[i * 64];                    // symbol 8 * i + lane / 8, chunk lanes 4 * (lane % 8) .. + 3 and those + 32
+                const uint32_t len = lens[f][8 * i + (lane >> 3)];
+                const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+                for (int k = 0; k < 4; k++) { acc[k] += (w[k] & 0xFFFFu) * len; acc[4 + k] += (w[k] >> 16) * len; }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                atomicAdd(&total[wave][f][4 * (lane & 7) + k], acc[k]);
+                atomicAdd(&total[wave][f][32 + 4 * (lane & 7) + k], acc[4 + k]);
+            }
+        }
+    }
+    __syncthreads();
+    if (!mine) return;
+    // the lane's last run: its last R symbols of either field
+    const uint64_t at = (uint64_t)chunk * cb + (cb - 1024) + lane * 16;
+    uint4 v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)) + at);
+    if (uni64((uint64_t)dp->base) != 0) v = xor4(v, *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) + at));
+    uint64_t P[2];
+    split_run<FMT>(v, P[0], P[1]);
+    uint32_t u[2];
+#pragma unroll
+    for (int f = 0; f < 2; f++) {
+        if (!coded[f]) {
+            u[f] = kind[f] == 3 ? 0u : cb / 32;                   // 8 bits per symbol, half the chunk's bytes; a constant field: nothing
+            continue;
+        }
+        const uint32_t R = uni32(dp->period[f]);                 // 2, 4 or 8
+        uint32_t last = 0;
+        for (uint32_t j = 8 - R; j < 8; j++) last += lens[f][(uint32_t)(P[f] >> (8 * j)) & 0xFFu];
+        const uint32_t steps = cb / 1024 * 8 / R;
+        uint32_t q = ((total[wave][f][lane] - last) >> 5) + 2;
+        q = q < steps ? q : steps;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+        u[f] = (q + 3) / 4;
+    }
+    if (lane == 0) {
+        uint32_t *my = units + uni32(dp->units_off);
+        const uint32_t nc = uni32(dp->n_chunks);
+        my[chunk] = u[0];
+        my[nc + chunk] = u[1];
+    }
+}
+
 __global__ __launch_bounds__(256) void k_encode_fp8(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables)
 {
     constexpr uint32_t kSeg = 256, kRing = 2048;                // words: 16 bytes per lane; 32 words per lane
@@ -1298,6 +1458,30 @@ int launch_sizes_fp8_counts(const TensorDev *d_descs, const WorkItem *d_work, ui
 {
     if (n_work == 0) return 0;
     hipLaunchKernelGGL(k_sizes_fp8_counts, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
+    return (int)hipGetLastError();
+}
+
+// fmt: ZC_FMT_BF16 or ZC_FMT_FP8_E4M3_BYTES.  One work item per whole chunk of kHistBlockBytes.
+int launch_hist_rows8_lanes(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint32_t *d_lane_counts, void *stream)
+{
+    if (n_work == 0) return 0;
+    if (fmt == ZC_FMT_BF16) hipLaunchKernelGGL(k_hist_rows8_lanes<ZC_FMT_BF16>, dim3(n_work), dim3(512), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
+    else if (fmt == ZC_FMT_FP8_E4M3_BYTES)
+        hipLaunchKernelGGL(k_hist_rows8_lanes<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(512), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
+    else return 1;
+    return (int)hipGetLastError();
+}
+
+// work items of kWavesPerGroup whole chunks, as for the generic whole-chunk size pass
+int launch_sizes_rows8_counts(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
+                              const uint32_t *d_lane_counts, uint32_t *d_units, void *stream)
+{
+    if (n_work == 0) return 0;
+    if (fmt == ZC_FMT_BF16)
+        hipLaunchKernelGGL(k_sizes_rows8_counts<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
+    else if (fmt == ZC_FMT_FP8_E4M3_BYTES)
+        hipLaunchKernelGGL(k_sizes_rows8_counts<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
+    else return 1;
     return (int)hipGetLastError();
 }
 

@@ -149,6 +149,57 @@ def test_config4_checkpoint_delta_reduced():
     check_case(zc.FMT_BF16, n, 65536, 64, policy=zc.POLICY_AUTO, data=(w1, None), base=w0, tag="config4-delta-auto")
 
 
+def test_stream_sizes_from_lane_counts_of_8_bit_symbols():
+    # BF16 and FP8 in byte symbols with 64 lanes and chunks of 256 KiB: the histogram pass also counts both fields' symbols
+    # per chunk lane, and the size pass of the tensors the 64-lane encoder takes works from those counts instead of reading
+    # the source again.  Every refill period of the exponent field (codes of up to 16, 8 and 4 bits: 2, 4 and 8 symbols per step), a
+    # sign+mantissa field that is flat, raw, table coded (a delta, periods 2 and 4) or constant, a short last chunk, a
+    # tensor shorter than a chunk, and a batch whose tensors go different ways
+    cb = 262144
+    rng = np.random.default_rng(17)
+
+    def bf16_of(n, n_exp, sm_bits):
+        ex = (rng.integers(0, n_exp, n).astype(np.uint16) + 100) & 0xFF
+        sm = rng.integers(0, 1 << sm_bits, n).astype(np.uint16)
+        return torch.from_numpy((((sm >> 7) << 15) | (ex << 7) | (sm & 0x7F)).astype(np.uint16).view(np.uint8).copy())
+
+    n = 5 * (cb // 2) + 12345
+    for n_exp, L in ((40, (0, 0, 0)), (40, (8, 0, 0)), (12, (0, 0, 0)), (200, (0, 0, 0)), (3, (0, 0, 0))):
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            check_case(zc.FMT_BF16, n, cb, 64, policy, L=L, data=(bf16_of(n, n_exp, 8), None), tag="bf16-lane-counts")
+    w0, w1 = wl.bf16_checkpoint_pair(n, seed=41)
+    w0, w1 = w0.view(torch.uint8), w1.view(torch.uint8)
+    for L in ((0, 0, 0), (16, 8, 0), (8, 8, 0), (11, 11, 0)):
+        check_case(zc.FMT_BF16, n, cb, 64, L=L, data=(w1, None), base=w0, tag="bf16-lane-counts-delta")
+    check_case(zc.FMT_BF16, n, cb, 64, data=(w1, None), base=w1, tag="bf16-lane-counts-constant")
+    check_case(zc.FMT_BF16, n, cb, 64, data=(bf16_of(n, 1, 8), None), tag="bf16-lane-counts-one-exponent")
+    check_case(zc.FMT_BF16, n, cb, 64, data=(bf16_of(n, 30, 0), None), tag="bf16-lane-counts-one-mantissa")
+    check_case(zc.FMT_BF16, 3 * (cb // 2), cb, 64, data=(bf16_of(3 * (cb // 2), 30, 8), None), tag="bf16-lane-counts-whole")
+    check_case(zc.FMT_BF16, 1000, cb, 64, data=(bf16_of(1000, 30, 8), None), tag="bf16-lane-counts-short")
+    a = wl.fp8_weight(4 * cb + 777, seed=42)
+    for L in ((0, 0, 0), (11, 0, 0), (8, 8, 0)):
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            check_case(zc.FMT_FP8_E4M3_BYTES, a.numel(), cb, 64, policy, L=L, data=(a, None), tag="fp8-bytes-lane-counts")
+    b = wl.fp8_weight(4 * cb + 777, seed=43)
+    check_case(zc.FMT_FP8_E4M3_BYTES, a.numel(), cb, 64, data=(a, None), base=b, tag="fp8-bytes-lane-counts-delta")
+    # a batch: tensors with a table-coded, a raw and a constant second field, whole and ragged, queued without a wait too
+    srcs = [bf16_of(2 * (cb // 2), 40, 8), w1, bf16_of(cb // 2 + 8, 1, 3), bf16_of(7 * (cb // 2), 9, 8)]
+    bases = [torch.zeros_like(srcs[0]), w0, torch.zeros_like(srcs[2]), torch.zeros_like(srcs[3])]      # a batch has bases for all or none
+    for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+        p, po = zc.params(zc.FMT_BF16, cb, policy=policy), o.params(o.BF16, cb, policy=policy)
+        bt = zc.Batch([dev(x) for x in srcs], [x.numel() // 2 for x in srcs], p, xor_bases=[dev(x) for x in bases])
+        sizes = bt.compress()
+        for t, x in enumerate(srcs):
+            want = o.compress(x.numpy(), x.numel() // 2, po, xor_base=bases[t].numpy())
+            assert sizes[t] == len(want) and np.array_equal(bt.container(t).cpu().numpy(), want), (policy, t)
+        bt.compress_async()
+        assert bt.refresh_info() == sizes
+        bt.decompress()
+        torch.cuda.synchronize()
+        for t, x in enumerate(srcs):
+            assert torch.equal(bt.out[t].cpu()[:x.numel()], x), t
+
+
 def test_config5_kv_pages_random_access():
     # pages of 16 tokens x 128 = 2 KiB are the chunks; decode a random 25% of the pages densely
     k, v = wl.fp8_kv_pair(batch=2, heads=4, tokens=1024, seed=5)
