@@ -214,8 +214,8 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
         # config 2 again with byte-grouped symbols (two exponents per symbol; the flat sign+mantissa field raw)
         set2 = [t for _, t in wl.fp8_weight_set(32, device=dev)]
         n2 = [t.numel() for t in set2]
-        run("c2_fp8_byte_symbols", zc.FMT_FP8_E4M3_BYTES, set2, n2, 262144, 64, policy=zc.POLICY_AUTO, decode_kernel=S64, compress_kernels="k_hist + k_codes + k_encode (sizes) + k_scan + k_encode_bf16<BYTES>")
-        run("c2_fp8_byte_symbols_limit_11", zc.FMT_FP8_E4M3_BYTES, set2, n2, 262144, 64, limit=(11, 11, 0), policy=zc.POLICY_AUTO, decode_kernel=S64, compress_kernels="k_hist + k_codes + k_encode (sizes) + k_scan + k_encode_bf16<BYTES>")
+        run("c2_fp8_byte_symbols", zc.FMT_FP8_E4M3_BYTES, set2, n2, 262144, 64, policy=zc.POLICY_AUTO, decode_kernel=S64, compress_kernels="k_hist_rows8_lanes + k_codes + k_sizes_rows8_counts + k_scan + k_encode_bf16<BYTES>")
+        run("c2_fp8_byte_symbols_limit_11", zc.FMT_FP8_E4M3_BYTES, set2, n2, 262144, 64, limit=(11, 11, 0), policy=zc.POLICY_AUTO, decode_kernel=S64, compress_kernels="k_hist_rows8_lanes + k_codes + k_sizes_rows8_counts + k_scan + k_encode_bf16<BYTES>")
         run("c2_fp8_plain_symbols_auto", zc.FMT_FP8_E4M3, set2, n2, 262144, 64, policy=zc.POLICY_AUTO, decode_kernel="k_decode_fp8", compress_kernels="k_hist_fp8_lanes + k_codes + k_sizes_fp8_counts + k_scan + k_encode_fp8")
         # the generic paths beside their specialised neighbours: a chunk size that is not whole rows of 1 KiB takes the
         # chunks that are not whole rows: the generic encoder, the 64-lane decoder's build for such chunks
@@ -251,10 +251,11 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
     pairs = [wl.bf16_checkpoint_pair(4096 * 16384, device=dev, seed=400 + i) for i in range(16)]
     w0, w1 = [q[0] for q in pairs], [q[1] for q in pairs]
     bf16_c = "k_hist + k_codes + k_encode (sizes) + k_scan + k_encode_bf16"
-    run("c4_bf16_checkpoint_w1", zc.FMT_BF16, w1, [4096 * 16384] * 16, 262144, 64, limit=(16, 16, 0), decode_kernel="k_decode_bf16_s64", compress_kernels=bf16_c)
-    run("c4_bf16_checkpoint_xor_delta", zc.FMT_BF16, w1, [4096 * 16384] * 16, 262144, 64, bases=w0, limit=(16, 16, 0), decode_kernel="k_decode_bf16_s64", compress_kernels=bf16_c)
+    bf16_lanes_c = "k_hist_rows8_lanes + k_codes + k_sizes_rows8_counts + k_scan + k_encode_bf16"       # 256 KiB chunks: sizes from counts per lane
+    run("c4_bf16_checkpoint_w1", zc.FMT_BF16, w1, [4096 * 16384] * 16, 262144, 64, limit=(16, 16, 0), decode_kernel="k_decode_bf16_s64", compress_kernels=bf16_lanes_c)
+    run("c4_bf16_checkpoint_xor_delta", zc.FMT_BF16, w1, [4096 * 16384] * 16, 262144, 64, bases=w0, limit=(16, 16, 0), decode_kernel="k_decode_bf16_s64", compress_kernels=bf16_lanes_c)
     if extras:
-        run("c4_bf16_checkpoint_xor_delta_limit_11", zc.FMT_BF16, w1, [4096 * 16384] * 16, 262144, 64, bases=w0, limit=(11, 11, 0), decode_kernel="k_decode_bf16_s64", compress_kernels=bf16_c)
+        run("c4_bf16_checkpoint_xor_delta_limit_11", zc.FMT_BF16, w1, [4096 * 16384] * 16, 262144, 64, bases=w0, limit=(11, 11, 0), decode_kernel="k_decode_bf16_s64", compress_kernels=bf16_lanes_c)
         run("c4_bf16_checkpoint_xor_delta_64KiB_chunks", zc.FMT_BF16, w1, [4096 * 16384] * 16, 65536, 64, bases=w0, limit=(16, 16, 0), decode_kernel="k_decode_bf16_s64", compress_kernels=bf16_c)
     del pairs, w0, w1
     kv = []
