@@ -24,10 +24,10 @@ namespace zc {
 // The geometry for which the histogram pass also counts exponents per chunk lane, so that the size pass need
 // not read the source again (k_hist_fp8_lanes, k_sizes_fp8_counts)
 bool lane_counts_shape(const Geometry &g) { return g.fmt == ZC_FMT_FP8_E4M3 && g.S == 64 && g.chunk_bytes == kHistBlockBytes; }
-// The same for BF16 and FP8 in byte symbols (k_hist_rows8_lanes, k_sizes_rows8_counts): 64 KiB of counts per chunk
+// The same for BF16, FP8 in byte symbols and FP8 E5M2 (k_hist_rows8_lanes, k_sizes_rows8_counts): 64 KiB of counts per chunk
 bool lane_counts8_shape(const Geometry &g)
 {
-    return (g.fmt == ZC_FMT_BF16 || g.fmt == ZC_FMT_FP8_E4M3_BYTES) && g.S == 64 && g.chunk_bytes == kHistBlockBytes;
+    return (g.fmt == ZC_FMT_BF16 || g.fmt == ZC_FMT_FP8_E4M3_BYTES || g.fmt == ZC_FMT_FP8_E5M2) && g.S == 64 && g.chunk_bytes == kHistBlockBytes;
 }
 
 zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T, Workspace *w)
@@ -160,7 +160,9 @@ zc_status CompressQueue::queue_sizes_and_scan() const
     // whose sizes come from this pass); the list of page-shaped tensors leaves both routes to the page kernels
     // (with the symbols counted per lane, route 2 has its sizes from the counts)
     if (sh.lanes8) LAUNCH_TRY(launch_sizes_rows8_counts(g.fmt, d_descs(), d_list(w.whole_work), n_whole, d_enc(), (const uint32_t *)d_lane_counts(), d_units(), stream));
-    LAUNCH_TRY(launch_sizes(g.fmt, sh.whole_mode, sh.lanes8 ? 0x6 : 0x2, d_descs(), d_list(w.whole_work), n_whole, d_enc(), d_units(), stream));
+    // (E5M2 has no encoder of its own, route 0, and all its whole chunks are sized from the counts)
+    if (!(sh.lanes8 && g.fmt == ZC_FMT_FP8_E5M2))
+        LAUNCH_TRY(launch_sizes(g.fmt, sh.whole_mode, sh.lanes8 ? 0x6 : 0x2, d_descs(), d_list(w.whole_work), n_whole, d_enc(), d_units(), stream));
     LAUNCH_TRY(launch_sizes(g.fmt, 0, 0x6, d_descs(), d_list(w.other_work), n_other, d_enc(), d_units(), stream));
     LAUNCH_TRY(launch_sizes(g.fmt, 0, 0, d_descs(), d_list(w.chunk_work), n_slow, d_enc(), d_units(), stream));
     // the chained kernel has placed and written the tensors of its route (1) itself

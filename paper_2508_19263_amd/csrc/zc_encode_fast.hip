@@ -280,8 +280,8 @@ __global__ __launch_bounds__(256) void k_sizes_fp8_counts(const TensorDev *descs
 
 // ---------------------------------------------------------------------------------------
 // The same two reads instead of three for the formats whose fields are 8-bit symbols, 8 per 16-byte run (BF16;
-// FP8 in byte symbols), with 64 lanes and chunks of kHistBlockBytes: weights, checkpoints and checkpoint deltas
-// (Sec. 3.1, 4.1).  A lane's field has 256 possible symbols, so its counts are 512 bytes per field and lane, 64 KiB
+// FP8 in byte symbols) or 16 (FP8 E5M2), with 64 lanes and chunks of kHistBlockBytes: weights, checkpoints and
+// checkpoint deltas (Sec. 3.1, 3.2, 4.1).  A lane's field has 256 possible symbols, so its counts are 512 bytes per field and lane, 64 KiB
 // per chunk: a quarter of the chunk, written once here and read once by k_sizes_rows8_counts, against a whole
 // second read of the source (and of the base of a delta) by the generic size pass.
 //
@@ -290,12 +290,13 @@ __global__ __launch_bounds__(256) void k_sizes_fp8_counts(const TensorDev *descs
 // k_hist_fp8_lanes (16-bit counters, lanes l and l + 32 in the halves of word [symbol][l % 32]: conflict-free
 // whatever the data; a lane holds 2,048 symbols of a field).  At the end the arrays go to lane_counts as they are
 // (field, symbol, word: 64 KiB at lane_counts + chunk * 16384 words), and their sums over the lanes are added to the
-// tensor's two histograms, where k_hist adds its own.
+// tensor's histograms, beside what k_hist counts.
 template <int FMT>
 __global__ __launch_bounds__(512) void k_hist_rows8_lanes(const TensorDev *descs, const WorkItem *work, uint64_t *hist, uint32_t *lane_counts)
 {
-    static_assert(Fmt<FMT>::G == 8 && Fmt<FMT>::SB == 8 && Fmt<FMT>::NF == 2, "two fields of eight 8-bit symbols per run");
-    static_assert(kHistBlockBytes / 16 / 64 * 8 < 65536, "a lane's count of one symbol fits 16 bits");
+    static_assert((Fmt<FMT>::G == 8 || Fmt<FMT>::G == 16) && Fmt<FMT>::SB == 8 && Fmt<FMT>::NF == 2, "two fields of 8 or 16 symbols of 8 bits per run");
+    static_assert(kHistBlockBytes / 16 / 64 * Fmt<FMT>::G < 65536, "a lane's count of one symbol fits 16 bits");
+    constexpr int kWords = Fmt<FMT>::G / 4;                      // words of four symbols per run and field
     __shared__ __attribute__((aligned(16))) uint32_t cnt[2 * 256 * 32];      // 64 KiB
     const WorkItem it = work[blockIdx.x];
     const TensorDev &d = descs[it.tensor];
@@ -310,11 +311,12 @@ __global__ __launch_bounds__(512) void k_hist_rows8_lanes(const TensorDev *descs
     const uint32_t l4 = (lane & 31) * 4, inc = lane < 32 ? 1u : 0x10000u;
     char *const lds0 = reinterpret_cast<char *>(cnt), *const lds1 = lds0 + 256 * 32 * 4;
     auto count = [&](const uint4 &v) {
-        uint64_t P0, P1;
-        split_run<FMT>(v, P0, P1);
-        const uint32_t w0[2] = {(uint32_t)P0, (uint32_t)(P0 >> 32)}, w1[2] = {(uint32_t)P1, (uint32_t)(P1 >> 32)};
+        uint64_t P0, Q0, P1, Q1;
+        split_run4<FMT>(v, P0, Q0, P1, Q1);
+        const uint32_t w0[4] = {(uint32_t)P0, (uint32_t)(P0 >> 32), (uint32_t)Q0, (uint32_t)(Q0 >> 32)};
+        const uint32_t w1[4] = {(uint32_t)P1, (uint32_t)(P1 >> 32), (uint32_t)Q1, (uint32_t)(Q1 >> 32)};
 #pragma unroll
-        for (int i = 0; i < 2; i++) {
+        for (int i = 0; i < kWords; i++) {
             atomicAdd(reinterpret_cast<uint32_t *>(lds0 + (((w0[i] << 7) & 0x7F80u) | l4)), inc);
             atomicAdd(reinterpret_cast<uint32_t *>(lds0 + (((w0[i] >> 1) & 0x7F80u) | l4)), inc);
             atomicAdd(reinterpret_cast<uint32_t *>(lds0 + (((w0[i] >> 9) & 0x7F80u) | l4)), inc);
@@ -352,11 +354,17 @@ __global__ __launch_bounds__(512) void k_hist_rows8_lanes(const TensorDev *descs
         const uint32_t c = cnt[(f * 256 + bin) * 32 + ((r + bin) & 31)];
         sum += (c & 0xFFFFu) + (c >> 16);
     }
-    if (sum) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + f) * 256 + bin]), (unsigned long long)sum);
+    // BF16 and byte symbols: field f's histogram is the tensor's slot f.  E5M2: slot 0 is the histogram of the bytes that
+    // k_hist counts, and the field histograms of what this kernel counts go to slot 1, exponents at 0..31 and sign+mantissa
+    // symbols at 32..39 (k_codes adds them up)
+    const uint64_t at = FMT == ZC_FMT_FP8_E5M2 ? 256 + (f ? 32 : 0) + bin : f * 256 + bin;
+    if (sum && (FMT != ZC_FMT_FP8_E5M2 || bin < (f ? 8u : 32u)))
+        atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(uint64_t)it.tensor * 768 + at]), (unsigned long long)sum);
 }
 
 // Stream sizes of whole chunks from those counts, for the tensors the 64-lane encoder of these formats takes (route 2:
-// exponent field table coded, sign+mantissa field flat, raw or table coded).  A table-coded field: as in
+// exponent field table coded, sign+mantissa field flat, raw or table coded) and for every E5M2 tensor (the generic
+// encoder writes those).  A table-coded field: as in
 // k_sizes_fp8_counts, with R symbols per refill step (R codes are at most 32 bits, which is all the argument there
 // needs): a lane's words are min(steps, floor((bits - bits of its last R codes) / 32) + 2), its bits the counts times
 // the code lengths.  A flat or raw field takes its plain size.  One wavefront per chunk, work items as for the
@@ -370,7 +378,8 @@ __global__ __launch_bounds__(256) void k_sizes_rows8_counts(const TensorDev *des
     __shared__ uint32_t total[kWavesPerGroup][2][64];
     const WorkItem it = work[blockIdx.x];
     const TensorDev *dp = descs + it.tensor;
-    if (dp->route != 2) return;                                  // whole workgroup: the generic size pass takes this tensor
+    if (dp->route != (FMT == ZC_FMT_FP8_E5M2 ? 0 : 2)) return;   // whole workgroup: the generic size pass takes this tensor
+    constexpr uint32_t G = Fmt<FMT>::G;                           // symbols per run and field
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     lens[0][tid] = enc_tables[(uint64_t)it.tensor * 768 + tid] >> 16;
     lens[1][tid] = enc_tables[(uint64_t)it.tensor * 768 + 256 + tid] >> 16;
@@ -411,19 +420,19 @@ __global__ __launch_bounds__(256) void k_sizes_rows8_counts(const TensorDev *des
     const uint64_t at = (uint64_t)chunk * cb + (cb - 1024) + lane * 16;
     uint4 v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)) + at);
     if (uni64((uint64_t)dp->base) != 0) v = xor4(v, *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) + at));
-    uint64_t P[2];
-    split_run<FMT>(v, P[0], P[1]);
+    uint64_t P[2], Q[2];
+    split_run4<FMT>(v, P[0], Q[0], P[1], Q[1]);
     uint32_t u[2];
 #pragma unroll
     for (int f = 0; f < 2; f++) {
         if (!coded[f]) {
-            u[f] = kind[f] == 3 ? 0u : cb / 32;                   // 8 bits per symbol, half the chunk's bytes; a constant field: nothing
+            u[f] = kind[f] == 3 ? 0u : cb / 256 * G;              // 8 bits per symbol, G symbols per 16 bytes of the chunk; a constant field: nothing
             continue;
         }
-        const uint32_t R = uni32(dp->period[f]);                 // 2, 4 or 8
+        const uint32_t R = uni32(dp->period[f]);                 // 2, 4, 8 or, with runs of 16 symbols, 16
         uint32_t last = 0;
-        for (uint32_t j = 8 - R; j < 8; j++) last += lens[f][(uint32_t)(P[f] >> (8 * j)) & 0xFFu];
-        const uint32_t steps = cb / 1024 * 8 / R;
+        for (uint32_t j = G - R; j < G; j++) last += lens[f][(uint32_t)((G == 16 && j >= 8 ? Q[f] : P[f]) >> (8 * (j & 7))) & 0xFFu];
+        const uint32_t steps = cb / 1024 * G / R;
         uint32_t q = ((total[wave][f][lane] - last) >> 5) + 2;
         q = q < steps ? q : steps;
 #pragma unroll
@@ -1461,13 +1470,15 @@ int launch_sizes_fp8_counts(const TensorDev *d_descs, const WorkItem *d_work, ui
     return (int)hipGetLastError();
 }
 
-// fmt: ZC_FMT_BF16 or ZC_FMT_FP8_E4M3_BYTES.  One work item per whole chunk of kHistBlockBytes.
+// fmt: ZC_FMT_BF16, ZC_FMT_FP8_E4M3_BYTES or ZC_FMT_FP8_E5M2.  One work item per whole chunk of kHistBlockBytes.
 int launch_hist_rows8_lanes(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint32_t *d_lane_counts, void *stream)
 {
     if (n_work == 0) return 0;
     if (fmt == ZC_FMT_BF16) hipLaunchKernelGGL(k_hist_rows8_lanes<ZC_FMT_BF16>, dim3(n_work), dim3(512), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
     else if (fmt == ZC_FMT_FP8_E4M3_BYTES)
         hipLaunchKernelGGL(k_hist_rows8_lanes<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(512), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
+    else if (fmt == ZC_FMT_FP8_E5M2)
+        hipLaunchKernelGGL(k_hist_rows8_lanes<ZC_FMT_FP8_E5M2>, dim3(n_work), dim3(512), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
     else return 1;
     return (int)hipGetLastError();
 }
@@ -1481,6 +1492,8 @@ int launch_sizes_rows8_counts(uint32_t fmt, const TensorDev *d_descs, const Work
         hipLaunchKernelGGL(k_sizes_rows8_counts<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
     else if (fmt == ZC_FMT_FP8_E4M3_BYTES)
         hipLaunchKernelGGL(k_sizes_rows8_counts<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
+    else if (fmt == ZC_FMT_FP8_E5M2)
+        hipLaunchKernelGGL(k_sizes_rows8_counts<ZC_FMT_FP8_E5M2>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
     else return 1;
     return (int)hipGetLastError();
 }

@@ -182,6 +182,22 @@ def test_stream_sizes_from_lane_counts_of_8_bit_symbols():
             check_case(zc.FMT_FP8_E4M3_BYTES, a.numel(), cb, 64, policy, L=L, data=(a, None), tag="fp8-bytes-lane-counts")
     b = wl.fp8_weight(4 * cb + 777, seed=43)
     check_case(zc.FMT_FP8_E4M3_BYTES, a.numel(), cb, 64, data=(a, None), base=b, tag="fp8-bytes-lane-counts-delta")
+    # FP8 E5M2: 16 symbols per run and field; exponent codes of every refill period (2, 4, 8 and, with four exponent values,
+    # 16), a delta, a constant sign+mantissa field, a uniform tensor (every code 8 bits long)
+    def e5m2_of(n, n_exp, geometric, n_sm=8):
+        sm = rng.integers(0, n_sm, n).astype(np.uint8)
+        ex = (np.minimum(rng.geometric(geometric, n) - 1, n_exp - 1) if geometric else rng.integers(0, n_exp, n)).astype(np.uint8)
+        return torch.from_numpy(((sm >> 2) << 7 | (ex << 2) | (sm & 3)).astype(np.uint8))
+
+    n5 = 4 * cb + 4321
+    for x, L in ((e5m2_of(n5, 32, 0.45), (16, 0, 0)), (e5m2_of(n5, 32, 0.45), (11, 0, 0)), (e5m2_of(n5, 32, 0.45), (8, 8, 0)), (e5m2_of(n5, 6, 0), (0, 0, 0)),
+                 (e5m2_of(n5, 4, 0), (0, 0, 0)), (e5m2_of(n5, 20, 0.3, n_sm=1), (0, 0, 0)), (wl.fp8_e5m2_weight(n5, seed=44), (0, 0, 0))):
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            check_case(zc.FMT_FP8_E5M2, n5, cb, 64, policy, L=L, data=(x, None), tag="e5m2-lane-counts")
+    check_case(zc.FMT_FP8_E5M2, n5, cb, 64, data=(e5m2_of(n5, 32, 0.45), None), base=e5m2_of(n5, 32, 0.3), tag="e5m2-lane-counts-delta")
+    u8 = torch.from_numpy(rng.integers(0, 256, 3 * cb, dtype=np.uint8))
+    check_case(zc.FMT_FP8_E5M2, u8.numel(), cb, 64, zc.POLICY_AUTO, data=(u8, None), tag="e5m2-lane-counts-uniform")
+    check_case(zc.FMT_FP8_E5M2, 3 * cb, cb, 64, data=(torch.full((3 * cb,), 0x3C, dtype=torch.uint8), None), tag="e5m2-lane-counts-constant")
     # a batch: tensors with a table-coded, a raw and a constant second field, whole and ragged, queued without a wait too
     srcs = [bf16_of(2 * (cb // 2), 40, 8), w1, bf16_of(cb // 2 + 8, 1, 3), bf16_of(7 * (cb // 2), 9, 8)]
     bases = [torch.zeros_like(srcs[0]), w0, torch.zeros_like(srcs[2]), torch.zeros_like(srcs[3])]      # a batch has bases for all or none
