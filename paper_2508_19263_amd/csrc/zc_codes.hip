@@ -294,9 +294,11 @@ __global__ __launch_bounds__(256) void k_codes_finish(TensorDev *descs, CodePara
     if (my_len) atomicMin(&lmin_s, my_len);
     __syncthreads();
     const bool plain_sm = d.kind[1] == 1 || d.kind[1] == 2;
+    // (FP8 E5M2, 16 symbols per run: both fields table coded, refill periods of at most 8)
+    const bool e5m2 = cp.fmt == ZC_FMT_FP8_E5M2 && d.streams == 64 && d.kind[1] == 0 && d.period[0] <= 8 && d.period[1] >= 2 && d.period[1] <= 8;
     const bool bf16 = d.fast_shape && d.kind[0] == 0 &&
-                      (d.streams == 64 ? ((cp.fmt == ZC_FMT_BF16 || cp.fmt == ZC_FMT_FP8_E4M3_BYTES) &&
-                                          (plain_sm || (d.kind[1] == 0 && (d.period[1] == 2 || d.period[1] == 4))))
+                      (d.streams == 64 ? (e5m2 || ((cp.fmt == ZC_FMT_BF16 || cp.fmt == ZC_FMT_FP8_E4M3_BYTES) &&
+                                                   (plain_sm || (d.kind[1] == 0 && (d.period[1] == 2 || d.period[1] == 4)))))
                                        : (cp.fmt == ZC_FMT_BF16 && plain_sm && (d.period[0] != 2 || lmin_s >= 2)));
     if (threadIdx.x == 0) d.route = fast ? 1 : bf16 ? 2 : 0;
 }

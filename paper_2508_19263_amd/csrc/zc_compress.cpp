@@ -105,7 +105,7 @@ CompressShape compress_shape(const Geometry &g, bool device_codes, uint64_t all_
     sh.lanes8 = device_codes && lane_counts8_shape(g);
     sh.bf16 = g.fmt == ZC_FMT_BF16;
     sh.whole_shape = g.S == 64 && g.chunk_bytes % 1024 == 0;
-    sh.rows8 = sh.whole_shape && (g.fmt == ZC_FMT_BF16 || g.fmt == ZC_FMT_FP8_E4M3_BYTES);
+    sh.rows8 = sh.whole_shape && (g.fmt == ZC_FMT_BF16 || g.fmt == ZC_FMT_FP8_E4M3_BYTES || g.fmt == ZC_FMT_FP8_E5M2);
     // FP4 elements rarely compress, so their fields are stored plainly and a chunk's rows can be shared by the four
     // wavefronts of a workgroup: one chunk per work item there
     sh.whole_mode = is_fp4(g.fmt) ? 2 : 1;
@@ -740,8 +740,10 @@ private:
         // exponents per refill step, no 1-bit code (the bound on their staging ring needs 4 bits per step)
         uint32_t lmin = 16;
         for (int v = 0; v < 256; v++) if (fc[0].len[v] && fc[0].len[v] < lmin) lmin = fc[0].len[v];
+        // (FP8 E5M2, 16 symbols per run: both fields table coded, refill periods of at most 8)
+        const bool e5m2_ok = g.fmt == ZC_FMT_FP8_E5M2 && d.kind[1] == 0 && d.period[0] <= 8 && d.period[1] >= 2 && d.period[1] <= 8;
         const bool bf16_ok = d.kind[0] == 0 &&
-                             (sh.whole_shape ? (sh.rows8 && (plain_sm || (d.kind[1] == 0 && (d.period[1] == 2 || d.period[1] == 4))))
+                             (sh.whole_shape ? (sh.rows8 && (g.fmt == ZC_FMT_FP8_E5M2 ? e5m2_ok : (plain_sm || (d.kind[1] == 0 && (d.period[1] == 2 || d.period[1] == 4)))))
                                           : (sh.bf16 && fast_shape(t) && plain_sm && (d.period[0] != 2 || lmin >= 2)));
         d.route = fast_ok ? 1 : bf16_ok ? 2 : 0;
         return ZC_OK;

@@ -363,8 +363,8 @@ __global__ __launch_bounds__(512) void k_hist_rows8_lanes(const TensorDev *descs
 }
 
 // Stream sizes of whole chunks from those counts, for the tensors the 64-lane encoder of these formats takes (route 2:
-// exponent field table coded, sign+mantissa field flat, raw or table coded) and for every E5M2 tensor (the generic
-// encoder writes those).  A table-coded field: as in
+// exponent field table coded, sign+mantissa field flat, raw or table coded) and for every E5M2 tensor (whichever
+// encoder writes it).  A table-coded field: as in
 // k_sizes_fp8_counts, with R symbols per refill step (R codes are at most 32 bits, which is all the argument there
 // needs): a lane's words are min(steps, floor((bits - bits of its last R codes) / 32) + 2), its bits the counts times
 // the code lengths.  A flat or raw field takes its plain size.  One wavefront per chunk, work items as for the
@@ -378,7 +378,7 @@ __global__ __launch_bounds__(256) void k_sizes_rows8_counts(const TensorDev *des
     __shared__ uint32_t total[kWavesPerGroup][2][64];
     const WorkItem it = work[blockIdx.x];
     const TensorDev *dp = descs + it.tensor;
-    if (dp->route != (FMT == ZC_FMT_FP8_E5M2 ? 0 : 2)) return;   // whole workgroup: the generic size pass takes this tensor
+    if (dp->route != 2 && (FMT != ZC_FMT_FP8_E5M2 || dp->route != 0)) return;      // whole workgroup: the generic size pass takes this tensor
     constexpr uint32_t G = Fmt<FMT>::G;                           // symbols per run and field
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     lens[0][tid] = enc_tables[(uint64_t)it.tensor * 768 + tid] >> 16;
@@ -666,17 +666,23 @@ __device__ __forceinline__ void close_stream(LaneStream &L, __amdgpu_buffer_rsrc
 }
 
 // R0: refill period of the exponent field; R1: of the sign+mantissa field when it is table coded, 0 when it is flat or raw.
-// BYTES: the source is FP8 coded in byte symbols (Sec. 3.2, Fig. 7: the exponents of two consecutive values in one byte,
-// their sign+mantissa values in another), 16 values per run; otherwise BF16, 8 values per run.  Either way a run is 8
-// symbols of 8 bits in each field, which is all the rest of the kernel knows.
-template <int R0, int R1, bool BYTES>
+// KIND: what the source is.  kSrcBf16: BF16, 8 values per run.  kSrcFp8Pairs: FP8 coded in byte symbols (Sec. 3.2, Fig. 7:
+// the exponents of two consecutive values in one byte, their sign+mantissa values in another), 16 values per run.  Either
+// way a run is 8 symbols of 8 bits in each field, which is all the rest of the kernel knows.  kSrcE5m2: FP8 E5M2, whose
+// 5-bit exponents and 3-bit sign+mantissa values are symbols of 8 bits each: 16 symbols per run and field, coded as two
+// halves of 8 one after the other (both fields table coded; a refill period is at most 8 symbols here).
+constexpr int kSrcBf16 = 0, kSrcFp8Pairs = 1, kSrcE5m2 = 2;
+template <int R0, int R1, int KIND>
 __device__ __forceinline__ void encode_bf16_chunk(const TensorDev *dp, const WorkItem &it, const uint32_t *enc)
 {
+    static_assert(KIND != kSrcE5m2 || R1 != 0, "E5M2: both fields table coded");
+    constexpr bool BYTES = KIND == kSrcFp8Pairs;
+    constexpr int kHalves = KIND == kSrcE5m2 ? 2 : 1;           // groups of 8 symbols per field in a 16-byte run
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t chunk = uni32(it.first + (threadIdx.x >> 6));
     const uint32_t cb = uni32(dp->chunk_bytes);
     const uint64_t n_elems = uni64(dp->n_elems);
-    if (chunk >= (uint32_t)(n_elems / (BYTES ? cb : cb / 2))) return;
+    if (chunk >= (uint32_t)(n_elems / (KIND == kSrcBf16 ? cb / 2 : cb))) return;
     const bool has_base = uni64((uint64_t)dp->base) != 0;
     const bool sm_raw = uni32(dp->kind[1]) == 2;
     uint8_t *comp = reinterpret_cast<uint8_t *>(uni64((uint64_t)dp->comp));
@@ -701,6 +707,19 @@ __device__ __forceinline__ void encode_bf16_chunk(const TensorDev *dp, const Wor
         if (has_base) y = __builtin_amdgcn_raw_buffer_load_b128(bas, (int)(lane * 16), (int)(row * 1024), 0);
     };
     auto encode_row = [&](const u32x4 &v, uint32_t row) {
+        if (KIND == kSrcE5m2) {
+            // a value is s eeeee mm, four per word: words 2b, 2b + 1 hold the symbols 8b .. 8b + 7 of either field
+#pragma unroll
+            for (int b = 0; b < kHalves; b++) {
+                const uint32_t ex[2] = {(v[2 * b] >> 2) & 0x1F1F1F1Fu, (v[2 * b + 1] >> 2) & 0x1F1F1F1Fu};
+                const uint32_t sm[2] = {((v[2 * b] >> 5) & 0x04040404u) | (v[2 * b] & 0x03030303u), ((v[2 * b + 1] >> 5) & 0x04040404u) | (v[2 * b + 1] & 0x03030303u)};
+#pragma unroll
+                for (int g = 0; g < 8 / R0; g++) code_period<R0>(E, ex, g * R0, lut0, es);
+#pragma unroll
+                for (int g = 0; g < 8 / (R1 ? R1 : 8); g++) code_period<(R1 ? R1 : 8)>(M, sm, g * R1, lut1, ms);
+            }
+            return;
+        }
         // ---- the eight exponents (bits 14..7 of a value) and sign+mantissa bytes (bit 15, bits 6..0), four per word
         uint32_t ex[2], sm[2];
 #pragma unroll
@@ -753,7 +772,7 @@ __device__ __forceinline__ void encode_bf16_chunk(const TensorDev *dp, const Wor
     if (R1 != 0) close_stream(M, ms, lane);
 }
 
-template <bool BYTES>
+template <int KIND>
 __global__ __launch_bounds__(256) void k_encode_bf16(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables)
 {
     __shared__ uint32_t enc[512];
@@ -764,26 +783,43 @@ __global__ __launch_bounds__(256) void k_encode_bf16(const TensorDev *descs, con
     enc[256 + threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + 256 + threadIdx.x];
     __syncthreads();
     const uint32_t r0 = uni32(dp->period[0]), r1 = uni32(dp->kind[1]) == 0 ? uni32(dp->period[1]) : 0u;
+    if (KIND == kSrcE5m2) {
+        switch (r0 * 16 + r1) {
+        case 0x22: encode_bf16_chunk<2, 2, KIND>(dp, it, enc); break;
+        case 0x42: encode_bf16_chunk<4, 2, KIND>(dp, it, enc); break;
+        case 0x82: encode_bf16_chunk<8, 2, KIND>(dp, it, enc); break;
+        case 0x24: encode_bf16_chunk<2, 4, KIND>(dp, it, enc); break;
+        case 0x44: encode_bf16_chunk<4, 4, KIND>(dp, it, enc); break;
+        case 0x84: encode_bf16_chunk<8, 4, KIND>(dp, it, enc); break;
+        case 0x28: encode_bf16_chunk<2, 8, KIND>(dp, it, enc); break;
+        case 0x48: encode_bf16_chunk<4, 8, KIND>(dp, it, enc); break;
+        case 0x88: encode_bf16_chunk<8, 8, KIND>(dp, it, enc); break;
+        default: break;                                          // the route is only given for these combinations
+        }
+        return;
+    }
+    constexpr int K = KIND == kSrcE5m2 ? kSrcBf16 : KIND;         // (the combinations below do not exist for E5M2)
     switch (r0 * 16 + r1) {
-    case 0x20: encode_bf16_chunk<2, 0, BYTES>(dp, it, enc); break;
-    case 0x40: encode_bf16_chunk<4, 0, BYTES>(dp, it, enc); break;
-    case 0x80: encode_bf16_chunk<8, 0, BYTES>(dp, it, enc); break;
-    case 0x22: encode_bf16_chunk<2, 2, BYTES>(dp, it, enc); break;
-    case 0x42: encode_bf16_chunk<4, 2, BYTES>(dp, it, enc); break;
-    case 0x82: encode_bf16_chunk<8, 2, BYTES>(dp, it, enc); break;
-    case 0x24: encode_bf16_chunk<2, 4, BYTES>(dp, it, enc); break;
-    case 0x44: encode_bf16_chunk<4, 4, BYTES>(dp, it, enc); break;
-    case 0x84: encode_bf16_chunk<8, 4, BYTES>(dp, it, enc); break;
+    case 0x20: encode_bf16_chunk<2, 0, K>(dp, it, enc); break;
+    case 0x40: encode_bf16_chunk<4, 0, K>(dp, it, enc); break;
+    case 0x80: encode_bf16_chunk<8, 0, K>(dp, it, enc); break;
+    case 0x22: encode_bf16_chunk<2, 2, K>(dp, it, enc); break;
+    case 0x42: encode_bf16_chunk<4, 2, K>(dp, it, enc); break;
+    case 0x82: encode_bf16_chunk<8, 2, K>(dp, it, enc); break;
+    case 0x24: encode_bf16_chunk<2, 4, K>(dp, it, enc); break;
+    case 0x44: encode_bf16_chunk<4, 4, K>(dp, it, enc); break;
+    case 0x84: encode_bf16_chunk<8, 4, K>(dp, it, enc); break;
     default: break;                                              // the route is only given for these combinations
     }
 }
 
-// fmt: ZC_FMT_BF16, or ZC_FMT_FP8_E4M3_BYTES (the same encoder over FP8 values split into byte symbols)
+// fmt: ZC_FMT_BF16, ZC_FMT_FP8_E4M3_BYTES (the same encoder over FP8 values split into byte symbols) or ZC_FMT_FP8_E5M2
 int launch_encode_bf16(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream)
 {
     if (n_work == 0) return 0;
-    if (fmt == ZC_FMT_FP8_E4M3_BYTES) hipLaunchKernelGGL(k_encode_bf16<true>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc);
-    else hipLaunchKernelGGL(k_encode_bf16<false>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc);
+    if (fmt == ZC_FMT_FP8_E4M3_BYTES) hipLaunchKernelGGL(k_encode_bf16<kSrcFp8Pairs>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc);
+    else if (fmt == ZC_FMT_FP8_E5M2) hipLaunchKernelGGL(k_encode_bf16<kSrcE5m2>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc);
+    else hipLaunchKernelGGL(k_encode_bf16<kSrcBf16>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc);
     return (int)hipGetLastError();
 }
 

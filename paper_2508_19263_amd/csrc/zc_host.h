@@ -96,7 +96,7 @@ struct CompressShape {
     bool lanes;                 // the code is built on the device and the histogram pass also counts exponents per chunk lane
     bool lanes8;                // the same for the formats of 8-bit symbols (BF16, FP8 in byte symbols): both fields' symbols per chunk lane
     bool bf16;
-    bool rows8;                 // 64 lanes, whole rows, 8 symbols of 8 bits per run and field (BF16, FP8 in byte symbols): the 64-lane encoder written for BF16
+    bool rows8;                 // 64 lanes, whole rows, 8 or 16 symbols of 8 bits per run and field (BF16, FP8 in byte symbols, FP8 E5M2): the 64-lane encoder written for BF16
     bool whole_shape;           // 64 lanes, chunks of whole 1 KiB rows: the generic encoder's whole-chunk build
     int whole_mode;             // 2: one whole chunk per work item, shared by its four wavefronts
     uint32_t whole_step, fast_step, cpi;    // chunks per work item of the whole-chunk list, the fast list, the generic kernels
