@@ -262,7 +262,7 @@ enum FieldKind : uint32_t { KIND_HUFF = 0, KIND_FLAT = 1, KIND_RAW = 2, KIND_CON
 // called: words [wbase, wbase + RW) are in the ring except the newest SEG, which may still be in flight or in
 // registers; wpos - wbase < 2 * SEG, and at most SEG words are handed out before the next call, so every word asked
 // for lies below wbase + 3 * SEG: present.
-constexpr uint32_t kRing2Words = 512, kRing2Segment = 128;
+constexpr uint32_t kRing2Words = 512;
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 struct HuffStream {

@@ -1,0 +1,381 @@
+// Histogram passes that also count symbols per chunk lane, and the size passes that work from those counts instead
+// of reading the source a second time (a3 and a5 for 64 lanes and chunks of one histogram block).
+#include <hip/hip_runtime.h>
+
+#include "zc_internal.h"
+#include "zc_device.h"
+#include "zc_encode_device.h"
+
+namespace zc {
+
+// ---------------------------------------------------------------------------------------
+// Histogram and stream sizes of FP8 chunks in two reads of the source instead of three.  With 64 lanes per chunk
+// a lane owns every 64th 16-byte run, and the number of words its stream takes follows from its bit total alone
+// (shown at k_sizes_fp8_counts).  So the histogram pass, which reads the chunk anyway, also counts the exponents
+// per lane (16 counts of 16 bits per lane, 2 KiB per chunk of 256 KiB), and once the code is known the size pass
+// reads those counts instead of the source.
+//
+// k_hist_fp8_lanes: one workgroup per whole chunk of kHistBlockBytes (= the chunk size; the host uses this kernel
+// for no other).  Thread t takes the runs t, t+256, ...: all of chunk lane t % 64, which it shares with three
+// threads of the other wavefronts.  Every chunk lane has a histogram of all 256 byte values in LDS (16-bit
+// counters, lanes l and l + 32 in the two halves of word [value][l % 32]: one atomic addition of a constant per
+// byte; each half of a wavefront falls into 32 different banks, so nothing collides, whatever the data; a lane
+// holds 4096 bytes, so nothing overflows).  At the end the lanes' histograms are folded into exponent counts
+// per lane, which go to lane_counts, and into the chunk's two field histograms, which are added to the tensor's
+// second histogram slot (exponents at 0..15, sign+mantissa at 16..31; the first slot keeps the byte histogram
+// of what k_hist counts, a short last chunk).
+__global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, const WorkItem *work, uint64_t *hist, uint16_t *lane_counts)
+{
+    static_assert(kHistBlockBytes / 64 < 65536, "a lane's count of one byte value fits 16 bits");
+    __shared__ uint32_t cnt[256 * 32];                            // 32 KiB
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev &d = descs[it.tensor];
+    const uint32_t tid = threadIdx.x, lane = tid & 63, quarter = tid >> 6;
+    const uint64_t start = (uint64_t)it.first * kHistBlockBytes;
+    if (d.chunk_bytes != kHistBlockBytes || start + kHistBlockBytes > d.n_elems) return;      // whole workgroup; the host never asks for this
+    for (uint32_t i = tid; i < 256 * 32; i += 256) cnt[i] = 0;
+    __syncthreads();
+    const uint8_t *p = d.src + start;
+    const uint8_t *base = d.base ? d.base + start : nullptr;
+    // byte value b of lane l: word b * 32 + l % 32, half l / 32 (the same for everything a thread counts)
+    const uint32_t l4 = (lane & 31) * 4, inc = lane < 32 ? 1u : 0x10000u;
+    char *const lds = reinterpret_cast<char *>(cnt);
+    auto count = [&](const uint4 &v) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            atomicAdd(reinterpret_cast<uint32_t *>(lds + (((w[i] << 7) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds + (((w[i] >> 1) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds + (((w[i] >> 9) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds + (((w[i] >> 17) & 0x7F80u) | l4)), inc);
+        }
+    };
+    // eight 16-byte loads per thread in flight at a time
+    constexpr uint32_t kStep = 256 * 16, kDepth = 8;
+    static_assert(kHistBlockBytes % (kStep * kDepth) == 0, "whole rounds");
+    for (uint32_t off = tid * 16; off < kHistBlockBytes; off += kDepth * kStep) {
+        uint4 v[kDepth];
+#pragma unroll
+        for (uint32_t k = 0; k < kDepth; k++) v[k] = *reinterpret_cast<const uint4 *>(p + off + k * kStep);
+        if (base) {
+#pragma unroll
+            for (uint32_t k = 0; k < kDepth; k++) v[k] = xor4(v[k], *reinterpret_cast<const uint4 *>(base + off + k * kStep));
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < kDepth; k++) count(v[k]);
+    }
+    __syncthreads();
+    // Thread (lane, quarter) folds the byte values 64*quarter .. +63 of its lane: value = s eeee mmm, so a quarter
+    // is one sign, eight exponents and all eight mantissas.
+    uint32_t ce[8], cm[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) { ce[i] = 0; cm[i] = 0; }
+    const uint32_t half_shift = lane < 32 ? 0u : 16u;
+#pragma unroll
+    for (int v = 0; v < 64; v++) {
+        const uint32_t c = (cnt[(quarter * 64 + v) * 32 + (lane & 31)] >> half_shift) & 0xFFFFu;
+        ce[v >> 3] += c;
+        cm[v & 7] += c;
+    }
+    const uint32_t e0 = (quarter & 1) * 8, s = quarter >> 1;      // the quarter's first exponent and its sign
+    __syncthreads();                                             // every thread has read its part of cnt: the array is free
+    // the exponent counts of (lane, quarter), in rows of 9 words against bank conflicts
+    uint32_t *const part = cnt;
+#pragma unroll
+    for (int i = 0; i < 8; i++) part[(quarter * 64 + lane) * 9 + i] = ce[i];
+    // the chunk's field histograms: every lane of this wavefront holds partial counts of the same 16 symbols.  They are
+    // summed over the lanes in a butterfly that halves what a lane carries at every step (8, 4, 2 and 1 exchanges, then
+    // two more of the one value left), so that lane j < 16 ends with the total of symbol j.
+    {
+        uint32_t c[16];
+#pragma unroll
+        for (int i = 0; i < 8; i++) { c[i] = ce[i]; c[8 + i] = cm[i]; }
+#pragma unroll
+        for (int step = 0; step < 4; step++) {
+            const int n = 8 >> step;                             // values kept per lane after this step
+            const bool upper = (lane >> step) & 1;
+#pragma unroll
+            for (int i = 0; i < n; i++) {
+                const uint32_t give = upper ? c[i] : c[n + i], keep = upper ? c[n + i] : c[i];
+                c[i] = keep + (uint32_t)__shfl_xor((int)give, 1 << step, 64);
+            }
+        }
+        c[0] += (uint32_t)__shfl_xor((int)c[0], 16, 64);
+        c[0] += (uint32_t)__shfl_xor((int)c[0], 32, 64);
+        // bit `step` of the lane chose the half it kept at that step, i.e. bit 3 - step of the symbol
+        const uint32_t sym = ((lane & 1) << 3) | ((lane & 2) << 1) | ((lane & 4) >> 1) | ((lane & 8) >> 3);
+        if (lane < 16 && c[0]) {
+            unsigned long long *slot = reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + 1) * 256]);
+            atomicAdd(slot + (sym < 8 ? e0 + sym : 16 + s * 8 + (sym - 8)), (unsigned long long)c[0]);
+        }
+    }
+    __syncthreads();
+    // thread t writes the counts of exponents 4*(t/64) .. +3 of lane t%64: those came from the quarters with the
+    // same exponent half (quarter & 1 == t/128), one per sign
+    {
+        const uint32_t s0 = quarter * 4, half = quarter >> 1, i0 = s0 & 7;
+        const uint32_t *pa = part + ((half + 0) * 64 + lane) * 9 + i0, *pb = part + ((half + 2) * 64 + lane) * 9 + i0;
+        const uint32_t c0 = pa[0] + pb[0], c1 = pa[1] + pb[1], c2 = pa[2] + pb[2], c3 = pa[3] + pb[3];
+        const uint64_t chunk_global = (uint64_t)(d.units_off / 2) + it.first;      // two fields: units_off counts two entries per chunk
+        const uint2 packed = make_uint2(c0 | (c1 << 16), c2 | (c3 << 16));
+        *reinterpret_cast<uint2 *>(lane_counts + (chunk_global * 64 + lane) * 16 + s0) = packed;
+    }
+}
+
+// Stream sizes of full chunks from the per-lane exponent counts.  The decoder of a lane asks for a word at a
+// refill step (every 4 symbols) when it holds k <= 32 unread bits, one word per step at most.  With B(g) the bits
+// of the lane's symbols before step g, the words asked for up to and including step g are min(g + 1,
+// floor(B(g) / 32) + 2): by induction, since B grows by at most 32 per step (four codes of at most 8 bits).  The
+// lane's total is that expression at its last step, where B is its bit total minus its last four codes.
+__global__ __launch_bounds__(256) void k_sizes_fp8_counts(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables,
+                                                          const uint16_t *lane_counts, uint32_t *units)
+{
+    __shared__ uint32_t len16[16];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev *dp = descs + it.tensor;
+    if (!dp->route) return;                                      // whole workgroup: the code does not suit this kernel
+    if (threadIdx.x < 16) len16[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + threadIdx.x] >> 16;
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t chunk = uni32(it.first + (threadIdx.x >> 6));
+    const uint32_t E = uni32(dp->chunk_bytes);
+    const uint64_t n_elems = uni64(dp->n_elems);
+    if (E != kHistBlockBytes || chunk >= (uint32_t)(n_elems / E)) return;
+    const uint64_t chunk_global = (uint64_t)(uni32(dp->units_off) / 2) + chunk;
+    const uint4 *mine = reinterpret_cast<const uint4 *>(lane_counts + (chunk_global * 64 + lane) * 16);
+    const uint4 c0 = mine[0], c1 = mine[1];
+    const uint32_t c[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+    uint32_t bits = 0;
+#pragma unroll
+    for (int j = 0; j < 8; j++) bits += (c[j] & 0xFFFFu) * len16[2 * j] + (c[j] >> 16) * len16[2 * j + 1];
+    // the lane's last four symbols: the last word of its run in the chunk's last row
+    const uint64_t at = (uint64_t)chunk * E + (E - 1024) + lane * 16 + 12;
+    uint32_t w = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)) + at);
+    if (uni64((uint64_t)dp->base) != 0) w ^= *reinterpret_cast<const uint32_t *>(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) + at);
+    const uint32_t last = len16[(w >> 3) & 15] + len16[(w >> 11) & 15] + len16[(w >> 19) & 15] + len16[(w >> 27) & 15];
+    const uint32_t steps = E / 256;                              // 4 per row of 1 KiB
+    uint32_t q = ((bits - last) >> 5) + 2;
+    q = q < steps ? q : steps;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+    if (lane == 0) {
+        uint32_t *my = units + uni32(dp->units_off);
+        const uint32_t nc = uni32(dp->n_chunks);
+        my[chunk] = (q + 3) / 4;
+        my[nc + chunk] = E / 32;                            // 4 bits per element, 16-byte units (flat code and raw alike)
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// The same two reads instead of three for the formats whose fields are 8-bit symbols, 8 per 16-byte run (BF16;
+// FP8 in byte symbols) or 16 (FP8 E5M2), with 64 lanes and chunks of kHistBlockBytes: weights, checkpoints and
+// checkpoint deltas (Sec. 3.1, 3.2, 4.1).  A lane's field has 256 possible symbols, so its counts are 512 bytes per field and lane, 64 KiB
+// per chunk: a quarter of the chunk, written once here and read once by k_sizes_rows8_counts, against a whole
+// second read of the source (and of the base of a delta) by the generic size pass.
+//
+// k_hist_rows8_lanes: one workgroup of eight wavefronts per whole chunk.  Thread t takes the runs t, t + 512, ...:
+// all of chunk lane t % 64.  LDS holds, per field, a histogram of the 256 symbols per lane in the layout of
+// k_hist_fp8_lanes (16-bit counters, lanes l and l + 32 in the halves of word [symbol][l % 32]: conflict-free
+// whatever the data; a lane holds 2,048 symbols of a field).  At the end the arrays go to lane_counts as they are
+// (field, symbol, word: 64 KiB at lane_counts + chunk * 16384 words), and their sums over the lanes are added to the
+// tensor's histograms, beside what k_hist counts.
+template <int FMT>
+__global__ __launch_bounds__(512) void k_hist_rows8_lanes(const TensorDev *descs, const WorkItem *work, uint64_t *hist, uint32_t *lane_counts)
+{
+    static_assert((Fmt<FMT>::G == 8 || Fmt<FMT>::G == 16) && Fmt<FMT>::SB == 8 && Fmt<FMT>::NF == 2, "two fields of 8 or 16 symbols of 8 bits per run");
+    static_assert(kHistBlockBytes / 16 / 64 * Fmt<FMT>::G < 65536, "a lane's count of one symbol fits 16 bits");
+    constexpr int kWords = Fmt<FMT>::G / 4;                      // words of four symbols per run and field
+    __shared__ __attribute__((aligned(16))) uint32_t cnt[2 * 256 * 32];      // 64 KiB
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev &d = descs[it.tensor];
+    const uint32_t tid = threadIdx.x, lane = tid & 63;
+    const uint64_t start = (uint64_t)it.first * kHistBlockBytes, nbytes = d.n_elems * (uint64_t)Fmt<FMT>::EB / 8;
+    if (d.chunk_bytes != kHistBlockBytes || start + kHistBlockBytes > nbytes) return;          // whole workgroup; the host never asks for this
+    uint4 *const cnt4 = reinterpret_cast<uint4 *>(cnt);
+    for (uint32_t i = tid; i < 2 * 256 * 32 / 4; i += 512) cnt4[i] = make_uint4(0, 0, 0, 0);
+    __syncthreads();
+    const uint8_t *p = d.src + start;
+    const uint8_t *base = d.base ? d.base + start : nullptr;
+    const uint32_t l4 = (lane & 31) * 4, inc = lane < 32 ? 1u : 0x10000u;
+    char *const lds0 = reinterpret_cast<char *>(cnt), *const lds1 = lds0 + 256 * 32 * 4;
+    auto count = [&](const uint4 &v) {
+        uint64_t P0, Q0, P1, Q1;
+        split_run4<FMT>(v, P0, Q0, P1, Q1);
+        const uint32_t w0[4] = {(uint32_t)P0, (uint32_t)(P0 >> 32), (uint32_t)Q0, (uint32_t)(Q0 >> 32)};
+        const uint32_t w1[4] = {(uint32_t)P1, (uint32_t)(P1 >> 32), (uint32_t)Q1, (uint32_t)(Q1 >> 32)};
+#pragma unroll
+        for (int i = 0; i < kWords; i++) {
+            atomicAdd(reinterpret_cast<uint32_t *>(lds0 + (((w0[i] << 7) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds0 + (((w0[i] >> 1) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds0 + (((w0[i] >> 9) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds0 + (((w0[i] >> 17) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds1 + (((w1[i] << 7) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds1 + (((w1[i] >> 1) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds1 + (((w1[i] >> 9) & 0x7F80u) | l4)), inc);
+            atomicAdd(reinterpret_cast<uint32_t *>(lds1 + (((w1[i] >> 17) & 0x7F80u) | l4)), inc);
+        }
+    };
+    // eight 16-byte loads per thread in flight at a time
+    constexpr uint32_t kStep = 512 * 16, kDepth = 8;
+    static_assert(kHistBlockBytes % (kStep * kDepth) == 0, "whole rounds");
+    for (uint32_t off = tid * 16; off < kHistBlockBytes; off += kDepth * kStep) {
+        uint4 v[kDepth];
+#pragma unroll
+        for (uint32_t k = 0; k < kDepth; k++) v[k] = *reinterpret_cast<const uint4 *>(p + off + k * kStep);
+        if (base) {
+#pragma unroll
+            for (uint32_t k = 0; k < kDepth; k++) v[k] = xor4(v[k], *reinterpret_cast<const uint4 *>(base + off + k * kStep));
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < kDepth; k++) count(v[k]);
+    }
+    __syncthreads();
+    // the counts per lane, as they lie
+    const uint64_t chunk_global = (uint64_t)(d.units_off / 2) + it.first;          // two fields: units_off counts two entries per chunk
+    uint4 *const out = reinterpret_cast<uint4 *>(lane_counts + chunk_global * (2 * 256 * 32));
+    for (uint32_t i = tid; i < 2 * 256 * 32 / 4; i += 512) out[i] = cnt4[i];
+    // thread (field, symbol) sums the symbol's 64 lanes, starting at a different word per thread (different banks)
+    const uint32_t f = tid >> 8, bin = tid & 255;
+    uint32_t sum = 0;
+#pragma unroll 8
+    for (uint32_t r = 0; r < 32; r++) {
+        const uint32_t c = cnt[(f * 256 + bin) * 32 + ((r + bin) & 31)];
+        sum += (c & 0xFFFFu) + (c >> 16);
+    }
+    // BF16 and byte symbols: field f's histogram is the tensor's slot f.  E5M2: slot 0 is the histogram of the bytes that
+    // k_hist counts, and the field histograms of what this kernel counts go to slot 1, exponents at 0..31 and sign+mantissa
+    // symbols at 32..39 (k_codes adds them up)
+    const uint64_t at = FMT == ZC_FMT_FP8_E5M2 ? 256 + (f ? 32 : 0) + bin : f * 256 + bin;
+    if (sum && (FMT != ZC_FMT_FP8_E5M2 || bin < (f ? 8u : 32u)))
+        atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(uint64_t)it.tensor * 768 + at]), (unsigned long long)sum);
+}
+
+// Stream sizes of whole chunks from those counts, for the tensors the 64-lane encoder of these formats takes (route 2:
+// exponent field table coded, sign+mantissa field flat, raw or table coded) and for every E5M2 tensor (whichever
+// encoder writes it).  A table-coded field: as in
+// k_sizes_fp8_counts, with R symbols per refill step (R codes are at most 32 bits, which is all the argument there
+// needs): a lane's words are min(steps, floor((bits - bits of its last R codes) / 32) + 2), its bits the counts times
+// the code lengths.  A flat or raw field takes its plain size.  One wavefront per chunk, work items as for the
+// generic whole-chunk size pass.  A wavefront reads a field's counts 16 bytes per lane (eight symbols' rows of 32
+// words per load), so a lane gathers parts of eight chunk lanes' bit totals; LDS additions bring them together.
+template <int FMT>
+__global__ __launch_bounds__(256) void k_sizes_rows8_counts(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables,
+                                                            const uint32_t *lane_counts, uint32_t *units)
+{
+    __shared__ uint32_t lens[2][256];
+    __shared__ uint32_t total[kWavesPerGroup][2][64];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev *dp = descs + it.tensor;
+    if (dp->route != 2 && (FMT != ZC_FMT_FP8_E5M2 || dp->route != 0)) return;      // whole workgroup: the generic size pass takes this tensor
+    constexpr uint32_t G = Fmt<FMT>::G;                           // symbols per run and field
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    lens[0][tid] = enc_tables[(uint64_t)it.tensor * 768 + tid] >> 16;
+    lens[1][tid] = enc_tables[(uint64_t)it.tensor * 768 + 256 + tid] >> 16;
+    total[wave][0][lane] = 0;
+    total[wave][1][lane] = 0;
+    __syncthreads();
+    const uint32_t chunk = uni32(it.first + wave);
+    const uint32_t cb = uni32(dp->chunk_bytes);
+    const uint64_t nbytes = uni64(dp->n_elems) * (uint64_t)Fmt<FMT>::EB / 8;
+    const bool mine = cb == kHistBlockBytes && chunk < (uint32_t)(nbytes / cb);
+    const uint64_t chunk_global = (uint64_t)(uni32(dp->units_off) / 2) + (mine ? chunk : 0u);
+    const uint32_t kind[2] = {uni32(dp->kind[0]), uni32(dp->kind[1])};       // 0 table coded, 1 flat code, 2 raw, 3 constant
+    const bool coded[2] = {kind[0] == 0, kind[1] == 0};
+    if (mine) {
+#pragma unroll
+        for (int f = 0; f < 2; f++) {
+            if (!coded[f]) continue;
+            const uint4 *rows = reinterpret_cast<const uint4 *>(lane_counts + chunk_global * (2 * 256 * 32) + f * (256 * 32)) + lane;
+            uint32_t acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll 4
+            for (uint32_t i = 0; i < 32; i++) {
+                const uint4 c = rows[i * 64];                    // symbol 8 * i + lane / 8, chunk lanes 4 * (lane % 8) .. + 3 and those + 32
+                const uint32_t len = lens[f][8 * i + (lane >> 3)];
+                const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+                for (int k = 0; k < 4; k++) { acc[k] += (w[k] & 0xFFFFu) * len; acc[4 + k] += (w[k] >> 16) * len; }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                atomicAdd(&total[wave][f][4 * (lane & 7) + k], acc[k]);
+                atomicAdd(&total[wave][f][32 + 4 * (lane & 7) + k], acc[4 + k]);
+            }
+        }
+    }
+    __syncthreads();
+    if (!mine) return;
+    // the lane's last run: its last R symbols of either field
+    const uint64_t at = (uint64_t)chunk * cb + (cb - 1024) + lane * 16;
+    uint4 v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)) + at);
+    if (uni64((uint64_t)dp->base) != 0) v = xor4(v, *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) + at));
+    uint64_t P[2], Q[2];
+    split_run4<FMT>(v, P[0], Q[0], P[1], Q[1]);
+    uint32_t u[2];
+#pragma unroll
+    for (int f = 0; f < 2; f++) {
+        if (!coded[f]) {
+            u[f] = kind[f] == 3 ? 0u : cb / 256 * G;              // 8 bits per symbol, G symbols per 16 bytes of the chunk; a constant field: nothing
+            continue;
+        }
+        const uint32_t R = uni32(dp->period[f]);                 // 2, 4, 8 or, with runs of 16 symbols, 16
+        uint32_t last = 0;
+        for (uint32_t j = G - R; j < G; j++) last += lens[f][(uint32_t)((G == 16 && j >= 8 ? Q[f] : P[f]) >> (8 * (j & 7))) & 0xFFu];
+        const uint32_t steps = cb / 1024 * G / R;
+        uint32_t q = ((total[wave][f][lane] - last) >> 5) + 2;
+        q = q < steps ? q : steps;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+        u[f] = (q + 3) / 4;
+    }
+    if (lane == 0) {
+        uint32_t *my = units + uni32(dp->units_off);
+        const uint32_t nc = uni32(dp->n_chunks);
+        my[chunk] = u[0];
+        my[nc + chunk] = u[1];
+    }
+}
+
+int launch_hist_fp8_lanes(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint16_t *d_lane_counts, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipLaunchKernelGGL(k_hist_fp8_lanes, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
+    return (int)hipGetLastError();
+}
+
+int launch_sizes_fp8_counts(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, const uint16_t *d_lane_counts,
+                            uint32_t *d_units, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipLaunchKernelGGL(k_sizes_fp8_counts, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
+    return (int)hipGetLastError();
+}
+
+// fmt: ZC_FMT_BF16, ZC_FMT_FP8_E4M3_BYTES or ZC_FMT_FP8_E5M2.  One work item per whole chunk of kHistBlockBytes.
+int launch_hist_rows8_lanes(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint32_t *d_lane_counts, void *stream)
+{
+    if (n_work == 0) return 0;
+    if (fmt == ZC_FMT_BF16) hipLaunchKernelGGL(k_hist_rows8_lanes<ZC_FMT_BF16>, dim3(n_work), dim3(512), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
+    else if (fmt == ZC_FMT_FP8_E4M3_BYTES)
+        hipLaunchKernelGGL(k_hist_rows8_lanes<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(512), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
+    else if (fmt == ZC_FMT_FP8_E5M2)
+        hipLaunchKernelGGL(k_hist_rows8_lanes<ZC_FMT_FP8_E5M2>, dim3(n_work), dim3(512), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
+    else return 1;
+    return (int)hipGetLastError();
+}
+
+// work items of kWavesPerGroup whole chunks, as for the generic whole-chunk size pass
+int launch_sizes_rows8_counts(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
+                              const uint32_t *d_lane_counts, uint32_t *d_units, void *stream)
+{
+    if (n_work == 0) return 0;
+    if (fmt == ZC_FMT_BF16)
+        hipLaunchKernelGGL(k_sizes_rows8_counts<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
+    else if (fmt == ZC_FMT_FP8_E4M3_BYTES)
+        hipLaunchKernelGGL(k_sizes_rows8_counts<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
+    else if (fmt == ZC_FMT_FP8_E5M2)
+        hipLaunchKernelGGL(k_sizes_rows8_counts<ZC_FMT_FP8_E5M2>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
+    else return 1;
+    return (int)hipGetLastError();
+}
+
+}  // namespace zc

@@ -159,19 +159,21 @@ int launch_decode_e5m2(bool xor_delta, const TensorDev *d_descs, const WorkItem 
 int launch_sizes_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream);
 // FP8, 64 lanes, chunks of kHistBlockBytes: the histogram pass that also counts exponents per chunk lane (one work
 // item per whole chunk; 16 u16 per lane, 2 KiB per chunk, at lane_counts[(units_off / 2 + chunk) * 1024]), and the
-// size pass that reads those counts instead of the source (same work list as launch_sizes_fp8)
+// size pass that reads those counts instead of the source (same work list as launch_sizes_fp8) (zc_hist_lanes.hip)
 int launch_hist_fp8_lanes(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint16_t *d_lane_counts, void *stream);
-// BF16 / FP8 in byte symbols, 64 lanes, chunks of kHistBlockBytes: the same for fields of 8-bit symbols (256 counts of 16 bits
-// per lane and field, 64 KiB per chunk, at lane_counts + (units_off / 2 + chunk) * 16384 words), and the size pass of the
-// tensors of route 2 from those counts
+// BF16 / FP8 in byte symbols / FP8 E5M2, 64 lanes, chunks of kHistBlockBytes: the same for fields of 8-bit symbols (256 counts
+// of 16 bits per lane and field, 64 KiB per chunk, at lane_counts + (units_off / 2 + chunk) * 16384 words), and the size pass of
+// the tensors of route 2 (E5M2: of every tensor) from those counts (zc_hist_lanes.hip)
 int launch_hist_rows8_lanes(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint32_t *d_lane_counts, void *stream);
 int launch_sizes_rows8_counts(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
                               const uint32_t *d_lane_counts, uint32_t *d_units, void *stream);
 int launch_sizes_fp8_counts(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, const uint16_t *d_lane_counts,
                             uint32_t *d_units, void *stream);
 int launch_encode_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
-// BF16, 64 lanes, full chunks, exponent field table coded, sign+mantissa flat or raw; work items as for the generic whole-chunk build
+// BF16 (FP8 in byte symbols, FP8 E5M2), 64 lanes, full chunks, exponent field table coded, sign+mantissa flat, raw or table coded;
+// work items as for the generic whole-chunk build (zc_encode_fast.hip)
 int launch_encode_bf16(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
+// K/V pages, 4 to 32 lanes per chunk (zc_encode_pages.hip)
 int launch_compress_pages_fused(uint32_t streams, uint32_t bf16_periods, bool reversed, const TensorDev *d_descs, uint32_t n_tensors, const uint32_t *d_enc,
                                 const uint8_t *d_blobs, uint32_t blob_bytes, ScanOut *d_out, void *stream);
 uint32_t compress_pages_fused_limit();      // most pages per tensor the fused kernel takes

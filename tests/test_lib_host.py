@@ -71,10 +71,17 @@ def test_bounds_and_workspace():
         sizes = [zc.workspace_bytes([n], zc.params(fmt, cb)) for n in (1 << 20, 1 << 24, 1 << 26)]
         assert sizes[0] < sizes[1] < sizes[2]
         assert zc.workspace_bytes([1 << 24, 1 << 24], zc.params(fmt, cb)) > sizes[1]
+    # The formats of 8-bit symbols (BF16, FP8 in byte symbols, FP8 E5M2) reserve 64 KiB per chunk there: 256 counts per
+    # chunk lane and field.  FP8 E4M3 and E5M2 have the same element size, fields and work lists, so they differ by the counts.
     n = 1 << 28
-    with_counts = zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E4M3, 262144))
-    without = zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E5M2, 262144))           # same element size, fields and work lists
-    assert with_counts - without == (n // 262144) * 2048
+    e4 = zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E4M3, 262144))
+    e5 = zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E5M2, 262144))
+    assert e5 - e4 == (n // 262144) * (65536 - 2048)
+    assert zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E4M3_BYTES, 262144)) == e5
+    assert zc.workspace_bytes([n // 2], zc.params(zc.FMT_BF16, 262144)) == e5
+    # other chunk sizes and lane counts reserve nothing of the kind
+    assert zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E5M2, 131072)) < e4
+    assert zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E5M2, 262144, streams=32)) < e4
     assert zc.compress_bound(100, zc.params(zc.FMT_FP8_E4M3, 100)) == 0       # chunk not a multiple of 16
     assert zc.compress_bound(100, zc.params(9, 4096)) == 0
     assert zc.compress_bound(33, zc.params(zc.FMT_FP4_E2M1_MX, 256)) == 0     # FP4 needs whole 32-blocks
