@@ -29,20 +29,21 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
-HEADLINE_KERNEL_SOURCE = os.path.join(ROOT, "paper_2508_19263_amd", "csrc", "zc_decode_fast.hip")
+# the headline kernel's source: the kernel's file and the device helpers it is built from
+HEADLINE_KERNEL_SOURCES = [os.path.join(ROOT, "paper_2508_19263_amd", "csrc", f) for f in ("zc_decode_fast.hip", "zc_decode_device.h")]
 HEADLINE_COUNTER_PROFILE = os.path.join(ROOT, "profiles", "k_decode_fp8__fp8_weight_set__counters.md")
 
 
 def measured_traffic(workload):
     """HBM bytes per decode launch from the committed counter profile (FETCH_SIZE + WRITE_SIZE of a rocprofv3 --pmc
     run, each scaled by what the same counter reads for the plain copy kernel).  The profile carries the hash of the
-    kernel's source file; when the file has changed since, the figure is stale and None is reported."""
+    kernel's source files; when they have changed since, the figure is stale and None is reported."""
     try:
         text = open(HEADLINE_COUNTER_PROFILE).read()
         m = re.search(r"bench: workload=(\S+) kernel=(\S+) traffic_bytes=(\d+) source_sha256=([0-9a-f]+) commit=(\S+)", text)
         if not m or m.group(1) != workload:
             return None
-        if hashlib.sha256(open(HEADLINE_KERNEL_SOURCE, "rb").read()).hexdigest()[:16] != m.group(4)[:16]:
+        if hashlib.sha256(b"".join(open(f, "rb").read() for f in HEADLINE_KERNEL_SOURCES)).hexdigest()[:16] != m.group(4)[:16]:
             return None
         return int(m.group(3))
     except OSError:
