@@ -323,7 +323,7 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
         run("bf16_kv_pages", zc.FMT_BF16, kv, [t.numel() for t in kv], 4096, 8, ids=ids, policy=zc.POLICY_AUTO, decode_kernel="k_decode_bf16_sub<8>", compress_kernels="k_hist + k_codes + k_encode_fp8_sub<BF16> (sizes) + k_scan + k_encode_fp8_sub<BF16>")
         # with the fields in reverse order a dictionary call codes, places and writes these pages in one read of them
         run("bf16_kv_pages_reverse_fields", zc.FMT_BF16, kv, [t.numel() for t in kv], 4096, 8, ids=ids, policy=zc.POLICY_AUTO, dictionary=True, flags=zc.FLAG_REVERSE_FIELDS,
-            decode_kernel="k_decode_bf16_sub<8>", compress_kernels="k_hist + k_codes + k_encode_fp8_sub<BF16> (sizes) + k_scan + k_encode_fp8_sub<BF16>")
+            decode_kernel="k_decode_bf16_sub<8>", compress_kernels="k_hist + k_codes + k_compress_pages_chained<BF16> (sizes, scan and encoder in one pass over the source)")
     return out
 
 

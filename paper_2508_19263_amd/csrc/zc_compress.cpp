@@ -151,7 +151,7 @@ zc_status CompressQueue::queue_codes(uint32_t policy) const
 zc_status CompressQueue::queue_sizes_and_scan() const
 {
     if (chained)
-        LAUNCH_TRY(launch_compress_pages_chained(g.S, 0, chain_hold, d_descs(), d_list(w.fast_work), n_fast, chain_step, d_enc(), ws + w.blobs, (uint32_t)kBlobBytes,
+        LAUNCH_TRY(launch_compress_pages_chained(g.S, sh.bf16 ? 16u : 0u, chain_hold, d_descs(), d_list(w.fast_work), n_fast, chain_step, d_enc(), ws + w.blobs, (uint32_t)kBlobBytes,
                                                  (uint64_t *)(ws + chain_status), (uint64_t *)(ws + chain_counter), (ScanOut *)(ws + w.scan), stream));
     else if (g.S == 64 && sh.lanes) LAUNCH_TRY(launch_sizes_fp8_counts(d_descs(), d_list(w.fast_work), n_fast, d_enc(), d_lane_counts(), d_units(), stream));
     else if (g.S == 64) LAUNCH_TRY(launch_sizes_fp8(d_descs(), d_list(w.fast_work), n_fast, d_enc(), d_units(), stream));
@@ -165,8 +165,8 @@ zc_status CompressQueue::queue_sizes_and_scan() const
         LAUNCH_TRY(launch_sizes(g.fmt, sh.whole_mode, sh.lanes8 ? 0x6 : 0x2, d_descs(), d_list(w.whole_work), n_whole, d_enc(), d_units(), stream));
     LAUNCH_TRY(launch_sizes(g.fmt, 0, 0x6, d_descs(), d_list(w.other_work), n_other, d_enc(), d_units(), stream));
     LAUNCH_TRY(launch_sizes(g.fmt, 0, 0, d_descs(), d_list(w.chunk_work), n_slow, d_enc(), d_units(), stream));
-    // the chained kernel has placed and written the tensors of its route (1) itself
-    LAUNCH_TRY(launch_scan(d_descs(), T, (int)g.nf, g.reversed, chained ? 0x2 : 0, d_units(), (ScanOut *)(ws + w.scan), stats_only ? nullptr : ws + w.blobs,
+    // the chained kernel has placed and written the tensors of its route (FP8: 1, BF16: 2) itself
+    LAUNCH_TRY(launch_scan(d_descs(), T, (int)g.nf, g.reversed, chained ? (sh.bf16 ? 0x4 : 0x2) : 0, d_units(), (ScanOut *)(ws + w.scan), stats_only ? nullptr : ws + w.blobs,
                            (uint32_t)kBlobBytes, stream));
     return ZC_OK;
 }
@@ -606,12 +606,12 @@ private:
     }
 
     // ---- the code is built on the device (a4): nothing between the histogram and the encoder waits for the host
-    // Codes built on the device and FP8 pages in a container with reversed payload order: the one-pass kernel takes every
-    // tensor whose code turns out to suit it (decided on the device; the others go through the generic kernels as
-    // before).  Its chain lives where the histograms were: they are dead once the codes are built.
+    // Codes built on the device and FP8 or BF16 pages in a container with reversed payload order: the one-pass kernel takes
+    // every tensor whose code turns out to suit it (decided on the device, BF16: whatever the refill period of its exponent
+    // field; the others go through the generic kernels as before).  Its chain lives where the histograms were: they are dead once the codes are built.
     void choose_chained_device_path()
     {
-        if (!g.reversed || g.fmt != ZC_FMT_FP8_E4M3 || g.S < 4 || g.S > 32 || stats_only) return;
+        if (!g.reversed || (g.fmt != ZC_FMT_FP8_E4M3 && g.fmt != ZC_FMT_BF16) || g.S < 4 || g.S > 32 || stats_only) return;
         uint64_t items = 0;
         const uint32_t step = chained_step();
         for (uint32_t t = 0; t < T; t++) {

@@ -266,6 +266,22 @@ __device__ __forceinline__ uint32_t encode_pages(const TensorDev *dp, uint32_t f
     return did_not_fit;
 }
 
+// The same for a kernel whose BF16 tensors may differ in the refill period of their exponent field (BF == kAnyBf16: the period
+// is the tensor's, 2, 4 or 8).
+constexpr int kAnyBf16 = 16;
+template <int S, int MODE, int BF>
+__device__ __forceinline__ uint32_t encode_pages_of(uint32_t period, const TensorDev *dp, uint32_t first_chunk, uint32_t slots_per_group, const uint32_t *pair,
+                                                    uint32_t *stage, uint32_t *pairs_of_rows, const uint32_t *index0, const uint32_t *index1, uint32_t *my,
+                                                    uint32_t my_stride, uint32_t rel, uint32_t hold)
+{
+    if (BF != kAnyBf16) return encode_pages<S, MODE, (BF == kAnyBf16 ? 2 : BF)>(dp, first_chunk, slots_per_group, pair, stage, pairs_of_rows, index0, index1, my, my_stride, rel, hold);
+    switch (period) {
+    case 2: return encode_pages<S, MODE, 2>(dp, first_chunk, slots_per_group, pair, stage, pairs_of_rows, index0, index1, my, my_stride, rel, hold);
+    case 4: return encode_pages<S, MODE, 4>(dp, first_chunk, slots_per_group, pair, stage, pairs_of_rows, index0, index1, my, my_stride, rel, hold);
+    default: return encode_pages<S, MODE, 8>(dp, first_chunk, slots_per_group, pair, stage, pairs_of_rows, index0, index1, my, my_stride, rel, hold);
+    }
+}
+
 template <int S, bool WRITE, int BF>
 __global__ __launch_bounds__(256) void k_encode_fp8_sub(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units,
                                                         uint32_t slots_per_group)
@@ -490,7 +506,8 @@ __global__ __launch_bounds__(256) void k_compress_pages_chained(const TensorDev 
     const uint32_t per_page = cb / 32;                          // units of a sign+mantissa stream
     // what the host checked before it chose this kernel; a tensor that is not as promised is left alone, but its
     // place in the chain is filled so that nobody waits for it
-    const bool mine = dp->route == (BF ? 2 : 1) && (!BF || dp->period[0] == BF) && comp && count > 0 &&
+    const uint32_t period = uni32(dp->period[0]);
+    const bool mine = dp->route == (BF ? 2 : 1) && (!BF || (BF == kAnyBf16 ? (period == 2 || period == 4 || period == 8) : period == (uint32_t)BF)) && comp && count > 0 &&
                       uni64(dp->n_elems) * (BF ? 2 : 1) == (uint64_t)nc * cb && (uint64_t)nc * per_page < 0x80000000ull;
     if (!mine) {
         if (tid == 0) chain_publish(status + item, kChainPrefix);
@@ -512,8 +529,8 @@ __global__ __launch_bounds__(256) void k_compress_pages_chained(const TensorDev 
     __syncthreads();
     const uint32_t slots = (count + kWavesPerGroup * kGroups - 1) / (kWavesPerGroup * kGroups) * (kWavesPerGroup * kGroups);
     // HOLD: the sign+mantissa streams are written here, the exponent streams stay in `stage`
-    const uint32_t did_not_fit = encode_pages<S, HOLD ? kPagesHold : kPagesSize, BF>(dp, first, slots, pair, stage, pairs_of_rows, nullptr, nullptr, sizes,
-                                                                                     0, first, hold);
+    const uint32_t did_not_fit = encode_pages_of<S, HOLD ? kPagesHold : kPagesSize, BF>(period, dp, first, slots, pair, stage, pairs_of_rows, nullptr, nullptr, sizes,
+                                                                                        0, first, hold);
     const bool again = __syncthreads_or((int)did_not_fit) != 0;
     if (tid < 64) {
         // exclusive scan of up to 256 sizes by one wavefront, four consecutive pages per lane
@@ -579,7 +596,7 @@ __global__ __launch_bounds__(256) void k_compress_pages_chained(const TensorDev 
         }
         return;
     }
-    encode_pages<S, kPagesWrite, BF>(dp, first, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr, 0, first);
+    encode_pages_of<S, kPagesWrite, BF>(period, dp, first, slots, pair, stage, pairs_of_rows, idx0, idx1, nullptr, 0, first, 0);
 }
 
 __global__ void k_chain_reset(uint64_t *status, uint32_t n_work, uint64_t *counter)
@@ -599,13 +616,14 @@ static void launch_chained_s(uint32_t hold, uint32_t bf16_period, const TensorDe
     case 0: ZC_CHAINED(0); break;
     case 2: ZC_CHAINED(2); break;
     case 4: ZC_CHAINED(4); break;
-    default: ZC_CHAINED(8); break;
+    case 8: ZC_CHAINED(8); break;
+    default: ZC_CHAINED(kAnyBf16); break;
     }
 #undef ZC_CHAINED
 }
 
 // streams: 4, 8, 16 or 32.  bf16_period: 0 for FP8 tensors (route 1), else the one refill period of the exponent field that
-// every BF16 tensor of the call has (route 2).  Work items in natural order (tensor by tensor, pages ascending), each
+// every BF16 tensor of the call has (route 2), or 16 where the tensors may differ in it (codes built on the device).  Work items in natural order (tensor by tensor, pages ascending), each
 // slots_per_item pages (a multiple of the pages a workgroup takes per pass, at most compress_pages_chained_limit()).
 // hold: 0, or the words of LDS per page (a multiple of 4) of the build that keeps the exponent streams there and reads
 // the source once; slots_per_item * hold is then at most compress_pages_held_words().  d_status: n_work words,
@@ -615,7 +633,8 @@ int launch_compress_pages_chained(uint32_t streams, uint32_t bf16_period, uint32
                                   uint64_t *d_counter, ScanOut *d_out, void *stream)
 {
     if (n_work == 0) return 0;
-    if (slots_per_item == 0 || slots_per_item > kChainItemPages || (bf16_period != 0 && bf16_period != 2 && bf16_period != 4 && bf16_period != 8)) return 1;
+    if (slots_per_item == 0 || slots_per_item > kChainItemPages) return 1;
+    if (bf16_period != 0 && bf16_period != 2 && bf16_period != 4 && bf16_period != 8 && bf16_period != (uint32_t)kAnyBf16) return 1;
     if (streams < 4 || streams > 32 || slots_per_item % (kWavesPerGroup * (64 / streams))) return 1;
     if (hold % 4 || (uint64_t)slots_per_item * hold > kHeldWords) return 1;
     hipStream_t st = (hipStream_t)stream;

@@ -997,6 +997,33 @@ def test_dictionary_compress_of_pages_in_one_pass():
                     out, _ = zc.decompress(comp, info)
                     torch.cuda.synchronize()
                     assert torch.equal(out.cpu(), b)
+    # BF16 pages with codes of their own, built on the device: one call whose tensors have exponent codes of different
+    # refill periods (8, 4 and 2 symbols), a constant exponent field and a table-coded sign+mantissa field (both left to
+    # the generic kernels), pages of 4 KiB (streams kept in LDS) and of 16 KiB (sized first)
+    def bf16_sm(n, n_exp, skew, sm_values):
+        sm = rng.integers(0, sm_values, n).astype(np.uint16)
+        pick = rng.integers(0, n_exp, n) if skew == 0 else np.minimum(rng.geometric(skew, n) - 1, 199)
+        ex = (pick.astype(np.uint16) * 3 + 60) & 0xFF
+        return torch.from_numpy((((sm >> 7) << 15) | (ex << 7) | (sm & 0x7F)).astype(np.uint16).view(np.uint8).copy())
+
+    for S, cb in ((8, 4096), (16, 4096), (32, 16384), (4, 1024)):
+        for policy in (zc.POLICY_HUFF_ALL, zc.POLICY_AUTO):
+            p, po = zc.params(zc.FMT_BF16, cb, streams=S, policy=policy, flags=R), o.params(o.BF16, cb, streams=S, policy=policy, payload_order=1)
+            srcs = [bf16_sm(700 * cb // 2, 12, 0, 256), bf16_sm(600 * cb // 2, 40, 0, 256), bf16_sm(1030 * cb // 2, 200, 0.08, 256),
+                    bf16_sm(520 * cb // 2, 1, 0, 256), bf16_sm(640 * cb // 2, 30, 0, 5), bf16_sm(3 * cb // 2, 40, 0, 256)]
+            print("one pass bf16, own codes S", S, "page", cb, "policy", policy, flush=True)
+            bt = zc.Batch([dev(x) for x in srcs], [x.numel() // 2 for x in srcs], p)
+            sizes = bt.compress()
+            for t, x in enumerate(srcs):
+                want = o.compress(x.numpy(), x.numel() // 2, po)
+                got = bt.container(t).cpu().numpy()
+                assert sizes[t] == len(want) and np.array_equal(got, want), (t, int(np.argmax(got[:len(want)] != want[:len(got)])))
+            bt.decompress()
+            torch.cuda.synchronize()
+            for t, x in enumerate(srcs):
+                assert torch.equal(bt.out[t].cpu()[:x.numel()], x), t
+            bt.compress_async()
+            assert bt.refresh_info() == sizes
 
 
 def test_byte_grouped_symbols():
