@@ -1208,6 +1208,28 @@ def test_random_sweep_whole_row_chunks_and_pages():
         check_case(fmt, n, cb, S, policy, L, data=(src, sc), base=base, tag="rows-%d" % case, order=int(case % 3 == 0))
 
 
+def test_random_sweep_chunks_of_256_kib():
+    # the same kind of sweep over 64 lanes with chunks of 256 KiB, where the histogram pass also counts symbols per chunk lane
+    # and the stream sizes come from those counts: FP8 (16 exponent counts per lane) and the formats of 8-bit symbols
+    rng = np.random.default_rng(20261130)
+    fmts = (zc.FMT_BF16, zc.FMT_FP8_E4M3_BYTES, zc.FMT_FP8_E5M2, zc.FMT_FP8_E4M3)
+    cb = 262144
+    for case in range(96):
+        fmt = fmts[case % len(fmts)]
+        E = cb * 8 // zc.elem_bits(fmt)
+        n = int(rng.integers(1, 4)) * E if rng.integers(0, 2) else int(rng.integers(0, 3 * E + 2))
+        policy = int(rng.integers(0, 2))
+        lo = 4 if fmt == zc.FMT_FP8_E4M3 else 8
+        L = (int(rng.integers(lo, 17)) if rng.integers(0, 2) else 0, int(rng.integers(lo, 17)) if rng.integers(0, 2) else 0, 0)
+        src, sc = _random_source(rng, fmt, n)
+        base = None
+        if rng.integers(0, 3) == 0 and n:
+            base = torch.from_numpy(rng.integers(0, 256, src.numel(), dtype=np.uint8) & np.uint8(rng.choice([0x01, 0x81, 0xFF, 0x03])))
+        if src.numel() == 0:
+            src = torch.zeros(0, dtype=torch.uint8)
+        check_case(fmt, n, cb, 64, policy, L, data=(src, sc), base=base, tag="256k-%d" % case, order=int(case % 3 == 0))
+
+
 def test_random_sweep_of_batches():
     # random sets of tensors (1 to 8, whole and ragged lengths, empty ones) through zc_compress_batch and
     # zc_decompress_batch: every container against the oracle's, every round trip bit for bit.  What a set shares
