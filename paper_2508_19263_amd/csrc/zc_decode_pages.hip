@@ -65,6 +65,9 @@ __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, 
     const uint32_t *index1 = reinterpret_cast<const uint32_t *>(comp + uniform32(d.index_off[1]));
     const bool sm_raw = uniform32(d.kind[1]) == 2;
     const uint32_t rows = cb / (16 * S);
+    // A group's store of a row is 16 * S contiguous bytes: from a whole cache line on (8 lanes) it carries the non-temporal
+    // hint, so that the decoded pages do not push the partly read lines of the streams out of the L2 (page lists 4 % faster)
+    constexpr int kOutPolicy = S >= 8 ? 2 : 0;
     const uint32_t one = 1;
     const char *lut_bytes = reinterpret_cast<const char *>(lut);
     char *const ring_bytes = reinterpret_cast<char *>(&ring[wave][0]) + grp * (kRing * 4);
@@ -160,7 +163,7 @@ __global__ __launch_bounds__(256) void k_decode_fp8_sub(const TensorDev *descs, 
             }
             u32x4 v = {o[0], o[1], o[2], o[3]};
             if (XOR) v ^= __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(base_off + (row * S + s) * 16), 0, 0);
-            if (alive) __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(out_off + (row * S + s) * 16), 0, 0);
+            if (alive) __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(out_off + (row * S + s) * 16), 0, kOutPolicy);
         }
     }
 }
@@ -242,6 +245,9 @@ __global__ __launch_bounds__(256) void k_decode_bf16_sub(const TensorDev *descs,
     const uint32_t period = uniform32(d.period[0]);
     const bool has_long = uniform32(tab.lmax) > (uint32_t)kLutBits;
     const uint32_t rows = cb / (16 * S);
+    // A group's store of a row is 16 * S contiguous bytes: from a whole cache line on (8 lanes) it carries the non-temporal
+    // hint, so that the decoded pages do not push the partly read lines of the streams out of the L2 (page lists 4 % faster)
+    constexpr int kOutPolicy = S >= 8 ? 2 : 0;
     const uint32_t mask = uniform32(tab.mask);
     const char *lut = reinterpret_cast<const char *>(tab.lut);
     char *const ring_bytes = reinterpret_cast<char *>(&ring[wave][0]) + grp * (kRing * 4);
@@ -344,7 +350,7 @@ __global__ __launch_bounds__(256) void k_decode_bf16_sub(const TensorDev *descs,
             const uint4 j = join_run4<ZC_FMT_BF16>((uint64_t)ex[0] | ((uint64_t)ex[1] << 32), 0, (uint64_t)m[0] | ((uint64_t)m[1] << 32), 0);
             u32x4 v = {j.x, j.y, j.z, j.w};
             if (XOR) v ^= __builtin_amdgcn_raw_buffer_load_b128(bs, (int)(base_off + (row * S + s) * 16), 0, 0);
-            if (alive) __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(out_off + (row * S + s) * 16), 0, 0);
+            if (alive) __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(out_off + (row * S + s) * 16), 0, kOutPolicy);
         }
     }
 }

@@ -126,7 +126,8 @@ __global__ __launch_bounds__(256) void k_decode_s64(const TensorDev *descs, cons
         const uint4 j = join_run4<FMT>(P0, Q0, P1, Q1);
         u32x4 v = {j.x, j.y, j.z, j.w};
         if (XOR) v ^= base;
-        __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
+        // (a whole row of the output, written once: stored with the non-temporal hint so that it does not displace the streams' lines in the L2)
+        __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 2);
     }
     if (TAIL && nbytes % 1024) {
         uint64_t P0 = 0, P1 = 0, Q0 = 0, Q1 = 0;
@@ -432,7 +433,7 @@ __device__ __forceinline__ void bf16_rows(const FieldTab *tab, uint32_t kind1, u
 #pragma unroll
         for (int i = 0; i < 4; i++) v[i] = bfi(kExpMask2, ea[i], mb[i]);
         if (XOR) v ^= base;
-        __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
+        __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 2);
     }
 }
 
@@ -561,7 +562,7 @@ __device__ __forceinline__ void e5m2_rows(const FieldTab &T, __amdgpu_buffer_rsr
         v[2] = e5m2_sm_bytes(__builtin_amdgcn_alignbit(hi, lo, 24)) | (uint32_t)Q;
         v[3] = e5m2_sm_bytes(hi >> 4) | (uint32_t)(Q >> 32);
         if (XOR) v ^= base;
-        __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 0);
+        __builtin_amdgcn_raw_buffer_store_b128(v, ds, (int)(lane * 16), (int)(row * 1024), 2);
     }
 }
 
