@@ -35,21 +35,25 @@ namespace zc {
 // the low half and field 1 in the high half: a copy is fed by 8 threads with at most 512 symbols each per
 // block, so neither half can overflow.
 template <int FMT>
-__global__ __launch_bounds__(256) void k_hist(const TensorDev *descs, const WorkItem *work, int elem_bits_, int scales_view, uint64_t *hist)
+__global__ __launch_bounds__(256) void k_hist(const TensorDev *descs, const WorkItem *work, int elem_bits_, int scales_view, uint64_t *hist, uint32_t split)
 {
     constexpr bool TWO = FMT != 0;
     static_assert(kHistBlockBytes / 16 * 8 / 32 < 65536, "a copy counts at most 8 symbols per 16-byte run of the block, over 32 copies");
     __shared__ uint32_t h[256 * 32];
-    const WorkItem it = work[blockIdx.x];
+    // split: workgroups per block of the work list (1, 2 or 4), each counting its part of the block: a list of few blocks is
+    // spread over more workgroups than the compute units hold at once, so that no second round of a few stragglers forms
+    const WorkItem it = work[blockIdx.x / split];
+    const uint32_t part_bytes = kHistBlockBytes / split;
     const TensorDev &d = descs[it.tensor];
     const uint8_t *p = scales_view ? d.scales : d.src;
     const uint8_t *base = scales_view ? nullptr : d.base;
     // scales_view: 0, or the number of elements per scale byte when the scale bytes are the input
     const uint64_t nbytes = scales_view ? d.n_elems / (uint32_t)scales_view : (d.n_elems * (uint64_t)elem_bits_ + 7) / 8;
+    const uint64_t start = (uint64_t)it.first * kHistBlockBytes + (uint64_t)(blockIdx.x % split) * part_bytes;
+    if (start >= nbytes) return;                                 // whole workgroup: the block ends before this part
     for (uint32_t i = threadIdx.x; i < 256 * 32; i += 256) h[i] = 0;
     __syncthreads();
-    const uint64_t start = (uint64_t)it.first * kHistBlockBytes;
-    const uint64_t end = start + kHistBlockBytes < nbytes ? start + kHistBlockBytes : nbytes;
+    const uint64_t end = start + part_bytes < nbytes ? start + part_bytes : nbytes;
     uint32_t *const mine = h + (threadIdx.x & 31);
     auto count = [&](const uint4 &v, uint32_t valid) {
         if (TWO) {
@@ -70,8 +74,8 @@ __global__ __launch_bounds__(256) void k_hist(const TensorDev *descs, const Work
                 if ((uint32_t)i < valid) atomicAdd(mine + ((w[i >> 2] >> (8 * (i & 3))) & 0xFFu) * 32, 1u);
         }
     };
-    if (end - start == kHistBlockBytes) {
-        // whole block: four 16-byte loads per thread in flight at a time
+    if (end - start == part_bytes) {
+        // whole part: four 16-byte loads per thread in flight at a time
         constexpr uint32_t kStep = 256 * 16;
         for (uint64_t off = start + (uint64_t)threadIdx.x * 16; off < end; off += 4 * kStep) {
             uint4 v[4];
@@ -110,14 +114,20 @@ int launch_hist(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, 
 {
     if (n_work == 0) return 0;
     hipStream_t st = (hipStream_t)stream;
+    static_assert(kHistBlockBytes % (4 * 4 * 256 * 16) == 0, "a quarter of a block is whole rounds of the kernel's loads");
+    // A list of so few blocks that the compute units are not full: two or four workgroups per block.  (Longer lists lose by
+    // it: every workgroup clears and folds its 32 KiB of counters and adds up to 256 totals to the tensor's bins, and C3's
+    // 1,344 blocks took 115 instead of 92 us in quarters.)
+    const uint32_t split = n_work <= 320 ? 4u : n_work <= 640 ? 2u : 1u;
+    const dim3 grid(n_work * split);
     if (fmt == ZC_FMT_BF16 && !scales_view)
-        hipLaunchKernelGGL(k_hist<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, 16, 0, d_hist);
+        hipLaunchKernelGGL(k_hist<ZC_FMT_BF16>, grid, dim3(256), 0, st, d_descs, d_work, 16, 0, d_hist, split);
     else if (fmt == ZC_FMT_FP8_E4M3_BYTES && !scales_view)
-        hipLaunchKernelGGL(k_hist<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, 8, 0, d_hist);
+        hipLaunchKernelGGL(k_hist<ZC_FMT_FP8_E4M3_BYTES>, grid, dim3(256), 0, st, d_descs, d_work, 8, 0, d_hist, split);
     else if (fmt == ZC_FMT_FP4_E2M1_MX_BYTES && !scales_view)
-        hipLaunchKernelGGL(k_hist<ZC_FMT_FP4_E2M1_MX_BYTES>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, 4, 0, d_hist);
+        hipLaunchKernelGGL(k_hist<ZC_FMT_FP4_E2M1_MX_BYTES>, grid, dim3(256), 0, st, d_descs, d_work, 4, 0, d_hist, split);
     else
-        hipLaunchKernelGGL(k_hist<0>, dim3(n_work), dim3(256), 0, st, d_descs, d_work, elem_bits(fmt), scales_view, d_hist);
+        hipLaunchKernelGGL(k_hist<0>, grid, dim3(256), 0, st, d_descs, d_work, elem_bits(fmt), scales_view, d_hist, split);
     return (int)hipGetLastError();
 }
 
