@@ -181,8 +181,8 @@ uint64_t zc_compress_bound(uint64_t n_elems, const zc_params *params);
 /* Scratch bytes a call on these tensors needs in d_ws (compress, stats and the
  * batched decompress).  n_elems: host array of n_tensors element counts.  A few hundred bytes per chunk and a few KB
  * per tensor, except for 64 lanes with chunks of 256 KiB, where the histogram pass leaves symbol counts per chunk lane
- * for the size pass (so that the source is read twice, not three times): 2 KiB per chunk for FP8, 64 KiB per chunk,
- * a quarter of the tensor, for BF16, FP8 in byte symbols and FP8 E5M2. */
+ * for the size pass (so that the source is read twice, not three times): 2 KiB per chunk for FP8 E4M3, 5 KiB for
+ * FP8 E5M2, and 64 KiB per chunk, a quarter of the tensor, for BF16 and FP8 in byte symbols. */
 uint64_t zc_workspace_bytes(const uint64_t *n_elems, uint32_t n_tensors, const zc_params *params);
 
 /* Compress one tensor: field split (+ XOR delta) and per-field histogram over the tensor,

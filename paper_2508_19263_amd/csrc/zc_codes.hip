@@ -135,7 +135,7 @@ __global__ __launch_bounds__(kCodeThreads) void k_codes(TensorDev *descs, const 
     // FP8: chunks counted by k_hist_fp8_lanes left their field histograms in the second slot (exponents at 0..15,
     // sign+mantissa at 16..31); the byte histogram above then covers only what that kernel did not take
     if (fmt == ZC_FMT_FP8_E4M3 && f < 2 && tid < 16) h[tid] += hist3[256 + 16 * f + tid];
-    // FP8 E5M2: likewise for k_hist_rows8_lanes (exponents at 0..31, sign+mantissa symbols at 32..39)
+    // FP8 E5M2: likewise for k_hist_fp8_lanes<true> (exponents at 0..31, sign+mantissa symbols at 32..39)
     if (fmt == ZC_FMT_FP8_E5M2 && f < 2 && tid < (f ? 8u : 32u)) h[tid] += hist3[256 + (f ? 32 : 0) + tid];
     __syncthreads();
 

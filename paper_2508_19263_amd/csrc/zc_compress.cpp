@@ -24,11 +24,10 @@ namespace zc {
 // The geometry for which the histogram pass also counts exponents per chunk lane, so that the size pass need
 // not read the source again (k_hist_fp8_lanes, k_sizes_fp8_counts)
 bool lane_counts_shape(const Geometry &g) { return g.fmt == ZC_FMT_FP8_E4M3 && g.S == 64 && g.chunk_bytes == kHistBlockBytes; }
-// The same for BF16, FP8 in byte symbols and FP8 E5M2 (k_hist_rows8_lanes, k_sizes_rows8_counts): 64 KiB of counts per chunk
-bool lane_counts8_shape(const Geometry &g)
-{
-    return (g.fmt == ZC_FMT_BF16 || g.fmt == ZC_FMT_FP8_E4M3_BYTES || g.fmt == ZC_FMT_FP8_E5M2) && g.S == 64 && g.chunk_bytes == kHistBlockBytes;
-}
+// The same for BF16 and FP8 in byte symbols (k_hist_rows8_lanes, k_sizes_rows8_counts): 64 KiB of counts per chunk
+bool lane_counts8_shape(const Geometry &g) { return (g.fmt == ZC_FMT_BF16 || g.fmt == ZC_FMT_FP8_E4M3_BYTES) && g.S == 64 && g.chunk_bytes == kHistBlockBytes; }
+// and for FP8 E5M2 (k_hist_fp8_lanes<true>, k_sizes_e5m2_counts): 40 counts per chunk lane
+bool lane_counts_e5m2_shape(const Geometry &g) { return g.fmt == ZC_FMT_FP8_E5M2 && g.S == 64 && g.chunk_bytes == kHistBlockBytes; }
 
 zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T, Workspace *w)
 {
@@ -66,6 +65,8 @@ zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T,
     if (lane_counts_shape(g)) off = align256(off + units / 2 * (64 * 16 * 2));
     // BF16 / FP8 in byte symbols, same geometry: 256 counts of 16 bits per chunk lane and field
     if (lane_counts8_shape(g)) off = align256(off + units / 2 * (2 * 64 * 256 * 2));
+    // FP8 E5M2, same geometry: 32 exponent and 8 sign+mantissa counts of 16 bits per chunk lane
+    if (lane_counts_e5m2_shape(g)) off = align256(off + units / 2 * (64 * 40 * 2));
     w->total = off;
     w->n_hist_work = (uint32_t)hw; w->n_scale_work = (uint32_t)sw; w->n_chunk_work = (uint32_t)cw; w->n_units = units;
     return ZC_OK;
@@ -85,7 +86,7 @@ TensorLists device_code_lists(const Geometry &g, const CompressShape &sh, uint64
     const uint64_t bytes = (n_elems * (uint64_t)elem_bits(g.fmt) + 7) / 8;
     const uint32_t whole_chunks = (uint32_t)(n_elems / g.elems_per_chunk);
     // a histogram block is a chunk when sh.lanes is set: whole chunks go to the kernel that counts per lane too
-    const uint32_t lane_blocks = (sh.lanes || sh.lanes8) ? whole_chunks : 0;
+    const uint32_t lane_blocks = (sh.lanes || sh.lanes8 || sh.lanes_e5m2) ? whole_chunks : 0;
     L.lane_hist = {0, lane_blocks, 1};
     L.hist = {lane_blocks, (uint32_t)((bytes + kHistBlockBytes - 1) / kHistBlockBytes), 1};
     if (L.hist.end < L.hist.first) L.hist.end = L.hist.first;
@@ -103,6 +104,7 @@ CompressShape compress_shape(const Geometry &g, bool device_codes, uint64_t all_
     sh.cpi = chunks_per_work_item(g.S);
     sh.lanes = device_codes && lane_counts_shape(g);
     sh.lanes8 = device_codes && lane_counts8_shape(g);
+    sh.lanes_e5m2 = device_codes && lane_counts_e5m2_shape(g);
     sh.bf16 = g.fmt == ZC_FMT_BF16;
     sh.whole_shape = g.S == 64 && g.chunk_bytes % 1024 == 0;
     sh.rows8 = sh.whole_shape && (g.fmt == ZC_FMT_BF16 || g.fmt == ZC_FMT_FP8_E4M3_BYTES || g.fmt == ZC_FMT_FP8_E5M2);
@@ -132,7 +134,7 @@ zc_status CompressQueue::queue_histogram() const
     LAUNCH_TRY(launch_zero(d_hist(), (uint64_t)T * 3 * 256, stream));
     LAUNCH_TRY(launch_hist(g.fmt, d_descs(), d_list(w.hist_work), n_hist, 0, d_hist(), stream));
     if (sh.lanes8) LAUNCH_TRY(launch_hist_rows8_lanes(g.fmt, d_descs(), d_list(w.hist_work) + n_hist, n_lane_hist, d_hist(), (uint32_t *)d_lane_counts(), stream));
-    else LAUNCH_TRY(launch_hist_fp8_lanes(d_descs(), d_list(w.hist_work) + n_hist, n_lane_hist, d_hist(), d_lane_counts(), stream));
+    else LAUNCH_TRY(launch_hist_fp8_lanes(sh.lanes_e5m2, d_descs(), d_list(w.hist_work) + n_hist, n_lane_hist, d_hist(), d_lane_counts(), stream));
     if (g.nf == 3) LAUNCH_TRY(launch_hist(g.fmt, d_descs(), d_list(w.scale_work), n_scale, (int)scale_block(g.fmt), d_hist(), stream));
     return ZC_OK;
 }
@@ -161,7 +163,8 @@ zc_status CompressQueue::queue_sizes_and_scan() const
     // (with the symbols counted per lane, route 2 has its sizes from the counts)
     if (sh.lanes8) LAUNCH_TRY(launch_sizes_rows8_counts(g.fmt, d_descs(), d_list(w.whole_work), n_whole, d_enc(), (const uint32_t *)d_lane_counts(), d_units(), stream));
     // (E5M2 has no encoder of its own, route 0, and all its whole chunks are sized from the counts)
-    if (!(sh.lanes8 && g.fmt == ZC_FMT_FP8_E5M2))
+    if (sh.lanes_e5m2) LAUNCH_TRY(launch_sizes_e5m2_counts(d_descs(), d_list(w.whole_work), n_whole, d_enc(), d_lane_counts(), d_units(), stream));
+    else
         LAUNCH_TRY(launch_sizes(g.fmt, sh.whole_mode, sh.lanes8 ? 0x6 : 0x2, d_descs(), d_list(w.whole_work), n_whole, d_enc(), d_units(), stream));
     LAUNCH_TRY(launch_sizes(g.fmt, 0, 0x6, d_descs(), d_list(w.other_work), n_other, d_enc(), d_units(), stream));
     LAUNCH_TRY(launch_sizes(g.fmt, 0, 0, d_descs(), d_list(w.chunk_work), n_slow, d_enc(), d_units(), stream));

@@ -24,6 +24,9 @@ namespace zc {
 // per lane, which go to lane_counts, and into the chunk's two field histograms, which are added to the tensor's
 // second histogram slot (exponents at 0..15, sign+mantissa at 16..31; the first slot keeps the byte histogram
 // of what k_hist counts, a short last chunk).
+// E5M2 (s eeeee mm) is counted the same way and folded differently: 32 exponent counts and 8 sign+mantissa counts per
+// lane (80 bytes, 5 KiB per chunk), field histograms at 0..31 and 32..39 of the second slot.
+template <bool E5M2>
 __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, const WorkItem *work, uint64_t *hist, uint16_t *lane_counts)
 {
     static_assert(kHistBlockBytes / 64 < 65536, "a lane's count of one byte value fits 16 bits");
@@ -65,6 +68,66 @@ __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, 
         for (uint32_t k = 0; k < kDepth; k++) count(v[k]);
     }
     __syncthreads();
+    if (E5M2) {
+        // Thread (lane, quarter) folds the byte values 64*quarter .. +63 of its lane: value = s eeeee mm, so a quarter is one
+        // sign, the exponents 16 * (quarter & 1) .. + 15 and all four mantissas.
+        uint32_t c[32];
+#pragma unroll
+        for (int i = 0; i < 32; i++) c[i] = 0;
+        const uint32_t half_shift = lane < 32 ? 0u : 16u;
+#pragma unroll
+        for (int v = 0; v < 64; v++) {
+            const uint32_t n = (cnt[(quarter * 64 + v) * 32 + (lane & 31)] >> half_shift) & 0xFFFFu;
+            c[v >> 2] += n;                                      // exponent 16 * (quarter & 1) + v / 4
+            c[16 + (v & 3)] += n;                                // sign+mantissa symbol 4 * (quarter >> 1) + v % 4
+        }
+        const uint32_t e_hi = quarter & 1, sgn = quarter >> 1;
+        __syncthreads();                                         // every thread has read its part of cnt: the array is free
+        uint32_t *const part = cnt;                              // rows of 21 words against bank conflicts
+#pragma unroll
+        for (int i = 0; i < 20; i++) part[(quarter * 64 + lane) * 21 + i] = c[i];
+        // the chunk's field histograms: the wavefront's 20 counts summed over its lanes in a butterfly that halves what a
+        // lane carries at every step; lane j < 32 ends with the total of count bitrev5(j)
+#pragma unroll
+        for (int step = 0; step < 5; step++) {
+            const int n = 16 >> step;
+            const bool upper = (lane >> step) & 1;
+#pragma unroll
+            for (int i = 0; i < n; i++) {
+                const uint32_t give = upper ? c[i] : c[n + i], keep = upper ? c[n + i] : c[i];
+                c[i] = keep + (uint32_t)__shfl_xor((int)give, 1 << step, 64);
+            }
+        }
+        c[0] += (uint32_t)__shfl_xor((int)c[0], 32, 64);
+        const uint32_t k = ((lane & 1) << 4) | ((lane & 2) << 2) | (lane & 4) | ((lane & 8) >> 2) | ((lane & 16) >> 4);
+        if (lane < 32 && k < 20 && c[0]) {
+            unsigned long long *slot = reinterpret_cast<unsigned long long *>(&hist[((uint64_t)it.tensor * 3 + 1) * 256]);
+            atomicAdd(slot + (k < 16 ? e_hi * 16 + k : 32 + sgn * 4 + (k - 16)), (unsigned long long)c[0]);
+        }
+        __syncthreads();
+        // the lane's 40 counts: quarters 0 and 1 write the exponents 0..15 and 16..31 (both signs added), quarter 2 the eight
+        // sign+mantissa symbols (both exponent halves added)
+        const uint64_t chunk_global = (uint64_t)(d.units_off / 2) + it.first;
+        uint16_t *mine = lane_counts + (chunk_global * 64 + lane) * 40;
+        if (quarter < 2) {
+            const uint32_t *pa = part + ((0 * 2 + quarter) * 64 + lane) * 21, *pb = part + ((1 * 2 + quarter) * 64 + lane) * 21;
+            uint32_t w[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) w[j] = (pa[2 * j] + pb[2 * j]) | ((pa[2 * j + 1] + pb[2 * j + 1]) << 16);
+            uint4 *out = reinterpret_cast<uint4 *>(mine + quarter * 16);
+            out[0] = make_uint4(w[0], w[1], w[2], w[3]);
+            out[1] = make_uint4(w[4], w[5], w[6], w[7]);
+        } else if (quarter == 2) {
+            uint32_t m[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const uint32_t sg = j >> 2;
+                m[j] = part[((sg * 2 + 0) * 64 + lane) * 21 + 16 + (j & 3)] + part[((sg * 2 + 1) * 64 + lane) * 21 + 16 + (j & 3)];
+            }
+            *reinterpret_cast<uint4 *>(mine + 32) = make_uint4(m[0] | (m[1] << 16), m[2] | (m[3] << 16), m[4] | (m[5] << 16), m[6] | (m[7] << 16));
+        }
+        return;
+    }
     // Thread (lane, quarter) folds the byte values 64*quarter .. +63 of its lane: value = s eeee mmm, so a quarter
     // is one sign, eight exponents and all eight mantissas.
     uint32_t ce[8], cm[8];
@@ -168,7 +231,7 @@ __global__ __launch_bounds__(256) void k_sizes_fp8_counts(const TensorDev *descs
 
 // ---------------------------------------------------------------------------------------
 // The same two reads instead of three for the formats whose fields are 8-bit symbols, 8 per 16-byte run (BF16;
-// FP8 in byte symbols) or 16 (FP8 E5M2), with 64 lanes and chunks of kHistBlockBytes: weights, checkpoints and
+// FP8 in byte symbols), with 64 lanes and chunks of kHistBlockBytes: weights, checkpoints and
 // checkpoint deltas (Sec. 3.1, 3.2, 4.1).  A lane's field has 256 possible symbols, so its counts are 512 bytes per field and lane, 64 KiB
 // per chunk: a quarter of the chunk, written once here and read once by k_sizes_rows8_counts, against a whole
 // second read of the source (and of the base of a delta) by the generic size pass.
@@ -182,7 +245,7 @@ __global__ __launch_bounds__(256) void k_sizes_fp8_counts(const TensorDev *descs
 template <int FMT>
 __global__ __launch_bounds__(512) void k_hist_rows8_lanes(const TensorDev *descs, const WorkItem *work, uint64_t *hist, uint32_t *lane_counts)
 {
-    static_assert((Fmt<FMT>::G == 8 || Fmt<FMT>::G == 16) && Fmt<FMT>::SB == 8 && Fmt<FMT>::NF == 2, "two fields of 8 or 16 symbols of 8 bits per run");
+    static_assert(Fmt<FMT>::G == 8 && Fmt<FMT>::SB == 8 && Fmt<FMT>::NF == 2, "two fields of 8 symbols of 8 bits per run");
     static_assert(kHistBlockBytes / 16 / 64 * Fmt<FMT>::G < 65536, "a lane's count of one symbol fits 16 bits");
     constexpr int kWords = Fmt<FMT>::G / 4;                      // words of four symbols per run and field
     __shared__ __attribute__((aligned(16))) uint32_t cnt[2 * 256 * 32];      // 64 KiB
@@ -242,17 +305,12 @@ __global__ __launch_bounds__(512) void k_hist_rows8_lanes(const TensorDev *descs
         const uint32_t c = cnt[(f * 256 + bin) * 32 + ((r + bin) & 31)];
         sum += (c & 0xFFFFu) + (c >> 16);
     }
-    // BF16 and byte symbols: field f's histogram is the tensor's slot f.  E5M2: slot 0 is the histogram of the bytes that
-    // k_hist counts, and the field histograms of what this kernel counts go to slot 1, exponents at 0..31 and sign+mantissa
-    // symbols at 32..39 (k_codes adds them up)
-    const uint64_t at = FMT == ZC_FMT_FP8_E5M2 ? 256 + (f ? 32 : 0) + bin : f * 256 + bin;
-    if (sum && (FMT != ZC_FMT_FP8_E5M2 || bin < (f ? 8u : 32u)))
-        atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(uint64_t)it.tensor * 768 + at]), (unsigned long long)sum);
+    // field f's histogram is the tensor's slot f
+    if (sum) atomicAdd(reinterpret_cast<unsigned long long *>(&hist[(uint64_t)it.tensor * 768 + f * 256 + bin]), (unsigned long long)sum);
 }
 
 // Stream sizes of whole chunks from those counts, for the tensors the 64-lane encoder of these formats takes (route 2:
-// exponent field table coded, sign+mantissa field flat, raw or table coded) and for every E5M2 tensor (whichever
-// encoder writes it).  A table-coded field: as in
+// exponent field table coded, sign+mantissa field flat, raw or table coded).  A table-coded field: as in
 // k_sizes_fp8_counts, with R symbols per refill step (R codes are at most 32 bits, which is all the argument there
 // needs): a lane's words are min(steps, floor((bits - bits of its last R codes) / 32) + 2), its bits the counts times
 // the code lengths.  A flat or raw field takes its plain size.  One wavefront per chunk, work items as for the
@@ -266,7 +324,7 @@ __global__ __launch_bounds__(256) void k_sizes_rows8_counts(const TensorDev *des
     __shared__ uint32_t total[kWavesPerGroup][2][64];
     const WorkItem it = work[blockIdx.x];
     const TensorDev *dp = descs + it.tensor;
-    if (dp->route != 2 && (FMT != ZC_FMT_FP8_E5M2 || dp->route != 0)) return;      // whole workgroup: the generic size pass takes this tensor
+    if (dp->route != 2) return;                                  // whole workgroup: the generic size pass takes this tensor
     constexpr uint32_t G = Fmt<FMT>::G;                           // symbols per run and field
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     lens[0][tid] = enc_tables[(uint64_t)it.tensor * 768 + tid] >> 16;
@@ -317,9 +375,9 @@ __global__ __launch_bounds__(256) void k_sizes_rows8_counts(const TensorDev *des
             u[f] = kind[f] == 3 ? 0u : cb / 256 * G;              // 8 bits per symbol, G symbols per 16 bytes of the chunk; a constant field: nothing
             continue;
         }
-        const uint32_t R = uni32(dp->period[f]);                 // 2, 4, 8 or, with runs of 16 symbols, 16
+        const uint32_t R = uni32(dp->period[f]);                 // 2, 4 or 8
         uint32_t last = 0;
-        for (uint32_t j = G - R; j < G; j++) last += lens[f][(uint32_t)((G == 16 && j >= 8 ? Q[f] : P[f]) >> (8 * (j & 7))) & 0xFFu];
+        for (uint32_t j = G - R; j < G; j++) last += lens[f][(uint32_t)(P[f] >> (8 * j)) & 0xFFu];
         const uint32_t steps = cb / 1024 * G / R;
         uint32_t q = ((total[wave][f][lane] - last) >> 5) + 2;
         q = q < steps ? q : steps;
@@ -335,10 +393,11 @@ __global__ __launch_bounds__(256) void k_sizes_rows8_counts(const TensorDev *des
     }
 }
 
-int launch_hist_fp8_lanes(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint16_t *d_lane_counts, void *stream)
+int launch_hist_fp8_lanes(bool e5m2, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint16_t *d_lane_counts, void *stream)
 {
     if (n_work == 0) return 0;
-    hipLaunchKernelGGL(k_hist_fp8_lanes, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
+    if (e5m2) hipLaunchKernelGGL(k_hist_fp8_lanes<true>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
+    else hipLaunchKernelGGL(k_hist_fp8_lanes<false>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
     return (int)hipGetLastError();
 }
 
@@ -350,15 +409,86 @@ int launch_sizes_fp8_counts(const TensorDev *d_descs, const WorkItem *d_work, ui
     return (int)hipGetLastError();
 }
 
-// fmt: ZC_FMT_BF16, ZC_FMT_FP8_E4M3_BYTES or ZC_FMT_FP8_E5M2.  One work item per whole chunk of kHistBlockBytes.
+// The same for FP8 E5M2 from the 40 counts per lane that k_hist_fp8_lanes<true> leaves (32 exponents, 8 sign+mantissa
+// symbols): either field, when table coded, takes min(steps, floor((bits - bits of its last R codes) / 32) + 2) words
+// per lane with R symbols per refill step (2, 4, 8 or 16 of the 16 symbols of a run).  One wavefront per chunk, work
+// items of kWavesPerGroup whole chunks (the list of the generic whole-chunk size pass, which leaves these tensors alone).
+__global__ __launch_bounds__(256) void k_sizes_e5m2_counts(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables,
+                                                           const uint16_t *lane_counts, uint32_t *units)
+{
+    __shared__ uint32_t len_e[32], len_m[8];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev *dp = descs + it.tensor;
+    if (threadIdx.x < 32) len_e[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + threadIdx.x] >> 16;
+    if (threadIdx.x < 8) len_m[threadIdx.x] = enc_tables[(uint64_t)it.tensor * 768 + 256 + threadIdx.x] >> 16;
+    __syncthreads();
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t chunk = uni32(it.first + (threadIdx.x >> 6));
+    const uint32_t cb = uni32(dp->chunk_bytes);
+    const uint64_t n_elems = uni64(dp->n_elems);
+    if (cb != kHistBlockBytes || chunk >= (uint32_t)(n_elems / cb)) return;
+    const uint64_t chunk_global = (uint64_t)(uni32(dp->units_off) / 2) + chunk;
+    const uint4 *mine = reinterpret_cast<const uint4 *>(lane_counts + (chunk_global * 64 + lane) * 40);
+    uint32_t bits[2] = {0, 0};
+#pragma unroll
+    for (int q = 0; q < 4; q++) {
+        const uint4 c = mine[q];
+        const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+        for (int j = 0; j < 4; j++) bits[0] += (w[j] & 0xFFFFu) * len_e[8 * q + 2 * j] + (w[j] >> 16) * len_e[8 * q + 2 * j + 1];
+    }
+    {
+        const uint4 c = mine[4];
+        const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+        for (int j = 0; j < 4; j++) bits[1] += (w[j] & 0xFFFFu) * len_m[2 * j] + (w[j] >> 16) * len_m[2 * j + 1];
+    }
+    // the lane's last run: its last R symbols of either field
+    const uint64_t at = (uint64_t)chunk * cb + (cb - 1024) + lane * 16;
+    uint4 v = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)) + at);
+    if (uni64((uint64_t)dp->base) != 0) v = xor4(v, *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) + at));
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t u[2];
+#pragma unroll
+    for (int f = 0; f < 2; f++) {
+        const uint32_t kind = uni32(dp->kind[f]);                // 0 table coded, 1 flat code, 2 raw, 3 constant
+        if (kind != 0) { u[f] = kind == 3 ? 0u : cb / 16; continue; }     // (8 bits per symbol, one symbol per byte of the chunk)
+        const uint32_t R = uni32(dp->period[f]);
+        uint32_t last = 0;
+        for (uint32_t j = 16 - R; j < 16; j++) {
+            const uint32_t b = (w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+            last += f == 0 ? len_e[(b >> 2) & 31u] : len_m[((b >> 7) << 2) | (b & 3u)];
+        }
+        const uint32_t steps = cb / 64 / R;                      // cb / 64 symbols per lane
+        uint32_t q = ((bits[f] - last) >> 5) + 2;
+        q = q < steps ? q : steps;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+        u[f] = (q + 3) / 4;
+    }
+    if (lane == 0) {
+        uint32_t *my = units + uni32(dp->units_off);
+        const uint32_t nc = uni32(dp->n_chunks);
+        my[chunk] = u[0];
+        my[nc + chunk] = u[1];
+    }
+}
+
+int launch_sizes_e5m2_counts(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, const uint16_t *d_lane_counts,
+                             uint32_t *d_units, void *stream)
+{
+    if (n_work == 0) return 0;
+    hipLaunchKernelGGL(k_sizes_e5m2_counts, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
+    return (int)hipGetLastError();
+}
+
+// fmt: ZC_FMT_BF16 or ZC_FMT_FP8_E4M3_BYTES.  One work item per whole chunk of kHistBlockBytes.
 int launch_hist_rows8_lanes(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint32_t *d_lane_counts, void *stream)
 {
     if (n_work == 0) return 0;
     if (fmt == ZC_FMT_BF16) hipLaunchKernelGGL(k_hist_rows8_lanes<ZC_FMT_BF16>, dim3(n_work), dim3(512), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
     else if (fmt == ZC_FMT_FP8_E4M3_BYTES)
         hipLaunchKernelGGL(k_hist_rows8_lanes<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(512), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
-    else if (fmt == ZC_FMT_FP8_E5M2)
-        hipLaunchKernelGGL(k_hist_rows8_lanes<ZC_FMT_FP8_E5M2>, dim3(n_work), dim3(512), 0, (hipStream_t)stream, d_descs, d_work, d_hist, d_lane_counts);
     else return 1;
     return (int)hipGetLastError();
 }
@@ -372,8 +502,6 @@ int launch_sizes_rows8_counts(uint32_t fmt, const TensorDev *d_descs, const Work
         hipLaunchKernelGGL(k_sizes_rows8_counts<ZC_FMT_BF16>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
     else if (fmt == ZC_FMT_FP8_E4M3_BYTES)
         hipLaunchKernelGGL(k_sizes_rows8_counts<ZC_FMT_FP8_E4M3_BYTES>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
-    else if (fmt == ZC_FMT_FP8_E5M2)
-        hipLaunchKernelGGL(k_sizes_rows8_counts<ZC_FMT_FP8_E5M2>, dim3(n_work), dim3(256), 0, (hipStream_t)stream, d_descs, d_work, d_enc, d_lane_counts, d_units);
     else return 1;
     return (int)hipGetLastError();
 }

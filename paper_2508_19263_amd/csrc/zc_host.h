@@ -95,6 +95,7 @@ zc_status plan_workspace(const Geometry &g, const uint64_t *n_elems, uint32_t T,
 struct CompressShape {
     bool lanes;                 // the code is built on the device and the histogram pass also counts exponents per chunk lane
     bool lanes8;                // the same for the formats of 8-bit symbols (BF16, FP8 in byte symbols): both fields' symbols per chunk lane
+    bool lanes_e5m2;            // the same for FP8 E5M2: 32 exponent and 8 sign+mantissa counts per chunk lane
     bool bf16;
     bool rows8;                 // 64 lanes, whole rows, 8 or 16 symbols of 8 bits per run and field (BF16, FP8 in byte symbols, FP8 E5M2): the 64-lane encoder written for BF16
     bool whole_shape;           // 64 lanes, chunks of whole 1 KiB rows: the generic encoder's whole-chunk build

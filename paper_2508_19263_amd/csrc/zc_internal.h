@@ -159,11 +159,16 @@ int launch_decode_e5m2(bool xor_delta, const TensorDev *d_descs, const WorkItem 
 int launch_sizes_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream);
 // FP8, 64 lanes, chunks of kHistBlockBytes: the histogram pass that also counts exponents per chunk lane (one work
 // item per whole chunk; 16 u16 per lane, 2 KiB per chunk, at lane_counts[(units_off / 2 + chunk) * 1024]), and the
-// size pass that reads those counts instead of the source (same work list as launch_sizes_fp8) (zc_hist_lanes.hip)
-int launch_hist_fp8_lanes(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint16_t *d_lane_counts, void *stream);
-// BF16 / FP8 in byte symbols / FP8 E5M2, 64 lanes, chunks of kHistBlockBytes: the same for fields of 8-bit symbols (256 counts
+// size pass that reads those counts instead of the source (same work list as launch_sizes_fp8) (zc_hist_lanes.hip).
+// e5m2: the E5M2 layout instead, 32 exponent and 8 sign+mantissa counts per lane (40 u16, 5 KiB per chunk, at
+// lane_counts[(units_off / 2 + chunk) * 2560]), read by launch_sizes_e5m2_counts (work list of the generic whole-chunk
+// size pass, which it replaces for every tensor)
+int launch_hist_fp8_lanes(bool e5m2, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint16_t *d_lane_counts, void *stream);
+int launch_sizes_e5m2_counts(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, const uint16_t *d_lane_counts,
+                             uint32_t *d_units, void *stream);
+// BF16 / FP8 in byte symbols, 64 lanes, chunks of kHistBlockBytes: the same for fields of 8-bit symbols (256 counts
 // of 16 bits per lane and field, 64 KiB per chunk, at lane_counts + (units_off / 2 + chunk) * 16384 words), and the size pass of
-// the tensors of route 2 (E5M2: of every tensor) from those counts (zc_hist_lanes.hip)
+// the tensors of route 2 from those counts (zc_hist_lanes.hip)
 int launch_hist_rows8_lanes(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint32_t *d_lane_counts, void *stream);
 int launch_sizes_rows8_counts(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
                               const uint32_t *d_lane_counts, uint32_t *d_units, void *stream);

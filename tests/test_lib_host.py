@@ -71,14 +71,16 @@ def test_bounds_and_workspace():
         sizes = [zc.workspace_bytes([n], zc.params(fmt, cb)) for n in (1 << 20, 1 << 24, 1 << 26)]
         assert sizes[0] < sizes[1] < sizes[2]
         assert zc.workspace_bytes([1 << 24, 1 << 24], zc.params(fmt, cb)) > sizes[1]
-    # The formats of 8-bit symbols (BF16, FP8 in byte symbols, FP8 E5M2) reserve 64 KiB per chunk there: 256 counts per
-    # chunk lane and field.  FP8 E4M3 and E5M2 have the same element size, fields and work lists, so they differ by the counts.
+    # The formats of 8-bit symbols (BF16, FP8 in byte symbols) reserve 64 KiB per chunk there: 256 counts per chunk lane
+    # and field; FP8 E5M2 reserves 5 KiB (40 counts per lane).  The FP8 formats have the same element size, fields and
+    # work lists, so they differ by the counts.
     n = 1 << 28
     e4 = zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E4M3, 262144))
     e5 = zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E5M2, 262144))
-    assert e5 - e4 == (n // 262144) * (65536 - 2048)
-    assert zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E4M3_BYTES, 262144)) == e5
-    assert zc.workspace_bytes([n // 2], zc.params(zc.FMT_BF16, 262144)) == e5
+    e8 = zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E4M3_BYTES, 262144))
+    assert e5 - e4 == (n // 262144) * (5120 - 2048)
+    assert e8 - e4 == (n // 262144) * (65536 - 2048)
+    assert zc.workspace_bytes([n // 2], zc.params(zc.FMT_BF16, 262144)) == e8
     # other chunk sizes and lane counts reserve nothing of the kind
     assert zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E5M2, 131072)) < e4
     assert zc.workspace_bytes([n], zc.params(zc.FMT_FP8_E5M2, 262144, streams=32)) < e4
