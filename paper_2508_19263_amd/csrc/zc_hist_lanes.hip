@@ -91,11 +91,13 @@ __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, 
 #pragma unroll
         for (int step = 0; step < 5; step++) {
             const int n = 16 >> step;
-            const bool upper = (lane >> step) & 1;
+            const uint32_t upper = 0u - ((lane >> step) & 1u);   // all ones in the lanes that keep the upper half
 #pragma unroll
             for (int i = 0; i < n; i++) {
-                const uint32_t give = upper ? c[i] : c[n + i], keep = upper ? c[n + i] : c[i];
-                c[i] = keep + (uint32_t)__shfl_xor((int)give, 1 << step, 64);
+                // (bitwise, so that the counts stay in registers: a choice between two array elements becomes an
+                // element at a computed index, which the compiler looks up with a chain of compares)
+                const uint32_t a = c[i], b = c[n + i], d = (a ^ b) & upper;
+                c[i] = (a ^ d) + (uint32_t)__shfl_xor((int)(b ^ d), 1 << step, 64);      // keeps b, gives a where upper
             }
         }
         c[0] += (uint32_t)__shfl_xor((int)c[0], 32, 64);
@@ -156,11 +158,13 @@ __global__ __launch_bounds__(256) void k_hist_fp8_lanes(const TensorDev *descs, 
 #pragma unroll
         for (int step = 0; step < 4; step++) {
             const int n = 8 >> step;                             // values kept per lane after this step
-            const bool upper = (lane >> step) & 1;
+            const uint32_t upper = 0u - ((lane >> step) & 1u);   // all ones in the lanes that keep the upper half
 #pragma unroll
             for (int i = 0; i < n; i++) {
-                const uint32_t give = upper ? c[i] : c[n + i], keep = upper ? c[n + i] : c[i];
-                c[i] = keep + (uint32_t)__shfl_xor((int)give, 1 << step, 64);
+                // (bitwise, so that the counts stay in registers: a choice between two array elements becomes an
+                // element at a computed index, which the compiler looks up with a chain of compares)
+                const uint32_t a = c[i], b = c[n + i], d = (a ^ b) & upper;
+                c[i] = (a ^ d) + (uint32_t)__shfl_xor((int)(b ^ d), 1 << step, 64);      // keeps b, gives a where upper
             }
         }
         c[0] += (uint32_t)__shfl_xor((int)c[0], 16, 64);
