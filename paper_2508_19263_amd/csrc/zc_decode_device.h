@@ -23,7 +23,7 @@ __device__ __forceinline__ uint32_t perm(uint32_t hi, uint32_t lo, uint32_t sel)
 // canonical tables of the 16-symbol exponent code, built by the first threads of the group
 struct Canon16 { uint32_t first[17], cnt[17], start[17]; uint8_t sorted[16]; };
 
-__device__ void build_canon16(Canon16 &Cn, const uint8_t *len_table)
+__device__ inline void build_canon16(Canon16 &Cn, const uint8_t *len_table)
 {
     if (threadIdx.x == 0) {
         uint8_t len[16];
