@@ -129,3 +129,35 @@ def test_refill_period_changes_with_longest_code():
     # check finds k = 32 exactly only after consuming, so the count is 14 + 1 request at step 8
     back, used = o.decode_stream(s_flat, len(syms), flat, 16, 64)
     assert used == len(s_flat) and np.array_equal(back, syms)
+
+
+def test_stream_length_has_a_closed_form():
+    # The decoder asks for a word at a refill step when it holds at most 32 unread bits, at most one word per step,
+    # and r codes are at most 32 bits: by induction over the steps a lane with bits B before its last step has
+    # taken min(steps, floor(B / 32) + 2) words when it ends.  So a stream's length follows from the lanes' bit
+    # totals alone, without walking the steps (the size passes that work from symbol counts rely on this).
+    rng = np.random.default_rng(20260317)
+    cases = 0
+    for A, L, G, S in ((16, 8, 16, 64), (16, 5, 16, 8), (256, 16, 8, 64), (256, 11, 8, 4), (256, 8, 16, 64), (32, 16, 16, 64),
+                       (4, 3, 16, 2), (256, 9, 16, 1), (16, 4, 16, 64), (256, 13, 8, 32)):
+        for n in (1, G - 1, G * S, G * S + 3, 5 * G * S - G - 1, 40 * G * S + G * (S // 2) + 2, 4096 + 17):
+            syms, f = random_case(rng, A, n, 12)
+            ln = np.asarray(o.code_lengths(f.tolist(), L))
+            lmax = int(ln.max())
+            r = 1
+            while 2 * r * lmax <= 32:
+                r *= 2
+            r = min(r, G)
+            words = 0
+            lane_of = (np.arange(n) // G) % S
+            for s in range(S):
+                mine = ln[syms[lane_of == s]].astype(np.int64)
+                if len(mine) == 0:
+                    continue
+                steps = -(-len(mine) // r)
+                before_last_step = int(mine[:(steps - 1) * r].sum())
+                words += min(steps, before_last_step // 32 + 2)
+            got = o.encode_stream(syms, ln.tolist(), G, S)
+            assert len(got) == 16 * (-(-words // 4)), (A, L, G, S, n)
+            cases += 1
+    assert cases == 70
