@@ -228,7 +228,7 @@ def other_workloads(torch, wl, zc, dev, extras, copy_gbps):
             compress_kernels="k_hist_fp8_lanes + k_codes + k_sizes_fp8_counts + k_scan + k_encode_fp8")
         del chunk_ids
         ragged = [t[:t.numel() - 4096 - 7 * 16] for t in set2]
-        run("c2_fp8_ragged_tails", zc.FMT_FP8_E4M3, ragged, [t.numel() for t in ragged], 262144, 64, decode_kernel="k_decode_fp8 + k_decode_s64<TAIL> (last chunks)", compress_kernels="k_hist_fp8_lanes + k_hist + k_codes + sizes + k_scan + k_encode_fp8 + k_encode (last chunks)")
+        run("c2_fp8_ragged_tails", zc.FMT_FP8_E4M3, ragged, [t.numel() for t in ragged], 262144, 64, decode_kernel="k_decode_fp8 + k_decode_s64<TAIL> (last chunks)", compress_kernels="k_hist_fp8_lanes + k_hist + k_codes + k_sizes_fp8_counts + k_sizes_tail (last chunks) + k_scan + k_encode_fp8 + k_encode (last chunks)")
         del set2, ragged
         set2 = [t for _, t in wl.fp8_weight_set(32, device=dev, e5m2=True)]
         run("c2_shapes_in_fp8_e5m2", zc.FMT_FP8_E5M2, set2, [t.numel() for t in set2], 262144, 64, decode_kernel=S64, compress_kernels="k_hist_fp8_lanes<E5M2> + k_codes + k_sizes_e5m2_counts + k_scan + k_encode_bf16<E5M2>")

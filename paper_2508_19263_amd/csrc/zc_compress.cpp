@@ -167,7 +167,10 @@ zc_status CompressQueue::queue_sizes_and_scan() const
     else
         LAUNCH_TRY(launch_sizes(g.fmt, sh.whole_mode, sh.lanes8 ? 0x6 : 0x2, d_descs(), d_list(w.whole_work), n_whole, d_enc(), d_units(), stream));
     LAUNCH_TRY(launch_sizes(g.fmt, 0, 0x6, d_descs(), d_list(w.other_work), n_other, d_enc(), d_units(), stream));
-    LAUNCH_TRY(launch_sizes(g.fmt, 0, 0, d_descs(), d_list(w.chunk_work), n_slow, d_enc(), d_units(), stream));
+    // what the whole-chunk kernels leave over: with 64 lanes and chunks of whole rows only a tensor's short last chunk,
+    // sized from its lanes' bit totals; otherwise every chunk, walked by the generic size pass
+    if (sh.whole_shape && g.nf == 2) LAUNCH_TRY(launch_sizes_tail(g.fmt, d_descs(), d_list(w.chunk_work), n_slow, d_enc(), d_units(), stream));
+    else LAUNCH_TRY(launch_sizes(g.fmt, 0, 0, d_descs(), d_list(w.chunk_work), n_slow, d_enc(), d_units(), stream));
     // the chained kernel has placed and written the tensors of its route (FP8: 1, BF16: 2) itself
     LAUNCH_TRY(launch_scan(d_descs(), T, (int)g.nf, g.reversed, chained ? (sh.bf16 ? 0x4 : 0x2) : 0, d_units(), (ScanOut *)(ws + w.scan), stats_only ? nullptr : ws + w.blobs,
                            (uint32_t)kBlobBytes, stream));

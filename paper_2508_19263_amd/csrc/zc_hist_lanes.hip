@@ -397,6 +397,113 @@ __global__ __launch_bounds__(256) void k_sizes_rows8_counts(const TensorDev *des
     }
 }
 
+// Stream sizes of the chunks the whole-chunk kernels leave over: with 64 lanes and chunks of whole rows that is a
+// tensor's short last chunk.  The closed form of the count-based size passes holds for lanes of different lengths
+// too: a lane of n symbols takes min(steps, floor((bits before its last step) / 32) + 2) words, steps = ceil(n / R).
+// So the chunk need not be walked step by step by one wavefront, which takes a few hundred microseconds whatever
+// else the GPU does: the four wavefronts of the workgroup add up code lengths over a quarter of the rows each.
+// Work items as for the generic size pass (up to kWavesPerGroup chunks from `first` on, one after the other).
+template <int FMT>
+__global__ __launch_bounds__(256) void k_sizes_tail(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units)
+{
+    using F_ = Fmt<FMT>;
+    static_assert(F_::NF == 2 && (F_::SB == 4 || F_::SB == 8) && F_::G * F_::SB <= 128, "two fields of 4- or 8-bit symbols, at most two 64-bit words per run");
+    __shared__ uint32_t lens[2][256];
+    __shared__ uint32_t part[kWavesPerGroup][2][64];
+    __shared__ uint32_t last_step[2][64];
+    const WorkItem it = work[blockIdx.x];
+    const TensorDev *dp = descs + it.tensor;
+    const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    lens[0][tid] = enc_tables[(uint64_t)it.tensor * 768 + tid] >> 16;
+    lens[1][tid] = enc_tables[(uint64_t)it.tensor * 768 + 256 + tid] >> 16;
+    const uint32_t nc = uni32(dp->n_chunks);
+    if (uni32(dp->streams) != 64) return;                        // whole workgroup; the host never asks for this
+    const uint64_t E = (uint64_t)uni32(dp->chunk_bytes) * 8 / F_::EB;     // elements of a whole chunk
+    const uint64_t n_elems = uni64(dp->n_elems);
+    const uint32_t mode[2] = {uni32(dp->mode[0]), uni32(dp->mode[1])};
+    const uint32_t R[2] = {uni32(dp->period[0]), uni32(dp->period[1])};
+    auto symbol = [](uint64_t P, uint64_t Q, uint32_t j) { return (uint32_t)((j * F_::SB < 64 ? P >> (j * F_::SB) : Q >> (j * F_::SB - 64)) & ((1u << F_::SB) - 1)); };
+    for (uint32_t chunk = it.first; chunk < it.first + kWavesPerGroup && chunk < nc; chunk++) {
+        const uint64_t first = (uint64_t)chunk * E;
+        const uint32_t n = (uint32_t)(n_elems - first < E ? n_elems - first : E);
+        const uint32_t nbytes = (uint32_t)(((uint64_t)n * F_::EB + 7) / 8);
+        const uint32_t runs = (nbytes + 15) / 16, rows = (runs + 63) / 64;
+        const uint8_t *src = reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->src)) + (uint64_t)chunk * uni32(dp->chunk_bytes);
+        const uint8_t *base = uni64((uint64_t)dp->base) ? reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) + (uint64_t)chunk * uni32(dp->chunk_bytes) : nullptr;
+        __syncthreads();                                         // the tables are there; the last chunk's sums have been read
+        uint32_t bits[2] = {0, 0};
+        for (uint32_t row = wave; row < rows; row += kWavesPerGroup) {
+            const uint32_t run = row * 64 + lane;
+            if (run >= runs) continue;
+            const uint32_t done = run * F_::EPR;
+            const uint32_t nel = n - done < (uint32_t)F_::EPR ? n - done : (uint32_t)F_::EPR;
+            const uint32_t nsym = (nel + F_::GRP - 1) / F_::GRP;  // a last partial group is filled with zeros
+            uint4 v = load_run(src + (uint64_t)run * 16, nbytes - run * 16);
+            if (base) v = xor4(v, load_run(base + (uint64_t)run * 16, nbytes - run * 16));
+            uint64_t P[2], Q[2];
+            split_run4<FMT>(v, P[0], Q[0], P[1], Q[1]);
+            const bool lanes_last = run + 64 >= runs;            // no later row has a run of this lane
+#pragma unroll
+            for (int f = 0; f < 2; f++) {
+                if (mode[f] != ZC_MODE_HUFF) continue;
+                const uint32_t j0 = (nsym - 1) / R[f] * R[f];    // first symbol of the run's last refill step
+                uint32_t all = 0, tail = 0;
+                for (uint32_t j = 0; j < nsym; j++) {
+                    const uint32_t l = lens[f][symbol(P[f], Q[f], j)];
+                    all += l;
+                    tail += j >= j0 ? l : 0u;
+                }
+                bits[f] += all;
+                // the lane's symbols: G per run before this one, nsym here
+                if (lanes_last) last_step[f][lane] = tail | ((row * (uint32_t)F_::G + nsym + R[f] - 1) / R[f]) << 8;
+            }
+        }
+        part[wave][0][lane] = bits[0];
+        part[wave][1][lane] = bits[1];
+        __syncthreads();
+        if (wave == 0) {
+            uint32_t u[2];
+#pragma unroll
+            for (int f = 0; f < 2; f++) {
+                uint32_t q = 0;
+                if (mode[f] == ZC_MODE_HUFF && lane < runs) {
+                    uint32_t B = 0;
+#pragma unroll
+                    for (uint32_t w = 0; w < kWavesPerGroup; w++) B += part[w][f][lane];
+                    const uint32_t ls = last_step[f][lane], steps = ls >> 8;
+                    q = ((B - (ls & 0xFFu)) >> 5) + 2;
+                    q = q < steps ? q : steps;
+                }
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) q += __shfl_xor(q, o, 64);
+                const uint32_t nsyms = (n + F_::GRP - 1) / F_::GRP;
+                u[f] = mode[f] == ZC_MODE_HUFF ? (q + 3) / 4 : mode[f] == ZC_MODE_RAW ? (uint32_t)((((uint64_t)nsyms * F_::SB + 7) / 8 + 15) / 16) : 0u;
+            }
+            if (lane == 0) {
+                uint32_t *my = units + uni32(dp->units_off);
+                my[chunk] = u[0];
+                my[nc + chunk] = u[1];
+            }
+        }
+    }
+}
+
+// fmt: a format of two fields.  The tensors must have 64 lanes per chunk.
+int launch_sizes_tail(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream)
+{
+    if (n_work == 0) return 0;
+    const dim3 grid(n_work), block(256);
+    hipStream_t st = (hipStream_t)stream;
+    switch (fmt) {
+    case ZC_FMT_BF16: hipLaunchKernelGGL(k_sizes_tail<ZC_FMT_BF16>, grid, block, 0, st, d_descs, d_work, d_enc, d_units); break;
+    case ZC_FMT_FP8_E4M3: hipLaunchKernelGGL(k_sizes_tail<ZC_FMT_FP8_E4M3>, grid, block, 0, st, d_descs, d_work, d_enc, d_units); break;
+    case ZC_FMT_FP8_E4M3_BYTES: hipLaunchKernelGGL(k_sizes_tail<ZC_FMT_FP8_E4M3_BYTES>, grid, block, 0, st, d_descs, d_work, d_enc, d_units); break;
+    case ZC_FMT_FP8_E5M2: hipLaunchKernelGGL(k_sizes_tail<ZC_FMT_FP8_E5M2>, grid, block, 0, st, d_descs, d_work, d_enc, d_units); break;
+    default: return (int)hipErrorInvalidValue;
+    }
+    return (int)hipGetLastError();
+}
+
 int launch_hist_fp8_lanes(bool e5m2, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint16_t *d_lane_counts, void *stream)
 {
     if (n_work == 0) return 0;

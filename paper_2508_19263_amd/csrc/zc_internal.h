@@ -172,6 +172,9 @@ int launch_sizes_e5m2_counts(const TensorDev *d_descs, const WorkItem *d_work, u
 int launch_hist_rows8_lanes(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, uint64_t *d_hist, uint32_t *d_lane_counts, void *stream);
 int launch_sizes_rows8_counts(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc,
                               const uint32_t *d_lane_counts, uint32_t *d_units, void *stream);
+// Two-field formats, 64 lanes: stream sizes of the chunks of a generic work list (up to kWavesPerGroup chunks per item)
+// from the closed form over the lanes' bit totals; meant for the short last chunks of tensors (zc_hist_lanes.hip)
+int launch_sizes_tail(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream);
 int launch_sizes_fp8_counts(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, const uint16_t *d_lane_counts,
                             uint32_t *d_units, void *stream);
 int launch_encode_fp8(const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, void *stream);
