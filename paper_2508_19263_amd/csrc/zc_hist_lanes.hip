@@ -401,21 +401,21 @@ __global__ __launch_bounds__(256) void k_sizes_rows8_counts(const TensorDev *des
 // tensor's short last chunk.  The closed form of the count-based size passes holds for lanes of different lengths
 // too: a lane of n symbols takes min(steps, floor((bits before its last step) / 32) + 2) words, steps = ceil(n / R).
 // So the chunk need not be walked step by step by one wavefront, which takes a few hundred microseconds whatever
-// else the GPU does: the four wavefronts of the workgroup add up code lengths over a quarter of the rows each.
+// else the GPU does: the sixteen wavefronts of the workgroup add up code lengths over a sixteenth of the rows each.
 // Work items as for the generic size pass (up to kWavesPerGroup chunks from `first` on, one after the other).
+constexpr uint32_t kTailWaves = 16;
 template <int FMT>
-__global__ __launch_bounds__(256) void k_sizes_tail(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units)
+__global__ __launch_bounds__(64 * kTailWaves) void k_sizes_tail(const TensorDev *descs, const WorkItem *work, const uint32_t *enc_tables, uint32_t *units)
 {
     using F_ = Fmt<FMT>;
     static_assert(F_::NF == 2 && (F_::SB == 4 || F_::SB == 8) && F_::G * F_::SB <= 128, "two fields of 4- or 8-bit symbols, at most two 64-bit words per run");
     __shared__ uint32_t lens[2][256];
-    __shared__ uint32_t part[kWavesPerGroup][2][64];
+    __shared__ uint32_t part[kTailWaves][2][64];
     __shared__ uint32_t last_step[2][64];
     const WorkItem it = work[blockIdx.x];
     const TensorDev *dp = descs + it.tensor;
     const uint32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    lens[0][tid] = enc_tables[(uint64_t)it.tensor * 768 + tid] >> 16;
-    lens[1][tid] = enc_tables[(uint64_t)it.tensor * 768 + 256 + tid] >> 16;
+    if (tid < 512) lens[tid >> 8][tid & 255] = enc_tables[(uint64_t)it.tensor * 768 + tid] >> 16;
     const uint32_t nc = uni32(dp->n_chunks);
     if (uni32(dp->streams) != 64) return;                        // whole workgroup; the host never asks for this
     const uint64_t E = (uint64_t)uni32(dp->chunk_bytes) * 8 / F_::EB;     // elements of a whole chunk
@@ -432,7 +432,7 @@ __global__ __launch_bounds__(256) void k_sizes_tail(const TensorDev *descs, cons
         const uint8_t *base = uni64((uint64_t)dp->base) ? reinterpret_cast<const uint8_t *>(uni64((uint64_t)dp->base)) + (uint64_t)chunk * uni32(dp->chunk_bytes) : nullptr;
         __syncthreads();                                         // the tables are there; the last chunk's sums have been read
         uint32_t bits[2] = {0, 0};
-        for (uint32_t row = wave; row < rows; row += kWavesPerGroup) {
+        for (uint32_t row = wave; row < rows; row += kTailWaves) {
             const uint32_t run = row * 64 + lane;
             if (run >= runs) continue;
             const uint32_t done = run * F_::EPR;
@@ -469,7 +469,7 @@ __global__ __launch_bounds__(256) void k_sizes_tail(const TensorDev *descs, cons
                 if (mode[f] == ZC_MODE_HUFF && lane < runs) {
                     uint32_t B = 0;
 #pragma unroll
-                    for (uint32_t w = 0; w < kWavesPerGroup; w++) B += part[w][f][lane];
+                    for (uint32_t w = 0; w < kTailWaves; w++) B += part[w][f][lane];
                     const uint32_t ls = last_step[f][lane], steps = ls >> 8;
                     q = ((B - (ls & 0xFFu)) >> 5) + 2;
                     q = q < steps ? q : steps;
@@ -492,7 +492,7 @@ __global__ __launch_bounds__(256) void k_sizes_tail(const TensorDev *descs, cons
 int launch_sizes_tail(uint32_t fmt, const TensorDev *d_descs, const WorkItem *d_work, uint32_t n_work, const uint32_t *d_enc, uint32_t *d_units, void *stream)
 {
     if (n_work == 0) return 0;
-    const dim3 grid(n_work), block(256);
+    const dim3 grid(n_work), block(64 * kTailWaves);
     hipStream_t st = (hipStream_t)stream;
     switch (fmt) {
     case ZC_FMT_BF16: hipLaunchKernelGGL(k_sizes_tail<ZC_FMT_BF16>, grid, block, 0, st, d_descs, d_work, d_enc, d_units); break;
