@@ -1,5 +1,6 @@
 // Histogram passes that also count symbols per chunk lane, and the size passes that work from those counts instead
-// of reading the source a second time (a3 and a5 for 64 lanes and chunks of one histogram block).
+// of reading the source a second time (a3 and a5 for 64 lanes and chunks of one histogram block); and the size pass
+// of a tensor's short last chunk, which rests on the same closed form (k_sizes_tail).
 #include <hip/hip_runtime.h>
 
 #include "zc_internal.h"
